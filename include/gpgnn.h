@@ -1,0 +1,199 @@
+/*
+ * gpgnn -- single-GPU (gfx950) triplet interaction block for DimeNet++ / GemNet-T
+ * style atomic graph networks: the per-GPU work of graph-parallel training
+ * (paper Sec. 2.2), i.e. radius-graph construction, triplet enumeration,
+ * TripletUpdate + TripletAggr and the edge MLPs around them (Sec. 2.1, 3.3, 3.4),
+ * forward and backward.
+ *
+ * Conventions
+ *   - Every function returns GP_OK (0) or a negative gp_status; it never throws
+ *     or aborts.  gp_last_error(ctx) gives a human-readable message for the last
+ *     failure on that context.
+ *   - Unless marked "host", every array pointer is a DEVICE pointer owned by the
+ *     caller; the library allocates no user-visible memory.  Temporary storage is
+ *     a caller-provided workspace whose size is queried first.
+ *   - All work is enqueued on the hipStream_t given to gp_create; only the
+ *     *_count calls synchronise (they return a host scalar).
+ *   - Arrays are row-major and contiguous.  Indices are int32, counts int64.
+ *     A weight matrix is W[in, out]; a layer computes x @ W + b.
+ *   - Edge e runs from source src[e] to target dst[e] (message m_st of Sec. 3.1).
+ *     A triplet t = (k -> j -> i) is the pair of edges (idx_kj[t], idx_ji[t]).
+ */
+#ifndef GPGNN_H
+#define GPGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GP_OK = 0,
+  GP_BAD_ARG = -1,           /* null pointer, negative size, inconsistent sizes   */
+  GP_BUFFER_TOO_SMALL = -2,  /* workspace smaller than the *_workspace query      */
+  GP_INT32_OVERFLOW = -3,    /* edge or triplet count does not fit int32 indices  */
+  GP_HIP_ERROR = -4,         /* a HIP runtime call or kernel launch failed        */
+  GP_UNSUPPORTED_DIMS = -5   /* layer widths outside what the kernels implement   */
+} gp_status;
+
+typedef struct gp_ctx gp_ctx;
+
+/* Context: binds a device and a stream.  hip_stream may be NULL (default stream). */
+int gp_create(gp_ctx** out /*host*/, int device_id, void* hip_stream);
+void gp_destroy(gp_ctx* ctx);
+const char* gp_last_error(const gp_ctx* ctx);
+const char* gp_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Graph construction (Sec. 3.1): target atom t gets an edge from every source atom s of the
+ * same structure with |x_t - x_s| < cutoff.  The test is the fp32 expression
+ *   d2 = ((dx*dx + dy*dy) + dz*dz), dx = x_t - x_s, each operation rounded once (no FMA),
+ * compared with cutoff*cutoff in fp32.  If max_neighbors > 0, each target keeps the
+ * max_neighbors sources with the smallest key (bits(d2), s).  Open boundaries.
+ *
+ * Two phases: gp_edges_count computes per-atom in-degrees and row_ptr into the workspace and
+ * returns E on the host; the caller allocates; gp_edges_fill (same arguments, same workspace)
+ * writes the edge list sorted by (dst, src).
+ *   pos[n_atoms,3] f32; graph_ptr[n_graphs+1] i32 (atoms of structure g are
+ *   graph_ptr[g]..graph_ptr[g+1]-1); outputs src[E], dst[E], row_ptr[n_atoms+1] (in-edges of
+ *   atom i are row_ptr[i]..row_ptr[i+1]-1), dist[E] = |x_dst - x_src| (f32),
+ *   unit[E,3] = (x_dst - x_src)/dist.  dist and unit may be NULL.
+ * Errors: GP_BAD_ARG, GP_BUFFER_TOO_SMALL, GP_INT32_OVERFLOW, GP_HIP_ERROR.
+ */
+int gp_edges_workspace(int64_t n_atoms, size_t* bytes /*host*/);
+int gp_edges_count(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, int64_t n_atoms,
+                   int32_t n_graphs, float cutoff, int32_t max_neighbors,
+                   void* ws, size_t ws_bytes, int64_t* n_edges /*host*/);
+int gp_edges_fill(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, int64_t n_atoms,
+                  int32_t n_graphs, float cutoff, int32_t max_neighbors,
+                  const void* ws, size_t ws_bytes, int64_t n_edges,
+                  int32_t* src, int32_t* dst, int32_t* row_ptr, float* dist, float* unit);
+
+/* ------------------------------------------------------------------------------------------
+ * Triplet enumeration (Sec. 3.1; the sum over k in N_j \ {i} in the update equation of
+ * Sec. 3.3): for every edge e = (j->i), every edge e' = (k->j) with k != i.
+ * Input: an edge list sorted by (dst, src) with its row_ptr (as produced above).
+ * Output, "ji-major" order (idx_ji ascending, then idx_kj ascending):
+ *   idx_kj[T], idx_ji[T], seg_ptr_ji[E+1] (triplets of target edge e are
+ *   seg_ptr_ji[e]..seg_ptr_ji[e+1]-1).
+ * Optional "kj-major" view used by the backward pass (all three NULL or all three given):
+ *   perm_kj[T]     triplet ids sorted by (idx_kj, idx_ji),
+ *   idx_ji_kj[T]   idx_ji[perm_kj[q]],
+ *   seg_ptr_kj[E+1] slots of source edge e' are seg_ptr_kj[e']..seg_ptr_kj[e'+1]-1.
+ * Errors as above; T > INT32_MAX gives GP_INT32_OVERFLOW.
+ */
+int gp_triplets_workspace(int64_t n_atoms, int64_t n_edges, size_t* bytes /*host*/);
+int gp_triplets_count(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
+                      int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes,
+                      int64_t* n_triplets /*host*/);
+int gp_triplets_fill(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
+                     int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes,
+                     int64_t n_triplets, int32_t* idx_kj, int32_t* idx_ji, int32_t* seg_ptr_ji,
+                     int32_t* perm_kj, int32_t* idx_ji_kj, int32_t* seg_ptr_kj);
+
+/* ------------------------------------------------------------------------------------------
+ * Layer widths of one interaction block.
+ */
+enum { GP_VARIANT_D = 0, GP_VARIANT_G = 1 };   /* Hadamard (Sec. 3.3) / bilinear (Sec. 3.4) */
+enum { GP_F32 = 0, GP_BF16_F32ACC = 1 };       /* GEMM operand type; accumulation is fp32   */
+#define GP_MAX_RES 4
+
+typedef struct {
+  int32_t variant, dtype;
+  int32_t emb;            /* edge embedding width                                  */
+  int32_t int_emb;        /* triplet width (down-projected); emb_trip in variant G */
+  int32_t basis_emb;      /* D: width of the two-step basis projections            */
+  int32_t emb_rbf, emb_cbf, emb_bil;   /* G                                        */
+  int32_t num_radial, num_spherical, envelope_p;
+  int32_t n_res_before, n_res_after;   /* D: residual layers around the skip       */
+  float cutoff;
+} gp_dims;
+
+/* ------------------------------------------------------------------------------------------
+ * Basis functions (Sec. 3.3 names a radial basis of the edge length and a spherical basis of
+ * (d_kj, alpha_(kj,ji)); formulas are the standard ones, see the oracle's header).
+ *   rbf[E, R]        D: u(d/c) sqrt(2/c) sin(n pi d/c)/d ;  G: u(d/c) exp(-((d/c-mu_n)/Delta)^2/2)
+ *   rad[E, S*R]      D only (else NULL): u(d/c) N_ln j_l(z_ln d/c), flat index l*R + (n-1)
+ *   cos_alpha[T]     cos of the angle at j between bonds j-i and j-k = -unit[ji].unit[kj]
+ *   cos_alpha_kj[T]  the same values in kj-major order (needs perm_kj; may be NULL with it)
+ *   sbf[T, S*R]      optional materialised spherical basis rad[idx_kj[t]] * Y_l0(cos_alpha[t])
+ * The interaction kernels consume the factored form (rad per edge, cos_alpha per triplet).
+ */
+int gp_basis_forward(gp_ctx* ctx, const gp_dims* dims, const float* dist, const float* unit,
+                     const int32_t* idx_kj, const int32_t* idx_ji, const int32_t* perm_kj,
+                     int64_t n_edges, int64_t n_triplets,
+                     float* rbf, float* rad, float* cos_alpha, float* cos_alpha_kj, float* sbf);
+
+/* ------------------------------------------------------------------------------------------
+ * Interaction block (Sec. 3.3 update equation; EdgeUpdate around TripletUpdate/TripletAggr).
+ */
+typedef struct {
+  int64_t n_edges, n_triplets;
+  const int32_t* idx_kj;       /* [T] ji-major */
+  const int32_t* seg_ptr_ji;   /* [E+1]        */
+  const int32_t* idx_ji_kj;    /* [T] kj-major */
+  const int32_t* seg_ptr_kj;   /* [E+1]        */
+} gp_graph;
+
+typedef struct {
+  const float* rbf;            /* [E, R]                 */
+  const float* rad;            /* [E, S*R]   (D)         */
+  const float* cos_alpha;      /* [T] ji-major           */
+  const float* cos_alpha_kj;   /* [T] kj-major           */
+} gp_basis;
+
+/* Variant D weights, fp32, W[in,out].  The same struct (non-const use) receives gradients. */
+typedef struct {
+  float *W_ji, *b_ji, *W_kj, *b_kj;            /* [emb,emb],[emb]              */
+  float *W_rbf1, *W_rbf2;                      /* [R,basis_emb],[basis_emb,emb] */
+  float *W_down;                               /* [emb,int_emb]                */
+  float *W_sbf1, *W_sbf2;                      /* [S*R,basis_emb],[basis_emb,int_emb] */
+  float *W_up;                                 /* [int_emb,emb]                */
+  float *res_before[GP_MAX_RES][4];            /* W1,b1,W2,b2 per residual layer */
+  float *W_lin, *b_lin;
+  float *res_after[GP_MAX_RES][4];
+} gp_weights_D;
+
+/* Bytes of the activation buffer kept from forward to backward, and of scratch space. */
+int gp_block_workspace(const gp_dims* dims, int64_t n_edges, int64_t n_triplets,
+                       size_t* saved_bytes /*host*/, size_t* scratch_bytes /*host*/);
+
+/* m_out[E,emb] = Block(m_in[E,emb]).  `saved` is written for the backward pass. */
+int gp_block_forward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
+                       const gp_graph* graph, const gp_basis* basis,
+                       const float* m_in, float* m_out,
+                       void* saved, size_t saved_bytes, void* scratch, size_t scratch_bytes);
+
+/* grad_m_in[E,emb] and all weight gradients (overwritten, not accumulated) from
+ * grad_m_out[E,emb]; `saved` is the buffer the matching forward call filled. */
+int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
+                        const gp_graph* graph, const gp_basis* basis,
+                        const float* m_in, const void* saved, size_t saved_bytes,
+                        const float* grad_m_out, float* grad_m_in, gp_weights_D* grad_w,
+                        void* scratch, size_t scratch_bytes);
+
+/* ------------------------------------------------------------------------------------------
+ * The core TripletUpdate + TripletAggr kernels on their own (Sec. 3.3: Hadamard product of the
+ * gathered message with the projected basis, summed over k into edge j->i).
+ *   Streaming form: s[T,F] is a materialised per-triplet basis projection (ji-major),
+ *     a[e,f] = sum_{t in seg_ji(e)} x[idx_kj[t], f] * s[t, f].
+ *   Backward: grad_x[e',f] = sum_{t: kj(t)=e'} grad_a[ji(t),f] * s[t,f]   (kj-major walk)
+ *             grad_s[t,f]  = grad_a[ji(t),f] * x[kj(t),f].
+ */
+int gp_triplet_aggregate_fwd(gp_ctx* ctx, const gp_graph* graph, int32_t width,
+                             const float* x, const float* s, float* a);
+int gp_triplet_aggregate_bwd(gp_ctx* ctx, const gp_graph* graph, const int32_t* perm_kj,
+                             int32_t width, const float* x, const float* s, const float* grad_a,
+                             float* grad_x, float* grad_s);
+
+/* Dense layer on its own: out = act(x @ W + b), fp32 MFMA.  act: 0 none, 1 SiLU.
+ * x[rows,k], W[k,n], b[n] or NULL, out[rows,n]. */
+int gp_linear_forward(gp_ctx* ctx, const float* x, const float* W, const float* b,
+                      int64_t rows, int32_t k, int32_t n, int32_t act, float* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPGNN_H */

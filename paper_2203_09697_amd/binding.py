@@ -1,0 +1,299 @@
+"""ctypes binding of libgpgnn.so: same names as the C ABI, tensors in, tensors out."""
+import ctypes as C
+import os
+
+import torch
+
+__all__ = [
+    "GpError", "load", "library_path", "Context", "Dims", "Graph", "Basis",
+    "gp_version", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
+    "gp_block_forward_D", "gp_block_backward_D", "gp_triplet_aggregate_fwd",
+    "gp_triplet_aggregate_bwd", "gp_linear_forward", "build_graph", "weights_to_device",
+    "EXPORTED_SYMBOLS", "D_WEIGHT_ORDER",
+]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+GP_MAX_RES = 4
+STATUS = {0: "GP_OK", -1: "GP_BAD_ARG", -2: "GP_BUFFER_TOO_SMALL", -3: "GP_INT32_OVERFLOW",
+          -4: "GP_HIP_ERROR", -5: "GP_UNSUPPORTED_DIMS"}
+
+EXPORTED_SYMBOLS = [
+    "gp_create", "gp_destroy", "gp_last_error", "gp_version",
+    "gp_edges_workspace", "gp_edges_count", "gp_edges_fill",
+    "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill",
+    "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
+    "gp_triplet_aggregate_fwd", "gp_triplet_aggregate_bwd", "gp_linear_forward",
+]
+
+
+class GpError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("%s (%d): %s" % (STATUS.get(code, "?"), code, msg))
+        self.code = code
+
+
+def library_path():
+    return os.path.join(_HERE, "libgpgnn.so")
+
+
+def load():
+    """Loads the HIP library; raises if it has not been built (there is no fallback)."""
+    global _LIB
+    if _LIB is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise ImportError("%s not found: build it with `python -m paper_2203_09697_amd.build`" % path)
+        lib = C.CDLL(path)
+        lib.gp_last_error.restype = C.c_char_p
+        lib.gp_version.restype = C.c_char_p
+        lib.gp_destroy.restype = None
+        _LIB = lib
+    return _LIB
+
+
+# ------------------------------------------------------------------ C structs
+class _Dims(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "variant", "dtype", "emb", "int_emb", "basis_emb", "emb_rbf", "emb_cbf", "emb_bil",
+        "num_radial", "num_spherical", "envelope_p", "n_res_before", "n_res_after")] + [("cutoff", C.c_float)]
+
+
+class _Graph(C.Structure):
+    _fields_ = [("n_edges", C.c_int64), ("n_triplets", C.c_int64), ("idx_kj", C.c_void_p),
+                ("seg_ptr_ji", C.c_void_p), ("idx_ji_kj", C.c_void_p), ("seg_ptr_kj", C.c_void_p)]
+
+
+class _Basis(C.Structure):
+    _fields_ = [("rbf", C.c_void_p), ("rad", C.c_void_p), ("cos_alpha", C.c_void_p), ("cos_alpha_kj", C.c_void_p)]
+
+
+class _WeightsD(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in (
+        "W_ji", "b_ji", "W_kj", "b_kj", "W_rbf1", "W_rbf2", "W_down", "W_sbf1", "W_sbf2", "W_up")] + [
+        ("res_before", (C.c_void_p * 4) * GP_MAX_RES), ("W_lin", C.c_void_p), ("b_lin", C.c_void_p),
+        ("res_after", (C.c_void_p * 4) * GP_MAX_RES)]
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor required"
+    return C.c_void_p(t.data_ptr())
+
+
+def Dims(d):
+    """gp_dims from a synth.BlockDims-like object (attribute access only)."""
+    return _Dims(variant=0 if d.variant == "D" else 1, dtype=0 if d.dtype == "f32" else 1, emb=d.emb,
+                 int_emb=d.int_emb, basis_emb=d.basis_emb, emb_rbf=d.emb_rbf, emb_cbf=d.emb_cbf,
+                 emb_bil=d.emb_bil, num_radial=d.num_radial, num_spherical=d.num_spherical,
+                 envelope_p=d.envelope_p, n_res_before=d.n_res_before, n_res_after=d.n_res_after,
+                 cutoff=d.cutoff)
+
+
+def Graph(g):
+    """gp_graph from the dict returned by build_graph / gp_triplets."""
+    return _Graph(n_edges=g["n_edges"], n_triplets=g["n_triplets"], idx_kj=_ptr(g["idx_kj"]),
+                  seg_ptr_ji=_ptr(g["seg_ptr_ji"]), idx_ji_kj=_ptr(g.get("idx_ji_kj")),
+                  seg_ptr_kj=_ptr(g.get("seg_ptr_kj")))
+
+
+def Basis(b):
+    return _Basis(rbf=_ptr(b.get("rbf")), rad=_ptr(b.get("rad")), cos_alpha=_ptr(b.get("cos_alpha")),
+                  cos_alpha_kj=_ptr(b.get("cos_alpha_kj")))
+
+
+def D_WEIGHT_ORDER(dims):
+    names = ["W_ji", "b_ji", "W_kj", "b_kj", "W_rbf1", "W_rbf2", "W_down", "W_sbf1", "W_sbf2", "W_up"]
+    for r in range(dims.n_res_before):
+        names += [f"W_b{r}_1", f"b_b{r}_1", f"W_b{r}_2", f"b_b{r}_2"]
+    names += ["W_lin", "b_lin"]
+    for r in range(dims.n_res_after):
+        names += [f"W_a{r}_1", f"b_a{r}_1", f"W_a{r}_2", f"b_a{r}_2"]
+    return names
+
+
+def _weights_D(dims, w):
+    s = _WeightsD()
+    for n in ("W_ji", "b_ji", "W_kj", "b_kj", "W_rbf1", "W_rbf2", "W_down", "W_sbf1", "W_sbf2", "W_up", "W_lin", "b_lin"):
+        setattr(s, n, _ptr(w[n]))
+    for r in range(dims.n_res_before):
+        for q, n in enumerate((f"W_b{r}_1", f"b_b{r}_1", f"W_b{r}_2", f"b_b{r}_2")):
+            s.res_before[r][q] = w[n].data_ptr()
+    for r in range(dims.n_res_after):
+        for q, n in enumerate((f"W_a{r}_1", f"b_a{r}_1", f"W_a{r}_2", f"b_a{r}_2")):
+            s.res_after[r][q] = w[n].data_ptr()
+    return s
+
+
+def weights_to_device(w, device="cuda:0"):
+    """dict of numpy arrays -> dict of fp32 device tensors."""
+    return {k: torch.as_tensor(v, dtype=torch.float32).contiguous().to(device) for k, v in w.items()}
+
+
+# ------------------------------------------------------------------ context
+class Context:
+    """gp_ctx bound to a device and to torch's current stream on it (or a given stream)."""
+
+    def __init__(self, device_id=0, stream=None):
+        lib = load()
+        if not torch.cuda.is_available():
+            raise RuntimeError("gpgnn needs a GPU: torch.cuda.is_available() is False")
+        self.device = torch.device("cuda", device_id)
+        st = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self.stream = st
+        self._h = C.c_void_p()
+        rc = lib.gp_create(C.byref(self._h), C.c_int(device_id), C.c_void_p(st.cuda_stream))
+        if rc != 0:
+            raise GpError(rc, "gp_create failed")
+
+    def check(self, rc):
+        if rc != 0:
+            raise GpError(rc, load().gp_last_error(self._h).decode())
+
+    def close(self):
+        if self._h:
+            load().gp_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def gp_version():
+    return load().gp_version().decode()
+
+
+def _empty(ctx, n, dtype):
+    return torch.empty(int(n), dtype=dtype, device=ctx.device)
+
+
+# ------------------------------------------------------------------ graph
+def gp_edges(ctx, pos, graph_ptr, cutoff, max_neighbors=0):
+    """gp_edges_workspace + gp_edges_count + gp_edges_fill.  pos [N,3] f32, graph_ptr [G+1] i32 (device)."""
+    lib = load()
+    n_atoms, n_graphs = pos.shape[0], graph_ptr.shape[0] - 1
+    nbytes = C.c_size_t()
+    ctx.check(lib.gp_edges_workspace(C.c_int64(n_atoms), C.byref(nbytes)))
+    ws = _empty(ctx, max(nbytes.value, 8), torch.uint8)
+    n_edges = C.c_int64()
+    args = (ctx._h, _ptr(pos), _ptr(graph_ptr), C.c_int64(n_atoms), C.c_int32(n_graphs), C.c_float(cutoff),
+            C.c_int32(max_neighbors), _ptr(ws), C.c_size_t(ws.numel()))
+    ctx.check(lib.gp_edges_count(*args, C.byref(n_edges)))
+    E = n_edges.value
+    out = dict(n_atoms=n_atoms, n_edges=E, src=_empty(ctx, E, torch.int32), dst=_empty(ctx, E, torch.int32),
+               row_ptr=_empty(ctx, n_atoms + 1, torch.int32), dist=_empty(ctx, E, torch.float32),
+               unit=torch.empty((E, 3), dtype=torch.float32, device=ctx.device))
+    ctx.check(lib.gp_edges_fill(*args, C.c_int64(E), _ptr(out["src"]), _ptr(out["dst"]), _ptr(out["row_ptr"]),
+                                _ptr(out["dist"]), _ptr(out["unit"])))
+    return out
+
+
+def gp_triplets(ctx, edges, with_kj=True):
+    """gp_triplets_workspace + gp_triplets_count + gp_triplets_fill on an edge dict from gp_edges."""
+    lib = load()
+    N, E = edges["n_atoms"], edges["n_edges"]
+    nbytes = C.c_size_t()
+    ctx.check(lib.gp_triplets_workspace(C.c_int64(N), C.c_int64(E), C.byref(nbytes)))
+    ws = _empty(ctx, max(nbytes.value, 8), torch.uint8)
+    n_trip = C.c_int64()
+    args = (ctx._h, _ptr(edges["src"]), _ptr(edges["dst"]), _ptr(edges["row_ptr"]), C.c_int64(N), C.c_int64(E),
+            _ptr(ws), C.c_size_t(ws.numel()))
+    ctx.check(lib.gp_triplets_count(*args, C.byref(n_trip)))
+    T = n_trip.value
+    out = dict(n_edges=E, n_triplets=T, idx_kj=_empty(ctx, T, torch.int32), idx_ji=_empty(ctx, T, torch.int32),
+               seg_ptr_ji=_empty(ctx, E + 1, torch.int32))
+    if with_kj:
+        out.update(perm_kj=_empty(ctx, T, torch.int32), idx_ji_kj=_empty(ctx, T, torch.int32),
+                   seg_ptr_kj=_empty(ctx, E + 1, torch.int32))
+    ctx.check(lib.gp_triplets_fill(*args, C.c_int64(T), _ptr(out["idx_kj"]), _ptr(out["idx_ji"]),
+                                   _ptr(out["seg_ptr_ji"]), _ptr(out.get("perm_kj")), _ptr(out.get("idx_ji_kj")),
+                                   _ptr(out.get("seg_ptr_kj"))))
+    return out
+
+
+def build_graph(ctx, pos, graph_ptr, cutoff, max_neighbors=0):
+    """Edges and triplets for device tensors pos / graph_ptr; returns (edges dict, triplets dict)."""
+    e = gp_edges(ctx, pos, graph_ptr, cutoff, max_neighbors)
+    return e, gp_triplets(ctx, e)
+
+
+# ------------------------------------------------------------------ basis
+def gp_basis_forward(ctx, dims, edges, trip, want_sbf=False):
+    lib = load()
+    E, T = edges["n_edges"], trip["n_triplets"]
+    S, R = dims.num_spherical, dims.num_radial
+    out = dict(rbf=torch.empty((E, R), dtype=torch.float32, device=ctx.device),
+               cos_alpha=_empty(ctx, T, torch.float32))
+    if dims.variant == "D":
+        out["rad"] = torch.empty((E, S * R), dtype=torch.float32, device=ctx.device)
+    if "perm_kj" in trip:
+        out["cos_alpha_kj"] = _empty(ctx, T, torch.float32)
+    if want_sbf:
+        out["sbf"] = torch.empty((T, S * R), dtype=torch.float32, device=ctx.device)
+    d = Dims(dims)
+    ctx.check(lib.gp_basis_forward(ctx._h, C.byref(d), _ptr(edges["dist"]), _ptr(edges["unit"]), _ptr(trip["idx_kj"]),
+                                   _ptr(trip["idx_ji"]), _ptr(trip.get("perm_kj")), C.c_int64(E), C.c_int64(T),
+                                   _ptr(out["rbf"]), _ptr(out.get("rad")), _ptr(out["cos_alpha"]),
+                                   _ptr(out.get("cos_alpha_kj")), _ptr(out.get("sbf"))))
+    return out
+
+
+# ------------------------------------------------------------------ block
+def gp_block_workspace(dims, n_edges, n_triplets):
+    lib = load()
+    d = Dims(dims)
+    a, b = C.c_size_t(), C.c_size_t()
+    rc = lib.gp_block_workspace(C.byref(d), C.c_int64(n_edges), C.c_int64(n_triplets), C.byref(a), C.byref(b))
+    if rc != 0:
+        raise GpError(rc, "gp_block_workspace")
+    return a.value, b.value
+
+
+def gp_block_forward_D(ctx, dims, w, trip, basis, m_in, m_out, saved, scratch):
+    lib = load()
+    d, g, b, ws = Dims(dims), Graph(trip), Basis(basis), _weights_D(dims, w)
+    ctx.check(lib.gp_block_forward_D(ctx._h, C.byref(d), C.byref(ws), C.byref(g), C.byref(b), _ptr(m_in), _ptr(m_out),
+                                     _ptr(saved), C.c_size_t(saved.numel()), _ptr(scratch), C.c_size_t(scratch.numel())))
+    return m_out
+
+
+def gp_block_backward_D(ctx, dims, w, trip, basis, m_in, saved, grad_m_out, grad_m_in, grad_w, scratch):
+    lib = load()
+    d, g, b = Dims(dims), Graph(trip), Basis(basis)
+    ws, gws = _weights_D(dims, w), _weights_D(dims, grad_w)
+    ctx.check(lib.gp_block_backward_D(ctx._h, C.byref(d), C.byref(ws), C.byref(g), C.byref(b), _ptr(m_in), _ptr(saved),
+                                      C.c_size_t(saved.numel()), _ptr(grad_m_out), _ptr(grad_m_in), C.byref(gws),
+                                      _ptr(scratch), C.c_size_t(scratch.numel())))
+    return grad_m_in, grad_w
+
+
+# ------------------------------------------------------------------ core kernels on their own
+def gp_triplet_aggregate_fwd(ctx, trip, x, s, a=None):
+    lib = load()
+    g = Graph(trip)
+    if a is None:
+        a = torch.empty_like(x)
+    ctx.check(lib.gp_triplet_aggregate_fwd(ctx._h, C.byref(g), C.c_int32(x.shape[1]), _ptr(x), _ptr(s), _ptr(a)))
+    return a
+
+
+def gp_triplet_aggregate_bwd(ctx, trip, x, s, grad_a):
+    lib = load()
+    g = Graph(trip)
+    gx, gs = torch.empty_like(x), torch.empty_like(s)
+    ctx.check(lib.gp_triplet_aggregate_bwd(ctx._h, C.byref(g), _ptr(trip["perm_kj"]), C.c_int32(x.shape[1]), _ptr(x),
+                                           _ptr(s), _ptr(grad_a), _ptr(gx), _ptr(gs)))
+    return gx, gs
+
+
+def gp_linear_forward(ctx, x, W, b=None, act=0):
+    lib = load()
+    out = torch.empty((x.shape[0], W.shape[1]), dtype=torch.float32, device=ctx.device)
+    ctx.check(lib.gp_linear_forward(ctx._h, _ptr(x), _ptr(W), _ptr(b), C.c_int64(x.shape[0]), C.c_int32(W.shape[0]),
+                                    C.c_int32(W.shape[1]), C.c_int32(act), _ptr(out)))
+    return out

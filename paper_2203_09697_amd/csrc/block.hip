@@ -1,0 +1,311 @@
+// Interaction block, variant D (paper Sec. 3.3): the EdgeUpdate MLPs around
+// TripletUpdate/TripletAggr, forward and hand-derived backward.  Pure launch sequencing on the
+// context's stream; every arithmetic step runs in the kernels of gemm.hip / triplet.hip.
+//
+//   x_ji = act(m W_ji + b_ji)
+//   x_kj = act(m W_kj + b_kj) * (rbf (W_rbf1 W_rbf2));  x_kj = act(x_kj W_down)
+//   a_e  = sum_{t in seg(e)} x_kj[kj(t)] * ((sbf_t W_sbf1) W_sbf2)
+//   h    = x_ji + act(a W_up);  residual layers;  h = act(h W_lin + b_lin) + m;  residual layers
+#include <stdarg.h>
+
+#include <algorithm>
+
+#include "gemm.h"
+#include "triplet.h"
+
+namespace {
+
+struct res_saved {
+  float *z1, *y1, *z2, *hout;
+};
+
+struct saved_D {
+  float *z_ji, *z_kj, *gate, *xg, *z_dn, *x_kj, *Q, *Bacc, *a, *z_up, *h0, *z_lin, *h_lin, *Wrbf;
+  res_saved before[GP_MAX_RES], after[GP_MAX_RES];
+};
+
+size_t carve_saved_D(void* p, const gp_dims* d, int64_t E, saved_D* s) {
+  gp_carver c(p);
+  const size_t H = d->emb, F = d->int_emb, B = d->basis_emb, S = d->num_spherical, R = d->num_radial;
+  s->z_ji = c.take<float>(E * H);
+  s->z_kj = c.take<float>(E * H);
+  s->gate = c.take<float>(E * H);
+  s->xg = c.take<float>(E * H);
+  s->z_dn = c.take<float>(E * F);
+  s->x_kj = c.take<float>(E * F);
+  s->Q = c.take<float>(E * S * B);
+  s->Bacc = c.take<float>(E * B * F);
+  s->a = c.take<float>(E * F);
+  s->z_up = c.take<float>(E * H);
+  s->h0 = c.take<float>(E * H);
+  s->z_lin = c.take<float>(E * H);
+  s->h_lin = c.take<float>(E * H);
+  s->Wrbf = c.take<float>(R * H);
+  for (int r = 0; r < d->n_res_before; ++r) {
+    s->before[r].z1 = c.take<float>(E * H);
+    s->before[r].y1 = c.take<float>(E * H);
+    s->before[r].z2 = c.take<float>(E * H);
+    s->before[r].hout = c.take<float>(E * H);
+  }
+  for (int r = 0; r < d->n_res_after; ++r) {
+    s->after[r].z1 = c.take<float>(E * H);
+    s->after[r].y1 = c.take<float>(E * H);
+    s->after[r].z2 = c.take<float>(E * H);
+    s->after[r].hout = c.take<float>(E * H);   // the last one is unused: the block output goes to m_out
+  }
+  return c.off;
+}
+
+struct scratch_D {
+  float* buf[7];     // [E,H] each
+  float *dF1, *dF2;  // [E,F]
+  float* dQ;         // [E,S*B]
+  float* dWrbf;      // [R,H]
+  float* part;
+  size_t part_bytes;
+};
+
+size_t part_bytes_D(const gp_dims* d, int64_t E) {
+  const int H = d->emb, F = d->int_emb, B = d->basis_emb, S = d->num_spherical, R = d->num_radial;
+  size_t m = gp_gemm_tn_scratch(E, H, H);
+  m = std::max(m, gp_gemm_tn_scratch(E, F, H));
+  m = std::max(m, gp_gemm_tn_scratch(E, H, F));
+  m = std::max(m, gp_gemm_tn_scratch(E, R, H));
+  m = std::max(m, gp_gemm_tn_scratch(R, B, H));
+  m = std::max(m, gp_colsum_scratch(E, H));
+  m = std::max(m, gp_tripD_wgrad_scratch(E, F, S, R, B));
+  return m;
+}
+
+size_t carve_scratch_D(void* p, const gp_dims* d, int64_t E, scratch_D* s) {
+  gp_carver c(p);
+  const size_t H = d->emb, F = d->int_emb, B = d->basis_emb, S = d->num_spherical, R = d->num_radial;
+  for (int i = 0; i < 7; ++i) s->buf[i] = c.take<float>(E * H);
+  s->dF1 = c.take<float>(E * F);
+  s->dF2 = c.take<float>(E * F);
+  s->dQ = c.take<float>(E * S * B);
+  s->dWrbf = c.take<float>(R * H);
+  s->part_bytes = part_bytes_D(d, E);
+  s->part = (float*)c.take<char>(s->part_bytes);
+  return c.off;
+}
+
+int check_dims_D(gp_ctx* ctx, const gp_dims* d) {
+  GP_REQUIRE(ctx, d, "dims is NULL");
+  if (d->variant != GP_VARIANT_D) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "variant %d is not the Hadamard block", d->variant);
+  if (d->dtype != GP_F32) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "variant D is implemented in fp32 only");
+  if (d->emb < 1 || d->emb > 4096 || d->int_emb < 1 || d->int_emb > 256 || d->basis_emb < 1 || d->basis_emb > 16 ||
+      d->num_spherical < 1 || d->num_spherical > 8 || d->num_radial < 1 || d->num_radial > 16 ||
+      d->n_res_before < 0 || d->n_res_before > GP_MAX_RES || d->n_res_after < 0 || d->n_res_after > GP_MAX_RES)
+    return gp_fail(ctx, GP_UNSUPPORTED_DIMS,
+                   "variant D supports emb<=4096, int_emb<=256, basis_emb<=16, num_spherical<=8, num_radial<=16, "
+                   "residual layers<=%d (got %d,%d,%d,%d,%d,%d,%d)", GP_MAX_RES, d->emb, d->int_emb, d->basis_emb,
+                   d->num_spherical, d->num_radial, d->n_res_before, d->n_res_after);
+  return GP_OK;
+}
+
+int check_weights_D(gp_ctx* ctx, const gp_dims* d, const gp_weights_D* w, const char* what) {
+  GP_REQUIRE(ctx, w, "%s is NULL", what);
+  bool ok = w->W_ji && w->b_ji && w->W_kj && w->b_kj && w->W_rbf1 && w->W_rbf2 && w->W_down && w->W_sbf1 &&
+            w->W_sbf2 && w->W_up && w->W_lin && w->b_lin;
+  for (int r = 0; r < d->n_res_before; ++r)
+    for (int q = 0; q < 4; ++q) ok = ok && w->res_before[r][q];
+  for (int r = 0; r < d->n_res_after; ++r)
+    for (int q = 0; q < 4; ++q) ok = ok && w->res_after[r][q];
+  GP_REQUIRE(ctx, ok, "%s has a NULL member", what);
+  return GP_OK;
+}
+
+// one residual layer forward: hout = hin + act(act(hin W1 + b1) W2 + b2)
+int res_forward(gp_ctx* ctx, const float* hin, float* const* w, const res_saved& s, float* hout, int64_t E, int H) {
+  gp_epilogue e1;
+  e1.bias = w[1]; e1.save_pre = s.z1; e1.act = 1; e1.out = s.y1;
+  GP_TRY(gp_gemm_nn(ctx, hin, w[0], E, H, H, e1));
+  gp_epilogue e2;
+  e2.bias = w[3]; e2.save_pre = s.z2; e2.act = 1; e2.add_post = hin; e2.out = hout;
+  return gp_gemm_nn(ctx, s.y1, w[2], E, H, H, e2);
+}
+
+// one residual layer backward; dh_out = dh + d(hin through the layer)
+int res_backward(gp_ctx* ctx, const float* hin, float* const* w, float* const* gw, const res_saved& s,
+                 const float* dh, float* dh_out, float* t1, float* t2, scratch_D& sc, int64_t E, int H) {
+  GP_TRY(gp_ew_dsilu_mul(ctx, dh, s.z2, t1, E * H));                                    // dz2
+  GP_TRY(gp_gemm_tn(ctx, s.y1, t1, E, H, H, gw[2], sc.part, sc.part_bytes));            // dW2
+  GP_TRY(gp_colsum(ctx, t1, E, H, gw[3], sc.part, sc.part_bytes));                      // db2
+  gp_epilogue e;
+  e.act = 2; e.zsrc = s.z1; e.out = t2;
+  GP_TRY(gp_gemm_nt(ctx, t1, w[2], E, H, H, e));                                        // dz1
+  GP_TRY(gp_gemm_tn(ctx, hin, t2, E, H, H, gw[0], sc.part, sc.part_bytes));             // dW1
+  GP_TRY(gp_colsum(ctx, t2, E, H, gw[1], sc.part, sc.part_bytes));                      // db1
+  gp_epilogue e2;
+  e2.add_post = dh; e2.out = dh_out;
+  return gp_gemm_nt(ctx, t2, w[0], E, H, H, e2);
+}
+
+}  // namespace
+
+extern "C" {
+
+int gp_block_workspace(const gp_dims* dims, int64_t n_edges, int64_t n_triplets, size_t* saved_bytes,
+                       size_t* scratch_bytes) {
+  if (!dims || !saved_bytes || !scratch_bytes || n_edges < 0 || n_triplets < 0) return GP_BAD_ARG;
+  if (dims->variant == GP_VARIANT_D) {
+    saved_D s;
+    scratch_D sc;
+    *saved_bytes = carve_saved_D(nullptr, dims, n_edges, &s);
+    *scratch_bytes = carve_scratch_D(nullptr, dims, n_edges, &sc);
+    return GP_OK;
+  }
+  return GP_UNSUPPORTED_DIMS;
+}
+
+int gp_block_forward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, const gp_graph* graph,
+                       const gp_basis* basis, const float* m_in, float* m_out, void* saved, size_t saved_bytes,
+                       void* scratch, size_t scratch_bytes) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_TRY(check_dims_D(ctx, dims));
+  GP_TRY(check_weights_D(ctx, dims, w, "weights"));
+  GP_REQUIRE(ctx, graph && basis, "gp_block_forward_D: graph/basis is NULL");
+  const int64_t E = graph->n_edges;
+  GP_REQUIRE(ctx, E >= 0 && graph->n_triplets >= 0, "gp_block_forward_D: negative size");
+  if (E == 0) return GP_OK;
+  GP_REQUIRE(ctx, m_in && m_out && saved && scratch, "gp_block_forward_D: NULL pointer");
+  GP_REQUIRE(ctx, basis->rbf && basis->rad && (graph->n_triplets == 0 || basis->cos_alpha), "gp_block_forward_D: basis arrays missing");
+  saved_D s;
+  scratch_D sc;
+  if (saved_bytes < carve_saved_D(saved, dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_D: saved buffer too small");
+  if (scratch_bytes < carve_scratch_D(scratch, dims, E, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_D: scratch too small");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  const int H = dims->emb, F = dims->int_emb, B = dims->basis_emb, S = dims->num_spherical, R = dims->num_radial;
+  float* x_ji = sc.buf[0];
+
+  gp_epilogue e;
+  e.bias = w->b_ji; e.save_pre = s.z_ji; e.act = 1; e.out = x_ji;
+  GP_TRY(gp_gemm_nn(ctx, m_in, w->W_ji, E, H, H, e));
+  e = gp_epilogue(); e.out = s.Wrbf;
+  GP_TRY(gp_gemm_nn(ctx, w->W_rbf1, w->W_rbf2, R, H, B, e));
+  e = gp_epilogue(); e.out = s.gate;
+  GP_TRY(gp_gemm_nn(ctx, basis->rbf, s.Wrbf, E, H, R, e));
+  e = gp_epilogue(); e.bias = w->b_kj; e.save_pre = s.z_kj; e.act = 1; e.mul = s.gate; e.out = s.xg;
+  GP_TRY(gp_gemm_nn(ctx, m_in, w->W_kj, E, H, H, e));
+  e = gp_epilogue(); e.save_pre = s.z_dn; e.act = 1; e.out = s.x_kj;
+  GP_TRY(gp_gemm_nn(ctx, s.xg, w->W_down, E, F, H, e));
+  GP_TRY(gp_tripD_project_radial(ctx, basis->rad, w->W_sbf1, E, S, R, B, s.Q));
+  GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a, s.Bacc));
+  e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = x_ji; e.out = s.h0;
+  GP_TRY(gp_gemm_nn(ctx, s.a, w->W_up, E, H, F, e));
+
+  const float* h = s.h0;
+  for (int r = 0; r < dims->n_res_before; ++r) {
+    GP_TRY(res_forward(ctx, h, w->res_before[r], s.before[r], s.before[r].hout, E, H));
+    h = s.before[r].hout;
+  }
+  float* lin_out = dims->n_res_after == 0 ? m_out : s.h_lin;
+  e = gp_epilogue(); e.bias = w->b_lin; e.save_pre = s.z_lin; e.act = 1; e.add_post = m_in; e.out = lin_out;
+  GP_TRY(gp_gemm_nn(ctx, h, w->W_lin, E, H, H, e));
+  h = lin_out;
+  for (int r = 0; r < dims->n_res_after; ++r) {
+    float* out = (r == dims->n_res_after - 1) ? m_out : s.after[r].hout;
+    GP_TRY(res_forward(ctx, h, w->res_after[r], s.after[r], out, E, H));
+    h = out;
+  }
+  return GP_OK;
+}
+
+int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, const gp_graph* graph,
+                        const gp_basis* basis, const float* m_in, const void* saved, size_t saved_bytes,
+                        const float* grad_m_out, float* grad_m_in, gp_weights_D* gw, void* scratch,
+                        size_t scratch_bytes) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_TRY(check_dims_D(ctx, dims));
+  GP_TRY(check_weights_D(ctx, dims, w, "weights"));
+  GP_TRY(check_weights_D(ctx, dims, gw, "grad_w"));
+  GP_REQUIRE(ctx, graph && basis, "gp_block_backward_D: graph/basis is NULL");
+  const int64_t E = graph->n_edges;
+  GP_REQUIRE(ctx, E >= 0 && graph->n_triplets >= 0, "gp_block_backward_D: negative size");
+  GP_REQUIRE(ctx, E > 0, "gp_block_backward_D: empty edge list");
+  GP_REQUIRE(ctx, m_in && grad_m_out && grad_m_in && saved && scratch, "gp_block_backward_D: NULL pointer");
+  GP_REQUIRE(ctx, basis->rbf && basis->rad && (graph->n_triplets == 0 || basis->cos_alpha_kj), "gp_block_backward_D: basis arrays missing");
+  saved_D s;
+  scratch_D sc;
+  if (saved_bytes < carve_saved_D(const_cast<void*>(saved), dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_D: saved buffer too small");
+  if (scratch_bytes < carve_scratch_D(scratch, dims, E, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_D: scratch too small");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  const int H = dims->emb, F = dims->int_emb, B = dims->basis_emb, S = dims->num_spherical, R = dims->num_radial;
+  const int64_t EH = E * H;
+  float *T1 = sc.buf[3], *T2 = sc.buf[4], *T3 = sc.buf[5], *dgate = sc.buf[6];
+  // rotating buffers for dh; `keep` is a gradient that must survive (the skip into m)
+  const float* dh = grad_m_out;
+  const float* keep = nullptr;
+  auto next_buf = [&]() -> float* {
+    for (int i = 0; i < 3; ++i)
+      if (sc.buf[i] != dh && sc.buf[i] != keep) return sc.buf[i];
+    return nullptr;
+  };
+
+  // residual layers after the skip, last to first
+  for (int r = dims->n_res_after - 1; r >= 0; --r) {
+    const float* hin = (r == 0) ? s.h_lin : s.after[r - 1].hout;
+    float* out = next_buf();
+    GP_TRY(res_backward(ctx, hin, w->res_after[r], gw->res_after[r], s.after[r], dh, out, T1, T2, sc, E, H));
+    dh = out;
+  }
+  // h_lin = act(h W_lin + b_lin) + m
+  keep = dh;
+  {
+    const float* hin = dims->n_res_before > 0 ? s.before[dims->n_res_before - 1].hout : s.h0;
+    GP_TRY(gp_ew_dsilu_mul(ctx, dh, s.z_lin, T1, EH));
+    GP_TRY(gp_gemm_tn(ctx, hin, T1, E, H, H, gw->W_lin, sc.part, sc.part_bytes));
+    GP_TRY(gp_colsum(ctx, T1, E, H, gw->b_lin, sc.part, sc.part_bytes));
+    float* out = next_buf();
+    gp_epilogue e; e.out = out;
+    GP_TRY(gp_gemm_nt(ctx, T1, w->W_lin, E, H, H, e));
+    dh = out;
+  }
+  for (int r = dims->n_res_before - 1; r >= 0; --r) {
+    const float* hin = (r == 0) ? s.h0 : s.before[r - 1].hout;
+    float* out = next_buf();
+    GP_TRY(res_backward(ctx, hin, w->res_before[r], gw->res_before[r], s.before[r], dh, out, T1, T2, sc, E, H));
+    dh = out;
+  }
+  // h0 = x_ji + act(a W_up)
+  GP_TRY(gp_ew_dsilu_mul(ctx, dh, s.z_up, T1, EH));                                          // dz_up
+  GP_TRY(gp_gemm_tn(ctx, s.a, T1, E, F, H, gw->W_up, sc.part, sc.part_bytes));
+  {
+    gp_epilogue e; e.out = sc.dF1;
+    GP_TRY(gp_gemm_nt(ctx, T1, w->W_up, E, F, H, e));                                        // da
+  }
+  // triplet interaction
+  GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, s.x_kj, s.Q, w->W_sbf2, sc.dF1, s.z_dn, F, S, B,
+                           sc.dF2, sc.dQ));                                                   // dz_dn, dQ
+  GP_TRY(gp_tripD_weight_grads(ctx, sc.dF1, s.Bacc, basis->rad, sc.dQ, E, F, S, R, B, gw->W_sbf2, gw->W_sbf1,
+                               sc.part, sc.part_bytes));
+  GP_TRY(gp_gemm_tn(ctx, s.xg, sc.dF2, E, H, F, gw->W_down, sc.part, sc.part_bytes));
+  {
+    gp_epilogue e; e.out = T2;
+    GP_TRY(gp_gemm_nt(ctx, sc.dF2, w->W_down, E, H, F, e));                                  // dxg
+  }
+  GP_TRY(gp_ew_gate_bwd(ctx, T2, s.z_kj, s.gate, T3, dgate, EH));                            // dz_kj, dgate
+  GP_TRY(gp_gemm_tn(ctx, basis->rbf, dgate, E, R, H, sc.dWrbf, sc.part, sc.part_bytes));
+  {
+    gp_epilogue e; e.out = gw->W_rbf1;
+    GP_TRY(gp_gemm_nt(ctx, sc.dWrbf, w->W_rbf2, R, B, H, e));
+  }
+  GP_TRY(gp_gemm_tn(ctx, w->W_rbf1, sc.dWrbf, R, B, H, gw->W_rbf2, sc.part, sc.part_bytes));
+  GP_TRY(gp_gemm_tn(ctx, m_in, T3, E, H, H, gw->W_kj, sc.part, sc.part_bytes));
+  GP_TRY(gp_colsum(ctx, T3, E, H, gw->b_kj, sc.part, sc.part_bytes));
+  {
+    gp_epilogue e; e.add_post = keep; e.out = grad_m_in;
+    GP_TRY(gp_gemm_nt(ctx, T3, w->W_kj, E, H, H, e));                                        // dm = skip + kj path
+  }
+  GP_TRY(gp_ew_dsilu_mul(ctx, dh, s.z_ji, T1, EH));                                          // dz_ji
+  GP_TRY(gp_gemm_tn(ctx, m_in, T1, E, H, H, gw->W_ji, sc.part, sc.part_bytes));
+  GP_TRY(gp_colsum(ctx, T1, E, H, gw->b_ji, sc.part, sc.part_bytes));
+  {
+    gp_epilogue e; e.add_post = grad_m_in; e.out = grad_m_in;
+    GP_TRY(gp_gemm_nt(ctx, T1, w->W_ji, E, H, H, e));                                        // dm += ji path
+  }
+  return GP_OK;
+}
+
+}  // extern "C"

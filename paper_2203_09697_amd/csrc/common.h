@@ -1,0 +1,89 @@
+// Internal helpers shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/gpgnn.h"
+
+struct gp_ctx {
+  int device;
+  hipStream_t stream;
+  char err[512];
+};
+
+inline int gp_fail(gp_ctx* ctx, int code, const char* fmt, ...) __attribute__((format(printf, 3, 4)));
+inline int gp_fail(gp_ctx* ctx, int code, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+#define GP_HIP(ctx, expr)                                                                  \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess)                                                                  \
+      return gp_fail((ctx), GP_HIP_ERROR, "%s failed: %s (%s:%d)", #expr,                  \
+                     hipGetErrorString(_e), __FILE__, __LINE__);                           \
+  } while (0)
+
+#define GP_LAUNCH_CHECK(ctx, name)                                                         \
+  do {                                                                                     \
+    hipError_t _e = hipGetLastError();                                                     \
+    if (_e != hipSuccess)                                                                  \
+      return gp_fail((ctx), GP_HIP_ERROR, "launch of %s failed: %s", name,                 \
+                     hipGetErrorString(_e));                                               \
+  } while (0)
+
+#define GP_REQUIRE(ctx, cond, ...)                                                         \
+  do {                                                                                     \
+    if (!(cond)) return gp_fail((ctx), GP_BAD_ARG, __VA_ARGS__);                           \
+  } while (0)
+
+#define GP_TRY(expr)                                                                       \
+  do {                                                                                     \
+    int _s = (expr);                                                                       \
+    if (_s != GP_OK) return _s;                                                            \
+  } while (0)
+
+static inline size_t gp_align(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Sequential carve-out of a caller-provided buffer.
+struct gp_carver {
+  char* base;
+  size_t off;
+  explicit gp_carver(void* p) : base((char*)p), off(0) {}
+  template <class T>
+  T* take(size_t n) {
+    T* r = base ? (T*)(base + off) : nullptr;
+    off += gp_align(n * sizeof(T));
+    return r;
+  }
+};
+
+constexpr int WAVE = 64;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
+
+// number of set bits of `mask` strictly below this lane
+__device__ __forceinline__ int mbcnt(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+// d/dz [ z * sigmoid(z) ]
+__device__ __forceinline__ float dsilu_f(float z) {
+  float s = 1.0f / (1.0f + __expf(-z));
+  return s * (1.0f + z * (1.0f - s));
+}

@@ -1,0 +1,39 @@
+// Dense fp32 building blocks used by the interaction block (internal, not part of the C ABI).
+#pragma once
+#include "common.h"
+
+// What happens to an accumulator value v at (row, col) before it is stored.  Steps run in
+// this order; null pointers / zero flags skip a step.  All matrices are [rows, n] row-major.
+struct gp_epilogue {
+  const float* bias = nullptr;      // v += bias[col]
+  const float* add_pre = nullptr;   // v += add_pre[row,col]
+  float* save_pre = nullptr;        // save_pre[row,col] = v            (pre-activation)
+  int act = 0;                      // 1: v = silu(v); 2: v *= silu'(zsrc[row,col])
+  const float* zsrc = nullptr;
+  const float* mul = nullptr;       // v *= mul[row,col]
+  const float* add_post = nullptr;  // v += add_post[row,col]
+  float scale = 1.0f;               // v *= scale
+  float* out = nullptr;             // out[row,col] = v
+  float* out2 = nullptr;            // out2[row,col] = v * silu'(z2src[row,col])
+  const float* z2src = nullptr;
+};
+
+// C = A[M,K] @ B[K,N]
+int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi);
+// C = A[M,K] @ Bt[N,K]^T
+int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi);
+// out[M,N] = A[rows,M]^T @ B[rows,N]; deterministic two-stage reduction through `part`
+size_t gp_gemm_tn_scratch(int64_t rows, int M, int N);
+int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M, int N, float* out,
+               float* part, size_t part_bytes);
+// out[n] = sum_r X[r,n]
+size_t gp_colsum_scratch(int64_t rows, int N);
+int gp_colsum(gp_ctx* ctx, const float* X, int64_t rows, int N, float* out, float* part, size_t part_bytes);
+
+// elementwise helpers, n elements
+int gp_ew_dsilu_mul(gp_ctx* ctx, const float* g, const float* z, float* out, int64_t n);   // out = g * silu'(z)
+int gp_ew_gate_bwd(gp_ctx* ctx, const float* dxg, const float* z, const float* gate, float* dz, float* dgate,
+                   int64_t n);   // dz = dxg*gate*silu'(z), dgate = dxg*silu(z)
+int gp_ew_add3(gp_ctx* ctx, const float* a, const float* b, const float* c, float* out, int64_t n);  // c may be NULL
+// out[i] = sum_z part[z*n + i], z < splits
+int gp_reduce_parts(gp_ctx* ctx, const float* part, int splits, int64_t n, float* out);

@@ -1,0 +1,431 @@
+// Radius-graph construction and triplet enumeration (paper Sec. 3.1; the index set
+// N_j \ {i} of the update equation in Sec. 3.3).  Integer outputs are bit-exact and
+// deterministic: positions are compared with an uncontracted fp32 expression, output
+// slots come from wavefront ballots and prefix counts, never from atomics' arrival order.
+#include <stdarg.h>
+
+#include "common.h"
+
+namespace {
+
+// ------------------------------------------------------------------ exclusive scan
+// One workgroup walks the array in chunks of its own size, carrying the running total.
+// in[n] (int32) -> out[n+1] (int32, exclusive prefix, out[n] = total); total64 gets the
+// untruncated sum so the host can detect int32 overflow.
+constexpr int SCAN_THREADS = 1024;
+__global__ void __launch_bounds__(SCAN_THREADS)
+scan_exclusive_kernel(const int32_t* __restrict__ in, int32_t* __restrict__ out, int64_t n,
+                      int64_t* __restrict__ total64) {
+  __shared__ int64_t wave_tot[SCAN_THREADS / WAVE];
+  __shared__ int64_t carry_s;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int64_t base = 0; base < n; base += SCAN_THREADS) {
+    int64_t i = base + tid;
+    int64_t v = (i < n) ? (int64_t)in[i] : 0;
+    int64_t incl = v;
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+      int64_t u = __shfl_up(incl, o, WAVE);
+      if (lane >= o) incl += u;
+    }
+    if (lane == WAVE - 1) wave_tot[w] = incl;
+    __syncthreads();
+    int64_t before = carry_s;
+    for (int k = 0; k < w; ++k) before += wave_tot[k];
+    if (i < n) out[i] = (int32_t)(before + incl - v);
+    __syncthreads();
+    if (tid == SCAN_THREADS - 1) carry_s = before + incl;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    out[n] = (int32_t)carry_s;
+    *total64 = carry_s;
+  }
+}
+
+// ------------------------------------------------------------------ edges
+// The distance predicate: every operation rounded once to fp32, no fused multiply-add.
+__device__ __forceinline__ float dist2_f32(float xi, float yi, float zi, float xj, float yj, float zj) {
+#pragma clang fp contract(off)
+  float dx = __fsub_rn(xi, xj), dy = __fsub_rn(yi, yj), dz = __fsub_rn(zi, zj);
+  return __fadd_rn(__fadd_rn(__fmul_rn(dx, dx), __fmul_rn(dy, dy)), __fmul_rn(dz, dz));
+}
+
+// One wavefront per target atom i.  FILL = false: deg[i] = number of kept sources.
+// FILL = true: write the kept sources in ascending order at row_ptr[i].
+template <bool FILL>
+__global__ void __launch_bounds__(256)
+edges_kernel(const float* __restrict__ pos, const int32_t* __restrict__ graph_ptr, int n_atoms,
+             int n_graphs, float c2, int max_nb, int32_t* __restrict__ deg,
+             const int32_t* __restrict__ row_ptr, int32_t* __restrict__ src, int32_t* __restrict__ dst,
+             float* __restrict__ dist, float* __restrict__ unit) {
+  const int i = blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x >> 6);
+  if (i >= n_atoms) return;
+  const int lane = lane_id();
+  // structure containing atom i: largest g with graph_ptr[g] <= i
+  int lo_g = 0, hi_g = n_graphs;
+  while (hi_g - lo_g > 1) {
+    int mid = (lo_g + hi_g) >> 1;
+    if (graph_ptr[mid] <= i) lo_g = mid; else hi_g = mid;
+  }
+  const int lo = graph_ptr[lo_g], hi = graph_ptr[lo_g + 1];
+  const float xi = pos[3 * i], yi = pos[3 * i + 1], zi = pos[3 * i + 2];
+
+  bool capped = false;
+  if (max_nb > 0) {
+    int cand = 0;
+    for (int base = lo; base < hi; base += WAVE) {
+      int j = base + lane;
+      bool in = false;
+      if (j < hi && j != i) in = dist2_f32(xi, yi, zi, pos[3 * j], pos[3 * j + 1], pos[3 * j + 2]) < c2;
+      cand += __popcll(__ballot(in));
+    }
+    capped = cand > max_nb;
+  }
+
+  int total = 0;
+  for (int base = lo; base < hi; base += WAVE) {
+    const int j = base + lane;
+    float d2 = 0.f, xj = 0.f, yj = 0.f, zj = 0.f;
+    bool keep = false;
+    if (j < hi && j != i) {
+      xj = pos[3 * j]; yj = pos[3 * j + 1]; zj = pos[3 * j + 2];
+      d2 = dist2_f32(xi, yi, zi, xj, yj, zj);
+      keep = d2 < c2;
+    }
+    if (capped) {
+      // rank of source j among all in-range sources by key (d2, index); keep the first max_nb
+      int rank = 0;
+      for (int q = lo; q < hi; ++q) {
+        float dq = dist2_f32(xi, yi, zi, pos[3 * q], pos[3 * q + 1], pos[3 * q + 2]);
+        bool in_q = (q != i) && (dq < c2);
+        rank += (in_q && (dq < d2 || (dq == d2 && q < j))) ? 1 : 0;
+      }
+      keep = keep && (rank < max_nb);
+    }
+    const uint64_t mask = __ballot(keep);
+    if (FILL && keep) {
+      const int slot = row_ptr[i] + total + mbcnt(mask);
+      src[slot] = j;
+      dst[slot] = i;
+      if (dist || unit) {
+        float d = sqrtf(d2);
+        if (dist) dist[slot] = d;
+        if (unit) {
+          float inv = 1.0f / d;
+          unit[3 * slot + 0] = (xi - xj) * inv;
+          unit[3 * slot + 1] = (yi - yj) * inv;
+          unit[3 * slot + 2] = (zi - zj) * inv;
+        }
+      }
+    }
+    total += __popcll(mask);
+  }
+  if (!FILL && lane == 0) deg[i] = total;
+}
+
+// ------------------------------------------------------------------ triplets
+// position of value v in the ascending list a[0..n), or -1
+__device__ __forceinline__ int find_sorted(const int32_t* __restrict__ a, int n, int v) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (a[mid] < v) lo = mid + 1; else hi = mid;
+  }
+  return (lo < n && a[lo] == v) ? lo : -1;
+}
+
+// Per edge e = (j->i): cnt[e] = indeg(j) - [i->j is an edge]; skip[e] = position of source i
+// inside the in-list of j, or -1.  Also histograms out-degrees.
+__global__ void triplet_count_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                     const int32_t* __restrict__ row_ptr, int n_edges,
+                                     int32_t* __restrict__ cnt, int32_t* __restrict__ skip,
+                                     int32_t* __restrict__ out_deg) {
+  int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_edges) return;
+  int j = src[e], i = dst[e];
+  int b = row_ptr[j], n = row_ptr[j + 1] - b;
+  int p = find_sorted(src + b, n, i);
+  skip[e] = p;
+  cnt[e] = n - (p >= 0 ? 1 : 0);
+  atomicAdd(&out_deg[j], 1);
+}
+
+// One wavefront per target edge: its triplets are the in-edges of j minus the one from i.
+__global__ void __launch_bounds__(256)
+triplet_fill_ji_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ row_ptr,
+                       const int32_t* __restrict__ seg, const int32_t* __restrict__ skip, int n_edges,
+                       int32_t* __restrict__ idx_kj, int32_t* __restrict__ idx_ji) {
+  const int e = blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x >> 6);
+  if (e >= n_edges) return;
+  const int j = src[e];
+  const int b = row_ptr[j], n = row_ptr[j + 1] - b;
+  const int sk = skip[e], out = seg[e];
+  for (int r = lane_id(); r < n; r += WAVE) {
+    if (r == sk) continue;
+    int slot = out + r - ((sk >= 0 && r > sk) ? 1 : 0);
+    idx_kj[slot] = b + r;
+    idx_ji[slot] = e;
+  }
+}
+
+// Out-edge lists: first in arrival order (atomic cursor), then ordered by edge id by counting.
+__global__ void out_scatter_kernel(const int32_t* __restrict__ src, int n_edges,
+                                   const int32_t* __restrict__ out_ptr, int32_t* __restrict__ cursor,
+                                   int32_t* __restrict__ out_tmp) {
+  int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_edges) return;
+  int j = src[e];
+  out_tmp[out_ptr[j] + atomicAdd(&cursor[j], 1)] = e;
+}
+
+__global__ void __launch_bounds__(256)
+out_sort_kernel(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_tmp, int n_atoms,
+                int32_t* __restrict__ out_list) {
+  const int j = blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x >> 6);
+  if (j >= n_atoms) return;
+  const int b = out_ptr[j], n = out_ptr[j + 1] - b;
+  for (int r = lane_id(); r < n; r += WAVE) {
+    int v = out_tmp[b + r], rank = 0;
+    for (int q = 0; q < n; ++q) rank += (out_tmp[b + q] < v) ? 1 : 0;
+    out_list[b + rank] = v;
+  }
+}
+
+// Per source edge e' = (k->j): number of out-edges of j that do not end in k.
+__global__ void triplet_count_kj_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                        const int32_t* __restrict__ row_ptr,
+                                        const int32_t* __restrict__ out_ptr, int n_edges,
+                                        int32_t* __restrict__ cnt_kj) {
+  int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_edges) return;
+  int k = src[e], j = dst[e];
+  int b = row_ptr[k], n = row_ptr[k + 1] - b;           // in-list of k: does it contain j ?
+  int has_rev = find_sorted(src + b, n, j) >= 0 ? 1 : 0;
+  cnt_kj[e] = out_ptr[j + 1] - out_ptr[j] - has_rev;
+}
+
+// One wavefront per source edge e' = (k->j): walk the out-edges e = (j->i) of j in ascending
+// edge id, drop i == k, and record the ji-major triplet id of (e', e).
+__global__ void __launch_bounds__(256)
+triplet_fill_kj_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                       const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
+                       const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ji,
+                       const int32_t* __restrict__ skip, const int32_t* __restrict__ seg_kj, int n_edges,
+                       int32_t* __restrict__ perm_kj, int32_t* __restrict__ idx_ji_kj) {
+  const int ep = blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x >> 6);
+  if (ep >= n_edges) return;
+  const int k = src[ep], j = dst[ep];
+  const int r_in = ep - row_ptr[j];                      // position of e' in the in-list of j
+  const int ob = out_ptr[j], on = out_ptr[j + 1] - ob;
+  int total = 0;
+  for (int base = 0; base < on; base += WAVE) {
+    int r = base + lane_id();
+    int e = -1;
+    bool keep = false;
+    if (r < on) {
+      e = out_list[ob + r];
+      keep = dst[e] != k;
+    }
+    uint64_t mask = __ballot(keep);
+    if (keep) {
+      int slot = seg_kj[ep] + total + mbcnt(mask);
+      int sk = skip[e];
+      perm_kj[slot] = seg_ji[e] + r_in - ((sk >= 0 && r_in > sk) ? 1 : 0);
+      idx_ji_kj[slot] = e;
+    }
+    total += __popcll(mask);
+  }
+}
+
+struct edges_ws {
+  int32_t* deg;      // [N]
+  int32_t* row_ptr;  // [N+1]
+  int64_t* total;    // [1]
+};
+inline size_t carve_edges(void* p, int64_t n_atoms, edges_ws* w) {
+  gp_carver c(p);
+  w->deg = c.take<int32_t>(n_atoms);
+  w->row_ptr = c.take<int32_t>(n_atoms + 1);
+  w->total = c.take<int64_t>(1);
+  return c.off;
+}
+
+struct triplets_ws {
+  int32_t *cnt, *skip, *seg_ji, *cnt_kj, *seg_kj, *out_tmp, *out_list;  // [E] / [E+1]
+  int32_t *out_deg, *out_ptr, *cursor;                                   // [N] / [N+1]
+  int64_t* totals;                                                       // [3]
+};
+inline size_t carve_triplets(void* p, int64_t n_atoms, int64_t n_edges, triplets_ws* w) {
+  gp_carver c(p);
+  w->cnt = c.take<int32_t>(n_edges);
+  w->skip = c.take<int32_t>(n_edges);
+  w->seg_ji = c.take<int32_t>(n_edges + 1);
+  w->cnt_kj = c.take<int32_t>(n_edges);
+  w->seg_kj = c.take<int32_t>(n_edges + 1);
+  w->out_tmp = c.take<int32_t>(n_edges);
+  w->out_list = c.take<int32_t>(n_edges);
+  w->out_deg = c.take<int32_t>(n_atoms);
+  w->out_ptr = c.take<int32_t>(n_atoms + 1);
+  w->cursor = c.take<int32_t>(n_atoms);
+  w->totals = c.take<int64_t>(3);
+  return c.off;
+}
+
+inline int blocks_for(int64_t n, int per_block) { return (int)((n + per_block - 1) / per_block); }
+
+}  // namespace
+
+extern "C" {
+
+int gp_edges_workspace(int64_t n_atoms, size_t* bytes) {
+  if (!bytes || n_atoms < 0) return GP_BAD_ARG;
+  edges_ws w;
+  *bytes = carve_edges(nullptr, n_atoms, &w);
+  return GP_OK;
+}
+
+int gp_edges_count(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, int64_t n_atoms,
+                   int32_t n_graphs, float cutoff, int32_t max_neighbors, void* ws, size_t ws_bytes,
+                   int64_t* n_edges) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, n_edges, "gp_edges_count: n_edges is NULL");
+  GP_REQUIRE(ctx, n_atoms >= 0 && n_graphs >= 0 && max_neighbors >= 0, "gp_edges_count: negative size");
+  GP_REQUIRE(ctx, cutoff > 0.f && cutoff == cutoff, "gp_edges_count: cutoff must be positive");
+  if (n_atoms > INT32_MAX - 1) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_edges_count: too many atoms");
+  *n_edges = 0;
+  if (n_atoms == 0 || n_graphs == 0) return GP_OK;
+  GP_REQUIRE(ctx, pos && graph_ptr && ws, "gp_edges_count: NULL pointer");
+  edges_ws w;
+  size_t need = carve_edges(ws, n_atoms, &w);
+  if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_edges_count: workspace %zu < %zu", ws_bytes, need);
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  const float c2 = cutoff * cutoff;
+  edges_kernel<false><<<blocks_for(n_atoms, 4), 256, 0, ctx->stream>>>(
+      pos, graph_ptr, (int)n_atoms, n_graphs, c2, max_neighbors, w.deg, nullptr, nullptr, nullptr, nullptr, nullptr);
+  GP_LAUNCH_CHECK(ctx, "edges_kernel<count>");
+  scan_exclusive_kernel<<<1, SCAN_THREADS, 0, ctx->stream>>>(w.deg, w.row_ptr, n_atoms, w.total);
+  GP_LAUNCH_CHECK(ctx, "scan_exclusive_kernel");
+  int64_t total = 0;
+  GP_HIP(ctx, hipMemcpyAsync(&total, w.total, sizeof(total), hipMemcpyDeviceToHost, ctx->stream));
+  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  *n_edges = total;
+  if (total > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_edges_count: %lld edges exceed int32", (long long)total);
+  return GP_OK;
+}
+
+int gp_edges_fill(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, int64_t n_atoms,
+                  int32_t n_graphs, float cutoff, int32_t max_neighbors, const void* ws, size_t ws_bytes,
+                  int64_t n_edges, int32_t* src, int32_t* dst, int32_t* row_ptr, float* dist, float* unit) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, n_atoms >= 0 && n_graphs >= 0 && max_neighbors >= 0 && n_edges >= 0, "gp_edges_fill: negative size");
+  GP_REQUIRE(ctx, cutoff > 0.f && cutoff == cutoff, "gp_edges_fill: cutoff must be positive");
+  GP_REQUIRE(ctx, row_ptr, "gp_edges_fill: row_ptr is NULL");
+  if (n_atoms > INT32_MAX - 1 || n_edges > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_edges_fill: sizes exceed int32");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  if (n_atoms == 0 || n_graphs == 0) {
+    GP_HIP(ctx, hipMemsetAsync(row_ptr, 0, sizeof(int32_t) * (n_atoms + 1), ctx->stream));
+    return GP_OK;
+  }
+  GP_REQUIRE(ctx, pos && graph_ptr && ws, "gp_edges_fill: NULL pointer");
+  GP_REQUIRE(ctx, n_edges == 0 || (src && dst), "gp_edges_fill: src/dst is NULL");
+  edges_ws w;
+  size_t need = carve_edges(const_cast<void*>(ws), n_atoms, &w);
+  if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_edges_fill: workspace %zu < %zu", ws_bytes, need);
+  GP_HIP(ctx, hipMemcpyAsync(row_ptr, w.row_ptr, sizeof(int32_t) * (n_atoms + 1), hipMemcpyDeviceToDevice, ctx->stream));
+  if (n_edges == 0) return GP_OK;
+  const float c2 = cutoff * cutoff;
+  edges_kernel<true><<<blocks_for(n_atoms, 4), 256, 0, ctx->stream>>>(
+      pos, graph_ptr, (int)n_atoms, n_graphs, c2, max_neighbors, nullptr, w.row_ptr, src, dst, dist, unit);
+  GP_LAUNCH_CHECK(ctx, "edges_kernel<fill>");
+  return GP_OK;
+}
+
+int gp_triplets_workspace(int64_t n_atoms, int64_t n_edges, size_t* bytes) {
+  if (!bytes || n_atoms < 0 || n_edges < 0) return GP_BAD_ARG;
+  triplets_ws w;
+  *bytes = carve_triplets(nullptr, n_atoms, n_edges, &w);
+  return GP_OK;
+}
+
+int gp_triplets_count(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
+                      int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes, int64_t* n_triplets) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, n_triplets, "gp_triplets_count: n_triplets is NULL");
+  GP_REQUIRE(ctx, n_atoms >= 0 && n_edges >= 0, "gp_triplets_count: negative size");
+  if (n_atoms > INT32_MAX - 1 || n_edges > INT32_MAX - 1) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_triplets_count: sizes exceed int32");
+  *n_triplets = 0;
+  if (n_edges == 0 || n_atoms == 0) return GP_OK;
+  GP_REQUIRE(ctx, src && dst && row_ptr && ws, "gp_triplets_count: NULL pointer");
+  triplets_ws w;
+  size_t need = carve_triplets(ws, n_atoms, n_edges, &w);
+  if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_triplets_count: workspace %zu < %zu", ws_bytes, need);
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = ctx->stream;
+  GP_HIP(ctx, hipMemsetAsync(w.out_deg, 0, sizeof(int32_t) * n_atoms, st));
+  GP_HIP(ctx, hipMemsetAsync(w.cursor, 0, sizeof(int32_t) * n_atoms, st));
+  triplet_count_kernel<<<blocks_for(n_edges, 256), 256, 0, st>>>(src, dst, row_ptr, (int)n_edges, w.cnt, w.skip, w.out_deg);
+  GP_LAUNCH_CHECK(ctx, "triplet_count_kernel");
+  scan_exclusive_kernel<<<1, SCAN_THREADS, 0, st>>>(w.cnt, w.seg_ji, n_edges, w.totals + 0);
+  GP_LAUNCH_CHECK(ctx, "scan_exclusive_kernel");
+  int64_t total = 0;
+  GP_HIP(ctx, hipMemcpyAsync(&total, w.totals, sizeof(total), hipMemcpyDeviceToHost, st));
+  GP_HIP(ctx, hipStreamSynchronize(st));
+  *n_triplets = total;
+  if (total > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_triplets_count: %lld triplets exceed int32", (long long)total);
+  return GP_OK;
+}
+
+int gp_triplets_fill(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
+                     int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes, int64_t n_triplets,
+                     int32_t* idx_kj, int32_t* idx_ji, int32_t* seg_ptr_ji, int32_t* perm_kj,
+                     int32_t* idx_ji_kj, int32_t* seg_ptr_kj) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, n_atoms >= 0 && n_edges >= 0 && n_triplets >= 0, "gp_triplets_fill: negative size");
+  if (n_atoms > INT32_MAX - 1 || n_edges > INT32_MAX - 1 || n_triplets > INT32_MAX)
+    return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_triplets_fill: sizes exceed int32");
+  GP_REQUIRE(ctx, seg_ptr_ji, "gp_triplets_fill: seg_ptr_ji is NULL");
+  const bool want_kj = perm_kj || idx_ji_kj || seg_ptr_kj;
+  GP_REQUIRE(ctx, !want_kj || (seg_ptr_kj && (n_triplets == 0 || (perm_kj && idx_ji_kj))),
+             "gp_triplets_fill: perm_kj, idx_ji_kj, seg_ptr_kj must be given together");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = ctx->stream;
+  if (n_edges == 0 || n_atoms == 0) {
+    GP_HIP(ctx, hipMemsetAsync(seg_ptr_ji, 0, sizeof(int32_t) * (n_edges + 1), st));
+    if (seg_ptr_kj) GP_HIP(ctx, hipMemsetAsync(seg_ptr_kj, 0, sizeof(int32_t) * (n_edges + 1), st));
+    return GP_OK;
+  }
+  GP_REQUIRE(ctx, src && dst && row_ptr && ws, "gp_triplets_fill: NULL pointer");
+  GP_REQUIRE(ctx, n_triplets == 0 || (idx_kj && idx_ji), "gp_triplets_fill: idx_kj/idx_ji is NULL");
+  triplets_ws w;
+  size_t need = carve_triplets(ws, n_atoms, n_edges, &w);
+  if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_triplets_fill: workspace %zu < %zu", ws_bytes, need);
+  GP_HIP(ctx, hipMemcpyAsync(seg_ptr_ji, w.seg_ji, sizeof(int32_t) * (n_edges + 1), hipMemcpyDeviceToDevice, st));
+  if (n_triplets > 0) {
+    triplet_fill_ji_kernel<<<blocks_for(n_edges, 4), 256, 0, st>>>(src, row_ptr, w.seg_ji, w.skip, (int)n_edges, idx_kj, idx_ji);
+    GP_LAUNCH_CHECK(ctx, "triplet_fill_ji_kernel");
+  }
+  if (!want_kj) return GP_OK;
+  scan_exclusive_kernel<<<1, SCAN_THREADS, 0, st>>>(w.out_deg, w.out_ptr, n_atoms, w.totals + 1);
+  GP_LAUNCH_CHECK(ctx, "scan_exclusive_kernel");
+  GP_HIP(ctx, hipMemsetAsync(w.cursor, 0, sizeof(int32_t) * n_atoms, st));
+  out_scatter_kernel<<<blocks_for(n_edges, 256), 256, 0, st>>>(src, (int)n_edges, w.out_ptr, w.cursor, w.out_tmp);
+  GP_LAUNCH_CHECK(ctx, "out_scatter_kernel");
+  out_sort_kernel<<<blocks_for(n_atoms, 4), 256, 0, st>>>(w.out_ptr, w.out_tmp, (int)n_atoms, w.out_list);
+  GP_LAUNCH_CHECK(ctx, "out_sort_kernel");
+  triplet_count_kj_kernel<<<blocks_for(n_edges, 256), 256, 0, st>>>(src, dst, row_ptr, w.out_ptr, (int)n_edges, w.cnt_kj);
+  GP_LAUNCH_CHECK(ctx, "triplet_count_kj_kernel");
+  scan_exclusive_kernel<<<1, SCAN_THREADS, 0, st>>>(w.cnt_kj, w.seg_kj, n_edges, w.totals + 2);
+  GP_LAUNCH_CHECK(ctx, "scan_exclusive_kernel");
+  GP_HIP(ctx, hipMemcpyAsync(seg_ptr_kj, w.seg_kj, sizeof(int32_t) * (n_edges + 1), hipMemcpyDeviceToDevice, st));
+  if (n_triplets > 0) {
+    triplet_fill_kj_kernel<<<blocks_for(n_edges, 4), 256, 0, st>>>(src, dst, row_ptr, w.out_ptr, w.out_list, w.seg_ji,
+                                                                 w.skip, w.seg_kj, (int)n_edges, perm_kj, idx_ji_kj);
+    GP_LAUNCH_CHECK(ctx, "triplet_fill_kj_kernel");
+  }
+  return GP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,29 @@
+// TripletUpdate + TripletAggr kernels, fused-basis forms used inside the interaction block
+// (internal, not part of the C ABI).
+#pragma once
+#include "common.h"
+
+// Variant D.  With Q[e',l,b] = sum_n rad[e',l,n] W_sbf1[l*R+n,b] (per edge) and
+// p_t[b] = sum_l Y_l0(cos alpha_t) Q[kj(t),l,b], the projected basis of a triplet is
+// s_t[f] = sum_b p_t[b] W_sbf2[b,f]; this is the two-step projection of the materialised
+// spherical basis, re-associated so that nothing of size T x S*R is ever stored.
+
+// Q[E, S*B] from rad[E, S*R] and W_sbf1[S*R, B]
+int gp_tripD_project_radial(gp_ctx* ctx, const float* rad, const float* W1, int64_t E, int S, int R, int B, float* Q);
+
+// a[e,f] = sum_{t in seg_ji(e)} x[kj(t),f] s_t[f];  Bacc[e,b,f] = sum_t p_t[b] x[kj(t),f]
+int gp_tripD_forward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Q,
+                     const float* W2, int F, int S, int B, float* a, float* Bacc);
+
+// From grad_a[E,F]:
+//   grad_x[e',f] = sum_{t: kj(t)=e'} grad_a[ji(t),f] s_t[f], multiplied by silu'(z[e',f]) if z != NULL
+//   grad_Q[e',l,b] = sum_{t: kj(t)=e'} Y_l(t) sum_f W2[b,f] grad_a[ji(t),f] x[e',f]
+int gp_tripD_backward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* x, const float* Q,
+                      const float* W2, const float* grad_a, const float* z, int F, int S, int B,
+                      float* grad_x, float* grad_Q);
+
+// grad_W2[b,f] = sum_e grad_a[e,f] Bacc[e,b,f];  grad_W1[l*R+n,b] = sum_e rad[e,l*R+n] grad_Q[e,l*B+b]
+size_t gp_tripD_wgrad_scratch(int64_t E, int F, int S, int R, int B);
+int gp_tripD_weight_grads(gp_ctx* ctx, const float* grad_a, const float* Bacc, const float* rad, const float* grad_Q,
+                          int64_t E, int F, int S, int R, int B, float* grad_W2, float* grad_W1,
+                          float* part, size_t part_bytes);

@@ -1,0 +1,485 @@
+// TripletUpdate + TripletAggr (paper Sec. 3.3: Hadamard product of the gathered, down-projected
+// message m_kj with the projected spherical basis, summed over k in N_j \ {i} into edge j->i),
+// forward and backward, variant D.
+//
+// Mapping: one wavefront per segment (a target edge in the forward pass, a source edge in the
+// backward pass); lanes run over the feature dimension so every gathered row is one coalesced
+// read; for rows narrower than 64 features the wavefront splits into 64/LPR groups that take
+// alternate triplets and are combined by a butterfly at the end.  Reductions follow the sorted
+// segment order, there are no atomics, results are bit-reproducible run to run.
+#include <stdarg.h>
+
+#include "gemm.h"
+#include "triplet.h"
+
+namespace {
+
+constexpr int WPB = 4;        // wavefronts per workgroup
+constexpr int ST = 8;         // max num_spherical
+__device__ __constant__ float Y_NORM[ST] = {
+    0.28209479177387814f, 0.4886025119029199f, 0.6307831305050401f, 0.7463526651802308f,
+    0.8462843753216345f, 0.9356025796273888f, 1.0171072362820548f, 1.0925484305920792f};  // sqrt((2l+1)/(4 pi))
+
+// wavefront-local ordering of LDS traffic (no other wavefront touches this wave's slice)
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Y[l] = sqrt((2l+1)/(4 pi)) P_l(c), l < S; zero above
+__device__ __forceinline__ void y_l0(float c, int S, float* Y) {
+  float p0 = 1.0f, p1 = c;
+#pragma unroll
+  for (int l = 0; l < ST; ++l) {
+    float P = (l == 0) ? 1.0f : p1;
+    Y[l] = (l < S) ? Y_NORM[l] * P : 0.0f;
+    if (l >= 1) {
+      float p2 = ((float)(2 * l + 1) * c * p1 - (float)l * p0) / (float)(l + 1);
+      p0 = p1;
+      p1 = p2;
+    }
+  }
+}
+
+template <int FPL>
+__device__ __forceinline__ void butterfly(float (&v)[FPL], int lpr) {
+  for (int off = lpr; off < WAVE; off <<= 1)
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) v[i] += __shfl_xor(v[i], off, WAVE);
+}
+
+// ------------------------------------------------------------------ per-edge radial projection
+__global__ void project_radial_kernel(const float* __restrict__ rad, const float* __restrict__ W1, int64_t E,
+                                      int S, int R, int B, float* __restrict__ Q) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= E * S * B) return;
+  int b = (int)(idx % B);
+  int l = (int)((idx / B) % S);
+  int64_t e = idx / ((int64_t)S * B);
+  const float* r = rad + (e * S + l) * R;
+  float s = 0.f;
+  for (int n = 0; n < R; ++n) s += r[n] * W1[(l * R + n) * B + b];
+  Q[idx] = s;
+}
+
+// ------------------------------------------------------------------ fused forward
+template <int BT, int LPR, int FPL>
+__global__ void __launch_bounds__(WPB* WAVE)
+tripD_fwd_kernel(const int32_t* __restrict__ seg, const int32_t* __restrict__ idx_kj,
+                 const float* __restrict__ cos_alpha, const float* __restrict__ x,
+                 const float* __restrict__ Q, const float* __restrict__ W2, int64_t E, int F, int S, int B,
+                 float* __restrict__ a, float* __restrict__ Bacc) {
+  constexpr int G = WAVE / LPR;
+  __shared__ float p_s[WPB][WAVE][BT];
+  __shared__ int kj_s[WPB][WAVE];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t e = (int64_t)blockIdx.x * WPB + w;
+  if (e >= E) return;
+  const int grp = lane / LPR, fl = lane % LPR;
+  float acc[BT][FPL];
+#pragma unroll
+  for (int b = 0; b < BT; ++b)
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) acc[b][i] = 0.f;
+  const int t0 = seg[e], t1 = seg[e + 1];
+  for (int base = t0; base < t1; base += WAVE) {
+    const int n = min(WAVE, t1 - base);
+    if (lane < n) {
+      const int t = base + lane;
+      const int kj = idx_kj[t];
+      float Y[ST];
+      y_l0(cos_alpha[t], S, Y);
+      const float* q = Q + (int64_t)kj * S * B;
+#pragma unroll
+      for (int b = 0; b < BT; ++b) {
+        float p = 0.f;
+        if (b < B)
+          for (int l = 0; l < S; ++l) p += Y[l] * q[l * B + b];
+        p_s[w][lane][b] = p;
+      }
+      kj_s[w][lane] = kj;
+    }
+    wave_lds_sync();
+    for (int tt = grp; tt < n; tt += G) {
+      const int64_t kj = kj_s[w][tt];
+#pragma unroll
+      for (int i = 0; i < FPL; ++i) {
+        const int f = fl + i * WAVE;
+        if (f < F) {
+          const float xv = x[kj * F + f];
+#pragma unroll
+          for (int b = 0; b < BT; ++b) acc[b][i] += p_s[w][tt][b] * xv;
+        }
+      }
+    }
+    wave_lds_sync();
+  }
+#pragma unroll
+  for (int b = 0; b < BT; ++b) butterfly<FPL>(acc[b], LPR);
+  if (grp == 0) {
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) {
+      const int f = fl + i * WAVE;
+      if (f < F) {
+        float s = 0.f;
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+          if (b < B) {
+            s += W2[b * F + f] * acc[b][i];
+            Bacc[(e * B + b) * F + f] = acc[b][i];
+          }
+        a[e * F + f] = s;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ fused backward (kj-major)
+template <int LPR, int FPL>
+__global__ void __launch_bounds__(WPB* WAVE)
+tripD_bwd_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__ idx_ji_kj,
+                 const float* __restrict__ cos_kj, const float* __restrict__ x, const float* __restrict__ Q,
+                 const float* __restrict__ W2, const float* __restrict__ ga, const float* __restrict__ z,
+                 int64_t E, int F, int S, int B, float* __restrict__ gx, float* __restrict__ gQ) {
+  constexpr int G = WAVE / LPR;
+  extern __shared__ float dyn_s[];
+  __shared__ float Y_s[WPB][WAVE][ST];
+  __shared__ int ji_s[WPB][WAVE];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t e = (int64_t)blockIdx.x * WPB + w;
+  if (e >= E) return;
+  const int LDU = F + 1;
+  float* u_s = dyn_s + (size_t)w * ST * LDU;
+  const int grp = lane / LPR, fl = lane % LPR;
+  float H[ST][FPL];
+#pragma unroll
+  for (int l = 0; l < ST; ++l)
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) H[l][i] = 0.f;
+  const int q0 = seg_kj[e], q1 = seg_kj[e + 1];
+  for (int base = q0; base < q1; base += WAVE) {
+    const int n = min(WAVE, q1 - base);
+    if (lane < n) {
+      float Y[ST];
+      y_l0(cos_kj[base + lane], S, Y);
+#pragma unroll
+      for (int l = 0; l < ST; ++l) Y_s[w][lane][l] = Y[l];
+      ji_s[w][lane] = idx_ji_kj[base + lane];
+    }
+    wave_lds_sync();
+    for (int tt = grp; tt < n; tt += G) {
+      const int64_t ji = ji_s[w][tt];
+#pragma unroll
+      for (int i = 0; i < FPL; ++i) {
+        const int f = fl + i * WAVE;
+        if (f < F) {
+          const float g = ga[ji * F + f];
+#pragma unroll
+          for (int l = 0; l < ST; ++l) H[l][i] += Y_s[w][tt][l] * g;
+        }
+      }
+    }
+    wave_lds_sync();
+  }
+#pragma unroll
+  for (int l = 0; l < ST; ++l) butterfly<FPL>(H[l], LPR);
+  // every group now holds the full sums; group 0 finishes the edge
+  const float* q = Q + e * S * B;
+  if (grp == 0) {
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) {
+      const int f = fl + i * WAVE;
+      if (f < F) {
+        float dx = 0.f;
+        for (int b = 0; b < B; ++b) {
+          float D = 0.f;
+#pragma unroll
+          for (int l = 0; l < ST; ++l)
+            if (l < S) D += q[l * B + b] * H[l][i];
+          dx += W2[b * F + f] * D;
+        }
+        if (z) dx *= dsilu_f(z[e * F + f]);
+        gx[e * F + f] = dx;
+        const float xv = x[e * F + f];
+#pragma unroll
+        for (int l = 0; l < ST; ++l) u_s[l * LDU + f] = xv * H[l][i];
+      }
+    }
+  }
+  wave_lds_sync();
+  for (int idx = lane; idx < S * B; idx += WAVE) {
+    const int l = idx / B, b = idx % B;
+    float s = 0.f;
+    for (int f = 0; f < F; ++f) s += W2[b * F + f] * u_s[l * LDU + f];
+    gQ[e * S * B + idx] = s;
+  }
+}
+
+// ------------------------------------------------------------------ weight-gradient partial sums
+__global__ void w2grad_part_kernel(const float* __restrict__ ga, const float* __restrict__ Bacc, int64_t E,
+                                   int F, int B, int64_t per, float* __restrict__ part) {
+  const int64_t e0 = (int64_t)blockIdx.x * per, e1 = min(E, e0 + per);
+  for (int idx = threadIdx.x; idx < B * F; idx += blockDim.x) {
+    const int b = idx / F, f = idx % F;
+    float s = 0.f;
+    for (int64_t e = e0; e < e1; ++e) s += ga[e * F + f] * Bacc[(e * B + b) * F + f];
+    part[(int64_t)blockIdx.x * B * F + idx] = s;
+  }
+}
+
+__global__ void w1grad_part_kernel(const float* __restrict__ rad, const float* __restrict__ gQ, int64_t E, int S,
+                                   int R, int B, int64_t per, float* __restrict__ part) {
+  const int64_t e0 = (int64_t)blockIdx.x * per, e1 = min(E, e0 + per);
+  const int n_out = S * R * B;
+  for (int idx = threadIdx.x; idx < n_out; idx += blockDim.x) {
+    const int b = idx % B, ln = idx / B, l = ln / R;
+    float s = 0.f;
+    for (int64_t e = e0; e < e1; ++e) s += rad[e * S * R + ln] * gQ[(e * S + l) * B + b];
+    part[(int64_t)blockIdx.x * n_out + idx] = s;
+  }
+}
+
+// ------------------------------------------------------------------ streaming forms
+template <int LPR, int FPL>
+__global__ void __launch_bounds__(WPB* WAVE)
+stream_fwd_kernel(const int32_t* __restrict__ seg, const int32_t* __restrict__ idx_kj, const float* __restrict__ x,
+                  const float* __restrict__ s, int64_t E, int F, float* __restrict__ a) {
+  constexpr int G = WAVE / LPR;
+  const int lane = threadIdx.x & 63;
+  const int64_t e = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (e >= E) return;
+  const int grp = lane / LPR, fl = lane % LPR;
+  float acc[FPL];
+#pragma unroll
+  for (int i = 0; i < FPL; ++i) acc[i] = 0.f;
+  const int t1 = seg[e + 1];
+  for (int64_t t = seg[e] + grp; t < t1; t += G) {
+    const int64_t kj = idx_kj[t];
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) {
+      const int f = fl + i * WAVE;
+      if (f < F) acc[i] += x[kj * F + f] * s[t * F + f];
+    }
+  }
+  butterfly<FPL>(acc, LPR);
+  if (grp == 0)
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) {
+      const int f = fl + i * WAVE;
+      if (f < F) a[e * F + f] = acc[i];
+    }
+}
+
+template <int LPR, int FPL>
+__global__ void __launch_bounds__(WPB* WAVE)
+stream_bwd_x_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__ idx_ji_kj,
+                    const int32_t* __restrict__ perm_kj, const float* __restrict__ s, const float* __restrict__ ga,
+                    int64_t E, int F, float* __restrict__ gx) {
+  constexpr int G = WAVE / LPR;
+  const int lane = threadIdx.x & 63;
+  const int64_t e = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (e >= E) return;
+  const int grp = lane / LPR, fl = lane % LPR;
+  float acc[FPL];
+#pragma unroll
+  for (int i = 0; i < FPL; ++i) acc[i] = 0.f;
+  const int q1 = seg_kj[e + 1];
+  for (int64_t q = seg_kj[e] + grp; q < q1; q += G) {
+    const int64_t ji = idx_ji_kj[q], t = perm_kj[q];
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) {
+      const int f = fl + i * WAVE;
+      if (f < F) acc[i] += ga[ji * F + f] * s[t * F + f];
+    }
+  }
+  butterfly<FPL>(acc, LPR);
+  if (grp == 0)
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) {
+      const int f = fl + i * WAVE;
+      if (f < F) gx[e * F + f] = acc[i];
+    }
+}
+
+template <int LPR, int FPL>
+__global__ void __launch_bounds__(WPB* WAVE)
+stream_bwd_s_kernel(const int32_t* __restrict__ seg, const int32_t* __restrict__ idx_kj, const float* __restrict__ x,
+                    const float* __restrict__ ga, int64_t E, int F, float* __restrict__ gs) {
+  constexpr int G = WAVE / LPR;
+  const int lane = threadIdx.x & 63;
+  const int64_t e = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (e >= E) return;
+  const int grp = lane / LPR, fl = lane % LPR;
+  float g[FPL];
+#pragma unroll
+  for (int i = 0; i < FPL; ++i) {
+    const int f = fl + i * WAVE;
+    g[i] = (f < F) ? ga[e * F + f] : 0.f;
+  }
+  const int t1 = seg[e + 1];
+  for (int64_t t = seg[e] + grp; t < t1; t += G) {
+    const int64_t kj = idx_kj[t];
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) {
+      const int f = fl + i * WAVE;
+      if (f < F) gs[t * F + f] = g[i] * x[kj * F + f];
+    }
+  }
+}
+
+inline unsigned seg_blocks(int64_t E) { return (unsigned)((E + WPB - 1) / WPB); }
+
+// pick (LPR, FPL) for a feature width and call fn.template operator()<LPR, FPL>()
+#define GP_DISPATCH_WIDTH(F, CALL)                      \
+  do {                                                  \
+    if ((F) <= 16) { CALL(16, 1); }                     \
+    else if ((F) <= 32) { CALL(32, 1); }                \
+    else if ((F) <= 64) { CALL(64, 1); }                \
+    else if ((F) <= 128) { CALL(64, 2); }               \
+    else { CALL(64, 4); }                               \
+  } while (0)
+
+void slab_plan(int64_t E, int* blocks, int64_t* per) {
+  int64_t b = (E + 63) / 64;
+  if (b > 1024) b = 1024;
+  if (b < 1) b = 1;
+  *per = (E + b - 1) / b;
+  if (*per < 1) *per = 1;
+  *blocks = (int)((E + *per - 1) / *per);
+  if (*blocks < 1) *blocks = 1;
+}
+
+int check_graph(gp_ctx* ctx, const gp_graph* g, bool need_ji, bool need_kj) {
+  GP_REQUIRE(ctx, g, "graph is NULL");
+  GP_REQUIRE(ctx, g->n_edges >= 0 && g->n_triplets >= 0, "graph: negative size");
+  if (g->n_edges > INT32_MAX - 1 || g->n_triplets > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "graph: sizes exceed int32");
+  if (g->n_edges == 0) return GP_OK;
+  if (need_ji) GP_REQUIRE(ctx, g->seg_ptr_ji && (g->n_triplets == 0 || g->idx_kj), "graph: ji-major arrays missing");
+  if (need_kj) GP_REQUIRE(ctx, g->seg_ptr_kj && (g->n_triplets == 0 || g->idx_ji_kj), "graph: kj-major arrays missing");
+  return GP_OK;
+}
+
+}  // namespace
+
+int gp_tripD_project_radial(gp_ctx* ctx, const float* rad, const float* W1, int64_t E, int S, int R, int B, float* Q) {
+  if (E == 0) return GP_OK;
+  int64_t n = E * S * B;
+  project_radial_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(rad, W1, E, S, R, B, Q);
+  GP_LAUNCH_CHECK(ctx, "project_radial_kernel");
+  return GP_OK;
+}
+
+int gp_tripD_forward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Q,
+                     const float* W2, int F, int S, int B, float* a, float* Bacc) {
+  GP_TRY(check_graph(ctx, g, true, false));
+  const int64_t E = g->n_edges;
+  if (E == 0) return GP_OK;
+  if (F < 1 || F > 256 || S < 1 || S > ST || B < 1 || B > 16)
+    return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "triplet D forward: int_emb=%d num_spherical=%d basis_emb=%d unsupported", F, S, B);
+  GP_REQUIRE(ctx, x && Q && W2 && a && Bacc && (g->n_triplets == 0 || cos_alpha), "triplet D forward: NULL pointer");
+#define CALL_FWD(LPR, FPL)                                                                                       \
+  do {                                                                                                           \
+    if (B <= 4) tripD_fwd_kernel<4, LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(                    \
+        g->seg_ptr_ji, g->idx_kj, cos_alpha, x, Q, W2, E, F, S, B, a, Bacc);                                     \
+    else if (B <= 8) tripD_fwd_kernel<8, LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(               \
+        g->seg_ptr_ji, g->idx_kj, cos_alpha, x, Q, W2, E, F, S, B, a, Bacc);                                     \
+    else tripD_fwd_kernel<16, LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(                          \
+        g->seg_ptr_ji, g->idx_kj, cos_alpha, x, Q, W2, E, F, S, B, a, Bacc);                                     \
+  } while (0)
+  GP_DISPATCH_WIDTH(F, CALL_FWD);
+#undef CALL_FWD
+  GP_LAUNCH_CHECK(ctx, "tripD_fwd_kernel");
+  return GP_OK;
+}
+
+int gp_tripD_backward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* x, const float* Q,
+                      const float* W2, const float* grad_a, const float* z, int F, int S, int B, float* grad_x,
+                      float* grad_Q) {
+  GP_TRY(check_graph(ctx, g, false, true));
+  const int64_t E = g->n_edges;
+  if (E == 0) return GP_OK;
+  if (F < 1 || F > 256 || S < 1 || S > ST || B < 1 || B > 16)
+    return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "triplet D backward: int_emb=%d num_spherical=%d basis_emb=%d unsupported", F, S, B);
+  GP_REQUIRE(ctx, x && Q && W2 && grad_a && grad_x && grad_Q && (g->n_triplets == 0 || cos_alpha_kj),
+             "triplet D backward: NULL pointer");
+  const size_t dyn = (size_t)WPB * ST * (F + 1) * sizeof(float);
+#define CALL_BWD(LPR, FPL)                                                                      \
+  tripD_bwd_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, dyn, ctx->stream>>>(                  \
+      g->seg_ptr_kj, g->idx_ji_kj, cos_alpha_kj, x, Q, W2, grad_a, z, E, F, S, B, grad_x, grad_Q)
+  GP_DISPATCH_WIDTH(F, CALL_BWD);
+#undef CALL_BWD
+  GP_LAUNCH_CHECK(ctx, "tripD_bwd_kernel");
+  return GP_OK;
+}
+
+size_t gp_tripD_wgrad_scratch(int64_t E, int F, int S, int R, int B) {
+  int blocks; int64_t per;
+  slab_plan(E, &blocks, &per);
+  size_t n = (size_t)(B * F > S * R * B ? B * F : S * R * B);
+  return gp_align((size_t)blocks * n * sizeof(float));
+}
+
+int gp_tripD_weight_grads(gp_ctx* ctx, const float* grad_a, const float* Bacc, const float* rad, const float* grad_Q,
+                          int64_t E, int F, int S, int R, int B, float* grad_W2, float* grad_W1, float* part,
+                          size_t part_bytes) {
+  int blocks; int64_t per;
+  slab_plan(E, &blocks, &per);
+  if (!part || part_bytes < gp_tripD_wgrad_scratch(E, F, S, R, B))
+    return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "triplet D weight grads: scratch too small");
+  if (E == 0) {
+    GP_HIP(ctx, hipMemsetAsync(grad_W2, 0, sizeof(float) * B * F, ctx->stream));
+    GP_HIP(ctx, hipMemsetAsync(grad_W1, 0, sizeof(float) * S * R * B, ctx->stream));
+    return GP_OK;
+  }
+  w2grad_part_kernel<<<blocks, 256, 0, ctx->stream>>>(grad_a, Bacc, E, F, B, per, part);
+  GP_LAUNCH_CHECK(ctx, "w2grad_part_kernel");
+  GP_TRY(gp_reduce_parts(ctx, part, blocks, (int64_t)B * F, grad_W2));
+  w1grad_part_kernel<<<blocks, 256, 0, ctx->stream>>>(rad, grad_Q, E, S, R, B, per, part);
+  GP_LAUNCH_CHECK(ctx, "w1grad_part_kernel");
+  GP_TRY(gp_reduce_parts(ctx, part, blocks, (int64_t)S * R * B, grad_W1));
+  return GP_OK;
+}
+
+extern "C" int gp_triplet_aggregate_fwd(gp_ctx* ctx, const gp_graph* graph, int32_t width, const float* x,
+                                        const float* s, float* a) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_TRY(check_graph(ctx, graph, true, false));
+  const int64_t E = graph->n_edges;
+  const int F = width;
+  if (F < 1 || F > 256) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "gp_triplet_aggregate_fwd: width %d not in 1..256", F);
+  if (E == 0) return GP_OK;
+  GP_REQUIRE(ctx, x && a && (graph->n_triplets == 0 || s), "gp_triplet_aggregate_fwd: NULL pointer");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+#define CALL_S(LPR, FPL) \
+  stream_fwd_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(graph->seg_ptr_ji, graph->idx_kj, x, s, E, F, a)
+  GP_DISPATCH_WIDTH(F, CALL_S);
+#undef CALL_S
+  GP_LAUNCH_CHECK(ctx, "stream_fwd_kernel");
+  return GP_OK;
+}
+
+extern "C" int gp_triplet_aggregate_bwd(gp_ctx* ctx, const gp_graph* graph, const int32_t* perm_kj, int32_t width,
+                                        const float* x, const float* s, const float* grad_a, float* grad_x,
+                                        float* grad_s) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_TRY(check_graph(ctx, graph, true, true));
+  const int64_t E = graph->n_edges;
+  const int F = width;
+  if (F < 1 || F > 256) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "gp_triplet_aggregate_bwd: width %d not in 1..256", F);
+  if (E == 0) return GP_OK;
+  GP_REQUIRE(ctx, x && grad_a && grad_x && (graph->n_triplets == 0 || (s && grad_s && perm_kj)),
+             "gp_triplet_aggregate_bwd: NULL pointer");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+#define CALL_S(LPR, FPL)                                                                                          \
+  do {                                                                                                            \
+    stream_bwd_x_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(                                 \
+        graph->seg_ptr_kj, graph->idx_ji_kj, perm_kj, s, grad_a, E, F, grad_x);                                   \
+    stream_bwd_s_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(graph->seg_ptr_ji, graph->idx_kj, \
+                                                                                 x, grad_a, E, F, grad_s);        \
+  } while (0)
+  GP_DISPATCH_WIDTH(F, CALL_S);
+#undef CALL_S
+  GP_LAUNCH_CHECK(ctx, "stream_bwd kernels");
+  return GP_OK;
+}
