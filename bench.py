@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark: triplets/sec of the interaction-block stack, forward + backward, on one MI355X.
+
+A step is one forward + backward pass of all blocks of the workload over one batch of
+synthetic structures (graph construction and basis evaluation happen once, before the timed
+region, and are reported separately).  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma_f32": (157.3, "TFLOP/s"), "mfma_bf16": (2500.0, "TFLOP/s"),
+        "alu_f32": (78.6, "TFLOP/s")}
+
+
+def cpu_baseline(workload, seed):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import torch
+
+    import synth
+    from tests import helpers as H
+
+    dims = workload.dims
+    n_struct = 2
+    args = list(workload.system_args)
+    args[0] = n_struct
+    pos, gptr = synth.slab_adsorbate_positions(*args, seed=seed)
+    g = H.oracle_graph(pos, gptr, dims.cutoff, workload.max_neighbors)
+    ob = H.oracle_basis_D(pos, g, dims)
+    W_list = [synth.weights_D(dims, seed=100 + b) for b in range(workload.n_blocks)]
+    m, gup = synth.edge_embeddings(len(g["src"]), dims.emb, seed=seed + 7)
+    t0 = time.perf_counter()
+    H.oracle_stack_D(g, ob, dims, W_list, m, gup)
+    dt = time.perf_counter() - t0
+    T = len(g["idx_kj"])
+    return {"value": T * workload.n_blocks / dt, "unit": "triplets/s", "cores": torch.get_num_threads(),
+            "kind": "oracle",
+            "sample": "%d of %d structures (%d edges, %d triplets), %d blocks fwd+bwd in fp64, %.1f s"
+                      % (n_struct, workload.system_args[0], len(g["src"]), T, workload.n_blocks, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs the interaction block on ONE GPU (no sharding, no collectives); "
+                 "--gpus %d is not supported" % a.gpus)
+
+    import numpy as np
+    import torch
+
+    import paper_2203_09697_amd as gp
+    import synth
+    from paper_2203_09697_amd.stack import StackD
+
+    w = synth.get_workload(a.workload)
+    dims = w.dims
+    if dims.variant != "D":
+        sys.exit("bench.py: workload %s (variant %s) is not implemented yet" % (a.workload, dims.variant))
+    pos, gptr = synth.make_positions(w, a.seed)
+    ctx = gp.Context(0)
+    dpos = torch.as_tensor(pos).to("cuda:0")
+    dptr = torch.as_tensor(gptr).to("cuda:0")
+
+    # graph + basis: once per batch, outside the timed region (reported separately)
+    gp.build_graph(ctx, dpos, dptr, dims.cutoff, w.max_neighbors)  # warm-up of the graph kernels
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e, t = gp.build_graph(ctx, dpos, dptr, dims.cutoff, w.max_neighbors)
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - t0) * 1e3
+    t0 = time.perf_counter()
+    basis = gp.gp_basis_forward(ctx, dims, e, t)
+    torch.cuda.synchronize()
+    basis_ms = (time.perf_counter() - t0) * 1e3
+    E, T = e["n_edges"], t["n_triplets"]
+
+    W_list = [gp.weights_to_device(synth.weights_D(dims, seed=100 + b)) for b in range(w.n_blocks)]
+    m, gup = synth.edge_embeddings(E, dims.emb, seed=a.seed + 7)
+    dm, dg = torch.as_tensor(m).to("cuda:0"), torch.as_tensor(gup).to("cuda:0")
+    stack = StackD(ctx, dims, W_list, t, basis)
+
+    def step():
+        stack.forward(dm)
+        stack.backward(dg)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(a.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = ev0.elapsed_time(ev1) / a.steps
+    value = T * w.n_blocks / (ms_per_step * 1e-3)
+
+    # per-kernel durations: the same K steps again with every launch bracketed by HIP events
+    gp.gp_profile_enable(ctx, True)
+    gp.gp_profile_reset(ctx)
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = gp.gp_profile_collect(ctx)
+    gp.gp_profile_enable(ctx, False)
+    kernels = []
+    for name, d in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
+        is_gemm = name.startswith("gemm_")
+        per_launch_ms = d["ms"] / d["launches"]
+        if is_gemm:
+            ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_f32"], "mfma"
+        elif name.startswith("tripD"):
+            ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["alu_f32"], "alu"
+        else:
+            ach, (peak, unit), bound = d["bytes"] / (d["ms"] * 1e-3) / 1e9, PEAK["hbm"], "hbm"
+        kernels.append({"kernel": name, "launches_per_step": d["launches"] / a.steps, "avg_ms": round(per_launch_ms, 5),
+                        "ms_per_step": round(d["ms"] / a.steps, 4), "bound": bound, "achieved": round(ach, 3),
+                        "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
+    top = kernels[0]
+    roofline = {"kernel": top["kernel"], "bound": top["bound"], "achieved": top["achieved"], "peak": top["peak"],
+                "unit": top["unit"], "frac": top["frac"], "avg_ms": top["avg_ms"], "traffic": None}
+
+    out = {
+        "metric": "triplets/sec (interaction block fwd+bwd), 1 MI355X", "value": value, "unit": "triplets/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d structures, N=%d atoms, E=%d edges, T=%d triplets, %d blocks, emb=%d int_emb=%d"
+                               % (w.name, len(gptr) - 1, len(pos), E, T, w.n_blocks, dims.emb, dims.int_emb),
+                   "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed},
+        "roofline": roofline,
+        "kernels": kernels[:8],
+        "graph_build_ms": round(graph_ms, 3), "basis_ms": round(basis_ms, 3), "wall_ms_per_step": round(wall_ms / a.steps, 4),
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, a.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

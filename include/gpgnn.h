@@ -46,6 +46,17 @@ void gp_destroy(gp_ctx* ctx);
 const char* gp_last_error(const gp_ctx* ctx);
 const char* gp_version(void);
 
+/* Measurement aid (not a step of the method): while enabled, every kernel launch the library
+ * issues on this context is bracketed by two HIP events on the context's stream.
+ * gp_profile_get(i) synchronises on launch i and returns its kernel name (static string),
+ * duration in ms, and the algorithmic flops and bytes of that launch.  gp_profile_reset
+ * forgets the recorded launches (events are recycled). */
+int gp_profile_enable(gp_ctx* ctx, int on);
+int gp_profile_reset(gp_ctx* ctx);
+int gp_profile_count(gp_ctx* ctx, int64_t* n /*host*/);
+int gp_profile_get(gp_ctx* ctx, int64_t i, const char** name /*host*/, float* ms /*host*/,
+                   double* flops /*host*/, double* bytes /*host*/);
+
 /* ------------------------------------------------------------------------------------------
  * Graph construction (Sec. 3.1): target atom t gets an edge from every source atom s of the
  * same structure with |x_t - x_s| < cutoff.  The test is the fp32 expression

@@ -6,7 +6,7 @@ import torch
 
 __all__ = [
     "GpError", "load", "library_path", "Context", "Dims", "Graph", "Basis",
-    "gp_version", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
+    "gp_version", "gp_profile_enable", "gp_profile_reset", "gp_profile_collect", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
     "gp_block_forward_D", "gp_block_backward_D", "gp_triplet_aggregate_fwd",
     "gp_triplet_aggregate_bwd", "gp_linear_forward", "build_graph", "weights_to_device",
     "EXPORTED_SYMBOLS", "D_WEIGHT_ORDER",
@@ -21,6 +21,7 @@ STATUS = {0: "GP_OK", -1: "GP_BAD_ARG", -2: "GP_BUFFER_TOO_SMALL", -3: "GP_INT32
 
 EXPORTED_SYMBOLS = [
     "gp_create", "gp_destroy", "gp_last_error", "gp_version",
+    "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get",
     "gp_edges_workspace", "gp_edges_count", "gp_edges_fill",
     "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill",
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
@@ -166,6 +167,32 @@ class Context:
 
 def gp_version():
     return load().gp_version().decode()
+
+
+def gp_profile_enable(ctx, on):
+    ctx.check(load().gp_profile_enable(ctx._h, C.c_int(1 if on else 0)))
+
+
+def gp_profile_reset(ctx):
+    ctx.check(load().gp_profile_reset(ctx._h))
+
+
+def gp_profile_collect(ctx):
+    """gp_profile_count + gp_profile_get for every recorded launch, summed per kernel name:
+    {name: dict(launches, ms, flops, bytes)}."""
+    lib = load()
+    n = C.c_int64()
+    ctx.check(lib.gp_profile_count(ctx._h, C.byref(n)))
+    out = {}
+    name, ms, fl, by = C.c_char_p(), C.c_float(), C.c_double(), C.c_double()
+    for i in range(n.value):
+        ctx.check(lib.gp_profile_get(ctx._h, C.c_int64(i), C.byref(name), C.byref(ms), C.byref(fl), C.byref(by)))
+        d = out.setdefault(name.value.decode(), dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
+        d["launches"] += 1
+        d["ms"] += ms.value
+        d["flops"] += fl.value
+        d["bytes"] += by.value
+    return out
 
 
 def _empty(ctx, n, dtype):

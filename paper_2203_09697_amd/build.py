@@ -18,9 +18,9 @@ FLAGS = [
 ]
 
 
-def _compile(src):
-    obj = os.path.join(OBJ_DIR, os.path.basename(src).replace(".hip", ".o"))
-    cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
+def _compile(src, extra=(), tag=""):
+    obj = os.path.join(OBJ_DIR, os.path.basename(src).replace(".hip", tag + ".o"))
+    cmd = [HIPCC] + FLAGS + list(extra) + ["-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass warns that it does not know the packed-fp32 feature; that is expected
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
@@ -29,21 +29,23 @@ def _compile(src):
     return obj, err
 
 
-def build(verbose=False):
+def build(verbose=False, extra_flags=(), out_path=None, tag=""):
+    """extra_flags / out_path / tag let experiments build differently-configured copies."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        results = list(ex.map(_compile, srcs))
+        results = list(ex.map(lambda s: _compile(s, extra_flags, tag), srcs))
     objs = [o for o, _ in results]
     if verbose:
         for _, err in results:
             if err.strip():
                 print(err, file=sys.stderr)
-    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB_PATH] + objs
+    lib_path = out_path or LIB_PATH
+    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib_path] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    return LIB_PATH
+    return lib_path
 
 
 if __name__ == "__main__":

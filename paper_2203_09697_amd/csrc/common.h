@@ -1,16 +1,55 @@
 // Internal helpers shared by the library's translation units (not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stdarg.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 #include "../../include/gpgnn.h"
 
+// One bracketed kernel launch (only recorded while profiling is enabled).
+struct gp_prof_entry {
+  const char* name;   // static string naming the kernel instantiation
+  hipEvent_t t0, t1;
+  double flops, bytes;  // algorithmic work of this launch
+};
+
 struct gp_ctx {
-  int device;
-  hipStream_t stream;
-  char err[512];
+  int device = 0;
+  hipStream_t stream = nullptr;
+  char err[512] = {0};
+  bool prof_on = false;
+  std::vector<gp_prof_entry> prof;
+  std::vector<hipEvent_t> event_pool;
+};
+
+// Brackets the launches issued during its lifetime with two HIP events on the context's
+// stream when profiling is on; otherwise does nothing.
+struct gp_prof_scope {
+  gp_ctx* c;
+  bool active;
+  hipEvent_t t1;
+  gp_prof_scope(gp_ctx* ctx, const char* name, double flops, double bytes) : c(ctx), active(false), t1(nullptr) {
+    if (!c || !c->prof_on) return;
+    hipEvent_t ev[2];
+    for (int i = 0; i < 2; ++i) {
+      if (!c->event_pool.empty()) {
+        ev[i] = c->event_pool.back();
+        c->event_pool.pop_back();
+      } else if (hipEventCreate(&ev[i]) != hipSuccess) {
+        return;
+      }
+    }
+    c->prof.push_back({name, ev[0], ev[1], flops, bytes});
+    t1 = ev[1];
+    active = hipEventRecord(ev[0], c->stream) == hipSuccess;
+  }
+  ~gp_prof_scope() {
+    if (active) (void)hipEventRecord(t1, c->stream);
+  }
 };
 
 inline int gp_fail(gp_ctx* ctx, int code, const char* fmt, ...) __attribute__((format(printf, 3, 4)));

@@ -22,10 +22,11 @@ struct gp_epilogue {
 int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi);
 // C = A[M,K] @ Bt[N,K]^T
 int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi);
-// out[M,N] = A[rows,M]^T @ B[rows,N]; deterministic two-stage reduction through `part`
+// out[M,N] = A[rows,M]^T @ B[rows,N]; deterministic two-stage reduction through `part`.
+// If colsum_out != NULL it also receives colsum_out[n] = sum_r B[r,n] (the bias gradient).
 size_t gp_gemm_tn_scratch(int64_t rows, int M, int N);
 int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M, int N, float* out,
-               float* part, size_t part_bytes);
+               float* colsum_out, float* part, size_t part_bytes);
 // out[n] = sum_r X[r,n]
 size_t gp_colsum_scratch(int64_t rows, int N);
 int gp_colsum(gp_ctx* ctx, const float* X, int64_t rows, int N, float* out, float* part, size_t part_bytes);

@@ -2,10 +2,11 @@
 // reductions and elementwise kernels the edge MLPs need (EdgeUpdate of paper Sec. 2.1 / 3.3).
 //
 // Tiling: a 256-thread workgroup (4 wavefronts of 64) owns a BM x BN tile of C; the K loop
-// advances 16 at a time through LDS tiles As[k][m], Bs[k][n] (k-major, so the 32 lanes that
-// feed one MFMA operand read consecutive LDS words).  Each wavefront owns (BM/WAVES_M) x
-// (BN/WAVES_N) of the tile as 32x32 MFMA blocks.  The next K-slab is fetched into registers
-// while the current one is multiplied.
+// advances BK = 32 at a time through double-buffered LDS tiles As[k][m], Bs[k][n] (k-major, so
+// the 32 lanes that feed one MFMA operand read consecutive LDS words).  Each wavefront owns
+// (BM/WAVES_M) x (BN/WAVES_N) of the tile as 32x32 MFMA blocks.  The next K-slab is fetched
+// into registers while the current one is multiplied and is written to the other LDS buffer
+// afterwards, so there is one barrier per slab.
 #include <stdarg.h>
 
 #include <type_traits>
@@ -17,8 +18,16 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BK = 16;
+#ifndef GP_GEMM_BK
+#define GP_GEMM_BK 16
+#endif
+#ifndef GP_GEMM_NBUF
+#define GP_GEMM_NBUF 1
+#endif
+constexpr int BK = GP_GEMM_BK;
+constexpr int NBUF = GP_GEMM_NBUF;   // LDS buffers per operand (2: one barrier per slab)
 constexpr int THREADS = 256;
+constexpr int EPI_LD = 36;             // row stride of a wavefront's 32x32 staging block (floats)
 enum { MODE_NN = 0, MODE_NT = 1, MODE_TN = 2 };
 
 struct gemm_args {
@@ -28,8 +37,10 @@ struct gemm_args {
   int N, K;    // cols of C, contraction length (TN: total rows to reduce)
   int64_t lda, ldb;
   int vecA, vecB;          // 16-byte vector loads are legal for this operand
+  int vecC;                // 16-byte accesses are legal for every matrix the epilogue touches
   int64_t k_per_split;     // TN only
   float* part;             // TN only: [splits, M, N]
+  float* colsum_part;      // TN only, optional: [splits * tiles_m, N] partial column sums of B
   gp_epilogue epi;
 };
 
@@ -47,6 +58,42 @@ __device__ __forceinline__ void epilogue_store(const gp_epilogue& e, int64_t row
   if (e.out2) e.out2[o] = v * dsilu_f(e.z2src[o]);
 }
 
+__device__ __forceinline__ f32x4 ld4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+__device__ __forceinline__ void st4(float* p, f32x4 v) { *reinterpret_cast<f32x4*>(p) = v; }
+
+// Same steps on 4 consecutive columns (col % 4 == 0, all pointers 16-byte aligned, n % 4 == 0).
+__device__ __forceinline__ void epilogue_store4(const gp_epilogue& e, int64_t row, int col, int n, f32x4 v) {
+  const int64_t o = row * n + col;
+  if (e.bias) v += ld4(e.bias + col);
+  if (e.add_pre) v += ld4(e.add_pre + o);
+  if (e.save_pre) st4(e.save_pre + o, v);
+  if (e.act == 1) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] = silu_f(v[c]);
+  } else if (e.act == 2) {
+    const f32x4 z = ld4(e.zsrc + o);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
+  }
+  if (e.mul) v *= ld4(e.mul + o);
+  if (e.add_post) v += ld4(e.add_post + o);
+  v *= e.scale;
+  if (e.out) st4(e.out + o, v);
+  if (e.out2) {
+    const f32x4 z = ld4(e.z2src + o);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
+    st4(e.out2 + o, v);
+  }
+}
+
+// wavefront-local ordering of LDS traffic (no other wavefront touches this wave's slice)
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Workgroup ids are dealt round-robin to the 8 XCDs; renumber them so that each XCD works on
 // a contiguous range of tiles and neighbouring tiles (same A rows) share that XCD's L2.
 __device__ __forceinline__ int xcd_remap(int bid, int n) {
@@ -58,17 +105,19 @@ __device__ __forceinline__ int xcd_remap(int bid, int n) {
 // Source has the contraction index contiguous: tile of X rows by BK k's, stored transposed.
 template <int X>
 struct loader_kcontig {
-  static constexpr int TOTAL = X * BK / 4;
+  static constexpr int KV = BK / 4;               // 16-byte vectors per row
+  static constexpr int TOTAL = X * KV;
   static constexpr int NV = (TOTAL + THREADS - 1) / THREADS;
+  static constexpr int LD = X + 1;                // odd stride: transposed stores hit distinct banks
   f32x4 r[NV];
   __device__ __forceinline__ void fetch(const float* __restrict__ src, int64_t ld, int64_t row0,
-                                        int64_t n_rows, int k0, int k_end, int vec) {
+                                        int64_t n_rows, int64_t k0, int64_t k_end, int vec) {
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = threadIdx.x + it * THREADS;
-      const int row = idx >> 2, kq = (idx & 3) * 4;
+      const int row = idx / KV, kq = (idx % KV) * 4;
       const int64_t gr = (TOTAL % THREADS == 0 || idx < TOTAL) ? row0 + row : n_rows;
-      const int gk = k0 + kq;
+      const int64_t gk = k0 + kq;
       f32x4 v = {0.f, 0.f, 0.f, 0.f};
       if (gr < n_rows) {
         const float* p = src + gr * ld + gk;
@@ -83,12 +132,11 @@ struct loader_kcontig {
       r[it] = v;
     }
   }
-  template <int LD>
   __device__ __forceinline__ void store(float* __restrict__ S) const {
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = threadIdx.x + it * THREADS;
-      const int row = idx >> 2, kq = (idx & 3) * 4;
+      const int row = idx / KV, kq = (idx % KV) * 4;
       if (TOTAL % THREADS != 0 && idx >= TOTAL) continue;
 #pragma unroll
       for (int c = 0; c < 4; ++c) S[(kq + c) * LD + row] = r[it][c];
@@ -101,6 +149,7 @@ template <int X>
 struct loader_xcontig {
   static constexpr int TOTAL = X * BK / 4;
   static constexpr int NV = (TOTAL + THREADS - 1) / THREADS;
+  static constexpr int LD = X + 4;
   f32x4 r[NV];
   __device__ __forceinline__ void fetch(const float* __restrict__ src, int64_t ld, int64_t x0,
                                         int64_t n_x, int64_t k0, int64_t k_end, int vec) {
@@ -123,7 +172,6 @@ struct loader_xcontig {
       r[it] = v;
     }
   }
-  template <int LD>
   __device__ __forceinline__ void store(float* __restrict__ S) const {
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
@@ -138,20 +186,21 @@ struct loader_xcontig {
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
 __global__ void __launch_bounds__(THREADS)
 gemm_f32_kernel(const gemm_args g) {
-  static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+  static_assert(WAVES_M * WAVES_N == 4 || BM == 64, "four wavefronts per workgroup");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MB = WM / 32, NB = WN / 32;
-  constexpr bool A_KC = (MODE != MODE_TN);   // A source has k contiguous
-  constexpr bool B_KC = (MODE == MODE_NT);
-  constexpr int LDA = BM + (A_KC ? 2 : 4);
-  constexpr int LDB = BN + (B_KC ? 2 : 4);
-  __shared__ __attribute__((aligned(16))) float As[BK * LDA];
-  __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
+  using loadA = typename std::conditional<MODE != MODE_TN, loader_kcontig<BM>, loader_xcontig<BM>>::type;
+  using loadB = typename std::conditional<MODE == MODE_NT, loader_kcontig<BN>, loader_xcontig<BN>>::type;
+  constexpr int LDA = loadA::LD, LDB = loadB::LD;
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  auto As = [&](int buf) -> float* { return smem + buf * (BK * LDA); };
+  auto Bs = [&](int buf) -> float* { return smem + NBUF * BK * LDA + buf * (BK * LDB); };
 
   const int tiles_n = (g.N + BN - 1) / BN;
   const int tiles_m = (int)((g.M + BM - 1) / BM);
   const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  const int64_t m0 = (int64_t)(tile / tiles_n) * BM;
+  const int tile_m = tile / tiles_n;
+  const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = (tile % tiles_n) * BN;
 
   int64_t k_begin = 0, k_end = g.K;
@@ -170,73 +219,112 @@ gemm_f32_kernel(const gemm_args g) {
     for (int j = 0; j < NB; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  float colsum = 0.f;   // TN: column threadIdx.x of the B tile, over the slabs this workgroup owns
 
-  typename std::conditional<A_KC, loader_kcontig<BM>, loader_xcontig<BM>>::type la;
-  typename std::conditional<B_KC, loader_kcontig<BN>, loader_xcontig<BN>>::type lb;
-
+  loadA la;
+  loadB lb;
   auto fetch = [&](int64_t k0) {
-    if constexpr (A_KC) la.fetch(g.A, g.lda, m0, g.M, (int)k0, (int)k_end, g.vecA);
-    else la.fetch(g.A, g.lda, m0, g.M, k0, k_end, g.vecA);
-    if constexpr (B_KC) lb.fetch(g.B, g.ldb, n0, g.N, (int)k0, (int)k_end, g.vecB);
-    else lb.fetch(g.B, g.ldb, n0, g.N, k0, k_end, g.vecB);
+    la.fetch(g.A, g.lda, m0, g.M, k0, k_end, g.vecA);
+    lb.fetch(g.B, g.ldb, n0, g.N, k0, k_end, g.vecB);
   };
 
   if (k_begin < k_end) {
     fetch(k_begin);
-    la.template store<LDA>(As);
-    lb.template store<LDB>(Bs);
+    la.store(As(0));
+    lb.store(Bs(0));
   }
   __syncthreads();
 
   const int kh = lane >> 5, l32 = lane & 31;
-  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+  int cur = 0, slab = 0;
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK, ++slab) {
     const bool more = k0 + BK < k_end;
     if (more) fetch(k0 + BK);
+    const float* __restrict__ Ac = As(cur);
+    const float* __restrict__ Bc = Bs(cur);
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
       float a[MB], b[NB];
 #pragma unroll
-      for (int i = 0; i < MB; ++i) a[i] = As[(kk + kh) * LDA + wm0 + i * 32 + l32];
+      for (int i = 0; i < MB; ++i) a[i] = Ac[(kk + kh) * LDA + wm0 + i * 32 + l32];
 #pragma unroll
-      for (int j = 0; j < NB; ++j) b[j] = Bs[(kk + kh) * LDB + wn0 + j * 32 + l32];
+      for (int j = 0; j < NB; ++j) b[j] = Bc[(kk + kh) * LDB + wn0 + j * 32 + l32];
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    __syncthreads();
+    if (MODE == MODE_TN && g.colsum_part && (slab % tiles_m) == tile_m && threadIdx.x < BN) {
+#pragma unroll
+      for (int kk = 0; kk < BK; ++kk) colsum += Bc[kk * LDB + threadIdx.x];
+    }
     if (more) {
-      la.template store<LDA>(As);
-      lb.template store<LDB>(Bs);
+      if (NBUF == 1) __syncthreads();
+      la.store(As(cur ^ (NBUF - 1)));
+      lb.store(Bs(cur ^ (NBUF - 1)));
     }
     __syncthreads();
+    cur ^= (NBUF - 1);
   }
 
-  // C layout of the 32x32 block: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, col l%32
+  // Epilogue.  The 32x32 MFMA block keeps, in register v of lane l, row 8*(v/4) + 4*(l/32) + v%4
+  // and column l%32.  Each wavefront transposes one block at a time through its own LDS slice so
+  // that a lane ends up with 4 consecutive columns: loads and stores become 16-byte accesses,
+  // eight 128-byte row segments per instruction.
+  __syncthreads();   // all wavefronts are done with the operand tiles; LDS is reused below
+  float* stage = smem + wave * (32 * EPI_LD);
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-      const int col = n0 + wn0 + j * 32 + l32;
-      if (col >= g.N) continue;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int64_t row = m0 + wm0 + i * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
-        if (row >= g.M) continue;
-        if (MODE == MODE_TN) g.part[((int64_t)blockIdx.y * g.M + row) * g.N + col] = acc[i][j][v];
-        else epilogue_store(g.epi, row, col, g.N, acc[i][j][v]);
+      for (int v = 0; v < 16; ++v) stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD + l32] = acc[i][j][v];
+      wave_lds_sync();
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int r = it * 8 + (lane >> 3), c4 = (lane & 7) * 4;
+        const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[r * EPI_LD + c4]);
+        const int64_t row = m0 + wm0 + i * 32 + r;
+        const int col = n0 + wn0 + j * 32 + c4;
+        if (row >= g.M || col >= g.N) continue;
+        if (MODE == MODE_TN) {
+          float* dst = g.part + ((int64_t)blockIdx.y * g.M + row) * g.N + col;
+          if (g.vecC) *reinterpret_cast<f32x4*>(dst) = v4;
+          else
+            for (int c = 0; c < 4; ++c)
+              if (col + c < g.N) dst[c] = v4[c];
+        } else {
+#ifdef GP_GEMM_DEBUG_NOSTORE
+          if (v4[0] != 123.456f) continue;
+#endif
+          if (g.vecC) epilogue_store4(g.epi, row, col, g.N, v4);
+          else
+            for (int c = 0; c < 4; ++c)
+              if (col + c < g.N) epilogue_store(g.epi, row, col + c, g.N, v4[c]);
+        }
       }
+      wave_lds_sync();
     }
+  if (MODE == MODE_TN && g.colsum_part && threadIdx.x < BN && n0 + (int)threadIdx.x < g.N)
+    g.colsum_part[((int64_t)blockIdx.y * tiles_m + tile_m) * g.N + n0 + threadIdx.x] = colsum;
 }
 
-// out[i] = sum_z part[z*n + i]
-__global__ void reduce_parts_kernel(const float* __restrict__ part, int splits, int64_t n, float* __restrict__ out) {
+// out[i] = sum_z part[z*n + i] for i < n;  out2[i] = sum_z part2[z*n2 + i] for i < n2
+__global__ void reduce_parts_kernel(const float* __restrict__ part, int splits, int64_t n, float* __restrict__ out,
+                                    const float* __restrict__ part2, int splits2, int64_t n2,
+                                    float* __restrict__ out2) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  float s = 0.f;
-  for (int z = 0; z < splits; ++z) s += part[(int64_t)z * n + i];
-  out[i] = s;
+  if (i < n) {
+    float s = 0.f;
+    for (int z = 0; z < splits; ++z) s += part[(int64_t)z * n + i];
+    out[i] = s;
+  } else if (i < n + n2) {
+    i -= n;
+    float s = 0.f;
+    for (int z = 0; z < splits2; ++z) s += part2[(int64_t)z * n2 + i];
+    out2[i] = s;
+  }
 }
 
 // part[b*N + c] = sum over the b-th slab of rows of X[r, c]
@@ -284,16 +372,44 @@ int launch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
   const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (tiles > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
   dim3 grid((unsigned)tiles, (unsigned)splits, 1);
-  gemm_f32_kernel<BM, BN, WMS, WNS, MODE><<<grid, THREADS, 0, ctx->stream>>>(g);
+  static char name[48];
+  if (!name[0]) snprintf(name, sizeof(name), "gemm_f32_%s_%dx%d", MODE == MODE_NN ? "nn" : MODE == MODE_NT ? "nt" : "tn", BM, BN);
+  const double mnk = (double)g.M * g.N * g.K;
+  gp_prof_scope prof(ctx, name, 2.0 * mnk,
+                     4.0 * ((double)g.M * g.K + (double)g.K * g.N + (double)g.M * g.N * (MODE == MODE_TN ? splits : 1)));
+  using loadA = typename std::conditional<MODE != MODE_TN, loader_kcontig<BM>, loader_xcontig<BM>>::type;
+  using loadB = typename std::conditional<MODE == MODE_NT, loader_kcontig<BN>, loader_xcontig<BN>>::type;
+  constexpr size_t lds_main = sizeof(float) * NBUF * BK * (loadA::LD + loadB::LD);
+  constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD;
+  constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+  static bool attr_set = false;
+  if (!attr_set) {
+    GP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f32_kernel<BM, BN, WMS, WNS, MODE>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  gemm_f32_kernel<BM, BN, WMS, WNS, MODE><<<grid, THREADS, lds, ctx->stream>>>(g);
   GP_LAUNCH_CHECK(ctx, "gemm_f32_kernel");
   return GP_OK;
 }
 
+// tile shape by output width
+inline int tile_bn(int N) { return N > 64 ? 128 : N > 32 ? 64 : 32; }
+#ifndef GP_GEMM_BM
+#define GP_GEMM_BM 128
+#endif
+constexpr int TILE_BM = GP_GEMM_BM;
+
 template <int MODE>
 int dispatch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
-  if (g.N > 64) return launch_gemm<128, 128, 2, 2, MODE>(ctx, g, splits);
-  if (g.N > 32) return launch_gemm<128, 64, 2, 2, MODE>(ctx, g, splits);
+#if GP_GEMM_BM == 64
+  if (g.N > 64) return launch_gemm<TILE_BM, 128, 1, 4, MODE>(ctx, g, splits);
+  if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
   return launch_gemm<128, 32, 4, 1, MODE>(ctx, g, splits);
+#endif
+  if (g.N > 64) return launch_gemm<TILE_BM, 128, 2, 2, MODE>(ctx, g, splits);
+  if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
+  return launch_gemm<TILE_BM, 32, 4, 1, MODE>(ctx, g, splits);
 }
 
 int check_epi(gp_ctx* ctx, const gp_epilogue& e) {
@@ -301,6 +417,35 @@ int check_epi(gp_ctx* ctx, const gp_epilogue& e) {
   GP_REQUIRE(ctx, e.act != 2 || e.zsrc, "gemm: act=2 needs zsrc");
   GP_REQUIRE(ctx, !e.out2 || e.z2src, "gemm: out2 needs z2src");
   return GP_OK;
+}
+
+bool epi_vec_ok(const gp_epilogue& e, int N) {
+  return N % 4 == 0 && aligned16(e.bias) && aligned16(e.add_pre) && aligned16(e.save_pre) && aligned16(e.zsrc) &&
+         aligned16(e.mul) && aligned16(e.add_post) && aligned16(e.out) && aligned16(e.out2) && aligned16(e.z2src);
+}
+
+struct tn_plan_t {
+  int splits, tiles_m, tiles_n;
+  int64_t per;
+};
+
+// Split the reduction so that about two workgroups per CU exist, each reducing >= 512 rows.
+tn_plan_t tn_plan(int64_t rows, int M, int N) {
+  tn_plan_t p;
+  p.tiles_m = (M + TILE_BM - 1) / TILE_BM;
+  p.tiles_n = (N + tile_bn(N) - 1) / tile_bn(N);
+  const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+  int64_t s = (512 + tiles - 1) / tiles;
+  const int64_t max_s = (rows + 511) / 512;
+  if (s > max_s) s = max_s;
+  if (s < 1) s = 1;
+  int64_t per = (rows + s - 1) / s;
+  per = (per + BK - 1) / BK * BK;
+  s = (rows + per - 1) / per;
+  if (s < 1) s = 1;
+  p.splits = (int)s;
+  p.per = per;
+  return p;
 }
 
 }  // namespace
@@ -314,6 +459,7 @@ int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, in
   g.vecA = (K % 4 == 0) && aligned16(A);
   g.vecB = (N % 4 == 0) && aligned16(B);
   g.epi = epi;
+  g.vecC = epi_vec_ok(epi, N);
   return dispatch_gemm<MODE_NN>(ctx, g, 1);
 }
 
@@ -326,50 +472,39 @@ int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, i
   g.vecA = (K % 4 == 0) && aligned16(A);
   g.vecB = (K % 4 == 0) && aligned16(Bt);
   g.epi = epi;
+  g.vecC = epi_vec_ok(epi, N);
   return dispatch_gemm<MODE_NT>(ctx, g, 1);
 }
 
-static void tn_plan(int64_t rows, int M, int N, int* splits, int64_t* per) {
-  // enough workgroups to cover the chip a few times over, each reducing at least 256 rows
-  const int64_t tiles = (int64_t)((M + 127) / 128) * ((N + (N > 64 ? 127 : N > 32 ? 63 : 31)) / (N > 64 ? 128 : N > 32 ? 64 : 32));
-  int64_t s = (1024 + tiles - 1) / tiles;
-  int64_t max_s = (rows + 255) / 256;
-  if (s > max_s) s = max_s;
-  if (s < 1) s = 1;
-  int64_t p = (rows + s - 1) / s;
-  p = (p + BK - 1) / BK * BK;
-  s = (rows + p - 1) / p;
-  if (s < 1) s = 1;
-  *splits = (int)s;
-  *per = p;
-}
-
 size_t gp_gemm_tn_scratch(int64_t rows, int M, int N) {
-  int s; int64_t p;
-  tn_plan(rows, M, N, &s, &p);
-  return gp_align((size_t)s * M * N * sizeof(float));
+  tn_plan_t p = tn_plan(rows, M, N);
+  return gp_align((size_t)p.splits * M * N * sizeof(float)) + gp_align((size_t)p.splits * p.tiles_m * N * sizeof(float));
 }
 
 int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M, int N, float* out,
-               float* part, size_t part_bytes) {
+               float* colsum_out, float* part, size_t part_bytes) {
   GP_REQUIRE(ctx, A && B && out && rows >= 0 && M > 0 && N > 0, "gemm_tn: bad arguments");
   if (rows == 0) {
     GP_HIP(ctx, hipMemsetAsync(out, 0, sizeof(float) * M * N, ctx->stream));
+    if (colsum_out) GP_HIP(ctx, hipMemsetAsync(colsum_out, 0, sizeof(float) * N, ctx->stream));
     return GP_OK;
   }
   if (rows > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "gemm_tn: too many rows");
-  int splits; int64_t per;
-  tn_plan(rows, M, N, &splits, &per);
-  size_t need = (size_t)splits * M * N * sizeof(float);
+  const tn_plan_t p = tn_plan(rows, M, N);
+  const size_t need = gp_gemm_tn_scratch(rows, M, N);
   if (!part || part_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gemm_tn: scratch %zu < %zu", part_bytes, need);
   gemm_args g{};
   g.A = A; g.B = B; g.M = M; g.N = N; g.K = (int)rows; g.lda = M; g.ldb = N;
   g.vecA = (M % 4 == 0) && aligned16(A);
   g.vecB = (N % 4 == 0) && aligned16(B);
-  g.k_per_split = per;
+  g.k_per_split = p.per;
   g.part = part;
-  GP_TRY(dispatch_gemm<MODE_TN>(ctx, g, splits));
-  reduce_parts_kernel<<<nblk((int64_t)M * N), 256, 0, ctx->stream>>>(part, splits, (int64_t)M * N, out);
+  g.vecC = (N % 4 == 0) && aligned16(part) && ((size_t)M * N % 4 == 0);
+  float* cpart = (float*)((char*)part + gp_align((size_t)p.splits * M * N * sizeof(float)));
+  g.colsum_part = colsum_out ? cpart : nullptr;
+  GP_TRY(dispatch_gemm<MODE_TN>(ctx, g, p.splits));
+  const int64_t n1 = (int64_t)M * N, n2 = colsum_out ? N : 0;
+  reduce_parts_kernel<<<nblk(n1 + n2), 256, 0, ctx->stream>>>(part, p.splits, n1, out, cpart, p.splits * p.tiles_m, n2, colsum_out);
   GP_LAUNCH_CHECK(ctx, "reduce_parts_kernel");
   return GP_OK;
 }
@@ -397,14 +532,12 @@ int gp_colsum(gp_ctx* ctx, const float* X, int64_t rows, int N, float* out, floa
   if (!part || part_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "colsum: scratch %zu < %zu", part_bytes, need);
   colsum_part_kernel<<<blocks, 256, 0, ctx->stream>>>(X, rows, N, per, part);
   GP_LAUNCH_CHECK(ctx, "colsum_part_kernel");
-  reduce_parts_kernel<<<nblk(N), 256, 0, ctx->stream>>>(part, blocks, N, out);
-  GP_LAUNCH_CHECK(ctx, "reduce_parts_kernel");
-  return GP_OK;
+  return gp_reduce_parts(ctx, part, blocks, N, out);
 }
 
 int gp_reduce_parts(gp_ctx* ctx, const float* part, int splits, int64_t n, float* out) {
   if (n == 0) return GP_OK;
-  reduce_parts_kernel<<<nblk(n), 256, 0, ctx->stream>>>(part, splits, n, out);
+  reduce_parts_kernel<<<nblk(n), 256, 0, ctx->stream>>>(part, splits, n, out, nullptr, 0, 0, nullptr);
   GP_LAUNCH_CHECK(ctx, "reduce_parts_kernel");
   return GP_OK;
 }

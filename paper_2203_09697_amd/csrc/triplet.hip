@@ -378,6 +378,9 @@ int gp_tripD_forward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, con
   if (F < 1 || F > 256 || S < 1 || S > ST || B < 1 || B > 16)
     return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "triplet D forward: int_emb=%d num_spherical=%d basis_emb=%d unsupported", F, S, B);
   GP_REQUIRE(ctx, x && Q && W2 && a && Bacc && (g->n_triplets == 0 || cos_alpha), "triplet D forward: NULL pointer");
+  const double Td = (double)g->n_triplets, Ed = (double)E;
+  gp_prof_scope prof(ctx, "tripD_fwd", Td * 2.0 * (S * B + B * F) + Ed * 2.0 * B * F,
+                     Td * 8.0 + Ed * 4.0 * (F + S * B + B * F + F) + Ed * 4.0);
 #define CALL_FWD(LPR, FPL)                                                                                       \
   do {                                                                                                           \
     if (B <= 4) tripD_fwd_kernel<4, LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(                    \
@@ -404,6 +407,9 @@ int gp_tripD_backward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj,
   GP_REQUIRE(ctx, x && Q && W2 && grad_a && grad_x && grad_Q && (g->n_triplets == 0 || cos_alpha_kj),
              "triplet D backward: NULL pointer");
   const size_t dyn = (size_t)WPB * ST * (F + 1) * sizeof(float);
+  const double Td = (double)g->n_triplets, Ed = (double)E;
+  gp_prof_scope prof(ctx, "tripD_bwd", Td * 2.0 * S * F + Ed * 2.0 * (S * B * F * 2 + B * F),
+                     Td * 8.0 + Ed * 4.0 * (F * 4 + S * B * 2) + Ed * 4.0);
 #define CALL_BWD(LPR, FPL)                                                                      \
   tripD_bwd_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, dyn, ctx->stream>>>(                  \
       g->seg_ptr_kj, g->idx_ji_kj, cos_alpha_kj, x, Q, W2, grad_a, z, E, F, S, B, grad_x, grad_Q)
@@ -451,6 +457,8 @@ extern "C" int gp_triplet_aggregate_fwd(gp_ctx* ctx, const gp_graph* graph, int3
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, x && a && (graph->n_triplets == 0 || s), "gp_triplet_aggregate_fwd: NULL pointer");
   GP_HIP(ctx, hipSetDevice(ctx->device));
+  gp_prof_scope prof(ctx, "triplet_stream_fwd", 2.0 * graph->n_triplets * F,
+                     (double)graph->n_triplets * (4.0 * F + 4.0) + (double)E * (8.0 * F + 4.0));
 #define CALL_S(LPR, FPL) \
   stream_fwd_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(graph->seg_ptr_ji, graph->idx_kj, x, s, E, F, a)
   GP_DISPATCH_WIDTH(F, CALL_S);
@@ -471,6 +479,8 @@ extern "C" int gp_triplet_aggregate_bwd(gp_ctx* ctx, const gp_graph* graph, cons
   GP_REQUIRE(ctx, x && grad_a && grad_x && (graph->n_triplets == 0 || (s && grad_s && perm_kj)),
              "gp_triplet_aggregate_bwd: NULL pointer");
   GP_HIP(ctx, hipSetDevice(ctx->device));
+  gp_prof_scope prof(ctx, "triplet_stream_bwd", 3.0 * graph->n_triplets * F,
+                     (double)graph->n_triplets * (12.0 * F + 16.0) + (double)E * (12.0 * F + 8.0));
 #define CALL_S(LPR, FPL)                                                                                          \
   do {                                                                                                            \
     stream_bwd_x_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(                                 \
