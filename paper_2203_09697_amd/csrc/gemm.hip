@@ -310,21 +310,59 @@ gemm_f32_kernel(const gemm_args g) {
     g.colsum_part[((int64_t)blockIdx.y * tiles_m + tile_m) * g.N + n0 + threadIdx.x] = colsum;
 }
 
-// out[i] = sum_z part[z*n + i] for i < n;  out2[i] = sum_z part2[z*n2 + i] for i < n2
-__global__ void reduce_parts_kernel(const float* __restrict__ part, int splits, int64_t n, float* __restrict__ out,
-                                    const float* __restrict__ part2, int splits2, int64_t n2,
-                                    float* __restrict__ out2) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) {
-    float s = 0.f;
-    for (int z = 0; z < splits; ++z) s += part[(int64_t)z * n + i];
-    out[i] = s;
-  } else if (i < n + n2) {
-    i -= n;
-    float s = 0.f;
-    for (int z = 0; z < splits2; ++z) s += part2[(int64_t)z * n2 + i];
-    out2[i] = s;
+// out[i] = sum_z part[z*n + i] for i < n;  out2[i] = sum_z part2[z*n2 + i] for i < n2.
+// 64 column groups x 4 split lanes per workgroup; each lane keeps several 16-byte loads in
+// flight and the four lanes are combined in a fixed order, so the result is reproducible.
+constexpr int RED_COLS = 64, RED_LANES = 4;
+__global__ void __launch_bounds__(RED_COLS* RED_LANES)
+reduce_parts_kernel(const float* __restrict__ part, int splits, int64_t n, int vec, float* __restrict__ out,
+                    int blocks1, const float* __restrict__ part2, int splits2, int64_t n2,
+                    float* __restrict__ out2) {
+  __shared__ f32x4 red[RED_LANES][RED_COLS];
+  const int cg = threadIdx.x % RED_COLS, sl = threadIdx.x / RED_COLS;
+  if ((int)blockIdx.x < blocks1) {
+    const int64_t i = ((int64_t)blockIdx.x * RED_COLS + cg) * 4;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (i < n) {
+      if (vec) {
+#pragma unroll 4
+        for (int z = sl; z < splits; z += RED_LANES) s += ld4(part + (int64_t)z * n + i);
+      } else {
+        for (int z = sl; z < splits; z += RED_LANES)
+          for (int c = 0; c < 4; ++c)
+            if (i + c < n) s[c] += part[(int64_t)z * n + i + c];
+      }
+    }
+    red[sl][cg] = s;
+    __syncthreads();
+    if (sl == 0 && i < n) {
+      f32x4 t = red[0][cg];
+      for (int k = 1; k < RED_LANES; ++k) t += red[k][cg];
+      if (vec) st4(out + i, t);
+      else
+        for (int c = 0; c < 4; ++c)
+          if (i + c < n) out[i + c] = t[c];
+    }
+  } else {
+    const int64_t i = (int64_t)(blockIdx.x - blocks1) * blockDim.x + threadIdx.x;
+    if (i < n2) {
+      float s = 0.f;
+      for (int z = 0; z < splits2; ++z) s += part2[(int64_t)z * n2 + i];
+      out2[i] = s;
+    }
   }
+}
+
+int launch_reduce(gp_ctx* ctx, const float* part, int splits, int64_t n, float* out, const float* part2, int splits2,
+                  int64_t n2, float* out2) {
+  const int per_block = RED_COLS * 4;
+  const int blocks1 = (int)((n + per_block - 1) / per_block);
+  const int blocks2 = (int)((n2 + RED_COLS * RED_LANES - 1) / (RED_COLS * RED_LANES));
+  const int vec = (n % 4 == 0) && (((uintptr_t)part | (uintptr_t)out) & 15) == 0;
+  reduce_parts_kernel<<<blocks1 + blocks2, RED_COLS * RED_LANES, 0, ctx->stream>>>(part, splits, n, vec, out, blocks1,
+                                                                                  part2, splits2, n2, out2);
+  GP_LAUNCH_CHECK(ctx, "reduce_parts_kernel");
+  return GP_OK;
 }
 
 // part[b*N + c] = sum over the b-th slab of rows of X[r, c]
@@ -504,9 +542,7 @@ int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M,
   g.colsum_part = colsum_out ? cpart : nullptr;
   GP_TRY(dispatch_gemm<MODE_TN>(ctx, g, p.splits));
   const int64_t n1 = (int64_t)M * N, n2 = colsum_out ? N : 0;
-  reduce_parts_kernel<<<nblk(n1 + n2), 256, 0, ctx->stream>>>(part, p.splits, n1, out, cpart, p.splits * p.tiles_m, n2, colsum_out);
-  GP_LAUNCH_CHECK(ctx, "reduce_parts_kernel");
-  return GP_OK;
+  return launch_reduce(ctx, part, p.splits, n1, out, cpart, p.splits * p.tiles_m, n2, colsum_out);
 }
 
 static void colsum_plan(int64_t rows, int* blocks, int64_t* per) {
@@ -537,9 +573,7 @@ int gp_colsum(gp_ctx* ctx, const float* X, int64_t rows, int N, float* out, floa
 
 int gp_reduce_parts(gp_ctx* ctx, const float* part, int splits, int64_t n, float* out) {
   if (n == 0) return GP_OK;
-  reduce_parts_kernel<<<nblk(n), 256, 0, ctx->stream>>>(part, splits, n, out, nullptr, 0, 0, nullptr);
-  GP_LAUNCH_CHECK(ctx, "reduce_parts_kernel");
-  return GP_OK;
+  return launch_reduce(ctx, part, splits, n, out, nullptr, 0, 0, nullptr);
 }
 
 int gp_ew_dsilu_mul(gp_ctx* ctx, const float* g, const float* z, float* out, int64_t n) {

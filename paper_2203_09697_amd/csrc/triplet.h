@@ -8,7 +8,7 @@
 // s_t[f] = sum_b p_t[b] W_sbf2[b,f]; this is the two-step projection of the materialised
 // spherical basis, re-associated so that nothing of size T x S*R is ever stored.
 
-// Q[E, S*B] from rad[E, S*R] and W_sbf1[S*R, B]
+// Q from rad[E, S*R] and W_sbf1[S*R, B], stored transposed: Qt[(l*B+b)*E + e]
 int gp_tripD_project_radial(gp_ctx* ctx, const float* rad, const float* W1, int64_t E, int S, int R, int B, float* Q);
 
 // a[e,f] = sum_{t in seg_ji(e)} x[kj(t),f] s_t[f];  Bacc[e,b,f] = sum_t p_t[b] x[kj(t),f]

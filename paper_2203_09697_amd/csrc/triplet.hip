@@ -16,6 +16,7 @@ namespace {
 
 constexpr int WPB = 4;        // wavefronts per workgroup
 constexpr int ST = 8;         // max num_spherical
+constexpr int UNR = 4;        // gathered rows kept in flight per group
 __device__ __constant__ float Y_NORM[ST] = {
     0.28209479177387814f, 0.4886025119029199f, 0.6307831305050401f, 0.7463526651802308f,
     0.8462843753216345f, 0.9356025796273888f, 1.0171072362820548f, 1.0925484305920792f};  // sqrt((2l+1)/(4 pi))
@@ -51,16 +52,24 @@ __device__ __forceinline__ void butterfly(float (&v)[FPL], int lpr) {
 
 // ------------------------------------------------------------------ per-edge radial projection
 __global__ void project_radial_kernel(const float* __restrict__ rad, const float* __restrict__ W1, int64_t E,
-                                      int S, int R, int B, float* __restrict__ Q) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= E * S * B) return;
-  int b = (int)(idx % B);
-  int l = (int)((idx / B) % S);
-  int64_t e = idx / ((int64_t)S * B);
-  const float* r = rad + (e * S + l) * R;
-  float s = 0.f;
-  for (int n = 0; n < R; ++n) s += r[n] * W1[(l * R + n) * B + b];
-  Q[idx] = s;
+                                      int S, int R, int B, float* __restrict__ Qt) {
+  // one workgroup per 64 edges: their rad rows are one contiguous chunk, staged in LDS so that
+  // both the read of rad and the transposed write of Qt are coalesced
+  extern __shared__ float rad_s[];                 // [64][S*R + 1]
+  const int SR = S * R, LD = SR + 1;
+  const int64_t e0 = (int64_t)blockIdx.x * 64;
+  const int ne = (int)min((int64_t)64, E - e0);
+  for (int i = threadIdx.x; i < ne * SR; i += blockDim.x) rad_s[(i / SR) * LD + (i % SR)] = rad[e0 * SR + i];
+  __syncthreads();
+  for (int o = threadIdx.x; o < 64 * S * B; o += blockDim.x) {
+    const int el = o & 63, lb = o >> 6;
+    if (el >= ne) continue;
+    const int b = lb % B, l = lb / B;
+    const float* r = rad_s + el * LD + l * R;
+    float s = 0.f;
+    for (int n = 0; n < R; ++n) s += r[n] * W1[(l * R + n) * B + b];
+    Qt[(int64_t)lb * E + e0 + el] = s;
+  }
 }
 
 // ------------------------------------------------------------------ fused forward
@@ -90,26 +99,40 @@ tripD_fwd_kernel(const int32_t* __restrict__ seg, const int32_t* __restrict__ id
       const int kj = idx_kj[t];
       float Y[ST];
       y_l0(cos_alpha[t], S, Y);
-      const float* q = Q + (int64_t)kj * S * B;
+      // Q is stored transposed, Qt[(l*B+b)*E + e]: the lanes of a segment hold (almost)
+      // consecutive source edges, so each of these loads is one or two cache lines per wavefront
+      const float* q = Q + kj;
 #pragma unroll
       for (int b = 0; b < BT; ++b) {
         float p = 0.f;
         if (b < B)
-          for (int l = 0; l < S; ++l) p += Y[l] * q[l * B + b];
+          for (int l = 0; l < S; ++l) p += Y[l] * q[(int64_t)(l * B + b) * E];
         p_s[w][lane][b] = p;
       }
       kj_s[w][lane] = kj;
     }
     wave_lds_sync();
-    for (int tt = grp; tt < n; tt += G) {
-      const int64_t kj = kj_s[w][tt];
+    // UNR gathered rows are requested before any is consumed, to keep loads in flight
+    for (int tt = grp; tt < n; tt += UNR * G) {
+      float xv[UNR][FPL];
 #pragma unroll
-      for (int i = 0; i < FPL; ++i) {
-        const int f = fl + i * WAVE;
-        if (f < F) {
-          const float xv = x[kj * F + f];
+      for (int u = 0; u < UNR; ++u) {
+        const int id = tt + u * G;
+        const int64_t kj = kj_s[w][id < n ? id : tt];
 #pragma unroll
-          for (int b = 0; b < BT; ++b) acc[b][i] += p_s[w][tt][b] * xv;
+        for (int i = 0; i < FPL; ++i) {
+          const int f = fl + i * WAVE;
+          xv[u][i] = (f < F && id < n) ? x[kj * F + f] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int id = tt + u * G;
+        if (id < n) {
+#pragma unroll
+          for (int i = 0; i < FPL; ++i)
+#pragma unroll
+            for (int b = 0; b < BT; ++b) acc[b][i] += p_s[w][id][b] * xv[u][i];
         }
       }
     }
@@ -168,15 +191,26 @@ tripD_bwd_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__
       ji_s[w][lane] = idx_ji_kj[base + lane];
     }
     wave_lds_sync();
-    for (int tt = grp; tt < n; tt += G) {
-      const int64_t ji = ji_s[w][tt];
+    for (int tt = grp; tt < n; tt += UNR * G) {
+      float gv[UNR][FPL];
 #pragma unroll
-      for (int i = 0; i < FPL; ++i) {
-        const int f = fl + i * WAVE;
-        if (f < F) {
-          const float g = ga[ji * F + f];
+      for (int u = 0; u < UNR; ++u) {
+        const int id = tt + u * G;
+        const int64_t ji = ji_s[w][id < n ? id : tt];
 #pragma unroll
-          for (int l = 0; l < ST; ++l) H[l][i] += Y_s[w][tt][l] * g;
+        for (int i = 0; i < FPL; ++i) {
+          const int f = fl + i * WAVE;
+          gv[u][i] = (f < F && id < n) ? ga[ji * F + f] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int id = tt + u * G;
+        if (id < n) {
+#pragma unroll
+          for (int i = 0; i < FPL; ++i)
+#pragma unroll
+            for (int l = 0; l < ST; ++l) H[l][i] += Y_s[w][id][l] * gv[u][i];
         }
       }
     }
@@ -185,7 +219,7 @@ tripD_bwd_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__
 #pragma unroll
   for (int l = 0; l < ST; ++l) butterfly<FPL>(H[l], LPR);
   // every group now holds the full sums; group 0 finishes the edge
-  const float* q = Q + e * S * B;
+  const float* q = Q + e;   // transposed table: element (l,b) of this edge at q[(l*B+b)*E]
   if (grp == 0) {
 #pragma unroll
     for (int i = 0; i < FPL; ++i) {
@@ -196,7 +230,7 @@ tripD_bwd_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__
           float D = 0.f;
 #pragma unroll
           for (int l = 0; l < ST; ++l)
-            if (l < S) D += q[l * B + b] * H[l][i];
+            if (l < S) D += q[(int64_t)(l * B + b) * E] * H[l][i];
           dx += W2[b * F + f] * D;
         }
         if (z) dx *= dsilu_f(z[e * F + f]);
@@ -364,8 +398,8 @@ int check_graph(gp_ctx* ctx, const gp_graph* g, bool need_ji, bool need_kj) {
 
 int gp_tripD_project_radial(gp_ctx* ctx, const float* rad, const float* W1, int64_t E, int S, int R, int B, float* Q) {
   if (E == 0) return GP_OK;
-  int64_t n = E * S * B;
-  project_radial_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(rad, W1, E, S, R, B, Q);
+  const size_t lds = (size_t)64 * (S * R + 1) * sizeof(float);
+  project_radial_kernel<<<(unsigned)((E + 63) / 64), 256, lds, ctx->stream>>>(rad, W1, E, S, R, B, Q);
   GP_LAUNCH_CHECK(ctx, "project_radial_kernel");
   return GP_OK;
 }
