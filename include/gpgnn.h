@@ -186,6 +186,34 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
                         void* scratch, size_t scratch_bytes);
 
 /* ------------------------------------------------------------------------------------------
+ * Interaction block, variant G (Sec. 3.4: a bilinear layer replaces the Hadamard product; the
+ * order of operations is chosen so that no tensor of size T x width is stored):
+ *   x = act(m W_ba) * (g (W_rbfS W_rbfB));  x = act(x W_down)            [E, int_emb]
+ *   Rad[e,l,c] = sum_n g[e,n] W_c[l,n,c];   y_t[c] = sum_l Y_l0(cos alpha_t) Rad[kj(t),l,c]
+ *   A_e[c,f]   = sum_{t in seg_ji(e)} y_t[c] x[kj(t),f];   z_e[o] = sum_{c,f} A_e[c,f] W_bil[c,f,o]
+ *   m' = (act(m W_skip) + act(z W_up)) / sqrt(2)
+ * basis->rbf is the Gaussian radial basis g[E, num_radial]; basis->rad is unused.
+ * Weights fp32, W[in,out]: W_ba[emb,emb], W_rbfS[R,emb_rbf], W_rbfB[emb_rbf,emb],
+ * W_down[emb,int_emb], W_c[S,R,emb_cbf], W_bil[emb_cbf,int_emb,emb_bil], W_up[emb_bil,emb],
+ * W_skip[emb,emb].  gp_block_workspace sizes `saved` and `scratch` for this variant too.
+ * Backward overwrites grad_m_in and every member of grad_w; if grad_rbf != NULL it also
+ * receives dL/dg [E, num_radial] (needed for forces).
+ */
+typedef struct {
+  float *W_ba, *W_rbfS, *W_rbfB, *W_down, *W_c, *W_bil, *W_up, *W_skip;
+} gp_weights_G;
+
+int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
+                       const gp_graph* graph, const gp_basis* basis,
+                       const float* m_in, float* m_out,
+                       void* saved, size_t saved_bytes, void* scratch, size_t scratch_bytes);
+int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
+                        const gp_graph* graph, const gp_basis* basis,
+                        const float* m_in, const void* saved, size_t saved_bytes,
+                        const float* grad_m_out, float* grad_m_in, gp_weights_G* grad_w,
+                        float* grad_rbf, void* scratch, size_t scratch_bytes);
+
+/* ------------------------------------------------------------------------------------------
  * The core TripletUpdate + TripletAggr kernels on their own (Sec. 3.3: Hadamard product of the
  * gathered message with the projected basis, summed over k into edge j->i).
  *   Streaming form: s[T,F] is a materialised per-triplet basis projection (ji-major),

@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = [
     "gp_edges_workspace", "gp_edges_count", "gp_edges_fill",
     "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill",
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
+    "gp_block_forward_G", "gp_block_backward_G",
     "gp_triplet_aggregate_fwd", "gp_triplet_aggregate_bwd", "gp_linear_forward",
 ]
 

@@ -1,0 +1,78 @@
+"""ctypes binding of the variant-G (bilinear) block entry points."""
+import ctypes as C
+
+import torch
+
+from . import binding as B
+
+__all__ = ["G_WEIGHT_NAMES", "gp_block_forward_G", "gp_block_backward_G", "StackG"]
+
+G_WEIGHT_NAMES = ("W_ba", "W_rbfS", "W_rbfB", "W_down", "W_c", "W_bil", "W_up", "W_skip")
+
+
+class _WeightsG(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in G_WEIGHT_NAMES]
+
+
+def _weights_G(w):
+    s = _WeightsG()
+    for n in G_WEIGHT_NAMES:
+        setattr(s, n, B._ptr(w[n]))
+    return s
+
+
+def gp_block_forward_G(ctx, dims, w, trip, basis, m_in, m_out, saved, scratch):
+    lib = B.load()
+    d, g, b, ws = B.Dims(dims), B.Graph(trip), B.Basis(basis), _weights_G(w)
+    ctx.check(lib.gp_block_forward_G(ctx._h, C.byref(d), C.byref(ws), C.byref(g), C.byref(b), B._ptr(m_in),
+                                     B._ptr(m_out), B._ptr(saved), C.c_size_t(saved.numel()), B._ptr(scratch),
+                                     C.c_size_t(scratch.numel())))
+    return m_out
+
+
+def gp_block_backward_G(ctx, dims, w, trip, basis, m_in, saved, grad_m_out, grad_m_in, grad_w, scratch, grad_rbf=None):
+    lib = B.load()
+    d, g, b = B.Dims(dims), B.Graph(trip), B.Basis(basis)
+    ws, gws = _weights_G(w), _weights_G(grad_w)
+    ctx.check(lib.gp_block_backward_G(ctx._h, C.byref(d), C.byref(ws), C.byref(g), C.byref(b), B._ptr(m_in),
+                                      B._ptr(saved), C.c_size_t(saved.numel()), B._ptr(grad_m_out), B._ptr(grad_m_in),
+                                      C.byref(gws), B._ptr(grad_rbf), B._ptr(scratch), C.c_size_t(scratch.numel())))
+    return grad_m_in, grad_w
+
+
+class StackG:
+    """n_blocks variant-G blocks sharing one graph and one basis (buffers allocated once)."""
+
+    def __init__(self, ctx, dims, weights_list, trip, basis):
+        self.ctx, self.dims, self.trip, self.basis = ctx, dims, trip, basis
+        self.w = weights_list
+        self.n_blocks = len(weights_list)
+        E, T = trip["n_edges"], trip["n_triplets"]
+        saved_b, scratch_b = B.gp_block_workspace(dims, E, T)
+        dev = ctx.device
+        self.saved = [torch.empty(max(saved_b, 8), dtype=torch.uint8, device=dev) for _ in range(self.n_blocks)]
+        self.scratch = torch.empty(max(scratch_b, 8), dtype=torch.uint8, device=dev)
+        self.m = [torch.empty((E, dims.emb), dtype=torch.float32, device=dev) for _ in range(self.n_blocks)]
+        self.g = [torch.empty((E, dims.emb), dtype=torch.float32, device=dev) for _ in range(2)]
+        self.grad_w = [{k: torch.empty_like(v) for k, v in w.items()} for w in weights_list]
+        self.m_in = None
+
+    def forward(self, m_in):
+        self.m_in = m_in
+        cur = m_in
+        for b in range(self.n_blocks):
+            gp_block_forward_G(self.ctx, self.dims, self.w[b], self.trip, self.basis, cur, self.m[b], self.saved[b],
+                               self.scratch)
+            cur = self.m[b]
+        return cur
+
+    def backward(self, grad_out, grad_rbf=None):
+        """grad_rbf, if given, is a list of per-block [E, R] buffers receiving dL/dg of each block."""
+        g = grad_out
+        for b in reversed(range(self.n_blocks)):
+            m_in = self.m_in if b == 0 else self.m[b - 1]
+            out = self.g[b % 2]
+            gp_block_backward_G(self.ctx, self.dims, self.w[b], self.trip, self.basis, m_in, self.saved[b], g, out,
+                                self.grad_w[b], self.scratch, None if grad_rbf is None else grad_rbf[b])
+            g = out
+        return g, self.grad_w

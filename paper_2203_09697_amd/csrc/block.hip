@@ -155,6 +155,11 @@ int gp_block_workspace(const gp_dims* dims, int64_t n_edges, int64_t n_triplets,
     *scratch_bytes = carve_scratch_D(nullptr, dims, n_edges, &sc);
     return GP_OK;
   }
+  if (dims->variant == GP_VARIANT_G) {
+    *saved_bytes = gp_block_G_saved_bytes(dims, n_edges);
+    *scratch_bytes = gp_block_G_scratch_bytes(dims, n_edges);
+    return GP_OK;
+  }
   return GP_UNSUPPORTED_DIMS;
 }
 

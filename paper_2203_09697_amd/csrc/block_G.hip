@@ -1,0 +1,231 @@
+// Interaction block, variant G (paper Sec. 3.4: bilinear layer in place of the Hadamard product,
+// operations ordered so that nothing of size T x width is stored), forward and backward.
+//
+//   x    = act(m W_ba) * (g (W_rbfS W_rbfB));  x = act(x W_down)                [E, F]
+//   Rad  = g . W_c                                                             [E, S, C]
+//   y_t  = sum_l Y_l0(cos alpha_t) Rad[kj(t), l, :]                             [T, C]  (never stored)
+//   A_e  = sum_{t in seg(e)} y_t (x) x[kj(t)]                                   [E, C, F]
+//   z    = A . W_bil                                                           [E, O]
+//   m'   = (act(m W_skip) + act(z W_up)) / sqrt(2)
+//
+// Backward: with H[e',l,o] = sum_{t: kj(t)=e'} Y_l(t) dz[ji(t),o] (one pass over the kj-major
+// triplet view), G[e',c,o] = sum_l Rad[e',l,c] H[e',l,o] gives dx = G . W_bil^T, and
+// V[e',c,o] = sum_f W_bil[c,f,o] x[e',f] gives dRad[e',l,c] = sum_o V[e',c,o] H[e',l,o].
+#include <stdarg.h>
+
+#include <algorithm>
+
+#include "gemm.h"
+#include "triplet.h"
+
+namespace {
+
+constexpr float INV_SQRT2 = 0.70710678118654752440f;
+
+struct saved_G {
+  float *z_ba, *gate, *xg, *z_dn, *x, *Radt, *A, *z, *z_up, *z_skip, *Wrbf, *WcT;
+};
+
+size_t carve_saved_G(void* p, const gp_dims* d, int64_t E, saved_G* s) {
+  gp_carver c(p);
+  const size_t H = d->emb, F = d->int_emb, C = d->emb_cbf, O = d->emb_bil, S = d->num_spherical, R = d->num_radial;
+  s->z_ba = c.take<float>(E * H);
+  s->gate = c.take<float>(E * H);
+  s->xg = c.take<float>(E * H);
+  s->z_dn = c.take<float>(E * F);
+  s->x = c.take<float>(E * F);
+  s->Radt = c.take<float>(S * C * E);
+  s->A = c.take<float>(E * C * F);
+  s->z = c.take<float>(E * O);
+  s->z_up = c.take<float>(E * H);
+  s->z_skip = c.take<float>(E * H);
+  s->Wrbf = c.take<float>(R * H);
+  s->WcT = c.take<float>(S * C * R);
+  return c.off;
+}
+
+struct scratch_G {
+  float* eh[4];                  // [E, H]
+  float *dz, *Hd, *Gm, *V, *dRad, *dzdn;
+  float *WbilP, *WbilV, *dWrbf, *dWcP;
+  float* part;
+  size_t part_bytes;
+};
+
+size_t part_bytes_G(const gp_dims* d, int64_t E) {
+  const int H = d->emb, F = d->int_emb, C = d->emb_cbf, O = d->emb_bil, S = d->num_spherical, R = d->num_radial;
+  size_t m = gp_gemm_tn_scratch(E, H, H);
+  m = std::max(m, gp_gemm_tn_scratch(E, O, H));
+  m = std::max(m, gp_gemm_tn_scratch(E, C * F, O));
+  m = std::max(m, gp_gemm_tn_scratch(E, R, S * C));
+  m = std::max(m, gp_gemm_tn_scratch(E, H, F));
+  m = std::max(m, gp_gemm_tn_scratch(E, R, H));
+  m = std::max(m, gp_gemm_tn_scratch(R, d->emb_rbf, H));
+  return m;
+}
+
+size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, scratch_G* s) {
+  gp_carver c(p);
+  const size_t H = d->emb, F = d->int_emb, C = d->emb_cbf, O = d->emb_bil, S = d->num_spherical, R = d->num_radial;
+  for (int i = 0; i < 4; ++i) s->eh[i] = c.take<float>(E * H);
+  s->dz = c.take<float>(E * O);
+  s->Hd = c.take<float>(E * S * O);
+  s->Gm = c.take<float>(E * C * O);
+  s->V = c.take<float>(E * C * O);
+  s->dRad = c.take<float>(E * S * C);
+  s->dzdn = c.take<float>(E * F);
+  s->WbilP = c.take<float>(C * O * F);
+  s->WbilV = c.take<float>(F * C * O);
+  s->dWrbf = c.take<float>(R * H);
+  s->dWcP = c.take<float>(R * S * C);
+  s->part_bytes = part_bytes_G(d, E);
+  s->part = (float*)c.take<char>(s->part_bytes);
+  return c.off;
+}
+
+int check_dims_G(gp_ctx* ctx, const gp_dims* d) {
+  GP_REQUIRE(ctx, d, "dims is NULL");
+  if (d->variant != GP_VARIANT_G) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "variant %d is not the bilinear block", d->variant);
+  if (d->emb < 1 || d->emb > 4096 || d->int_emb < 1 || d->int_emb > 256 || d->emb_cbf < 1 || d->emb_cbf > 16 ||
+      d->emb_bil < 1 || d->emb_bil > 128 || d->emb_rbf < 1 || d->emb_rbf > 256 || d->num_spherical < 1 ||
+      d->num_spherical > 8 || d->num_radial < 2 || d->num_radial > 1024)
+    return gp_fail(ctx, GP_UNSUPPORTED_DIMS,
+                   "variant G supports emb<=4096, emb_trip<=256, emb_cbf<=16, emb_bil<=128, emb_rbf<=256, "
+                   "num_spherical<=8, num_radial<=1024 (got %d,%d,%d,%d,%d,%d,%d)", d->emb, d->int_emb, d->emb_cbf,
+                   d->emb_bil, d->emb_rbf, d->num_spherical, d->num_radial);
+  return GP_OK;
+}
+
+int check_weights_G(gp_ctx* ctx, const gp_weights_G* w, const char* what) {
+  GP_REQUIRE(ctx, w, "%s is NULL", what);
+  GP_REQUIRE(ctx, w->W_ba && w->W_rbfS && w->W_rbfB && w->W_down && w->W_c && w->W_bil && w->W_up && w->W_skip,
+             "%s has a NULL member", what);
+  return GP_OK;
+}
+
+}  // namespace
+
+size_t gp_block_G_saved_bytes(const gp_dims* d, int64_t E) {
+  saved_G s;
+  return carve_saved_G(nullptr, d, E, &s);
+}
+size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E) {
+  scratch_G s;
+  return carve_scratch_G(nullptr, d, E, &s);
+}
+
+extern "C" {
+
+int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
+                       const gp_basis* basis, const float* m_in, float* m_out, void* saved, size_t saved_bytes,
+                       void* scratch, size_t scratch_bytes) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_TRY(check_dims_G(ctx, dims));
+  GP_TRY(check_weights_G(ctx, w, "weights"));
+  GP_REQUIRE(ctx, graph && basis, "gp_block_forward_G: graph/basis is NULL");
+  const int64_t E = graph->n_edges;
+  GP_REQUIRE(ctx, E >= 0 && graph->n_triplets >= 0, "gp_block_forward_G: negative size");
+  if (E == 0) return GP_OK;
+  GP_REQUIRE(ctx, m_in && m_out && saved && scratch, "gp_block_forward_G: NULL pointer");
+  GP_REQUIRE(ctx, basis->rbf && (graph->n_triplets == 0 || basis->cos_alpha), "gp_block_forward_G: basis arrays missing");
+  saved_G s;
+  scratch_G sc;
+  if (saved_bytes < carve_saved_G(saved, dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: saved buffer too small");
+  if (scratch_bytes < carve_scratch_G(scratch, dims, E, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: scratch too small");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  const int H = dims->emb, F = dims->int_emb, C = dims->emb_cbf, O = dims->emb_bil, S = dims->num_spherical,
+            R = dims->num_radial, RB = dims->emb_rbf;
+  const float* g = basis->rbf;
+  gp_epilogue e;
+
+  e = gp_epilogue(); e.out = s.Wrbf;
+  GP_TRY(gp_gemm_nn(ctx, w->W_rbfS, w->W_rbfB, R, H, RB, e));                       // W_rbf = W_rbfS W_rbfB
+  e = gp_epilogue(); e.out = s.gate;
+  GP_TRY(gp_gemm_nn(ctx, g, s.Wrbf, E, H, R, e));                                   // gate
+  e = gp_epilogue(); e.save_pre = s.z_ba; e.act = 1; e.mul = s.gate; e.out = s.xg;
+  GP_TRY(gp_gemm_nn(ctx, m_in, w->W_ba, E, H, H, e));                               // xg
+  e = gp_epilogue(); e.save_pre = s.z_dn; e.act = 1; e.out = s.x;
+  GP_TRY(gp_gemm_nn(ctx, s.xg, w->W_down, E, F, H, e));                             // x
+  GP_TRY(gp_permute3(ctx, w->W_c, S, R, C, 0, 2, 1, s.WcT));                        // WcT[(l,c), n]
+  e = gp_epilogue(); e.out = s.Radt;
+  GP_TRY(gp_gemm_nt(ctx, s.WcT, g, S * C, (int)E, R, e));                           // Radt[(l,c), e]
+  GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
+  e = gp_epilogue(); e.out = s.z;
+  GP_TRY(gp_gemm_nn(ctx, s.A, w->W_bil, E, O, C * F, e));                           // z
+  float* t_skip = sc.eh[0];
+  e = gp_epilogue(); e.save_pre = s.z_skip; e.act = 1; e.out = t_skip;
+  GP_TRY(gp_gemm_nn(ctx, m_in, w->W_skip, E, H, H, e));
+  e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = INV_SQRT2; e.out = m_out;
+  GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
+  return GP_OK;
+}
+
+int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
+                        const gp_basis* basis, const float* m_in, const void* saved, size_t saved_bytes,
+                        const float* grad_m_out, float* grad_m_in, gp_weights_G* gw, float* grad_rbf,
+                        void* scratch, size_t scratch_bytes) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_TRY(check_dims_G(ctx, dims));
+  GP_TRY(check_weights_G(ctx, w, "weights"));
+  GP_TRY(check_weights_G(ctx, gw, "grad_w"));
+  GP_REQUIRE(ctx, graph && basis, "gp_block_backward_G: graph/basis is NULL");
+  const int64_t E = graph->n_edges;
+  GP_REQUIRE(ctx, E > 0 && graph->n_triplets >= 0, "gp_block_backward_G: empty edge list");
+  GP_REQUIRE(ctx, m_in && grad_m_out && grad_m_in && saved && scratch, "gp_block_backward_G: NULL pointer");
+  GP_REQUIRE(ctx, basis->rbf && (graph->n_triplets == 0 || basis->cos_alpha_kj), "gp_block_backward_G: basis arrays missing");
+  saved_G s;
+  scratch_G sc;
+  if (saved_bytes < carve_saved_G(const_cast<void*>(saved), dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: saved buffer too small");
+  if (scratch_bytes < carve_scratch_G(scratch, dims, E, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: scratch too small");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  const int H = dims->emb, F = dims->int_emb, C = dims->emb_cbf, O = dims->emb_bil, S = dims->num_spherical,
+            R = dims->num_radial, RB = dims->emb_rbf;
+  const int64_t EH = E * H;
+  const float* g = basis->rbf;
+  float *d_up = sc.eh[0], *d_skip = sc.eh[1], *dxg = sc.eh[2], *dgate = sc.eh[3];
+  gp_epilogue e;
+
+  GP_TRY(gp_ew_dsilu2(ctx, grad_m_out, INV_SQRT2, s.z_up, s.z_skip, d_up, d_skip, EH));
+  GP_TRY(gp_gemm_tn(ctx, s.z, d_up, E, O, H, gw->W_up, nullptr, sc.part, sc.part_bytes));
+  e = gp_epilogue(); e.out = sc.dz;
+  GP_TRY(gp_gemm_nt(ctx, d_up, w->W_up, E, O, H, e));                               // dz
+  GP_TRY(gp_gemm_tn(ctx, m_in, d_skip, E, H, H, gw->W_skip, nullptr, sc.part, sc.part_bytes));
+  e = gp_epilogue(); e.out = grad_m_in;
+  GP_TRY(gp_gemm_nt(ctx, d_skip, w->W_skip, E, H, H, e));                           // dm (skip path)
+  GP_TRY(gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part, sc.part_bytes));
+  // one pass over the triplets (kj-major): H[e', l, o]
+  GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, nullptr, nullptr, nullptr, sc.dz, nullptr, O, S, 1,
+                           sc.Hd, nullptr));
+  GP_TRY(gp_tripG_edge_G(ctx, s.Radt, sc.Hd, E, S, C, O, sc.Gm));                   // G[e', (c,o)]
+  GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                   // [(c,o), f]
+  e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
+  GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e));                         // dz_dn
+  GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));                   // [f, (c,o)]
+  e = gp_epilogue(); e.out = sc.V;
+  GP_TRY(gp_gemm_nn(ctx, s.x, sc.WbilV, E, C * O, F, e));                           // V[e', (c,o)]
+  GP_TRY(gp_tripG_edge_dRad(ctx, sc.V, sc.Hd, E, S, C, O, sc.dRad));                // dRad[e', (l,c)]
+  GP_TRY(gp_gemm_tn(ctx, g, sc.dRad, E, R, S * C, sc.dWcP, nullptr, sc.part, sc.part_bytes));   // [n, (l,c)]
+  GP_TRY(gp_permute3(ctx, sc.dWcP, R, S, C, 1, 0, 2, gw->W_c));                     // -> [l, n, c]
+  GP_TRY(gp_gemm_tn(ctx, s.xg, sc.dzdn, E, H, F, gw->W_down, nullptr, sc.part, sc.part_bytes));
+  e = gp_epilogue(); e.out = dxg;
+  GP_TRY(gp_gemm_nt(ctx, sc.dzdn, w->W_down, E, H, F, e));                          // dxg
+  float* dz_ba = d_up;   // d_up is no longer needed
+  GP_TRY(gp_ew_gate_bwd(ctx, dxg, s.z_ba, s.gate, dz_ba, dgate, EH));
+  GP_TRY(gp_gemm_tn(ctx, g, dgate, E, R, H, sc.dWrbf, nullptr, sc.part, sc.part_bytes));
+  e = gp_epilogue(); e.out = gw->W_rbfS;
+  GP_TRY(gp_gemm_nt(ctx, sc.dWrbf, w->W_rbfB, R, RB, H, e));
+  GP_TRY(gp_gemm_tn(ctx, w->W_rbfS, sc.dWrbf, R, RB, H, gw->W_rbfB, nullptr, sc.part, sc.part_bytes));
+  GP_TRY(gp_gemm_tn(ctx, m_in, dz_ba, E, H, H, gw->W_ba, nullptr, sc.part, sc.part_bytes));
+  e = gp_epilogue(); e.add_post = grad_m_in; e.out = grad_m_in;
+  GP_TRY(gp_gemm_nt(ctx, dz_ba, w->W_ba, E, H, H, e));                              // dm += ba path
+  if (grad_rbf) {
+    // dL/dg = dgate W_rbf^T + dRad . W_c  (both paths through the Gaussian basis)
+    e = gp_epilogue(); e.out = grad_rbf;
+    GP_TRY(gp_gemm_nt(ctx, dgate, s.Wrbf, E, R, H, e));
+    e = gp_epilogue(); e.add_post = grad_rbf; e.out = grad_rbf;
+    GP_TRY(gp_gemm_nn(ctx, sc.dRad, s.WcT, E, R, S * C, e));
+  }
+  return GP_OK;
+}
+
+}  // extern "C"

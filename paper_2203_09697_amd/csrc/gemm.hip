@@ -102,34 +102,43 @@ __device__ __forceinline__ int xcd_remap(int bid, int n) {
   return x * q + (x < r ? x : r) + i;
 }
 
+// Operand loaders.  A fetch only ISSUES global loads (addresses are clamped into the matrix, so
+// no branch surrounds a load and nothing waits on the data); the out-of-range elements are
+// zeroed later, in store(), from a bit mask.  That keeps the loads of the next K-slab in flight
+// while the current slab is multiplied.  VEC: 16-byte loads are legal (extent % 4 == 0, aligned).
+
 // Source has the contraction index contiguous: tile of X rows by BK k's, stored transposed.
-template <int X>
+template <int X, bool VEC>
 struct loader_kcontig {
   static constexpr int KV = BK / 4;               // 16-byte vectors per row
   static constexpr int TOTAL = X * KV;
   static constexpr int NV = (TOTAL + THREADS - 1) / THREADS;
   static constexpr int LD = X + 1;                // odd stride: transposed stores hit distinct banks
   f32x4 r[NV];
+  uint32_t mask;
   __device__ __forceinline__ void fetch(const float* __restrict__ src, int64_t ld, int64_t row0,
-                                        int64_t n_rows, int64_t k0, int64_t k_end, int vec) {
+                                        int64_t n_rows, int64_t k0, int64_t k_end) {
+    mask = 0;
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = threadIdx.x + it * THREADS;
       const int row = idx / KV, kq = (idx % KV) * 4;
-      const int64_t gr = (TOTAL % THREADS == 0 || idx < TOTAL) ? row0 + row : n_rows;
-      const int64_t gk = k0 + kq;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (gr < n_rows) {
-        const float* p = src + gr * ld + gk;
-        if (vec) {
-          if (gk < k_end) v = *reinterpret_cast<const f32x4*>(p);
-        } else {
+      const bool in_tile = (TOTAL % THREADS == 0) || idx < TOTAL;
+      const int64_t gr = row0 + row, gk = k0 + kq;
+      const bool row_ok = in_tile && gr < n_rows;
+      const float* p = src + (gr < n_rows ? gr : n_rows - 1) * ld;
+      if (VEC) {
+        const bool ok = row_ok && gk < k_end;
+        r[it] = ld4(p + (gk < k_end ? gk : k_end - 4));
+        mask |= (ok ? 0xFu : 0u) << (4 * it);
+      } else {
 #pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (gk + c < k_end) v[c] = p[c];
+        for (int c = 0; c < 4; ++c) {
+          const int64_t kc = gk + c;
+          r[it][c] = p[kc < k_end ? kc : k_end - 1];
+          mask |= ((row_ok && kc < k_end) ? 1u : 0u) << (4 * it + c);
         }
       }
-      r[it] = v;
     }
   }
   __device__ __forceinline__ void store(float* __restrict__ S) const {
@@ -139,37 +148,42 @@ struct loader_kcontig {
       const int row = idx / KV, kq = (idx % KV) * 4;
       if (TOTAL % THREADS != 0 && idx >= TOTAL) continue;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) S[(kq + c) * LD + row] = r[it][c];
+      for (int c = 0; c < 4; ++c) S[(kq + c) * LD + row] = ((mask >> (4 * it + c)) & 1u) ? r[it][c] : 0.f;
     }
   }
 };
 
 // Source has the tile's m/n index contiguous: BK rows by X columns, stored as is.
-template <int X>
+template <int X, bool VEC>
 struct loader_xcontig {
   static constexpr int TOTAL = X * BK / 4;
   static constexpr int NV = (TOTAL + THREADS - 1) / THREADS;
   static constexpr int LD = X + 4;
   f32x4 r[NV];
+  uint32_t mask;
   __device__ __forceinline__ void fetch(const float* __restrict__ src, int64_t ld, int64_t x0,
-                                        int64_t n_x, int64_t k0, int64_t k_end, int vec) {
+                                        int64_t n_x, int64_t k0, int64_t k_end) {
+    mask = 0;
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = threadIdx.x + it * THREADS;
       const int k = idx / (X / 4), xq = (idx % (X / 4)) * 4;
-      const int64_t gk = (TOTAL % THREADS == 0 || idx < TOTAL) ? k0 + k : k_end, gx = x0 + xq;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (gk < k_end) {
-        const float* p = src + gk * ld + gx;
-        if (vec) {
-          if (gx < n_x) v = *reinterpret_cast<const f32x4*>(p);
-        } else {
+      const bool in_tile = (TOTAL % THREADS == 0) || idx < TOTAL;
+      const int64_t gk = k0 + k, gx = x0 + xq;
+      const bool k_ok = in_tile && gk < k_end;
+      const float* p = src + (gk < k_end ? gk : k_end - 1) * ld;
+      if (VEC) {
+        const bool ok = k_ok && gx < n_x;
+        r[it] = ld4(p + (gx < n_x ? gx : n_x - 4));
+        mask |= (ok ? 0xFu : 0u) << (4 * it);
+      } else {
 #pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (gx + c < n_x) v[c] = p[c];
+        for (int c = 0; c < 4; ++c) {
+          const int64_t xc = gx + c;
+          r[it][c] = p[xc < n_x ? xc : n_x - 1];
+          mask |= ((k_ok && xc < n_x) ? 1u : 0u) << (4 * it + c);
         }
       }
-      r[it] = v;
     }
   }
   __device__ __forceinline__ void store(float* __restrict__ S) const {
@@ -178,19 +192,22 @@ struct loader_xcontig {
       const int idx = threadIdx.x + it * THREADS;
       const int k = idx / (X / 4), xq = (idx % (X / 4)) * 4;
       if (TOTAL % THREADS != 0 && idx >= TOTAL) continue;
-      *reinterpret_cast<f32x4*>(&S[k * LD + xq]) = r[it];
+      f32x4 v;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) v[c] = ((mask >> (4 * it + c)) & 1u) ? r[it][c] : 0.f;
+      *reinterpret_cast<f32x4*>(&S[k * LD + xq]) = v;
     }
   }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE, bool VEC>
 __global__ void __launch_bounds__(THREADS)
 gemm_f32_kernel(const gemm_args g) {
   static_assert(WAVES_M * WAVES_N == 4 || BM == 64, "four wavefronts per workgroup");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MB = WM / 32, NB = WN / 32;
-  using loadA = typename std::conditional<MODE != MODE_TN, loader_kcontig<BM>, loader_xcontig<BM>>::type;
-  using loadB = typename std::conditional<MODE == MODE_NT, loader_kcontig<BN>, loader_xcontig<BN>>::type;
+  using loadA = typename std::conditional<MODE != MODE_TN, loader_kcontig<BM, VEC>, loader_xcontig<BM, VEC>>::type;
+  using loadB = typename std::conditional<MODE == MODE_NT, loader_kcontig<BN, VEC>, loader_xcontig<BN, VEC>>::type;
   constexpr int LDA = loadA::LD, LDB = loadB::LD;
   extern __shared__ __attribute__((aligned(16))) float smem[];
   auto As = [&](int buf) -> float* { return smem + buf * (BK * LDA); };
@@ -224,8 +241,8 @@ gemm_f32_kernel(const gemm_args g) {
   loadA la;
   loadB lb;
   auto fetch = [&](int64_t k0) {
-    la.fetch(g.A, g.lda, m0, g.M, k0, k_end, g.vecA);
-    lb.fetch(g.B, g.ldb, n0, g.N, k0, k_end, g.vecB);
+    la.fetch(g.A, g.lda, m0, g.M, k0, k_end);
+    lb.fetch(g.B, g.ldb, n0, g.N, k0, k_end);
   };
 
   if (k_begin < k_end) {
@@ -242,18 +259,26 @@ gemm_f32_kernel(const gemm_args g) {
     if (more) fetch(k0 + BK);
     const float* __restrict__ Ac = As(cur);
     const float* __restrict__ Bc = Bs(cur);
+    // LDS operands for step kk+2 are requested before the MFMAs of step kk are issued
+    float a[2][MB], b[2][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) a[0][i] = Ac[kh * LDA + wm0 + i * 32 + l32];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) b[0][j] = Bc[kh * LDB + wn0 + j * 32 + l32];
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      float a[MB], b[NB];
+      const int cb = (kk >> 1) & 1;
+      if (kk + 2 < BK) {
 #pragma unroll
-      for (int i = 0; i < MB; ++i) a[i] = Ac[(kk + kh) * LDA + wm0 + i * 32 + l32];
+        for (int i = 0; i < MB; ++i) a[cb ^ 1][i] = Ac[(kk + 2 + kh) * LDA + wm0 + i * 32 + l32];
 #pragma unroll
-      for (int j = 0; j < NB; ++j) b[j] = Bc[(kk + kh) * LDB + wn0 + j * 32 + l32];
+        for (int j = 0; j < NB; ++j) b[cb ^ 1][j] = Bc[(kk + 2 + kh) * LDB + wn0 + j * 32 + l32];
+      }
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cb][i], b[cb][j], acc[i][j], 0, 0, 0);
     }
     if (MODE == MODE_TN && g.colsum_part && (slab % tiles_m) == tile_m && threadIdx.x < BN) {
 #pragma unroll
@@ -405,8 +430,8 @@ __global__ void ew_add3_kernel(const float* __restrict__ a, const float* __restr
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 inline int nblk(int64_t n) { return (int)((n + 255) / 256); }
 
-template <int BM, int BN, int WMS, int WNS, int MODE>
-int launch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
+template <int BM, int BN, int WMS, int WNS, int MODE, bool VEC>
+int launch_gemm_v(gp_ctx* ctx, gemm_args& g, int splits) {
   const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (tiles > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
   dim3 grid((unsigned)tiles, (unsigned)splits, 1);
@@ -415,20 +440,26 @@ int launch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
   const double mnk = (double)g.M * g.N * g.K;
   gp_prof_scope prof(ctx, name, 2.0 * mnk,
                      4.0 * ((double)g.M * g.K + (double)g.K * g.N + (double)g.M * g.N * (MODE == MODE_TN ? splits : 1)));
-  using loadA = typename std::conditional<MODE != MODE_TN, loader_kcontig<BM>, loader_xcontig<BM>>::type;
-  using loadB = typename std::conditional<MODE == MODE_NT, loader_kcontig<BN>, loader_xcontig<BN>>::type;
+  using loadA = typename std::conditional<MODE != MODE_TN, loader_kcontig<BM, VEC>, loader_xcontig<BM, VEC>>::type;
+  using loadB = typename std::conditional<MODE == MODE_NT, loader_kcontig<BN, VEC>, loader_xcontig<BN, VEC>>::type;
   constexpr size_t lds_main = sizeof(float) * NBUF * BK * (loadA::LD + loadB::LD);
   constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD;
   constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
   static bool attr_set = false;
   if (!attr_set) {
-    GP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f32_kernel<BM, BN, WMS, WNS, MODE>),
+    GP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f32_kernel<BM, BN, WMS, WNS, MODE, VEC>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  gemm_f32_kernel<BM, BN, WMS, WNS, MODE><<<grid, THREADS, lds, ctx->stream>>>(g);
+  gemm_f32_kernel<BM, BN, WMS, WNS, MODE, VEC><<<grid, THREADS, lds, ctx->stream>>>(g);
   GP_LAUNCH_CHECK(ctx, "gemm_f32_kernel");
   return GP_OK;
+}
+
+template <int BM, int BN, int WMS, int WNS, int MODE>
+int launch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
+  if (g.vecA && g.vecB) return launch_gemm_v<BM, BN, WMS, WNS, MODE, true>(ctx, g, splits);
+  return launch_gemm_v<BM, BN, WMS, WNS, MODE, false>(ctx, g, splits);
 }
 
 // tile shape by output width

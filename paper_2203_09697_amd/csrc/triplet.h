@@ -27,3 +27,24 @@ size_t gp_tripD_wgrad_scratch(int64_t E, int F, int S, int R, int B);
 int gp_tripD_weight_grads(gp_ctx* ctx, const float* grad_a, const float* Bacc, const float* rad, const float* grad_Q,
                           int64_t E, int F, int S, int R, int B, float* grad_W2, float* grad_W1,
                           float* part, size_t part_bytes);
+
+// workspace sizes of the variant-G block (block_G.hip)
+size_t gp_block_G_saved_bytes(const gp_dims* d, int64_t E);
+size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E);
+
+// ---- variant G (bilinear interaction, Sec. 3.4) ---------------------------------------------
+// The forward accumulator A[e,c,f] = sum_t y_t[c] x[kj(t),f], y_t[c] = sum_l Y_l(t) Rad[kj(t),l,c],
+// is gp_tripD_forward with W2 = NULL, B = emb_cbf and Q = the transposed radial table
+// Radt[(l*C+c)*E + e].  The backward pass needs only H[e',l,o] = sum_{t: kj(t)=e'} Y_l(t) dz[ji(t),o],
+// which is gp_tripD_backward with Q = NULL (grad_x receives H[E,S,O]); everything else per
+// source edge follows from H by the two small per-edge products below.
+
+// Gout[e, c*O + o] = sum_l Radt[(l*C+c)*E + e] * H[e, l, o]
+int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout);
+// dRad[e, l*C + c] = sum_o V[e, c*O + o] * H[e, l, o]
+int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad);
+// dst[a,b,c] = src element whose index along source dimension p0 is a, along p1 is b, along p2 is c
+// (src has dimensions n0 x n1 x n2; dst has n[p0] x n[p1] x n[p2]); for small weight tensors
+int gp_permute3(gp_ctx* ctx, const float* src, int n0, int n1, int n2, int p0, int p1, int p2, float* dst);
+// d1 = g * s * silu'(z1), d2 = g * s * silu'(z2)
+int gp_ew_dsilu2(gp_ctx* ctx, const float* g, float s, const float* z1, const float* z2, float* d1, float* d2, int64_t n);

@@ -149,10 +149,10 @@ tripD_fwd_kernel(const int32_t* __restrict__ seg, const int32_t* __restrict__ id
 #pragma unroll
         for (int b = 0; b < BT; ++b)
           if (b < B) {
-            s += W2[b * F + f] * acc[b][i];
+            if (W2) s += W2[b * F + f] * acc[b][i];
             Bacc[(e * B + b) * F + f] = acc[b][i];
           }
-        a[e * F + f] = s;
+        if (W2) a[e * F + f] = s;   // W2 == NULL: bilinear form, only the accumulator is wanted
       }
     }
   }
@@ -219,6 +219,19 @@ tripD_bwd_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__
 #pragma unroll
   for (int l = 0; l < ST; ++l) butterfly<FPL>(H[l], LPR);
   // every group now holds the full sums; group 0 finishes the edge
+  if (!Q) {
+    // H-only mode (bilinear variant): gx receives H[e, l, f]
+    if (grp == 0)
+#pragma unroll
+      for (int i = 0; i < FPL; ++i) {
+        const int f = fl + i * WAVE;
+        if (f < F)
+#pragma unroll
+          for (int l = 0; l < ST; ++l)
+            if (l < S) gx[(e * S + l) * F + f] = H[l][i];
+      }
+    return;
+  }
   const float* q = Q + e;   // transposed table: element (l,b) of this edge at q[(l*B+b)*E]
   if (grp == 0) {
 #pragma unroll
@@ -411,9 +424,9 @@ int gp_tripD_forward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, con
   if (E == 0) return GP_OK;
   if (F < 1 || F > 256 || S < 1 || S > ST || B < 1 || B > 16)
     return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "triplet D forward: int_emb=%d num_spherical=%d basis_emb=%d unsupported", F, S, B);
-  GP_REQUIRE(ctx, x && Q && W2 && a && Bacc && (g->n_triplets == 0 || cos_alpha), "triplet D forward: NULL pointer");
+  GP_REQUIRE(ctx, x && Q && Bacc && (!W2 || a) && (g->n_triplets == 0 || cos_alpha), "triplet forward: NULL pointer");
   const double Td = (double)g->n_triplets, Ed = (double)E;
-  gp_prof_scope prof(ctx, "tripD_fwd", Td * 2.0 * (S * B + B * F) + Ed * 2.0 * B * F,
+  gp_prof_scope prof(ctx, W2 ? "tripD_fwd" : "tripG_fwd", Td * 2.0 * (S * B + B * F) + Ed * 2.0 * B * F,
                      Td * 8.0 + Ed * 4.0 * (F + S * B + B * F + F) + Ed * 4.0);
 #define CALL_FWD(LPR, FPL)                                                                                       \
   do {                                                                                                           \
@@ -438,11 +451,11 @@ int gp_tripD_backward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj,
   if (E == 0) return GP_OK;
   if (F < 1 || F > 256 || S < 1 || S > ST || B < 1 || B > 16)
     return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "triplet D backward: int_emb=%d num_spherical=%d basis_emb=%d unsupported", F, S, B);
-  GP_REQUIRE(ctx, x && Q && W2 && grad_a && grad_x && grad_Q && (g->n_triplets == 0 || cos_alpha_kj),
-             "triplet D backward: NULL pointer");
+  GP_REQUIRE(ctx, grad_a && grad_x && (!Q || (x && W2 && grad_Q)) && (g->n_triplets == 0 || cos_alpha_kj),
+             "triplet backward: NULL pointer");
   const size_t dyn = (size_t)WPB * ST * (F + 1) * sizeof(float);
   const double Td = (double)g->n_triplets, Ed = (double)E;
-  gp_prof_scope prof(ctx, "tripD_bwd", Td * 2.0 * S * F + Ed * 2.0 * (S * B * F * 2 + B * F),
+  gp_prof_scope prof(ctx, Q ? "tripD_bwd" : "trip_bwd_H", Td * 2.0 * S * F + Ed * 2.0 * (S * B * F * 2 + B * F),
                      Td * 8.0 + Ed * 4.0 * (F * 4 + S * B * 2) + Ed * 4.0);
 #define CALL_BWD(LPR, FPL)                                                                      \
   tripD_bwd_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, dyn, ctx->stream>>>(                  \
@@ -525,5 +538,111 @@ extern "C" int gp_triplet_aggregate_bwd(gp_ctx* ctx, const gp_graph* graph, cons
   GP_DISPATCH_WIDTH(F, CALL_S);
 #undef CALL_S
   GP_LAUNCH_CHECK(ctx, "stream_bwd kernels");
+  return GP_OK;
+}
+
+// ================================================================== variant G per-edge pieces
+namespace {
+
+__global__ void __launch_bounds__(WPB* WAVE)
+edge_G_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64_t E, int S, int C, int O,
+              float* __restrict__ Gout) {
+  const int lane = threadIdx.x & 63;
+  const int64_t e = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (e >= E) return;
+  for (int o = lane; o < O; o += WAVE) {
+    float h[ST];
+#pragma unroll
+    for (int l = 0; l < ST; ++l) h[l] = (l < S) ? H[(e * S + l) * O + o] : 0.f;
+    for (int c = 0; c < C; ++c) {
+      float s = 0.f;
+#pragma unroll
+      for (int l = 0; l < ST; ++l)
+        if (l < S) s += Radt[(int64_t)(l * C + c) * E + e] * h[l];
+      Gout[(e * C + c) * O + o] = s;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(WPB* WAVE)
+edge_dRad_kernel(const float* __restrict__ V, const float* __restrict__ H, int64_t E, int S, int C, int O,
+                 float* __restrict__ dRad) {
+  extern __shared__ float dyn_s[];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t e = (int64_t)blockIdx.x * WPB + w;
+  if (e >= E) return;
+  const int LD = O + 1;
+  float* V_s = dyn_s + (size_t)w * (C + S) * LD;
+  float* H_s = V_s + (size_t)C * LD;
+  for (int i = lane; i < C * O; i += WAVE) V_s[(i / O) * LD + (i % O)] = V[e * C * O + i];
+  for (int i = lane; i < S * O; i += WAVE) H_s[(i / O) * LD + (i % O)] = H[e * S * O + i];
+  wave_lds_sync();
+  for (int idx = lane; idx < S * C; idx += WAVE) {
+    const int l = idx / C, c = idx % C;
+    float s = 0.f;
+    for (int o = 0; o < O; ++o) s += V_s[c * LD + o] * H_s[l * LD + o];
+    dRad[e * S * C + idx] = s;
+  }
+}
+
+__global__ void permute3_kernel(const float* __restrict__ src, int n0, int n1, int n2, int p0, int p1, int p2,
+                                float* __restrict__ dst) {
+  const int n[3] = {n0, n1, n2};
+  const int total = n0 * n1 * n2;
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int d2 = n[p2], d1 = n[p1];
+  const int c = i % d2, b = (i / d2) % d1, a = i / (d2 * d1);
+  int idx[3];
+  idx[p0] = a; idx[p1] = b; idx[p2] = c;
+  dst[i] = src[(idx[0] * n1 + idx[1]) * n2 + idx[2]];
+}
+
+__global__ void ew_dsilu2_kernel(const float* __restrict__ g, float s, const float* __restrict__ z1,
+                                 const float* __restrict__ z2, float* __restrict__ d1, float* __restrict__ d2,
+                                 int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float v = g[i] * s;
+  d1[i] = v * dsilu_f(z1[i]);
+  d2[i] = v * dsilu_f(z2[i]);
+}
+
+}  // namespace
+
+int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout) {
+  if (E == 0) return GP_OK;
+  GP_REQUIRE(ctx, Radt && H && Gout && S >= 1 && S <= ST && C >= 1 && O >= 1, "edge_G: bad arguments");
+  gp_prof_scope prof(ctx, "tripG_edge_G", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
+  edge_G_kernel<<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(Radt, H, E, S, C, O, Gout);
+  GP_LAUNCH_CHECK(ctx, "edge_G_kernel");
+  return GP_OK;
+}
+
+int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad) {
+  if (E == 0) return GP_OK;
+  GP_REQUIRE(ctx, V && H && dRad && S >= 1 && S <= ST && C >= 1 && O >= 1, "edge_dRad: bad arguments");
+  const size_t lds = (size_t)WPB * (C + S) * (O + 1) * sizeof(float);
+  if (lds > 64 * 1024) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "edge_dRad: (emb_cbf+num_spherical)*emb_bil too large");
+  gp_prof_scope prof(ctx, "tripG_edge_dRad", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
+  edge_dRad_kernel<<<seg_blocks(E), WPB * WAVE, lds, ctx->stream>>>(V, H, E, S, C, O, dRad);
+  GP_LAUNCH_CHECK(ctx, "edge_dRad_kernel");
+  return GP_OK;
+}
+
+int gp_permute3(gp_ctx* ctx, const float* src, int n0, int n1, int n2, int p0, int p1, int p2, float* dst) {
+  GP_REQUIRE(ctx, src && dst && n0 > 0 && n1 > 0 && n2 > 0, "permute3: bad arguments");
+  GP_REQUIRE(ctx, ((1 << p0) | (1 << p1) | (1 << p2)) == 7, "permute3: not a permutation");
+  const int total = n0 * n1 * n2;
+  permute3_kernel<<<(total + 255) / 256, 256, 0, ctx->stream>>>(src, n0, n1, n2, p0, p1, p2, dst);
+  GP_LAUNCH_CHECK(ctx, "permute3_kernel");
+  return GP_OK;
+}
+
+int gp_ew_dsilu2(gp_ctx* ctx, const float* g, float s, const float* z1, const float* z2, float* d1, float* d2,
+                 int64_t n) {
+  if (n == 0) return GP_OK;
+  ew_dsilu2_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(g, s, z1, z2, d1, d2, n);
+  GP_LAUNCH_CHECK(ctx, "ew_dsilu2_kernel");
   return GP_OK;
 }

@@ -53,6 +53,30 @@ def oracle_stack_D(g, ob, dims, W_list, m, gup):
     return out.detach().numpy(), gm, gW
 
 
+def oracle_basis_G(pos, g, dims):
+    pos64 = torch.tensor(pos, dtype=F64)
+    d, unit, ca = obasis.geometry(pos64, g["src"], g["dst"], g["idx_kj"], g["idx_ji"])
+    rbf = obasis.rbf_gauss(d, dims.cutoff, dims.num_radial, dims.envelope_p)
+    Y = obasis.y_l0(ca, dims.num_spherical)
+    return dict(d=d, unit=unit, cos_alpha=ca, rbf=rbf, Y=Y)
+
+
+def oracle_stack_G(g, ob, dims, W_list, m, gup, want_grad_rbf=False):
+    """Forward + gradients of L = sum(out * gup) w.r.t. m, every weight and (optionally) the radial basis."""
+    Wt = [{k: v.clone().requires_grad_(True) for k, v in t64(W).items()} for W in W_list]
+    mt = torch.tensor(m, dtype=F64, requires_grad=True)
+    rbf = ob["rbf"].detach().clone().requires_grad_(True)
+    out = oblock.stack_G(mt, rbf, ob["Y"], g["idx_kj"], g["idx_ji"], Wt)
+    leaves = [mt, rbf] + [W[k] for W in Wt for k in W]
+    grads = oblock.loss_and_grads(out, torch.tensor(gup, dtype=F64), leaves)
+    gm, grbf = grads[0].numpy(), grads[1].numpy()
+    gW, i = [], 2
+    for W in Wt:
+        gW.append({k: grads[i + j].numpy() for j, k in enumerate(W)})
+        i += len(W)
+    return out.detach().numpy(), gm, gW, grbf
+
+
 def to_dev(a, dtype, device="cuda:0"):
     return torch.as_tensor(np.ascontiguousarray(a), dtype=dtype).to(device)
 

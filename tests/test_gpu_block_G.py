@@ -1,0 +1,66 @@
+"""GPU parity: the variant-G (bilinear) interaction block, forward and backward, vs the fp64 oracle.
+
+Tolerance: relative L2 error <= 1e-4 per tensor for the fp32 path.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    return lib.Context(0)
+
+
+def _parity(lib, ctx, workload, seed, n_blocks, pos_gptr):
+    from paper_2203_09697_amd.binding_g import StackG
+    dims = workload.dims
+    pos, gptr = pos_gptr
+    ref = H.oracle_graph(pos, gptr, dims.cutoff, workload.max_neighbors)
+    e, t = lib.build_graph(ctx, H.to_dev(pos, torch.float32), H.to_dev(gptr, torch.int32), dims.cutoff,
+                           workload.max_neighbors)
+    assert np.array_equal(t["idx_kj"].cpu().numpy(), ref["idx_kj"])
+    E = len(ref["src"])
+    W_list = [synth.weights_G(dims, seed=200 + seed + b) for b in range(n_blocks)]
+    m, gup = synth.edge_embeddings(E, dims.emb, seed=seed + 7)
+    ob = H.oracle_basis_G(pos, ref, dims)
+    out_ref, gm_ref, gW_ref, grbf_ref = H.oracle_stack_G(ref, ob, dims, W_list, m, gup)
+    gb = lib.gp_basis_forward(ctx, dims, e, t)
+    assert H.rel_l2(gb["rbf"].cpu().numpy(), ob["rbf"].numpy()) < 1e-5
+    stack = StackG(ctx, dims, [lib.weights_to_device(W) for W in W_list], t, gb)
+    out = stack.forward(H.to_dev(m, torch.float32))
+    grbf = [torch.empty((E, dims.num_radial), dtype=torch.float32, device="cuda:0") for _ in range(n_blocks)]
+    gm, gW = stack.backward(H.to_dev(gup, torch.float32), grad_rbf=grbf)
+    torch.cuda.synchronize()
+    errs = {"m_out": H.rel_l2(out.cpu().numpy(), out_ref), "grad_m": H.rel_l2(gm.cpu().numpy(), gm_ref),
+            "grad_rbf": H.rel_l2(sum(x.cpu().numpy().astype(np.float64) for x in grbf), grbf_ref)}
+    for b in range(n_blocks):
+        for k in gW_ref[b]:
+            errs[f"block{b}.{k}"] = H.rel_l2(gW[b][k].cpu().numpy(), gW_ref[b][k])
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, bad
+    return errs
+
+
+def test_block_G_small_dims(lib, ctx):
+    w = synth.get_workload("cfg3", emb=32, int_emb=16, emb_rbf=4, emb_cbf=5, emb_bil=12, num_radial=9,
+                           num_spherical=4, cutoff=4.0, dtype="f32")
+    _parity(lib, ctx, w, 0, 2, synth.cube_positions(30, 6.0, 0.9, seed=1))
+
+
+def test_block_G_cfg3_shape_one_structure(lib, ctx):
+    # configuration-3 layer widths on one of its 8 structures (200 atoms, cap 50)
+    w = synth.get_workload("cfg3", dtype="f32")
+    _parity(lib, ctx, w, 1, 1, synth.slab_adsorbate_positions(1, 8, 5, 4, 40, seed=2))
+
+
+def test_block_G_cfg4_widths_small_graph(lib, ctx):
+    # configuration-4 layer widths (emb 1024, emb_trip 128) on a 60-atom box with long segments
+    w = synth.get_workload("cfg4", dtype="f32", cutoff=6.0)
+    _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3))
