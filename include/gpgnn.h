@@ -196,8 +196,10 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
  * Weights fp32, W[in,out]: W_ba[emb,emb], W_rbfS[R,emb_rbf], W_rbfB[emb_rbf,emb],
  * W_down[emb,int_emb], W_c[S,R,emb_cbf], W_bil[emb_cbf,int_emb,emb_bil], W_up[emb_bil,emb],
  * W_skip[emb,emb].  gp_block_workspace sizes `saved` and `scratch` for this variant too.
- * Backward overwrites grad_m_in and every member of grad_w; if grad_rbf != NULL it also
- * receives dL/dg [E, num_radial] (needed for forces).
+ * Backward overwrites grad_m_in and every member of grad_w.  For forces (Sec. 3.2) it can also
+ * return the gradient with respect to the basis: grad_rbf[E, num_radial] = dL/dg and
+ * grad_cos_kj[T] = dL/dcos(alpha) in kj-major order (either may be NULL); with
+ * accumulate_basis_grads != 0 they are added to (several blocks share one basis), else overwritten.
  */
 typedef struct {
   float *W_ba, *W_rbfS, *W_rbfB, *W_down, *W_c, *W_bil, *W_up, *W_skip;
@@ -211,7 +213,49 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
                         const gp_graph* graph, const gp_basis* basis,
                         const float* m_in, const void* saved, size_t saved_bytes,
                         const float* grad_m_out, float* grad_m_in, gp_weights_G* grad_w,
-                        float* grad_rbf, void* scratch, size_t scratch_bytes);
+                        float* grad_rbf, float* grad_cos_kj, int32_t accumulate_basis_grads,
+                        void* scratch, size_t scratch_bytes);
+
+/* ------------------------------------------------------------------------------------------
+ * Energy head (Sec. 3.3 output step: messages summed per target atom, then an MLP) and forces
+ * (Sec. 3.2, energy-centric: f = -dE/dx by back-propagation).
+ *   h_i = sum_{e: dst[e]=i} m_e;  E_i = w2 . act(h_i W1 + b1) + b2;  energy[g] = sum_{i in g} E_i
+ * W1[emb,hidden], b1[hidden], w2[hidden], b2[1]; energy[n_graphs] is a device array.
+ * gp_energy_backward differentiates sum_g energy[g]: grad_m[E,emb] (overwritten) and, if
+ * grad_w != NULL, the head's weight gradients.
+ */
+typedef struct {
+  float *W1, *b1, *w2, *b2;
+} gp_weights_head;
+
+int gp_energy_workspace(int32_t emb, int32_t hidden, int64_t n_atoms,
+                        size_t* saved_bytes /*host*/, size_t* scratch_bytes /*host*/);
+int gp_energy_forward(gp_ctx* ctx, int32_t emb, int32_t hidden, const gp_weights_head* w,
+                      const float* m, const int32_t* row_ptr, const int32_t* graph_ptr,
+                      int64_t n_atoms, int32_t n_graphs, float* energy,
+                      void* saved, size_t saved_bytes);
+int gp_energy_backward(gp_ctx* ctx, int32_t emb, int32_t hidden, const gp_weights_head* w,
+                       const int32_t* dst, int64_t n_atoms, int64_t n_edges,
+                       const void* saved, size_t saved_bytes, float* grad_m,
+                       gp_weights_head* grad_w, void* scratch, size_t scratch_bytes);
+
+/* Out-edge lists: out_list[out_ptr[j]..out_ptr[j+1]-1] are the ids of the edges whose source is
+ * atom j, ascending.  (The edge list itself is sorted by target.) */
+int gp_edges_by_source_workspace(int64_t n_atoms, int64_t n_edges, size_t* bytes /*host*/);
+int gp_edges_by_source(gp_ctx* ctx, const int32_t* src, int64_t n_atoms, int64_t n_edges,
+                       void* ws, size_t ws_bytes, int32_t* out_ptr, int32_t* out_list);
+
+/* forces[N,3] = -dL/dx given dL/dg (grad_rbf[E,R], Gaussian radial basis of variant G) and
+ * dL/dcos(alpha) (grad_cos_kj[T], kj-major), with the graph held fixed:
+ *   d d_e/dx_dst = u_e, d d_e/dx_src = -u_e;  cos(alpha_t) = -u_ji . u_kj, u_e = (x_dst-x_src)/d_e.
+ * No atomics: per-edge vector gradients are sorted-segment sums over the two triplet views,
+ * per-atom sums run over the in-edge rows and the out-edge lists. */
+int gp_forces_workspace(int64_t n_edges, int64_t n_triplets, size_t* bytes /*host*/);
+int gp_forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* graph,
+                              const int32_t* perm_kj, const int32_t* row_ptr,
+                              const int32_t* out_ptr, const int32_t* out_list, int64_t n_atoms,
+                              const float* dist, const float* unit, const float* grad_rbf,
+                              const float* grad_cos_kj, float* forces, void* ws, size_t ws_bytes);
 
 /* ------------------------------------------------------------------------------------------
  * The core TripletUpdate + TripletAggr kernels on their own (Sec. 3.3: Hadamard product of the

@@ -26,6 +26,8 @@ EXPORTED_SYMBOLS = [
     "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill",
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
     "gp_block_forward_G", "gp_block_backward_G",
+    "gp_energy_workspace", "gp_energy_forward", "gp_energy_backward",
+    "gp_edges_by_source_workspace", "gp_edges_by_source", "gp_forces_workspace", "gp_forces_from_basis_grad",
     "gp_triplet_aggregate_fwd", "gp_triplet_aggregate_bwd", "gp_linear_forward",
 ]
 

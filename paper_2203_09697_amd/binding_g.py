@@ -30,13 +30,15 @@ def gp_block_forward_G(ctx, dims, w, trip, basis, m_in, m_out, saved, scratch):
     return m_out
 
 
-def gp_block_backward_G(ctx, dims, w, trip, basis, m_in, saved, grad_m_out, grad_m_in, grad_w, scratch, grad_rbf=None):
+def gp_block_backward_G(ctx, dims, w, trip, basis, m_in, saved, grad_m_out, grad_m_in, grad_w, scratch, grad_rbf=None,
+                        grad_cos_kj=None, accumulate=False):
     lib = B.load()
     d, g, b = B.Dims(dims), B.Graph(trip), B.Basis(basis)
     ws, gws = _weights_G(w), _weights_G(grad_w)
     ctx.check(lib.gp_block_backward_G(ctx._h, C.byref(d), C.byref(ws), C.byref(g), C.byref(b), B._ptr(m_in),
                                       B._ptr(saved), C.c_size_t(saved.numel()), B._ptr(grad_m_out), B._ptr(grad_m_in),
-                                      C.byref(gws), B._ptr(grad_rbf), B._ptr(scratch), C.c_size_t(scratch.numel())))
+                                      C.byref(gws), B._ptr(grad_rbf), B._ptr(grad_cos_kj), C.c_int32(1 if accumulate else 0),
+                                      B._ptr(scratch), C.c_size_t(scratch.numel())))
     return grad_m_in, grad_w
 
 
@@ -66,13 +68,16 @@ class StackG:
             cur = self.m[b]
         return cur
 
-    def backward(self, grad_out, grad_rbf=None):
-        """grad_rbf, if given, is a list of per-block [E, R] buffers receiving dL/dg of each block."""
+    def backward(self, grad_out, grad_rbf=None, grad_cos_kj=None):
+        """grad_rbf [E,R] / grad_cos_kj [T], if given, receive the basis gradients summed over all blocks
+        (the first block processed overwrites, the others accumulate inside the library)."""
         g = grad_out
+        first = True
         for b in reversed(range(self.n_blocks)):
             m_in = self.m_in if b == 0 else self.m[b - 1]
             out = self.g[b % 2]
             gp_block_backward_G(self.ctx, self.dims, self.w[b], self.trip, self.basis, m_in, self.saved[b], g, out,
-                                self.grad_w[b], self.scratch, None if grad_rbf is None else grad_rbf[b])
+                                self.grad_w[b], self.scratch, grad_rbf, grad_cos_kj, accumulate=not first)
             g = out
+            first = False
         return g, self.grad_w

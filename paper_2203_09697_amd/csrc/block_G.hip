@@ -46,7 +46,7 @@ size_t carve_saved_G(void* p, const gp_dims* d, int64_t E, saved_G* s) {
 
 struct scratch_G {
   float* eh[4];                  // [E, H]
-  float *dz, *Hd, *Gm, *V, *dRad, *dzdn;
+  float *dz, *Hd, *Gm, *V, *dRad, *dzdn, *U;
   float *WbilP, *WbilV, *dWrbf, *dWcP;
   float* part;
   size_t part_bytes;
@@ -74,6 +74,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, scratch_G* s) {
   s->V = c.take<float>(E * C * O);
   s->dRad = c.take<float>(E * S * C);
   s->dzdn = c.take<float>(E * F);
+  s->U = c.take<float>(E * S * O);
   s->WbilP = c.take<float>(C * O * F);
   s->WbilV = c.take<float>(F * C * O);
   s->dWrbf = c.take<float>(R * H);
@@ -163,7 +164,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
 int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
                         const gp_basis* basis, const float* m_in, const void* saved, size_t saved_bytes,
                         const float* grad_m_out, float* grad_m_in, gp_weights_G* gw, float* grad_rbf,
-                        void* scratch, size_t scratch_bytes) {
+                        float* grad_cos_kj, int32_t accumulate_basis_grads, void* scratch, size_t scratch_bytes) {
   if (!ctx) return GP_BAD_ARG;
   GP_TRY(check_dims_G(ctx, dims));
   GP_TRY(check_weights_G(ctx, w, "weights"));
@@ -204,6 +205,10 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   e = gp_epilogue(); e.out = sc.V;
   GP_TRY(gp_gemm_nn(ctx, s.x, sc.WbilV, E, C * O, F, e));                           // V[e', (c,o)]
   GP_TRY(gp_tripG_edge_dRad(ctx, sc.V, sc.Hd, E, S, C, O, sc.dRad));                // dRad[e', (l,c)]
+  if (grad_cos_kj && graph->n_triplets > 0) {
+    GP_TRY(gp_tripG_edge_U(ctx, s.Radt, sc.V, E, S, C, O, sc.U));
+    GP_TRY(gp_tripG_grad_cos(ctx, graph, basis->cos_alpha_kj, sc.U, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj));
+  }
   GP_TRY(gp_gemm_tn(ctx, g, sc.dRad, E, R, S * C, sc.dWcP, nullptr, sc.part, sc.part_bytes));   // [n, (l,c)]
   GP_TRY(gp_permute3(ctx, sc.dWcP, R, S, C, 1, 0, 2, gw->W_c));                     // -> [l, n, c]
   GP_TRY(gp_gemm_tn(ctx, s.xg, sc.dzdn, E, H, F, gw->W_down, nullptr, sc.part, sc.part_bytes));
@@ -221,6 +226,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   if (grad_rbf) {
     // dL/dg = dgate W_rbf^T + dRad . W_c  (both paths through the Gaussian basis)
     e = gp_epilogue(); e.out = grad_rbf;
+    if (accumulate_basis_grads) e.add_post = grad_rbf;
     GP_TRY(gp_gemm_nt(ctx, dgate, s.Wrbf, E, R, H, e));
     e = gp_epilogue(); e.add_post = grad_rbf; e.out = grad_rbf;
     GP_TRY(gp_gemm_nn(ctx, sc.dRad, s.WcT, E, R, S * C, e));

@@ -1,0 +1,391 @@
+// Energy head and forces (paper Sec. 3.3: per-atom sum of incoming messages followed by an MLP;
+// Sec. 3.2, energy-centric paradigm: forces are the negative gradient of the energy with respect
+// to the positions).  The position gradient is assembled without atomics: per-edge vector
+// gradients come from sorted-segment sums over the ji-major and kj-major triplet views, per-atom
+// sums from the in-edge rows and the out-edge lists.
+#include <math.h>
+#include <stdarg.h>
+
+#include <algorithm>
+
+#include "gemm.h"
+#include "triplet.h"
+
+namespace {
+
+constexpr int WPB = 4;
+
+// ------------------------------------------------------------------ out-edge lists (by source)
+__global__ void hist_kernel(const int32_t* __restrict__ key, int64_t n, int32_t* __restrict__ cnt) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) atomicAdd(&cnt[key[i]], 1);
+}
+// one workgroup: exclusive scan of cnt[n] -> ptr[n+1]
+__global__ void __launch_bounds__(1024) scan_small_kernel(const int32_t* __restrict__ cnt, int64_t n, int32_t* __restrict__ ptr) {
+  __shared__ int32_t wave_tot[16];
+  __shared__ int32_t carry;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid == 0) carry = 0;
+  __syncthreads();
+  for (int64_t base = 0; base < n; base += 1024) {
+    const int64_t i = base + tid;
+    const int v = i < n ? cnt[i] : 0;
+    int incl = v;
+    for (int o = 1; o < 64; o <<= 1) {
+      int u = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += u;
+    }
+    if (lane == 63) wave_tot[w] = incl;
+    __syncthreads();
+    int before = carry;
+    for (int k = 0; k < w; ++k) before += wave_tot[k];
+    if (i < n) ptr[i] = before + incl - v;
+    __syncthreads();
+    if (tid == 1023) carry = before + incl;
+    __syncthreads();
+  }
+  if (tid == 0) ptr[n] = carry;
+}
+__global__ void scatter_by_key_kernel(const int32_t* __restrict__ key, int64_t n, const int32_t* __restrict__ ptr,
+                                      int32_t* __restrict__ cursor, int32_t* __restrict__ tmp) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) tmp[ptr[key[i]] + atomicAdd(&cursor[key[i]], 1)] = (int32_t)i;
+}
+// order each list ascending by counting (lists are short); one wavefront per atom
+__global__ void __launch_bounds__(256)
+sort_lists_kernel(const int32_t* __restrict__ ptr, const int32_t* __restrict__ tmp, int64_t n_atoms, int32_t* __restrict__ out) {
+  const int64_t j = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (j >= n_atoms) return;
+  const int b = ptr[j], n = ptr[j + 1] - b;
+  for (int r = threadIdx.x & 63; r < n; r += 64) {
+    const int v = tmp[b + r];
+    int rank = 0;
+    for (int q = 0; q < n; ++q) rank += tmp[b + q] < v ? 1 : 0;
+    out[b + rank] = v;
+  }
+}
+
+// ------------------------------------------------------------------ energy head
+// h[i, f] = sum over the in-edge row of atom i of m[e, f]; one wavefront per atom
+__global__ void __launch_bounds__(256)
+atom_sum_kernel(const float* __restrict__ m, const int32_t* __restrict__ row_ptr, int64_t n_atoms, int H,
+                float* __restrict__ h) {
+  const int64_t i = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (i >= n_atoms) return;
+  const int e0 = row_ptr[i], e1 = row_ptr[i + 1];
+  for (int f = threadIdx.x & 63; f < H; f += 64) {
+    float s = 0.f;
+    for (int e = e0; e < e1; ++e) s += m[(int64_t)e * H + f];
+    h[i * H + f] = s;
+  }
+}
+// e_atom[i] = sum_k a1[i,k] w2[k] + b2; one wavefront per atom
+__global__ void __launch_bounds__(256)
+atom_energy_kernel(const float* __restrict__ a1, const float* __restrict__ w2, const float* __restrict__ b2,
+                   int64_t n_atoms, int K, float* __restrict__ e_atom) {
+  const int64_t i = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (i >= n_atoms) return;
+  float s = 0.f;
+  for (int k = threadIdx.x & 63; k < K; k += 64) s += a1[i * K + k] * w2[k];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) e_atom[i] = s + b2[0];
+}
+// energy[g] = sum of e_atom over the atoms of structure g (fixed order); one wavefront per structure
+__global__ void __launch_bounds__(256)
+graph_energy_kernel(const float* __restrict__ e_atom, const int32_t* __restrict__ graph_ptr, int n_graphs,
+                    float* __restrict__ energy) {
+  const int g = blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (g >= n_graphs) return;
+  float s = 0.f;
+  for (int i = graph_ptr[g] + (threadIdx.x & 63); i < graph_ptr[g + 1]; i += 64) s += e_atom[i];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) energy[g] = s;
+}
+// dz1[i,k] = w2[k] * silu'(z1[i,k])
+__global__ void head_dz_kernel(const float* __restrict__ z1, const float* __restrict__ w2, int64_t n, int K,
+                               float* __restrict__ dz1) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dz1[i] = w2[i % K] * dsilu_f(z1[i]);
+}
+// grad_m[e, :] = dh[dst[e], :]
+__global__ void gather_rows_kernel(const float* __restrict__ dh, const int32_t* __restrict__ dst, int64_t n_edges, int H,
+                                   float* __restrict__ gm) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_edges * H) return;
+  const int64_t e = i / H;
+  gm[i] = dh[(int64_t)dst[e] * H + (i % H)];
+}
+__global__ void fill_kernel(float* p, int64_t n, float v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ------------------------------------------------------------------ forces
+// grad_d[e] = sum_n grad_g[e,n] * d g_n / d d,  g_n(d) = u(d/c) exp(-((d/c - mu_n)/Delta)^2 / 2)
+__global__ void __launch_bounds__(256)
+grad_dist_gauss_kernel(const float* __restrict__ dist, const float* __restrict__ gg, int64_t n_edges, int R, int p,
+                       double cutoff, float* __restrict__ gd) {
+  const int64_t e = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (e >= n_edges) return;
+  const double x = (double)dist[e] / cutoff;
+  double xp1 = 1.0;                       // x^(p-1)
+  for (int k = 0; k < p - 1; ++k) xp1 *= x;
+  const double a = -0.5 * (p + 1) * (p + 2), b = (double)p * (p + 2), c = -0.5 * p * (p + 1);
+  const double u = 1.0 + xp1 * x * (a + x * (b + x * c));
+  const double du = xp1 * (p * a + x * ((p + 1) * b + x * (p + 2) * c));
+  const double inv_delta = (double)(R - 1);
+  double s = 0.0;
+  for (int n = threadIdx.x & 63; n < R; n += 64) {
+    const double t = (x - (double)n / (double)(R - 1)) * inv_delta;
+    const double ex = exp(-0.5 * t * t);
+    s += (double)gg[e * R + n] * ex * (du - u * t * inv_delta);
+  }
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if ((threadIdx.x & 63) == 0) gd[e] = (float)(s / cutoff);
+}
+// out[perm[q]] = in[q]
+__global__ void unpermute_kernel(const float* __restrict__ in, const int32_t* __restrict__ perm, int64_t n,
+                                 float* __restrict__ out) {
+  int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q < n) out[perm[q]] = in[q];
+}
+// gu[e, :] (+)= -sum_{t in seg(e)} gc[t] * unit[other[t], :]; one wavefront per edge
+__global__ void __launch_bounds__(256)
+edge_unit_grad_kernel(const int32_t* __restrict__ seg, const int32_t* __restrict__ other, const float* __restrict__ gc,
+                      const float* __restrict__ unit, int64_t n_edges, int accumulate, float* __restrict__ gu) {
+  const int64_t e = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (e >= n_edges) return;
+  float sx = 0.f, sy = 0.f, sz = 0.f;
+  for (int t = seg[e] + (threadIdx.x & 63); t < seg[e + 1]; t += 64) {
+    const float g = gc[t];
+    const float* u = unit + 3 * (int64_t)other[t];
+    sx -= g * u[0]; sy -= g * u[1]; sz -= g * u[2];
+  }
+  sx = wave_sum(sx); sy = wave_sum(sy); sz = wave_sum(sz);
+  if ((threadIdx.x & 63) == 0) {
+    float* o = gu + 3 * e;
+    if (accumulate) { o[0] += sx; o[1] += sy; o[2] += sz; }
+    else { o[0] = sx; o[1] = sy; o[2] = sz; }
+  }
+}
+// dv[e,:] = (gu - (gu.u) u) / d + gd * u   (gradient w.r.t. the edge vector x_dst - x_src)
+__global__ void edge_vec_grad_kernel(const float* __restrict__ gu, const float* __restrict__ gd,
+                                     const float* __restrict__ unit, const float* __restrict__ dist, int64_t n_edges,
+                                     float* __restrict__ dv) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_edges) return;
+  const float ux = unit[3 * e], uy = unit[3 * e + 1], uz = unit[3 * e + 2];
+  const float gx = gu[3 * e], gy = gu[3 * e + 1], gz = gu[3 * e + 2];
+  const float dot = gx * ux + gy * uy + gz * uz, inv = 1.0f / dist[e], g = gd[e];
+  dv[3 * e] = (gx - dot * ux) * inv + g * ux;
+  dv[3 * e + 1] = (gy - dot * uy) * inv + g * uy;
+  dv[3 * e + 2] = (gz - dot * uz) * inv + g * uz;
+}
+// forces[i] = -( sum_{e into i} dv[e] - sum_{e out of i} dv[e] ); one wavefront per atom
+__global__ void __launch_bounds__(256)
+atom_force_kernel(const float* __restrict__ dv, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
+                  const int32_t* __restrict__ out_list, int64_t n_atoms, float* __restrict__ forces) {
+  const int64_t i = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (i >= n_atoms) return;
+  float sx = 0.f, sy = 0.f, sz = 0.f;
+  for (int e = row_ptr[i] + (threadIdx.x & 63); e < row_ptr[i + 1]; e += 64) {
+    sx += dv[3 * (int64_t)e]; sy += dv[3 * (int64_t)e + 1]; sz += dv[3 * (int64_t)e + 2];
+  }
+  for (int r = out_ptr[i] + (threadIdx.x & 63); r < out_ptr[i + 1]; r += 64) {
+    const int64_t e = out_list[r];
+    sx -= dv[3 * e]; sy -= dv[3 * e + 1]; sz -= dv[3 * e + 2];
+  }
+  sx = wave_sum(sx); sy = wave_sum(sy); sz = wave_sum(sz);
+  if ((threadIdx.x & 63) == 0) {
+    forces[3 * i] = -sx; forces[3 * i + 1] = -sy; forces[3 * i + 2] = -sz;
+  }
+}
+
+inline unsigned nblk(int64_t n) { return (unsigned)((n + 255) / 256); }
+inline unsigned wblk(int64_t n) { return (unsigned)((n + WPB - 1) / WPB); }
+
+struct head_saved {
+  float *h, *z1, *a1, *e_atom;
+};
+size_t carve_head_saved(void* p, int64_t N, int H, int K, head_saved* s) {
+  gp_carver c(p);
+  s->h = c.take<float>(N * H);
+  s->z1 = c.take<float>(N * K);
+  s->a1 = c.take<float>(N * K);
+  s->e_atom = c.take<float>(N);
+  return c.off;
+}
+struct head_scratch {
+  float *dz1, *dh, *part;
+  size_t part_bytes;
+};
+size_t carve_head_scratch(void* p, int64_t N, int H, int K, head_scratch* s) {
+  gp_carver c(p);
+  s->dz1 = c.take<float>(N * K);
+  s->dh = c.take<float>(N * H);
+  s->part_bytes = std::max(gp_gemm_tn_scratch(N, H, K), gp_colsum_scratch(N, K));
+  s->part = (float*)c.take<char>(s->part_bytes);
+  return c.off;
+}
+struct forces_ws {
+  float *gd, *gc_ji, *gu, *dv;
+};
+size_t carve_forces(void* p, int64_t E, int64_t T, forces_ws* w) {
+  gp_carver c(p);
+  w->gd = c.take<float>(E);
+  w->gc_ji = c.take<float>(T);
+  w->gu = c.take<float>(3 * E);
+  w->dv = c.take<float>(3 * E);
+  return c.off;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gp_edges_by_source_workspace(int64_t n_atoms, int64_t n_edges, size_t* bytes) {
+  if (!bytes || n_atoms < 0 || n_edges < 0) return GP_BAD_ARG;
+  *bytes = gp_align(sizeof(int32_t) * n_atoms) * 2 + gp_align(sizeof(int32_t) * n_edges);
+  return GP_OK;
+}
+
+int gp_edges_by_source(gp_ctx* ctx, const int32_t* src, int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes,
+                       int32_t* out_ptr, int32_t* out_list) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, n_atoms >= 0 && n_edges >= 0 && out_ptr, "gp_edges_by_source: bad arguments");
+  if (n_atoms > INT32_MAX - 1 || n_edges > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_edges_by_source: sizes exceed int32");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = ctx->stream;
+  if (n_atoms == 0 || n_edges == 0) {
+    GP_HIP(ctx, hipMemsetAsync(out_ptr, 0, sizeof(int32_t) * (n_atoms + 1), st));
+    return GP_OK;
+  }
+  GP_REQUIRE(ctx, src && out_list && ws, "gp_edges_by_source: NULL pointer");
+  size_t need;
+  gp_edges_by_source_workspace(n_atoms, n_edges, &need);
+  if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_edges_by_source: workspace %zu < %zu", ws_bytes, need);
+  gp_carver c(ws);
+  int32_t* cnt = c.take<int32_t>(n_atoms);
+  int32_t* cursor = c.take<int32_t>(n_atoms);
+  int32_t* tmp = c.take<int32_t>(n_edges);
+  GP_HIP(ctx, hipMemsetAsync(cnt, 0, sizeof(int32_t) * n_atoms, st));
+  GP_HIP(ctx, hipMemsetAsync(cursor, 0, sizeof(int32_t) * n_atoms, st));
+  hist_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, cnt);
+  scan_small_kernel<<<1, 1024, 0, st>>>(cnt, n_atoms, out_ptr);
+  scatter_by_key_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, out_ptr, cursor, tmp);
+  sort_lists_kernel<<<wblk(n_atoms), 256, 0, st>>>(out_ptr, tmp, n_atoms, out_list);
+  GP_LAUNCH_CHECK(ctx, "edges_by_source kernels");
+  return GP_OK;
+}
+
+int gp_energy_workspace(int32_t emb, int32_t hidden, int64_t n_atoms, size_t* saved_bytes, size_t* scratch_bytes) {
+  if (!saved_bytes || !scratch_bytes || emb < 1 || hidden < 1 || n_atoms < 0) return GP_BAD_ARG;
+  head_saved s;
+  head_scratch sc;
+  *saved_bytes = carve_head_saved(nullptr, n_atoms, emb, hidden, &s);
+  *scratch_bytes = carve_head_scratch(nullptr, n_atoms, emb, hidden, &sc);
+  return GP_OK;
+}
+
+int gp_energy_forward(gp_ctx* ctx, int32_t emb, int32_t hidden, const gp_weights_head* w, const float* m,
+                      const int32_t* row_ptr, const int32_t* graph_ptr, int64_t n_atoms, int32_t n_graphs,
+                      float* energy, void* saved, size_t saved_bytes) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, emb >= 1 && hidden >= 1 && n_atoms >= 0 && n_graphs >= 0, "gp_energy_forward: bad sizes");
+  GP_REQUIRE(ctx, w && w->W1 && w->b1 && w->w2 && w->b2, "gp_energy_forward: weights missing");
+  if (n_atoms == 0 || n_graphs == 0) return GP_OK;
+  GP_REQUIRE(ctx, m && row_ptr && graph_ptr && energy && saved, "gp_energy_forward: NULL pointer");
+  head_saved s;
+  if (saved_bytes < carve_head_saved(saved, n_atoms, emb, hidden, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_energy_forward: saved buffer too small");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = ctx->stream;
+  atom_sum_kernel<<<wblk(n_atoms), 256, 0, st>>>(m, row_ptr, n_atoms, emb, s.h);
+  GP_LAUNCH_CHECK(ctx, "atom_sum_kernel");
+  gp_epilogue e;
+  e.bias = w->b1; e.save_pre = s.z1; e.act = 1; e.out = s.a1;
+  GP_TRY(gp_gemm_nn(ctx, s.h, w->W1, n_atoms, hidden, emb, e));
+  atom_energy_kernel<<<wblk(n_atoms), 256, 0, st>>>(s.a1, w->w2, w->b2, n_atoms, hidden, s.e_atom);
+  graph_energy_kernel<<<wblk(n_graphs), 256, 0, st>>>(s.e_atom, graph_ptr, n_graphs, energy);
+  GP_LAUNCH_CHECK(ctx, "energy kernels");
+  return GP_OK;
+}
+
+int gp_energy_backward(gp_ctx* ctx, int32_t emb, int32_t hidden, const gp_weights_head* w, const int32_t* dst,
+                       int64_t n_atoms, int64_t n_edges, const void* saved, size_t saved_bytes, float* grad_m,
+                       gp_weights_head* grad_w, void* scratch, size_t scratch_bytes) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, emb >= 1 && hidden >= 1 && n_atoms > 0 && n_edges >= 0, "gp_energy_backward: bad sizes");
+  GP_REQUIRE(ctx, w && w->W1 && w->w2 && saved && scratch && (n_edges == 0 || (dst && grad_m)), "gp_energy_backward: NULL pointer");
+  head_saved s;
+  head_scratch sc;
+  if (saved_bytes < carve_head_saved(const_cast<void*>(saved), n_atoms, emb, hidden, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_energy_backward: saved buffer too small");
+  if (scratch_bytes < carve_head_scratch(scratch, n_atoms, emb, hidden, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_energy_backward: scratch too small");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = ctx->stream;
+  head_dz_kernel<<<nblk(n_atoms * hidden), 256, 0, st>>>(s.z1, w->w2, n_atoms * hidden, hidden, sc.dz1);
+  GP_LAUNCH_CHECK(ctx, "head_dz_kernel");
+  gp_epilogue e;
+  e.out = sc.dh;
+  GP_TRY(gp_gemm_nt(ctx, sc.dz1, w->W1, n_atoms, emb, hidden, e));
+  if (n_edges > 0) {
+    gather_rows_kernel<<<nblk(n_edges * emb), 256, 0, st>>>(sc.dh, dst, n_edges, emb, grad_m);
+    GP_LAUNCH_CHECK(ctx, "gather_rows_kernel");
+  }
+  if (grad_w) {
+    GP_REQUIRE(ctx, grad_w->W1 && grad_w->b1 && grad_w->w2 && grad_w->b2, "gp_energy_backward: grad_w has a NULL member");
+    GP_TRY(gp_gemm_tn(ctx, s.h, sc.dz1, n_atoms, emb, hidden, grad_w->W1, grad_w->b1, sc.part, sc.part_bytes));
+    GP_TRY(gp_colsum(ctx, s.a1, n_atoms, hidden, grad_w->w2, sc.part, sc.part_bytes));
+    fill_kernel<<<1, 64, 0, st>>>(grad_w->b2, 1, (float)n_atoms);
+    GP_LAUNCH_CHECK(ctx, "fill_kernel");
+  }
+  return GP_OK;
+}
+
+int gp_forces_workspace(int64_t n_edges, int64_t n_triplets, size_t* bytes) {
+  if (!bytes || n_edges < 0 || n_triplets < 0) return GP_BAD_ARG;
+  forces_ws w;
+  *bytes = carve_forces(nullptr, n_edges, n_triplets, &w);
+  return GP_OK;
+}
+
+int gp_forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* graph, const int32_t* perm_kj,
+                              const int32_t* row_ptr, const int32_t* out_ptr, const int32_t* out_list,
+                              int64_t n_atoms, const float* dist, const float* unit, const float* grad_rbf,
+                              const float* grad_cos_kj, float* forces, void* ws, size_t ws_bytes) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, dims && graph, "gp_forces_from_basis_grad: dims/graph is NULL");
+  if (dims->variant != GP_VARIANT_G)
+    return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "gp_forces_from_basis_grad: only the Gaussian radial basis (variant G) is implemented");
+  const int64_t E = graph->n_edges, T = graph->n_triplets;
+  GP_REQUIRE(ctx, n_atoms >= 0 && E >= 0 && T >= 0, "gp_forces_from_basis_grad: negative size");
+  if (n_atoms == 0) return GP_OK;
+  GP_REQUIRE(ctx, forces && row_ptr && out_ptr, "gp_forces_from_basis_grad: NULL pointer");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = ctx->stream;
+  if (E == 0) {
+    fill_kernel<<<nblk(3 * n_atoms), 256, 0, st>>>(forces, 3 * n_atoms, 0.f);
+    GP_LAUNCH_CHECK(ctx, "fill_kernel");
+    return GP_OK;
+  }
+  GP_REQUIRE(ctx, out_list && dist && unit && grad_rbf && ws, "gp_forces_from_basis_grad: NULL pointer");
+  GP_REQUIRE(ctx, T == 0 || (grad_cos_kj && perm_kj && graph->idx_kj && graph->seg_ptr_ji && graph->idx_ji_kj && graph->seg_ptr_kj),
+             "gp_forces_from_basis_grad: triplet arrays missing");
+  forces_ws w;
+  if (ws_bytes < carve_forces(ws, E, T, &w)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_forces_from_basis_grad: workspace too small");
+  grad_dist_gauss_kernel<<<wblk(E), 256, 0, st>>>(dist, grad_rbf, E, dims->num_radial, dims->envelope_p,
+                                                  (double)dims->cutoff, w.gd);
+  if (T > 0) {
+    unpermute_kernel<<<nblk(T), 256, 0, st>>>(grad_cos_kj, perm_kj, T, w.gc_ji);
+    // cos = -unit[ji].unit[kj]: d/d unit[ji] = -unit[kj] (ji-major walk), d/d unit[kj] = -unit[ji] (kj-major walk)
+    edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_ji, graph->idx_kj, w.gc_ji, unit, E, 0, w.gu);
+    edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_kj, graph->idx_ji_kj, grad_cos_kj, unit, E, 1, w.gu);
+  } else {
+    fill_kernel<<<nblk(3 * E), 256, 0, st>>>(w.gu, 3 * E, 0.f);
+  }
+  edge_vec_grad_kernel<<<nblk(E), 256, 0, st>>>(w.gu, w.gd, unit, dist, E, w.dv);
+  atom_force_kernel<<<wblk(n_atoms), 256, 0, st>>>(w.dv, row_ptr, out_ptr, out_list, n_atoms, forces);
+  GP_LAUNCH_CHECK(ctx, "force kernels");
+  return GP_OK;
+}
+
+}  // extern "C"
