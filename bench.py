@@ -3,7 +3,8 @@
 
 A step is one forward + backward pass of all blocks of the workload over one batch of
 synthetic structures (graph construction and basis evaluation happen once, before the timed
-region, and are reported separately).  Prints ONE JSON line.
+region, and are reported separately).  For the force workload (cfg5) a step is energy forward,
+backward and the force assembly.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -17,36 +18,60 @@ if ROOT not in sys.path:
 
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma_f32": (157.3, "TFLOP/s"), "mfma_bf16": (2500.0, "TFLOP/s"),
         "alu_f32": (78.6, "TFLOP/s")}
+ALU_KERNELS = ("tripD_fwd", "tripD_bwd", "tripG_fwd", "trip_bwd_H", "tripG_grad_cos", "tripG_edge")
+
+
+def sample_system(workload, seed):
+    """A bounded sample of the workload for the CPU oracle: fewer structures of the same recipe, or
+    (single-structure workloads) a smaller box at the same density and cutoff."""
+    import synth
+    args = list(workload.system_args)
+    if workload.system == "slab":
+        args[0] = max(1, args[0] // 2) if workload.dims.variant == "D" else 1
+        return synth.slab_adsorbate_positions(*args, seed=seed), "%d of %d structures" % (args[0], workload.system_args[0])
+    if workload.system == "box":
+        args[0] = 120
+        return synth.box_positions(*args, seed=seed), "%d-atom box at the same density and cutoff (workload: %d atoms)" % (
+            args[0], workload.system_args[0])
+    return synth.make_positions(workload, seed), "whole workload"
 
 
 def cpu_baseline(workload, seed):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
-    import numpy as np
     import torch
 
     import synth
+    from oracle import energy as oenergy
     from tests import helpers as H
 
     dims = workload.dims
-    n_struct = max(1, workload.system_args[0] // 2)
-    args = list(workload.system_args)
-    args[0] = n_struct
-    pos, gptr = synth.slab_adsorbate_positions(*args, seed=seed)
+    (pos, gptr), what = sample_system(workload, seed)
     g = H.oracle_graph(pos, gptr, dims.cutoff, workload.max_neighbors)
-    ob = H.oracle_basis_D(pos, g, dims)
-    W_list = [synth.weights_D(dims, seed=100 + b) for b in range(workload.n_blocks)]
-    m, gup = synth.edge_embeddings(len(g["src"]), dims.emb, seed=seed + 7)
+    E, T = len(g["src"]), len(g["idx_kj"])
+    m, gup = synth.edge_embeddings(E, dims.emb, seed=seed + 7)
+    if dims.variant == "D":
+        ob = H.oracle_basis_D(pos, g, dims)
+        W_list = [synth.weights_D(dims, seed=100 + b) for b in range(workload.n_blocks)]
+        run = lambda: H.oracle_stack_D(g, ob, dims, W_list, m, gup)
+    elif workload.head_hidden == 0:
+        ob = H.oracle_basis_G(pos, g, dims)
+        W_list = [synth.weights_G(dims, seed=100 + b) for b in range(workload.n_blocks)]
+        run = lambda: H.oracle_stack_G(g, ob, dims, W_list, m, gup)
+    else:
+        W_list = [H.t64(synth.weights_G(dims, seed=100 + b)) for b in range(workload.n_blocks)]
+        Wh = H.t64(synth.weights_head(dims.emb, workload.head_hidden, seed=99))
+        m64 = torch.tensor(m, dtype=torch.float64)
+        run = lambda: oenergy.forces(oenergy.energy_G, pos, g["src"], g["dst"], g["idx_kj"], g["idx_ji"], m64, W_list, Wh, dims)
     reps, dt = 0, 0.0
-    while reps < 2 or (dt < 10.0 and reps < 8):      # about 10-20 s of CPU work in total
+    while reps < 1 or (dt < 10.0 and reps < 8):      # about 10-30 s of CPU work in total
         t0 = time.perf_counter()
-        H.oracle_stack_D(g, ob, dims, W_list, m, gup)
+        run()
         dt += time.perf_counter() - t0
         reps += 1
-    T = len(g["idx_kj"])
     return {"value": T * workload.n_blocks * reps / dt, "unit": "triplets/s", "cores": torch.get_num_threads(),
             "kind": "oracle",
-            "sample": "%d of %d structures (%d edges, %d triplets), %d blocks fwd+bwd in fp64, %d passes, %.1f s"
-                      % (n_struct, workload.system_args[0], len(g["src"]), T, workload.n_blocks, reps, dt)}
+            "sample": "%s (%d edges, %d triplets), %d blocks fwd+bwd in fp64, %d passes, %.1f s"
+                      % (what, E, T, workload.n_blocks, reps, dt)}
 
 
 def main():
@@ -62,17 +87,16 @@ def main():
         sys.exit("bench.py: this build runs the interaction block on ONE GPU (no sharding, no collectives); "
                  "--gpus %d is not supported" % a.gpus)
 
-    import numpy as np
     import torch
 
     import paper_2203_09697_amd as gp
     import synth
+    from paper_2203_09697_amd.binding_e import ForceModelG
+    from paper_2203_09697_amd.binding_g import StackG
     from paper_2203_09697_amd.stack import StackD
 
     w = synth.get_workload(a.workload)
     dims = w.dims
-    if dims.variant != "D":
-        sys.exit("bench.py: workload %s (variant %s) is not implemented yet" % (a.workload, dims.variant))
     pos, gptr = synth.make_positions(w, a.seed)
     ctx = gp.Context(0)
     dpos = torch.as_tensor(pos).to("cuda:0")
@@ -91,14 +115,27 @@ def main():
     basis_ms = (time.perf_counter() - t0) * 1e3
     E, T = e["n_edges"], t["n_triplets"]
 
-    W_list = [gp.weights_to_device(synth.weights_D(dims, seed=100 + b)) for b in range(w.n_blocks)]
     m, gup = synth.edge_embeddings(E, dims.emb, seed=a.seed + 7)
     dm, dg = torch.as_tensor(m).to("cuda:0"), torch.as_tensor(gup).to("cuda:0")
-    stack = StackD(ctx, dims, W_list, t, basis)
+    del m, gup
+    if dims.variant == "D":
+        W_list = [gp.weights_to_device(synth.weights_D(dims, seed=100 + b)) for b in range(w.n_blocks)]
+        stack = StackD(ctx, dims, W_list, t, basis)
+    else:
+        W_list = [gp.weights_to_device(synth.weights_G(dims, seed=100 + b)) for b in range(w.n_blocks)]
+        if w.head_hidden:
+            Wh = gp.weights_to_device(synth.weights_head(dims.emb, w.head_hidden, seed=99))
+            model = ForceModelG(ctx, dims, W_list, Wh, w.head_hidden, e, t, basis, dptr)
+        else:
+            stack = StackG(ctx, dims, W_list, t, basis)
 
-    def step():
-        stack.forward(dm)
-        stack.backward(dg)
+    if w.head_hidden:
+        def step():
+            model.energy_and_forces(dm)
+    else:
+        def step():
+            stack.forward(dm)
+            stack.backward(dg)
 
     for _ in range(a.warmup):
         step()
@@ -114,26 +151,28 @@ def main():
     ms_per_step = ev0.elapsed_time(ev1) / a.steps
     value = T * w.n_blocks / (ms_per_step * 1e-3)
 
-    # per-kernel durations: the same K steps again with every launch bracketed by HIP events
+    # per-kernel durations: the same steps again with every launch bracketed by HIP events
+    prof_steps = min(a.steps, 5)
     gp.gp_profile_enable(ctx, True)
     gp.gp_profile_reset(ctx)
-    for _ in range(a.steps):
+    for _ in range(prof_steps):
         step()
     torch.cuda.synchronize()
     prof = gp.gp_profile_collect(ctx)
     gp.gp_profile_enable(ctx, False)
     kernels = []
     for name, d in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
-        is_gemm = name.startswith("gemm_")
         per_launch_ms = d["ms"] / d["launches"]
-        if is_gemm:
+        if name.startswith("gemm_f32"):
             ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_f32"], "mfma"
-        elif name.startswith("tripD"):
+        elif name.startswith("gemm_bf16"):
+            ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_bf16"], "mfma"
+        elif name.startswith(ALU_KERNELS):
             ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["alu_f32"], "alu"
         else:
             ach, (peak, unit), bound = d["bytes"] / (d["ms"] * 1e-3) / 1e9, PEAK["hbm"], "hbm"
-        kernels.append({"kernel": name, "launches_per_step": d["launches"] / a.steps, "avg_ms": round(per_launch_ms, 5),
-                        "ms_per_step": round(d["ms"] / a.steps, 4), "bound": bound, "achieved": round(ach, 3),
+        kernels.append({"kernel": name, "launches_per_step": d["launches"] / prof_steps, "avg_ms": round(per_launch_ms, 5),
+                        "ms_per_step": round(d["ms"] / prof_steps, 4), "bound": bound, "achieved": round(ach, 3),
                         "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
     top = kernels[0]
     roofline = {"kernel": top["kernel"], "bound": top["bound"], "achieved": top["achieved"], "peak": top["peak"],
@@ -142,12 +181,13 @@ def main():
     out = {
         "metric": "triplets/sec (interaction block fwd+bwd), 1 MI355X", "value": value, "unit": "triplets/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %d structures, N=%d atoms, E=%d edges, T=%d triplets, %d blocks, emb=%d int_emb=%d"
-                               % (w.name, len(gptr) - 1, len(pos), E, T, w.n_blocks, dims.emb, dims.int_emb),
+        "scaling": "weak", "vs_baseline": None, "dtype": dims.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d structures, N=%d atoms, E=%d edges, T=%d triplets, %d blocks, variant %s, "
+                               "emb=%d int_emb=%d%s" % (w.name, len(gptr) - 1, len(pos), E, T, w.n_blocks, dims.variant,
+                                                        dims.emb, dims.int_emb, ", energy head + forces" if w.head_hidden else ""),
                    "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed},
         "roofline": roofline,
-        "kernels": kernels[:8],
+        "kernels": kernels[:10],
         "graph_build_ms": round(graph_ms, 3), "basis_ms": round(basis_ms, 3), "wall_ms_per_step": round(wall_ms / a.steps, 4),
     }
     if not a.no_cpu_baseline:

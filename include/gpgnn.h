@@ -275,6 +275,10 @@ int gp_triplet_aggregate_bwd(gp_ctx* ctx, const gp_graph* graph, const int32_t* 
  * x[rows,k], W[k,n], b[n] or NULL, out[rows,n]. */
 int gp_linear_forward(gp_ctx* ctx, const float* x, const float* W, const float* b,
                       int64_t rows, int32_t k, int32_t n, int32_t act, float* out);
+/* The same layer with x and W rounded to bf16 on load (bf16 MFMA, fp32 accumulate and output),
+ * the operand type the bilinear block uses when gp_dims.dtype == GP_BF16_F32ACC. */
+int gp_linear_forward_bf16(gp_ctx* ctx, const float* x, const float* W, const float* b,
+                           int64_t rows, int32_t k, int32_t n, int32_t act, float* out);
 
 #ifdef __cplusplus
 }

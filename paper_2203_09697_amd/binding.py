@@ -28,7 +28,7 @@ EXPORTED_SYMBOLS = [
     "gp_block_forward_G", "gp_block_backward_G",
     "gp_energy_workspace", "gp_energy_forward", "gp_energy_backward",
     "gp_edges_by_source_workspace", "gp_edges_by_source", "gp_forces_workspace", "gp_forces_from_basis_grad",
-    "gp_triplet_aggregate_fwd", "gp_triplet_aggregate_bwd", "gp_linear_forward",
+    "gp_triplet_aggregate_fwd", "gp_triplet_aggregate_bwd", "gp_linear_forward", "gp_linear_forward_bf16",
 ]
 
 
@@ -321,9 +321,10 @@ def gp_triplet_aggregate_bwd(ctx, trip, x, s, grad_a):
     return gx, gs
 
 
-def gp_linear_forward(ctx, x, W, b=None, act=0):
+def gp_linear_forward(ctx, x, W, b=None, act=0, bf16=False):
     lib = load()
     out = torch.empty((x.shape[0], W.shape[1]), dtype=torch.float32, device=ctx.device)
-    ctx.check(lib.gp_linear_forward(ctx._h, _ptr(x), _ptr(W), _ptr(b), C.c_int64(x.shape[0]), C.c_int32(W.shape[0]),
+    fn = lib.gp_linear_forward_bf16 if bf16 else lib.gp_linear_forward
+    ctx.check(fn(ctx._h, _ptr(x), _ptr(W), _ptr(b), C.c_int64(x.shape[0]), C.c_int32(W.shape[0]),
                                     C.c_int32(W.shape[1]), C.c_int32(act), _ptr(out)))
     return out

@@ -134,6 +134,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   if (saved_bytes < carve_saved_G(saved, dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: saved buffer too small");
   if (scratch_bytes < carve_scratch_G(scratch, dims, E, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: scratch too small");
   GP_HIP(ctx, hipSetDevice(ctx->device));
+  gp_bf16_scope gemm_dtype(ctx, dims->dtype == GP_BF16_F32ACC);
   const int H = dims->emb, F = dims->int_emb, C = dims->emb_cbf, O = dims->emb_bil, S = dims->num_spherical,
             R = dims->num_radial, RB = dims->emb_rbf;
   const float* g = basis->rbf;
@@ -179,6 +180,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   if (saved_bytes < carve_saved_G(const_cast<void*>(saved), dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: saved buffer too small");
   if (scratch_bytes < carve_scratch_G(scratch, dims, E, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: scratch too small");
   GP_HIP(ctx, hipSetDevice(ctx->device));
+  gp_bf16_scope gemm_dtype(ctx, dims->dtype == GP_BF16_F32ACC);
   const int H = dims->emb, F = dims->int_emb, C = dims->emb_cbf, O = dims->emb_bil, S = dims->num_spherical,
             R = dims->num_radial, RB = dims->emb_rbf;
   const int64_t EH = E * H;

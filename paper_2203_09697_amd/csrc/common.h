@@ -22,6 +22,7 @@ struct gp_ctx {
   hipStream_t stream = nullptr;
   char err[512] = {0};
   bool prof_on = false;
+  bool gemm_bf16 = false;   // set by a block call whose dims ask for bf16 GEMM operands
   std::vector<gp_prof_entry> prof;
   std::vector<hipEvent_t> event_pool;
 };

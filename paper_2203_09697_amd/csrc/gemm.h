@@ -36,5 +36,14 @@ int gp_ew_dsilu_mul(gp_ctx* ctx, const float* g, const float* z, float* out, int
 int gp_ew_gate_bwd(gp_ctx* ctx, const float* dxg, const float* z, const float* gate, float* dz, float* dgate,
                    int64_t n);   // dz = dxg*gate*silu'(z), dgate = dxg*silu(z)
 int gp_ew_add3(gp_ctx* ctx, const float* a, const float* b, const float* c, float* out, int64_t n);  // c may be NULL
+// bf16-operand kernels (gemm_bf16.hip); mode 0 NN, 1 NT, 2 TN; args is the fp32 path's argument block
+int gp_gemm_bf16_launch(gp_ctx* ctx, int mode, void* args, int splits);
+// While alive, GEMMs issued on the context round their operands to bf16 if `on`.
+struct gp_bf16_scope {
+  gp_ctx* c;
+  bool prev;
+  gp_bf16_scope(gp_ctx* ctx, bool on) : c(ctx), prev(ctx->gemm_bf16) { c->gemm_bf16 = on; }
+  ~gp_bf16_scope() { c->gemm_bf16 = prev; }
+};
 // out[i] = sum_z part[z*n + i], z < splits
 int gp_reduce_parts(gp_ctx* ctx, const float* part, int splits, int64_t n, float* out);

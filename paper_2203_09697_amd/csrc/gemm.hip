@@ -11,12 +11,9 @@
 
 #include <type_traits>
 
-#include "gemm.h"
+#include "gemm_common.h"
 
 namespace {
-
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #ifndef GP_GEMM_BK
 #define GP_GEMM_BK 16
@@ -26,82 +23,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #endif
 constexpr int BK = GP_GEMM_BK;
 constexpr int NBUF = GP_GEMM_NBUF;   // LDS buffers per operand (2: one barrier per slab)
-constexpr int THREADS = 256;
-constexpr int EPI_LD = 36;             // row stride of a wavefront's 32x32 staging block (floats)
-enum { MODE_NN = 0, MODE_NT = 1, MODE_TN = 2 };
-
-struct gemm_args {
-  const float* A;
-  const float* B;
-  int64_t M;   // rows of C
-  int N, K;    // cols of C, contraction length (TN: total rows to reduce)
-  int64_t lda, ldb;
-  int vecA, vecB;          // 16-byte vector loads are legal for this operand
-  int vecC;                // 16-byte accesses are legal for every matrix the epilogue touches
-  int64_t k_per_split;     // TN only
-  float* part;             // TN only: [splits, M, N]
-  float* colsum_part;      // TN only, optional: [splits * tiles_m, N] partial column sums of B
-  gp_epilogue epi;
-};
-
-__device__ __forceinline__ void epilogue_store(const gp_epilogue& e, int64_t row, int col, int n, float v) {
-  const int64_t o = row * n + col;
-  if (e.bias) v += e.bias[col];
-  if (e.add_pre) v += e.add_pre[o];
-  if (e.save_pre) e.save_pre[o] = v;
-  if (e.act == 1) v = silu_f(v);
-  else if (e.act == 2) v *= dsilu_f(e.zsrc[o]);
-  if (e.mul) v *= e.mul[o];
-  if (e.add_post) v += e.add_post[o];
-  v *= e.scale;
-  if (e.out) e.out[o] = v;
-  if (e.out2) e.out2[o] = v * dsilu_f(e.z2src[o]);
-}
-
-__device__ __forceinline__ f32x4 ld4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
-__device__ __forceinline__ void st4(float* p, f32x4 v) { *reinterpret_cast<f32x4*>(p) = v; }
-
-// Same steps on 4 consecutive columns (col % 4 == 0, all pointers 16-byte aligned, n % 4 == 0).
-__device__ __forceinline__ void epilogue_store4(const gp_epilogue& e, int64_t row, int col, int n, f32x4 v) {
-  const int64_t o = row * n + col;
-  if (e.bias) v += ld4(e.bias + col);
-  if (e.add_pre) v += ld4(e.add_pre + o);
-  if (e.save_pre) st4(e.save_pre + o, v);
-  if (e.act == 1) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) v[c] = silu_f(v[c]);
-  } else if (e.act == 2) {
-    const f32x4 z = ld4(e.zsrc + o);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
-  }
-  if (e.mul) v *= ld4(e.mul + o);
-  if (e.add_post) v += ld4(e.add_post + o);
-  v *= e.scale;
-  if (e.out) st4(e.out + o, v);
-  if (e.out2) {
-    const f32x4 z = ld4(e.z2src + o);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
-    st4(e.out2 + o, v);
-  }
-}
-
-// wavefront-local ordering of LDS traffic (no other wavefront touches this wave's slice)
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Workgroup ids are dealt round-robin to the 8 XCDs; renumber them so that each XCD works on
-// a contiguous range of tiles and neighbouring tiles (same A rows) share that XCD's L2.
-__device__ __forceinline__ int xcd_remap(int bid, int n) {
-  const int q = n >> 3, r = n & 7;
-  const int x = bid & 7, i = bid >> 3;
-  return x * q + (x < r ? x : r) + i;
-}
-
 // Operand loaders.  A fetch only ISSUES global loads (addresses are clamped into the matrix, so
 // no branch surrounds a load and nothing waits on the data); the out-of-range elements are
 // zeroed later, in store(), from a bit mask.  That keeps the loads of the next K-slab in flight
@@ -471,6 +392,9 @@ constexpr int TILE_BM = GP_GEMM_BM;
 
 template <int MODE>
 int dispatch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
+  // bf16 operands (fp32 accumulate) when the calling block asks for them; the fused column
+  // sums exist only in the fp32 kernel
+  if (ctx->gemm_bf16 && !(MODE == MODE_TN && g.colsum_part)) return gp_gemm_bf16_launch(ctx, MODE, &g, splits);
 #if GP_GEMM_BM == 64
   if (g.N > 64) return launch_gemm<TILE_BM, 128, 1, 4, MODE>(ctx, g, splits);
   if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
@@ -639,4 +563,14 @@ extern "C" int gp_linear_forward(gp_ctx* ctx, const float* x, const float* W, co
   e.act = act;
   e.out = out;
   return gp_gemm_nn(ctx, x, W, rows, n, k, e);
+}
+
+extern "C" int gp_linear_forward_bf16(gp_ctx* ctx, const float* x, const float* W, const float* b, int64_t rows,
+                                      int32_t k, int32_t n, int32_t act, float* out) {
+  if (!ctx) return GP_BAD_ARG;
+  const bool prev = ctx->gemm_bf16;
+  ctx->gemm_bf16 = true;
+  const int rc = gp_linear_forward(ctx, x, W, b, rows, k, n, act, out);
+  ctx->gemm_bf16 = prev;
+  return rc;
 }

@@ -1,0 +1,61 @@
+"""GPU parity of the bf16-operand (fp32-accumulate) MFMA path: dense layer and the variant-G block.
+
+Bar: relative L2 error <= 2e-2 per tensor against the fp64 oracle fed the unrounded fp32 inputs
+(the target's bf16 figure).  The dense layer is additionally checked against the exact product of
+the bf16-rounded operands, which pins the MFMA operand layout independently of rounding noise.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import block as oblock
+from tests import helpers as H
+from tests.test_gpu_block_G import _parity
+
+pytestmark = pytest.mark.gpu
+F64 = torch.float64
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    return lib.Context(0)
+
+
+@pytest.mark.parametrize("rows,k,n,act", [(1, 8, 4, 0), (37, 32, 16, 1), (300, 6, 32, 0), (1000, 256, 256, 1),
+                                            (513, 64, 512, 1), (2049, 1024, 64, 0), (129, 42, 8, 0), (5, 7, 3, 1),
+                                            (700, 1024, 1024, 0)])
+def test_linear_forward_bf16(lib, ctx, rows, k, n, act):
+    rng = np.random.default_rng(rows + k)
+    x = rng.standard_normal((rows, k)).astype(np.float32)
+    W = synth.glorot(rng, (k, n))
+    b = rng.uniform(-0.5, 0.5, n).astype(np.float32)
+    out = lib.gp_linear_forward(ctx, H.to_dev(x, torch.float32), H.to_dev(W, torch.float32),
+                                H.to_dev(b, torch.float32), act, bf16=True).cpu().numpy()
+    bt = torch.tensor(b, dtype=F64)
+    z = torch.tensor(x, dtype=F64) @ torch.tensor(W, dtype=F64) + bt
+    ref = (oblock.act(z) if act else z).numpy()
+    assert H.rel_l2(out, ref) < 2e-2
+    # exact product of the rounded operands (rounding by the library's round-to-nearest-even cast)
+    xr = torch.tensor(x).bfloat16().to(F64)
+    Wr = torch.tensor(W).bfloat16().to(F64)
+    zr = xr @ Wr + bt
+    refr = (oblock.act(zr) if act else zr).numpy()
+    assert H.rel_l2(out, refr) < 2e-5
+
+
+def test_block_G_bf16_small_dims(lib, ctx):
+    w = synth.get_workload("cfg3", emb=32, int_emb=16, emb_rbf=4, emb_cbf=5, emb_bil=12, num_radial=9,
+                           num_spherical=4, cutoff=4.0)
+    assert w.dims.dtype == "bf16"
+    _parity(lib, ctx, w, 0, 2, synth.cube_positions(30, 6.0, 0.9, seed=1), tol=2e-2)
+
+
+def test_block_G_bf16_cfg3_shape_one_structure(lib, ctx):
+    w = synth.get_workload("cfg3")
+    _parity(lib, ctx, w, 1, 1, synth.slab_adsorbate_positions(1, 8, 5, 4, 40, seed=2), tol=2e-2)
+
+
+def test_block_G_bf16_cfg4_widths_small_graph(lib, ctx):
+    w = synth.get_workload("cfg4", cutoff=6.0)
+    _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3), tol=2e-2)
