@@ -21,6 +21,19 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_f32": (157.3, "TFLOP/s"), "mfma_bf16": (2
 ALU_KERNELS = ("tripD_fwd", "tripD_bwd", "tripG_fwd", "trip_bwd_H", "tripG_grad_cos", "tripG_edge")
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if any
+    (profiles/block_<variant>_<workload>_hbm_traffic.md; counters cannot be read from inside the run)."""
+    path = os.path.join(ROOT, "profiles", "block_%s_%s_hbm_traffic.md" % (workload.dims.variant, workload.name))
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 5 and cells[1].isdigit():
+                out[cells[0]] = (float(cells[2]) + float(cells[3])) * 1024.0
+    return out
+
+
 def sample_system(workload, seed):
     """A bounded sample of the workload for the CPU oracle: fewer structures of the same recipe, or
     (single-structure workloads) a smaller box at the same density and cutoff."""
@@ -82,6 +95,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="run one 256 MiB device copy first (known traffic, to scale rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs the interaction block on ONE GPU (no sharding, no collectives); "
@@ -137,6 +152,12 @@ def main():
             stack.forward(dm)
             stack.backward(dg)
 
+    if a.calib_copy:
+        src_c = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0").normal_()
+        dst_c = torch.empty_like(src_c)
+        dst_c.copy_(src_c)
+        torch.cuda.synchronize()
+        del src_c, dst_c
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
@@ -175,8 +196,11 @@ def main():
                         "ms_per_step": round(d["ms"] / prof_steps, 4), "bound": bound, "achieved": round(ach, 3),
                         "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
     top = kernels[0]
+    traffic = measured_traffic(w)
+    for k in kernels:
+        k["traffic"] = traffic.get(k["kernel"])
     roofline = {"kernel": top["kernel"], "bound": top["bound"], "achieved": top["achieved"], "peak": top["peak"],
-                "unit": top["unit"], "frac": top["frac"], "avg_ms": top["avg_ms"], "traffic": None}
+                "unit": top["unit"], "frac": top["frac"], "avg_ms": top["avg_ms"], "traffic": top["traffic"]}
 
     out = {
         "metric": "triplets/sec (interaction block fwd+bwd), 1 MI355X", "value": value, "unit": "triplets/s",
