@@ -53,3 +53,7 @@ int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, i
 // grad_cos_kj[q] (+)= sum_l Y_l0'(cos_alpha_kj[q]) sum_o dz[ji(q), o] U[kj(q), l, o]   (kj-major order)
 int gp_tripG_grad_cos(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* U, const float* dz,
                       int O, int S, int accumulate, float* grad_cos_kj);
+// 16-byte vectorised streaming kernels (triplet_stream.hip); return 1 if they handled the call
+int gp_stream_fwd_fast(gp_ctx* ctx, const gp_graph* g, int F, const float* x, const float* s, float* a);
+int gp_stream_bwd_fast(gp_ctx* ctx, const gp_graph* g, const int32_t* perm_kj, int F, const float* x, const float* s,
+                       const float* ga, float* gx, float* gs);

@@ -506,6 +506,10 @@ extern "C" int gp_triplet_aggregate_fwd(gp_ctx* ctx, const gp_graph* graph, int3
   GP_HIP(ctx, hipSetDevice(ctx->device));
   gp_prof_scope prof(ctx, "triplet_stream_fwd", 2.0 * graph->n_triplets * F,
                      (double)graph->n_triplets * (4.0 * F + 4.0) + (double)E * (8.0 * F + 4.0));
+  if (gp_stream_fwd_fast(ctx, graph, F, x, s, a)) {
+    GP_LAUNCH_CHECK(ctx, "stream_fwd4_kernel");
+    return GP_OK;
+  }
 #define CALL_S(LPR, FPL) \
   stream_fwd_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(graph->seg_ptr_ji, graph->idx_kj, x, s, E, F, a)
   GP_DISPATCH_WIDTH(F, CALL_S);
@@ -528,6 +532,10 @@ extern "C" int gp_triplet_aggregate_bwd(gp_ctx* ctx, const gp_graph* graph, cons
   GP_HIP(ctx, hipSetDevice(ctx->device));
   gp_prof_scope prof(ctx, "triplet_stream_bwd", 3.0 * graph->n_triplets * F,
                      (double)graph->n_triplets * (12.0 * F + 16.0) + (double)E * (12.0 * F + 8.0));
+  if (graph->n_triplets > 0 && gp_stream_bwd_fast(ctx, graph, perm_kj, F, x, s, grad_a, grad_x, grad_s)) {
+    GP_LAUNCH_CHECK(ctx, "stream_bwd4 kernels");
+    return GP_OK;
+  }
 #define CALL_S(LPR, FPL)                                                                                          \
   do {                                                                                                            \
     stream_bwd_x_kernel<LPR, FPL><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(                                 \
