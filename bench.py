@@ -172,8 +172,10 @@ def main():
     ms_per_step = ev0.elapsed_time(ev1) / a.steps
     value = T * w.n_blocks / (ms_per_step * 1e-3)
 
-    # per-kernel durations: the same steps again with every launch bracketed by HIP events
+    # per-kernel durations: the same steps again with every launch bracketed by HIP events, all on
+    # one stream (with the side stream on, two kernels overlap and a launch has no duration of its own)
     prof_steps = min(a.steps, 5)
+    gp.gp_set_side_stream(ctx, False)
     gp.gp_profile_enable(ctx, True)
     gp.gp_profile_reset(ctx)
     for _ in range(prof_steps):
@@ -181,6 +183,7 @@ def main():
     torch.cuda.synchronize()
     prof = gp.gp_profile_collect(ctx)
     gp.gp_profile_enable(ctx, False)
+    gp.gp_set_side_stream(ctx, True)
     kernels = []
     for name, d in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
         per_launch_ms = d["ms"] / d["launches"]

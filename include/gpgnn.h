@@ -46,6 +46,12 @@ void gp_destroy(gp_ctx* ctx);
 const char* gp_last_error(const gp_ctx* ctx);
 const char* gp_version(void);
 
+/* The backward passes issue their weight-gradient GEMMs on a second, library-owned stream next to
+ * the input-gradient chain and join it before returning (callers see single-stream semantics).
+ * gp_set_side_stream(ctx, 0) keeps everything on the context's stream, e.g. to time kernels one
+ * at a time; the environment variable GP_NO_AUX_STREAM=1 has the same effect at gp_create. */
+int gp_set_side_stream(gp_ctx* ctx, int on);
+
 /* Measurement aid (not a step of the method): while enabled, every kernel launch the library
  * issues on this context is bracketed by two HIP events on the context's stream.
  * gp_profile_get(i) synchronises on launch i and returns its kernel name (static string),

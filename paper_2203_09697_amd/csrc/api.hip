@@ -19,6 +19,11 @@ int gp_create(gp_ctx** out, int device_id, void* hip_stream) {
   if (!c) return GP_HIP_ERROR;
   c->device = device_id;
   c->stream = (hipStream_t)hip_stream;
+  // side stream at the default priority; without it everything simply runs on the main stream
+  if (hipSetDevice(device_id) != hipSuccess || hipStreamCreateWithFlags(&c->aux_stream, hipStreamNonBlocking) != hipSuccess)
+    c->aux_stream = nullptr;
+  const char* no_aux = getenv("GP_NO_AUX_STREAM");
+  c->use_aux = !(no_aux && no_aux[0] == '1');
   *out = c;
   return GP_OK;
 }
@@ -30,7 +35,15 @@ void gp_destroy(gp_ctx* ctx) {
     (void)hipEventDestroy(p.t1);
   }
   for (auto e : ctx->event_pool) (void)hipEventDestroy(e);
+  for (auto e : ctx->aux_event_pool) (void)hipEventDestroy(e);
+  if (ctx->aux_stream) (void)hipStreamDestroy(ctx->aux_stream);
   delete ctx;
+}
+
+int gp_set_side_stream(gp_ctx* ctx, int on) {
+  if (!ctx) return GP_BAD_ARG;
+  ctx->use_aux = on != 0;
+  return GP_OK;
 }
 
 int gp_profile_enable(gp_ctx* ctx, int on) {

@@ -10,6 +10,7 @@
 
 #include <algorithm>
 
+#include "aux_stream.h"
 #include "gemm.h"
 #include "triplet.h"
 
@@ -62,6 +63,7 @@ struct scratch_D {
   float* dQ;         // [E,S*B]
   float* dWrbf;      // [R,H]
   float* part;
+  float* part_aux;   // split-K partials of the GEMMs issued on the side stream
   size_t part_bytes;
 };
 
@@ -87,6 +89,7 @@ size_t carve_scratch_D(void* p, const gp_dims* d, int64_t E, scratch_D* s) {
   s->dWrbf = c.take<float>(R * H);
   s->part_bytes = part_bytes_D(d, E);
   s->part = (float*)c.take<char>(s->part_bytes);
+  s->part_aux = (float*)c.take<char>(s->part_bytes);
   return c.off;
 }
 
@@ -128,16 +131,19 @@ int res_forward(gp_ctx* ctx, const float* hin, float* const* w, const res_saved&
 
 // One residual layer backward.  dz2 = dh * silu'(z2) is given (written by the producer of dh).
 // dh_out = dh + d(hin through the layer); if z_next != NULL also dz_next = dh_out * silu'(z_next).
-int res_backward(gp_ctx* ctx, const float* hin, float* const* w, float* const* gw, const res_saved& s,
+// The two weight-gradient GEMMs go to the side stream.
+int res_backward(gp_ctx* ctx, gp_aux& aux, const float* hin, float* const* w, float* const* gw, const res_saved& s,
                  const float* dh, const float* dz2, float* dh_out, float* t2, const float* z_next, float* dz_next,
                  scratch_D& sc, int64_t E, int H) {
-  GP_TRY(gp_gemm_tn(ctx, s.y1, dz2, E, H, H, gw[2], gw[3], sc.part, sc.part_bytes));    // dW2, db2
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.y1, dz2, E, H, H, gw[2], gw[3], sc.part_aux, sc.part_bytes); }, {dz2}));
   gp_epilogue e;
   e.act = 2; e.zsrc = s.z1; e.out = t2;
+  GP_TRY(aux.before_write(t2));
   GP_TRY(gp_gemm_nt(ctx, dz2, w[2], E, H, H, e));                                       // dz1
-  GP_TRY(gp_gemm_tn(ctx, hin, t2, E, H, H, gw[0], gw[1], sc.part, sc.part_bytes));      // dW1, db1
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, hin, t2, E, H, H, gw[0], gw[1], sc.part_aux, sc.part_bytes); }, {t2}));
   gp_epilogue e2;
   e2.add_post = dh; e2.out = dh_out; e2.out2 = z_next ? dz_next : nullptr; e2.z2src = z_next;
+  if (z_next) GP_TRY(aux.before_write(dz_next));
   return gp_gemm_nt(ctx, t2, w[0], E, H, H, e2);
 }
 
@@ -247,6 +253,7 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
     return nullptr;
   };
 
+  gp_aux aux(ctx);
   // dz of the last activation in the block: the only elementwise pass that has no producer GEMM
   const float* z_first = dims->n_res_after > 0 ? s.after[dims->n_res_after - 1].z2 : s.z_lin;
   float* dzcur = T1;
@@ -259,8 +266,8 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
     const float* z_next = (r > 0) ? s.after[r - 1].z2 : s.z_lin;
     float* out = next_buf();
     float* dznext = other_dz();
-    GP_TRY(res_backward(ctx, hin, w->res_after[r], gw->res_after[r], s.after[r], dh, dzcur, out, T2, z_next, dznext,
-                        sc, E, H));
+    GP_TRY(res_backward(ctx, aux, hin, w->res_after[r], gw->res_after[r], s.after[r], dh, dzcur, out, T2, z_next,
+                        dznext, sc, E, H));
     dh = out;
     dzcur = dznext;
   }
@@ -269,9 +276,11 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
   {
     const float* hin = dims->n_res_before > 0 ? s.before[dims->n_res_before - 1].hout : s.h0;
     const float* z_next = dims->n_res_before > 0 ? s.before[dims->n_res_before - 1].z2 : s.z_up;
-    GP_TRY(gp_gemm_tn(ctx, hin, dzcur, E, H, H, gw->W_lin, gw->b_lin, sc.part, sc.part_bytes));
+    GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, hin, dzcur, E, H, H, gw->W_lin, gw->b_lin, sc.part_aux, sc.part_bytes); },
+                      {dzcur}));
     float* out = next_buf();
     float* dznext = other_dz();
+    GP_TRY(aux.before_write(dznext));
     gp_epilogue e; e.out = out; e.out2 = dznext; e.z2src = z_next;
     GP_TRY(gp_gemm_nt(ctx, dzcur, w->W_lin, E, H, H, e));
     dh = out;
@@ -282,13 +291,14 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
     const float* z_next = (r > 0) ? s.before[r - 1].z2 : s.z_up;
     float* out = next_buf();
     float* dznext = other_dz();
-    GP_TRY(res_backward(ctx, hin, w->res_before[r], gw->res_before[r], s.before[r], dh, dzcur, out, T2, z_next, dznext,
-                        sc, E, H));
+    GP_TRY(res_backward(ctx, aux, hin, w->res_before[r], gw->res_before[r], s.before[r], dh, dzcur, out, T2, z_next,
+                        dznext, sc, E, H));
     dh = out;
     dzcur = dznext;
   }
   // h0 = x_ji + act(a W_up);  dh = dh0, dzcur = dz_up
-  GP_TRY(gp_gemm_tn(ctx, s.a, dzcur, E, F, H, gw->W_up, nullptr, sc.part, sc.part_bytes));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.a, dzcur, E, F, H, gw->W_up, nullptr, sc.part_aux, sc.part_bytes); },
+                    {dzcur}));
   {
     gp_epilogue e; e.out = sc.dF1;
     GP_TRY(gp_gemm_nt(ctx, dzcur, w->W_up, E, F, H, e));                                     // da
@@ -298,11 +308,14 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
                            sc.dF2, sc.dQ));                                                   // dz_dn, dQ
   GP_TRY(gp_tripD_weight_grads(ctx, sc.dF1, s.Bacc, basis->rad, sc.dQ, E, F, S, R, B, gw->W_sbf2, gw->W_sbf1,
                                sc.part, sc.part_bytes));
-  GP_TRY(gp_gemm_tn(ctx, s.xg, sc.dF2, E, H, F, gw->W_down, nullptr, sc.part, sc.part_bytes));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dF2, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes); },
+                    {sc.dF2}));
   {
+    GP_TRY(aux.before_write(T2));
     gp_epilogue e; e.out = T2;
     GP_TRY(gp_gemm_nt(ctx, sc.dF2, w->W_down, E, H, F, e));                                  // dxg
   }
+  GP_TRY(aux.before_write(T3));
   GP_TRY(gp_ew_gate_bwd(ctx, T2, s.z_kj, s.gate, T3, dgate, EH));                            // dz_kj, dgate
   GP_TRY(gp_gemm_tn(ctx, basis->rbf, dgate, E, R, H, sc.dWrbf, nullptr, sc.part, sc.part_bytes));
   {
@@ -310,18 +323,19 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
     GP_TRY(gp_gemm_nt(ctx, sc.dWrbf, w->W_rbf2, R, B, H, e));
   }
   GP_TRY(gp_gemm_tn(ctx, w->W_rbf1, sc.dWrbf, R, B, H, gw->W_rbf2, nullptr, sc.part, sc.part_bytes));
-  GP_TRY(gp_gemm_tn(ctx, m_in, T3, E, H, H, gw->W_kj, gw->b_kj, sc.part, sc.part_bytes));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, T3, E, H, H, gw->W_kj, gw->b_kj, sc.part_aux, sc.part_bytes); }, {T3}));
   {
     gp_epilogue e; e.add_post = keep; e.out = grad_m_in;
     GP_TRY(gp_gemm_nt(ctx, T3, w->W_kj, E, H, H, e));                                        // dm = skip + kj path
   }
+  GP_TRY(aux.before_write(T1));
   GP_TRY(gp_ew_dsilu_mul(ctx, dh, s.z_ji, T1, EH));                                          // dz_ji
-  GP_TRY(gp_gemm_tn(ctx, m_in, T1, E, H, H, gw->W_ji, gw->b_ji, sc.part, sc.part_bytes));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, T1, E, H, H, gw->W_ji, gw->b_ji, sc.part_aux, sc.part_bytes); }, {T1}));
   {
     gp_epilogue e; e.add_post = grad_m_in; e.out = grad_m_in;
     GP_TRY(gp_gemm_nt(ctx, T1, w->W_ji, E, H, H, e));                                        // dm += ji path
   }
-  return GP_OK;
+  return aux.join();
 }
 
 }  // extern "C"

@@ -23,6 +23,9 @@ struct gp_ctx {
   char err[512] = {0};
   bool prof_on = false;
   bool gemm_bf16 = false;   // set by a block call whose dims ask for bf16 GEMM operands
+  hipStream_t aux_stream = nullptr;   // side stream for weight-gradient GEMMs (see aux_stream.h)
+  bool use_aux = true;
+  std::vector<hipEvent_t> aux_event_pool;
   std::vector<gp_prof_entry> prof;
   std::vector<hipEvent_t> event_pool;
 };

@@ -257,21 +257,23 @@ gemm_f32_kernel(const gemm_args g) {
 }
 
 // out[i] = sum_z part[z*n + i] for i < n;  out2[i] = sum_z part2[z*n2 + i] for i < n2.
-// 64 column groups x 4 split lanes per workgroup; each lane keeps several 16-byte loads in
-// flight and the four lanes are combined in a fixed order, so the result is reproducible.
-constexpr int RED_COLS = 64, RED_LANES = 4;
+// 16 column groups x 16 split lanes per workgroup: every lane issues its (few) 16-byte loads
+// back to back, the 16 lanes of a column group are combined in a fixed order through LDS, so
+// the result is reproducible.  The second (narrow) array is handled the same way, one float
+// per column group.
+constexpr int RED_COLS = 16, RED_LANES = 16;
 __global__ void __launch_bounds__(RED_COLS* RED_LANES)
 reduce_parts_kernel(const float* __restrict__ part, int splits, int64_t n, int vec, float* __restrict__ out,
                     int blocks1, const float* __restrict__ part2, int splits2, int64_t n2,
                     float* __restrict__ out2) {
   __shared__ f32x4 red[RED_LANES][RED_COLS];
   const int cg = threadIdx.x % RED_COLS, sl = threadIdx.x / RED_COLS;
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
   if ((int)blockIdx.x < blocks1) {
     const int64_t i = ((int64_t)blockIdx.x * RED_COLS + cg) * 4;
-    f32x4 s = {0.f, 0.f, 0.f, 0.f};
     if (i < n) {
       if (vec) {
-#pragma unroll 4
+#pragma unroll 8
         for (int z = sl; z < splits; z += RED_LANES) s += ld4(part + (int64_t)z * n + i);
       } else {
         for (int z = sl; z < splits; z += RED_LANES)
@@ -290,11 +292,17 @@ reduce_parts_kernel(const float* __restrict__ part, int splits, int64_t n, int v
           if (i + c < n) out[i + c] = t[c];
     }
   } else {
-    const int64_t i = (int64_t)(blockIdx.x - blocks1) * blockDim.x + threadIdx.x;
+    const int64_t i = (int64_t)(blockIdx.x - blocks1) * RED_COLS + cg;
     if (i < n2) {
-      float s = 0.f;
-      for (int z = 0; z < splits2; ++z) s += part2[(int64_t)z * n2 + i];
-      out2[i] = s;
+#pragma unroll 8
+      for (int z = sl; z < splits2; z += RED_LANES) s[0] += part2[(int64_t)z * n2 + i];
+    }
+    red[sl][cg] = s;
+    __syncthreads();
+    if (sl == 0 && i < n2) {
+      float t = red[0][cg][0];
+      for (int k = 1; k < RED_LANES; ++k) t += red[k][cg][0];
+      out2[i] = t;
     }
   }
 }
@@ -303,7 +311,7 @@ int launch_reduce(gp_ctx* ctx, const float* part, int splits, int64_t n, float* 
                   int64_t n2, float* out2) {
   const int per_block = RED_COLS * 4;
   const int blocks1 = (int)((n + per_block - 1) / per_block);
-  const int blocks2 = (int)((n2 + RED_COLS * RED_LANES - 1) / (RED_COLS * RED_LANES));
+  const int blocks2 = (int)((n2 + RED_COLS - 1) / RED_COLS);
   const int vec = (n % 4 == 0) && (((uintptr_t)part | (uintptr_t)out) & 15) == 0;
   reduce_parts_kernel<<<blocks1 + blocks2, RED_COLS * RED_LANES, 0, ctx->stream>>>(part, splits, n, vec, out, blocks1,
                                                                                   part2, splits2, n2, out2);
