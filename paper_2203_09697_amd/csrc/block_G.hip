@@ -15,6 +15,7 @@
 
 #include <algorithm>
 
+#include "aux_stream.h"
 #include "gemm.h"
 #include "triplet.h"
 
@@ -49,6 +50,7 @@ struct scratch_G {
   float *dz, *Hd, *Gm, *V, *dRad, *dzdn, *U;
   float *WbilP, *WbilV, *dWrbf, *dWcP;
   float* part;
+  float* part_aux;   // split-K partials of the GEMMs issued on the side stream
   size_t part_bytes;
 };
 
@@ -81,6 +83,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, scratch_G* s) {
   s->dWcP = c.take<float>(R * S * C);
   s->part_bytes = part_bytes_G(d, E);
   s->part = (float*)c.take<char>(s->part_bytes);
+  s->part_aux = (float*)c.take<char>(s->part_bytes);
   return c.off;
 }
 
@@ -188,14 +191,15 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   float *d_up = sc.eh[0], *d_skip = sc.eh[1], *dxg = sc.eh[2], *dgate = sc.eh[3];
   gp_epilogue e;
 
+  gp_aux aux(ctx);   // the large weight-gradient GEMMs run on the side stream
   GP_TRY(gp_ew_dsilu2(ctx, grad_m_out, INV_SQRT2, s.z_up, s.z_skip, d_up, d_skip, EH));
-  GP_TRY(gp_gemm_tn(ctx, s.z, d_up, E, O, H, gw->W_up, nullptr, sc.part, sc.part_bytes));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.z, d_up, E, O, H, gw->W_up, nullptr, sc.part_aux, sc.part_bytes); }, {d_up}));
   e = gp_epilogue(); e.out = sc.dz;
   GP_TRY(gp_gemm_nt(ctx, d_up, w->W_up, E, O, H, e));                               // dz
-  GP_TRY(gp_gemm_tn(ctx, m_in, d_skip, E, H, H, gw->W_skip, nullptr, sc.part, sc.part_bytes));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, d_skip, E, H, H, gw->W_skip, nullptr, sc.part_aux, sc.part_bytes); }, {}));
   e = gp_epilogue(); e.out = grad_m_in;
   GP_TRY(gp_gemm_nt(ctx, d_skip, w->W_skip, E, H, H, e));                           // dm (skip path)
-  GP_TRY(gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part, sc.part_bytes));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part_aux, sc.part_bytes); }, {}));
   // one pass over the triplets (kj-major): H[e', l, o]
   GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, nullptr, nullptr, nullptr, sc.dz, nullptr, O, S, 1,
                            sc.Hd, nullptr));
@@ -213,16 +217,17 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   }
   GP_TRY(gp_gemm_tn(ctx, g, sc.dRad, E, R, S * C, sc.dWcP, nullptr, sc.part, sc.part_bytes));   // [n, (l,c)]
   GP_TRY(gp_permute3(ctx, sc.dWcP, R, S, C, 1, 0, 2, gw->W_c));                     // -> [l, n, c]
-  GP_TRY(gp_gemm_tn(ctx, s.xg, sc.dzdn, E, H, F, gw->W_down, nullptr, sc.part, sc.part_bytes));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dzdn, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes); }, {}));
   e = gp_epilogue(); e.out = dxg;
   GP_TRY(gp_gemm_nt(ctx, sc.dzdn, w->W_down, E, H, F, e));                          // dxg
-  float* dz_ba = d_up;   // d_up is no longer needed
+  float* dz_ba = d_up;   // d_up is no longer needed on this stream
+  GP_TRY(aux.before_write(d_up));
   GP_TRY(gp_ew_gate_bwd(ctx, dxg, s.z_ba, s.gate, dz_ba, dgate, EH));
   GP_TRY(gp_gemm_tn(ctx, g, dgate, E, R, H, sc.dWrbf, nullptr, sc.part, sc.part_bytes));
   e = gp_epilogue(); e.out = gw->W_rbfS;
   GP_TRY(gp_gemm_nt(ctx, sc.dWrbf, w->W_rbfB, R, RB, H, e));
   GP_TRY(gp_gemm_tn(ctx, w->W_rbfS, sc.dWrbf, R, RB, H, gw->W_rbfB, nullptr, sc.part, sc.part_bytes));
-  GP_TRY(gp_gemm_tn(ctx, m_in, dz_ba, E, H, H, gw->W_ba, nullptr, sc.part, sc.part_bytes));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, dz_ba, E, H, H, gw->W_ba, nullptr, sc.part_aux, sc.part_bytes); }, {}));
   e = gp_epilogue(); e.add_post = grad_m_in; e.out = grad_m_in;
   GP_TRY(gp_gemm_nt(ctx, dz_ba, w->W_ba, E, H, H, e));                              // dm += ba path
   if (grad_rbf) {
@@ -233,7 +238,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
     e = gp_epilogue(); e.add_post = grad_rbf; e.out = grad_rbf;
     GP_TRY(gp_gemm_nn(ctx, sc.dRad, s.WcT, E, R, S * C, e));
   }
-  return GP_OK;
+  return aux.join();
 }
 
 }  // extern "C"
