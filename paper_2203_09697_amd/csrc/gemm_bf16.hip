@@ -5,8 +5,16 @@
 //
 // LDS tiles are As[m][k], Bs[n][k] with k contiguous (rows padded to 80 bytes), so the 8
 // consecutive k that one lane feeds to an MFMA are a single 16-byte read.  A 256-thread
-// workgroup owns a 128 x BN tile, each wavefront 32x32 blocks of it; K advances 32 per slab,
-// global loads for the next slab are issued before the current one is multiplied.
+// workgroup owns a BM x BN tile (256x128 for tall matrices), each wavefront 32x32 blocks of it;
+// K advances 32 per slab, global loads for the next slab are issued before the current one is
+// multiplied.
+//
+// One MFMA of this shape does 32768 flop in 32 cycles, so the loop around it has to stay within a
+// few vector instructions per MFMA.  The loaders therefore keep a uniform base pointer that moves
+// with the slab plus one 32-bit byte offset per item computed once, and full slabs take a path
+// with no bounds arithmetic at all: rows/columns past the edge of the matrix are read from a
+// clamped (valid) address and only influence outputs that are never stored.  Only the last,
+// partial slab of the contraction masks its operands to zero.
 #include <stdarg.h>
 
 #include <type_traits>
@@ -20,102 +28,185 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BKH = 32;        // k per slab
 constexpr int LDK = BKH + 8;   // bf16 per LDS row: 80 bytes, 16-byte reads of 8 lanes cover all banks
 constexpr int K8 = BKH / 8;    // 16-byte groups per row
+constexpr int64_t MAX_LD = 1 << 21;   // keeps every per-thread byte offset below 2^32
 
-__device__ __forceinline__ bf16x8 to_bf16x8(const float* v, uint32_t bits) {
+__device__ __forceinline__ f32x4 ldg4(const float* base, uint32_t byte_off) {
+  return *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+__device__ __forceinline__ float ldg1(const float* base, uint32_t byte_off) {
+  return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+
+__device__ __forceinline__ bf16x8 to_bf16x8(const float* v) {
+  bf16x8 r;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) r[c] = (__bf16)v[c];
+  return r;
+}
+__device__ __forceinline__ bf16x8 to_bf16x8_masked(const float* v, uint32_t bits) {
   bf16x8 r;
 #pragma unroll
   for (int c = 0; c < 8; ++c) r[c] = (__bf16)(((bits >> c) & 1u) ? v[c] : 0.f);
   return r;
 }
 
-// source rows = tile rows, contraction index contiguous; item = (row, group of 8 k)
+// Source rows = tile rows, contraction index contiguous; item = (row, group of 8 k).
 template <int X, bool VEC>
 struct bl_kcontig {
   static constexpr int ITEMS = X * K8;
   static constexpr int NV = (ITEMS + THREADS - 1) / THREADS;
+  static constexpr bool ALL = ITEMS % THREADS == 0;
+  const float* base;   // first row of the tile (uniform)
+  uint32_t off[NV];    // bytes from base to the item's first element at k0 = 0
   float r[NV][8];
-  uint32_t mask;
-  __device__ __forceinline__ void fetch(const float* __restrict__ src, int64_t ld, int64_t row0, int64_t n_rows,
-                                        int64_t k0, int64_t k_end) {
+  uint32_t mask;       // partial slab only: bit 8*it+c set when that k lies inside the contraction
+
+  __device__ __forceinline__ void init(const float* __restrict__ src, int64_t ld, int64_t row0, int64_t n_rows) {
+    base = src + row0 * ld;
+    const int last = (int)(n_rows - 1 - row0 < X - 1 ? n_rows - 1 - row0 : X - 1);
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      const int row = idx / K8, kq = (idx % K8) * 8;
+      off[it] = (uint32_t)(((int64_t)(row < last ? row : last) * ld + kq) * 4);
+    }
+  }
+  __device__ __forceinline__ void fetch_full(int64_t k0) {
+    const float* p = base + k0;
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      if (!ALL && (int)threadIdx.x + it * THREADS >= ITEMS) continue;
+      if (VEC) {
+        const f32x4 v0 = ldg4(p, off[it]), v1 = ldg4(p, off[it] + 16);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) r[it][c] = v0[c], r[it][4 + c] = v1[c];
+      } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) r[it][c] = ldg1(p, off[it] + 4 * c);
+      }
+    }
+  }
+  __device__ __forceinline__ void fetch_tail(int64_t k0, int64_t k_end) {
     mask = 0;
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = threadIdx.x + it * THREADS;
-      const int row = idx / K8, kq = (idx % K8) * 8;
-      const bool in_tile = (ITEMS % THREADS == 0) || idx < ITEMS;
-      const int64_t gr = row0 + row, gk = k0 + kq;
-      const bool row_ok = in_tile && gr < n_rows;
-      const float* p = src + (gr < n_rows ? gr : n_rows - 1) * ld;
-      if (VEC) {
+      if (!ALL && idx >= ITEMS) continue;
+      const int kq = (idx % K8) * 8;
+      const float* prow = reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + (off[it] - 4u * kq));
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int64_t k = gk + 4 * h;
-          const f32x4 v = ld4(p + (k < k_end ? k : k_end - 4));
-#pragma unroll
-          for (int c = 0; c < 4; ++c) r[it][4 * h + c] = v[c];
-          mask |= ((row_ok && k < k_end) ? 0xFu : 0u) << (8 * it + 4 * h);
-        }
-      } else {
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          const int64_t k = gk + c;
-          r[it][c] = p[k < k_end ? k : k_end - 1];
-          mask |= ((row_ok && k < k_end) ? 1u : 0u) << (8 * it + c);
-        }
+      for (int c = 0; c < 8; ++c) {
+        const int64_t k = k0 + kq + c;
+        r[it][c] = prow[k < k_end ? k : k_end - 1];
+        mask |= (k < k_end ? 1u : 0u) << (8 * it + c);
       }
     }
   }
-  __device__ __forceinline__ void store(__bf16* __restrict__ S) const {
+  __device__ __forceinline__ void store(__bf16* __restrict__ S, bool tail) const {
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = threadIdx.x + it * THREADS;
-      if (ITEMS % THREADS != 0 && idx >= ITEMS) continue;
+      if (!ALL && idx >= ITEMS) continue;
       const int row = idx / K8, kq = (idx % K8) * 8;
-      *reinterpret_cast<bf16x8*>(&S[row * LDK + kq]) = to_bf16x8(r[it], (mask >> (8 * it)) & 0xFFu);
+      *reinterpret_cast<bf16x8*>(&S[row * LDK + kq]) =
+          tail ? to_bf16x8_masked(r[it], (mask >> (8 * it)) & 0xFFu) : to_bf16x8(r[it]);
     }
   }
 };
 
-// source has the tile's m/n index contiguous and the contraction index strided; item = (x, group of 8 k);
-// consecutive lanes take consecutive x, so every one of the 8 loads is coalesced
+// Source has the tile's m/n index (x) contiguous and the contraction index strided.  A thread
+// owns a group of 4 consecutive x by 8 consecutive k: eight 16-byte loads (one per k row),
+// regrouped in registers into four 8-k items.  Lanes take consecutive k-groups first, then
+// consecutive x-groups, so the LDS writes of 8 lanes cover all banks.  Without VEC (extent not
+// a multiple of 4, or unaligned) the same group is read by 32 scalar loads.
 template <int X, bool VEC>
 struct bl_xcontig {
-  static constexpr int ITEMS = X * K8;
-  static constexpr int NV = (ITEMS + THREADS - 1) / THREADS;
-  float r[NV][8];
-  uint32_t mask;
-  __device__ __forceinline__ void fetch(const float* __restrict__ src, int64_t ld, int64_t x0, int64_t n_x,
-                                        int64_t k0, int64_t k_end) {
-    mask = 0;
+  static constexpr int GROUPS = (X / 4) * K8;
+  static constexpr int NV = (GROUPS + THREADS - 1) / THREADS;
+  static constexpr bool ALL = GROUPS % THREADS == 0;
+  static constexpr int NX = VEC ? 1 : 4;
+  const float* base;       // first x of the tile at k = 0 (uniform)
+  int64_t ld;
+  uint32_t off[NV][NX];    // bytes from the slab's first k row to (first k of the group, clamped x)
+  float r[NV][8][4];       // [k][x]
+  uint32_t kmask[NV];      // partial slab only
+
+  __device__ __forceinline__ void init(const float* __restrict__ src, int64_t ld_, int64_t x0, int64_t n_x) {
+    base = src + x0;
+    ld = ld_;
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = threadIdx.x + it * THREADS;
-      const int x = idx % X, kq = (idx / X) * 8;
-      const bool in_tile = (ITEMS % THREADS == 0) || idx < ITEMS;
-      const int64_t gx = x0 + x;
-      const bool x_ok = in_tile && gx < n_x;
-      const float* p = src + (gx < n_x ? gx : n_x - 1);
+      const int kq = (idx % K8) * 8, xq = (idx / K8) * 4;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        const int64_t k = k0 + kq + c;
-        r[it][c] = p[(k < k_end ? k : k_end - 1) * ld];
-        mask |= ((x_ok && k < k_end) ? 1u : 0u) << (8 * it + c);
+      for (int c = 0; c < NX; ++c) {
+        const int64_t lim = n_x - x0 - (VEC ? 4 : 1);     // last legal start inside the matrix
+        const int64_t x = xq + c < lim ? xq + c : lim;
+        off[it][c] = (uint32_t)((kq * ld + x) * 4);
       }
     }
   }
-  __device__ __forceinline__ void store(__bf16* __restrict__ S) const {
+  __device__ __forceinline__ void fetch_full(int64_t k0) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const float* p = base + (k0 + kk) * ld;
+#pragma unroll
+      for (int it = 0; it < NV; ++it) {
+        if (!ALL && (int)threadIdx.x + it * THREADS >= GROUPS) continue;
+        if (VEC) {
+          const f32x4 v = ldg4(p, off[it][0]);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) r[it][kk][c] = v[c];
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) r[it][kk][c] = ldg1(p, off[it][c]);
+        }
+      }
+    }
+  }
+  __device__ __forceinline__ void fetch_tail(int64_t k0, int64_t k_end) {
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = threadIdx.x + it * THREADS;
-      if (ITEMS % THREADS != 0 && idx >= ITEMS) continue;
-      const int x = idx % X, kq = (idx / X) * 8;
-      *reinterpret_cast<bf16x8*>(&S[x * LDK + kq]) = to_bf16x8(r[it], (mask >> (8 * it)) & 0xFFu);
+      kmask[it] = 0;
+      if (!ALL && idx >= GROUPS) continue;
+      const int kq = (idx % K8) * 8;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const int64_t k = k0 + kq + kk;
+        kmask[it] |= (k < k_end ? 1u : 0u) << kk;
+        // row k (clamped), then the group's x offset without its k part
+        const float* p = base + (k < k_end ? k : k_end - 1) * ld - (int64_t)kq * ld;
+        if (VEC) {
+          const f32x4 v = ldg4(p, off[it][0]);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) r[it][kk][c] = v[c];
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) r[it][kk][c] = ldg1(p, off[it][c]);
+        }
+      }
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* __restrict__ S, bool tail) const {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      if (!ALL && idx >= GROUPS) continue;
+      const int kq = (idx % K8) * 8, xq = (idx / K8) * 4;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        float col[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) col[kk] = r[it][kk][c];
+        *reinterpret_cast<bf16x8*>(&S[(xq + c) * LDK + kq]) = tail ? to_bf16x8_masked(col, kmask[it]) : to_bf16x8(col);
+      }
     }
   }
 };
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE, bool VEC>
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS, 2)   // two wavefronts per SIMD: 256 registers each
 gemm_bf16_kernel(const gemm_args g) {
   static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -150,42 +241,57 @@ gemm_bf16_kernel(const gemm_args g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  loadA la;
-  loadB lb;
-  auto fetch = [&](int64_t k0) {
-    la.fetch(g.A, g.lda, m0, g.M, k0, k_end);
-    lb.fetch(g.B, g.ldb, n0, g.N, k0, k_end);
-  };
-
   if (k_begin < k_end) {
-    fetch(k_begin);
-    la.store(As);
-    lb.store(Bs);
-  }
-  __syncthreads();
-
-  for (int64_t k0 = k_begin; k0 < k_end; k0 += BKH) {
-    const bool more = k0 + BKH < k_end;
-    if (more) fetch(k0 + BKH);
+    loadA la;
+    loadB lb;
+    la.init(g.A, g.lda, m0, g.M);
+    lb.init(g.B, g.ldb, n0, g.N);
+    auto multiply = [&]() {
 #pragma unroll
-    for (int kk = 0; kk < BKH; kk += 16) {
-      bf16x8 a[MB], b[NB];
+      for (int kk = 0; kk < BKH; kk += 16) {
+        bf16x8 a[MB], b[NB];
 #pragma unroll
-      for (int i = 0; i < MB; ++i) a[i] = *reinterpret_cast<const bf16x8*>(&As[(wm0 + i * 32 + l32) * LDK + kk + kh * 8]);
+        for (int i = 0; i < MB; ++i) a[i] = *reinterpret_cast<const bf16x8*>(&As[(wm0 + i * 32 + l32) * LDK + kk + kh * 8]);
 #pragma unroll
-      for (int j = 0; j < NB; ++j) b[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn0 + j * 32 + l32) * LDK + kk + kh * 8]);
+        for (int j = 0; j < NB; ++j) b[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn0 + j * 32 + l32) * LDK + kk + kh * 8]);
 #pragma unroll
-      for (int i = 0; i < MB; ++i)
+        for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < NB; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    };
+    // complete slabs, software-pipelined: the loads of slab s+1 are in flight while slab s is multiplied
+    const int64_t n_full = (k_end - k_begin) / BKH;
+    if (n_full > 0) {
+      la.fetch_full(k_begin);
+      lb.fetch_full(k_begin);
+      la.store(As, false);
+      lb.store(Bs, false);
+      __syncthreads();
+      for (int64_t s = 1; s < n_full; ++s) {
+        la.fetch_full(k_begin + s * BKH);
+        lb.fetch_full(k_begin + s * BKH);
+        multiply();
+        __syncthreads();
+        la.store(As, false);
+        lb.store(Bs, false);
+        __syncthreads();
+      }
+      multiply();
+      __syncthreads();
     }
-    __syncthreads();
-    if (more) {
-      la.store(As);
-      lb.store(Bs);
+    // the partial slab at the end of the contraction, operands masked to zero past k_end
+    const int64_t k_tail = k_begin + n_full * BKH;
+    if (k_tail < k_end) {
+      la.fetch_tail(k_tail, k_end);
+      lb.fetch_tail(k_tail, k_end);
+      la.store(As, true);
+      lb.store(Bs, true);
+      __syncthreads();
+      multiply();
+      __syncthreads();
     }
-    __syncthreads();
   }
 
   // epilogue: same register layout as the fp32 32x32 MFMA; transposed through a per-wavefront
@@ -226,6 +332,7 @@ template <int BM, int BN, int WMS, int WNS, int MODE, bool VEC>
 int launch_v(gp_ctx* ctx, gemm_args& g, int splits) {
   const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (tiles > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
+  if (g.lda >= MAX_LD || g.ldb >= MAX_LD) return gp_fail(ctx, GP_BAD_ARG, "gemm (bf16): leading dimension above %lld", (long long)MAX_LD);
   dim3 grid((unsigned)tiles, (unsigned)splits, 1);
   static char name[48];
   if (!name[0]) snprintf(name, sizeof(name), "gemm_bf16_%s_%dx%d", MODE == MODE_NN ? "nn" : MODE == MODE_NT ? "nt" : "tn", BM, BN);
@@ -235,6 +342,7 @@ int launch_v(gp_ctx* ctx, gemm_args& g, int splits) {
   constexpr size_t lds_main = sizeof(__bf16) * (size_t)(BM + BN) * LDK;
   constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD;
   constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+  static_assert(lds <= 48 * 1024, "tile fits the default dynamic LDS limit");
   gemm_bf16_kernel<BM, BN, WMS, WNS, MODE, VEC><<<grid, THREADS, lds, ctx->stream>>>(g);
   GP_LAUNCH_CHECK(ctx, "gemm_bf16_kernel");
   return GP_OK;
@@ -242,14 +350,16 @@ int launch_v(gp_ctx* ctx, gemm_args& g, int splits) {
 
 template <int MODE>
 int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
-#define GP_BF16_LAUNCH(BN, WMS, WNS)                                                      \
-  do {                                                                                    \
-    if (g.vecA && g.vecB) return launch_v<128, BN, WMS, WNS, MODE, true>(ctx, g, splits); \
-    return launch_v<128, BN, WMS, WNS, MODE, false>(ctx, g, splits);                      \
+#define GP_BF16_LAUNCH(BM, BN, WMS, WNS)                                                 \
+  do {                                                                                   \
+    if (g.vecA && g.vecB) return launch_v<BM, BN, WMS, WNS, MODE, true>(ctx, g, splits); \
+    return launch_v<BM, BN, WMS, WNS, MODE, false>(ctx, g, splits);                      \
   } while (0)
-  if (g.N > 64) GP_BF16_LAUNCH(128, 2, 2);
-  if (g.N > 32) GP_BF16_LAUNCH(64, 2, 2);
-  GP_BF16_LAUNCH(32, 4, 1);
+  // the reduction over rows (TN) keeps the 128-row tiles its split plan was made for
+  if (MODE != MODE_TN && g.M >= 8192 && g.N > 64) GP_BF16_LAUNCH(256, 128, 2, 2);
+  if (g.N > 64) GP_BF16_LAUNCH(128, 128, 2, 2);
+  if (g.N > 32) GP_BF16_LAUNCH(128, 64, 2, 2);
+  GP_BF16_LAUNCH(128, 32, 4, 1);
 #undef GP_BF16_LAUNCH
 }
 
