@@ -189,7 +189,7 @@ def main():
         per_launch_ms = d["ms"] / d["launches"]
         if name.startswith("gemm_f32"):
             ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_f32"], "mfma"
-        elif name.startswith("gemm_bf16"):
+        elif name.startswith(("gemm_bf16", "tripG_mfma")):
             ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_bf16"], "mfma"
         elif name.startswith(ALU_KERNELS):
             ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["alu_f32"], "alu"

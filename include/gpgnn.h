@@ -110,6 +110,12 @@ int gp_triplets_fill(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const 
                      int64_t n_triplets, int32_t* idx_kj, int32_t* idx_ji, int32_t* seg_ptr_ji,
                      int32_t* perm_kj, int32_t* idx_ji_kj, int32_t* seg_ptr_kj);
 
+/* Largest row length ptr[i+1] - ptr[i], i < n, of a device-resident offsets array with n+1
+ * entries (e.g. the largest in-degree, for gp_graph.max_in_degree).  ws: device scratch of at
+ * least 4 bytes.  Synchronises the context's stream; *max_degree is a host variable. */
+int gp_csr_max_degree(gp_ctx* ctx, const int32_t* ptr, int64_t n, void* ws, size_t ws_bytes,
+                      int32_t* max_degree /*host*/);
+
 /* ------------------------------------------------------------------------------------------
  * Layer widths of one interaction block.
  */
@@ -152,6 +158,19 @@ typedef struct {
   const int32_t* seg_ptr_ji;   /* [E+1]        */
   const int32_t* idx_ji_kj;    /* [T] kj-major */
   const int32_t* seg_ptr_kj;   /* [E+1]        */
+  /* Optional lists by centre atom (the atom j shared by both edges of a triplet k->j->i); give
+   * all of them or leave n_atoms = 0.  With them, and bf16 GEMM operands selected in gp_dims,
+   * the bilinear block runs its triplet sums on the matrix cores.  They require what
+   * gp_edges_fill / gp_triplets_fill produce: edges sorted by target atom, and idx_kj of the
+   * segment of edge j->i equal to the in-edge rows of j in ascending order with at most the
+   * row coming from atom i left out.  max_in_degree must not be below the true maximum
+   * (atoms above it are skipped). */
+  int64_t n_atoms;
+  int32_t max_in_degree;       /* max over atoms of row_ptr[j+1] - row_ptr[j] */
+  int32_t reserved;
+  const int32_t* row_ptr;      /* [N+1] in-edges of atom j are edge rows row_ptr[j] .. row_ptr[j+1]-1 */
+  const int32_t* out_ptr;      /* [N+1] */
+  const int32_t* out_list;     /* [E] out_list[out_ptr[j] .. out_ptr[j+1]-1] = ids of the edges whose source is j */
 } gp_graph;
 
 typedef struct {

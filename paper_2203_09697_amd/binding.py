@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
     "gp_create", "gp_destroy", "gp_last_error", "gp_version",
     "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get", "gp_set_side_stream",
     "gp_edges_workspace", "gp_edges_count", "gp_edges_fill",
-    "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill",
+    "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill", "gp_csr_max_degree",
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
     "gp_block_forward_G", "gp_block_backward_G",
     "gp_energy_workspace", "gp_energy_forward", "gp_energy_backward",
@@ -66,7 +66,9 @@ class _Dims(C.Structure):
 
 class _Graph(C.Structure):
     _fields_ = [("n_edges", C.c_int64), ("n_triplets", C.c_int64), ("idx_kj", C.c_void_p),
-                ("seg_ptr_ji", C.c_void_p), ("idx_ji_kj", C.c_void_p), ("seg_ptr_kj", C.c_void_p)]
+                ("seg_ptr_ji", C.c_void_p), ("idx_ji_kj", C.c_void_p), ("seg_ptr_kj", C.c_void_p),
+                ("n_atoms", C.c_int64), ("max_in_degree", C.c_int32), ("reserved", C.c_int32),
+                ("row_ptr", C.c_void_p), ("out_ptr", C.c_void_p), ("out_list", C.c_void_p)]
 
 
 class _Basis(C.Structure):
@@ -100,7 +102,10 @@ def Graph(g):
     """gp_graph from the dict returned by build_graph / gp_triplets."""
     return _Graph(n_edges=g["n_edges"], n_triplets=g["n_triplets"], idx_kj=_ptr(g["idx_kj"]),
                   seg_ptr_ji=_ptr(g["seg_ptr_ji"]), idx_ji_kj=_ptr(g.get("idx_ji_kj")),
-                  seg_ptr_kj=_ptr(g.get("seg_ptr_kj")))
+                  seg_ptr_kj=_ptr(g.get("seg_ptr_kj")),
+                  n_atoms=g.get("n_atoms", 0) if g.get("out_list") is not None else 0,
+                  max_in_degree=g.get("max_in_degree", 0), reserved=0, row_ptr=_ptr(g.get("row_ptr")),
+                  out_ptr=_ptr(g.get("out_ptr")), out_list=_ptr(g.get("out_list")))
 
 
 def Basis(b):
@@ -247,7 +252,28 @@ def gp_triplets(ctx, edges, with_kj=True):
     ctx.check(lib.gp_triplets_fill(*args, C.c_int64(T), _ptr(out["idx_kj"]), _ptr(out["idx_ji"]),
                                    _ptr(out["seg_ptr_ji"]), _ptr(out.get("perm_kj")), _ptr(out.get("idx_ji_kj")),
                                    _ptr(out.get("seg_ptr_kj"))))
+    if with_kj and E > 0:
+        # lists by centre atom (optional members of gp_graph)
+        out_ptr, out_list = gp_edges_by_source(ctx, edges)
+        md = C.c_int32()
+        ctx.check(lib.gp_csr_max_degree(ctx._h, _ptr(edges["row_ptr"]), C.c_int64(N), _ptr(ws), C.c_size_t(ws.numel()),
+                                        C.byref(md)))
+        out.update(n_atoms=N, row_ptr=edges["row_ptr"], out_ptr=out_ptr, out_list=out_list, max_in_degree=md.value)
     return out
+
+
+def gp_edges_by_source(ctx, edges):
+    """out_ptr[N+1], out_list[E]: ids of the edges grouped by source atom."""
+    lib = load()
+    N, E = edges["n_atoms"], edges["n_edges"]
+    nb = C.c_size_t()
+    ctx.check(lib.gp_edges_by_source_workspace(C.c_int64(N), C.c_int64(E), C.byref(nb)))
+    ws = torch.empty(max(nb.value, 8), dtype=torch.uint8, device=ctx.device)
+    out_ptr = torch.empty(N + 1, dtype=torch.int32, device=ctx.device)
+    out_list = torch.empty(E, dtype=torch.int32, device=ctx.device)
+    ctx.check(lib.gp_edges_by_source(ctx._h, _ptr(edges["src"]), C.c_int64(N), C.c_int64(E), _ptr(ws),
+                                     C.c_size_t(ws.numel()), _ptr(out_ptr), _ptr(out_list)))
+    return out_ptr, out_list
 
 
 def build_graph(ctx, pos, graph_ptr, cutoff, max_neighbors=0):

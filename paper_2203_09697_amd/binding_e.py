@@ -46,17 +46,7 @@ def gp_energy_backward(ctx, emb, hidden, w, dst, n_atoms, saved, grad_m, grad_w,
     return grad_m
 
 
-def gp_edges_by_source(ctx, edges):
-    lib = B.load()
-    N, E = edges["n_atoms"], edges["n_edges"]
-    nb = C.c_size_t()
-    ctx.check(lib.gp_edges_by_source_workspace(C.c_int64(N), C.c_int64(E), C.byref(nb)))
-    ws = torch.empty(max(nb.value, 8), dtype=torch.uint8, device=ctx.device)
-    out_ptr = torch.empty(N + 1, dtype=torch.int32, device=ctx.device)
-    out_list = torch.empty(E, dtype=torch.int32, device=ctx.device)
-    ctx.check(lib.gp_edges_by_source(ctx._h, B._ptr(edges["src"]), C.c_int64(N), C.c_int64(E), B._ptr(ws),
-                                     C.c_size_t(ws.numel()), B._ptr(out_ptr), B._ptr(out_list)))
-    return out_ptr, out_list
+gp_edges_by_source = B.gp_edges_by_source
 
 
 def gp_forces_from_basis_grad(ctx, dims, edges, trip, out_ptr, out_list, grad_rbf, grad_cos_kj, forces, ws):

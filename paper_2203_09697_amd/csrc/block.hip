@@ -163,7 +163,7 @@ int gp_block_workspace(const gp_dims* dims, int64_t n_edges, int64_t n_triplets,
   }
   if (dims->variant == GP_VARIANT_G) {
     *saved_bytes = gp_block_G_saved_bytes(dims, n_edges);
-    *scratch_bytes = gp_block_G_scratch_bytes(dims, n_edges);
+    *scratch_bytes = gp_block_G_scratch_bytes(dims, n_edges, n_triplets);
     return GP_OK;
   }
   return GP_UNSUPPORTED_DIMS;

@@ -52,6 +52,8 @@ struct scratch_G {
   float* part;
   float* part_aux;   // split-K partials of the GEMMs issued on the side stream
   size_t part_bytes;
+  void* ybuf;        // per-triplet y in bf16 for the matrix-core triplet kernels (bf16 blocks only)
+  size_t ybytes;
 };
 
 size_t part_bytes_G(const gp_dims* d, int64_t E) {
@@ -66,7 +68,7 @@ size_t part_bytes_G(const gp_dims* d, int64_t E) {
   return m;
 }
 
-size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, scratch_G* s) {
+size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, int64_t T, scratch_G* s) {
   gp_carver c(p);
   const size_t H = d->emb, F = d->int_emb, C = d->emb_cbf, O = d->emb_bil, S = d->num_spherical, R = d->num_radial;
   for (int i = 0; i < 4; ++i) s->eh[i] = c.take<float>(E * H);
@@ -84,6 +86,8 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, scratch_G* s) {
   s->part_bytes = part_bytes_G(d, E);
   s->part = (float*)c.take<char>(s->part_bytes);
   s->part_aux = (float*)c.take<char>(s->part_bytes);
+  s->ybytes = d->dtype == GP_BF16_F32ACC ? gp_tripG_mfma_scratch(E, T) : 0;
+  s->ybuf = c.take<char>(s->ybytes);
   return c.off;
 }
 
@@ -113,9 +117,9 @@ size_t gp_block_G_saved_bytes(const gp_dims* d, int64_t E) {
   saved_G s;
   return carve_saved_G(nullptr, d, E, &s);
 }
-size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E) {
+size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E, int64_t T) {
   scratch_G s;
-  return carve_scratch_G(nullptr, d, E, &s);
+  return carve_scratch_G(nullptr, d, E, T, &s);
 }
 
 extern "C" {
@@ -135,7 +139,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   saved_G s;
   scratch_G sc;
   if (saved_bytes < carve_saved_G(saved, dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: saved buffer too small");
-  if (scratch_bytes < carve_scratch_G(scratch, dims, E, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: scratch too small");
+  if (scratch_bytes < carve_scratch_G(scratch, dims, E, graph->n_triplets, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: scratch too small");
   GP_HIP(ctx, hipSetDevice(ctx->device));
   gp_bf16_scope gemm_dtype(ctx, dims->dtype == GP_BF16_F32ACC);
   const int H = dims->emb, F = dims->int_emb, C = dims->emb_cbf, O = dims->emb_bil, S = dims->num_spherical,
@@ -154,7 +158,10 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   GP_TRY(gp_permute3(ctx, w->W_c, S, R, C, 0, 2, 1, s.WcT));                        // WcT[(l,c), n]
   e = gp_epilogue(); e.out = s.Radt;
   GP_TRY(gp_gemm_nt(ctx, s.WcT, g, S * C, (int)E, R, e));                           // Radt[(l,c), e]
-  GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
+  if (dims->dtype == GP_BF16_F32ACC && gp_tripG_mfma_usable(graph, F, S, C))
+    GP_TRY(gp_tripG_forward_mfma(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes));
+  else
+    GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
   e = gp_epilogue(); e.out = s.z;
   GP_TRY(gp_gemm_nn(ctx, s.A, w->W_bil, E, O, C * F, e));                           // z
   float* t_skip = sc.eh[0];
@@ -181,7 +188,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   saved_G s;
   scratch_G sc;
   if (saved_bytes < carve_saved_G(const_cast<void*>(saved), dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: saved buffer too small");
-  if (scratch_bytes < carve_scratch_G(scratch, dims, E, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: scratch too small");
+  if (scratch_bytes < carve_scratch_G(scratch, dims, E, graph->n_triplets, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: scratch too small");
   GP_HIP(ctx, hipSetDevice(ctx->device));
   gp_bf16_scope gemm_dtype(ctx, dims->dtype == GP_BF16_F32ACC);
   const int H = dims->emb, F = dims->int_emb, C = dims->emb_cbf, O = dims->emb_bil, S = dims->num_spherical,

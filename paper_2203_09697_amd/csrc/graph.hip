@@ -276,9 +276,47 @@ inline size_t carve_triplets(void* p, int64_t n_atoms, int64_t n_edges, triplets
 
 inline int blocks_for(int64_t n, int per_block) { return (int)((n + per_block - 1) / per_block); }
 
+// largest ptr[i+1] - ptr[i]; one workgroup
+__global__ void __launch_bounds__(1024)
+max_degree_kernel(const int32_t* __restrict__ ptr, int64_t n, int32_t* __restrict__ out) {
+  __shared__ int red[16];
+  int m = 0;
+  for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
+    const int d = ptr[i + 1] - ptr[i];
+    m = d > m ? d : m;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const int v = __shfl_xor(m, o, 64);
+    m = v > m ? v : m;
+  }
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < (int)(blockDim.x >> 6); ++w) m = red[w] > m ? red[w] : m;
+    *out = m;
+  }
+}
+
 }  // namespace
 
 extern "C" {
+
+int gp_csr_max_degree(gp_ctx* ctx, const int32_t* ptr, int64_t n, void* ws, size_t ws_bytes, int32_t* max_degree) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, max_degree, "gp_csr_max_degree: max_degree is NULL");
+  GP_REQUIRE(ctx, n >= 0, "gp_csr_max_degree: negative size");
+  *max_degree = 0;
+  if (n == 0) return GP_OK;
+  GP_REQUIRE(ctx, ptr && ws, "gp_csr_max_degree: NULL pointer");
+  if (ws_bytes < sizeof(int32_t)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_csr_max_degree: workspace below 4 bytes");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  max_degree_kernel<<<1, 1024, 0, ctx->stream>>>(ptr, n, static_cast<int32_t*>(ws));
+  GP_LAUNCH_CHECK(ctx, "max_degree_kernel");
+  GP_HIP(ctx, hipMemcpyAsync(max_degree, ws, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return GP_OK;
+}
 
 int gp_edges_workspace(int64_t n_atoms, size_t* bytes) {
   if (!bytes || n_atoms < 0) return GP_BAD_ARG;

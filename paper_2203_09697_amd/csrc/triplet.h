@@ -30,7 +30,7 @@ int gp_tripD_weight_grads(gp_ctx* ctx, const float* grad_a, const float* Bacc, c
 
 // workspace sizes of the variant-G block (block_G.hip)
 size_t gp_block_G_saved_bytes(const gp_dims* d, int64_t E);
-size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E);
+size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E, int64_t T);
 
 // ---- variant G (bilinear interaction, Sec. 3.4) ---------------------------------------------
 // The forward accumulator A[e,c,f] = sum_t y_t[c] x[kj(t),f], y_t[c] = sum_l Y_l(t) Rad[kj(t),l,c],
@@ -53,6 +53,13 @@ int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, i
 // grad_cos_kj[q] (+)= sum_l Y_l0'(cos_alpha_kj[q]) sum_o dz[ji(q), o] U[kj(q), l, o]   (kj-major order)
 int gp_tripG_grad_cos(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* U, const float* dz,
                       int O, int S, int accumulate, float* grad_cos_kj);
+// Matrix-core form of the forward accumulator A (triplet_g_mfma.hip), bf16 operands: usable when
+// the graph carries its lists by centre atom and the widths fit (F a multiple of 32 up to 128,
+// C <= 16, one atom's rows of x fit in LDS); ybuf is scratch of gp_tripG_mfma_scratch bytes.
+bool gp_tripG_mfma_usable(const gp_graph* g, int F, int S, int C);
+size_t gp_tripG_mfma_scratch(int64_t E, int64_t T);
+int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
+                          int F, int S, int C, float* A, void* ybuf, size_t ybytes);
 // 16-byte vectorised streaming kernels (triplet_stream.hip); return 1 if they handled the call
 int gp_stream_fwd_fast(gp_ctx* ctx, const gp_graph* g, int F, const float* x, const float* s, float* a);
 int gp_stream_bwd_fast(gp_ctx* ctx, const gp_graph* g, const int32_t* perm_kj, int F, const float* x, const float* s,

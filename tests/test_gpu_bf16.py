@@ -59,3 +59,12 @@ def test_block_G_bf16_cfg3_shape_one_structure(lib, ctx):
 def test_block_G_bf16_cfg4_widths_small_graph(lib, ctx):
     w = synth.get_workload("cfg4", cutoff=6.0)
     _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3), tol=2e-2)
+
+
+def test_block_G_bf16_narrow_cbf_eight_spherical(lib, ctx):
+    # emb_cbf below the 16 rows an edge occupies in a matrix-core tile, num_spherical = 8, trip width 32;
+    # capped neighbour lists make some edges one-directional (no row left out of their segments)
+    from dataclasses import replace
+    w = replace(synth.get_workload("cfg3", emb=64, int_emb=32, emb_rbf=8, emb_cbf=5, emb_bil=16, num_radial=16,
+                                   num_spherical=8), max_neighbors=12)
+    _parity(lib, ctx, w, 3, 1, synth.slab_adsorbate_positions(2, 4, 4, 3, 10, seed=5), tol=2e-2)
