@@ -52,6 +52,13 @@ const char* gp_version(void);
  * at a time; the environment variable GP_NO_AUX_STREAM=1 has the same effect at gp_create. */
 int gp_set_side_stream(gp_ctx* ctx, int on);
 
+/* Triplet sums of the bilinear block (Sec. 3.4) with bf16 GEMM operands selected: when gp_graph
+ * carries its lists by centre atom they can run as dense products per centre atom on the matrix
+ * cores.  mode 1: whenever the widths allow; 0: never (one wavefront per edge on the vector
+ * units); -1 (default): only for graphs with at least 96 triplets per edge on average, where the
+ * dense form pays.  GP_TRIPLET_MFMA=0/1 in the environment sets the mode at gp_create. */
+int gp_set_triplet_mfma(gp_ctx* ctx, int mode);
+
 /* Measurement aid (not a step of the method): while enabled, every kernel launch the library
  * issues on this context is bracketed by two HIP events on the context's stream.
  * gp_profile_get(i) synchronises on launch i and returns its kernel name (static string),
@@ -163,11 +170,11 @@ typedef struct {
    * the bilinear block runs its triplet sums on the matrix cores.  They require what
    * gp_edges_fill / gp_triplets_fill produce: edges sorted by target atom, and idx_kj of the
    * segment of edge j->i equal to the in-edge rows of j in ascending order with at most the
-   * row coming from atom i left out.  max_in_degree must not be below the true maximum
-   * (atoms above it are skipped). */
+   * row coming from atom i left out.  max_in_degree / max_out_degree must not be below the true
+   * maxima (atoms above them are skipped). */
   int64_t n_atoms;
   int32_t max_in_degree;       /* max over atoms of row_ptr[j+1] - row_ptr[j] */
-  int32_t reserved;
+  int32_t max_out_degree;      /* max over atoms of out_ptr[j+1] - out_ptr[j] */
   const int32_t* row_ptr;      /* [N+1] in-edges of atom j are edge rows row_ptr[j] .. row_ptr[j+1]-1 */
   const int32_t* out_ptr;      /* [N+1] */
   const int32_t* out_list;     /* [E] out_list[out_ptr[j] .. out_ptr[j+1]-1] = ids of the edges whose source is j */

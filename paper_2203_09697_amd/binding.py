@@ -6,7 +6,8 @@ import torch
 
 __all__ = [
     "GpError", "load", "library_path", "Context", "Dims", "Graph", "Basis",
-    "gp_version", "gp_profile_enable", "gp_profile_reset", "gp_profile_collect", "gp_set_side_stream", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
+    "gp_version", "gp_profile_enable", "gp_profile_reset", "gp_profile_collect", "gp_set_side_stream", "gp_set_triplet_mfma",
+    "gp_edges_by_source", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
     "gp_block_forward_D", "gp_block_backward_D", "gp_triplet_aggregate_fwd",
     "gp_triplet_aggregate_bwd", "gp_linear_forward", "build_graph", "weights_to_device",
     "EXPORTED_SYMBOLS", "D_WEIGHT_ORDER",
@@ -21,7 +22,7 @@ STATUS = {0: "GP_OK", -1: "GP_BAD_ARG", -2: "GP_BUFFER_TOO_SMALL", -3: "GP_INT32
 
 EXPORTED_SYMBOLS = [
     "gp_create", "gp_destroy", "gp_last_error", "gp_version",
-    "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get", "gp_set_side_stream",
+    "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get", "gp_set_side_stream", "gp_set_triplet_mfma",
     "gp_edges_workspace", "gp_edges_count", "gp_edges_fill",
     "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill", "gp_csr_max_degree",
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
@@ -67,7 +68,7 @@ class _Dims(C.Structure):
 class _Graph(C.Structure):
     _fields_ = [("n_edges", C.c_int64), ("n_triplets", C.c_int64), ("idx_kj", C.c_void_p),
                 ("seg_ptr_ji", C.c_void_p), ("idx_ji_kj", C.c_void_p), ("seg_ptr_kj", C.c_void_p),
-                ("n_atoms", C.c_int64), ("max_in_degree", C.c_int32), ("reserved", C.c_int32),
+                ("n_atoms", C.c_int64), ("max_in_degree", C.c_int32), ("max_out_degree", C.c_int32),
                 ("row_ptr", C.c_void_p), ("out_ptr", C.c_void_p), ("out_list", C.c_void_p)]
 
 
@@ -104,7 +105,7 @@ def Graph(g):
                   seg_ptr_ji=_ptr(g["seg_ptr_ji"]), idx_ji_kj=_ptr(g.get("idx_ji_kj")),
                   seg_ptr_kj=_ptr(g.get("seg_ptr_kj")),
                   n_atoms=g.get("n_atoms", 0) if g.get("out_list") is not None else 0,
-                  max_in_degree=g.get("max_in_degree", 0), reserved=0, row_ptr=_ptr(g.get("row_ptr")),
+                  max_in_degree=g.get("max_in_degree", 0), max_out_degree=g.get("max_out_degree", 0), row_ptr=_ptr(g.get("row_ptr")),
                   out_ptr=_ptr(g.get("out_ptr")), out_list=_ptr(g.get("out_list")))
 
 
@@ -179,6 +180,10 @@ def gp_version():
 
 def gp_profile_enable(ctx, on):
     ctx.check(load().gp_profile_enable(ctx._h, C.c_int(1 if on else 0)))
+
+
+def gp_set_triplet_mfma(ctx, mode):
+    ctx.check(load().gp_set_triplet_mfma(ctx._h, C.c_int(mode)))
 
 
 def gp_set_side_stream(ctx, on):
@@ -258,7 +263,10 @@ def gp_triplets(ctx, edges, with_kj=True):
         md = C.c_int32()
         ctx.check(lib.gp_csr_max_degree(ctx._h, _ptr(edges["row_ptr"]), C.c_int64(N), _ptr(ws), C.c_size_t(ws.numel()),
                                         C.byref(md)))
-        out.update(n_atoms=N, row_ptr=edges["row_ptr"], out_ptr=out_ptr, out_list=out_list, max_in_degree=md.value)
+        mo = C.c_int32()
+        ctx.check(lib.gp_csr_max_degree(ctx._h, _ptr(out_ptr), C.c_int64(N), _ptr(ws), C.c_size_t(ws.numel()), C.byref(mo)))
+        out.update(n_atoms=N, row_ptr=edges["row_ptr"], out_ptr=out_ptr, out_list=out_list, max_in_degree=md.value,
+                   max_out_degree=mo.value)
     return out
 
 

@@ -24,6 +24,8 @@ int gp_create(gp_ctx** out, int device_id, void* hip_stream) {
     c->aux_stream = nullptr;
   const char* no_aux = getenv("GP_NO_AUX_STREAM");
   c->use_aux = !(no_aux && no_aux[0] == '1');
+  const char* tm = getenv("GP_TRIPLET_MFMA");
+  if (tm && (tm[0] == '0' || tm[0] == '1')) c->trip_mfma = tm[0] - '0';
   *out = c;
   return GP_OK;
 }
@@ -43,6 +45,12 @@ void gp_destroy(gp_ctx* ctx) {
 int gp_set_side_stream(gp_ctx* ctx, int on) {
   if (!ctx) return GP_BAD_ARG;
   ctx->use_aux = on != 0;
+  return GP_OK;
+}
+
+int gp_set_triplet_mfma(gp_ctx* ctx, int mode) {
+  if (!ctx || mode < -1 || mode > 1) return GP_BAD_ARG;
+  ctx->trip_mfma = mode;
   return GP_OK;
 }
 

@@ -104,6 +104,13 @@ int check_dims_G(gp_ctx* ctx, const gp_dims* d) {
   return GP_OK;
 }
 
+// the dense per-centre-atom form pays once an edge has about a hundred triplets
+bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
+  if (d->dtype != GP_BF16_F32ACC || ctx->trip_mfma == 0) return false;
+  if (ctx->trip_mfma == 1) return true;
+  return g->n_edges > 0 && (double)g->n_triplets >= 96.0 * (double)g->n_edges;
+}
+
 int check_weights_G(gp_ctx* ctx, const gp_weights_G* w, const char* what) {
   GP_REQUIRE(ctx, w, "%s is NULL", what);
   GP_REQUIRE(ctx, w->W_ba && w->W_rbfS && w->W_rbfB && w->W_down && w->W_c && w->W_bil && w->W_up && w->W_skip,
@@ -158,7 +165,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   GP_TRY(gp_permute3(ctx, w->W_c, S, R, C, 0, 2, 1, s.WcT));                        // WcT[(l,c), n]
   e = gp_epilogue(); e.out = s.Radt;
   GP_TRY(gp_gemm_nt(ctx, s.WcT, g, S * C, (int)E, R, e));                           // Radt[(l,c), e]
-  if (dims->dtype == GP_BF16_F32ACC && gp_tripG_mfma_usable(graph, F, S, C))
+  if (want_trip_mfma(ctx, dims, graph) && gp_tripG_mfma_usable(graph, F, S, C))
     GP_TRY(gp_tripG_forward_mfma(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes));
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
@@ -208,8 +215,12 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(gp_gemm_nt(ctx, d_skip, w->W_skip, E, H, H, e));                           // dm (skip path)
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part_aux, sc.part_bytes); }, {}));
   // one pass over the triplets (kj-major): H[e', l, o]
-  GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, nullptr, nullptr, nullptr, sc.dz, nullptr, O, S, 1,
-                           sc.Hd, nullptr));
+  const bool bwd_mfma = want_trip_mfma(ctx, dims, graph) && gp_tripG_mfma_bwd_usable(graph, O, S);
+  if (bwd_mfma)
+    GP_TRY(gp_tripG_backward_H_mfma(ctx, graph, basis->cos_alpha_kj, sc.dz, O, S, sc.Hd));
+  else
+    GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, nullptr, nullptr, nullptr, sc.dz, nullptr, O, S, 1,
+                             sc.Hd, nullptr));
   GP_TRY(gp_tripG_edge_G(ctx, s.Radt, sc.Hd, E, S, C, O, sc.Gm));                   // G[e', (c,o)]
   GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                   // [(c,o), f]
   e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
@@ -220,7 +231,10 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(gp_tripG_edge_dRad(ctx, sc.V, sc.Hd, E, S, C, O, sc.dRad));                // dRad[e', (l,c)]
   if (grad_cos_kj && graph->n_triplets > 0) {
     GP_TRY(gp_tripG_edge_U(ctx, s.Radt, sc.V, E, S, C, O, sc.U));
-    GP_TRY(gp_tripG_grad_cos(ctx, graph, basis->cos_alpha_kj, sc.U, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj));
+    if (bwd_mfma)
+      GP_TRY(gp_tripG_grad_cos_mfma(ctx, graph, basis->cos_alpha_kj, sc.U, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj));
+    else
+      GP_TRY(gp_tripG_grad_cos(ctx, graph, basis->cos_alpha_kj, sc.U, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj));
   }
   GP_TRY(gp_gemm_tn(ctx, g, sc.dRad, E, R, S * C, sc.dWcP, nullptr, sc.part, sc.part_bytes));   // [n, (l,c)]
   GP_TRY(gp_permute3(ctx, sc.dWcP, R, S, C, 1, 0, 2, gw->W_c));                     // -> [l, n, c]

@@ -25,6 +25,7 @@ struct gp_ctx {
   bool gemm_bf16 = false;   // set by a block call whose dims ask for bf16 GEMM operands
   hipStream_t aux_stream = nullptr;   // side stream for weight-gradient GEMMs (see aux_stream.h)
   bool use_aux = true;
+  int trip_mfma = -1;       // matrix-core triplet kernels of the bilinear block: -1 by graph density, 0 never, 1 whenever usable
   std::vector<hipEvent_t> aux_event_pool;
   std::vector<gp_prof_entry> prof;
   std::vector<hipEvent_t> event_pool;

@@ -408,6 +408,9 @@ int dispatch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
   if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
   return launch_gemm<128, 32, 4, 1, MODE>(ctx, g, splits);
 #endif
+#ifdef GP_GEMM_DEBUG_BN64
+  if (MODE != MODE_TN && g.N > 64) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
+#endif
   if (g.N > 64) return launch_gemm<TILE_BM, 128, 2, 2, MODE>(ctx, g, splits);
   if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
   return launch_gemm<TILE_BM, 32, 4, 1, MODE>(ctx, g, splits);

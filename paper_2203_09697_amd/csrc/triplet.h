@@ -60,6 +60,12 @@ bool gp_tripG_mfma_usable(const gp_graph* g, int F, int S, int C);
 size_t gp_tripG_mfma_scratch(int64_t E, int64_t T);
 int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
                           int F, int S, int C, float* A, void* ybuf, size_t ybytes);
+// Matrix-core forms of H[e',l,o] and of grad_cos (kj-major), same conditions on the graph; O a multiple of 32 up to 128
+bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S);
+int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S,
+                             float* H);
+int gp_tripG_grad_cos_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* U, const float* dz,
+                           int O, int S, int accumulate, float* grad_cos_kj);
 // 16-byte vectorised streaming kernels (triplet_stream.hip); return 1 if they handled the call
 int gp_stream_fwd_fast(gp_ctx* ctx, const gp_graph* g, int F, const float* x, const float* s, float* a);
 int gp_stream_bwd_fast(gp_ctx* ctx, const gp_graph* g, const int32_t* perm_kj, int F, const float* x, const float* s,

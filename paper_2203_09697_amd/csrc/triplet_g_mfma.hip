@@ -36,8 +36,8 @@ constexpr int ST = 8;        // max num_spherical
 constexpr int CP = 16;       // rows per edge in an MFMA tile = max emb_cbf
 constexpr int PARTS = 8;     // at most this many workgroups share one centre atom
 constexpr int EPP = 64;      // target edges per workgroup
-constexpr int YT = 256;      // threads of the y kernel
-constexpr int MT = 512;      // threads of the contraction kernel
+constexpr int YT = 256;      // most threads of the y kernel (one per position of the longest row, rounded to 64)
+constexpr int MT = 512;      // most threads of the contraction kernel
 constexpr int KU = 4;        // k-steps of A fragments loaded ahead
 constexpr size_t LDS_MAX = 160 * 1024;
 
@@ -85,7 +85,7 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
   __shared__ int s_e[64], s_seg[64], s_cnt[64], s_gap[64];
   const int n_pg = P.Kp / 8;
   const int cp = threadIdx.x & 7;
-  for (int pg0 = 0; pg0 < n_pg; pg0 += YT / 8) {
+  for (int pg0 = 0; pg0 < n_pg; pg0 += (int)(blockDim.x >> 3)) {
     const int pg = pg0 + (threadIdx.x >> 3);
     const bool active = pg < n_pg;
     float rad[SM][2][8];
@@ -120,30 +120,47 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
       __syncthreads();
       const int n = P.ee - c0 < 64 ? P.ee - c0 : 64;
       if (!active) continue;
-      for (int ei = 0; ei < n; ++ei) {
-        const int e = s_e[ei], seg = s_seg[ei], cnt = s_cnt[ei], gap = s_gap[ei];
-        float y[2][8];
+      // cosines of the 8 positions for edge ei of the chunk (0 and an unset mask bit where there is no triplet)
+      auto load_cos = [&](int ei, float (&cs)[8], unsigned& vmask) {
+        const int seg = s_seg[ei], cnt = s_cnt[ei], gap = s_gap[ei];
+        vmask = 0;
 #pragma unroll
         for (int pi = 0; pi < 8; ++pi) {
           const int p = 8 * pg + pi;
           const int q = p - (p > gap ? 1 : 0);
           const bool valid = p != gap && q < cnt;
-          const float cs = valid ? cos_alpha[seg + q] : 0.f;
-          float p0 = 1.f, p1 = cs;
+          cs[pi] = valid ? cos_alpha[seg + q] : 0.f;
+          vmask |= (valid ? 1u : 0u) << pi;
+        }
+      };
+      float cs_next[8];
+      unsigned vm_next;
+      load_cos(0, cs_next, vm_next);
+      for (int ei = 0; ei < n; ++ei) {
+        float cs[8];
+        const unsigned vm = vm_next;
+#pragma unroll
+        for (int pi = 0; pi < 8; ++pi) cs[pi] = cs_next[pi];
+        if (ei + 1 < n) load_cos(ei + 1, cs_next, vm_next);   // in flight during the arithmetic below
+        float y[2][8];
+#pragma unroll
+        for (int pi = 0; pi < 8; ++pi) {
+          float p0 = 1.f, p1 = cs[pi];
           float a0 = Y_NORM_M[0] * rad[0][0][pi], a1 = Y_NORM_M[0] * rad[0][1][pi];
 #pragma unroll
           for (int l = 1; l < SM; ++l) {
             const float yl = Y_NORM_M[l] * p1;
             a0 += yl * rad[l][0][pi];
             a1 += yl * rad[l][1][pi];
-            const float p2 = ((float)(2 * l + 1) * cs * p1 - (float)l * p0) * (1.0f / (float)(l + 1));
+            const float p2 = ((float)(2 * l + 1) * cs[pi] * p1 - (float)l * p0) * (1.0f / (float)(l + 1));
             p0 = p1;
             p1 = p2;
           }
+          const bool valid = (vm >> pi) & 1u;
           y[0][pi] = valid ? a0 : 0.f;
           y[1][pi] = valid ? a1 : 0.f;
         }
-        __bf16* dst = Yb + y_offset(seg, e) + (int64_t)pg * (CP * 8) + (2 * cp) * 8;
+        __bf16* dst = Yb + y_offset(s_seg[ei], s_e[ei]) + (int64_t)pg * (CP * 8) + (2 * cp) * 8;
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
           bf16x8 v;
@@ -174,7 +191,7 @@ tripG_mfma_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
   // stage X_j: a wavefront takes a tile of 16 positions x 32 features; a lane converts two rows of
   // 4 features and writes 4 packed position pairs
   const int tiles_p = P.Kp / 16;
-  for (int t = wave; t < tiles_p * CB; t += MT / 64) {
+  for (int t = wave; t < tiles_p * CB; t += (int)(blockDim.x >> 6)) {
     const int pp = (t % tiles_p) * 8 + (lane & 7), fq = (t / tiles_p) * 8 + (lane >> 3);
     const int p0 = 2 * pp;
     f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
@@ -193,7 +210,7 @@ tripG_mfma_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
   const int kh = lane >> 5, l32 = lane & 31;
   const int nks = P.Kp / 16;
   const int n_e = P.ee - P.eb;
-  for (int grp = wave; grp * 4 < n_e; grp += MT / 64) {
+  for (int grp = wave; grp * 4 < n_e; grp += (int)(blockDim.x >> 6)) {
     int e4[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -265,7 +282,278 @@ tripG_mfma_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
   }
 }
 
+// ---- backward (kj-major): rows are the in-edges of the centre atom, the sum runs over its out-edges ----
+//
+// For in-edge row p of atom j (edge e' = r0 + p) the kj-major segment lists the out-edges of j in
+// the order of out_list, with (at most) the edge that returns to the source atom of e' left out.
+struct rowinfo_t {
+  int seg, cnt, gap;
+};
+
+__device__ __forceinline__ rowinfo_t row_info(const int32_t* __restrict__ seg_ptr_kj, const int32_t* __restrict__ idx_ji_kj,
+                                              const int32_t* __restrict__ outs, int e) {
+  rowinfo_t r;
+  r.seg = seg_ptr_kj[e];
+  r.cnt = seg_ptr_kj[e + 1] - r.seg;
+  int lo = 0, hi = r.cnt;   // first slot whose target edge is not the out-edge at the same position
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (idx_ji_kj[r.seg + mid] == outs[mid]) lo = mid + 1;
+    else hi = mid;
+  }
+  r.gap = lo;
+  return r;
+}
+
+// Share of a workgroup: centre atom j, `per` row groups of 8 in-edge rows each from group gb on
+struct rows_t {
+  int r0, d, o0, dout, gb, ge;
+};
+constexpr int GPW = 8;   // row groups per workgroup aimed at (two per wavefront)
+
+__device__ __forceinline__ bool centre_rows(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
+                                            rows_t& P) {
+  const int j = blockIdx.x / PARTS, part = blockIdx.x % PARTS;
+  P.r0 = row_ptr[j];
+  P.d = row_ptr[j + 1] - P.r0;
+  P.o0 = out_ptr[j];
+  P.dout = out_ptr[j + 1] - P.o0;
+  if (P.d <= 0) return false;
+  const int groups = (P.d + 7) / 8;
+  int nparts = (groups + GPW - 1) / GPW;
+  nparts = nparts < PARTS ? nparts : PARTS;
+  if (part >= nparts) return false;
+  const int len = (groups + nparts - 1) / nparts;
+  P.gb = part * len;
+  P.ge = P.gb + len < groups ? P.gb + len : groups;
+  return P.gb < P.ge;
+}
+
+// Y_l0(x) = x^(l%2) (q0 + q1 x^2 + q2 x^4 + q3 x^6): Legendre polynomials in even/odd form,
+// normalised by sqrt((2l+1)/(4 pi))
+__device__ __constant__ float LEG_Q[ST][4] = {
+    {1.f, 0.f, 0.f, 0.f},
+    {1.f, 0.f, 0.f, 0.f},
+    {-0.5f, 1.5f, 0.f, 0.f},
+    {-1.5f, 2.5f, 0.f, 0.f},
+    {0.375f, -3.75f, 4.375f, 0.f},
+    {1.875f, -8.75f, 7.875f, 0.f},
+    {-0.3125f, 6.5625f, -19.6875f, 14.4375f},
+    {-2.1875f, 19.6875f, -43.3125f, 26.8125f}};
+
+// H[e', l, o] = sum_{t: kj(t)=e'} Y_l0(cos alpha_t) dz[ji(t), o].  MFMA rows are (4 in-edge rows) x (l = 0..7),
+// the contraction runs over the out-edge positions n, columns are o.  A fragments are evaluated in
+// registers (a lane keeps one l, so Y_l0 is one short polynomial); dz of the out-edges is staged
+// transposed in LDS.
+template <int CB>   // O = 32 CB
+__global__ void __launch_bounds__(256)
+tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
+                    const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_kj,
+                    const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ cos_kj,
+                    const float* __restrict__ dz, int S, int kn_cap, float* __restrict__ H) {
+  constexpr int O = 32 * CB;
+  rows_t P;
+  if (!centre_rows(row_ptr, out_ptr, P)) return;
+  const int Kn = (P.dout + 15) & ~15;
+  if (Kn > kn_cap) return;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  __bf16* ZT = reinterpret_cast<__bf16*>(smem_raw);   // ZT[o][n], row stride LDN
+  const int LDN = Kn + 8;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int32_t* outs = out_list + P.o0;
+
+  const int tiles_n = Kn / 16;
+  for (int t = wave; t < tiles_n * CB; t += 4) {
+    const int np = (t % tiles_n) * 8 + (lane & 7), oq = (t / tiles_n) * 8 + (lane >> 3);
+    const int n0 = 2 * np;
+    f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
+    if (n0 < P.dout) v0 = *reinterpret_cast<const f32x4*>(dz + (int64_t)outs[n0] * O + 4 * oq);
+    if (n0 + 1 < P.dout) v1 = *reinterpret_cast<const f32x4*>(dz + (int64_t)outs[n0 + 1] * O + 4 * oq);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      bf16x2 pr;
+      pr[0] = (__bf16)v0[i];
+      pr[1] = (__bf16)v1[i];
+      *reinterpret_cast<bf16x2*>(&ZT[(4 * oq + i) * LDN + n0]) = pr;
+    }
+  }
+  __syncthreads();
+
+  const int kh = lane >> 5, l32 = lane & 31;
+  const int l = l32 & 7;
+  float q[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) q[i] = l < S ? Y_NORM_M[l] * LEG_Q[l][i] : 0.f;
+  const bool odd = l & 1;
+  const int nks = Kn / 16;
+
+  for (int grp = P.gb + wave; grp < P.ge; grp += 4) {
+    rowinfo_t ri[2];
+    bool pv[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      const int p = grp * 8 + rb * 4 + (l32 >> 3);
+      pv[rb] = p < P.d;
+      ri[rb] = row_info(seg_ptr_kj, idx_ji_kj, outs, P.r0 + (pv[rb] ? p : P.d - 1));
+    }
+    f32x16 acc[2][CB];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.f;
+
+    for (int ks = 0; ks < nks; ++ks) {
+      bf16x8 a[2], b[CB];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int n = ks * 16 + kh * 8 + i;
+          const int slot = n - (n > ri[rb].gap ? 1 : 0);
+          const bool valid = pv[rb] && n != ri[rb].gap && slot < ri[rb].cnt;
+          const float x = valid ? cos_kj[ri[rb].seg + slot] : 0.f;
+          const float t2 = x * x;
+          const float y = (odd ? x : 1.f) * (q[0] + t2 * (q[1] + t2 * (q[2] + t2 * q[3])));
+          a[rb][i] = (__bf16)(valid ? y : 0.f);
+        }
+      }
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+        b[cb] = *reinterpret_cast<const bf16x8*>(&ZT[(cb * 32 + l32) * LDN + ks * 16 + kh * 8]);
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+          acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rb], b[cb], acc[rb][cb], 0, 0, 0);
+    }
+
+    // accumulator register v of lane (kh, l32): row 8 (v/4) + 4 kh + v%4 = (in-edge row v/4 of the block, l = 4 kh + v%4)
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int p = grp * 8 + rb * 4 + (v >> 2), lo = 4 * kh + (v & 3);
+        if (p >= P.d || lo >= S) continue;
+        float* dst = H + ((int64_t)(P.r0 + p) * S + lo) * O + l32;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) dst[cb * 32] = acc[rb][cb][v];
+      }
+  }
+}
+
+// grad_cos_kj[slot of (e', e)] (+)= sum_l Y_l0'(cos) W[(e', l), e],  W = U_j . dz_out^T  (rows (in-edge row, l),
+// columns out-edge positions n, contraction over o).  U rows go straight from memory to A fragments,
+// dz of the out-edges is staged in LDS (bf16); the derivative weights are applied to the accumulators.
+template <int KS>   // O = 16 KS
+__global__ void __launch_bounds__(256)
+tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
+                       const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_kj,
+                       const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ cos_kj,
+                       const float* __restrict__ U, const float* __restrict__ dz, int S, int kn_cap, int accumulate,
+                       float* __restrict__ grad_cos_kj) {
+  constexpr int O = 16 * KS, LDO = O + 8;
+  rows_t P;
+  if (!centre_rows(row_ptr, out_ptr, P)) return;
+  const int Kn = (P.dout + 31) & ~31;
+  if (Kn > kn_cap || P.dout == 0) return;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  __bf16* ZB = reinterpret_cast<__bf16*>(smem_raw);   // ZB[n][o], row stride LDO
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int32_t* outs = out_list + P.o0;
+
+  for (int it = threadIdx.x; it < Kn * (O / 8); it += 256) {
+    const int n = it / (O / 8), oc = (it % (O / 8)) * 8;
+    bf16x8 v;
+    if (n < P.dout) {
+      const float* src = dz + (int64_t)outs[n] * O + oc;
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(src), v1 = *reinterpret_cast<const f32x4*>(src + 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = (__bf16)v0[i], v[4 + i] = (__bf16)v1[i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = (__bf16)0.f;
+    }
+    *reinterpret_cast<bf16x8*>(&ZB[n * LDO + oc]) = v;
+  }
+  __syncthreads();
+
+  const int kh = lane >> 5, l32 = lane & 31;
+  const int l = l32 & 7;
+  for (int grp = P.gb + wave; grp < P.ge; grp += 4) {
+    // A fragments: row (in-edge row l32/8 of the block, l), 8 consecutive o per k-step
+    bf16x8 a[2][KS];
+    rowinfo_t mine[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      const int p = grp * 8 + rb * 4 + (l32 >> 3);
+      const bool ok = p < P.d && l < S;
+      const int e = P.r0 + (p < P.d ? p : P.d - 1);
+      mine[rb] = row_info(seg_ptr_kj, idx_ji_kj, outs, e);
+      const float* src = U + ((int64_t)e * S + (l < S ? l : 0)) * O + kh * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(src + ks * 16), v1 = *reinterpret_cast<const f32x4*>(src + ks * 16 + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a[rb][ks][i] = (__bf16)(ok ? v0[i] : 0.f);
+          a[rb][ks][4 + i] = (__bf16)(ok ? v1[i] : 0.f);
+        }
+      }
+    }
+    for (int nb = 0; nb < Kn / 32; ++nb) {
+      f32x16 acc[2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(&ZB[(nb * 32 + l32) * LDO + ks * 16 + kh * 8]);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rb][ks], b, acc[rb], 0, 0, 0);
+      }
+      const int n = nb * 32 + l32;   // this lane's column
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int pl = 0; pl < 4; ++pl) {
+          // row information of in-edge row pl of the block sits in lanes 8 pl .. 8 pl + 7
+          const int seg = __shfl(mine[rb].seg, pl * 8, 64), cnt = __shfl(mine[rb].cnt, pl * 8, 64),
+                    gap = __shfl(mine[rb].gap, pl * 8, 64);
+          const int p = grp * 8 + rb * 4 + pl;
+          const int slot = n - (n > gap ? 1 : 0);
+          const bool valid = p < P.d && n != gap && slot < cnt;
+          const float x = valid ? cos_kj[seg + slot] : 0.f;
+          // dY[l] = sqrt((2l+1)/(4 pi)) P_l'(x), P'_{l+1} = P'_{l-1} + (2l+1) P_l; this lane needs l = 4 kh .. 4 kh + 3
+          float Pl[ST], dP[ST];
+          Pl[0] = 1.f; dP[0] = 0.f;
+          Pl[1] = x;   dP[1] = 1.f;
+#pragma unroll
+          for (int k = 1; k < ST - 1; ++k) {
+            Pl[k + 1] = ((float)(2 * k + 1) * x * Pl[k] - (float)k * Pl[k - 1]) * (1.0f / (float)(k + 1));
+            dP[k + 1] = dP[k - 1] + (float)(2 * k + 1) * Pl[k];
+          }
+          float part = 0.f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float lo = (i < S) ? Y_NORM_M[i] * dP[i] : 0.f;
+            const float hi = (4 + i < S) ? Y_NORM_M[4 + i] * dP[4 + i] : 0.f;
+            part += acc[rb][4 * pl + i] * (kh ? hi : lo);
+          }
+          const float total = part + __shfl_xor(part, 32, 64);
+          if (valid && kh == (pl >> 1)) {
+            float* dst = grad_cos_kj + seg + slot;
+            *dst = accumulate ? *dst + total : total;
+          }
+        }
+    }
+  }
+}
+
 int kp_of(const gp_graph* g) { return (g->max_in_degree + 15) & ~15; }
+int kn_of(const gp_graph* g) { return (g->max_out_degree + 31) & ~31; }
 
 }  // namespace
 
@@ -291,16 +579,19 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
   __bf16* Yb = static_cast<__bf16*>(ybuf);
   {
     gp_prof_scope prof(ctx, "tripG_y", Td * (2.0 * S * C + 4.0 * S), (Td + 16.0 * Ed) * CP * 2.0 + Td * 8.0 + Ed * 4.0 * S * C);
+    const int yt = kp_cap >= YT ? YT : (kp_cap + 63) & ~63;
     if (S <= 7)
-      tripG_y_kernel<7><<<grid, YT, 0, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj,
+      tripG_y_kernel<7><<<grid, yt, 0, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj,
                                                        cos_alpha, Radt, E, S, C, kp_cap, Yb);
     else
-      tripG_y_kernel<8><<<grid, YT, 0, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj,
+      tripG_y_kernel<8><<<grid, yt, 0, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj,
                                                        cos_alpha, Radt, E, S, C, kp_cap, Yb);
     GP_LAUNCH_CHECK(ctx, "tripG_y_kernel");
   }
   {
     const size_t lds = (size_t)F * (kp_cap + 8) * sizeof(__bf16);
+    // registers allow 8 wavefronts per CU: two workgroups of 256 threads if their X tiles fit side by side
+    const int mt = lds <= LDS_MAX / 2 ? 256 : MT;
     gp_prof_scope prof(ctx, "tripG_mfma_fwd", Td * 2.0 * C * F, (Td + 16.0 * Ed) * CP * 2.0 + Ed * 4.0 * (F + (double)C * F));
 #define GP_TRIPG_LAUNCH(CB)                                                                                       \
   do {                                                                                                            \
@@ -310,7 +601,7 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                     \
       lds_set = lds;                                                                                              \
     }                                                                                                             \
-    tripG_mfma_kernel<CB><<<grid, MT, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, x,  \
+    tripG_mfma_kernel<CB><<<grid, mt, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, x,  \
                                                           Yb, C, kp_cap, A);                                      \
   } while (0)
     switch (F / 32) {
@@ -322,5 +613,77 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
 #undef GP_TRIPG_LAUNCH
     GP_LAUNCH_CHECK(ctx, "tripG_mfma_kernel");
   }
+  return GP_OK;
+}
+
+bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S) {
+  if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_out_degree <= 0) return false;
+  if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS) return false;
+  if (O % 32 != 0 || O < 32 || O > 128 || S < 1 || S > ST) return false;
+  return (size_t)O * (kn_of(g) + 8) * sizeof(__bf16) <= LDS_MAX && (size_t)kn_of(g) * (O + 8) * sizeof(__bf16) <= LDS_MAX;
+}
+
+int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S,
+                             float* H) {
+  const int64_t E = g->n_edges, T = g->n_triplets;
+  if (E == 0) return GP_OK;
+  GP_REQUIRE(ctx, gp_tripG_mfma_bwd_usable(g, O, S), "triplet G backward (matrix-core form): graph lists or widths not supported");
+  GP_REQUIRE(ctx, dz && H && (T == 0 || cos_alpha_kj), "triplet G backward: NULL pointer");
+  const int kn_cap = kn_of(g);
+  const unsigned grid = (unsigned)(g->n_atoms * PARTS);
+  const size_t lds = (size_t)O * (kn_cap + 8) * sizeof(__bf16);
+  gp_prof_scope prof(ctx, "tripG_mfma_H", (double)T * 2.0 * 8 * O, (double)T * 4.0 + 4.0 * E * (O + (double)S * O));
+#define GP_TRIPG_LAUNCH(CB)                                                                                          \
+  do {                                                                                                               \
+    static size_t lds_set = 0;                                                                                       \
+    if (lds > lds_set) {                                                                                             \
+      GP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&tripG_mfma_H_kernel<CB>),                       \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                        \
+      lds_set = lds;                                                                                                 \
+    }                                                                                                                \
+    tripG_mfma_H_kernel<CB><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj,     \
+                                                             g->idx_ji_kj, cos_alpha_kj, dz, S, kn_cap, H);          \
+  } while (0)
+  switch (O / 32) {
+    case 1: GP_TRIPG_LAUNCH(1); break;
+    case 2: GP_TRIPG_LAUNCH(2); break;
+    case 3: GP_TRIPG_LAUNCH(3); break;
+    default: GP_TRIPG_LAUNCH(4); break;
+  }
+#undef GP_TRIPG_LAUNCH
+  GP_LAUNCH_CHECK(ctx, "tripG_mfma_H_kernel");
+  return GP_OK;
+}
+
+int gp_tripG_grad_cos_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* U, const float* dz,
+                           int O, int S, int accumulate, float* grad_cos_kj) {
+  const int64_t E = g->n_edges, T = g->n_triplets;
+  if (E == 0 || T == 0) return GP_OK;
+  GP_REQUIRE(ctx, gp_tripG_mfma_bwd_usable(g, O, S), "grad_cos (matrix-core form): graph lists or widths not supported");
+  GP_REQUIRE(ctx, cos_alpha_kj && U && dz && grad_cos_kj, "grad_cos: NULL pointer");
+  const int kn_cap = kn_of(g);
+  const unsigned grid = (unsigned)(g->n_atoms * PARTS);
+  const size_t lds = (size_t)kn_cap * (O + 8) * sizeof(__bf16);
+  gp_prof_scope prof(ctx, "tripG_mfma_dcos", (double)T * 2.0 * 8 * O, (double)T * 12.0 + 4.0 * E * (O + (double)S * O));
+#define GP_TRIPG_LAUNCH(KS)                                                                                          \
+  do {                                                                                                               \
+    static size_t lds_set = 0;                                                                                       \
+    if (lds > lds_set) {                                                                                             \
+      GP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&tripG_mfma_dcos_kernel<KS>),                    \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                        \
+      lds_set = lds;                                                                                                 \
+    }                                                                                                                \
+    tripG_mfma_dcos_kernel<KS><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj,  \
+                                                                g->idx_ji_kj, cos_alpha_kj, U, dz, S, kn_cap,        \
+                                                                accumulate, grad_cos_kj);                            \
+  } while (0)
+  switch (O / 32) {
+    case 1: GP_TRIPG_LAUNCH(2); break;
+    case 2: GP_TRIPG_LAUNCH(4); break;
+    case 3: GP_TRIPG_LAUNCH(6); break;
+    default: GP_TRIPG_LAUNCH(8); break;
+  }
+#undef GP_TRIPG_LAUNCH
+  GP_LAUNCH_CHECK(ctx, "tripG_mfma_dcos_kernel");
   return GP_OK;
 }

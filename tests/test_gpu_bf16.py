@@ -44,6 +44,15 @@ def test_linear_forward_bf16(lib, ctx, rows, k, n, act):
     assert H.rel_l2(out, refr) < 2e-5
 
 
+@pytest.fixture(params=[1, 0], ids=["matrix-core triplets", "vector triplets"])
+def trip_mode(request, lib, ctx):
+    """Both forms of the triplet sums of the bf16 block: per centre atom on the matrix cores (forced
+    on: these graphs are below the density at which the library picks it by itself) and per edge."""
+    lib.gp_set_triplet_mfma(ctx, request.param)
+    yield request.param
+    lib.gp_set_triplet_mfma(ctx, -1)
+
+
 def test_block_G_bf16_small_dims(lib, ctx):
     w = synth.get_workload("cfg3", emb=32, int_emb=16, emb_rbf=4, emb_cbf=5, emb_bil=12, num_radial=9,
                            num_spherical=4, cutoff=4.0)
@@ -51,17 +60,17 @@ def test_block_G_bf16_small_dims(lib, ctx):
     _parity(lib, ctx, w, 0, 2, synth.cube_positions(30, 6.0, 0.9, seed=1), tol=2e-2)
 
 
-def test_block_G_bf16_cfg3_shape_one_structure(lib, ctx):
+def test_block_G_bf16_cfg3_shape_one_structure(lib, ctx, trip_mode):
     w = synth.get_workload("cfg3")
     _parity(lib, ctx, w, 1, 1, synth.slab_adsorbate_positions(1, 8, 5, 4, 40, seed=2), tol=2e-2)
 
 
-def test_block_G_bf16_cfg4_widths_small_graph(lib, ctx):
+def test_block_G_bf16_cfg4_widths_small_graph(lib, ctx, trip_mode):
     w = synth.get_workload("cfg4", cutoff=6.0)
     _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3), tol=2e-2)
 
 
-def test_block_G_bf16_narrow_cbf_eight_spherical(lib, ctx):
+def test_block_G_bf16_narrow_cbf_eight_spherical(lib, ctx, trip_mode):
     # emb_cbf below the 16 rows an edge occupies in a matrix-core tile, num_spherical = 8, trip width 32;
     # capped neighbour lists make some edges one-directional (no row left out of their segments)
     from dataclasses import replace

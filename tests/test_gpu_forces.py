@@ -75,3 +75,19 @@ def test_forces_two_structures_cfg3_widths(lib, ctx):
     assert len(E_gpu) == 2
     assert abs(E_gpu.sum() - E_ref) <= 1e-4 * max(1.0, abs(E_ref))
     assert H.rel_l2(f_gpu, f_ref) <= 1e-4, H.rel_l2(f_gpu, f_ref)
+
+
+@pytest.mark.parametrize("mode", [1, 0], ids=["matrix-core triplets", "vector triplets"])
+def test_forces_bf16_cfg3_widths(lib, ctx, mode):
+    # bf16 GEMM operands (the precision of configuration 5), two blocks so that the basis gradients of the
+    # second block accumulate onto the first; both forms of the triplet kernels.  Bar: the bf16 figure, 2e-2.
+    w = synth.get_workload("cfg3")
+    assert w.dims.dtype == "bf16"
+    lib.gp_set_triplet_mfma(ctx, mode)
+    try:
+        pos_gptr = synth.slab_adsorbate_positions(2, 4, 3, 3, 9, seed=6)
+        pos, E_gpu, f_gpu, E_ref, f_ref, e = _force_case(lib, ctx, w, pos_gptr, 4, 2, 64)
+    finally:
+        lib.gp_set_triplet_mfma(ctx, -1)
+    assert abs(E_gpu.sum() - E_ref) <= 2e-2 * max(1.0, abs(E_ref))
+    assert H.rel_l2(f_gpu, f_ref) <= 2e-2, H.rel_l2(f_gpu, f_ref)
