@@ -552,22 +552,34 @@ extern "C" int gp_triplet_aggregate_bwd(gp_ctx* ctx, const gp_graph* graph, cons
 // ================================================================== variant G per-edge pieces
 namespace {
 
+// A workgroup takes 64 consecutive edges: their slice of the transposed radial table is 256
+// contiguous bytes per (l, c), staged in LDS once; then one wavefront per edge, lanes over o.
+constexpr int EG_EDGES = 64;
+
 __global__ void __launch_bounds__(WPB* WAVE)
 edge_G_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64_t E, int S, int C, int O,
               float* __restrict__ Gout) {
-  const int lane = threadIdx.x & 63;
-  const int64_t e = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
-  if (e >= E) return;
-  for (int o = lane; o < O; o += WAVE) {
-    float h[ST];
+  extern __shared__ float dyn_s[];   // rad_s[(l*C + c) * 64 + edge]
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int64_t e0 = (int64_t)blockIdx.x * EG_EDGES;
+  for (int i = threadIdx.x; i < S * C * EG_EDGES; i += WPB * WAVE) {
+    const int64_t e = e0 + (i & (EG_EDGES - 1));
+    dyn_s[i] = e < E ? Radt[(int64_t)(i / EG_EDGES) * E + e] : 0.f;
+  }
+  __syncthreads();
+  for (int el = w; el < EG_EDGES && e0 + el < E; el += WPB) {
+    const int64_t e = e0 + el;
+    for (int o = lane; o < O; o += WAVE) {
+      float h[ST];
 #pragma unroll
-    for (int l = 0; l < ST; ++l) h[l] = (l < S) ? H[(e * S + l) * O + o] : 0.f;
-    for (int c = 0; c < C; ++c) {
-      float s = 0.f;
+      for (int l = 0; l < ST; ++l) h[l] = (l < S) ? H[(e * S + l) * O + o] : 0.f;
+      for (int c = 0; c < C; ++c) {
+        float s = 0.f;
 #pragma unroll
-      for (int l = 0; l < ST; ++l)
-        if (l < S) s += Radt[(int64_t)(l * C + c) * E + e] * h[l];
-      Gout[(e * C + c) * O + o] = s;
+        for (int l = 0; l < ST; ++l)
+          if (l < S) s += dyn_s[(l * C + c) * EG_EDGES + el] * h[l];
+        Gout[(e * C + c) * O + o] = s;
+      }
     }
   }
 }
@@ -622,7 +634,8 @@ int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, i
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, Radt && H && Gout && S >= 1 && S <= ST && C >= 1 && O >= 1, "edge_G: bad arguments");
   gp_prof_scope prof(ctx, "tripG_edge_G", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
-  edge_G_kernel<<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(Radt, H, E, S, C, O, Gout);
+  edge_G_kernel<<<(unsigned)((E + EG_EDGES - 1) / EG_EDGES), WPB * WAVE, (size_t)S * C * EG_EDGES * sizeof(float), ctx->stream>>>(
+      Radt, H, E, S, C, O, Gout);
   GP_LAUNCH_CHECK(ctx, "edge_G_kernel");
   return GP_OK;
 }

@@ -34,26 +34,38 @@ __device__ __forceinline__ void dy_l0(float c, int S, float* dY) {
   for (int l = 0; l < ST; ++l) dY[l] = (l < S) ? Y_NORM_G[l] * dP[l] : 0.f;
 }
 
-// U[e, l, o] = sum_c Radt[(l*C+c)*E + e] * V[e, c*O + o]; one wavefront per edge, lanes over o
+// U[e, l, o] = sum_c Radt[(l*C+c)*E + e] * V[e, c*O + o].  A workgroup takes 64 consecutive edges and
+// stages their slice of the transposed radial table in LDS (256 contiguous bytes per (l, c)); then one
+// wavefront per edge, lanes over o.
+constexpr int EU_EDGES = 64;
+
 __global__ void __launch_bounds__(WPB* 64)
 edge_U_kernel(const float* __restrict__ Radt, const float* __restrict__ V, int64_t E, int S, int C, int O,
               float* __restrict__ U) {
-  const int lane = threadIdx.x & 63;
-  const int64_t e = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
-  if (e >= E) return;
-  for (int o = lane; o < O; o += 64) {
-    float acc[ST];
+  extern __shared__ float rad_s[];   // [(l*C + c) * 64 + edge]
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int64_t e0 = (int64_t)blockIdx.x * EU_EDGES;
+  for (int i = threadIdx.x; i < S * C * EU_EDGES; i += WPB * 64) {
+    const int64_t e = e0 + (i & (EU_EDGES - 1));
+    rad_s[i] = e < E ? Radt[(int64_t)(i / EU_EDGES) * E + e] : 0.f;
+  }
+  __syncthreads();
+  for (int el = w; el < EU_EDGES && e0 + el < E; el += WPB) {
+    const int64_t e = e0 + el;
+    for (int o = lane; o < O; o += 64) {
+      float acc[ST];
 #pragma unroll
-    for (int l = 0; l < ST; ++l) acc[l] = 0.f;
-    for (int c = 0; c < C; ++c) {
-      const float v = V[(e * C + c) * O + o];
+      for (int l = 0; l < ST; ++l) acc[l] = 0.f;
+      for (int c = 0; c < C; ++c) {
+        const float v = V[(e * C + c) * O + o];
+#pragma unroll
+        for (int l = 0; l < ST; ++l)
+          if (l < S) acc[l] += rad_s[(l * C + c) * EU_EDGES + el] * v;
+      }
 #pragma unroll
       for (int l = 0; l < ST; ++l)
-        if (l < S) acc[l] += Radt[(int64_t)(l * C + c) * E + e] * v;
+        if (l < S) U[(e * S + l) * O + o] = acc[l];
     }
-#pragma unroll
-    for (int l = 0; l < ST; ++l)
-      if (l < S) U[(e * S + l) * O + o] = acc[l];
   }
 }
 
@@ -118,7 +130,8 @@ int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, i
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, Radt && V && U && S >= 1 && S <= ST && C >= 1 && O >= 1, "edge_U: bad arguments");
   gp_prof_scope prof(ctx, "tripG_edge_U", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
-  edge_U_kernel<<<(unsigned)((E + WPB - 1) / WPB), WPB * 64, 0, ctx->stream>>>(Radt, V, E, S, C, O, U);
+  edge_U_kernel<<<(unsigned)((E + EU_EDGES - 1) / EU_EDGES), WPB * 64, (size_t)S * C * EU_EDGES * sizeof(float), ctx->stream>>>(
+      Radt, V, E, S, C, O, U);
   GP_LAUNCH_CHECK(ctx, "edge_U_kernel");
   return GP_OK;
 }

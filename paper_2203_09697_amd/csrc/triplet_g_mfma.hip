@@ -14,7 +14,7 @@
 //   tripG_y_kernel     writes Y in bf16, already in the register layout of the MFMA A operand:
 //                      per edge e a block Yb[pg][c][8] (pg = group of 8 positions), starting at
 //                      position offset seg_ptr_ji[e] + 16 e (room for padding d to a multiple
-//                      of 16).  A thread owns 8 positions x 2 values of c and keeps the radial
+//                      of 16).  A thread owns 8 positions x 2 values of c (c, c+8) and keeps the radial
 //                      rows it needs (8 x S x 2 values) in registers while it walks the edges.
 //   tripG_mfma_kernel  v_mfma_f32_32x32x16_bf16: a wavefront owns 4 edges (2 row blocks of
 //                      2 edges x 16 c) by all F columns; A fragments come straight from Yb
@@ -44,6 +44,16 @@ constexpr size_t LDS_MAX = 160 * 1024;
 __device__ __constant__ float Y_NORM_M[ST] = {
     0.28209479177387814f, 0.4886025119029199f, 0.6307831305050401f, 0.7463526651802308f,
     0.8462843753216345f, 0.9356025796273888f, 1.0171072362820548f, 1.0925484305920792f};  // sqrt((2l+1)/(4 pi))
+
+// leading coefficient of the Legendre polynomial P_l: (2l)! / (2^l (l!)^2)
+__device__ __constant__ float LEG_LEAD[ST] = {1.f, 1.f, 1.5f, 2.5f, 4.375f, 7.875f, 14.4375f, 26.8125f};
+
+// wavefront-local ordering of LDS traffic (no other wavefront touches the slice concerned)
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 // The share of one workgroup: centre atom j = blockIdx.x / PARTS, its in-edge rows r0 .. r0+d-1
 // (Kp = d rounded up to 16) and the slice [eb, ee) of its out-edge list.
@@ -95,9 +105,12 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
       for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
         for (int pi = 0; pi < 8; ++pi) {
-          const int p = 8 * pg + pi, c = 2 * cp + cc;
+          const int p = 8 * pg + pi, c = cp + 8 * cc;
           const bool ok = active && l < S && c < C && p < P.d;
-          rad[l][cc][pi] = ok ? Radt[(int64_t)(l * C + c) * E + P.r0 + p] : 0.f;
+          // pre-multiplied by the normalisation of Y_l0 and the leading coefficient of P_l (see below)
+          // unconditional load from a clamped (valid) address: no branch around it
+          const float rv = Radt[(int64_t)((l < S ? l : S - 1) * C + (c < C ? c : C - 1)) * E + P.r0 + (p < P.d ? p : P.d - 1)];
+          rad[l][cc][pi] = ok ? Y_NORM_M[l] * LEG_LEAD[l] * rv : 0.f;
         }
     for (int c0 = P.eb; c0 < P.ee; c0 += 64) {
       __syncthreads();
@@ -145,28 +158,30 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
         float y[2][8];
 #pragma unroll
         for (int pi = 0; pi < 8; ++pi) {
-          float p0 = 1.f, p1 = cs[pi];
-          float a0 = Y_NORM_M[0] * rad[0][0][pi], a1 = Y_NORM_M[0] * rad[0][1][pi];
+          // monic Legendre polynomials: pi_0 = 1, pi_1 = x, pi_{l+1} = x pi_l - l^2/(4 l^2 - 1) pi_{l-1};
+          // P_l = LEG_LEAD[l] pi_l.  Starting from pi_0 = 0 where there is no triplet zeroes the sums.
+          const float v = ((vm >> pi) & 1u) ? 1.f : 0.f;
+          float p0 = v, p1 = v * cs[pi];
+          float a0 = p0 * rad[0][0][pi], a1 = p0 * rad[0][1][pi];
 #pragma unroll
           for (int l = 1; l < SM; ++l) {
-            const float yl = Y_NORM_M[l] * p1;
-            a0 += yl * rad[l][0][pi];
-            a1 += yl * rad[l][1][pi];
-            const float p2 = ((float)(2 * l + 1) * cs[pi] * p1 - (float)l * p0) * (1.0f / (float)(l + 1));
+            a0 += p1 * rad[l][0][pi];
+            a1 += p1 * rad[l][1][pi];
+            const float p2 = cs[pi] * p1 - ((float)(l * l) / (float)(4 * l * l - 1)) * p0;
             p0 = p1;
             p1 = p2;
           }
-          const bool valid = (vm >> pi) & 1u;
-          y[0][pi] = valid ? a0 : 0.f;
-          y[1][pi] = valid ? a1 : 0.f;
+          y[0][pi] = a0;
+          y[1][pi] = a1;
         }
-        __bf16* dst = Yb + y_offset(s_seg[ei], s_e[ei]) + (int64_t)pg * (CP * 8) + (2 * cp) * 8;
+        // c = cp and cp + 8: the 8 threads of a position group write 128 contiguous bytes per store
+        __bf16* dst = Yb + y_offset(s_seg[ei], s_e[ei]) + (int64_t)pg * (CP * 8) + cp * 8;
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
           bf16x8 v;
 #pragma unroll
           for (int pi = 0; pi < 8; ++pi) v[pi] = (__bf16)y[cc][pi];
-          *reinterpret_cast<bf16x8*>(dst + 8 * cc) = v;
+          *reinterpret_cast<bf16x8*>(dst + 64 * cc) = v;
         }
       }
     }
@@ -404,21 +419,31 @@ tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restri
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.f;
 
-    for (int ks = 0; ks < nks; ++ks) {
-      bf16x8 a[2], b[CB];
+    // cosines of k-step ks for both row blocks (2 marks "no triplet"); fetched two k-steps ahead
+    auto load_x = [&](int ks, float (&x)[2][8]) {
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
+      for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int n = ks * 16 + kh * 8 + i;
           const int slot = n - (n > ri[rb].gap ? 1 : 0);
-          const bool valid = pv[rb] && n != ri[rb].gap && slot < ri[rb].cnt;
-          const float x = valid ? cos_kj[ri[rb].seg + slot] : 0.f;
+          const bool valid = ks < nks && pv[rb] && n != ri[rb].gap && slot < ri[rb].cnt;
+          const float cv = cos_kj[valid ? ri[rb].seg + slot : 0];   // unconditional load, index 0 when unused
+          x[rb][i] = valid ? cv : 2.f;
+        }
+    };
+    auto step = [&](int ks, const float (&xc)[2][8]) {
+      bf16x8 a[2], b[CB];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const bool valid = xc[rb][i] <= 1.5f;
+          const float x = valid ? xc[rb][i] : 0.f;
           const float t2 = x * x;
           const float y = (odd ? x : 1.f) * (q[0] + t2 * (q[1] + t2 * (q[2] + t2 * q[3])));
           a[rb][i] = (__bf16)(valid ? y : 0.f);
         }
-      }
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb)
         b[cb] = *reinterpret_cast<const bf16x8*>(&ZT[(cb * 32 + l32) * LDN + ks * 16 + kh * 8]);
@@ -427,6 +452,20 @@ tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restri
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
           acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rb], b[cb], acc[rb][cb], 0, 0, 0);
+    };
+    float xn0[2][8], xn1[2][8];
+    load_x(0, xn0);
+    load_x(1, xn1);
+    for (int ks = 0; ks < nks; ks += 2) {
+      float xc0[2][8], xc1[2][8];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xc0[rb][i] = xn0[rb][i], xc1[rb][i] = xn1[rb][i];
+      load_x(ks + 2, xn0);
+      load_x(ks + 3, xn1);
+      step(ks, xc0);
+      if (ks + 1 < nks) step(ks + 1, xc1);
     }
 
     // accumulator register v of lane (kh, l32): row 8 (v/4) + 4 kh + v%4 = (in-edge row v/4 of the block, l = 4 kh + v%4)
@@ -502,7 +541,42 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
         }
       }
     }
+    // row information of in-edge row pl of a block sits in lanes 8 pl .. 8 pl + 7
+    int rseg[2][4], rcnt[2][4], rgap[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int pl = 0; pl < 4; ++pl) {
+        rseg[rb][pl] = __shfl(mine[rb].seg, pl * 8, 64);
+        rgap[rb][pl] = __shfl(mine[rb].gap, pl * 8, 64);
+        // rows past the end of the atom's list take part in nothing
+        rcnt[rb][pl] = grp * 8 + rb * 4 + pl < P.d ? __shfl(mine[rb].cnt, pl * 8, 64) : 0;
+      }
+    // cosines (and, when accumulating, the values to add to) of this lane's column for the 8 rows;
+    // fetched one column block ahead so that the loads overlap the products
+    auto fetch = [&](int nb, float (&xs)[2][4], float (&old)[2][4]) {
+      const int n = nb * 32 + l32;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int pl = 0; pl < 4; ++pl) {
+          const int slot = n - (n > rgap[rb][pl] ? 1 : 0);
+          const bool valid = n != rgap[rb][pl] && slot < rcnt[rb][pl];
+          const int at = valid ? rseg[rb][pl] + slot : 0;   // unconditional loads, index 0 when unused
+          const float cv = cos_kj[at], ov = accumulate ? grad_cos_kj[at] : 0.f;
+          xs[rb][pl] = valid ? cv : 0.f;
+          old[rb][pl] = valid ? ov : 0.f;
+        }
+    };
+    float xs_n[2][4], old_n[2][4];
+    fetch(0, xs_n, old_n);
     for (int nb = 0; nb < Kn / 32; ++nb) {
+      float xs[2][4], old[2][4];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int pl = 0; pl < 4; ++pl) xs[rb][pl] = xs_n[rb][pl], old[rb][pl] = old_n[rb][pl];
+      if (nb + 1 < Kn / 32) fetch(nb + 1, xs_n, old_n);
       f32x16 acc[2];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb)
@@ -519,13 +593,9 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
       for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int pl = 0; pl < 4; ++pl) {
-          // row information of in-edge row pl of the block sits in lanes 8 pl .. 8 pl + 7
-          const int seg = __shfl(mine[rb].seg, pl * 8, 64), cnt = __shfl(mine[rb].cnt, pl * 8, 64),
-                    gap = __shfl(mine[rb].gap, pl * 8, 64);
-          const int p = grp * 8 + rb * 4 + pl;
-          const int slot = n - (n > gap ? 1 : 0);
-          const bool valid = p < P.d && n != gap && slot < cnt;
-          const float x = valid ? cos_kj[seg + slot] : 0.f;
+          const int slot = n - (n > rgap[rb][pl] ? 1 : 0);
+          const bool valid = n != rgap[rb][pl] && slot < rcnt[rb][pl];
+          const float x = xs[rb][pl];
           // dY[l] = sqrt((2l+1)/(4 pi)) P_l'(x), P'_{l+1} = P'_{l-1} + (2l+1) P_l; this lane needs l = 4 kh .. 4 kh + 3
           float Pl[ST], dP[ST];
           Pl[0] = 1.f; dP[0] = 0.f;
@@ -543,10 +613,7 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
             part += acc[rb][4 * pl + i] * (kh ? hi : lo);
           }
           const float total = part + __shfl_xor(part, 32, 64);
-          if (valid && kh == (pl >> 1)) {
-            float* dst = grad_cos_kj + seg + slot;
-            *dst = accumulate ? *dst + total : total;
-          }
+          if (valid && kh == (pl >> 1)) grad_cos_kj[rseg[rb][pl] + slot] = old[rb][pl] + total;
         }
     }
   }
@@ -554,6 +621,8 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
 
 int kp_of(const gp_graph* g) { return (g->max_in_degree + 15) & ~15; }
 int kn_of(const gp_graph* g) { return (g->max_out_degree + 31) & ~31; }
+// dz of the out-edges (bf16, transposed)
+size_t lds_H(int O, int kn) { return (size_t)(kn + 8) * O * sizeof(__bf16); }
 
 }  // namespace
 
@@ -561,6 +630,7 @@ size_t gp_tripG_mfma_scratch(int64_t E, int64_t T) { return gp_align((size_t)(T 
 
 bool gp_tripG_mfma_usable(const gp_graph* g, int F, int S, int C) {
   if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_in_degree <= 0) return false;
+  if (g->n_triplets <= 0) return false;   // the kernels read cos_alpha[0] for absent triplets
   if (g->n_atoms > INT32_MAX / PARTS) return false;
   if (F % 32 != 0 || F < 32 || F > 128 || C < 1 || C > CP || S < 1 || S > ST) return false;
   return (size_t)F * (kp_of(g) + 8) * sizeof(__bf16) <= LDS_MAX;
@@ -618,9 +688,10 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
 
 bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S) {
   if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_out_degree <= 0) return false;
+  if (g->n_triplets <= 0) return false;   // the kernels read cos_alpha_kj[0] for absent triplets
   if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS) return false;
   if (O % 32 != 0 || O < 32 || O > 128 || S < 1 || S > ST) return false;
-  return (size_t)O * (kn_of(g) + 8) * sizeof(__bf16) <= LDS_MAX && (size_t)kn_of(g) * (O + 8) * sizeof(__bf16) <= LDS_MAX;
+  return lds_H(O, kn_of(g)) <= LDS_MAX && (size_t)kn_of(g) * (O + 8) * sizeof(__bf16) <= LDS_MAX;
 }
 
 int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S,
@@ -631,7 +702,7 @@ int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_al
   GP_REQUIRE(ctx, dz && H && (T == 0 || cos_alpha_kj), "triplet G backward: NULL pointer");
   const int kn_cap = kn_of(g);
   const unsigned grid = (unsigned)(g->n_atoms * PARTS);
-  const size_t lds = (size_t)O * (kn_cap + 8) * sizeof(__bf16);
+  const size_t lds = lds_H(O, kn_cap);
   gp_prof_scope prof(ctx, "tripG_mfma_H", (double)T * 2.0 * 8 * O, (double)T * 4.0 + 4.0 * E * (O + (double)S * O));
 #define GP_TRIPG_LAUNCH(CB)                                                                                          \
   do {                                                                                                               \
