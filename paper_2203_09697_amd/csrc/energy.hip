@@ -66,18 +66,28 @@ sort_lists_kernel(const int32_t* __restrict__ ptr, const int32_t* __restrict__ t
 }
 
 // ------------------------------------------------------------------ energy head
-// h[i, f] = sum over the in-edge row of atom i of m[e, f]; one wavefront per atom
+// h[i, f] = sum over the in-edge row of atom i of m[e, f]; one wavefront per (atom, 64 features),
+// four rows in flight, partial sums combined in a fixed order
 __global__ void __launch_bounds__(256)
 atom_sum_kernel(const float* __restrict__ m, const int32_t* __restrict__ row_ptr, int64_t n_atoms, int H,
                 float* __restrict__ h) {
-  const int64_t i = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  const int chunks = (H + 63) / 64;
+  const int64_t w = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  const int64_t i = w / chunks;
   if (i >= n_atoms) return;
+  const int f = (int)(w % chunks) * 64 + (threadIdx.x & 63);
+  if (f >= H) return;
   const int e0 = row_ptr[i], e1 = row_ptr[i + 1];
-  for (int f = threadIdx.x & 63; f < H; f += 64) {
-    float s = 0.f;
-    for (int e = e0; e < e1; ++e) s += m[(int64_t)e * H + f];
-    h[i * H + f] = s;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int e = e0;
+  for (; e + 3 < e1; e += 4) {
+    s0 += m[(int64_t)e * H + f];
+    s1 += m[(int64_t)(e + 1) * H + f];
+    s2 += m[(int64_t)(e + 2) * H + f];
+    s3 += m[(int64_t)(e + 3) * H + f];
   }
+  for (; e < e1; ++e) s0 += m[(int64_t)e * H + f];
+  h[i * H + f] = (s0 + s1) + (s2 + s3);
 }
 // e_atom[i] = sum_k a1[i,k] w2[k] + b2; one wavefront per atom
 __global__ void __launch_bounds__(256)
@@ -299,7 +309,7 @@ int gp_energy_forward(gp_ctx* ctx, int32_t emb, int32_t hidden, const gp_weights
   if (saved_bytes < carve_head_saved(saved, n_atoms, emb, hidden, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_energy_forward: saved buffer too small");
   GP_HIP(ctx, hipSetDevice(ctx->device));
   hipStream_t st = ctx->stream;
-  atom_sum_kernel<<<wblk(n_atoms), 256, 0, st>>>(m, row_ptr, n_atoms, emb, s.h);
+  atom_sum_kernel<<<wblk(n_atoms * ((emb + 63) / 64)), 256, 0, st>>>(m, row_ptr, n_atoms, emb, s.h);
   GP_LAUNCH_CHECK(ctx, "atom_sum_kernel");
   gp_epilogue e;
   e.bias = w->b1; e.save_pre = s.z1; e.act = 1; e.out = s.a1;

@@ -2,11 +2,12 @@
 // reductions and elementwise kernels the edge MLPs need (EdgeUpdate of paper Sec. 2.1 / 3.3).
 //
 // Tiling: a 256-thread workgroup (4 wavefronts of 64) owns a BM x BN tile of C; the K loop
-// advances BK = 32 at a time through double-buffered LDS tiles As[k][m], Bs[k][n] (k-major, so
-// the 32 lanes that feed one MFMA operand read consecutive LDS words).  Each wavefront owns
+// advances BK = 16 at a time through LDS tiles As[k][m], Bs[k][n] (k-major, so the 32 lanes that
+// feed one MFMA operand read consecutive LDS words).  Each wavefront owns
 // (BM/WAVES_M) x (BN/WAVES_N) of the tile as 32x32 MFMA blocks.  The next K-slab is fetched
-// into registers while the current one is multiplied and is written to the other LDS buffer
-// afterwards, so there is one barrier per slab.
+// into registers while the current one is multiplied and written to LDS between two barriers
+// (BK = 32 with two LDS buffers and one barrier per slab can be compiled in; it measured
+// slower because it halves the number of resident workgroups).
 #include <stdarg.h>
 
 #include <type_traits>
