@@ -198,12 +198,20 @@ def main():
         kernels.append({"kernel": name, "launches_per_step": d["launches"] / prof_steps, "avg_ms": round(per_launch_ms, 5),
                         "ms_per_step": round(d["ms"] / prof_steps, 4), "bound": bound, "achieved": round(ach, 3),
                         "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
+    # the same fractions against rates measured on this GPU (copy kernel, register-resident MFMA chains)
+    mp = gp.gp_measure_peaks(ctx)
+    measured = {"hbm": mp["copy_GBps"], "mfma_f32": mp["mfma_f32_TFLOPs"], "mfma_bf16": mp["mfma_bf16_TFLOPs"]}
+    for k in kernels:
+        key = "hbm" if k["bound"] == "hbm" else ("mfma_bf16" if k["peak"] == PEAK["mfma_bf16"][0] else
+                                                  "mfma_f32" if k["bound"] == "mfma" else None)
+        k["frac_of_measured"] = round(k["achieved"] / measured[key], 4) if key else None
     top = kernels[0]
     traffic = measured_traffic(w)
     for k in kernels:
         k["traffic"] = traffic.get(k["kernel"])
     roofline = {"kernel": top["kernel"], "bound": top["bound"], "achieved": top["achieved"], "peak": top["peak"],
-                "unit": top["unit"], "frac": top["frac"], "avg_ms": top["avg_ms"], "traffic": top["traffic"]}
+                "unit": top["unit"], "frac": top["frac"], "frac_of_measured": top["frac_of_measured"], "avg_ms": top["avg_ms"],
+                "traffic": top["traffic"]}
 
     out = {
         "metric": "triplets/sec (interaction block fwd+bwd), 1 MI355X", "value": value, "unit": "triplets/s",
@@ -214,6 +222,7 @@ def main():
                                                         dims.emb, dims.int_emb, ", energy head + forces" if w.head_hidden else ""),
                    "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed},
         "roofline": roofline,
+        "measured_peaks": {k: round(v, 1) for k, v in mp.items()},
         "kernels": kernels[:10],
         "graph_build_ms": round(graph_ms, 3), "basis_ms": round(basis_ms, 3), "wall_ms_per_step": round(wall_ms / a.steps, 4),
     }

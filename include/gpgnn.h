@@ -70,6 +70,14 @@ int gp_profile_count(gp_ctx* ctx, int64_t* n /*host*/);
 int gp_profile_get(gp_ctx* ctx, int64_t i, const char** name /*host*/, float* ms /*host*/,
                    double* flops /*host*/, double* bytes /*host*/);
 
+/* Measurement aid: rates this GPU reaches with the simplest kernels that can reach them, for
+ * quoting roofline fractions against measured as well as published peaks: a 16-byte copy of half
+ * the workspace into the other half (GB/s, bytes read + written) and register-resident chains
+ * of fp32 32x32x2 and bf16 32x32x16 matrix-core instructions (TFLOP/s).  ws: device scratch of at
+ * least 64 MiB (contents destroyed).  Synchronises; the three results are host variables. */
+int gp_measure_peaks(gp_ctx* ctx, void* ws, size_t ws_bytes, double* copy_gbps /*host*/,
+                     double* mfma_f32_tflops /*host*/, double* mfma_bf16_tflops /*host*/);
+
 /* ------------------------------------------------------------------------------------------
  * Graph construction (Sec. 3.1): target atom t gets an edge from every source atom s of the
  * same structure with |x_t - x_s| < cutoff.  The test is the fp32 expression

@@ -7,7 +7,7 @@ import torch
 __all__ = [
     "GpError", "load", "library_path", "Context", "Dims", "Graph", "Basis",
     "gp_version", "gp_profile_enable", "gp_profile_reset", "gp_profile_collect", "gp_set_side_stream", "gp_set_triplet_mfma",
-    "gp_edges_by_source", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
+    "gp_measure_peaks", "gp_edges_by_source", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
     "gp_block_forward_D", "gp_block_backward_D", "gp_triplet_aggregate_fwd",
     "gp_triplet_aggregate_bwd", "gp_linear_forward", "build_graph", "weights_to_device",
     "EXPORTED_SYMBOLS", "D_WEIGHT_ORDER",
@@ -22,7 +22,7 @@ STATUS = {0: "GP_OK", -1: "GP_BAD_ARG", -2: "GP_BUFFER_TOO_SMALL", -3: "GP_INT32
 
 EXPORTED_SYMBOLS = [
     "gp_create", "gp_destroy", "gp_last_error", "gp_version",
-    "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get", "gp_set_side_stream", "gp_set_triplet_mfma",
+    "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get", "gp_set_side_stream", "gp_set_triplet_mfma", "gp_measure_peaks",
     "gp_edges_workspace", "gp_edges_count", "gp_edges_fill",
     "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill", "gp_csr_max_degree",
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
@@ -180,6 +180,14 @@ def gp_version():
 
 def gp_profile_enable(ctx, on):
     ctx.check(load().gp_profile_enable(ctx._h, C.c_int(1 if on else 0)))
+
+
+def gp_measure_peaks(ctx, mib=512):
+    """{"copy_GBps", "mfma_f32_TFLOPs", "mfma_bf16_TFLOPs"} measured on the context's device."""
+    ws = torch.empty(mib << 20, dtype=torch.uint8, device=ctx.device)
+    a, b, c = C.c_double(), C.c_double(), C.c_double()
+    ctx.check(load().gp_measure_peaks(ctx._h, _ptr(ws), C.c_size_t(ws.numel()), C.byref(a), C.byref(b), C.byref(c)))
+    return {"copy_GBps": a.value, "mfma_f32_TFLOPs": b.value, "mfma_bf16_TFLOPs": c.value}
 
 
 def gp_set_triplet_mfma(ctx, mode):
