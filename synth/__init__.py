@@ -18,5 +18,6 @@ from .tensors import (  # noqa: F401
     weights_D,
     weights_G,
     weights_head,
+    weights_out,
     edge_embeddings,
 )

@@ -72,6 +72,18 @@ def weights_head(emb, hidden, seed=0, bias_scale=0.0):
     return w
 
 
+def weights_out(emb, out_emb, num_radial, n_layers=3, seed=0, bias_scale=0.0):
+    """Output block: radial weighting of the messages, up-projection, n_layers dense layers, final vector."""
+    rng = np.random.default_rng(seed)
+    w = {}
+    w["W_rbf"] = glorot(rng, (num_radial, emb))
+    w["W_up"] = glorot(rng, (emb, out_emb))
+    for k in range(n_layers):
+        w[f"W{k}"] = glorot(rng, (out_emb, out_emb)); w[f"b{k}"] = _bias(rng, out_emb, bias_scale)
+    w["w_final"] = glorot(rng, (out_emb, 1)).reshape(out_emb)
+    return w
+
+
 def edge_embeddings(n_edges, emb, seed=0):
     """Input messages m ~ N(0,1) and an upstream gradient of the same shape."""
     rng = np.random.default_rng(seed)
