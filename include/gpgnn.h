@@ -279,6 +279,44 @@ int gp_energy_backward(gp_ctx* ctx, int32_t emb, int32_t hidden, const gp_weight
                        const void* saved, size_t saved_bytes, float* grad_m,
                        gp_weights_head* grad_w, void* scratch, size_t scratch_bytes);
 
+/* ------------------------------------------------------------------------------------------
+ * Output block (Sec. 3.3: the updated messages are fed to an output block that sums them per
+ * atom, EdgeAggr, and transforms the sum by an MLP, NodeUpdate), one per interaction block:
+ *   t_e = m_e * (rbf_e W_rbf);  h_i = sum_{e: dst[e]=i} t_e;  u = h W_up;
+ *   u = act(u W[k] + b[k]), k < n_layers;  P_i = u_i . w_final;  energy[g] (+)= sum_{i in g} P_i
+ * W_rbf[num_radial, emb], W_up[emb, out_emb], W[k][out_emb, out_emb], b[k][out_emb],
+ * w_final[out_emb]; energy[n_graphs] is a device array, overwritten unless accumulate != 0 (the
+ * model's energy is the sum over its output blocks).  m[E, emb] are the block's output
+ * messages, rbf[E, num_radial] the radial basis, row_ptr/dst/graph_ptr as produced by
+ * gp_edges_fill.  gp_output_backward differentiates sum_g grad_energy[g] * energy[g]:
+ * grad_m[E, emb] is overwritten, or added to if accumulate_grad_m != 0 (the gradient arriving
+ * from the next interaction block), and grad_w (may be NULL) receives the weight gradients.
+ * saved is written by the forward call and read by the backward call; scratch is free between
+ * calls.  Errors: GP_UNSUPPORTED_DIMS for widths above 4096 or more than GP_MAX_OUT_LAYERS
+ * layers, GP_BUFFER_TOO_SMALL, GP_BAD_ARG for NULL pointers.
+ */
+#define GP_MAX_OUT_LAYERS 4
+typedef struct {
+  float *W_rbf, *W_up;
+  float *W[GP_MAX_OUT_LAYERS], *b[GP_MAX_OUT_LAYERS];
+  float *w_final;
+} gp_weights_out;
+
+int gp_output_workspace(int32_t emb, int32_t out_emb, int32_t num_radial, int32_t n_layers,
+                        int64_t n_atoms, int64_t n_edges,
+                        size_t* saved_bytes /*host*/, size_t* scratch_bytes /*host*/);
+int gp_output_forward(gp_ctx* ctx, int32_t emb, int32_t out_emb, int32_t num_radial, int32_t n_layers,
+                      const gp_weights_out* w, const float* m, const float* rbf,
+                      const int32_t* row_ptr, const int32_t* graph_ptr,
+                      int64_t n_atoms, int64_t n_edges, int32_t n_graphs, int32_t accumulate,
+                      float* energy, void* saved, size_t saved_bytes, void* scratch, size_t scratch_bytes);
+int gp_output_backward(gp_ctx* ctx, int32_t emb, int32_t out_emb, int32_t num_radial, int32_t n_layers,
+                       const gp_weights_out* w, const float* m, const float* rbf,
+                       const int32_t* dst, const int32_t* graph_ptr,
+                       int64_t n_atoms, int64_t n_edges, int32_t n_graphs, const float* grad_energy,
+                       const void* saved, size_t saved_bytes, int32_t accumulate_grad_m, float* grad_m,
+                       gp_weights_out* grad_w, void* scratch, size_t scratch_bytes);
+
 /* Out-edge lists: out_list[out_ptr[j]..out_ptr[j+1]-1] are the ids of the edges whose source is
  * atom j, ascending.  (The edge list itself is sorted by target.) */
 int gp_edges_by_source_workspace(int64_t n_atoms, int64_t n_edges, size_t* bytes /*host*/);

@@ -28,6 +28,7 @@ EXPORTED_SYMBOLS = [
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
     "gp_block_forward_G", "gp_block_backward_G",
     "gp_energy_workspace", "gp_energy_forward", "gp_energy_backward",
+    "gp_output_workspace", "gp_output_forward", "gp_output_backward",
     "gp_edges_by_source_workspace", "gp_edges_by_source", "gp_forces_workspace", "gp_forces_from_basis_grad",
     "gp_triplet_aggregate_fwd", "gp_triplet_aggregate_bwd", "gp_linear_forward", "gp_linear_forward_bf16",
 ]
