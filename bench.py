@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--output-blocks", action="store_true",
+                    help="variant-D workloads: add an output block (out_emb 256, 3 layers) after every interaction "
+                         "block and differentiate the summed energies instead of a random upstream gradient")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run one 256 MiB device copy first (known traffic, to scale rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -135,7 +138,14 @@ def main():
     del m, gup
     if dims.variant == "D":
         W_list = [gp.weights_to_device(synth.weights_D(dims, seed=100 + b)) for b in range(w.n_blocks)]
-        stack = StackD(ctx, dims, W_list, t, basis)
+        if a.output_blocks:
+            from paper_2203_09697_amd.binding_o import ModelD
+            Wo = [gp.weights_to_device(synth.weights_out(dims.emb, 256, dims.num_radial, 3, seed=200 + b))
+                  for b in range(w.n_blocks)]
+            modelD = ModelD(ctx, dims, W_list, Wo, e, t, basis, dptr)
+            gE = torch.ones(len(gptr) - 1, dtype=torch.float32, device="cuda:0")
+        else:
+            stack = StackD(ctx, dims, W_list, t, basis)
     else:
         W_list = [gp.weights_to_device(synth.weights_G(dims, seed=100 + b)) for b in range(w.n_blocks)]
         if w.head_hidden:
@@ -144,7 +154,13 @@ def main():
         else:
             stack = StackG(ctx, dims, W_list, t, basis)
 
-    if w.head_hidden:
+    if a.output_blocks and dims.variant != "D":
+        sys.exit("bench.py: --output-blocks is implemented for the variant-D workloads (cfg1, cfg2)")
+    if a.output_blocks:
+        def step():
+            modelD.forward(dm)
+            modelD.backward(gE)
+    elif w.head_hidden:
         def step():
             model.energy_and_forces(dm)
     else:
@@ -219,7 +235,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": dims.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d structures, N=%d atoms, E=%d edges, T=%d triplets, %d blocks, variant %s, "
                                "emb=%d int_emb=%d%s" % (w.name, len(gptr) - 1, len(pos), E, T, w.n_blocks, dims.variant,
-                                                        dims.emb, dims.int_emb, ", energy head + forces" if w.head_hidden else ""),
+                                                        dims.emb, dims.int_emb, ", energy head + forces" if w.head_hidden else
+                                                        ", output block per interaction block" if a.output_blocks else ""),
                    "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed},
         "roofline": roofline,
         "measured_peaks": {k: round(v, 1) for k, v in mp.items()},

@@ -56,6 +56,50 @@ def test_cfg2_full_stack(lib, ctx):
     assert not bad, bad
 
 
+def test_cfg2_full_model_with_output_blocks(lib, ctx):
+    # configuration 2 with an output block (out_emb 256, 3 layers) after each of the 4 interaction blocks,
+    # as bench.py --output-blocks runs it: energies and every gradient against the full oracle
+    from oracle import output as ooutput
+    from paper_2203_09697_amd.binding_o import ModelD
+    w = synth.get_workload("cfg2")
+    dims = w.dims
+    pos, gptr, e, t = _graph(lib, ctx, w, 0)
+    ref = H.oracle_graph(pos, gptr, dims.cutoff, w.max_neighbors)
+    E, N = e["n_edges"], len(pos)
+    Wb = [synth.weights_D(dims, seed=100 + b) for b in range(w.n_blocks)]
+    Wo = [synth.weights_out(dims.emb, 256, dims.num_radial, 3, seed=200 + b) for b in range(w.n_blocks)]
+    m, _ = synth.edge_embeddings(E, dims.emb, seed=7)
+    coef = np.ones(len(gptr) - 1, dtype=np.float32)
+    gb = lib.gp_basis_forward(ctx, dims, e, t)
+    model = ModelD(ctx, dims, [lib.weights_to_device(W) for W in Wb], [lib.weights_to_device(W) for W in Wo], e, t, gb,
+                   H.to_dev(gptr, torch.int32))
+    energy = model.forward(H.to_dev(m, torch.float32))
+    gm, gWb, gWo = model.backward(H.to_dev(coef, torch.float32))
+    torch.cuda.synchronize()
+    ob = H.oracle_basis_D(pos, ref, dims)
+    Wbt = [{k: v.clone().requires_grad_(True) for k, v in H.t64(W).items()} for W in Wb]
+    Wot = [{k: v.clone().requires_grad_(True) for k, v in H.t64(W).items()} for W in Wo]
+    mt = torch.tensor(m, dtype=F64, requires_grad=True)
+    E_ref = ooutput.model_D_energies(mt, ob["rbf"], ob["sbf"], ref["idx_kj"], ref["idx_ji"], ref["dst"], gptr, N, Wbt, Wot,
+                                     dims.n_res_before, dims.n_res_after)
+    leaves = [mt] + [W[k] for W in Wbt for k in W] + [W[k] for W in Wot for k in W]
+    grads = torch.autograd.grad(E_ref.sum(), leaves)
+    errs = {"energy": H.rel_l2(energy.cpu().numpy(), E_ref.detach().numpy()), "grad_m": H.rel_l2(gm.cpu().numpy(), grads[0].numpy())}
+    i = 1
+    for b, W in enumerate(Wbt):
+        for k in W:
+            if float(grads[i].norm()) > 0:
+                errs[f"block{b}.{k}"] = H.rel_l2(gWb[b][k].cpu().numpy(), grads[i].numpy())
+            i += 1
+    for b, W in enumerate(Wot):
+        for k in W:
+            if float(grads[i].norm()) > 0:
+                errs[f"out{b}.{k}"] = H.rel_l2(gWo[b][k].cpu().numpy(), grads[i].numpy())
+            i += 1
+    bad = {k: v for k, v in errs.items() if not v <= 1e-4}
+    assert not bad, bad
+
+
 def test_cfg3_full_block_bf16(lib, ctx):
     from paper_2203_09697_amd.binding_g import StackG
     w = synth.get_workload("cfg3")
