@@ -70,14 +70,20 @@ def block_D(m, rbf, sbf, idx_kj, idx_ji, W, n_res_before=1, n_res_after=2):
     return h
 
 
-def block_G(m, g, Y, idx_kj, idx_ji, W):
-    """Variant G.  m [E,emb], g [E,R] Gaussian rbf, Y [T,S] = Y_l0(cos alpha)."""
+def block_G(m, g, Y, idx_kj, idx_ji, W, radial_at_target=False):
+    """Variant G.  m [E,emb], g [E,R] Gaussian rbf, Y [T,S] = Y_l0(cos alpha).
+
+    The radial factor of the triplet basis is taken at the source edge k->j of the triplet, or,
+    with radial_at_target, at its target edge j->i (the ordering of operations in which the
+    radial factor leaves the sum over k; Sec. 3.4 speaks of choosing the order of operations of
+    the bilinear layer).  Here the sum is written out per triplet in both cases.
+    """
     E = m.shape[0]
     x = act(m @ W["W_ba"])
     x = x * ((g @ W["W_rbfS"]) @ W["W_rbfB"])
     x = act(x @ W["W_down"])                                   # [E, emb_trip]
     Rad = torch.einsum("en,lnc->elc", g, W["W_c"])             # [E, S, emb_cbf]
-    y = torch.einsum("tl,tlc->tc", Y, Rad[_long(idx_kj)])      # [T, emb_cbf]
+    y = torch.einsum("tl,tlc->tc", Y, Rad[_long(idx_ji if radial_at_target else idx_kj)])      # [T, emb_cbf]
     A = triplet_aggregate_G(x, y, idx_kj, idx_ji, E)           # [E, emb_cbf, emb_trip]
     z = torch.einsum("ecf,cfo->eo", A, W["W_bil"])             # [E, emb_bil]
     return (act(m @ W["W_skip"]) + act(z @ W["W_up"])) / math.sqrt(2.0)
@@ -89,9 +95,9 @@ def stack_D(m, rbf, sbf, idx_kj, idx_ji, W_list, n_res_before=1, n_res_after=2):
     return m
 
 
-def stack_G(m, g, Y, idx_kj, idx_ji, W_list):
+def stack_G(m, g, Y, idx_kj, idx_ji, W_list, radial_at_target=False):
     for W in W_list:
-        m = block_G(m, g, Y, idx_kj, idx_ji, W)
+        m = block_G(m, g, Y, idx_kj, idx_ji, W, radial_at_target)
     return m
 
 

@@ -28,7 +28,7 @@ def energy_G(pos, src, dst, idx_kj, idx_ji, m0, W_list, Wh, dims):
     d, _unit, cos_alpha = basis.geometry(pos, src, dst, idx_kj, idx_ji)
     g = basis.rbf_gauss(d, dims.cutoff, dims.num_radial, dims.envelope_p)
     Y = basis.y_l0(cos_alpha, dims.num_spherical)
-    m = block.stack_G(m0, g, Y, idx_kj, idx_ji, W_list)
+    m = block.stack_G(m0, g, Y, idx_kj, idx_ji, W_list, getattr(dims, "radial_at_target", False))
     E, _ = energy_head(m, dst, pos.shape[0], Wh)
     return E
 

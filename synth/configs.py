@@ -24,6 +24,7 @@ class BlockDims:
     emb_bil: int = 0        # variant G
     n_res_before: int = 1   # variant D
     n_res_after: int = 2    # variant D
+    radial_at_target: bool = False   # variant G: radial factor of the triplet basis at the target edge j->i
 
 
 @dataclass(frozen=True)

@@ -305,3 +305,77 @@ def test_forces_are_negative_energy_gradient(variant):
     E1, f1 = energy.forces(efn, pos @ Q.T, *args)
     assert abs(E1 - E0) < 1e-11 * max(1, abs(E0))
     assert np.abs(f1 - f @ Q.T).max() < 1e-10 * max(1, scale)
+
+
+# ---- variant G with the radial factor at the target edge ---------------------------------------
+def test_radial_at_target_matches_brute_force_loops():
+    # the defining sum written as explicit loops over edges, their triplets, l, c and f
+    s = _tiny("G", seed=4, n_atoms=9)
+    E = len(s["src"])
+    pos64 = torch.tensor(s["pos"], dtype=F64)
+    g, Y = _features(s, pos64)
+    W = s["W"]
+    out = block.block_G(s["m"], g, Y, s["idx_kj"], s["idx_ji"], W, radial_at_target=True).numpy()
+    m, gn, Yn = s["m"].numpy(), g.numpy(), Y.numpy()
+    Wn = {k: v.numpy() for k, v in W.items()}
+    x = _silu(m @ Wn["W_ba"]) * ((gn @ Wn["W_rbfS"]) @ Wn["W_rbfB"])
+    x = _silu(x @ Wn["W_down"])
+    S, R, C = Wn["W_c"].shape
+    F = x.shape[1]
+    z = np.zeros((E, Wn["W_bil"].shape[2]))
+    for e in range(E):
+        Rad_e = np.array([[sum(gn[e, n] * Wn["W_c"][l, n, c] for n in range(R)) for c in range(C)] for l in range(S)])
+        A = np.zeros((C, F))
+        for t in np.nonzero(np.asarray(s["idx_ji"]) == e)[0]:
+            y = np.array([sum(Yn[t, l] * Rad_e[l, c] for l in range(S)) for c in range(C)])
+            A += np.outer(y, x[s["idx_kj"][t]])
+        z[e] = np.einsum("cf,cfo->o", A, Wn["W_bil"])
+    ref = (_silu(m @ Wn["W_skip"]) + _silu(z @ Wn["W_up"])) / math.sqrt(2.0)
+    assert np.allclose(out, ref, rtol=1e-11, atol=1e-12)
+
+
+def test_radial_at_target_equals_source_form_when_all_edges_share_a_length():
+    # if every edge carries the same radial basis row, it does not matter which edge of a triplet supplies it
+    s = _tiny("G", seed=5)
+    pos64 = torch.tensor(s["pos"], dtype=F64)
+    g, Y = _features(s, pos64)
+    g_same = g[3].expand_as(g).clone()
+    a = block.block_G(s["m"], g_same, Y, s["idx_kj"], s["idx_ji"], s["W"], radial_at_target=False)
+    b = block.block_G(s["m"], g_same, Y, s["idx_kj"], s["idx_ji"], s["W"], radial_at_target=True)
+    assert torch.allclose(a, b, rtol=1e-12, atol=1e-13)
+    # and with the real basis the two readings differ
+    c = block.block_G(s["m"], g, Y, s["idx_kj"], s["idx_ji"], s["W"], radial_at_target=True)
+    d = block.block_G(s["m"], g, Y, s["idx_kj"], s["idx_ji"], s["W"], radial_at_target=False)
+    assert not torch.allclose(c, d, rtol=1e-3, atol=1e-6)
+
+
+def test_radial_at_target_factorises_and_differentiates():
+    # the radial factor leaves the sum over k: A_e = Rad_e^T (sum_t Y(t) (x) x_kj), the re-association
+    # the fast path uses; plus central differences of the gradient w.r.t. the radial basis
+    s = _tiny("G", seed=6)
+    E = len(s["src"])
+    pos64 = torch.tensor(s["pos"], dtype=F64)
+    g, Y = _features(s, pos64)
+    W = s["W"]
+    x = block.act(block.act(s["m"] @ W["W_ba"]) * ((g @ W["W_rbfS"]) @ W["W_rbfB"]) @ W["W_down"])
+    Rad = torch.einsum("en,lnc->elc", g, W["W_c"])
+    B1 = torch.zeros((E, Y.shape[1], x.shape[1]), dtype=F64)
+    B1.index_add_(0, torch.as_tensor(np.asarray(s["idx_ji"]), dtype=torch.long),
+                  Y[:, :, None] * x[torch.as_tensor(np.asarray(s["idx_kj"]), dtype=torch.long)][:, None, :])
+    A = torch.einsum("elc,elf->ecf", Rad, B1)
+    z = torch.einsum("ecf,cfo->eo", A, W["W_bil"])
+    ref = (block.act(s["m"] @ W["W_skip"]) + block.act(z @ W["W_up"])) / math.sqrt(2.0)
+    out = block.block_G(s["m"], g, Y, s["idx_kj"], s["idx_ji"], W, radial_at_target=True)
+    assert torch.allclose(out, ref, rtol=1e-12, atol=1e-13)
+    gq = g.clone().requires_grad_(True)
+    L = (block.block_G(s["m"], gq, Y, s["idx_kj"], s["idx_ji"], W, radial_at_target=True) * s["gup"]).sum()
+    (grad,) = torch.autograd.grad(L, gq)
+    rng = np.random.default_rng(2)
+    for idx in rng.choice(g.numel(), size=8, replace=False):
+        h = 1e-6
+        def at(delta):
+            y = g.clone().reshape(-1)
+            y[idx] += delta
+            return float((block.block_G(s["m"], y.reshape(g.shape), Y, s["idx_kj"], s["idx_ji"], W, radial_at_target=True) * s["gup"]).sum())
+        fd = (at(h) - at(-h)) / (2 * h)
+        assert abs(fd - float(grad.reshape(-1)[idx])) <= 1e-6 * max(1.0, abs(fd))
