@@ -146,6 +146,9 @@ typedef struct {
   int32_t emb_rbf, emb_cbf, emb_bil;   /* G                                        */
   int32_t num_radial, num_spherical, envelope_p;
   int32_t n_res_before, n_res_after;   /* D: residual layers around the skip       */
+  int32_t radial_at_target;            /* G: 0 = radial factor of the triplet basis taken at the source
+                                          edge k->j; 1 = at the target edge j->i, where it leaves the sum
+                                          over k (Sec. 3.4, order of operations of the bilinear layer) */
   float cutoff;
 } gp_dims;
 
@@ -186,6 +189,8 @@ typedef struct {
   const int32_t* row_ptr;      /* [N+1] in-edges of atom j are edge rows row_ptr[j] .. row_ptr[j+1]-1 */
   const int32_t* out_ptr;      /* [N+1] */
   const int32_t* out_list;     /* [E] out_list[out_ptr[j] .. out_ptr[j+1]-1] = ids of the edges whose source is j */
+  const int32_t* perm_kj;      /* [T] optional: ji-major id of the triplet in kj-major slot q; needed only by
+                                  gp_block_backward_G with radial_at_target = 1 and grad_cos_kj requested */
 } gp_graph;
 
 typedef struct {

@@ -63,14 +63,14 @@ def load():
 class _Dims(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "variant", "dtype", "emb", "int_emb", "basis_emb", "emb_rbf", "emb_cbf", "emb_bil",
-        "num_radial", "num_spherical", "envelope_p", "n_res_before", "n_res_after")] + [("cutoff", C.c_float)]
+        "num_radial", "num_spherical", "envelope_p", "n_res_before", "n_res_after", "radial_at_target")] + [("cutoff", C.c_float)]
 
 
 class _Graph(C.Structure):
     _fields_ = [("n_edges", C.c_int64), ("n_triplets", C.c_int64), ("idx_kj", C.c_void_p),
                 ("seg_ptr_ji", C.c_void_p), ("idx_ji_kj", C.c_void_p), ("seg_ptr_kj", C.c_void_p),
                 ("n_atoms", C.c_int64), ("max_in_degree", C.c_int32), ("max_out_degree", C.c_int32),
-                ("row_ptr", C.c_void_p), ("out_ptr", C.c_void_p), ("out_list", C.c_void_p)]
+                ("row_ptr", C.c_void_p), ("out_ptr", C.c_void_p), ("out_list", C.c_void_p), ("perm_kj", C.c_void_p)]
 
 
 class _Basis(C.Structure):
@@ -97,7 +97,7 @@ def Dims(d):
                  int_emb=d.int_emb, basis_emb=d.basis_emb, emb_rbf=d.emb_rbf, emb_cbf=d.emb_cbf,
                  emb_bil=d.emb_bil, num_radial=d.num_radial, num_spherical=d.num_spherical,
                  envelope_p=d.envelope_p, n_res_before=d.n_res_before, n_res_after=d.n_res_after,
-                 cutoff=d.cutoff)
+                 radial_at_target=1 if getattr(d, "radial_at_target", False) else 0, cutoff=d.cutoff)
 
 
 def Graph(g):
@@ -107,7 +107,7 @@ def Graph(g):
                   seg_ptr_kj=_ptr(g.get("seg_ptr_kj")),
                   n_atoms=g.get("n_atoms", 0) if g.get("out_list") is not None else 0,
                   max_in_degree=g.get("max_in_degree", 0), max_out_degree=g.get("max_out_degree", 0), row_ptr=_ptr(g.get("row_ptr")),
-                  out_ptr=_ptr(g.get("out_ptr")), out_list=_ptr(g.get("out_list")))
+                  out_ptr=_ptr(g.get("out_ptr")), out_list=_ptr(g.get("out_list")), perm_kj=_ptr(g.get("perm_kj")))
 
 
 def Basis(b):

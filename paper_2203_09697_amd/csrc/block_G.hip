@@ -25,6 +25,7 @@ constexpr float INV_SQRT2 = 0.70710678118654752440f;
 
 struct saved_G {
   float *z_ba, *gate, *xg, *z_dn, *x, *Radt, *A, *z, *z_up, *z_skip, *Wrbf, *WcT;
+  float* B1;   // radial factor at the target edge only: B1[e,l,f] = sum_t Y_l(t) x[kj(t),f]
 };
 
 size_t carve_saved_G(void* p, const gp_dims* d, int64_t E, saved_G* s) {
@@ -42,6 +43,7 @@ size_t carve_saved_G(void* p, const gp_dims* d, int64_t E, saved_G* s) {
   s->z_skip = c.take<float>(E * H);
   s->Wrbf = c.take<float>(R * H);
   s->WcT = c.take<float>(S * C * R);
+  s->B1 = c.take<float>(d->radial_at_target ? E * S * F : 0);
   return c.off;
 }
 
@@ -54,6 +56,7 @@ struct scratch_G {
   size_t part_bytes;
   void* ybuf;        // per-triplet y in bf16 for the matrix-core triplet kernels (bf16 blocks only)
   size_t ybytes;
+  float *dA, *dB1, *gc_ji;   // radial factor at the target edge only: [E,C,F], [E,S,F], [T]
 };
 
 size_t part_bytes_G(const gp_dims* d, int64_t E) {
@@ -88,6 +91,10 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, int64_t T, scratch_
   s->part_aux = (float*)c.take<char>(s->part_bytes);
   s->ybytes = d->dtype == GP_BF16_F32ACC ? gp_tripG_mfma_scratch(E, T) : 0;
   s->ybuf = c.take<char>(s->ybytes);
+  const bool rt = d->radial_at_target != 0;
+  s->dA = c.take<float>(rt ? E * C * F : 0);
+  s->dB1 = c.take<float>(rt ? E * S * F : 0);
+  s->gc_ji = c.take<float>(rt ? (size_t)T : 0);
   return c.off;
 }
 
@@ -104,9 +111,33 @@ int check_dims_G(gp_ctx* ctx, const gp_dims* d) {
   return GP_OK;
 }
 
+// The triplet kernels walk one of the two sorted views of the triplet list.  Handing them a graph
+// whose two views are exchanged makes the kernel written for "sum over the triplets of a source
+// edge" sum over the triplets of a target edge and vice versa (used when the radial factor sits
+// at the target edge: every formula is the mirror image of the source-edge form).
+gp_graph mirrored(const gp_graph* g) {
+  gp_graph m = *g;
+  m.idx_kj = g->idx_ji_kj;
+  m.seg_ptr_ji = g->seg_ptr_kj;
+  m.idx_ji_kj = g->idx_kj;
+  m.seg_ptr_kj = g->seg_ptr_ji;
+  m.n_atoms = 0;   // the lists by centre atom do not describe the mirrored views
+  m.row_ptr = m.out_ptr = m.out_list = nullptr;
+  return m;
+}
+
+// dst[q] (+)= src[perm[q]]
+__global__ void permute_add_kernel(const float* __restrict__ src, const int32_t* __restrict__ perm, int64_t n,
+                                   int accumulate, float* __restrict__ dst) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= n) return;
+  const float v = src[perm[q]];
+  dst[q] = accumulate ? dst[q] + v : v;
+}
+
 // the dense per-centre-atom form pays once an edge has about a hundred triplets
 bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
-  if (d->dtype != GP_BF16_F32ACC || ctx->trip_mfma == 0) return false;
+  if (d->dtype != GP_BF16_F32ACC || ctx->trip_mfma == 0 || d->radial_at_target) return false;
   if (ctx->trip_mfma == 1) return true;
   return g->n_edges > 0 && (double)g->n_triplets >= 96.0 * (double)g->n_edges;
 }
@@ -165,7 +196,13 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   GP_TRY(gp_permute3(ctx, w->W_c, S, R, C, 0, 2, 1, s.WcT));                        // WcT[(l,c), n]
   e = gp_epilogue(); e.out = s.Radt;
   GP_TRY(gp_gemm_nt(ctx, s.WcT, g, S * C, (int)E, R, e));                           // Radt[(l,c), e]
-  if (want_trip_mfma(ctx, dims, graph) && gp_tripG_mfma_usable(graph, F, S, C))
+  if (dims->radial_at_target) {
+    // A_e = Rad_e^T B1_e,  B1[e,l,f] = sum_{t in seg(e)} Y_l(t) x[kj(t),f]: the radial factor has left the sum
+    GP_REQUIRE(ctx, graph->seg_ptr_kj && (graph->n_triplets == 0 || graph->idx_ji_kj), "gp_block_forward_G: kj-major view missing");
+    const gp_graph gm = mirrored(graph);
+    GP_TRY(gp_tripD_backward(ctx, &gm, basis->cos_alpha, nullptr, nullptr, nullptr, s.x, nullptr, F, S, 1, s.B1, nullptr));
+    GP_TRY(gp_tripG_edge_G(ctx, s.Radt, s.B1, E, S, C, F, s.A));
+  } else if (want_trip_mfma(ctx, dims, graph) && gp_tripG_mfma_usable(graph, F, S, C))
     GP_TRY(gp_tripG_forward_mfma(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes));
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
@@ -214,6 +251,27 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   e = gp_epilogue(); e.out = grad_m_in;
   GP_TRY(gp_gemm_nt(ctx, d_skip, w->W_skip, E, H, H, e));                           // dm (skip path)
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part_aux, sc.part_bytes); }, {}));
+  if (dims->radial_at_target) {
+    // mirror image of the source-edge form: G[e',c,o] = sum_{t: kj(t)=e'} y'_t[c] dz[ji(t),o] with
+    // y'_t[c] = sum_l Y_l(t) Rad[ji(t),l,c] is the forward kernel on the mirrored views
+    const gp_graph gm = mirrored(graph);
+    GP_TRY(gp_tripD_forward(ctx, &gm, basis->cos_alpha_kj, sc.dz, s.Radt, nullptr, O, S, C, nullptr, sc.Gm));
+    GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                 // [(c,o), f]
+    e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
+    GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e));                       // dz_dn
+    GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 2, 0, 1, sc.WbilV));                 // [o, (c,f)]
+    e = gp_epilogue(); e.out = sc.dA;
+    GP_TRY(gp_gemm_nn(ctx, sc.dz, sc.WbilV, E, C * F, O, e));                       // dA[e, (c,f)]
+    GP_TRY(gp_tripG_edge_dRad(ctx, sc.dA, s.B1, E, S, C, F, sc.dRad));              // dRad[e, (l,c)]
+    if (grad_cos_kj && graph->n_triplets > 0) {
+      GP_REQUIRE(ctx, graph->perm_kj, "gp_block_backward_G: graph->perm_kj is needed for grad_cos_kj with radial_at_target");
+      GP_TRY(gp_tripG_edge_U(ctx, s.Radt, sc.dA, E, S, C, F, sc.dB1));              // dB1[e,l,f]
+      GP_TRY(gp_tripG_grad_cos(ctx, &gm, basis->cos_alpha, sc.dB1, s.x, F, S, 0, sc.gc_ji));   // ji-major order
+      permute_add_kernel<<<(unsigned)((graph->n_triplets + 255) / 256), 256, 0, ctx->stream>>>(
+          sc.gc_ji, graph->perm_kj, graph->n_triplets, accumulate_basis_grads, grad_cos_kj);
+      GP_LAUNCH_CHECK(ctx, "permute_add_kernel");
+    }
+  } else {
   // one pass over the triplets (kj-major): H[e', l, o]
   const bool bwd_mfma = want_trip_mfma(ctx, dims, graph) && gp_tripG_mfma_bwd_usable(graph, O, S);
   if (bwd_mfma)
@@ -235,6 +293,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
       GP_TRY(gp_tripG_grad_cos_mfma(ctx, graph, basis->cos_alpha_kj, sc.U, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj));
     else
       GP_TRY(gp_tripG_grad_cos(ctx, graph, basis->cos_alpha_kj, sc.U, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj));
+  }
   }
   GP_TRY(gp_gemm_tn(ctx, g, sc.dRad, E, R, S * C, sc.dWcP, nullptr, sc.part, sc.part_bytes));   // [n, (l,c)]
   GP_TRY(gp_permute3(ctx, sc.dWcP, R, S, C, 1, 0, 2, gw->W_c));                     // -> [l, n, c]

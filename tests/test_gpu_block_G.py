@@ -64,3 +64,21 @@ def test_block_G_cfg4_widths_small_graph(lib, ctx):
     # configuration-4 layer widths (emb 1024, emb_trip 128) on a 60-atom box with long segments
     w = synth.get_workload("cfg4", dtype="f32", cutoff=6.0)
     _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3))
+
+
+# ---- radial factor of the triplet basis at the target edge (the mirrored form) ----
+def test_block_G_radial_at_target_small_dims(lib, ctx):
+    w = synth.get_workload("cfg3", emb=32, int_emb=16, emb_rbf=4, emb_cbf=5, emb_bil=12, num_radial=9,
+                           num_spherical=4, cutoff=4.0, dtype="f32", radial_at_target=True)
+    _parity(lib, ctx, w, 0, 2, synth.cube_positions(30, 6.0, 0.9, seed=1))
+
+
+def test_block_G_radial_at_target_cfg3_shape(lib, ctx):
+    w = synth.get_workload("cfg3", dtype="f32", radial_at_target=True)
+    _parity(lib, ctx, w, 1, 1, synth.slab_adsorbate_positions(1, 8, 5, 4, 40, seed=2))
+
+
+def test_block_G_radial_at_target_cfg4_widths_bf16(lib, ctx):
+    w = synth.get_workload("cfg4", cutoff=6.0, radial_at_target=True)
+    assert w.dims.dtype == "bf16"
+    _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3), tol=2e-2)

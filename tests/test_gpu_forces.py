@@ -91,3 +91,13 @@ def test_forces_bf16_cfg3_widths(lib, ctx, mode):
         lib.gp_set_triplet_mfma(ctx, -1)
     assert abs(E_gpu.sum() - E_ref) <= 2e-2 * max(1.0, abs(E_ref))
     assert H.rel_l2(f_gpu, f_ref) <= 2e-2, H.rel_l2(f_gpu, f_ref)
+
+
+def test_forces_radial_at_target(lib, ctx):
+    # the mirrored form: grad of cos(alpha) is produced in ji-major order and permuted; two blocks accumulate
+    w = synth.get_workload("cfg5", emb=32, int_emb=16, emb_rbf=4, emb_cbf=5, emb_bil=12, num_radial=9,
+                           num_spherical=4, cutoff=4.0, dtype="f32", radial_at_target=True)
+    pos, E_gpu, f_gpu, E_ref, f_ref, e = _force_case(lib, ctx, w, synth.cube_positions(30, 6.0, 0.9, seed=2), 5, 2, 7)
+    assert abs(E_gpu.sum() - E_ref) <= 1e-4 * max(1.0, abs(E_ref))
+    assert H.rel_l2(f_gpu, f_ref) <= 1e-4, H.rel_l2(f_gpu, f_ref)
+    assert np.abs(f_gpu.sum(axis=0)).max() <= 1e-4 * np.abs(f_ref).max() * np.sqrt(len(pos))
