@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--radial-at-target", action="store_true",
+                    help="variant-G workloads: radial factor of the triplet basis at the target edge")
     ap.add_argument("--output-blocks", action="store_true",
                     help="variant-D workloads: add an output block (out_emb 256, 3 layers) after every interaction "
                          "block and differentiate the summed energies instead of a random upstream gradient")
@@ -113,8 +115,10 @@ def main():
     from paper_2203_09697_amd.binding_g import StackG
     from paper_2203_09697_amd.stack import StackD
 
-    w = synth.get_workload(a.workload)
+    w = synth.get_workload(a.workload, radial_at_target=True) if a.radial_at_target else synth.get_workload(a.workload)
     dims = w.dims
+    if a.radial_at_target and dims.variant != "G":
+        sys.exit("bench.py: --radial-at-target applies to the variant-G workloads (cfg3, cfg4, cfg5)")
     pos, gptr = synth.make_positions(w, a.seed)
     ctx = gp.Context(0)
     dpos = torch.as_tensor(pos).to("cuda:0")
@@ -236,7 +240,8 @@ def main():
         "config": {"workload": "%s: %d structures, N=%d atoms, E=%d edges, T=%d triplets, %d blocks, variant %s, "
                                "emb=%d int_emb=%d%s" % (w.name, len(gptr) - 1, len(pos), E, T, w.n_blocks, dims.variant,
                                                         dims.emb, dims.int_emb, ", energy head + forces" if w.head_hidden else
-                                                        ", output block per interaction block" if a.output_blocks else ""),
+                                                        ", output block per interaction block" if a.output_blocks else
+                                                        ", radial factor at the target edge" if a.radial_at_target else ""),
                    "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed},
         "roofline": roofline,
         "measured_peaks": {k: round(v, 1) for k, v in mp.items()},
