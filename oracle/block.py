@@ -70,13 +70,18 @@ def block_D(m, rbf, sbf, idx_kj, idx_ji, W, n_res_before=1, n_res_after=2):
     return h
 
 
-def block_G(m, g, Y, idx_kj, idx_ji, W, radial_at_target=False):
+def block_G(m, g, Y, idx_kj, idx_ji, W, radial_at_target=False, id_swap=None):
     """Variant G.  m [E,emb], g [E,R] Gaussian rbf, Y [T,S] = Y_l0(cos alpha).
 
     The radial factor of the triplet basis is taken at the source edge k->j of the triplet, or,
     with radial_at_target, at its target edge j->i (the ordering of operations in which the
     radial factor leaves the sum over k; Sec. 3.4 speaks of choosing the order of operations of
     the bilinear layer).  Here the sum is written out per triplet in both cases.
+
+    With id_swap (the opposite edge of every edge, -1 if absent) the two messages on a bond are
+    coupled (Sec. 3.4, symmetric message passing): the triplet result z is up-projected twice and
+    edge e receives (act(z_e W_up) + act(z_swap(e) W_up_ac)) / sqrt(2), the second term being
+    zero where the opposite edge does not exist.
     """
     E = m.shape[0]
     x = act(m @ W["W_ba"])
@@ -86,7 +91,13 @@ def block_G(m, g, Y, idx_kj, idx_ji, W, radial_at_target=False):
     y = torch.einsum("tl,tlc->tc", Y, Rad[_long(idx_ji if radial_at_target else idx_kj)])      # [T, emb_cbf]
     A = triplet_aggregate_G(x, y, idx_kj, idx_ji, E)           # [E, emb_cbf, emb_trip]
     z = torch.einsum("ecf,cfo->eo", A, W["W_bil"])             # [E, emb_bil]
-    return (act(m @ W["W_skip"]) + act(z @ W["W_up"])) / math.sqrt(2.0)
+    x3 = act(z @ W["W_up"])
+    if id_swap is not None:
+        sw = _long(id_swap)
+        x_ac = act(z @ W["W_up_ac"])
+        has = (sw >= 0).to(F64)[:, None]
+        x3 = (x3 + x_ac[sw.clamp(min=0)] * has) / math.sqrt(2.0)
+    return (act(m @ W["W_skip"]) + x3) / math.sqrt(2.0)
 
 
 def stack_D(m, rbf, sbf, idx_kj, idx_ji, W_list, n_res_before=1, n_res_after=2):
@@ -95,9 +106,9 @@ def stack_D(m, rbf, sbf, idx_kj, idx_ji, W_list, n_res_before=1, n_res_after=2):
     return m
 
 
-def stack_G(m, g, Y, idx_kj, idx_ji, W_list, radial_at_target=False):
+def stack_G(m, g, Y, idx_kj, idx_ji, W_list, radial_at_target=False, id_swap=None):
     for W in W_list:
-        m = block_G(m, g, Y, idx_kj, idx_ji, W, radial_at_target)
+        m = block_G(m, g, Y, idx_kj, idx_ji, W, radial_at_target, id_swap)
     return m
 
 

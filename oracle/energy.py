@@ -10,7 +10,7 @@ the input messages m are held fixed).
 import numpy as np
 import torch
 
-from . import basis, block
+from . import basis, block, graph
 
 F64 = torch.float64
 
@@ -28,7 +28,8 @@ def energy_G(pos, src, dst, idx_kj, idx_ji, m0, W_list, Wh, dims):
     d, _unit, cos_alpha = basis.geometry(pos, src, dst, idx_kj, idx_ji)
     g = basis.rbf_gauss(d, dims.cutoff, dims.num_radial, dims.envelope_p)
     Y = basis.y_l0(cos_alpha, dims.num_spherical)
-    m = block.stack_G(m0, g, Y, idx_kj, idx_ji, W_list, getattr(dims, "radial_at_target", False))
+    id_swap = graph.reverse_edges(src, dst) if getattr(dims, "symmetric", False) else None
+    m = block.stack_G(m0, g, Y, idx_kj, idx_ji, W_list, getattr(dims, "radial_at_target", False), id_swap)
     E, _ = energy_head(m, dst, pos.shape[0], Wh)
     return E
 

@@ -122,3 +122,11 @@ def triplets_loops(edge_pairs):
             if j2 == j and k != i:
                 out.append((e2, e))
     return out
+
+
+def reverse_edges(src, dst):
+    """id_swap[e] = id of the edge running opposite to edge e (dst[e] -> src[e]), or -1 if the edge
+    list has none (a neighbour cap can keep j->i and drop i->j).  Needed to couple the two
+    messages on the same bond (Sec. 3.4, symmetric message passing)."""
+    where = {(int(s), int(d)): e for e, (s, d) in enumerate(zip(src, dst))}
+    return np.array([where.get((int(d), int(s)), -1) for s, d in zip(src, dst)], dtype=np.int64)

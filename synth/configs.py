@@ -25,6 +25,7 @@ class BlockDims:
     n_res_before: int = 1   # variant D
     n_res_after: int = 2    # variant D
     radial_at_target: bool = False   # variant G: radial factor of the triplet basis at the target edge j->i
+    symmetric: bool = False          # variant G: couple the two messages on a bond (second up-projection W_up_ac)
 
 
 @dataclass(frozen=True)

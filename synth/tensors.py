@@ -60,6 +60,8 @@ def weights_G(dims, seed=0):
                         fan_in=dims.emb_cbf * t, fan_out=dims.emb_bil)
     w["W_up"] = glorot(rng, (dims.emb_bil, e))
     w["W_skip"] = glorot(rng, (e, e))
+    if getattr(dims, "symmetric", False):
+        w["W_up_ac"] = glorot(rng, (dims.emb_bil, e))
     return w
 
 

@@ -66,7 +66,8 @@ def oracle_stack_G(g, ob, dims, W_list, m, gup, want_grad_rbf=False):
     Wt = [{k: v.clone().requires_grad_(True) for k, v in t64(W).items()} for W in W_list]
     mt = torch.tensor(m, dtype=F64, requires_grad=True)
     rbf = ob["rbf"].detach().clone().requires_grad_(True)
-    out = oblock.stack_G(mt, rbf, ob["Y"], g["idx_kj"], g["idx_ji"], Wt, getattr(dims, "radial_at_target", False))
+    id_swap = ograph.reverse_edges(g["src"], g["dst"]) if getattr(dims, "symmetric", False) else None
+    out = oblock.stack_G(mt, rbf, ob["Y"], g["idx_kj"], g["idx_ji"], Wt, getattr(dims, "radial_at_target", False), id_swap)
     leaves = [mt, rbf] + [W[k] for W in Wt for k in W]
     grads = oblock.loss_and_grads(out, torch.tensor(gup, dtype=F64), leaves)
     gm, grbf = grads[0].numpy(), grads[1].numpy()

@@ -379,3 +379,70 @@ def test_radial_at_target_factorises_and_differentiates():
             return float((block.block_G(s["m"], y.reshape(g.shape), Y, s["idx_kj"], s["idx_ji"], W, radial_at_target=True) * s["gup"]).sum())
         fd = (at(h) - at(-h)) / (2 * h)
         assert abs(fd - float(grad.reshape(-1)[idx])) <= 1e-6 * max(1.0, abs(fd))
+
+
+# ---- symmetric message passing ------------------------------------------------------------------
+def test_reverse_edges_is_an_involution_and_respects_the_cap():
+    pos, gptr = synth.cube_positions(14, 4.5, 0.9, seed=8)
+    src, dst, _ = graph.edges(pos, gptr, 3.2)                 # no cap: every edge has its opposite
+    sw = graph.reverse_edges(src, dst)
+    assert (sw >= 0).all() and np.array_equal(sw[sw], np.arange(len(src)))
+    assert np.array_equal(np.asarray(src)[sw], dst) and np.array_equal(np.asarray(dst)[sw], src)
+    src, dst, _ = graph.edges(pos, gptr, 3.2, 3)              # cap 3: some edges lose their opposite
+    sw = graph.reverse_edges(src, dst)
+    pairs = set(zip(map(int, src), map(int, dst)))
+    for e in range(len(src)):
+        has = (int(dst[e]), int(src[e])) in pairs
+        assert (sw[e] >= 0) == has
+        if has:
+            assert src[sw[e]] == dst[e] and dst[sw[e]] == src[e] and sw[sw[e]] == e
+    assert (sw < 0).any()
+
+
+def test_symmetric_block_matches_explicit_loops_and_gradients():
+    s = _tiny("G", seed=9, n_atoms=10)
+    E = len(s["src"])
+    pos64 = torch.tensor(s["pos"], dtype=F64)
+    g, Y = _features(s, pos64)
+    rng = np.random.default_rng(3)
+    W = dict(s["W"])
+    W["W_up_ac"] = torch.tensor(rng.uniform(-0.4, 0.4, tuple(W["W_up"].shape)), dtype=F64)
+    # drop the opposite of a few edges by hand to exercise the "absent" branch
+    sw = graph.reverse_edges(s["src"], s["dst"])
+    sw[[0, 5, 7]] = -1
+    out = block.block_G(s["m"], g, Y, s["idx_kj"], s["idx_ji"], W, id_swap=sw).numpy()
+    # explicit: recompute z exactly as the non-symmetric block does, then couple edge by edge
+    Wz = {k: v for k, v in W.items() if k != "W_up_ac"}
+    Wz = dict(Wz)
+    x = block.act(block.act(s["m"] @ W["W_ba"]) * ((g @ W["W_rbfS"]) @ W["W_rbfB"]) @ W["W_down"])
+    Rad = torch.einsum("en,lnc->elc", g, W["W_c"])
+    kj = torch.as_tensor(np.asarray(s["idx_kj"]), dtype=torch.long)
+    y = torch.einsum("tl,tlc->tc", Y, Rad[kj])
+    A = block.triplet_aggregate_G(x, y, s["idx_kj"], s["idx_ji"], E)
+    z = torch.einsum("ecf,cfo->eo", A, W["W_bil"]).numpy()
+    mn = s["m"].numpy()
+    ref = np.zeros_like(mn)
+    for e in range(E):
+        x3 = _silu(z[e] @ W["W_up"].numpy())
+        if sw[e] >= 0:
+            x3 = x3 + _silu(z[sw[e]] @ W["W_up_ac"].numpy())
+        x3 = x3 / math.sqrt(2.0)
+        ref[e] = (_silu(mn[e] @ W["W_skip"].numpy()) + x3) / math.sqrt(2.0)
+    assert np.allclose(out, ref, rtol=1e-12, atol=1e-13)
+    # central differences w.r.t. the new weight and the input messages
+    def loss(m_, Wac):
+        W2 = dict(W)
+        W2["W_up_ac"] = Wac
+        return (block.block_G(m_, g, Y, s["idx_kj"], s["idx_ji"], W2, id_swap=sw) * s["gup"]).sum()
+    mq, wq = s["m"].clone().requires_grad_(True), W["W_up_ac"].clone().requires_grad_(True)
+    gm, gw = torch.autograd.grad(loss(mq, wq), [mq, wq])
+    for name, x0, gr in (("m", s["m"], gm), ("W_up_ac", W["W_up_ac"], gw)):
+        for idx in rng.choice(x0.numel(), size=6, replace=False):
+            h = 1e-6
+            def at(delta):
+                yv = x0.clone().reshape(-1)
+                yv[idx] += delta
+                yv = yv.reshape(x0.shape)
+                return float(loss(yv, W["W_up_ac"]) if name == "m" else loss(s["m"], yv))
+            fd = (at(h) - at(-h)) / (2 * h)
+            assert abs(fd - float(gr.reshape(-1)[idx])) <= 1e-6 * max(1.0, abs(fd)), name
