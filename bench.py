@@ -97,6 +97,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--radial-at-target", action="store_true",
                     help="variant-G workloads: radial factor of the triplet basis at the target edge")
+    ap.add_argument("--symmetric", action="store_true",
+                    help="variant-G workloads: symmetric message passing (second up-projection gathered from the opposite edge)")
     ap.add_argument("--output-blocks", action="store_true",
                     help="variant-D workloads: add an output block (out_emb 256, 3 layers) after every interaction "
                          "block and differentiate the summed energies instead of a random upstream gradient")
@@ -115,10 +117,11 @@ def main():
     from paper_2203_09697_amd.binding_g import StackG
     from paper_2203_09697_amd.stack import StackD
 
-    w = synth.get_workload(a.workload, radial_at_target=True) if a.radial_at_target else synth.get_workload(a.workload)
+    opts = {k: True for k, on in (("radial_at_target", a.radial_at_target), ("symmetric", a.symmetric)) if on}
+    w = synth.get_workload(a.workload, **opts)
     dims = w.dims
-    if a.radial_at_target and dims.variant != "G":
-        sys.exit("bench.py: --radial-at-target applies to the variant-G workloads (cfg3, cfg4, cfg5)")
+    if opts and dims.variant != "G":
+        sys.exit("bench.py: --radial-at-target / --symmetric apply to the variant-G workloads (cfg3, cfg4, cfg5)")
     pos, gptr = synth.make_positions(w, a.seed)
     ctx = gp.Context(0)
     dpos = torch.as_tensor(pos).to("cuda:0")
@@ -241,7 +244,8 @@ def main():
                                "emb=%d int_emb=%d%s" % (w.name, len(gptr) - 1, len(pos), E, T, w.n_blocks, dims.variant,
                                                         dims.emb, dims.int_emb, ", energy head + forces" if w.head_hidden else
                                                         ", output block per interaction block" if a.output_blocks else
-                                                        ", radial factor at the target edge" if a.radial_at_target else ""),
+                                                        (", radial factor at the target edge" if a.radial_at_target else "") +
+                                                        (", symmetric messages" if a.symmetric else "")),
                    "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed},
         "roofline": roofline,
         "measured_peaks": {k: round(v, 1) for k, v in mp.items()},

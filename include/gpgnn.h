@@ -125,6 +125,12 @@ int gp_triplets_fill(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const 
                      int64_t n_triplets, int32_t* idx_kj, int32_t* idx_ji, int32_t* seg_ptr_ji,
                      int32_t* perm_kj, int32_t* idx_ji_kj, int32_t* seg_ptr_kj);
 
+/* Opposite edges (Sec. 3.4, symmetric message passing couples m_ji and m_ij): for an edge list
+ * sorted by (dst, src) with its row_ptr, id_swap[e] = id of the edge dst[e] -> src[e], or -1 if
+ * the list has none (a neighbour cap can keep one direction only).  Exact (integer) result. */
+int gp_reverse_edges(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
+                     int64_t n_atoms, int64_t n_edges, int32_t* id_swap);
+
 /* Largest row length ptr[i+1] - ptr[i], i < n, of a device-resident offsets array with n+1
  * entries (e.g. the largest in-degree, for gp_graph.max_in_degree).  ws: device scratch of at
  * least 4 bytes.  Synchronises the context's stream; *max_degree is a host variable. */
@@ -146,6 +152,8 @@ typedef struct {
   int32_t emb_rbf, emb_cbf, emb_bil;   /* G                                        */
   int32_t num_radial, num_spherical, envelope_p;
   int32_t n_res_before, n_res_after;   /* D: residual layers around the skip       */
+  int32_t symmetric;                   /* G: 1 = couple the two messages on a bond (Sec. 3.4, symmetric message
+                                          passing): needs gp_graph.id_swap and gp_weights_G.W_up_ac */
   int32_t radial_at_target;            /* G: 0 = radial factor of the triplet basis taken at the source
                                           edge k->j; 1 = at the target edge j->i, where it leaves the sum
                                           over k (Sec. 3.4, order of operations of the bilinear layer) */
@@ -191,6 +199,8 @@ typedef struct {
   const int32_t* out_list;     /* [E] out_list[out_ptr[j] .. out_ptr[j+1]-1] = ids of the edges whose source is j */
   const int32_t* perm_kj;      /* [T] optional: ji-major id of the triplet in kj-major slot q; needed only by
                                   gp_block_backward_G with radial_at_target = 1 and grad_cos_kj requested */
+  const int32_t* id_swap;      /* [E] optional: id of the edge opposite to edge e, -1 if absent (gp_reverse_edges);
+                                  needed only by blocks with gp_dims.symmetric = 1 */
 } gp_graph;
 
 typedef struct {
@@ -248,6 +258,9 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
  */
 typedef struct {
   float *W_ba, *W_rbfS, *W_rbfB, *W_down, *W_c, *W_bil, *W_up, *W_skip;
+  float *W_up_ac;   /* [emb_bil, emb]; symmetric = 1 only (else ignored, may be NULL):
+                       m' = (act(m W_skip) + (act(z W_up) + act(z W_up_ac)[id_swap]) / sqrt(2)) / sqrt(2),
+                       the gathered term being zero where id_swap < 0 */
 } gp_weights_G;
 
 int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,

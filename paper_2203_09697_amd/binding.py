@@ -7,7 +7,7 @@ import torch
 __all__ = [
     "GpError", "load", "library_path", "Context", "Dims", "Graph", "Basis",
     "gp_version", "gp_profile_enable", "gp_profile_reset", "gp_profile_collect", "gp_set_side_stream", "gp_set_triplet_mfma",
-    "gp_measure_peaks", "gp_edges_by_source", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
+    "gp_measure_peaks", "gp_edges_by_source", "gp_reverse_edges", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
     "gp_block_forward_D", "gp_block_backward_D", "gp_triplet_aggregate_fwd",
     "gp_triplet_aggregate_bwd", "gp_linear_forward", "build_graph", "weights_to_device",
     "EXPORTED_SYMBOLS", "D_WEIGHT_ORDER",
@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "gp_create", "gp_destroy", "gp_last_error", "gp_version",
     "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get", "gp_set_side_stream", "gp_set_triplet_mfma", "gp_measure_peaks",
     "gp_edges_workspace", "gp_edges_count", "gp_edges_fill",
-    "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill", "gp_csr_max_degree",
+    "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill", "gp_csr_max_degree", "gp_reverse_edges",
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
     "gp_block_forward_G", "gp_block_backward_G",
     "gp_energy_workspace", "gp_energy_forward", "gp_energy_backward",
@@ -63,14 +63,14 @@ def load():
 class _Dims(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "variant", "dtype", "emb", "int_emb", "basis_emb", "emb_rbf", "emb_cbf", "emb_bil",
-        "num_radial", "num_spherical", "envelope_p", "n_res_before", "n_res_after", "radial_at_target")] + [("cutoff", C.c_float)]
+        "num_radial", "num_spherical", "envelope_p", "n_res_before", "n_res_after", "symmetric", "radial_at_target")] + [("cutoff", C.c_float)]
 
 
 class _Graph(C.Structure):
     _fields_ = [("n_edges", C.c_int64), ("n_triplets", C.c_int64), ("idx_kj", C.c_void_p),
                 ("seg_ptr_ji", C.c_void_p), ("idx_ji_kj", C.c_void_p), ("seg_ptr_kj", C.c_void_p),
                 ("n_atoms", C.c_int64), ("max_in_degree", C.c_int32), ("max_out_degree", C.c_int32),
-                ("row_ptr", C.c_void_p), ("out_ptr", C.c_void_p), ("out_list", C.c_void_p), ("perm_kj", C.c_void_p)]
+                ("row_ptr", C.c_void_p), ("out_ptr", C.c_void_p), ("out_list", C.c_void_p), ("perm_kj", C.c_void_p), ("id_swap", C.c_void_p)]
 
 
 class _Basis(C.Structure):
@@ -97,6 +97,7 @@ def Dims(d):
                  int_emb=d.int_emb, basis_emb=d.basis_emb, emb_rbf=d.emb_rbf, emb_cbf=d.emb_cbf,
                  emb_bil=d.emb_bil, num_radial=d.num_radial, num_spherical=d.num_spherical,
                  envelope_p=d.envelope_p, n_res_before=d.n_res_before, n_res_after=d.n_res_after,
+                 symmetric=1 if getattr(d, "symmetric", False) else 0,
                  radial_at_target=1 if getattr(d, "radial_at_target", False) else 0, cutoff=d.cutoff)
 
 
@@ -107,7 +108,7 @@ def Graph(g):
                   seg_ptr_kj=_ptr(g.get("seg_ptr_kj")),
                   n_atoms=g.get("n_atoms", 0) if g.get("out_list") is not None else 0,
                   max_in_degree=g.get("max_in_degree", 0), max_out_degree=g.get("max_out_degree", 0), row_ptr=_ptr(g.get("row_ptr")),
-                  out_ptr=_ptr(g.get("out_ptr")), out_list=_ptr(g.get("out_list")), perm_kj=_ptr(g.get("perm_kj")))
+                  out_ptr=_ptr(g.get("out_ptr")), out_list=_ptr(g.get("out_list")), perm_kj=_ptr(g.get("perm_kj")), id_swap=_ptr(g.get("id_swap")))
 
 
 def Basis(b):
@@ -275,7 +276,16 @@ def gp_triplets(ctx, edges, with_kj=True):
         mo = C.c_int32()
         ctx.check(lib.gp_csr_max_degree(ctx._h, _ptr(out_ptr), C.c_int64(N), _ptr(ws), C.c_size_t(ws.numel()), C.byref(mo)))
         out.update(n_atoms=N, row_ptr=edges["row_ptr"], out_ptr=out_ptr, out_list=out_list, max_in_degree=md.value,
-                   max_out_degree=mo.value)
+                   max_out_degree=mo.value, id_swap=gp_reverse_edges(ctx, edges))
+    return out
+
+
+def gp_reverse_edges(ctx, edges):
+    """id_swap[E]: id of the opposite edge of every edge, -1 where the list has none."""
+    N, E = edges["n_atoms"], edges["n_edges"]
+    out = torch.empty(E, dtype=torch.int32, device=ctx.device)
+    ctx.check(load().gp_reverse_edges(ctx._h, _ptr(edges["src"]), _ptr(edges["dst"]), _ptr(edges["row_ptr"]), C.c_int64(N),
+                                      C.c_int64(E), _ptr(out)))
     return out
 
 

@@ -7,7 +7,7 @@ from . import binding as B
 
 __all__ = ["G_WEIGHT_NAMES", "gp_block_forward_G", "gp_block_backward_G", "StackG"]
 
-G_WEIGHT_NAMES = ("W_ba", "W_rbfS", "W_rbfB", "W_down", "W_c", "W_bil", "W_up", "W_skip")
+G_WEIGHT_NAMES = ("W_ba", "W_rbfS", "W_rbfB", "W_down", "W_c", "W_bil", "W_up", "W_skip", "W_up_ac")
 
 
 class _WeightsG(C.Structure):
@@ -17,7 +17,7 @@ class _WeightsG(C.Structure):
 def _weights_G(w):
     s = _WeightsG()
     for n in G_WEIGHT_NAMES:
-        setattr(s, n, B._ptr(w[n]))
+        setattr(s, n, B._ptr(w.get(n)))     # W_up_ac exists only for symmetric blocks
     return s
 
 

@@ -26,6 +26,7 @@ constexpr float INV_SQRT2 = 0.70710678118654752440f;
 struct saved_G {
   float *z_ba, *gate, *xg, *z_dn, *x, *Radt, *A, *z, *z_up, *z_skip, *Wrbf, *WcT;
   float* B1;   // radial factor at the target edge only: B1[e,l,f] = sum_t Y_l(t) x[kj(t),f]
+  float* z_ac; // symmetric blocks only: pre-activation of the second up-projection [E, H]
 };
 
 size_t carve_saved_G(void* p, const gp_dims* d, int64_t E, saved_G* s) {
@@ -44,6 +45,7 @@ size_t carve_saved_G(void* p, const gp_dims* d, int64_t E, saved_G* s) {
   s->Wrbf = c.take<float>(R * H);
   s->WcT = c.take<float>(S * C * R);
   s->B1 = c.take<float>(d->radial_at_target ? E * S * F : 0);
+  s->z_ac = c.take<float>(d->symmetric ? E * H : 0);
   return c.off;
 }
 
@@ -57,6 +59,7 @@ struct scratch_G {
   void* ybuf;        // per-triplet y in bf16 for the matrix-core triplet kernels (bf16 blocks only)
   size_t ybytes;
   float *dA, *dB1, *gc_ji;   // radial factor at the target edge only: [E,C,F], [E,S,F], [T]
+  float* eh5;                // symmetric blocks only: a fifth [E, H] buffer
 };
 
 size_t part_bytes_G(const gp_dims* d, int64_t E) {
@@ -95,6 +98,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, int64_t T, scratch_
   s->dA = c.take<float>(rt ? E * C * F : 0);
   s->dB1 = c.take<float>(rt ? E * S * F : 0);
   s->gc_ji = c.take<float>(rt ? (size_t)T : 0);
+  s->eh5 = c.take<float>(d->symmetric ? E * H : 0);
   return c.off;
 }
 
@@ -126,6 +130,28 @@ gp_graph mirrored(const gp_graph* g) {
   return m;
 }
 
+// Symmetric message passing, forward: t[e,:] = sqrt(2) t[e,:] + u_ac[id_swap[e],:] (second term 0 without an
+// opposite edge); the up-projection GEMM then stores (act(.) + t) / 2.
+__global__ void sym_mix_kernel(float* __restrict__ t, const float* __restrict__ u_ac, const int32_t* __restrict__ id_swap,
+                               int64_t E, int H) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= E * H) return;
+  const int sw = id_swap[i / H];
+  t[i] = 1.41421356237309504880f * t[i] + (sw >= 0 ? u_ac[(int64_t)sw * H + (i % H)] : 0.f);
+}
+// backward: d_up = g/2 silu'(z_up), d_skip = g/sqrt(2) silu'(z_skip), d_ac[e] = g[id_swap[e]]/2 silu'(z_ac[e]) (0 if none)
+__global__ void sym_bwd_kernel(const float* __restrict__ g, const float* __restrict__ z_up, const float* __restrict__ z_skip,
+                               const float* __restrict__ z_ac, const int32_t* __restrict__ id_swap, int64_t E, int H,
+                               float* __restrict__ d_up, float* __restrict__ d_skip, float* __restrict__ d_ac) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= E * H) return;
+  const float gv = g[i];
+  d_up[i] = 0.5f * gv * dsilu_f(z_up[i]);
+  d_skip[i] = 0.70710678118654752440f * gv * dsilu_f(z_skip[i]);
+  const int sw = id_swap[i / H];
+  d_ac[i] = sw >= 0 ? 0.5f * g[(int64_t)sw * H + (i % H)] * dsilu_f(z_ac[i]) : 0.f;
+}
+
 // dst[q] (+)= src[perm[q]]
 __global__ void permute_add_kernel(const float* __restrict__ src, const int32_t* __restrict__ perm, int64_t n,
                                    int accumulate, float* __restrict__ dst) {
@@ -142,8 +168,9 @@ bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
   return g->n_edges > 0 && (double)g->n_triplets >= 96.0 * (double)g->n_edges;
 }
 
-int check_weights_G(gp_ctx* ctx, const gp_weights_G* w, const char* what) {
+int check_weights_G(gp_ctx* ctx, const gp_dims* d, const gp_weights_G* w, const char* what) {
   GP_REQUIRE(ctx, w, "%s is NULL", what);
+  GP_REQUIRE(ctx, !d->symmetric || w->W_up_ac, "%s: W_up_ac is needed by a symmetric block", what);
   GP_REQUIRE(ctx, w->W_ba && w->W_rbfS && w->W_rbfB && w->W_down && w->W_c && w->W_bil && w->W_up && w->W_skip,
              "%s has a NULL member", what);
   return GP_OK;
@@ -167,7 +194,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
                        void* scratch, size_t scratch_bytes) {
   if (!ctx) return GP_BAD_ARG;
   GP_TRY(check_dims_G(ctx, dims));
-  GP_TRY(check_weights_G(ctx, w, "weights"));
+  GP_TRY(check_weights_G(ctx, dims, w, "weights"));
   GP_REQUIRE(ctx, graph && basis, "gp_block_forward_G: graph/basis is NULL");
   const int64_t E = graph->n_edges;
   GP_REQUIRE(ctx, E >= 0 && graph->n_triplets >= 0, "gp_block_forward_G: negative size");
@@ -211,6 +238,19 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   float* t_skip = sc.eh[0];
   e = gp_epilogue(); e.save_pre = s.z_skip; e.act = 1; e.out = t_skip;
   GP_TRY(gp_gemm_nn(ctx, m_in, w->W_skip, E, H, H, e));
+  if (dims->symmetric) {
+    // m' = (t_skip + (act(z W_up) + act(z W_up_ac)[id_swap]) / sqrt(2)) / sqrt(2) = (act(z W_up) + t) / 2,
+    // t = sqrt(2) t_skip + act(z W_up_ac)[id_swap]
+    GP_REQUIRE(ctx, graph->id_swap, "gp_block_forward_G: graph->id_swap is needed by a symmetric block");
+    float* u_ac = sc.eh[1];
+    e = gp_epilogue(); e.save_pre = s.z_ac; e.act = 1; e.out = u_ac;
+    GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up_ac, E, H, O, e));
+    sym_mix_kernel<<<(unsigned)(((int64_t)E * H + 255) / 256), 256, 0, ctx->stream>>>(t_skip, u_ac, graph->id_swap, E, H);
+    GP_LAUNCH_CHECK(ctx, "sym_mix_kernel");
+    e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = 0.5f; e.out = m_out;
+    GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
+    return GP_OK;
+  }
   e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = INV_SQRT2; e.out = m_out;
   GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
   return GP_OK;
@@ -222,8 +262,8 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
                         float* grad_cos_kj, int32_t accumulate_basis_grads, void* scratch, size_t scratch_bytes) {
   if (!ctx) return GP_BAD_ARG;
   GP_TRY(check_dims_G(ctx, dims));
-  GP_TRY(check_weights_G(ctx, w, "weights"));
-  GP_TRY(check_weights_G(ctx, gw, "grad_w"));
+  GP_TRY(check_weights_G(ctx, dims, w, "weights"));
+  GP_TRY(check_weights_G(ctx, dims, gw, "grad_w"));
   GP_REQUIRE(ctx, graph && basis, "gp_block_backward_G: graph/basis is NULL");
   const int64_t E = graph->n_edges;
   GP_REQUIRE(ctx, E > 0 && graph->n_triplets >= 0, "gp_block_backward_G: empty edge list");
@@ -243,9 +283,21 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   gp_epilogue e;
 
   gp_aux aux(ctx);   // the large weight-gradient GEMMs run on the side stream
-  GP_TRY(gp_ew_dsilu2(ctx, grad_m_out, INV_SQRT2, s.z_up, s.z_skip, d_up, d_skip, EH));
+  if (dims->symmetric) {
+    GP_REQUIRE(ctx, graph->id_swap, "gp_block_backward_G: graph->id_swap is needed by a symmetric block");
+    float* d_ac = sc.eh5;
+    sym_bwd_kernel<<<(unsigned)((EH + 255) / 256), 256, 0, ctx->stream>>>(grad_m_out, s.z_up, s.z_skip, s.z_ac, graph->id_swap,
+                                                                          E, H, d_up, d_skip, d_ac);
+    GP_LAUNCH_CHECK(ctx, "sym_bwd_kernel");
+    GP_TRY(gp_gemm_tn(ctx, s.z, d_ac, E, O, H, gw->W_up_ac, nullptr, sc.part, sc.part_bytes));
+    e = gp_epilogue(); e.out = sc.dz;
+    GP_TRY(gp_gemm_nt(ctx, d_ac, w->W_up_ac, E, O, H, e));                          // dz (opposite-edge path)
+  } else {
+    GP_TRY(gp_ew_dsilu2(ctx, grad_m_out, INV_SQRT2, s.z_up, s.z_skip, d_up, d_skip, EH));
+  }
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.z, d_up, E, O, H, gw->W_up, nullptr, sc.part_aux, sc.part_bytes); }, {d_up}));
   e = gp_epilogue(); e.out = sc.dz;
+  if (dims->symmetric) e.add_post = sc.dz;
   GP_TRY(gp_gemm_nt(ctx, d_up, w->W_up, E, O, H, e));                               // dz
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, d_skip, E, H, H, gw->W_skip, nullptr, sc.part_aux, sc.part_bytes); }, {}));
   e = gp_epilogue(); e.out = grad_m_in;

@@ -276,6 +276,21 @@ inline size_t carve_triplets(void* p, int64_t n_atoms, int64_t n_edges, triplets
 
 inline int blocks_for(int64_t n, int per_block) { return (int)((n + per_block - 1) / per_block); }
 
+// id_swap[e] = edge dst[e] -> src[e]: binary search for source dst[e] in the row of target src[e]
+__global__ void reverse_edges_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                     const int32_t* __restrict__ row_ptr, int64_t n_edges, int32_t* __restrict__ id_swap) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_edges) return;
+  const int j = src[e], i = dst[e];
+  int lo = row_ptr[j], hi = row_ptr[j + 1];   // in-edges of j, sources ascending
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (src[mid] < i) lo = mid + 1;
+    else hi = mid;
+  }
+  id_swap[e] = (lo < row_ptr[j + 1] && src[lo] == i) ? lo : -1;
+}
+
 // largest ptr[i+1] - ptr[i]; one workgroup
 __global__ void __launch_bounds__(1024)
 max_degree_kernel(const int32_t* __restrict__ ptr, int64_t n, int32_t* __restrict__ out) {
@@ -301,6 +316,19 @@ max_degree_kernel(const int32_t* __restrict__ ptr, int64_t n, int32_t* __restric
 }  // namespace
 
 extern "C" {
+
+int gp_reverse_edges(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr, int64_t n_atoms,
+                     int64_t n_edges, int32_t* id_swap) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, n_atoms >= 0 && n_edges >= 0, "gp_reverse_edges: negative size");
+  if (n_edges > INT32_MAX - 1 || n_atoms > INT32_MAX - 1) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_reverse_edges: sizes exceed int32");
+  if (n_edges == 0) return GP_OK;
+  GP_REQUIRE(ctx, src && dst && row_ptr && id_swap, "gp_reverse_edges: NULL pointer");
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  reverse_edges_kernel<<<blocks_for(n_edges, 256), 256, 0, ctx->stream>>>(src, dst, row_ptr, n_edges, id_swap);
+  GP_LAUNCH_CHECK(ctx, "reverse_edges_kernel");
+  return GP_OK;
+}
 
 int gp_csr_max_degree(gp_ctx* ctx, const int32_t* ptr, int64_t n, void* ws, size_t ws_bytes, int32_t* max_degree) {
   if (!ctx) return GP_BAD_ARG;

@@ -82,3 +82,33 @@ def test_block_G_radial_at_target_cfg4_widths_bf16(lib, ctx):
     w = synth.get_workload("cfg4", cutoff=6.0, radial_at_target=True)
     assert w.dims.dtype == "bf16"
     _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3), tol=2e-2)
+
+
+# ---- symmetric message passing (the two messages on a bond are coupled) ----
+def test_reverse_edges_bit_exact(lib, ctx):
+    from oracle import graph as ograph
+    for cap, seed in ((0, 1), (9, 2), (3, 3)):
+        pos, gptr = synth.slab_adsorbate_positions(2, 4, 3, 3, 7, seed=seed)
+        ref = H.oracle_graph(pos, gptr, 5.0, cap)
+        e, t = lib.build_graph(ctx, H.to_dev(pos, torch.float32), H.to_dev(gptr, torch.int32), 5.0, cap)
+        want = ograph.reverse_edges(ref["src"], ref["dst"])
+        assert np.array_equal(t["id_swap"].cpu().numpy(), want)
+        assert (want < 0).any() == (cap > 0)
+
+
+def test_block_G_symmetric_small_dims(lib, ctx):
+    w = synth.get_workload("cfg3", emb=32, int_emb=16, emb_rbf=4, emb_cbf=5, emb_bil=12, num_radial=9,
+                           num_spherical=4, cutoff=4.0, dtype="f32", symmetric=True)
+    _parity(lib, ctx, w, 0, 2, synth.cube_positions(30, 6.0, 0.9, seed=1))
+
+
+def test_block_G_symmetric_cfg3_shape_capped(lib, ctx):
+    # the neighbour cap leaves some edges without an opposite edge
+    from dataclasses import replace
+    w = replace(synth.get_workload("cfg3", dtype="f32", symmetric=True), max_neighbors=20)
+    _parity(lib, ctx, w, 1, 1, synth.slab_adsorbate_positions(1, 8, 5, 4, 40, seed=2))
+
+
+def test_block_G_symmetric_and_radial_at_target_bf16(lib, ctx):
+    w = synth.get_workload("cfg4", cutoff=6.0, symmetric=True, radial_at_target=True)
+    _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3), tol=2e-2)

@@ -101,3 +101,11 @@ def test_forces_radial_at_target(lib, ctx):
     assert abs(E_gpu.sum() - E_ref) <= 1e-4 * max(1.0, abs(E_ref))
     assert H.rel_l2(f_gpu, f_ref) <= 1e-4, H.rel_l2(f_gpu, f_ref)
     assert np.abs(f_gpu.sum(axis=0)).max() <= 1e-4 * np.abs(f_ref).max() * np.sqrt(len(pos))
+
+
+def test_forces_symmetric(lib, ctx):
+    w = synth.get_workload("cfg5", emb=32, int_emb=16, emb_rbf=4, emb_cbf=5, emb_bil=12, num_radial=9,
+                           num_spherical=4, cutoff=4.0, dtype="f32", symmetric=True)
+    pos, E_gpu, f_gpu, E_ref, f_ref, e = _force_case(lib, ctx, w, synth.cube_positions(30, 6.0, 0.9, seed=3), 6, 2, 7)
+    assert abs(E_gpu.sum() - E_ref) <= 1e-4 * max(1.0, abs(E_ref))
+    assert H.rel_l2(f_gpu, f_ref) <= 1e-4, H.rel_l2(f_gpu, f_ref)

@@ -36,8 +36,8 @@ def test_every_declared_symbol_is_exported(cdll):
 
 def test_struct_layouts():
     from paper_2203_09697_amd import binding as B
-    assert C.sizeof(B._Dims) == 15 * 4
-    assert C.sizeof(B._Graph) == 2 * 8 + 4 * 8 + 8 + 2 * 4 + 4 * 8
+    assert C.sizeof(B._Dims) == 16 * 4
+    assert C.sizeof(B._Graph) == 2 * 8 + 4 * 8 + 8 + 2 * 4 + 5 * 8
     assert C.sizeof(B._Basis) == 4 * 8
     assert C.sizeof(B._WeightsD) == (10 + 2 + 2 * 4 * B.GP_MAX_RES) * 8
 
