@@ -27,15 +27,18 @@ F64 = torch.float64
 
 
 # ----------------------------------------------------------------------------- geometry
-def geometry(pos, src, dst, idx_kj, idx_ji):
+def geometry(pos, src, dst, idx_kj, idx_ji, shift=None):
     """Edge lengths, unit vectors and triplet cosines.
 
     pos: torch [N,3] fp64.  Edge e runs src[e] -> dst[e]; unit[e] = (x_dst - x_src)/d_e.
     cos_alpha[t] = u_ji . u_jk with u_jk = (x_k - x_j)/d_kj = -unit[idx_kj[t]].
+    shift [E,3] (periodic structures): the source atom of edge e sits at x_src + shift[e].
     """
     src = torch.as_tensor(np.asarray(src), dtype=torch.long)
     dst = torch.as_tensor(np.asarray(dst), dtype=torch.long)
     vec = pos[dst] - pos[src]
+    if shift is not None:
+        vec = vec - torch.as_tensor(np.asarray(shift), dtype=pos.dtype)
     d = torch.sqrt((vec * vec).sum(dim=1))
     unit = vec / d[:, None]
     kj = torch.as_tensor(np.asarray(idx_kj), dtype=torch.long)

@@ -14,8 +14,16 @@ Readings where the paper is silent:
     set bit for bit;
   * an optional neighbour cap keeps, per target atom, the M sources with the
     smallest key (bit pattern of d2, source index);
-  * open boundaries (no periodic images);
+  * open boundaries (no periodic images) unless the *_pbc functions are used;
   * output order: edges by (target, source); triplets by (edge j->i, edge k->j).
+
+Periodic structures (edges_pbc): the source of an edge may be a periodic image of an atom,
+x_src + n0 a0 + n1 a1 + n2 a2 with integer n (the edge's cell offset) and lattice vectors a
+(rows of the structure's cell).  Every image with |n_a| <= rep[a] is tested with the same fp32
+predicate on the shifted source position, shift component = fl(fl(fl(n0 a0) + fl(n1 a1)) + fl(n2 a2));
+the atom itself (n = 0) is excluded, its own images are not.  Edges are ordered by (target,
+source, n0, n1, n2); the cap key is (bit pattern of d2, source, n0, n1, n2).  A triplet
+k->j->i is excluded only if k's image coincides with atom i: same atom and opposite offsets.
 """
 import numpy as np
 
@@ -65,12 +73,13 @@ def edges(pos, graph_ptr, cutoff, max_neighbors=0):
     return src.astype(np.int32), dst.astype(np.int32), row_ptr.astype(np.int32)
 
 
-def triplets(src, dst, row_ptr):
+def triplets(src, dst, row_ptr, offset=None):
     """Triplet list k->j->i, k != i.
 
     Returns idx_kj[T], idx_ji[T] (edge ids, int32) ordered by (idx_ji, idx_kj)
     and seg_ptr[E+1] (int64) with the triplets of target edge e at
-    seg_ptr[e]:seg_ptr[e+1].
+    seg_ptr[e]:seg_ptr[e+1].  offset [E,3] (periodic structures): k != i then means that
+    the image of k is not atom i itself, i.e. not (same atom and offset_kj = -offset_ji).
     """
     n_edges = len(src)
     kj_l, ji_l = [], []
@@ -78,7 +87,11 @@ def triplets(src, dst, row_ptr):
     for e in range(n_edges):
         j, i = int(src[e]), int(dst[e])
         cand = np.arange(row_ptr[j], row_ptr[j + 1], dtype=np.int64)  # in-edges k->j
-        cand = cand[src[cand] != i]
+        if offset is None:
+            cand = cand[src[cand] != i]
+        else:
+            same = (src[cand] == i) & np.all(np.asarray(offset)[cand] == -np.asarray(offset)[e], axis=1)
+            cand = cand[~same]
         kj_l.append(cand)
         ji_l.append(np.full(len(cand), e, dtype=np.int64))
         seg[e + 1] = len(cand)
@@ -124,9 +137,70 @@ def triplets_loops(edge_pairs):
     return out
 
 
-def reverse_edges(src, dst):
+def reverse_edges(src, dst, offset=None):
     """id_swap[e] = id of the edge running opposite to edge e (dst[e] -> src[e]), or -1 if the edge
     list has none (a neighbour cap can keep j->i and drop i->j).  Needed to couple the two
-    messages on the same bond (Sec. 3.4, symmetric message passing)."""
-    where = {(int(s), int(d)): e for e, (s, d) in enumerate(zip(src, dst))}
-    return np.array([where.get((int(d), int(s)), -1) for s, d in zip(src, dst)], dtype=np.int64)
+    messages on the same bond (Sec. 3.4, symmetric message passing).  With cell offsets the
+    opposite edge carries the negated offset."""
+    if offset is None:
+        offset = np.zeros((len(src), 3), dtype=np.int64)
+    off = np.asarray(offset)
+    where = {(int(s), int(d), *map(int, o)): e for e, (s, d, o) in enumerate(zip(src, dst, off))}
+    return np.array([where.get((int(d), int(s), *map(int, -o)), -1) for s, d, o in zip(src, dst, off)], dtype=np.int64)
+
+
+def image_shift_f32(cell, n):
+    """fp32 shift vector n0 a0 + n1 a1 + n2 a2, products and sums rounded one by one."""
+    c = np.asarray(cell, dtype=np.float32)
+    f = np.float32
+    return np.array([f(f(f(f(n[0]) * c[0, k]) + f(f(n[1]) * c[1, k])) + f(f(n[2]) * c[2, k])) for k in range(3)], dtype=np.float32)
+
+
+def edges_pbc(pos, graph_ptr, cells, cutoff, rep, max_neighbors=0):
+    """Directed edge list of the radius graph of periodic structures.
+
+    cells [G,3,3] (rows = lattice vectors), rep = (r0, r1, r2): images with |n_a| <= r_a are tested.
+    Returns src, dst (int32), offset [E,3] (int32, the image of the source), row_ptr (int32),
+    sorted by (dst, src, n0, n1, n2).
+    """
+    pos = np.ascontiguousarray(pos, dtype=np.float32)
+    n = pos.shape[0]
+    c = np.float32(cutoff)
+    c2 = np.float32(c * c)
+    images = [(a, b, d) for a in range(-rep[0], rep[0] + 1) for b in range(-rep[1], rep[1] + 1)
+              for d in range(-rep[2], rep[2] + 1)]
+    src_l, dst_l, off_l = [], [], []
+    row_ptr = np.zeros(n + 1, dtype=np.int64)
+    for g in range(len(graph_ptr) - 1):
+        lo, hi = int(graph_ptr[g]), int(graph_ptr[g + 1])
+        shifts = np.stack([image_shift_f32(cells[g], im) for im in images])          # [NI,3] fp32
+        for i in range(lo, hi):
+            cand = []
+            for j in range(lo, hi):
+                ps = pos[j][None, :] + shifts                                        # fp32, one rounding
+                dx = pos[i, 0] - ps[:, 0]
+                dy = pos[i, 1] - ps[:, 1]
+                dz = pos[i, 2] - ps[:, 2]
+                d2 = (dx * dx + dy * dy) + dz * dz
+                for q, im in enumerate(images):
+                    if j == i and im == (0, 0, 0):
+                        continue
+                    if d2[q] < c2:
+                        cand.append((int(d2[q].view(np.uint32)), j, im))
+            if max_neighbors > 0 and len(cand) > max_neighbors:
+                cand = sorted(cand)[:max_neighbors]
+            kept = sorted((j, im) for _, j, im in cand)
+            src_l += [j for j, _ in kept]
+            off_l += [im for _, im in kept]
+            dst_l += [i] * len(kept)
+            row_ptr[i + 1] = len(kept)
+    row_ptr = np.cumsum(row_ptr)
+    return (np.array(src_l, dtype=np.int32), np.array(dst_l, dtype=np.int32),
+            np.array(off_l, dtype=np.int32).reshape(-1, 3), row_ptr.astype(np.int32))
+
+
+def edge_shifts(offset, dst, graph_ptr, cells):
+    """fp64 shift vector of every edge: offset[e] . cell of the structure of the edge."""
+    gp = np.asarray(graph_ptr)
+    g_of = np.searchsorted(gp, np.asarray(dst), side="right") - 1
+    return np.einsum("ea,eak->ek", np.asarray(offset, dtype=np.float64), np.asarray(cells, dtype=np.float64)[g_of])
