@@ -128,8 +128,40 @@ int gp_triplets_fill(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const 
 /* Opposite edges (Sec. 3.4, symmetric message passing couples m_ji and m_ij): for an edge list
  * sorted by (dst, src) with its row_ptr, id_swap[e] = id of the edge dst[e] -> src[e], or -1 if
  * the list has none (a neighbour cap can keep one direction only).  Exact (integer) result. */
-int gp_reverse_edges(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
-                     int64_t n_atoms, int64_t n_edges, int32_t* id_swap);
+int gp_reverse_edges(gp_ctx* ctx, const int32_t* src, const int32_t* dst,
+                     const int32_t* offset /*[E,3] cell offsets of a periodic edge list, or NULL*/,
+                     const int32_t* row_ptr, int64_t n_atoms, int64_t n_edges, int32_t* id_swap);
+
+/* ------------------------------------------------------------------------------------------
+ * Periodic structures.  cell[G,3,3] (device) holds the lattice vectors of every structure as
+ * rows.  The source of an edge may be a periodic image of an atom, x_src + n0 a0 + n1 a1 + n2 a2;
+ * the integer triple n is the edge's cell offset (offset[E,3]).  Every image with
+ * |n_a| <= rep_a is tested (the caller chooses rep so that rep_a times the cell's height along
+ * axis a covers the cutoff; 0..16) with the same fp32 predicate as gp_edges_count on the shifted
+ * source position, shift component = fl(fl(fl(n0 a0) + fl(n1 a1)) + fl(n2 a2)), products and sums
+ * rounded once each.  The atom itself (n = 0) is not its own neighbour, its images are.
+ * Order: (dst, src, n0, n1, n2); cap key: (bits(d2), src, n0, n1, n2).  dist and unit refer to the
+ * shifted source.  Triplets k->j->i of a periodic edge list leave out only the image of k that
+ * coincides with atom i (same atom, offset_kj = -offset_ji); everything else is as in the
+ * open-boundary calls, whose outputs these reproduce when no image is within the cutoff.
+ */
+int gp_edges_count_pbc(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, const float* cell,
+                       int64_t n_atoms, int32_t n_graphs, float cutoff, int32_t max_neighbors,
+                       int32_t rep0, int32_t rep1, int32_t rep2,
+                       void* ws, size_t ws_bytes, int64_t* n_edges /*host*/);
+int gp_edges_fill_pbc(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, const float* cell,
+                      int64_t n_atoms, int32_t n_graphs, float cutoff, int32_t max_neighbors,
+                      int32_t rep0, int32_t rep1, int32_t rep2,
+                      const void* ws, size_t ws_bytes, int64_t n_edges,
+                      int32_t* src, int32_t* dst, int32_t* offset, int32_t* row_ptr, float* dist, float* unit);
+int gp_triplets_count_pbc(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* offset,
+                          const int32_t* row_ptr, int64_t n_atoms, int64_t n_edges,
+                          void* ws, size_t ws_bytes, int64_t* n_triplets /*host*/);
+int gp_triplets_fill_pbc(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* offset,
+                         const int32_t* row_ptr, int64_t n_atoms, int64_t n_edges,
+                         void* ws, size_t ws_bytes, int64_t n_triplets,
+                         int32_t* idx_kj, int32_t* idx_ji, int32_t* seg_ptr_ji,
+                         int32_t* perm_kj, int32_t* idx_ji_kj, int32_t* seg_ptr_kj);
 
 /* Largest row length ptr[i+1] - ptr[i], i < n, of a device-resident offsets array with n+1
  * entries (e.g. the largest in-degree, for gp_graph.max_in_degree).  ws: device scratch of at

@@ -23,12 +23,14 @@ def energy_head(m, dst, n_atoms, Wh):
     return e_atom.sum(), e_atom
 
 
-def energy_G(pos, src, dst, idx_kj, idx_ji, m0, W_list, Wh, dims):
-    """Energy of the variant-G stack + head as a differentiable function of pos (torch fp64 [N,3])."""
-    d, _unit, cos_alpha = basis.geometry(pos, src, dst, idx_kj, idx_ji)
+def energy_G(pos, src, dst, idx_kj, idx_ji, m0, W_list, Wh, dims, shift=None):
+    """Energy of the variant-G stack + head as a differentiable function of pos (torch fp64 [N,3]).
+    shift [E,3]: constant image shifts of the edge sources (periodic structures)."""
+    d, _unit, cos_alpha = basis.geometry(pos, src, dst, idx_kj, idx_ji, shift)
     g = basis.rbf_gauss(d, dims.cutoff, dims.num_radial, dims.envelope_p)
     Y = basis.y_l0(cos_alpha, dims.num_spherical)
-    id_swap = graph.reverse_edges(src, dst) if getattr(dims, "symmetric", False) else None
+    id_swap = graph.reverse_edges(src, dst) if getattr(dims, "symmetric", False) and shift is None else None
+    assert not (getattr(dims, "symmetric", False) and shift is not None), "pass offsets to reverse_edges for periodic graphs"
     m = block.stack_G(m0, g, Y, idx_kj, idx_ji, W_list, getattr(dims, "radial_at_target", False), id_swap)
     E, _ = energy_head(m, dst, pos.shape[0], Wh)
     return E

@@ -23,7 +23,8 @@ STATUS = {0: "GP_OK", -1: "GP_BAD_ARG", -2: "GP_BUFFER_TOO_SMALL", -3: "GP_INT32
 EXPORTED_SYMBOLS = [
     "gp_create", "gp_destroy", "gp_last_error", "gp_version",
     "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get", "gp_set_side_stream", "gp_set_triplet_mfma", "gp_measure_peaks",
-    "gp_edges_workspace", "gp_edges_count", "gp_edges_fill",
+    "gp_edges_workspace", "gp_edges_count", "gp_edges_fill", "gp_edges_count_pbc", "gp_edges_fill_pbc",
+    "gp_triplets_count_pbc", "gp_triplets_fill_pbc",
     "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill", "gp_csr_max_degree", "gp_reverse_edges",
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
     "gp_block_forward_G", "gp_block_backward_G",
@@ -227,23 +228,34 @@ def _empty(ctx, n, dtype):
 
 
 # ------------------------------------------------------------------ graph
-def gp_edges(ctx, pos, graph_ptr, cutoff, max_neighbors=0):
-    """gp_edges_workspace + gp_edges_count + gp_edges_fill.  pos [N,3] f32, graph_ptr [G+1] i32 (device)."""
+def gp_edges(ctx, pos, graph_ptr, cutoff, max_neighbors=0, cell=None, rep=None):
+    """gp_edges_workspace + gp_edges_count + gp_edges_fill.  pos [N,3] f32, graph_ptr [G+1] i32 (device).
+    With cell [G,3,3] f32 (device) and rep = (r0, r1, r2): the periodic calls gp_edges_count_pbc / fill_pbc;
+    the returned dict then also holds offset [E,3] i32."""
     lib = load()
     n_atoms, n_graphs = pos.shape[0], graph_ptr.shape[0] - 1
     nbytes = C.c_size_t()
     ctx.check(lib.gp_edges_workspace(C.c_int64(n_atoms), C.byref(nbytes)))
     ws = _empty(ctx, max(nbytes.value, 8), torch.uint8)
     n_edges = C.c_int64()
-    args = (ctx._h, _ptr(pos), _ptr(graph_ptr), C.c_int64(n_atoms), C.c_int32(n_graphs), C.c_float(cutoff),
-            C.c_int32(max_neighbors), _ptr(ws), C.c_size_t(ws.numel()))
-    ctx.check(lib.gp_edges_count(*args, C.byref(n_edges)))
+    pbc = cell is not None
+    head = (ctx._h, _ptr(pos), _ptr(graph_ptr)) + ((_ptr(cell),) if pbc else ())
+    mid = (C.c_int64(n_atoms), C.c_int32(n_graphs), C.c_float(cutoff), C.c_int32(max_neighbors))
+    if pbc:
+        mid += tuple(C.c_int32(int(r)) for r in rep)
+    args = head + mid + (_ptr(ws), C.c_size_t(ws.numel()))
+    ctx.check((lib.gp_edges_count_pbc if pbc else lib.gp_edges_count)(*args, C.byref(n_edges)))
     E = n_edges.value
     out = dict(n_atoms=n_atoms, n_edges=E, src=_empty(ctx, E, torch.int32), dst=_empty(ctx, E, torch.int32),
                row_ptr=_empty(ctx, n_atoms + 1, torch.int32), dist=_empty(ctx, E, torch.float32),
                unit=torch.empty((E, 3), dtype=torch.float32, device=ctx.device))
-    ctx.check(lib.gp_edges_fill(*args, C.c_int64(E), _ptr(out["src"]), _ptr(out["dst"]), _ptr(out["row_ptr"]),
-                                _ptr(out["dist"]), _ptr(out["unit"])))
+    if pbc:
+        out["offset"] = torch.empty((E, 3), dtype=torch.int32, device=ctx.device)
+        ctx.check(lib.gp_edges_fill_pbc(*args, C.c_int64(E), _ptr(out["src"]), _ptr(out["dst"]), _ptr(out["offset"]),
+                                        _ptr(out["row_ptr"]), _ptr(out["dist"]), _ptr(out["unit"])))
+    else:
+        ctx.check(lib.gp_edges_fill(*args, C.c_int64(E), _ptr(out["src"]), _ptr(out["dst"]), _ptr(out["row_ptr"]),
+                                    _ptr(out["dist"]), _ptr(out["unit"])))
     return out
 
 
@@ -255,16 +267,17 @@ def gp_triplets(ctx, edges, with_kj=True):
     ctx.check(lib.gp_triplets_workspace(C.c_int64(N), C.c_int64(E), C.byref(nbytes)))
     ws = _empty(ctx, max(nbytes.value, 8), torch.uint8)
     n_trip = C.c_int64()
-    args = (ctx._h, _ptr(edges["src"]), _ptr(edges["dst"]), _ptr(edges["row_ptr"]), C.c_int64(N), C.c_int64(E),
-            _ptr(ws), C.c_size_t(ws.numel()))
-    ctx.check(lib.gp_triplets_count(*args, C.byref(n_trip)))
+    pbc = edges.get("offset") is not None     # periodic edge list: image-aware exclusion of k = i
+    args = (ctx._h, _ptr(edges["src"]), _ptr(edges["dst"])) + ((_ptr(edges["offset"]),) if pbc else ()) + (
+        _ptr(edges["row_ptr"]), C.c_int64(N), C.c_int64(E), _ptr(ws), C.c_size_t(ws.numel()))
+    ctx.check((lib.gp_triplets_count_pbc if pbc else lib.gp_triplets_count)(*args, C.byref(n_trip)))
     T = n_trip.value
     out = dict(n_edges=E, n_triplets=T, idx_kj=_empty(ctx, T, torch.int32), idx_ji=_empty(ctx, T, torch.int32),
                seg_ptr_ji=_empty(ctx, E + 1, torch.int32))
     if with_kj:
         out.update(perm_kj=_empty(ctx, T, torch.int32), idx_ji_kj=_empty(ctx, T, torch.int32),
                    seg_ptr_kj=_empty(ctx, E + 1, torch.int32))
-    ctx.check(lib.gp_triplets_fill(*args, C.c_int64(T), _ptr(out["idx_kj"]), _ptr(out["idx_ji"]),
+    ctx.check((lib.gp_triplets_fill_pbc if pbc else lib.gp_triplets_fill)(*args, C.c_int64(T), _ptr(out["idx_kj"]), _ptr(out["idx_ji"]),
                                    _ptr(out["seg_ptr_ji"]), _ptr(out.get("perm_kj")), _ptr(out.get("idx_ji_kj")),
                                    _ptr(out.get("seg_ptr_kj"))))
     if with_kj and E > 0:
@@ -284,8 +297,8 @@ def gp_reverse_edges(ctx, edges):
     """id_swap[E]: id of the opposite edge of every edge, -1 where the list has none."""
     N, E = edges["n_atoms"], edges["n_edges"]
     out = torch.empty(E, dtype=torch.int32, device=ctx.device)
-    ctx.check(load().gp_reverse_edges(ctx._h, _ptr(edges["src"]), _ptr(edges["dst"]), _ptr(edges["row_ptr"]), C.c_int64(N),
-                                      C.c_int64(E), _ptr(out)))
+    ctx.check(load().gp_reverse_edges(ctx._h, _ptr(edges["src"]), _ptr(edges["dst"]), _ptr(edges.get("offset")),
+                                      _ptr(edges["row_ptr"]), C.c_int64(N), C.c_int64(E), _ptr(out)))
     return out
 
 
@@ -303,9 +316,10 @@ def gp_edges_by_source(ctx, edges):
     return out_ptr, out_list
 
 
-def build_graph(ctx, pos, graph_ptr, cutoff, max_neighbors=0):
-    """Edges and triplets for device tensors pos / graph_ptr; returns (edges dict, triplets dict)."""
-    e = gp_edges(ctx, pos, graph_ptr, cutoff, max_neighbors)
+def build_graph(ctx, pos, graph_ptr, cutoff, max_neighbors=0, cell=None, rep=None):
+    """Edges and triplets for device tensors pos / graph_ptr (periodic with cell [G,3,3] and rep); returns
+    (edges dict, triplets dict)."""
+    e = gp_edges(ctx, pos, graph_ptr, cutoff, max_neighbors, cell, rep)
     return e, gp_triplets(ctx, e)
 
 

@@ -53,14 +53,43 @@ __device__ __forceinline__ float dist2_f32(float xi, float yi, float zi, float x
   return __fadd_rn(__fadd_rn(__fmul_rn(dx, dx), __fmul_rn(dy, dy)), __fmul_rn(dz, dz));
 }
 
-// One wavefront per target atom i.  FILL = false: deg[i] = number of kept sources.
-// FILL = true: write the kept sources in ascending order at row_ptr[i].
+// Periodic images tested per source atom: n_a = -rep[a] .. rep[a]; image index img counts them in
+// lexicographic order of (n0, n1, n2).  Without a cell there is the one image n = 0.
+struct images_t {
+  const float* cell;   // [G, 3, 3] rows = lattice vectors, or NULL
+  int r0, r1, r2;
+  __host__ __device__ int count() const { return cell ? (2 * r0 + 1) * (2 * r1 + 1) * (2 * r2 + 1) : 1; }
+};
+
+// shift of image (n0, n1, n2) of structure g: n0 a0 + n1 a1 + n2 a2, every product and sum rounded once
+__device__ __forceinline__ void image_of(const images_t& im, int g, int img, int& n0, int& n1, int& n2, float& sx,
+                                         float& sy, float& sz) {
+#pragma clang fp contract(off)
+  if (!im.cell) {
+    n0 = n1 = n2 = 0;
+    sx = sy = sz = 0.f;
+    return;
+  }
+  const int w2 = 2 * im.r2 + 1, w1 = 2 * im.r1 + 1;
+  n2 = img % w2 - im.r2;
+  n1 = (img / w2) % w1 - im.r1;
+  n0 = img / (w2 * w1) - im.r0;
+  const float* c = im.cell + 9 * (int64_t)g;
+  const float f0 = (float)n0, f1 = (float)n1, f2 = (float)n2;
+  sx = __fadd_rn(__fadd_rn(__fmul_rn(f0, c[0]), __fmul_rn(f1, c[3])), __fmul_rn(f2, c[6]));
+  sy = __fadd_rn(__fadd_rn(__fmul_rn(f0, c[1]), __fmul_rn(f1, c[4])), __fmul_rn(f2, c[7]));
+  sz = __fadd_rn(__fadd_rn(__fmul_rn(f0, c[2]), __fmul_rn(f1, c[5])), __fmul_rn(f2, c[8]));
+}
+
+// One wavefront per target atom i; candidates are (source atom j, image) pairs in the order
+// (j, image index), the atom itself (j = i, n = 0) left out.  FILL = false: deg[i] = number of kept
+// candidates.  FILL = true: write them in that order at row_ptr[i].
 template <bool FILL>
 __global__ void __launch_bounds__(256)
 edges_kernel(const float* __restrict__ pos, const int32_t* __restrict__ graph_ptr, int n_atoms,
-             int n_graphs, float c2, int max_nb, int32_t* __restrict__ deg,
+             int n_graphs, float c2, int max_nb, images_t im, int32_t* __restrict__ deg,
              const int32_t* __restrict__ row_ptr, int32_t* __restrict__ src, int32_t* __restrict__ dst,
-             float* __restrict__ dist, float* __restrict__ unit) {
+             int32_t* __restrict__ offset, float* __restrict__ dist, float* __restrict__ unit) {
   const int i = blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x >> 6);
   if (i >= n_atoms) return;
   const int lane = lane_id();
@@ -72,36 +101,57 @@ edges_kernel(const float* __restrict__ pos, const int32_t* __restrict__ graph_pt
   }
   const int lo = graph_ptr[lo_g], hi = graph_ptr[lo_g + 1];
   const float xi = pos[3 * i], yi = pos[3 * i + 1], zi = pos[3 * i + 2];
+  const int NI = im.count();
+  const int centre = im.cell ? ((im.r0 * (2 * im.r1 + 1) + im.r1) * (2 * im.r2 + 1) + im.r2) : 0;
+  const int n_cand = (hi - lo) * NI;
+
+  // squared distance from atom i to candidate q (and where that candidate sits)
+  auto cand_d2 = [&](int q, int& j, int& n0, int& n1, int& n2, float& xs, float& ys, float& zs) -> float {
+    j = lo + q / NI;
+    float sx, sy, sz;
+    image_of(im, lo_g, q % NI, n0, n1, n2, sx, sy, sz);
+    xs = __fadd_rn(pos[3 * j], sx);
+    ys = __fadd_rn(pos[3 * j + 1], sy);
+    zs = __fadd_rn(pos[3 * j + 2], sz);
+    return dist2_f32(xi, yi, zi, xs, ys, zs);
+  };
+  const int self_q = (i - lo) * NI + centre;
 
   bool capped = false;
   if (max_nb > 0) {
     int cand = 0;
-    for (int base = lo; base < hi; base += WAVE) {
-      int j = base + lane;
+    for (int base = 0; base < n_cand; base += WAVE) {
+      const int q = base + lane;
       bool in = false;
-      if (j < hi && j != i) in = dist2_f32(xi, yi, zi, pos[3 * j], pos[3 * j + 1], pos[3 * j + 2]) < c2;
+      if (q < n_cand && q != self_q) {
+        int j, n0, n1, n2;
+        float xs, ys, zs;
+        in = cand_d2(q, j, n0, n1, n2, xs, ys, zs) < c2;
+      }
       cand += __popcll(__ballot(in));
     }
     capped = cand > max_nb;
   }
 
   int total = 0;
-  for (int base = lo; base < hi; base += WAVE) {
-    const int j = base + lane;
-    float d2 = 0.f, xj = 0.f, yj = 0.f, zj = 0.f;
+  for (int base = 0; base < n_cand; base += WAVE) {
+    const int q = base + lane;
+    float d2 = 0.f, xs = 0.f, ys = 0.f, zs = 0.f;
+    int j = 0, n0 = 0, n1 = 0, n2 = 0;
     bool keep = false;
-    if (j < hi && j != i) {
-      xj = pos[3 * j]; yj = pos[3 * j + 1]; zj = pos[3 * j + 2];
-      d2 = dist2_f32(xi, yi, zi, xj, yj, zj);
+    if (q < n_cand && q != self_q) {
+      d2 = cand_d2(q, j, n0, n1, n2, xs, ys, zs);
       keep = d2 < c2;
     }
     if (capped) {
-      // rank of source j among all in-range sources by key (d2, index); keep the first max_nb
+      // rank of this candidate among all in-range candidates by key (d2, candidate order); keep the first max_nb
       int rank = 0;
-      for (int q = lo; q < hi; ++q) {
-        float dq = dist2_f32(xi, yi, zi, pos[3 * q], pos[3 * q + 1], pos[3 * q + 2]);
-        bool in_q = (q != i) && (dq < c2);
-        rank += (in_q && (dq < d2 || (dq == d2 && q < j))) ? 1 : 0;
+      for (int p = 0; p < n_cand; ++p) {
+        int jp, a0, a1, a2;
+        float xp, yp, zp;
+        const float dq = cand_d2(p, jp, a0, a1, a2, xp, yp, zp);
+        const bool in_q = (p != self_q) && (dq < c2);
+        rank += (in_q && (dq < d2 || (dq == d2 && p < q))) ? 1 : 0;
       }
       keep = keep && (rank < max_nb);
     }
@@ -110,14 +160,19 @@ edges_kernel(const float* __restrict__ pos, const int32_t* __restrict__ graph_pt
       const int slot = row_ptr[i] + total + mbcnt(mask);
       src[slot] = j;
       dst[slot] = i;
+      if (offset) {
+        offset[3 * slot + 0] = n0;
+        offset[3 * slot + 1] = n1;
+        offset[3 * slot + 2] = n2;
+      }
       if (dist || unit) {
         float d = sqrtf(d2);
         if (dist) dist[slot] = d;
         if (unit) {
           float inv = 1.0f / d;
-          unit[3 * slot + 0] = (xi - xj) * inv;
-          unit[3 * slot + 1] = (yi - yj) * inv;
-          unit[3 * slot + 2] = (zi - zj) * inv;
+          unit[3 * slot + 0] = (xi - xs) * inv;
+          unit[3 * slot + 1] = (yi - ys) * inv;
+          unit[3 * slot + 2] = (zi - zs) * inv;
         }
       }
     }
@@ -127,30 +182,41 @@ edges_kernel(const float* __restrict__ pos, const int32_t* __restrict__ graph_pt
 }
 
 // ------------------------------------------------------------------ triplets
-// position of value v in the ascending list a[0..n), or -1
-__device__ __forceinline__ int find_sorted(const int32_t* __restrict__ a, int n, int v) {
+// Position, inside rows b .. b+n of an edge list sorted by (source, cell offset), of the edge with
+// source v and offset (t0, t1, t2); -1 if there is none.  off == NULL: open boundaries, all offsets zero.
+__device__ __forceinline__ int find_edge(const int32_t* __restrict__ src, const int32_t* __restrict__ off, int b, int n,
+                                         int v, int t0, int t1, int t2) {
   int lo = 0, hi = n;
   while (lo < hi) {
-    int mid = (lo + hi) >> 1;
-    if (a[mid] < v) lo = mid + 1; else hi = mid;
+    const int mid = (lo + hi) >> 1, e = b + mid;
+    bool less = src[e] < v;
+    if (off && src[e] == v) {
+      const int o0 = off[3 * e], o1 = off[3 * e + 1], o2 = off[3 * e + 2];
+      less = o0 < t0 || (o0 == t0 && (o1 < t1 || (o1 == t1 && o2 < t2)));
+    }
+    if (less) lo = mid + 1; else hi = mid;
   }
-  return (lo < n && a[lo] == v) ? lo : -1;
+  if (lo >= n || src[b + lo] != v) return -1;
+  if (off && (off[3 * (b + lo)] != t0 || off[3 * (b + lo) + 1] != t1 || off[3 * (b + lo) + 2] != t2)) return -1;
+  return lo;
 }
 
-// Per edge e = (j->i): cnt[e] = indeg(j) - [i->j is an edge]; skip[e] = position of source i
-// inside the in-list of j, or -1.  Also histograms out-degrees.
+// Per edge e = (j->i): cnt[e] = indeg(j) - [the opposite edge exists]; skip[e] = position of the opposite
+// edge (source i, negated offset: the image of k that is atom i itself) inside the in-list of j, or -1.
+// Also histograms out-degrees.
 __global__ void triplet_count_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
-                                     const int32_t* __restrict__ row_ptr, int n_edges,
+                                     const int32_t* __restrict__ off, const int32_t* __restrict__ row_ptr, int n_edges,
                                      int32_t* __restrict__ cnt, int32_t* __restrict__ skip,
                                      int32_t* __restrict__ out_deg) {
   int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= n_edges) return;
   int j = src[e], i = dst[e];
   int b = row_ptr[j], n = row_ptr[j + 1] - b;
-  int p = find_sorted(src + b, n, i);
+  int p = off ? find_edge(src, off, b, n, i, -off[3 * e], -off[3 * e + 1], -off[3 * e + 2])
+              : find_edge(src, nullptr, b, n, i, 0, 0, 0);
   skip[e] = p;
   cnt[e] = n - (p >= 0 ? 1 : 0);
-  atomicAdd(&out_deg[j], 1);
+  if (out_deg) atomicAdd(&out_deg[j], 1);
 }
 
 // One wavefront per target edge: its triplets are the in-edges of j minus the one from i.
@@ -196,22 +262,24 @@ out_sort_kernel(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__
 
 // Per source edge e' = (k->j): number of out-edges of j that do not end in k.
 __global__ void triplet_count_kj_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
-                                        const int32_t* __restrict__ row_ptr,
+                                        const int32_t* __restrict__ off, const int32_t* __restrict__ row_ptr,
                                         const int32_t* __restrict__ out_ptr, int n_edges,
                                         int32_t* __restrict__ cnt_kj) {
   int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= n_edges) return;
   int k = src[e], j = dst[e];
-  int b = row_ptr[k], n = row_ptr[k + 1] - b;           // in-list of k: does it contain j ?
-  int has_rev = find_sorted(src + b, n, j) >= 0 ? 1 : 0;
-  cnt_kj[e] = out_ptr[j + 1] - out_ptr[j] - has_rev;
+  int b = row_ptr[k], n = row_ptr[k + 1] - b;           // in-list of k: does it contain the opposite edge ?
+  int p = off ? find_edge(src, off, b, n, j, -off[3 * e], -off[3 * e + 1], -off[3 * e + 2])
+              : find_edge(src, nullptr, b, n, j, 0, 0, 0);
+  cnt_kj[e] = out_ptr[j + 1] - out_ptr[j] - (p >= 0 ? 1 : 0);
 }
 
 // One wavefront per source edge e' = (k->j): walk the out-edges e = (j->i) of j in ascending
 // edge id, drop i == k, and record the ji-major triplet id of (e', e).
 __global__ void __launch_bounds__(256)
 triplet_fill_kj_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
-                       const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
+                       const int32_t* __restrict__ off, const int32_t* __restrict__ row_ptr,
+                       const int32_t* __restrict__ out_ptr,
                        const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ji,
                        const int32_t* __restrict__ skip, const int32_t* __restrict__ seg_kj, int n_edges,
                        int32_t* __restrict__ perm_kj, int32_t* __restrict__ idx_ji_kj) {
@@ -228,6 +296,8 @@ triplet_fill_kj_kernel(const int32_t* __restrict__ src, const int32_t* __restric
     if (r < on) {
       e = out_list[ob + r];
       keep = dst[e] != k;
+      if (off && !keep)   // ends in atom k: excluded only if it is the opposite edge (negated offset)
+        keep = off[3 * e] != -off[3 * ep] || off[3 * e + 1] != -off[3 * ep + 1] || off[3 * e + 2] != -off[3 * ep + 2];
     }
     uint64_t mask = __ballot(keep);
     if (keep) {
@@ -276,19 +346,17 @@ inline size_t carve_triplets(void* p, int64_t n_atoms, int64_t n_edges, triplets
 
 inline int blocks_for(int64_t n, int per_block) { return (int)((n + per_block - 1) / per_block); }
 
-// id_swap[e] = edge dst[e] -> src[e]: binary search for source dst[e] in the row of target src[e]
+// id_swap[e] = the edge dst[e] -> src[e] with the negated cell offset, found in the row of target src[e]
 __global__ void reverse_edges_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
-                                     const int32_t* __restrict__ row_ptr, int64_t n_edges, int32_t* __restrict__ id_swap) {
+                                     const int32_t* __restrict__ off, const int32_t* __restrict__ row_ptr,
+                                     int64_t n_edges, int32_t* __restrict__ id_swap) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= n_edges) return;
   const int j = src[e], i = dst[e];
-  int lo = row_ptr[j], hi = row_ptr[j + 1];   // in-edges of j, sources ascending
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (src[mid] < i) lo = mid + 1;
-    else hi = mid;
-  }
-  id_swap[e] = (lo < row_ptr[j + 1] && src[lo] == i) ? lo : -1;
+  const int b = row_ptr[j], n = row_ptr[j + 1] - b;
+  const int p = off ? find_edge(src, off, b, n, i, -off[3 * e], -off[3 * e + 1], -off[3 * e + 2])
+                    : find_edge(src, nullptr, b, n, i, 0, 0, 0);
+  id_swap[e] = p >= 0 ? b + p : -1;
 }
 
 // largest ptr[i+1] - ptr[i]; one workgroup
@@ -317,15 +385,15 @@ max_degree_kernel(const int32_t* __restrict__ ptr, int64_t n, int32_t* __restric
 
 extern "C" {
 
-int gp_reverse_edges(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr, int64_t n_atoms,
-                     int64_t n_edges, int32_t* id_swap) {
+int gp_reverse_edges(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* offset,
+                     const int32_t* row_ptr, int64_t n_atoms, int64_t n_edges, int32_t* id_swap) {
   if (!ctx) return GP_BAD_ARG;
   GP_REQUIRE(ctx, n_atoms >= 0 && n_edges >= 0, "gp_reverse_edges: negative size");
   if (n_edges > INT32_MAX - 1 || n_atoms > INT32_MAX - 1) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_reverse_edges: sizes exceed int32");
   if (n_edges == 0) return GP_OK;
   GP_REQUIRE(ctx, src && dst && row_ptr && id_swap, "gp_reverse_edges: NULL pointer");
   GP_HIP(ctx, hipSetDevice(ctx->device));
-  reverse_edges_kernel<<<blocks_for(n_edges, 256), 256, 0, ctx->stream>>>(src, dst, row_ptr, n_edges, id_swap);
+  reverse_edges_kernel<<<blocks_for(n_edges, 256), 256, 0, ctx->stream>>>(src, dst, offset, row_ptr, n_edges, id_swap);
   GP_LAUNCH_CHECK(ctx, "reverse_edges_kernel");
   return GP_OK;
 }
@@ -353,24 +421,34 @@ int gp_edges_workspace(int64_t n_atoms, size_t* bytes) {
   return GP_OK;
 }
 
-int gp_edges_count(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, int64_t n_atoms,
-                   int32_t n_graphs, float cutoff, int32_t max_neighbors, void* ws, size_t ws_bytes,
-                   int64_t* n_edges) {
-  if (!ctx) return GP_BAD_ARG;
-  GP_REQUIRE(ctx, n_edges, "gp_edges_count: n_edges is NULL");
-  GP_REQUIRE(ctx, n_atoms >= 0 && n_graphs >= 0 && max_neighbors >= 0, "gp_edges_count: negative size");
-  GP_REQUIRE(ctx, cutoff > 0.f && cutoff == cutoff, "gp_edges_count: cutoff must be positive");
-  if (n_atoms > INT32_MAX - 1) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_edges_count: too many atoms");
+}  // extern "C"
+
+namespace {
+
+int check_images(gp_ctx* ctx, const char* who, const float* cell, int r0, int r1, int r2, int64_t n_atoms, images_t* im) {
+  GP_REQUIRE(ctx, cell, "%s: cell is NULL", who);
+  GP_REQUIRE(ctx, r0 >= 0 && r1 >= 0 && r2 >= 0 && r0 <= 16 && r1 <= 16 && r2 <= 16, "%s: image range must be 0..16 per axis", who);
+  *im = images_t{cell, r0, r1, r2};
+  if ((int64_t)im->count() * n_atoms > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "%s: atoms x images exceed int32", who);
+  return GP_OK;
+}
+
+int edges_count_impl(gp_ctx* ctx, const char* who, const float* pos, const int32_t* graph_ptr, images_t im, int64_t n_atoms,
+                     int32_t n_graphs, float cutoff, int32_t max_neighbors, void* ws, size_t ws_bytes, int64_t* n_edges) {
+  GP_REQUIRE(ctx, n_edges, "%s: n_edges is NULL", who);
+  GP_REQUIRE(ctx, n_atoms >= 0 && n_graphs >= 0 && max_neighbors >= 0, "%s: negative size", who);
+  GP_REQUIRE(ctx, cutoff > 0.f && cutoff == cutoff, "%s: cutoff must be positive", who);
+  if (n_atoms > INT32_MAX - 1) return gp_fail(ctx, GP_INT32_OVERFLOW, "%s: too many atoms", who);
   *n_edges = 0;
   if (n_atoms == 0 || n_graphs == 0) return GP_OK;
-  GP_REQUIRE(ctx, pos && graph_ptr && ws, "gp_edges_count: NULL pointer");
+  GP_REQUIRE(ctx, pos && graph_ptr && ws, "%s: NULL pointer", who);
   edges_ws w;
   size_t need = carve_edges(ws, n_atoms, &w);
-  if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_edges_count: workspace %zu < %zu", ws_bytes, need);
+  if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "%s: workspace %zu < %zu", who, ws_bytes, need);
   GP_HIP(ctx, hipSetDevice(ctx->device));
   const float c2 = cutoff * cutoff;
   edges_kernel<false><<<blocks_for(n_atoms, 4), 256, 0, ctx->stream>>>(
-      pos, graph_ptr, (int)n_atoms, n_graphs, c2, max_neighbors, w.deg, nullptr, nullptr, nullptr, nullptr, nullptr);
+      pos, graph_ptr, (int)n_atoms, n_graphs, c2, max_neighbors, im, w.deg, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
   GP_LAUNCH_CHECK(ctx, "edges_kernel<count>");
   scan_exclusive_kernel<<<1, SCAN_THREADS, 0, ctx->stream>>>(w.deg, w.row_ptr, n_atoms, w.total);
   GP_LAUNCH_CHECK(ctx, "scan_exclusive_kernel");
@@ -378,35 +456,76 @@ int gp_edges_count(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, int6
   GP_HIP(ctx, hipMemcpyAsync(&total, w.total, sizeof(total), hipMemcpyDeviceToHost, ctx->stream));
   GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
   *n_edges = total;
-  if (total > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_edges_count: %lld edges exceed int32", (long long)total);
+  if (total > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "%s: %lld edges exceed int32", who, (long long)total);
   return GP_OK;
+}
+
+int edges_fill_impl(gp_ctx* ctx, const char* who, const float* pos, const int32_t* graph_ptr, images_t im, int64_t n_atoms,
+                    int32_t n_graphs, float cutoff, int32_t max_neighbors, const void* ws, size_t ws_bytes, int64_t n_edges,
+                    int32_t* src, int32_t* dst, int32_t* offset, int32_t* row_ptr, float* dist, float* unit) {
+  GP_REQUIRE(ctx, n_atoms >= 0 && n_graphs >= 0 && max_neighbors >= 0 && n_edges >= 0, "%s: negative size", who);
+  GP_REQUIRE(ctx, cutoff > 0.f && cutoff == cutoff, "%s: cutoff must be positive", who);
+  GP_REQUIRE(ctx, row_ptr, "%s: row_ptr is NULL", who);
+  if (n_atoms > INT32_MAX - 1 || n_edges > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "%s: sizes exceed int32", who);
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  if (n_atoms == 0 || n_graphs == 0) {
+    GP_HIP(ctx, hipMemsetAsync(row_ptr, 0, sizeof(int32_t) * (n_atoms + 1), ctx->stream));
+    return GP_OK;
+  }
+  GP_REQUIRE(ctx, pos && graph_ptr && ws, "%s: NULL pointer", who);
+  GP_REQUIRE(ctx, n_edges == 0 || (src && dst), "%s: src/dst is NULL", who);
+  edges_ws w;
+  size_t need = carve_edges(const_cast<void*>(ws), n_atoms, &w);
+  if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "%s: workspace %zu < %zu", who, ws_bytes, need);
+  GP_HIP(ctx, hipMemcpyAsync(row_ptr, w.row_ptr, sizeof(int32_t) * (n_atoms + 1), hipMemcpyDeviceToDevice, ctx->stream));
+  if (n_edges == 0) return GP_OK;
+  const float c2 = cutoff * cutoff;
+  edges_kernel<true><<<blocks_for(n_atoms, 4), 256, 0, ctx->stream>>>(
+      pos, graph_ptr, (int)n_atoms, n_graphs, c2, max_neighbors, im, nullptr, w.row_ptr, src, dst, offset, dist, unit);
+  GP_LAUNCH_CHECK(ctx, "edges_kernel<fill>");
+  return GP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gp_edges_count(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, int64_t n_atoms,
+                   int32_t n_graphs, float cutoff, int32_t max_neighbors, void* ws, size_t ws_bytes,
+                   int64_t* n_edges) {
+  if (!ctx) return GP_BAD_ARG;
+  return edges_count_impl(ctx, "gp_edges_count", pos, graph_ptr, images_t{nullptr, 0, 0, 0}, n_atoms, n_graphs, cutoff,
+                          max_neighbors, ws, ws_bytes, n_edges);
 }
 
 int gp_edges_fill(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, int64_t n_atoms,
                   int32_t n_graphs, float cutoff, int32_t max_neighbors, const void* ws, size_t ws_bytes,
                   int64_t n_edges, int32_t* src, int32_t* dst, int32_t* row_ptr, float* dist, float* unit) {
   if (!ctx) return GP_BAD_ARG;
-  GP_REQUIRE(ctx, n_atoms >= 0 && n_graphs >= 0 && max_neighbors >= 0 && n_edges >= 0, "gp_edges_fill: negative size");
-  GP_REQUIRE(ctx, cutoff > 0.f && cutoff == cutoff, "gp_edges_fill: cutoff must be positive");
-  GP_REQUIRE(ctx, row_ptr, "gp_edges_fill: row_ptr is NULL");
-  if (n_atoms > INT32_MAX - 1 || n_edges > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_edges_fill: sizes exceed int32");
-  GP_HIP(ctx, hipSetDevice(ctx->device));
-  if (n_atoms == 0 || n_graphs == 0) {
-    GP_HIP(ctx, hipMemsetAsync(row_ptr, 0, sizeof(int32_t) * (n_atoms + 1), ctx->stream));
-    return GP_OK;
-  }
-  GP_REQUIRE(ctx, pos && graph_ptr && ws, "gp_edges_fill: NULL pointer");
-  GP_REQUIRE(ctx, n_edges == 0 || (src && dst), "gp_edges_fill: src/dst is NULL");
-  edges_ws w;
-  size_t need = carve_edges(const_cast<void*>(ws), n_atoms, &w);
-  if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_edges_fill: workspace %zu < %zu", ws_bytes, need);
-  GP_HIP(ctx, hipMemcpyAsync(row_ptr, w.row_ptr, sizeof(int32_t) * (n_atoms + 1), hipMemcpyDeviceToDevice, ctx->stream));
-  if (n_edges == 0) return GP_OK;
-  const float c2 = cutoff * cutoff;
-  edges_kernel<true><<<blocks_for(n_atoms, 4), 256, 0, ctx->stream>>>(
-      pos, graph_ptr, (int)n_atoms, n_graphs, c2, max_neighbors, nullptr, w.row_ptr, src, dst, dist, unit);
-  GP_LAUNCH_CHECK(ctx, "edges_kernel<fill>");
-  return GP_OK;
+  return edges_fill_impl(ctx, "gp_edges_fill", pos, graph_ptr, images_t{nullptr, 0, 0, 0}, n_atoms, n_graphs, cutoff,
+                         max_neighbors, ws, ws_bytes, n_edges, src, dst, nullptr, row_ptr, dist, unit);
+}
+
+int gp_edges_count_pbc(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, const float* cell, int64_t n_atoms,
+                       int32_t n_graphs, float cutoff, int32_t max_neighbors, int32_t rep0, int32_t rep1, int32_t rep2,
+                       void* ws, size_t ws_bytes, int64_t* n_edges) {
+  if (!ctx) return GP_BAD_ARG;
+  images_t im;
+  GP_TRY(check_images(ctx, "gp_edges_count_pbc", cell, rep0, rep1, rep2, n_atoms, &im));
+  return edges_count_impl(ctx, "gp_edges_count_pbc", pos, graph_ptr, im, n_atoms, n_graphs, cutoff, max_neighbors, ws,
+                          ws_bytes, n_edges);
+}
+
+int gp_edges_fill_pbc(gp_ctx* ctx, const float* pos, const int32_t* graph_ptr, const float* cell, int64_t n_atoms,
+                      int32_t n_graphs, float cutoff, int32_t max_neighbors, int32_t rep0, int32_t rep1, int32_t rep2,
+                      const void* ws, size_t ws_bytes, int64_t n_edges, int32_t* src, int32_t* dst, int32_t* offset,
+                      int32_t* row_ptr, float* dist, float* unit) {
+  if (!ctx) return GP_BAD_ARG;
+  images_t im;
+  GP_TRY(check_images(ctx, "gp_edges_fill_pbc", cell, rep0, rep1, rep2, n_atoms, &im));
+  GP_REQUIRE(ctx, n_edges == 0 || offset, "gp_edges_fill_pbc: offset is NULL");
+  return edges_fill_impl(ctx, "gp_edges_fill_pbc", pos, graph_ptr, im, n_atoms, n_graphs, cutoff, max_neighbors, ws,
+                         ws_bytes, n_edges, src, dst, offset, row_ptr, dist, unit);
 }
 
 int gp_triplets_workspace(int64_t n_atoms, int64_t n_edges, size_t* bytes) {
@@ -416,9 +535,12 @@ int gp_triplets_workspace(int64_t n_atoms, int64_t n_edges, size_t* bytes) {
   return GP_OK;
 }
 
-int gp_triplets_count(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
-                      int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes, int64_t* n_triplets) {
-  if (!ctx) return GP_BAD_ARG;
+}  // extern "C"
+
+namespace {
+
+int triplets_count_impl(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* offset, const int32_t* row_ptr,
+                        int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes, int64_t* n_triplets) {
   GP_REQUIRE(ctx, n_triplets, "gp_triplets_count: n_triplets is NULL");
   GP_REQUIRE(ctx, n_atoms >= 0 && n_edges >= 0, "gp_triplets_count: negative size");
   if (n_atoms > INT32_MAX - 1 || n_edges > INT32_MAX - 1) return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_triplets_count: sizes exceed int32");
@@ -432,7 +554,7 @@ int gp_triplets_count(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const
   hipStream_t st = ctx->stream;
   GP_HIP(ctx, hipMemsetAsync(w.out_deg, 0, sizeof(int32_t) * n_atoms, st));
   GP_HIP(ctx, hipMemsetAsync(w.cursor, 0, sizeof(int32_t) * n_atoms, st));
-  triplet_count_kernel<<<blocks_for(n_edges, 256), 256, 0, st>>>(src, dst, row_ptr, (int)n_edges, w.cnt, w.skip, w.out_deg);
+  triplet_count_kernel<<<blocks_for(n_edges, 256), 256, 0, st>>>(src, dst, offset, row_ptr, (int)n_edges, w.cnt, w.skip, w.out_deg);
   GP_LAUNCH_CHECK(ctx, "triplet_count_kernel");
   scan_exclusive_kernel<<<1, SCAN_THREADS, 0, st>>>(w.cnt, w.seg_ji, n_edges, w.totals + 0);
   GP_LAUNCH_CHECK(ctx, "scan_exclusive_kernel");
@@ -444,11 +566,10 @@ int gp_triplets_count(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const
   return GP_OK;
 }
 
-int gp_triplets_fill(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
-                     int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes, int64_t n_triplets,
-                     int32_t* idx_kj, int32_t* idx_ji, int32_t* seg_ptr_ji, int32_t* perm_kj,
-                     int32_t* idx_ji_kj, int32_t* seg_ptr_kj) {
-  if (!ctx) return GP_BAD_ARG;
+int triplets_fill_impl(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* offset, const int32_t* row_ptr,
+                       int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes, int64_t n_triplets,
+                       int32_t* idx_kj, int32_t* idx_ji, int32_t* seg_ptr_ji, int32_t* perm_kj,
+                       int32_t* idx_ji_kj, int32_t* seg_ptr_kj) {
   GP_REQUIRE(ctx, n_atoms >= 0 && n_edges >= 0 && n_triplets >= 0, "gp_triplets_fill: negative size");
   if (n_atoms > INT32_MAX - 1 || n_edges > INT32_MAX - 1 || n_triplets > INT32_MAX)
     return gp_fail(ctx, GP_INT32_OVERFLOW, "gp_triplets_fill: sizes exceed int32");
@@ -481,17 +602,54 @@ int gp_triplets_fill(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const 
   GP_LAUNCH_CHECK(ctx, "out_scatter_kernel");
   out_sort_kernel<<<blocks_for(n_atoms, 4), 256, 0, st>>>(w.out_ptr, w.out_tmp, (int)n_atoms, w.out_list);
   GP_LAUNCH_CHECK(ctx, "out_sort_kernel");
-  triplet_count_kj_kernel<<<blocks_for(n_edges, 256), 256, 0, st>>>(src, dst, row_ptr, w.out_ptr, (int)n_edges, w.cnt_kj);
+  triplet_count_kj_kernel<<<blocks_for(n_edges, 256), 256, 0, st>>>(src, dst, offset, row_ptr, w.out_ptr, (int)n_edges, w.cnt_kj);
   GP_LAUNCH_CHECK(ctx, "triplet_count_kj_kernel");
   scan_exclusive_kernel<<<1, SCAN_THREADS, 0, st>>>(w.cnt_kj, w.seg_kj, n_edges, w.totals + 2);
   GP_LAUNCH_CHECK(ctx, "scan_exclusive_kernel");
   GP_HIP(ctx, hipMemcpyAsync(seg_ptr_kj, w.seg_kj, sizeof(int32_t) * (n_edges + 1), hipMemcpyDeviceToDevice, st));
   if (n_triplets > 0) {
-    triplet_fill_kj_kernel<<<blocks_for(n_edges, 4), 256, 0, st>>>(src, dst, row_ptr, w.out_ptr, w.out_list, w.seg_ji,
+    triplet_fill_kj_kernel<<<blocks_for(n_edges, 4), 256, 0, st>>>(src, dst, offset, row_ptr, w.out_ptr, w.out_list, w.seg_ji,
                                                                  w.skip, w.seg_kj, (int)n_edges, perm_kj, idx_ji_kj);
     GP_LAUNCH_CHECK(ctx, "triplet_fill_kj_kernel");
   }
   return GP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gp_triplets_count(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
+                      int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes, int64_t* n_triplets) {
+  if (!ctx) return GP_BAD_ARG;
+  return triplets_count_impl(ctx, src, dst, nullptr, row_ptr, n_atoms, n_edges, ws, ws_bytes, n_triplets);
+}
+
+int gp_triplets_fill(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* row_ptr,
+                     int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes, int64_t n_triplets,
+                     int32_t* idx_kj, int32_t* idx_ji, int32_t* seg_ptr_ji, int32_t* perm_kj,
+                     int32_t* idx_ji_kj, int32_t* seg_ptr_kj) {
+  if (!ctx) return GP_BAD_ARG;
+  return triplets_fill_impl(ctx, src, dst, nullptr, row_ptr, n_atoms, n_edges, ws, ws_bytes, n_triplets, idx_kj, idx_ji,
+                            seg_ptr_ji, perm_kj, idx_ji_kj, seg_ptr_kj);
+}
+
+int gp_triplets_count_pbc(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* offset,
+                          const int32_t* row_ptr, int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes,
+                          int64_t* n_triplets) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, n_edges == 0 || offset, "gp_triplets_count_pbc: offset is NULL");
+  return triplets_count_impl(ctx, src, dst, offset, row_ptr, n_atoms, n_edges, ws, ws_bytes, n_triplets);
+}
+
+int gp_triplets_fill_pbc(gp_ctx* ctx, const int32_t* src, const int32_t* dst, const int32_t* offset,
+                         const int32_t* row_ptr, int64_t n_atoms, int64_t n_edges, void* ws, size_t ws_bytes,
+                         int64_t n_triplets, int32_t* idx_kj, int32_t* idx_ji, int32_t* seg_ptr_ji, int32_t* perm_kj,
+                         int32_t* idx_ji_kj, int32_t* seg_ptr_kj) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, n_edges == 0 || offset, "gp_triplets_fill_pbc: offset is NULL");
+  return triplets_fill_impl(ctx, src, dst, offset, row_ptr, n_atoms, n_edges, ws, ws_bytes, n_triplets, idx_kj, idx_ji,
+                            seg_ptr_ji, perm_kj, idx_ji_kj, seg_ptr_kj);
 }
 
 }  // extern "C"
