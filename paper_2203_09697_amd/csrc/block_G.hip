@@ -23,10 +23,13 @@ namespace {
 
 constexpr float INV_SQRT2 = 0.70710678118654752440f;
 
+bool half_storage(const gp_dims* d);
+
 struct saved_G {
   float *z_ba, *gate, *xg, *z_dn, *x, *Radt, *A, *z, *z_up, *z_skip, *Wrbf, *WcT;
   float* B1;   // radial factor at the target edge only: B1[e,l,f] = sum_t Y_l(t) x[kj(t),f]
   float* z_ac; // symmetric blocks only: pre-activation of the second up-projection [E, H]
+  __bf16* m_h; // bf16 storage only: the block's input messages rounded to bf16 [E, H] (operand of four GEMMs)
 };
 
 size_t carve_saved_G(void* p, const gp_dims* d, int64_t E, saved_G* s) {
@@ -46,6 +49,7 @@ size_t carve_saved_G(void* p, const gp_dims* d, int64_t E, saved_G* s) {
   s->WcT = c.take<float>(S * C * R);
   s->B1 = c.take<float>(d->radial_at_target ? E * S * F : 0);
   s->z_ac = c.take<float>(d->symmetric ? E * H : 0);
+  s->m_h = c.take<__bf16>(half_storage(d) ? E * H : 0);
   return c.off;
 }
 
@@ -152,6 +156,84 @@ __global__ void sym_bwd_kernel(const float* __restrict__ g, const float* __restr
   d_ac[i] = sw >= 0 ? 0.5f * g[(int64_t)sw * H + (i % H)] * dsilu_f(z_ac[i]) : 0.f;
 }
 
+// ---- bf16 storage of the [E, emb] intermediates (bf16 blocks): elementwise kernels, 4 elements per thread
+typedef __bf16 h4 __attribute__((ext_vector_type(4)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// d1 = g s silu'(z1), d2 = g s silu'(z2);  g fp32, everything else bf16
+__global__ void dsilu2_half_kernel(const float* __restrict__ g, float s, const __bf16* __restrict__ z1,
+                                   const __bf16* __restrict__ z2, __bf16* __restrict__ d1, __bf16* __restrict__ d2,
+                                   int64_t n) {
+  const int64_t i = 4 * ((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
+  if (i >= n) return;
+  if (i + 3 < n) {
+    const f4 gv = *reinterpret_cast<const f4*>(g + i);
+    const h4 a = *reinterpret_cast<const h4*>(z1 + i), b = *reinterpret_cast<const h4*>(z2 + i);
+    h4 o1, o2;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      o1[c] = (__bf16)(gv[c] * s * dsilu_f((float)a[c]));
+      o2[c] = (__bf16)(gv[c] * s * dsilu_f((float)b[c]));
+    }
+    *reinterpret_cast<h4*>(d1 + i) = o1;
+    *reinterpret_cast<h4*>(d2 + i) = o2;
+  } else {
+    for (int64_t k = i; k < n; ++k) {
+      d1[k] = (__bf16)(g[k] * s * dsilu_f((float)z1[k]));
+      d2[k] = (__bf16)(g[k] * s * dsilu_f((float)z2[k]));
+    }
+  }
+}
+
+// dz = dxg gate silu'(z), dgate = dxg silu(z);  all bf16
+__global__ void gate_bwd_half_kernel(const __bf16* __restrict__ dxg, const __bf16* __restrict__ z,
+                                     const __bf16* __restrict__ gate, __bf16* __restrict__ dz, __bf16* __restrict__ dgate,
+                                     int64_t n) {
+  const int64_t i = 4 * ((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
+  if (i >= n) return;
+  if (i + 3 < n) {
+    const h4 d = *reinterpret_cast<const h4*>(dxg + i), zz = *reinterpret_cast<const h4*>(z + i),
+             gt = *reinterpret_cast<const h4*>(gate + i);
+    h4 o1, o2;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float dv = (float)d[c], zv = (float)zz[c];
+      o1[c] = (__bf16)(dv * (float)gt[c] * dsilu_f(zv));
+      o2[c] = (__bf16)(dv * silu_f(zv));
+    }
+    *reinterpret_cast<h4*>(dz + i) = o1;
+    *reinterpret_cast<h4*>(dgate + i) = o2;
+  } else {
+    for (int64_t k = i; k < n; ++k) {
+      const float dv = (float)dxg[k], zv = (float)z[k];
+      dz[k] = (__bf16)(dv * (float)gate[k] * dsilu_f(zv));
+      dgate[k] = (__bf16)(dv * silu_f(zv));
+    }
+  }
+}
+
+// out = bf16(in), 4 elements per thread
+__global__ void to_half_kernel(const float* __restrict__ in, __bf16* __restrict__ out, int64_t n) {
+  const int64_t i = 4 * ((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
+  if (i >= n) return;
+  if (i + 3 < n) {
+    const f4 v = *reinterpret_cast<const f4*>(in + i);
+    h4 o;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) o[c] = (__bf16)v[c];
+    *reinterpret_cast<h4*>(out + i) = o;
+  } else {
+    for (int64_t k = i; k < n; ++k) out[k] = (__bf16)in[k];
+  }
+}
+
+// Whether the [E, emb]-sized intermediates of a block are stored as bf16: bf16 blocks whose widths
+// allow 16-byte rows of bf16.  They are consumed by bf16-operand GEMMs (which would round them
+// anyway) or by elementwise activation derivatives.  The buffers keep their fp32 sizes.
+bool half_storage(const gp_dims* d) {
+  return d->dtype == GP_BF16_F32ACC && !d->symmetric && d->emb % 8 == 0 && (d->emb_cbf * d->emb_bil) % 8 == 0;
+}
+
 // dst[q] (+)= src[perm[q]]
 __global__ void permute_add_kernel(const float* __restrict__ src, const int32_t* __restrict__ perm, int64_t n,
                                    int accumulate, float* __restrict__ dst) {
@@ -214,12 +296,21 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
 
   e = gp_epilogue(); e.out = s.Wrbf;
   GP_TRY(gp_gemm_nn(ctx, w->W_rbfS, w->W_rbfB, R, H, RB, e));                       // W_rbf = W_rbfS W_rbfB
-  e = gp_epilogue(); e.out = s.gate;
+  const bool hs = half_storage(dims);   // gate, z_ba, xg, z_skip, t_skip, z_up live in HBM as bf16
+  e = gp_epilogue(); e.out = s.gate; e.bf16 = hs ? EPI_BF_OUT : 0u;
   GP_TRY(gp_gemm_nn(ctx, g, s.Wrbf, E, H, R, e));                                   // gate
+  const float* m_op = m_in;   // the input messages as a GEMM operand
+  if (hs) {
+    gp_prof_scope prof(ctx, "to_half", 0.0, 6.0 * (double)E * H);
+    to_half_kernel<<<(unsigned)(((int64_t)E * H / 4 + 256) / 256), 256, 0, ctx->stream>>>(m_in, s.m_h, (int64_t)E * H);
+    GP_LAUNCH_CHECK(ctx, "to_half_kernel");
+    m_op = reinterpret_cast<const float*>(s.m_h);
+  }
   e = gp_epilogue(); e.save_pre = s.z_ba; e.act = 1; e.mul = s.gate; e.out = s.xg;
-  GP_TRY(gp_gemm_nn(ctx, m_in, w->W_ba, E, H, H, e));                               // xg
+  e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_MUL | EPI_BF_OUT) : 0u;
+  GP_TRY(gp_gemm_nn(ctx, m_op, w->W_ba, E, H, H, e, hs));                           // xg
   e = gp_epilogue(); e.save_pre = s.z_dn; e.act = 1; e.out = s.x;
-  GP_TRY(gp_gemm_nn(ctx, s.xg, w->W_down, E, F, H, e));                             // x
+  GP_TRY(gp_gemm_nn(ctx, s.xg, w->W_down, E, F, H, e, hs));                         // x
   GP_TRY(gp_permute3(ctx, w->W_c, S, R, C, 0, 2, 1, s.WcT));                        // WcT[(l,c), n]
   e = gp_epilogue(); e.out = s.Radt;
   GP_TRY(gp_gemm_nt(ctx, s.WcT, g, S * C, (int)E, R, e));                           // Radt[(l,c), e]
@@ -236,8 +327,8 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   e = gp_epilogue(); e.out = s.z;
   GP_TRY(gp_gemm_nn(ctx, s.A, w->W_bil, E, O, C * F, e));                           // z
   float* t_skip = sc.eh[0];
-  e = gp_epilogue(); e.save_pre = s.z_skip; e.act = 1; e.out = t_skip;
-  GP_TRY(gp_gemm_nn(ctx, m_in, w->W_skip, E, H, H, e));
+  e = gp_epilogue(); e.save_pre = s.z_skip; e.act = 1; e.out = t_skip; e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_OUT) : 0u;
+  GP_TRY(gp_gemm_nn(ctx, m_op, w->W_skip, E, H, H, e, hs));
   if (dims->symmetric) {
     // m' = (t_skip + (act(z W_up) + act(z W_up_ac)[id_swap]) / sqrt(2)) / sqrt(2) = (act(z W_up) + t) / 2,
     // t = sqrt(2) t_skip + act(z W_up_ac)[id_swap]
@@ -252,6 +343,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     return GP_OK;
   }
   e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = INV_SQRT2; e.out = m_out;
+  e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST) : 0u;
   GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
   return GP_OK;
 }
@@ -279,6 +371,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
             R = dims->num_radial, RB = dims->emb_rbf;
   const int64_t EH = E * H;
   const float* g = basis->rbf;
+  const bool hs = half_storage(dims);   // saved z_ba, gate, xg, z_skip, z_up and the four buffers below are bf16
   float *d_up = sc.eh[0], *d_skip = sc.eh[1], *dxg = sc.eh[2], *dgate = sc.eh[3];
   gp_epilogue e;
 
@@ -292,16 +385,21 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
     GP_TRY(gp_gemm_tn(ctx, s.z, d_ac, E, O, H, gw->W_up_ac, nullptr, sc.part, sc.part_bytes));
     e = gp_epilogue(); e.out = sc.dz;
     GP_TRY(gp_gemm_nt(ctx, d_ac, w->W_up_ac, E, O, H, e));                          // dz (opposite-edge path)
+  } else if (hs) {
+    dsilu2_half_kernel<<<(unsigned)((EH / 4 + 256) / 256), 256, 0, ctx->stream>>>(
+        grad_m_out, INV_SQRT2, (const __bf16*)s.z_up, (const __bf16*)s.z_skip, (__bf16*)d_up, (__bf16*)d_skip, EH);
+    GP_LAUNCH_CHECK(ctx, "dsilu2_half_kernel");
   } else {
     GP_TRY(gp_ew_dsilu2(ctx, grad_m_out, INV_SQRT2, s.z_up, s.z_skip, d_up, d_skip, EH));
   }
-  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.z, d_up, E, O, H, gw->W_up, nullptr, sc.part_aux, sc.part_bytes); }, {d_up}));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.z, d_up, E, O, H, gw->W_up, nullptr, sc.part_aux, sc.part_bytes, 0, hs); }, {d_up}));
   e = gp_epilogue(); e.out = sc.dz;
   if (dims->symmetric) e.add_post = sc.dz;
-  GP_TRY(gp_gemm_nt(ctx, d_up, w->W_up, E, O, H, e));                               // dz
-  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, d_skip, E, H, H, gw->W_skip, nullptr, sc.part_aux, sc.part_bytes); }, {}));
+  GP_TRY(gp_gemm_nt(ctx, d_up, w->W_up, E, O, H, e, hs));                           // dz
+  const float* m_op = hs ? reinterpret_cast<const float*>(s.m_h) : m_in;   // rounded copy written by the forward pass
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_op, d_skip, E, H, H, gw->W_skip, nullptr, sc.part_aux, sc.part_bytes, hs, hs); }, {}));
   e = gp_epilogue(); e.out = grad_m_in;
-  GP_TRY(gp_gemm_nt(ctx, d_skip, w->W_skip, E, H, H, e));                           // dm (skip path)
+  GP_TRY(gp_gemm_nt(ctx, d_skip, w->W_skip, E, H, H, e, hs));                       // dm (skip path)
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part_aux, sc.part_bytes); }, {}));
   if (dims->radial_at_target) {
     // mirror image of the source-edge form: G[e',c,o] = sum_{t: kj(t)=e'} y'_t[c] dz[ji(t),o] with
@@ -331,10 +429,10 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   else
     GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, nullptr, nullptr, nullptr, sc.dz, nullptr, O, S, 1,
                              sc.Hd, nullptr));
-  GP_TRY(gp_tripG_edge_G(ctx, s.Radt, sc.Hd, E, S, C, O, sc.Gm));                   // G[e', (c,o)]
+  GP_TRY(gp_tripG_edge_G(ctx, s.Radt, sc.Hd, E, S, C, O, sc.Gm, hs));               // G[e', (c,o)] (bf16 with hs)
   GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                   // [(c,o), f]
   e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
-  GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e));                         // dz_dn
+  GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e, hs));                     // dz_dn
   GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));                   // [f, (c,o)]
   e = gp_epilogue(); e.out = sc.V;
   GP_TRY(gp_gemm_nn(ctx, s.x, sc.WbilV, E, C * O, F, e));                           // V[e', (c,o)]
@@ -349,24 +447,30 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   }
   GP_TRY(gp_gemm_tn(ctx, g, sc.dRad, E, R, S * C, sc.dWcP, nullptr, sc.part, sc.part_bytes));   // [n, (l,c)]
   GP_TRY(gp_permute3(ctx, sc.dWcP, R, S, C, 1, 0, 2, gw->W_c));                     // -> [l, n, c]
-  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dzdn, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes); }, {}));
-  e = gp_epilogue(); e.out = dxg;
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dzdn, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes, hs, 0); }, {}));
+  e = gp_epilogue(); e.out = dxg; e.bf16 = hs ? EPI_BF_OUT : 0u;
   GP_TRY(gp_gemm_nt(ctx, sc.dzdn, w->W_down, E, H, F, e));                          // dxg
   float* dz_ba = d_up;   // d_up is no longer needed on this stream
   GP_TRY(aux.before_write(d_up));
-  GP_TRY(gp_ew_gate_bwd(ctx, dxg, s.z_ba, s.gate, dz_ba, dgate, EH));
-  GP_TRY(gp_gemm_tn(ctx, g, dgate, E, R, H, sc.dWrbf, nullptr, sc.part, sc.part_bytes));
+  if (hs) {
+    gate_bwd_half_kernel<<<(unsigned)((EH / 4 + 256) / 256), 256, 0, ctx->stream>>>(
+        (const __bf16*)dxg, (const __bf16*)s.z_ba, (const __bf16*)s.gate, (__bf16*)dz_ba, (__bf16*)dgate, EH);
+    GP_LAUNCH_CHECK(ctx, "gate_bwd_half_kernel");
+  } else {
+    GP_TRY(gp_ew_gate_bwd(ctx, dxg, s.z_ba, s.gate, dz_ba, dgate, EH));
+  }
+  GP_TRY(gp_gemm_tn(ctx, g, dgate, E, R, H, sc.dWrbf, nullptr, sc.part, sc.part_bytes, 0, hs));
   e = gp_epilogue(); e.out = gw->W_rbfS;
   GP_TRY(gp_gemm_nt(ctx, sc.dWrbf, w->W_rbfB, R, RB, H, e));
   GP_TRY(gp_gemm_tn(ctx, w->W_rbfS, sc.dWrbf, R, RB, H, gw->W_rbfB, nullptr, sc.part, sc.part_bytes));
-  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, dz_ba, E, H, H, gw->W_ba, nullptr, sc.part_aux, sc.part_bytes); }, {}));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_op, dz_ba, E, H, H, gw->W_ba, nullptr, sc.part_aux, sc.part_bytes, hs, hs); }, {}));
   e = gp_epilogue(); e.add_post = grad_m_in; e.out = grad_m_in;
-  GP_TRY(gp_gemm_nt(ctx, dz_ba, w->W_ba, E, H, H, e));                              // dm += ba path
+  GP_TRY(gp_gemm_nt(ctx, dz_ba, w->W_ba, E, H, H, e, hs));                          // dm += ba path
   if (grad_rbf) {
     // dL/dg = dgate W_rbf^T + dRad . W_c  (both paths through the Gaussian basis)
     e = gp_epilogue(); e.out = grad_rbf;
     if (accumulate_basis_grads) e.add_post = grad_rbf;
-    GP_TRY(gp_gemm_nt(ctx, dgate, s.Wrbf, E, R, H, e));
+    GP_TRY(gp_gemm_nt(ctx, dgate, s.Wrbf, E, R, H, e, hs));
     e = gp_epilogue(); e.add_post = grad_rbf; e.out = grad_rbf;
     GP_TRY(gp_gemm_nn(ctx, sc.dRad, s.WcT, E, R, S * C, e));
   }

@@ -16,17 +16,26 @@ struct gp_epilogue {
   float* out = nullptr;             // out[row,col] = v
   float* out2 = nullptr;            // out2[row,col] = v * silu'(z2src[row,col])
   const float* z2src = nullptr;
+  // Storage type of the [rows, n] matrices above: a set bit means the pointer addresses bf16
+  // elements (2 bytes, round-to-nearest-even on store) instead of fp32; bias is always fp32.
+  // Only the bf16-operand GEMM kernels accept a non-zero mask.
+  unsigned bf16 = 0;
+};
+enum : unsigned {
+  EPI_BF_ADD_PRE = 1u, EPI_BF_SAVE_PRE = 2u, EPI_BF_ZSRC = 4u, EPI_BF_MUL = 8u, EPI_BF_ADD_POST = 16u,
+  EPI_BF_OUT = 32u, EPI_BF_OUT2 = 64u, EPI_BF_Z2SRC = 128u
 };
 
 // C = A[M,K] @ B[K,N]
-int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi);
+// a_bf16 (bf16-operand kernels only): A addresses bf16 elements instead of fp32
+int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16 = 0);
 // C = A[M,K] @ Bt[N,K]^T
-int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi);
+int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16 = 0);
 // out[M,N] = A[rows,M]^T @ B[rows,N]; deterministic two-stage reduction through `part`.
 // If colsum_out != NULL it also receives colsum_out[n] = sum_r B[r,n] (the bias gradient).
 size_t gp_gemm_tn_scratch(int64_t rows, int M, int N);
 int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M, int N, float* out,
-               float* colsum_out, float* part, size_t part_bytes);
+               float* colsum_out, float* part, size_t part_bytes, int a_bf16 = 0, int b_bf16 = 0);
 // out[n] = sum_r X[r,n]
 size_t gp_colsum_scratch(int64_t rows, int N);
 int gp_colsum(gp_ctx* ctx, const float* X, int64_t rows, int N, float* out, float* part, size_t part_bytes);

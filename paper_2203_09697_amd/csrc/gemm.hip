@@ -404,6 +404,8 @@ int dispatch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
   // bf16 operands (fp32 accumulate) when the calling block asks for them; the fused column
   // sums exist only in the fp32 kernel
   if (ctx->gemm_bf16 && !(MODE == MODE_TN && g.colsum_part)) return gp_gemm_bf16_launch(ctx, MODE, &g, splits);
+  if (g.a_bf16 || g.b_bf16 || g.epi.bf16)
+    return gp_fail(ctx, GP_BAD_ARG, "gemm: bf16 storage is only handled by the bf16-operand kernels");
 #if GP_GEMM_BM == 64
   if (g.N > 64) return launch_gemm<TILE_BM, 128, 1, 4, MODE>(ctx, g, splits);
   if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
@@ -455,26 +457,28 @@ tn_plan_t tn_plan(int64_t rows, int M, int N) {
 
 }  // namespace
 
-int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi) {
+int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16) {
   GP_REQUIRE(ctx, A && B && M >= 0 && N > 0 && K > 0, "gemm_nn: bad arguments");
   GP_TRY(check_epi(ctx, epi));
   if (M == 0) return GP_OK;
   gemm_args g{};
   g.A = A; g.B = B; g.M = M; g.N = N; g.K = K; g.lda = K; g.ldb = N;
-  g.vecA = (K % 4 == 0) && aligned16(A);
+  g.a_bf16 = a_bf16;
+  g.vecA = (K % (a_bf16 ? 8 : 4) == 0) && aligned16(A);
   g.vecB = (N % 4 == 0) && aligned16(B);
   g.epi = epi;
   g.vecC = epi_vec_ok(epi, N);
   return dispatch_gemm<MODE_NN>(ctx, g, 1);
 }
 
-int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi) {
+int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16) {
   GP_REQUIRE(ctx, A && Bt && M >= 0 && N > 0 && K > 0, "gemm_nt: bad arguments");
   GP_TRY(check_epi(ctx, epi));
   if (M == 0) return GP_OK;
   gemm_args g{};
   g.A = A; g.B = Bt; g.M = M; g.N = N; g.K = K; g.lda = K; g.ldb = K;
-  g.vecA = (K % 4 == 0) && aligned16(A);
+  g.a_bf16 = a_bf16;
+  g.vecA = (K % (a_bf16 ? 8 : 4) == 0) && aligned16(A);
   g.vecB = (K % 4 == 0) && aligned16(Bt);
   g.epi = epi;
   g.vecC = epi_vec_ok(epi, N);
@@ -487,7 +491,8 @@ size_t gp_gemm_tn_scratch(int64_t rows, int M, int N) {
 }
 
 int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M, int N, float* out,
-               float* colsum_out, float* part, size_t part_bytes) {
+               float* colsum_out, float* part, size_t part_bytes, int a_bf16, int b_bf16) {
+  GP_REQUIRE(ctx, !colsum_out || !(a_bf16 || b_bf16), "gemm_tn: column sums need fp32 operands");
   GP_REQUIRE(ctx, A && B && out && rows >= 0 && M > 0 && N > 0, "gemm_tn: bad arguments");
   if (rows == 0) {
     GP_HIP(ctx, hipMemsetAsync(out, 0, sizeof(float) * M * N, ctx->stream));
@@ -500,8 +505,11 @@ int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M,
   if (!part || part_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gemm_tn: scratch %zu < %zu", part_bytes, need);
   gemm_args g{};
   g.A = A; g.B = B; g.M = M; g.N = N; g.K = (int)rows; g.lda = M; g.ldb = N;
-  g.vecA = (M % 4 == 0) && aligned16(A);
-  g.vecB = (N % 4 == 0) && aligned16(B);
+  g.a_bf16 = a_bf16;
+  g.b_bf16 = b_bf16;
+  // fp32 operand: 16-byte loads legal; bf16 operand (4-byte loads of column pairs): even extent, 4-byte aligned
+  g.vecA = a_bf16 ? (M % 2 == 0 && ((uintptr_t)A & 3) == 0) : (M % 4 == 0) && aligned16(A);
+  g.vecB = b_bf16 ? (N % 2 == 0 && ((uintptr_t)B & 3) == 0) : (N % 4 == 0) && aligned16(B);
   g.k_per_split = p.per;
   g.part = part;
   g.vecC = (N % 4 == 0) && aligned16(part) && ((size_t)M * N % 4 == 0);

@@ -205,14 +205,152 @@ struct bl_xcontig {
   }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE, bool VEC>
+// ---- operands already stored as bf16 (activations written by a producer's epilogue): no conversion,
+// half the bytes; 16-byte / 4-byte aligned rows are required (leading dimension a multiple of 8 / 2).
+
+// rows = tile rows, k contiguous: one 16-byte load is one LDS item
+template <int X>
+struct bl_kcontig_bf {
+  static constexpr int ITEMS = X * K8;
+  static constexpr int NV = (ITEMS + THREADS - 1) / THREADS;
+  static constexpr bool ALL = ITEMS % THREADS == 0;
+  const __bf16* base;
+  uint32_t off[NV];   // bytes
+  bf16x8 r[NV];
+
+  __device__ __forceinline__ void init(const float* __restrict__ src, int64_t ld, int64_t row0, int64_t n_rows) {
+    base = reinterpret_cast<const __bf16*>(src) + row0 * ld;
+    const int last = (int)(n_rows - 1 - row0 < X - 1 ? n_rows - 1 - row0 : X - 1);
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      const int row = idx / K8, kq = (idx % K8) * 8;
+      off[it] = (uint32_t)(((int64_t)(row < last ? row : last) * ld + kq) * 2);
+    }
+  }
+  __device__ __forceinline__ void fetch_full(int64_t k0) {
+    const char* p = reinterpret_cast<const char*>(base + k0);
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      if (!ALL && (int)threadIdx.x + it * THREADS >= ITEMS) continue;
+      r[it] = *reinterpret_cast<const bf16x8*>(p + off[it]);
+    }
+  }
+  __device__ __forceinline__ void fetch_tail(int64_t k0, int64_t k_end) {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      if (!ALL && idx >= ITEMS) continue;
+      const int kq = (idx % K8) * 8;
+      const __bf16* prow = reinterpret_cast<const __bf16*>(reinterpret_cast<const char*>(base) + (off[it] - 2u * kq));
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const int64_t k = k0 + kq + c;
+        const __bf16 v = prow[k < k_end ? k : k_end - 1];
+        r[it][c] = k < k_end ? v : (__bf16)0.f;
+      }
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* __restrict__ S, bool) const {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      if (!ALL && idx >= ITEMS) continue;
+      const int row = idx / K8, kq = (idx % K8) * 8;
+      *reinterpret_cast<bf16x8*>(&S[row * LDK + kq]) = r[it];
+    }
+  }
+};
+
+// x contiguous, k strided: a thread owns 2 consecutive x by 8 consecutive k; eight 4-byte loads, repacked
+// into two 8-k items.  Lanes take consecutive x pairs (256 contiguous bytes per k row and wavefront; the
+// two 16-byte LDS writes of neighbouring lanes are 160 bytes apart and cover all banks).
+template <int X>
+struct bl_xcontig_bf {
+  static constexpr int ITEMS = (X / 2) * K8;
+  static constexpr int NV = (ITEMS + THREADS - 1) / THREADS;
+  static constexpr bool ALL = ITEMS % THREADS == 0;
+  const __bf16* base;
+  int64_t ld;
+  uint32_t off[NV];       // bytes from the slab's first k row
+  uint32_t r[NV][8];      // [k] = (x, x+1)
+  uint32_t kmask[NV];
+
+  __device__ __forceinline__ void init(const float* __restrict__ src, int64_t ld_, int64_t x0, int64_t n_x) {
+    base = reinterpret_cast<const __bf16*>(src) + x0;
+    ld = ld_;
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      const int xq = (idx % (X / 2)) * 2, kq = (idx / (X / 2)) * 8;
+      const int64_t lim = n_x - x0 - 2;
+      off[it] = (uint32_t)((kq * ld + (xq < lim ? xq : lim)) * 2);
+      kmask[it] = 0xFFu;
+    }
+  }
+  __device__ __forceinline__ void fetch_full(int64_t k0) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const char* p = reinterpret_cast<const char*>(base + (k0 + kk) * ld);
+#pragma unroll
+      for (int it = 0; it < NV; ++it) {
+        if (!ALL && (int)threadIdx.x + it * THREADS >= ITEMS) continue;
+        r[it][kk] = *reinterpret_cast<const uint32_t*>(p + off[it]);
+      }
+    }
+  }
+  __device__ __forceinline__ void fetch_tail(int64_t k0, int64_t k_end) {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      kmask[it] = 0;
+      if (!ALL && idx >= ITEMS) continue;
+      const int kq = (idx / (X / 2)) * 8;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const int64_t k = k0 + kq + kk;
+        kmask[it] |= (k < k_end ? 1u : 0u) << kk;
+        const char* p = reinterpret_cast<const char*>(base + ((k < k_end ? k : k_end - 1) - kq) * ld);
+        r[it][kk] = *reinterpret_cast<const uint32_t*>(p + off[it]);
+      }
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* __restrict__ S, bool tail) const {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      if (!ALL && idx >= ITEMS) continue;
+      const int xq = (idx % (X / 2)) * 2, kq = (idx / (X / 2)) * 8;
+      uint32_t d[8];
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) d[kk] = (!tail || ((kmask[it] >> kk) & 1u)) ? r[it][kk] : 0u;
+      uint32_t lo[4], hi[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        lo[j] = (d[2 * j] & 0xFFFFu) | (d[2 * j + 1] << 16);
+        hi[j] = (d[2 * j] >> 16) | (d[2 * j + 1] & 0xFFFF0000u);
+      }
+      uint32_t* s0 = reinterpret_cast<uint32_t*>(&S[xq * LDK + kq]);
+      uint32_t* s1 = reinterpret_cast<uint32_t*>(&S[(xq + 1) * LDK + kq]);
+      typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+      *reinterpret_cast<u32x4*>(s0) = u32x4{lo[0], lo[1], lo[2], lo[3]};
+      *reinterpret_cast<u32x4*>(s1) = u32x4{hi[0], hi[1], hi[2], hi[3]};
+    }
+  }
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE, bool VEC, bool ABF, bool BBF>
 __global__ void __launch_bounds__(THREADS, 2)   // two wavefronts per SIMD: 256 registers each
 gemm_bf16_kernel(const gemm_args g) {
   static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+  static_assert(!BBF || MODE == MODE_TN, "the second operand is an activation only in the weight-gradient form");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MB = WM / 32, NB = WN / 32;
-  using loadA = typename std::conditional<MODE != MODE_TN, bl_kcontig<BM, VEC>, bl_xcontig<BM, VEC>>::type;
-  using loadB = typename std::conditional<MODE == MODE_NT, bl_kcontig<BN, VEC>, bl_xcontig<BN, VEC>>::type;
+  using loadA32 = typename std::conditional<MODE != MODE_TN, bl_kcontig<BM, VEC>, bl_xcontig<BM, VEC>>::type;
+  using loadA16 = typename std::conditional<MODE != MODE_TN, bl_kcontig_bf<BM>, bl_xcontig_bf<BM>>::type;
+  using loadB32 = typename std::conditional<MODE == MODE_NT, bl_kcontig<BN, VEC>, bl_xcontig<BN, VEC>>::type;
+  using loadA = typename std::conditional<ABF, loadA16, loadA32>::type;
+  using loadB = typename std::conditional<BBF, bl_xcontig_bf<BN>, loadB32>::type;
   extern __shared__ __attribute__((aligned(16))) float smem[];
   __bf16* As = reinterpret_cast<__bf16*>(smem);
   __bf16* Bs = As + BM * LDK;
@@ -304,7 +442,7 @@ gemm_bf16_kernel(const gemm_args g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD + l32] = acc[i][j][v];
       wave_lds_sync();
-#pragma unroll
+#pragma unroll 1   // the typed epilogue is long; unrolled 4 x MB x NB times it would not fit the register file
       for (int it = 0; it < 4; ++it) {
         const int r = it * 8 + (lane >> 3), c4 = (lane & 7) * 4;
         const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[r * EPI_LD + c4]);
@@ -328,32 +466,49 @@ gemm_bf16_kernel(const gemm_args g) {
     }
 }
 
-template <int BM, int BN, int WMS, int WNS, int MODE, bool VEC>
+template <int BM, int BN, int WMS, int WNS, int MODE, bool VEC, bool ABF = false, bool BBF = false>
 int launch_v(gp_ctx* ctx, gemm_args& g, int splits) {
   const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (tiles > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
   if (g.lda >= MAX_LD || g.ldb >= MAX_LD) return gp_fail(ctx, GP_BAD_ARG, "gemm (bf16): leading dimension above %lld", (long long)MAX_LD);
   dim3 grid((unsigned)tiles, (unsigned)splits, 1);
   static char name[48];
-  if (!name[0]) snprintf(name, sizeof(name), "gemm_bf16_%s_%dx%d", MODE == MODE_NN ? "nn" : MODE == MODE_NT ? "nt" : "tn", BM, BN);
+  if (!name[0])
+    snprintf(name, sizeof(name), "gemm_bf16%s_%s_%dx%d", (ABF || BBF) ? (ABF && BBF ? "_hh" : ABF ? "_hf" : "_fh") : "",
+             MODE == MODE_NN ? "nn" : MODE == MODE_NT ? "nt" : "tn", BM, BN);
   const double mnk = (double)g.M * g.N * g.K;
   gp_prof_scope prof(ctx, name, 2.0 * mnk,
-                     4.0 * ((double)g.M * g.K + (double)g.K * g.N + (double)g.M * g.N * (MODE == MODE_TN ? splits : 1)));
+                     (ABF ? 2.0 : 4.0) * (double)g.M * g.K + (BBF ? 2.0 : 4.0) * (double)g.K * g.N +
+                         4.0 * (double)g.M * g.N * (MODE == MODE_TN ? splits : 1));
   constexpr size_t lds_main = sizeof(__bf16) * (size_t)(BM + BN) * LDK;
   constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD;
   constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
   static_assert(lds <= 48 * 1024, "tile fits the default dynamic LDS limit");
-  gemm_bf16_kernel<BM, BN, WMS, WNS, MODE, VEC><<<grid, THREADS, lds, ctx->stream>>>(g);
+  gemm_bf16_kernel<BM, BN, WMS, WNS, MODE, VEC, ABF, BBF><<<grid, THREADS, lds, ctx->stream>>>(g);
   GP_LAUNCH_CHECK(ctx, "gemm_bf16_kernel");
   return GP_OK;
 }
 
 template <int MODE>
 int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
-#define GP_BF16_LAUNCH(BM, BN, WMS, WNS)                                                 \
-  do {                                                                                   \
-    if (g.vecA && g.vecB) return launch_v<BM, BN, WMS, WNS, MODE, true>(ctx, g, splits); \
-    return launch_v<BM, BN, WMS, WNS, MODE, false>(ctx, g, splits);                      \
+  // an operand stored as bf16 must satisfy its loader's alignment (vecA / vecB say so); VEC then only
+  // describes the remaining fp32 operand
+  if ((g.a_bf16 && !g.vecA) || (g.b_bf16 && !g.vecB))
+    return gp_fail(ctx, GP_BAD_ARG, "gemm (bf16 storage): operand not aligned / extent not a multiple of 8");
+  if (g.b_bf16 && MODE != MODE_TN) return gp_fail(ctx, GP_BAD_ARG, "gemm (bf16 storage): only the weight-gradient form takes a bf16 second operand");
+#define GP_BF16_LAUNCH(BM, BN, WMS, WNS)                                                                            \
+  do {                                                                                                              \
+    if (g.a_bf16 && g.b_bf16) return launch_v<BM, BN, WMS, WNS, MODE, true, true, MODE == MODE_TN>(ctx, g, splits); \
+    if (g.a_bf16) {                                                                                                 \
+      if (g.vecB) return launch_v<BM, BN, WMS, WNS, MODE, true, true, false>(ctx, g, splits);                       \
+      return launch_v<BM, BN, WMS, WNS, MODE, false, true, false>(ctx, g, splits);                                  \
+    }                                                                                                               \
+    if (g.b_bf16) {                                                                                                 \
+      if (g.vecA) return launch_v<BM, BN, WMS, WNS, MODE, true, false, MODE == MODE_TN>(ctx, g, splits);            \
+      return launch_v<BM, BN, WMS, WNS, MODE, false, false, MODE == MODE_TN>(ctx, g, splits);                       \
+    }                                                                                                               \
+    if (g.vecA && g.vecB) return launch_v<BM, BN, WMS, WNS, MODE, true>(ctx, g, splits);                            \
+    return launch_v<BM, BN, WMS, WNS, MODE, false>(ctx, g, splits);                                                 \
   } while (0)
   // the reduction over rows (TN) keeps the 128-row tiles its split plan was made for
   if (MODE != MODE_TN && g.M >= 8192 && g.N > 64) GP_BF16_LAUNCH(256, 128, 2, 2);

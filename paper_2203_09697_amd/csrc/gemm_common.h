@@ -20,52 +20,85 @@ struct gemm_args {
   int64_t lda, ldb;
   int vecA, vecB;          // 16-byte vector loads are legal for this operand
   int vecC;                // 16-byte accesses are legal for every matrix the epilogue touches
+  int a_bf16, b_bf16;      // operand storage is bf16 (bf16-operand kernels only)
   int64_t k_per_split;     // TN only
   float* part;             // TN only: [splits, M, N]
   float* colsum_part;      // TN only, optional: [splits * tiles_m, N] partial column sums of B
   gp_epilogue epi;
 };
 
-__device__ __forceinline__ void epilogue_store(const gp_epilogue& e, int64_t row, int col, int n, float v) {
-  const int64_t o = row * n + col;
-  if (e.bias) v += e.bias[col];
-  if (e.add_pre) v += e.add_pre[o];
-  if (e.save_pre) e.save_pre[o] = v;
-  if (e.act == 1) v = silu_f(v);
-  else if (e.act == 2) v *= dsilu_f(e.zsrc[o]);
-  if (e.mul) v *= e.mul[o];
-  if (e.add_post) v += e.add_post[o];
-  v *= e.scale;
-  if (e.out) e.out[o] = v;
-  if (e.out2) e.out2[o] = v * dsilu_f(e.z2src[o]);
-}
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ f32x4 ld4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
 __device__ __forceinline__ void st4(float* p, f32x4 v) { *reinterpret_cast<f32x4*>(p) = v; }
 
+// element o of a matrix stored as fp32 or (bf) bf16
+__device__ __forceinline__ float ldx(const float* p, int64_t o, unsigned bf) {
+  return bf ? (float)reinterpret_cast<const __bf16*>(p)[o] : p[o];
+}
+__device__ __forceinline__ void stx(float* p, int64_t o, unsigned bf, float v) {
+  if (bf) reinterpret_cast<__bf16*>(p)[o] = (__bf16)v;
+  else p[o] = v;
+}
+// 4 consecutive elements from o (o % 4 == 0, base 16-byte aligned)
+__device__ __forceinline__ f32x4 ldx4(const float* p, int64_t o, unsigned bf) {
+  if (!bf) return ld4(p + o);
+  const bf16x4 h = *reinterpret_cast<const bf16x4*>(reinterpret_cast<const __bf16*>(p) + o);
+  f32x4 v;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) v[c] = (float)h[c];
+  return v;
+}
+__device__ __forceinline__ void stx4(float* p, int64_t o, unsigned bf, f32x4 v) {
+  if (!bf) {
+    st4(p + o, v);
+    return;
+  }
+  bf16x4 h;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) h[c] = (__bf16)v[c];
+  *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p) + o) = h;
+}
+
+__device__ __forceinline__ void epilogue_store(const gp_epilogue& e, int64_t row, int col, int n, float v) {
+  const int64_t o = row * n + col;
+  const unsigned b = e.bf16;
+  if (e.bias) v += e.bias[col];
+  if (e.add_pre) v += ldx(e.add_pre, o, b & EPI_BF_ADD_PRE);
+  if (e.save_pre) stx(e.save_pre, o, b & EPI_BF_SAVE_PRE, v);
+  if (e.act == 1) v = silu_f(v);
+  else if (e.act == 2) v *= dsilu_f(ldx(e.zsrc, o, b & EPI_BF_ZSRC));
+  if (e.mul) v *= ldx(e.mul, o, b & EPI_BF_MUL);
+  if (e.add_post) v += ldx(e.add_post, o, b & EPI_BF_ADD_POST);
+  v *= e.scale;
+  if (e.out) stx(e.out, o, b & EPI_BF_OUT, v);
+  if (e.out2) stx(e.out2, o, b & EPI_BF_OUT2, v * dsilu_f(ldx(e.z2src, o, b & EPI_BF_Z2SRC)));
+}
+
 // Same steps on 4 consecutive columns (col % 4 == 0, all pointers 16-byte aligned, n % 4 == 0).
 __device__ __forceinline__ void epilogue_store4(const gp_epilogue& e, int64_t row, int col, int n, f32x4 v) {
   const int64_t o = row * n + col;
+  const unsigned b = e.bf16;
   if (e.bias) v += ld4(e.bias + col);
-  if (e.add_pre) v += ld4(e.add_pre + o);
-  if (e.save_pre) st4(e.save_pre + o, v);
+  if (e.add_pre) v += ldx4(e.add_pre, o, b & EPI_BF_ADD_PRE);
+  if (e.save_pre) stx4(e.save_pre, o, b & EPI_BF_SAVE_PRE, v);
   if (e.act == 1) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) v[c] = silu_f(v[c]);
   } else if (e.act == 2) {
-    const f32x4 z = ld4(e.zsrc + o);
+    const f32x4 z = ldx4(e.zsrc, o, b & EPI_BF_ZSRC);
 #pragma unroll
     for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
   }
-  if (e.mul) v *= ld4(e.mul + o);
-  if (e.add_post) v += ld4(e.add_post + o);
+  if (e.mul) v *= ldx4(e.mul, o, b & EPI_BF_MUL);
+  if (e.add_post) v += ldx4(e.add_post, o, b & EPI_BF_ADD_POST);
   v *= e.scale;
-  if (e.out) st4(e.out + o, v);
+  if (e.out) stx4(e.out, o, b & EPI_BF_OUT, v);
   if (e.out2) {
-    const f32x4 z = ld4(e.z2src + o);
+    const f32x4 z = ldx4(e.z2src, o, b & EPI_BF_Z2SRC);
 #pragma unroll
     for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
-    st4(e.out2 + o, v);
+    stx4(e.out2, o, b & EPI_BF_OUT2, v);
   }
 }
 

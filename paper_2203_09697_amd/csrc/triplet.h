@@ -40,7 +40,9 @@ size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E, int64_t T);
 // source edge follows from H by the two small per-edge products below.
 
 // Gout[e, c*O + o] = sum_l Radt[(l*C+c)*E + e] * H[e, l, o]
-int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout);
+// (out_half: Gout addresses bf16 elements)
+int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout,
+                    int out_half = 0);
 // dRad[e, l*C + c] = sum_o V[e, c*O + o] * H[e, l, o]
 int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad);
 // dst[a,b,c] = src element whose index along source dimension p0 is a, along p1 is b, along p2 is c

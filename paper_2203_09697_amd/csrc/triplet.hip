@@ -558,7 +558,7 @@ constexpr int EG_EDGES = 64;
 
 __global__ void __launch_bounds__(WPB* WAVE)
 edge_G_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64_t E, int S, int C, int O,
-              float* __restrict__ Gout) {
+              int out_half, float* __restrict__ Gout) {
   extern __shared__ float dyn_s[];   // rad_s[(l*C + c) * 64 + edge]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int64_t e0 = (int64_t)blockIdx.x * EG_EDGES;
@@ -578,7 +578,8 @@ edge_G_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64
 #pragma unroll
         for (int l = 0; l < ST; ++l)
           if (l < S) s += dyn_s[(l * C + c) * EG_EDGES + el] * h[l];
-        Gout[(e * C + c) * O + o] = s;
+        if (out_half) reinterpret_cast<__bf16*>(Gout)[(e * C + c) * O + o] = (__bf16)s;
+        else Gout[(e * C + c) * O + o] = s;
       }
     }
   }
@@ -630,12 +631,12 @@ __global__ void ew_dsilu2_kernel(const float* __restrict__ g, float s, const flo
 
 }  // namespace
 
-int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout) {
+int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout, int out_half) {
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, Radt && H && Gout && S >= 1 && S <= ST && C >= 1 && O >= 1, "edge_G: bad arguments");
   gp_prof_scope prof(ctx, "tripG_edge_G", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
   edge_G_kernel<<<(unsigned)((E + EG_EDGES - 1) / EG_EDGES), WPB * WAVE, (size_t)S * C * EG_EDGES * sizeof(float), ctx->stream>>>(
-      Radt, H, E, S, C, O, Gout);
+      Radt, H, E, S, C, O, out_half, Gout);
   GP_LAUNCH_CHECK(ctx, "edge_G_kernel");
   return GP_OK;
 }
