@@ -250,6 +250,14 @@ bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
   return g->n_edges > 0 && (double)g->n_triplets >= 96.0 * (double)g->n_edges;
 }
 
+// The accumulator A[E, C, F] is stored as bf16 when the matrix-core kernel writes it and bf16 storage is on: its
+// only readers are two bf16-operand GEMMs.  Forward and backward must agree, so the triplet mode of the
+// context must not change between the two calls of a step.
+bool a_half(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
+  return half_storage(d) && (d->emb_cbf * d->int_emb) % 8 == 0 && want_trip_mfma(ctx, d, g) &&
+         gp_tripG_mfma_usable(g, d->int_emb, d->num_spherical, d->emb_cbf);
+}
+
 int check_weights_G(gp_ctx* ctx, const gp_dims* d, const gp_weights_G* w, const char* what) {
   GP_REQUIRE(ctx, w, "%s is NULL", what);
   GP_REQUIRE(ctx, !d->symmetric || w->W_up_ac, "%s: W_up_ac is needed by a symmetric block", what);
@@ -297,6 +305,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   e = gp_epilogue(); e.out = s.Wrbf;
   GP_TRY(gp_gemm_nn(ctx, w->W_rbfS, w->W_rbfB, R, H, RB, e));                       // W_rbf = W_rbfS W_rbfB
   const bool hs = half_storage(dims);   // gate, z_ba, xg, z_skip, t_skip, z_up live in HBM as bf16
+  const bool ah = a_half(ctx, dims, graph);
   e = gp_epilogue(); e.out = s.gate; e.bf16 = hs ? EPI_BF_OUT : 0u;
   GP_TRY(gp_gemm_nn(ctx, g, s.Wrbf, E, H, R, e));                                   // gate
   const float* m_op = m_in;   // the input messages as a GEMM operand
@@ -321,11 +330,11 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     GP_TRY(gp_tripD_backward(ctx, &gm, basis->cos_alpha, nullptr, nullptr, nullptr, s.x, nullptr, F, S, 1, s.B1, nullptr));
     GP_TRY(gp_tripG_edge_G(ctx, s.Radt, s.B1, E, S, C, F, s.A));
   } else if (want_trip_mfma(ctx, dims, graph) && gp_tripG_mfma_usable(graph, F, S, C))
-    GP_TRY(gp_tripG_forward_mfma(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes));
+    GP_TRY(gp_tripG_forward_mfma(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes, ah));
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
   e = gp_epilogue(); e.out = s.z;
-  GP_TRY(gp_gemm_nn(ctx, s.A, w->W_bil, E, O, C * F, e));                           // z
+  GP_TRY(gp_gemm_nn(ctx, s.A, w->W_bil, E, O, C * F, e, ah));                       // z
   float* t_skip = sc.eh[0];
   e = gp_epilogue(); e.save_pre = s.z_skip; e.act = 1; e.out = t_skip; e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_OUT) : 0u;
   GP_TRY(gp_gemm_nn(ctx, m_op, w->W_skip, E, H, H, e, hs));
@@ -400,7 +409,8 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_op, d_skip, E, H, H, gw->W_skip, nullptr, sc.part_aux, sc.part_bytes, hs, hs); }, {}));
   e = gp_epilogue(); e.out = grad_m_in;
   GP_TRY(gp_gemm_nt(ctx, d_skip, w->W_skip, E, H, H, e, hs));                       // dm (skip path)
-  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part_aux, sc.part_bytes); }, {}));
+  const bool ah = a_half(ctx, dims, graph);
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part_aux, sc.part_bytes, ah, 0); }, {}));
   if (dims->radial_at_target) {
     // mirror image of the source-edge form: G[e',c,o] = sum_{t: kj(t)=e'} y'_t[c] dz[ji(t),o] with
     // y'_t[c] = sum_l Y_l(t) Rad[ji(t),l,c] is the forward kernel on the mirrored views

@@ -61,7 +61,7 @@ int gp_tripG_grad_cos(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj,
 bool gp_tripG_mfma_usable(const gp_graph* g, int F, int S, int C);
 size_t gp_tripG_mfma_scratch(int64_t E, int64_t T);
 int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
-                          int F, int S, int C, float* A, void* ybuf, size_t ybytes);
+                          int F, int S, int C, float* A, void* ybuf, size_t ybytes, int out_half = 0);   // out_half: A is bf16
 // Matrix-core forms of H[e',l,o] and of grad_cos (kj-major), same conditions on the graph; O a multiple of 32 up to 128
 bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S);
 int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S,

@@ -192,7 +192,7 @@ template <int CB>   // F = 32 CB
 __global__ void __launch_bounds__(MT)
 tripG_mfma_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                   const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_ji,
-                  const float* __restrict__ x, const __bf16* __restrict__ Yb, int C, int kp_cap,
+                  const float* __restrict__ x, const __bf16* __restrict__ Yb, int C, int kp_cap, int out_half,
                   float* __restrict__ A) {
   constexpr int F = 32 * CB;
   part_t P;
@@ -290,9 +290,14 @@ tripG_mfma_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
         const int k = 2 * rb + (v >> 3);                       // edge of the group (uniform)
         const int c = 8 * ((v >> 2) & 1) + 4 * kh + (v & 3);
         if (grp * 4 + k >= n_e || c >= C) continue;
-        float* dst = A + ((int64_t)e4[k] * C + c) * F + l32;
+        const int64_t at = ((int64_t)e4[k] * C + c) * F + l32;
+        if (out_half) {
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) dst[cb * 32] = acc[rb][cb][v];
+          for (int cb = 0; cb < CB; ++cb) reinterpret_cast<__bf16*>(A)[at + cb * 32] = (__bf16)acc[rb][cb][v];
+        } else {
+#pragma unroll
+          for (int cb = 0; cb < CB; ++cb) A[at + cb * 32] = acc[rb][cb][v];
+        }
       }
   }
 }
@@ -637,7 +642,7 @@ bool gp_tripG_mfma_usable(const gp_graph* g, int F, int S, int C) {
 }
 
 int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
-                          int F, int S, int C, float* A, void* ybuf, size_t ybytes) {
+                          int F, int S, int C, float* A, void* ybuf, size_t ybytes, int out_half) {
   const int64_t E = g->n_edges, T = g->n_triplets;
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, gp_tripG_mfma_usable(g, F, S, C), "triplet G (matrix-core form): graph lists or widths not supported");
@@ -662,7 +667,7 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
     const size_t lds = (size_t)F * (kp_cap + 8) * sizeof(__bf16);
     // registers allow 8 wavefronts per CU: two workgroups of 256 threads if their X tiles fit side by side
     const int mt = lds <= LDS_MAX / 2 ? 256 : MT;
-    gp_prof_scope prof(ctx, "tripG_mfma_fwd", Td * 2.0 * C * F, (Td + 16.0 * Ed) * CP * 2.0 + Ed * 4.0 * (F + (double)C * F));
+    gp_prof_scope prof(ctx, "tripG_mfma_fwd", Td * 2.0 * C * F, (Td + 16.0 * Ed) * CP * 2.0 + Ed * (4.0 * F + (out_half ? 2.0 : 4.0) * C * F));
 #define GP_TRIPG_LAUNCH(CB)                                                                                       \
   do {                                                                                                            \
     static size_t lds_set = 0;                                                                                    \
@@ -672,7 +677,7 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
       lds_set = lds;                                                                                              \
     }                                                                                                             \
     tripG_mfma_kernel<CB><<<grid, mt, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, x,  \
-                                                          Yb, C, kp_cap, A);                                      \
+                                                          Yb, C, kp_cap, out_half, A);                            \
   } while (0)
     switch (F / 32) {
       case 1: GP_TRIPG_LAUNCH(1); break;
