@@ -64,6 +64,9 @@ struct scratch_G {
   size_t ybytes;
   float *dA, *dB1, *gc_ji;   // radial factor at the target edge only: [E,C,F], [E,S,F], [T]
   float* eh5;                // symmetric blocks only: a fifth [E, H] buffer
+  // bf16 storage only: weight matrices rounded to bf16 once per call, so that both operands of the large
+  // GEMMs are copied to LDS without conversion
+  __bf16 *W_ba_h, *W_skip_h, *W_down_h, *W_up_h, *W_bil_h, *WbilP_h;
 };
 
 size_t part_bytes_G(const gp_dims* d, int64_t E) {
@@ -103,6 +106,13 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, int64_t T, scratch_
   s->dB1 = c.take<float>(rt ? E * S * F : 0);
   s->gc_ji = c.take<float>(rt ? (size_t)T : 0);
   s->eh5 = c.take<float>(d->symmetric ? E * H : 0);
+  const bool hs = half_storage(d);
+  s->W_ba_h = c.take<__bf16>(hs ? H * H : 0);
+  s->W_skip_h = c.take<__bf16>(hs ? H * H : 0);
+  s->W_down_h = c.take<__bf16>(hs ? H * F : 0);
+  s->W_up_h = c.take<__bf16>(hs ? O * H : 0);
+  s->W_bil_h = c.take<__bf16>(hs ? C * F * O : 0);
+  s->WbilP_h = c.take<__bf16>(hs ? C * O * F : 0);
   return c.off;
 }
 
@@ -253,6 +263,23 @@ bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
 // The accumulator A[E, C, F] is stored as bf16 when the matrix-core kernel writes it and bf16 storage is on: its
 // only readers are two bf16-operand GEMMs.  Forward and backward must agree, so the triplet mode of the
 // context must not change between the two calls of a step.
+// bf16 copies of the weights are used when their row lengths allow paired loads
+bool weights_half(const gp_dims* d) { return half_storage(d) && d->int_emb % 2 == 0 && d->emb_bil % 2 == 0; }
+
+int to_half(gp_ctx* ctx, const float* in, __bf16* out, int64_t n) {
+  gp_prof_scope prof(ctx, "to_half", 0.0, 6.0 * (double)n);
+  to_half_kernel<<<(unsigned)((n / 4 + 256) / 256), 256, 0, ctx->stream>>>(in, out, n);
+  GP_LAUNCH_CHECK(ctx, "to_half_kernel");
+  return GP_OK;
+}
+// the weight as a GEMM operand: its bf16 copy (made here) or the fp32 original
+const float* weight_operand(gp_ctx* ctx, bool half, const float* W, __bf16* W_h, int64_t n, int* rc) {
+  if (!half) return W;
+  const int r = to_half(ctx, W, W_h, n);
+  if (r != GP_OK) *rc = r;
+  return reinterpret_cast<const float*>(W_h);
+}
+
 bool a_half(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
   return half_storage(d) && (d->emb_cbf * d->int_emb) % 8 == 0 && want_trip_mfma(ctx, d, g) &&
          gp_tripG_mfma_usable(g, d->int_emb, d->num_spherical, d->emb_cbf);
@@ -310,16 +337,21 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   GP_TRY(gp_gemm_nn(ctx, g, s.Wrbf, E, H, R, e));                                   // gate
   const float* m_op = m_in;   // the input messages as a GEMM operand
   if (hs) {
-    gp_prof_scope prof(ctx, "to_half", 0.0, 6.0 * (double)E * H);
-    to_half_kernel<<<(unsigned)(((int64_t)E * H / 4 + 256) / 256), 256, 0, ctx->stream>>>(m_in, s.m_h, (int64_t)E * H);
-    GP_LAUNCH_CHECK(ctx, "to_half_kernel");
+    GP_TRY(to_half(ctx, m_in, s.m_h, (int64_t)E * H));
     m_op = reinterpret_cast<const float*>(s.m_h);
   }
+  const bool wh = weights_half(dims);
+  int rc = GP_OK;
+  const float* W_ba = weight_operand(ctx, wh, w->W_ba, sc.W_ba_h, (int64_t)H * H, &rc);
+  const float* W_skip = weight_operand(ctx, wh, w->W_skip, sc.W_skip_h, (int64_t)H * H, &rc);
+  const float* W_down = weight_operand(ctx, wh, w->W_down, sc.W_down_h, (int64_t)H * F, &rc);
+  const float* W_bil = weight_operand(ctx, wh && ah, w->W_bil, sc.W_bil_h, (int64_t)C * F * O, &rc);
+  GP_TRY(rc);
   e = gp_epilogue(); e.save_pre = s.z_ba; e.act = 1; e.mul = s.gate; e.out = s.xg;
   e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_MUL | EPI_BF_OUT) : 0u;
-  GP_TRY(gp_gemm_nn(ctx, m_op, w->W_ba, E, H, H, e, hs));                           // xg
+  GP_TRY(gp_gemm_nn(ctx, m_op, W_ba, E, H, H, e, hs, wh));                          // xg
   e = gp_epilogue(); e.save_pre = s.z_dn; e.act = 1; e.out = s.x;
-  GP_TRY(gp_gemm_nn(ctx, s.xg, w->W_down, E, F, H, e, hs));                         // x
+  GP_TRY(gp_gemm_nn(ctx, s.xg, W_down, E, F, H, e, hs, wh));                        // x
   GP_TRY(gp_permute3(ctx, w->W_c, S, R, C, 0, 2, 1, s.WcT));                        // WcT[(l,c), n]
   e = gp_epilogue(); e.out = s.Radt;
   GP_TRY(gp_gemm_nt(ctx, s.WcT, g, S * C, (int)E, R, e));                           // Radt[(l,c), e]
@@ -334,10 +366,10 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
   e = gp_epilogue(); e.out = s.z;
-  GP_TRY(gp_gemm_nn(ctx, s.A, w->W_bil, E, O, C * F, e, ah));                       // z
+  GP_TRY(gp_gemm_nn(ctx, s.A, W_bil, E, O, C * F, e, ah, wh && ah));                // z
   float* t_skip = sc.eh[0];
   e = gp_epilogue(); e.save_pre = s.z_skip; e.act = 1; e.out = t_skip; e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_OUT) : 0u;
-  GP_TRY(gp_gemm_nn(ctx, m_op, w->W_skip, E, H, H, e, hs));
+  GP_TRY(gp_gemm_nn(ctx, m_op, W_skip, E, H, H, e, hs, wh));
   if (dims->symmetric) {
     // m' = (t_skip + (act(z W_up) + act(z W_up_ac)[id_swap]) / sqrt(2)) / sqrt(2) = (act(z W_up) + t) / 2,
     // t = sqrt(2) t_skip + act(z W_up_ac)[id_swap]
@@ -384,6 +416,12 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   float *d_up = sc.eh[0], *d_skip = sc.eh[1], *dxg = sc.eh[2], *dgate = sc.eh[3];
   gp_epilogue e;
 
+  const bool wh = weights_half(dims);
+  int rc = GP_OK;
+  const float* W_up = weight_operand(ctx, wh, w->W_up, sc.W_up_h, (int64_t)O * H, &rc);
+  const float* W_skip = weight_operand(ctx, wh, w->W_skip, sc.W_skip_h, (int64_t)H * H, &rc);
+  const float* W_ba = weight_operand(ctx, wh, w->W_ba, sc.W_ba_h, (int64_t)H * H, &rc);
+  GP_TRY(rc);
   gp_aux aux(ctx);   // the large weight-gradient GEMMs run on the side stream
   if (dims->symmetric) {
     GP_REQUIRE(ctx, graph->id_swap, "gp_block_backward_G: graph->id_swap is needed by a symmetric block");
@@ -404,11 +442,11 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.z, d_up, E, O, H, gw->W_up, nullptr, sc.part_aux, sc.part_bytes, 0, hs); }, {d_up}));
   e = gp_epilogue(); e.out = sc.dz;
   if (dims->symmetric) e.add_post = sc.dz;
-  GP_TRY(gp_gemm_nt(ctx, d_up, w->W_up, E, O, H, e, hs));                           // dz
+  GP_TRY(gp_gemm_nt(ctx, d_up, W_up, E, O, H, e, hs, wh));                          // dz
   const float* m_op = hs ? reinterpret_cast<const float*>(s.m_h) : m_in;   // rounded copy written by the forward pass
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_op, d_skip, E, H, H, gw->W_skip, nullptr, sc.part_aux, sc.part_bytes, hs, hs); }, {}));
   e = gp_epilogue(); e.out = grad_m_in;
-  GP_TRY(gp_gemm_nt(ctx, d_skip, w->W_skip, E, H, H, e, hs));                       // dm (skip path)
+  GP_TRY(gp_gemm_nt(ctx, d_skip, W_skip, E, H, H, e, hs, wh));                      // dm (skip path)
   const bool ah = a_half(ctx, dims, graph);
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part_aux, sc.part_bytes, ah, 0); }, {}));
   if (dims->radial_at_target) {
@@ -442,7 +480,9 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(gp_tripG_edge_G(ctx, s.Radt, sc.Hd, E, S, C, O, sc.Gm, hs));               // G[e', (c,o)] (bf16 with hs)
   GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                   // [(c,o), f]
   e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
-  GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e, hs));                     // dz_dn
+  const float* WbilP = weight_operand(ctx, wh, sc.WbilP, sc.WbilP_h, (int64_t)C * O * F, &rc);
+  GP_TRY(rc);
+  GP_TRY(gp_gemm_nn(ctx, sc.Gm, WbilP, E, F, C * O, e, hs, wh));                    // dz_dn
   GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));                   // [f, (c,o)]
   e = gp_epilogue(); e.out = sc.V;
   GP_TRY(gp_gemm_nn(ctx, s.x, sc.WbilV, E, C * O, F, e));                           // V[e', (c,o)]
@@ -475,7 +515,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(gp_gemm_tn(ctx, w->W_rbfS, sc.dWrbf, R, RB, H, gw->W_rbfB, nullptr, sc.part, sc.part_bytes));
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_op, dz_ba, E, H, H, gw->W_ba, nullptr, sc.part_aux, sc.part_bytes, hs, hs); }, {}));
   e = gp_epilogue(); e.add_post = grad_m_in; e.out = grad_m_in;
-  GP_TRY(gp_gemm_nt(ctx, dz_ba, w->W_ba, E, H, H, e, hs));                          // dm += ba path
+  GP_TRY(gp_gemm_nt(ctx, dz_ba, W_ba, E, H, H, e, hs, wh));                         // dm += ba path
   if (grad_rbf) {
     // dL/dg = dgate W_rbf^T + dRad . W_c  (both paths through the Gaussian basis)
     e = gp_epilogue(); e.out = grad_rbf;

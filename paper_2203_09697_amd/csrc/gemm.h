@@ -28,9 +28,11 @@ enum : unsigned {
 
 // C = A[M,K] @ B[K,N]
 // a_bf16 (bf16-operand kernels only): A addresses bf16 elements instead of fp32
-int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16 = 0);
+int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16 = 0,
+               int b_bf16 = 0);
 // C = A[M,K] @ Bt[N,K]^T
-int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16 = 0);
+int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16 = 0,
+               int b_bf16 = 0);
 // out[M,N] = A[rows,M]^T @ B[rows,N]; deterministic two-stage reduction through `part`.
 // If colsum_out != NULL it also receives colsum_out[n] = sum_r B[r,n] (the bias gradient).
 size_t gp_gemm_tn_scratch(int64_t rows, int M, int N);

@@ -457,29 +457,33 @@ tn_plan_t tn_plan(int64_t rows, int M, int N) {
 
 }  // namespace
 
-int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16) {
+int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16,
+               int b_bf16) {
   GP_REQUIRE(ctx, A && B && M >= 0 && N > 0 && K > 0, "gemm_nn: bad arguments");
   GP_TRY(check_epi(ctx, epi));
   if (M == 0) return GP_OK;
   gemm_args g{};
   g.A = A; g.B = B; g.M = M; g.N = N; g.K = K; g.lda = K; g.ldb = N;
   g.a_bf16 = a_bf16;
+  g.b_bf16 = b_bf16;
   g.vecA = (K % (a_bf16 ? 8 : 4) == 0) && aligned16(A);
-  g.vecB = (N % 4 == 0) && aligned16(B);
+  g.vecB = b_bf16 ? (N % 2 == 0 && ((uintptr_t)B & 3) == 0) : (N % 4 == 0) && aligned16(B);
   g.epi = epi;
   g.vecC = epi_vec_ok(epi, N);
   return dispatch_gemm<MODE_NN>(ctx, g, 1);
 }
 
-int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16) {
+int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16,
+               int b_bf16) {
   GP_REQUIRE(ctx, A && Bt && M >= 0 && N > 0 && K > 0, "gemm_nt: bad arguments");
   GP_TRY(check_epi(ctx, epi));
   if (M == 0) return GP_OK;
   gemm_args g{};
   g.A = A; g.B = Bt; g.M = M; g.N = N; g.K = K; g.lda = K; g.ldb = K;
   g.a_bf16 = a_bf16;
+  g.b_bf16 = b_bf16;
   g.vecA = (K % (a_bf16 ? 8 : 4) == 0) && aligned16(A);
-  g.vecB = (K % 4 == 0) && aligned16(Bt);
+  g.vecB = (K % (b_bf16 ? 8 : 4) == 0) && aligned16(Bt);
   g.epi = epi;
   g.vecC = epi_vec_ok(epi, N);
   return dispatch_gemm<MODE_NT>(ctx, g, 1);

@@ -343,14 +343,16 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE, bool VEC, bool ABF
 __global__ void __launch_bounds__(THREADS, 2)   // two wavefronts per SIMD: 256 registers each
 gemm_bf16_kernel(const gemm_args g) {
   static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
-  static_assert(!BBF || MODE == MODE_TN, "the second operand is an activation only in the weight-gradient form");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MB = WM / 32, NB = WN / 32;
   using loadA32 = typename std::conditional<MODE != MODE_TN, bl_kcontig<BM, VEC>, bl_xcontig<BM, VEC>>::type;
   using loadA16 = typename std::conditional<MODE != MODE_TN, bl_kcontig_bf<BM>, bl_xcontig_bf<BM>>::type;
   using loadB32 = typename std::conditional<MODE == MODE_NT, bl_kcontig<BN, VEC>, bl_xcontig<BN, VEC>>::type;
   using loadA = typename std::conditional<ABF, loadA16, loadA32>::type;
-  using loadB = typename std::conditional<BBF, bl_xcontig_bf<BN>, loadB32>::type;
+  using loadB16 = typename std::conditional<MODE == MODE_NT, bl_kcontig_bf<BN>, bl_xcontig_bf<BN>>::type;
+  using loadB = typename std::conditional<BBF, loadB16, loadB32>::type;
+  // both operands bf16: a slab is 6 registers of loads per thread, so two slabs are kept in flight
+  constexpr bool DEEP = ABF && BBF;
   extern __shared__ __attribute__((aligned(16))) float smem[];
   __bf16* As = reinterpret_cast<__bf16*>(smem);
   __bf16* Bs = As + BM * LDK;
@@ -380,10 +382,14 @@ gemm_bf16_kernel(const gemm_args g) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   if (k_begin < k_end) {
-    loadA la;
-    loadB lb;
+    loadA la, la2;
+    loadB lb, lb2;
     la.init(g.A, g.lda, m0, g.M);
     lb.init(g.B, g.ldb, n0, g.N);
+    if (DEEP) {
+      la2.init(g.A, g.lda, m0, g.M);
+      lb2.init(g.B, g.ldb, n0, g.N);
+    }
     auto multiply = [&]() {
 #pragma unroll
       for (int kk = 0; kk < BKH; kk += 16) {
@@ -401,7 +407,48 @@ gemm_bf16_kernel(const gemm_args g) {
     };
     // complete slabs, software-pipelined: the loads of slab s+1 are in flight while slab s is multiplied
     const int64_t n_full = (k_end - k_begin) / BKH;
-    if (n_full > 0) {
+    if (DEEP && n_full > 0) {
+      // register set 1 (la, lb) and set 2 (la2, lb2) alternate: while slab s is multiplied, slab s+1 sits in
+      // one set and the loads of slab s+2 are issued into the other
+      auto at = [&](int64_t s) { return k_begin + s * BKH; };
+      la.fetch_full(at(0));
+      lb.fetch_full(at(0));
+      if (n_full > 1) {
+        la2.fetch_full(at(1));
+        lb2.fetch_full(at(1));
+      }
+      la.store(As, false);
+      lb.store(Bs, false);
+      __syncthreads();
+      int64_t s = 0;
+      for (; s + 2 < n_full; s += 2) {
+        la.fetch_full(at(s + 2));
+        lb.fetch_full(at(s + 2));
+        multiply();               // slab s
+        __syncthreads();
+        la2.store(As, false);     // slab s+1
+        lb2.store(Bs, false);
+        __syncthreads();
+        if (s + 3 < n_full) {
+          la2.fetch_full(at(s + 3));
+          lb2.fetch_full(at(s + 3));
+        }
+        multiply();               // slab s+1
+        __syncthreads();
+        la.store(As, false);      // slab s+2
+        lb.store(Bs, false);
+        __syncthreads();
+      }
+      multiply();                 // slab s
+      __syncthreads();
+      if (s + 1 < n_full) {
+        la2.store(As, false);
+        lb2.store(Bs, false);
+        __syncthreads();
+        multiply();               // slab s+1
+        __syncthreads();
+      }
+    } else if (n_full > 0) {
       la.fetch_full(k_begin);
       lb.fetch_full(k_begin);
       la.store(As, false);
@@ -495,17 +542,16 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
   // describes the remaining fp32 operand
   if ((g.a_bf16 && !g.vecA) || (g.b_bf16 && !g.vecB))
     return gp_fail(ctx, GP_BAD_ARG, "gemm (bf16 storage): operand not aligned / extent not a multiple of 8");
-  if (g.b_bf16 && MODE != MODE_TN) return gp_fail(ctx, GP_BAD_ARG, "gemm (bf16 storage): only the weight-gradient form takes a bf16 second operand");
 #define GP_BF16_LAUNCH(BM, BN, WMS, WNS)                                                                            \
   do {                                                                                                              \
-    if (g.a_bf16 && g.b_bf16) return launch_v<BM, BN, WMS, WNS, MODE, true, true, MODE == MODE_TN>(ctx, g, splits); \
+    if (g.a_bf16 && g.b_bf16) return launch_v<BM, BN, WMS, WNS, MODE, true, true, true>(ctx, g, splits);               \
     if (g.a_bf16) {                                                                                                 \
       if (g.vecB) return launch_v<BM, BN, WMS, WNS, MODE, true, true, false>(ctx, g, splits);                       \
       return launch_v<BM, BN, WMS, WNS, MODE, false, true, false>(ctx, g, splits);                                  \
     }                                                                                                               \
     if (g.b_bf16) {                                                                                                 \
-      if (g.vecA) return launch_v<BM, BN, WMS, WNS, MODE, true, false, MODE == MODE_TN>(ctx, g, splits);            \
-      return launch_v<BM, BN, WMS, WNS, MODE, false, false, MODE == MODE_TN>(ctx, g, splits);                       \
+      if (g.vecA) return launch_v<BM, BN, WMS, WNS, MODE, true, false, true>(ctx, g, splits);                       \
+      return launch_v<BM, BN, WMS, WNS, MODE, false, false, true>(ctx, g, splits);                                  \
     }                                                                                                               \
     if (g.vecA && g.vecB) return launch_v<BM, BN, WMS, WNS, MODE, true>(ctx, g, splits);                            \
     return launch_v<BM, BN, WMS, WNS, MODE, false>(ctx, g, splits);                                                 \
