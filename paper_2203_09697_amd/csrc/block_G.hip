@@ -223,6 +223,21 @@ __global__ void gate_bwd_half_kernel(const __bf16* __restrict__ dxg, const __bf1
 }
 
 // out = bf16(in), 4 elements per thread
+// out[c, r] = bf16(in[r, c]), in [rows, cols] (weights only: at most a few million elements)
+__global__ void to_half_T_kernel(const float* __restrict__ in, __bf16* __restrict__ out, int rows, int cols) {
+  __shared__ float t[32][33];
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+  for (int i = threadIdx.y; i < 32; i += 8) {
+    const int r = r0 + i, c = c0 + threadIdx.x;
+    t[i][threadIdx.x] = (r < rows && c < cols) ? in[(int64_t)r * cols + c] : 0.f;
+  }
+  __syncthreads();
+  for (int i = threadIdx.y; i < 32; i += 8) {
+    const int c = c0 + i, r = r0 + threadIdx.x;
+    if (c < cols && r < rows) out[(int64_t)c * rows + r] = (__bf16)t[threadIdx.x][i];
+  }
+}
+
 __global__ void to_half_kernel(const float* __restrict__ in, __bf16* __restrict__ out, int64_t n) {
   const int64_t i = 4 * ((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
   if (i >= n) return;
@@ -270,6 +285,12 @@ int to_half(gp_ctx* ctx, const float* in, __bf16* out, int64_t n) {
   gp_prof_scope prof(ctx, "to_half", 0.0, 6.0 * (double)n);
   to_half_kernel<<<(unsigned)((n / 4 + 256) / 256), 256, 0, ctx->stream>>>(in, out, n);
   GP_LAUNCH_CHECK(ctx, "to_half_kernel");
+  return GP_OK;
+}
+int to_half_T(gp_ctx* ctx, const float* in, __bf16* out, int rows, int cols) {
+  gp_prof_scope prof(ctx, "to_half", 0.0, 6.0 * (double)rows * cols);
+  to_half_T_kernel<<<dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, ctx->stream>>>(in, out, rows, cols);
+  GP_LAUNCH_CHECK(ctx, "to_half_T_kernel");
   return GP_OK;
 }
 // the weight as a GEMM operand: its bf16 copy (made here) or the fp32 original
@@ -342,14 +363,21 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   }
   const bool wh = weights_half(dims);
   int rc = GP_OK;
-  const float* W_ba = weight_operand(ctx, wh, w->W_ba, sc.W_ba_h, (int64_t)H * H, &rc);
-  const float* W_skip = weight_operand(ctx, wh, w->W_skip, sc.W_skip_h, (int64_t)H * H, &rc);
+  // the two H x H weights as transposed bf16 copies: activations times a [N, K] weight is the form the
+  // global->LDS GEMM kernel takes
+  if (wh) {
+    GP_TRY(to_half_T(ctx, w->W_ba, sc.W_ba_h, H, H));
+    GP_TRY(to_half_T(ctx, w->W_skip, sc.W_skip_h, H, H));
+  }
+  const float* W_ba_T = reinterpret_cast<const float*>(sc.W_ba_h);
+  const float* W_skip_T = reinterpret_cast<const float*>(sc.W_skip_h);
   const float* W_down = weight_operand(ctx, wh, w->W_down, sc.W_down_h, (int64_t)H * F, &rc);
   const float* W_bil = weight_operand(ctx, wh && ah, w->W_bil, sc.W_bil_h, (int64_t)C * F * O, &rc);
   GP_TRY(rc);
   e = gp_epilogue(); e.save_pre = s.z_ba; e.act = 1; e.mul = s.gate; e.out = s.xg;
   e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_MUL | EPI_BF_OUT) : 0u;
-  GP_TRY(gp_gemm_nn(ctx, m_op, W_ba, E, H, H, e, hs, wh));                          // xg
+  if (wh) GP_TRY(gp_gemm_nt(ctx, m_op, W_ba_T, E, H, H, e, 1, 1));                  // xg
+  else GP_TRY(gp_gemm_nn(ctx, m_op, w->W_ba, E, H, H, e, hs));
   e = gp_epilogue(); e.save_pre = s.z_dn; e.act = 1; e.out = s.x;
   GP_TRY(gp_gemm_nn(ctx, s.xg, W_down, E, F, H, e, hs, wh));                        // x
   GP_TRY(gp_permute3(ctx, w->W_c, S, R, C, 0, 2, 1, s.WcT));                        // WcT[(l,c), n]
@@ -369,7 +397,8 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   GP_TRY(gp_gemm_nn(ctx, s.A, W_bil, E, O, C * F, e, ah, wh && ah));                // z
   float* t_skip = sc.eh[0];
   e = gp_epilogue(); e.save_pre = s.z_skip; e.act = 1; e.out = t_skip; e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_OUT) : 0u;
-  GP_TRY(gp_gemm_nn(ctx, m_op, W_skip, E, H, H, e, hs, wh));
+  if (wh) GP_TRY(gp_gemm_nt(ctx, m_op, W_skip_T, E, H, H, e, 1, 1));
+  else GP_TRY(gp_gemm_nn(ctx, m_op, w->W_skip, E, H, H, e, hs));
   if (dims->symmetric) {
     // m' = (t_skip + (act(z W_up) + act(z W_up_ac)[id_swap]) / sqrt(2)) / sqrt(2) = (act(z W_up) + t) / 2,
     // t = sqrt(2) t_skip + act(z W_up_ac)[id_swap]

@@ -1,25 +1,29 @@
-// GEMM with bf16 operands and fp32 accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16),
-// for the wide edge layers of the bilinear block (paper Sec. 3.4; Table 4 widths).  Matrices
-// stay fp32 in HBM; operands are rounded to bf16 (round-to-nearest-even) on their way into LDS,
-// the fused epilogue and all outputs are fp32.
+// GEMM with bf16 operands and fp32 accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16), for the wide
+// edge layers of the bilinear block (paper Sec. 3.4; Table 4 widths).  An operand is either an fp32 matrix that
+// is rounded to bf16 (round-to-nearest-even) on its way into LDS, or a matrix already stored as bf16 by a
+// producer's epilogue; outputs and the matrices the fused epilogue reads are fp32 or bf16 per a mask.
 //
-// LDS tiles are As[m][k], Bs[n][k] with k contiguous (rows padded to 80 bytes), so the 8
-// consecutive k that one lane feeds to an MFMA are a single 16-byte read.  A 256-thread
-// workgroup owns a BM x BN tile (256x128 for tall matrices), each wavefront 32x32 blocks of it;
-// K advances 32 per slab, global loads for the next slab are issued before the current one is
-// multiplied.
+// Three kernels:
+//  * gemm_bf16_kernel: any mix of operand storage, any shape.  LDS tiles As[m][k], Bs[n][k] with k contiguous
+//    (rows padded to 80 bytes), so the 8 consecutive k one lane feeds to an MFMA are a single 16-byte read.  A
+//    256-thread workgroup owns a BM x BN tile, each wavefront 32x32 blocks of it; K advances 32 per slab, the
+//    global loads of the next slab are issued before the current one is multiplied.
+//  * gemm_hh_kernel: both operands bf16.  Two slabs of loads in flight in registers, two LDS buffers and one
+//    barrier per slab, operand fragments of the next MFMA group requested before the current group is issued.
+//  * gemm_dl_kernel: C = A B^T, both operands bf16 and k-contiguous, tall A: tiles go from global memory
+//    straight into LDS (see the comment at the kernel).
 //
-// One MFMA of this shape does 32768 flop in 32 cycles, so the loop around it has to stay within a
-// few vector instructions per MFMA.  The loaders therefore keep a uniform base pointer that moves
-// with the slab plus one 32-bit byte offset per item computed once, and full slabs take a path
-// with no bounds arithmetic at all: rows/columns past the edge of the matrix are read from a
-// clamped (valid) address and only influence outputs that are never stored.  Only the last,
-// partial slab of the contraction masks its operands to zero.
+// One MFMA of this shape does 32768 flop in 32 cycles, so the loop around it has to stay within a few vector
+// instructions per MFMA.  The loaders therefore keep a uniform base pointer that moves with the slab plus one
+// 32-bit byte offset per item computed once, and full slabs take a path with no bounds arithmetic at all:
+// rows/columns past the edge of the matrix are read from a clamped (valid) address and only influence outputs
+// that are never stored.  Only the last, partial slab of the contraction masks its operands to zero.
 #include <stdarg.h>
 
 #include <type_traits>
 
 #include "gemm_common.h"
+
 
 namespace {
 
@@ -339,6 +343,45 @@ struct bl_xcontig_bf {
   }
 };
 
+// Epilogue of one workgroup tile: accumulators have the register layout of the 32x32 MFMA and are transposed
+// through a per-wavefront LDS slice so that loads and stores are 16-byte accesses.
+template <int MB, int NB, int MODE>
+__device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[MB][NB], float* smem, int64_t m0, int n0,
+                                              int wm0, int wn0, int split) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kh = lane >> 5, l32 = lane & 31;
+  float* stage = smem + wave * (32 * EPI_LD);
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD + l32] = acc[i][j][v];
+      wave_lds_sync();
+#pragma unroll 1   // the typed epilogue is long; unrolled 4 x MB x NB times it would not fit the register file
+      for (int it = 0; it < 4; ++it) {
+        const int r = it * 8 + (lane >> 3), c4 = (lane & 7) * 4;
+        const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[r * EPI_LD + c4]);
+        const int64_t row = m0 + wm0 + i * 32 + r;
+        const int col = n0 + wn0 + j * 32 + c4;
+        if (row >= g.M || col >= g.N) continue;
+        if (MODE == MODE_TN) {
+          float* dst = g.part + ((int64_t)split * g.M + row) * g.N + col;
+          if (g.vecC) *reinterpret_cast<f32x4*>(dst) = v4;
+          else
+            for (int c = 0; c < 4; ++c)
+              if (col + c < g.N) dst[c] = v4[c];
+        } else {
+          if (g.vecC) epilogue_store4(g.epi, row, col, g.N, v4);
+          else
+            for (int c = 0; c < 4; ++c)
+              if (col + c < g.N) epilogue_store(g.epi, row, col + c, g.N, v4[c]);
+        }
+      }
+      wave_lds_sync();
+    }
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE, bool VEC, bool ABF, bool BBF>
 __global__ void __launch_bounds__(THREADS, 2)   // two wavefronts per SIMD: 256 registers each
 gemm_bf16_kernel(const gemm_args g) {
@@ -351,8 +394,6 @@ gemm_bf16_kernel(const gemm_args g) {
   using loadA = typename std::conditional<ABF, loadA16, loadA32>::type;
   using loadB16 = typename std::conditional<MODE == MODE_NT, bl_kcontig_bf<BN>, bl_xcontig_bf<BN>>::type;
   using loadB = typename std::conditional<BBF, loadB16, loadB32>::type;
-  // both operands bf16: a slab is 6 registers of loads per thread, so two slabs are kept in flight
-  constexpr bool DEEP = ABF && BBF;
   extern __shared__ __attribute__((aligned(16))) float smem[];
   __bf16* As = reinterpret_cast<__bf16*>(smem);
   __bf16* Bs = As + BM * LDK;
@@ -382,14 +423,10 @@ gemm_bf16_kernel(const gemm_args g) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   if (k_begin < k_end) {
-    loadA la, la2;
-    loadB lb, lb2;
+    loadA la;
+    loadB lb;
     la.init(g.A, g.lda, m0, g.M);
     lb.init(g.B, g.ldb, n0, g.N);
-    if (DEEP) {
-      la2.init(g.A, g.lda, m0, g.M);
-      lb2.init(g.B, g.ldb, n0, g.N);
-    }
     auto multiply = [&]() {
 #pragma unroll
       for (int kk = 0; kk < BKH; kk += 16) {
@@ -407,48 +444,7 @@ gemm_bf16_kernel(const gemm_args g) {
     };
     // complete slabs, software-pipelined: the loads of slab s+1 are in flight while slab s is multiplied
     const int64_t n_full = (k_end - k_begin) / BKH;
-    if (DEEP && n_full > 0) {
-      // register set 1 (la, lb) and set 2 (la2, lb2) alternate: while slab s is multiplied, slab s+1 sits in
-      // one set and the loads of slab s+2 are issued into the other
-      auto at = [&](int64_t s) { return k_begin + s * BKH; };
-      la.fetch_full(at(0));
-      lb.fetch_full(at(0));
-      if (n_full > 1) {
-        la2.fetch_full(at(1));
-        lb2.fetch_full(at(1));
-      }
-      la.store(As, false);
-      lb.store(Bs, false);
-      __syncthreads();
-      int64_t s = 0;
-      for (; s + 2 < n_full; s += 2) {
-        la.fetch_full(at(s + 2));
-        lb.fetch_full(at(s + 2));
-        multiply();               // slab s
-        __syncthreads();
-        la2.store(As, false);     // slab s+1
-        lb2.store(Bs, false);
-        __syncthreads();
-        if (s + 3 < n_full) {
-          la2.fetch_full(at(s + 3));
-          lb2.fetch_full(at(s + 3));
-        }
-        multiply();               // slab s+1
-        __syncthreads();
-        la.store(As, false);      // slab s+2
-        lb.store(Bs, false);
-        __syncthreads();
-      }
-      multiply();                 // slab s
-      __syncthreads();
-      if (s + 1 < n_full) {
-        la2.store(As, false);
-        lb2.store(Bs, false);
-        __syncthreads();
-        multiply();               // slab s+1
-        __syncthreads();
-      }
-    } else if (n_full > 0) {
+    if (n_full > 0) {
       la.fetch_full(k_begin);
       lb.fetch_full(k_begin);
       la.store(As, false);
@@ -479,38 +475,328 @@ gemm_bf16_kernel(const gemm_args g) {
     }
   }
 
-  // epilogue: same register layout as the fp32 32x32 MFMA; transposed through a per-wavefront
-  // LDS slice so that loads and stores are 16-byte accesses
-  float* stage = smem + wave * (32 * EPI_LD);
+  tile_epilogue<MB, NB, MODE>(g, acc, smem, m0, n0, wm0, wn0, blockIdx.y);
+}
+
+// Both operands stored as bf16.  A slab is then only 6 sixteen-byte loads per thread, so NS slabs are kept in
+// flight in registers (memory latency under load is several slab times), LDS holds two slabs so that one
+// barrier per slab suffices: while slab t is multiplied out of one buffer, slab t+1 is written to the other.
+// Register sets and buffers rotate statically (the loop is unrolled over one full rotation); loads past the
+// last full slab re-read that slab (in bounds, never used).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
+__global__ void __launch_bounds__(THREADS, 2)
+gemm_hh_kernel(const gemm_args g) {
+  static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int MB = WM / 32, NB = WN / 32;
+  using loadA = typename std::conditional<MODE != MODE_TN, bl_kcontig_bf<BM>, bl_xcontig_bf<BM>>::type;
+  using loadB = typename std::conditional<MODE == MODE_NT, bl_kcontig_bf<BN>, bl_xcontig_bf<BN>>::type;
+  constexpr int STAGE = (BM + BN) * LDK;           // bf16 elements per LDS buffer
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  __bf16* S = reinterpret_cast<__bf16*>(smem);
+
+  const int tiles_n = (g.N + BN - 1) / BN;
+  const int tiles_m = (int)((g.M + BM - 1) / BM);
+  // one-dimensional grid over (split, tile), split-major: each XCD gets a contiguous range, so the tiles of one
+  // split (which all read the same rows of both operands) run side by side on one XCD and share its L2
+  const int work = xcd_remap(blockIdx.x, gridDim.x);
+  const int split = work / (tiles_m * tiles_n);
+  const int tile = work % (tiles_m * tiles_n);
+  const int64_t m0 = (int64_t)(tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
+  int64_t k_begin = 0, k_end = g.K;
+  if (MODE == MODE_TN) {
+    k_begin = (int64_t)split * g.k_per_split;
+    k_end = k_begin + g.k_per_split < (int64_t)g.K ? k_begin + g.k_per_split : (int64_t)g.K;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int kh = lane >> 5, l32 = lane & 31;
+
+  f32x16 acc[MB][NB];
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
+    for (int j = 0; j < NB; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD + l32] = acc[i][j][v];
-      wave_lds_sync();
-#pragma unroll 1   // the typed epilogue is long; unrolled 4 x MB x NB times it would not fit the register file
-      for (int it = 0; it < 4; ++it) {
-        const int r = it * 8 + (lane >> 3), c4 = (lane & 7) * 4;
-        const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[r * EPI_LD + c4]);
-        const int64_t row = m0 + wm0 + i * 32 + r;
-        const int col = n0 + wn0 + j * 32 + c4;
-        if (row >= g.M || col >= g.N) continue;
-        if (MODE == MODE_TN) {
-          float* dst = g.part + ((int64_t)blockIdx.y * g.M + row) * g.N + col;
-          if (g.vecC) *reinterpret_cast<f32x4*>(dst) = v4;
-          else
-            for (int c = 0; c < 4; ++c)
-              if (col + c < g.N) dst[c] = v4[c];
-        } else {
-          if (g.vecC) epilogue_store4(g.epi, row, col, g.N, v4);
-          else
-            for (int c = 0; c < 4; ++c)
-              if (col + c < g.N) epilogue_store(g.epi, row, col + c, g.N, v4[c]);
-        }
-      }
-      wave_lds_sync();
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  if (k_begin < k_end) {
+    static_assert(BKH == 32, "the schedule below is written for two MFMA steps per slab");
+    loadA la[2];
+    loadB lb[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      la[u].init(g.A, g.lda, m0, g.M);
+      lb[u].init(g.B, g.ldb, n0, g.N);
     }
+    bf16x8 fa[2][MB], fb[2][NB];   // operand fragments of the two MFMA steps
+    auto read_frags = [&](const __bf16* __restrict__ As, int kk, int q) __attribute__((always_inline)) {
+      const __bf16* Bs = As + BM * LDK;
+#pragma unroll
+      for (int i = 0; i < MB; ++i) fa[q][i] = *reinterpret_cast<const bf16x8*>(&As[(wm0 + i * 32 + l32) * LDK + kk + kh * 8]);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) fb[q][j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn0 + j * 32 + l32) * LDK + kk + kh * 8]);
+    };
+    auto mfma_group = [&](int q) __attribute__((always_inline)) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[q][i], fb[q][j], acc[i][j], 0, 0, 0);
+    };
+    const int64_t n_full = (k_end - k_begin) / BKH;
+    if (n_full > 0) {
+      auto at = [&](int64_t s) { return k_begin + (s < n_full ? s : n_full - 1) * BKH; };
+      la[0].fetch_full(at(0));
+      lb[0].fetch_full(at(0));
+      la[1].fetch_full(at(1));
+      lb[1].fetch_full(at(1));
+      __builtin_amdgcn_sched_barrier(0);   // keep the issue order of the loads the same as in the loop
+      la[0].store(S, false);
+      lb[0].store(S + BM * LDK, false);
+      la[0].fetch_full(at(2));
+      lb[0].fetch_full(at(2));
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+      read_frags(S, 0, 0);
+      // Slab t is multiplied in two MFMA groups.  While the first runs, the fragments of the second are already
+      // on their way from LDS, slab t+1 moves from registers to the other LDS buffer and the loads of slab t+3
+      // are issued into the registers it leaves; after the barrier the first fragments of slab t+1 are requested
+      // and the second group runs.  Every LDS or global access thus has one MFMA group (256 cycles) to complete.
+      auto slab = [&](const int u, int64_t t) __attribute__((always_inline)) {
+        const __bf16* cur = S + u * STAGE;
+        __bf16* nxt = S + (1 - u) * STAGE;
+        read_frags(cur, 16, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_group(0);
+        la[1 - u].store(nxt, false);                 // slab t+1
+        lb[1 - u].store(nxt + BM * LDK, false);
+        la[1 - u].fetch_full(at(t + 3));
+        lb[1 - u].fetch_full(at(t + 3));
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        read_frags(nxt, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_group(1);
+      };
+      int64_t t = 0;
+      for (; t + 1 < n_full; t += 2) {   // no exit between the two halves: the wait counts stay exact
+        slab(0, t);
+        slab(1, t + 1);
+      }
+      if (t < n_full) slab(0, t);
+      __syncthreads();   // the fragments requested last are not used; nobody reads LDS past this point
+    }
+    // the partial slab at the end of the contraction, operands masked to zero past k_end
+    const int64_t k_tail = k_begin + n_full * BKH;
+    if (k_tail < k_end) {
+      la[0].fetch_tail(k_tail, k_end);
+      lb[0].fetch_tail(k_tail, k_end);
+      la[0].store(S, true);
+      lb[0].store(S + BM * LDK, true);
+      __syncthreads();
+      read_frags(S, 0, 0);
+      read_frags(S, 16, 1);
+      mfma_group(0);
+      mfma_group(1);
+      __syncthreads();
+    }
+  }
+  tile_epilogue<MB, NB, MODE>(g, acc, smem, m0, n0, wm0, wn0, split);
+}
+
+template <int BM, int BN, int WMS, int WNS, int MODE>
+int launch_hh(gp_ctx* ctx, gemm_args& g, int splits) {
+  const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  if (tiles > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
+  if (g.lda >= MAX_LD || g.ldb >= MAX_LD) return gp_fail(ctx, GP_BAD_ARG, "gemm (bf16): leading dimension above %lld", (long long)MAX_LD);
+  if (tiles * splits > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
+  dim3 grid((unsigned)(tiles * splits), 1, 1);
+  static char name[48];
+  if (!name[0]) snprintf(name, sizeof(name), "gemm_bf16_hh_%s_%dx%d", MODE == MODE_NN ? "nn" : MODE == MODE_NT ? "nt" : "tn", BM, BN);
+  const double mnk = (double)g.M * g.N * g.K;
+  gp_prof_scope prof(ctx, name, 2.0 * mnk,
+                     2.0 * (double)g.M * g.K + 2.0 * (double)g.K * g.N + 4.0 * (double)g.M * g.N * (MODE == MODE_TN ? splits : 1));
+  constexpr size_t lds_main = sizeof(__bf16) * 2 * (size_t)(BM + BN) * LDK;
+  constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD;
+  constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+  static_assert(lds <= 64 * 1024, "two slabs fit the default dynamic LDS limit");
+  gemm_hh_kernel<BM, BN, WMS, WNS, MODE><<<grid, THREADS, lds, ctx->stream>>>(g);
+  GP_LAUNCH_CHECK(ctx, "gemm_hh_kernel");
+  return GP_OK;
+}
+
+// ---- C = A B^T with both operands stored as bf16 and k contiguous (activations times a weight matrix held as
+// [N, K]), K a multiple of the slab depth BK: the tiles go from global memory straight into LDS (16-byte
+// global->LDS loads: no registers, no LDS write instructions in the wavefronts' instruction streams) through a
+// ring of STAGES LDS buffers.
+//
+// What bounds these GEMMs on this chip is the path from L2 into the compute unit, not the matrix cores: a
+// 256x128 tile needs 47 bytes per clock and compute unit at full MFMA rate, and loads whose 64 lanes fetch
+// 64-byte pieces of 16 different rows deliver about a quarter of that.  Hence 256x256 tiles (32 bytes per
+// clock) and slabs of 64 k, so that every row contributes a whole 128-byte line to each load instruction
+// (measured: twice the throughput of half lines).  Eight wavefronts share the tile; each owns 128x64.
+//
+// LDS tile layout: row r (an m or n index) occupies BK*2 bytes = BK/8 groups of 8 consecutive k; group c is
+// stored at position c ^ swz(r) with swz(r) = (r >> 2) & 3 for 64-byte rows and (r >> 1) & 7 for 128-byte
+// rows.  A global->LDS load writes the 64 lanes' 16 bytes to consecutive LDS addresses, so lane l of the load
+// that covers groups [64 j, 64 j + 64) fetches the group that belongs there; the swizzle makes the fragment
+// reads (32 rows x one group per half-wavefront) touch every bank equally.
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+
+// s_waitcnt with vmcnt = N, lgkmcnt = 0 (gfx9 encoding: vmcnt in bits [3:0] and [15:14], expcnt [6:4] = 7: no
+// wait, lgkmcnt [11:8])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_lgkmcnt0() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | ((N >> 4) << 14));
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, WAVES_M * WAVES_N == 8 ? 1 : 2)
+gemm_dl_kernel(const gemm_args g) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD and workgroup");
+  static_assert(BK == 32 || BK == 64, "slab depth");
+  static_assert(STAGES == 2 || STAGES == 3, "ring depth");
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int MB = WM / 32, NB = WN / 32;
+  constexpr int ROWB = BK * 2;                        // bytes per LDS row
+  constexpr int CH = BK / 8;                          // 16-byte groups per row
+  constexpr int KS = BK / 16;                         // MFMA steps per slab
+  constexpr int STAGE_B = (BM + BN) * ROWB;           // bytes per stage
+  constexpr int LOADS = (BM + BN) * CH / 64;          // wavefront-wide 16-byte loads per slab
+  constexpr int PER = LOADS / NW;                     // per wavefront
+  constexpr int A_LOADS = BM * CH / 64;
+  static_assert(LOADS % NW == 0 && PER * (STAGES - 1) < 64, "the loads of a slab are dealt evenly to the wavefronts");
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  char* lds = reinterpret_cast<char*>(smem);
+
+  const int tiles_n = (g.N + BN - 1) / BN;
+  const int tiles_m = (int)((g.M + BM - 1) / BM);
+  const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  const int64_t m0 = (int64_t)(tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int kh = lane >> 5, l32 = lane & 31;
+  auto swz = [](int r) { return BK == 32 ? (r >> 2) & 3 : (r >> 1) & 7; };
+
+  // this lane's source address for each of the wavefront's loads (slab 0); rows past the matrix are clamped
+  const char* src[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int j = wave * PER + i;                     // load index within the slab (uniform)
+    const bool is_a = j < A_LOADS;
+    const int q = (is_a ? j : j - A_LOADS) * 64 + lane;
+    const int row = q / CH, c = (q % CH) ^ swz(row);
+    if (is_a) {
+      const int64_t r = m0 + row < g.M ? m0 + row : g.M - 1;
+      src[i] = reinterpret_cast<const char*>(g.A) + (r * g.lda + c * 8) * 2;
+    } else {
+      const int64_t r = n0 + row < g.N ? n0 + row : g.N - 1;
+      src[i] = reinterpret_cast<const char*>(g.B) + (r * g.ldb + c * 8) * 2;
+    }
+  }
+  const int n_slabs = g.K / BK;
+  auto issue = [&](int slab, int stage) __attribute__((always_inline)) {
+    const int64_t kb = (int64_t)(slab < n_slabs ? slab : n_slabs - 1) * ROWB;   // past the end: re-read the last slab
+    char* dst = lds + stage * STAGE_B + wave * PER * 1024;
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(src[i] + kb), (lds_void_ptr)(dst + i * 1024), 16, 0, 0);
+  };
+
+  f32x16 acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // fragment addresses inside a stage: row base plus, per MFMA step, the swizzled position of the lane's group
+  const int sw = swz(l32);   // rows of a fragment differ from l32 by multiples of 32, which the swizzle ignores
+  const int a_row = (wm0 + l32) * ROWB, b_row = BM * ROWB + (wn0 + l32) * ROWB;
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = ((2 * ks + kh) ^ sw) << 4;
+  bf16x8 fa[2][MB], fb[2][NB];
+  auto read_frags = [&](int stage, int ks) __attribute__((always_inline)) {
+    const char* sa = lds + stage * STAGE_B + a_row + koff[ks];
+    const char* sb = lds + stage * STAGE_B + b_row + koff[ks];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) fa[ks & 1][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * ROWB);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) fb[ks & 1][j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * ROWB);
+  };
+  auto mfma_group = [&](int ks) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+  };
+
+#pragma unroll
+  for (int s = 0; s < STAGES; ++s) issue(s, s);
+  wait_vmcnt_lgkmcnt0<(STAGES - 1) * PER>();   // slab 0 has landed (this wavefront's part)
+  __syncthreads();                             // ... and everybody else's
+  read_frags(0, 0);
+  int st = 0;                                  // stage of slab t
+  for (int t = 0; t < n_slabs; ++t) {
+    const int st1 = st == STAGES - 1 ? 0 : st + 1;
+    // While one MFMA group runs, the fragments of the next are on their way from LDS.  Before the last group
+    // the wavefront holds all it needs from stage st in registers: after the barrier that stage is refilled
+    // with slab t+STAGES, and the first fragments of slab t+1 (landed: each wavefront waited for its own loads
+    // before the barrier) are requested.
+#pragma unroll
+    for (int ks = 0; ks + 1 < KS; ++ks) {
+      read_frags(st, ks + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(ks);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_vmcnt_lgkmcnt0<(STAGES - 2) * PER>();
+    __syncthreads();
+    issue(t + STAGES, st);
+    read_frags(st1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(KS - 1);
+    __builtin_amdgcn_sched_barrier(0);
+    st = st1;
+  }
+  wait_vmcnt_lgkmcnt0<0>();                    // the loads issued past the end must not land in the epilogue's staging area
+  __syncthreads();
+  tile_epilogue<MB, NB, MODE_NT>(g, acc, smem, m0, n0, wm0, wn0, 0);
+}
+
+template <int BM, int BN, int WMS, int WNS, int BK, int STAGES>
+int launch_dl(gp_ctx* ctx, gemm_args& g) {
+  const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  if (tiles > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
+  static char name[48];
+  if (!name[0]) snprintf(name, sizeof(name), "gemm_bf16_dl_nt_%dx%d", BM, BN);
+  const double mnk = (double)g.M * g.N * g.K;
+  gp_prof_scope prof(ctx, name, 2.0 * mnk, 2.0 * (double)g.M * g.K + 2.0 * (double)g.K * g.N + 4.0 * (double)g.M * g.N);
+  constexpr int NW = WMS * WNS;
+  constexpr size_t lds_main = (size_t)STAGES * (BM + BN) * BK * 2;
+  constexpr size_t lds_epi = sizeof(float) * NW * 32 * EPI_LD;
+  constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+  static_assert((NW == 8 ? 1 : 2) * lds <= 160 * 1024, "fits the compute unit's LDS");
+  static bool raised = false;
+  if (!raised && lds > 64 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dl_kernel<BM, BN, WMS, WNS, BK, STAGES>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return gp_fail(ctx, GP_HIP_ERROR, "gemm: cannot raise the dynamic LDS limit to %zu bytes", lds);
+    raised = true;
+  }
+  gemm_dl_kernel<BM, BN, WMS, WNS, BK, STAGES><<<dim3((unsigned)tiles), 64 * NW, lds, ctx->stream>>>(g);
+  GP_LAUNCH_CHECK(ctx, "gemm_dl_kernel");
+  return GP_OK;
 }
 
 template <int BM, int BN, int WMS, int WNS, int MODE, bool VEC, bool ABF = false, bool BBF = false>
@@ -530,10 +816,17 @@ int launch_v(gp_ctx* ctx, gemm_args& g, int splits) {
   constexpr size_t lds_main = sizeof(__bf16) * (size_t)(BM + BN) * LDK;
   constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD;
   constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
-  static_assert(lds <= 48 * 1024, "tile fits the default dynamic LDS limit");
+  static_assert(lds <= 64 * 1024, "tile fits the default dynamic LDS limit");
   gemm_bf16_kernel<BM, BN, WMS, WNS, MODE, VEC, ABF, BBF><<<grid, THREADS, lds, ctx->stream>>>(g);
   GP_LAUNCH_CHECK(ctx, "gemm_bf16_kernel");
   return GP_OK;
+}
+
+// both operands bf16: the register-pipelined kernel needs at least 64 columns per tile
+template <int BM, int BN, int WMS, int WNS, int MODE>
+int launch_both_bf16(gp_ctx* ctx, gemm_args& g, int splits) {
+  if constexpr (BN >= 64) return launch_hh<BM, BN, WMS, WNS, MODE>(ctx, g, splits);
+  else return launch_v<BM, BN, WMS, WNS, MODE, true, true, true>(ctx, g, splits);
 }
 
 template <int MODE>
@@ -544,7 +837,7 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
     return gp_fail(ctx, GP_BAD_ARG, "gemm (bf16 storage): operand not aligned / extent not a multiple of 8");
 #define GP_BF16_LAUNCH(BM, BN, WMS, WNS)                                                                            \
   do {                                                                                                              \
-    if (g.a_bf16 && g.b_bf16) return launch_v<BM, BN, WMS, WNS, MODE, true, true, true>(ctx, g, splits);               \
+    if (g.a_bf16 && g.b_bf16) return launch_both_bf16<BM, BN, WMS, WNS, MODE>(ctx, g, splits);                      \
     if (g.a_bf16) {                                                                                                 \
       if (g.vecB) return launch_v<BM, BN, WMS, WNS, MODE, true, true, false>(ctx, g, splits);                       \
       return launch_v<BM, BN, WMS, WNS, MODE, false, true, false>(ctx, g, splits);                                  \
@@ -556,6 +849,10 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
     if (g.vecA && g.vecB) return launch_v<BM, BN, WMS, WNS, MODE, true>(ctx, g, splits);                            \
     return launch_v<BM, BN, WMS, WNS, MODE, false>(ctx, g, splits);                                                 \
   } while (0)
+  // tall activations times a wide weight matrix, both bf16 and k-contiguous: global->LDS loads, 256x256 tiles
+  if (MODE == MODE_NT && g.a_bf16 && g.b_bf16 && g.M >= 8192 && g.N > 128 && g.K % 64 == 0 && g.K >= 128 &&
+      g.lda % 8 == 0 && g.ldb % 8 == 0)
+    return launch_dl<256, 256, 2, 4, 64, 2>(ctx, g);
   // the reduction over rows (TN) keeps the 128-row tiles its split plan was made for
   if (MODE != MODE_TN && g.M >= 8192 && g.N > 64) GP_BF16_LAUNCH(256, 128, 2, 2);
   if (g.N > 64) GP_BF16_LAUNCH(128, 128, 2, 2);
@@ -574,3 +871,4 @@ int gp_gemm_bf16_launch(gp_ctx* ctx, int mode, void* args, int splits) {
   if (mode == MODE_NT) return dispatch<MODE_NT>(ctx, g, splits);
   return dispatch<MODE_TN>(ctx, g, splits);
 }
+
