@@ -55,7 +55,19 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// The share of one workgroup: centre atom j = blockIdx.x / PARTS, its in-edge rows r0 .. r0+d-1
+// Workgroup ids are dealt round-robin to the 8 XCDs.  Numbering the (atom, part) pairs atom-major and giving
+// each XCD a contiguous range of them keeps every XCD equally busy (with part = id % 8 the XCDs that get the
+// high part numbers, which most atoms do not have, would idle) and runs the parts of one atom, which read the
+// same in-edge rows, side by side on one L2.
+__device__ __forceinline__ void atom_and_part(int& j, int& part) {
+  const int n = (int)gridDim.x, q = n >> 3, r = n & 7;
+  const int x = (int)blockIdx.x & 7, i = (int)blockIdx.x >> 3;
+  const int w = x * q + (x < r ? x : r) + i;
+  j = w / PARTS;
+  part = w % PARTS;
+}
+
+// The share of one workgroup: centre atom j, its in-edge rows r0 .. r0+d-1
 // (Kp = d rounded up to 16) and the slice [eb, ee) of its out-edge list.
 struct part_t {
   int r0, d, Kp, o0, eb, ee;
@@ -64,7 +76,8 @@ struct part_t {
 // false (for every thread of the workgroup alike) if this workgroup has nothing to do
 __device__ __forceinline__ bool centre_part(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                                             int kp_cap, part_t& P) {
-  const int j = blockIdx.x / PARTS, part = blockIdx.x % PARTS;
+  int j, part;
+  atom_and_part(j, part);
   P.r0 = row_ptr[j];
   P.d = row_ptr[j + 1] - P.r0;
   P.Kp = (P.d + 15) & ~15;
@@ -95,9 +108,15 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
   __shared__ int s_e[64], s_seg[64], s_cnt[64], s_gap[64];
   const int n_pg = P.Kp / 8;
   const int cp = threadIdx.x & 7;
-  for (int pg0 = 0; pg0 < n_pg; pg0 += (int)(blockDim.x >> 3)) {
-    const int pg = pg0 + (threadIdx.x >> 3);
-    const bool active = pg < n_pg;
+  const int n_slots = (int)(blockDim.x >> 3);   // groups of 8 threads; a group owns 8 positions of all 16 c
+  for (int pg0 = 0; pg0 < n_pg; pg0 += n_slots) {
+    // A pass with fewer position groups left than thread groups splits each position group's edges among
+    // several thread groups (edges e_off, e_off + e_step, ...), so that the last pass keeps the block busy.
+    const int left = n_pg - pg0, slot = threadIdx.x >> 3;
+    const int e_step = left >= n_slots ? 1 : n_slots / left;
+    const int e_off = left >= n_slots ? 0 : slot / left;
+    const int pg = pg0 + (left >= n_slots ? slot : slot % left);
+    const bool active = e_off < e_step;
     float rad[SM][2][8];
 #pragma unroll
     for (int l = 0; l < SM; ++l)
@@ -146,15 +165,16 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
           vmask |= (valid ? 1u : 0u) << pi;
         }
       };
+      if (e_off >= n) continue;
       float cs_next[8];
       unsigned vm_next;
-      load_cos(0, cs_next, vm_next);
-      for (int ei = 0; ei < n; ++ei) {
+      load_cos(e_off, cs_next, vm_next);
+      for (int ei = e_off; ei < n; ei += e_step) {
         float cs[8];
         const unsigned vm = vm_next;
 #pragma unroll
         for (int pi = 0; pi < 8; ++pi) cs[pi] = cs_next[pi];
-        if (ei + 1 < n) load_cos(ei + 1, cs_next, vm_next);   // in flight during the arithmetic below
+        if (ei + e_step < n) load_cos(ei + e_step, cs_next, vm_next);   // in flight during the arithmetic below
         float y[2][8];
 #pragma unroll
         for (int pi = 0; pi < 8; ++pi) {
@@ -333,7 +353,8 @@ constexpr int GPW = 8;   // row groups per workgroup aimed at (two per wavefront
 
 __device__ __forceinline__ bool centre_rows(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                                             rows_t& P) {
-  const int j = blockIdx.x / PARTS, part = blockIdx.x % PARTS;
+  int j, part;
+  atom_and_part(j, part);
   P.r0 = row_ptr[j];
   P.d = row_ptr[j + 1] - P.r0;
   P.o0 = out_ptr[j];
