@@ -95,6 +95,7 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-kernels", action="store_true", help="list every kernel of the step, not only the ten longest")
     ap.add_argument("--radial-at-target", action="store_true",
                     help="variant-G workloads: radial factor of the triplet basis at the target edge")
     ap.add_argument("--symmetric", action="store_true",
@@ -249,7 +250,7 @@ def main():
                    "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed},
         "roofline": roofline,
         "measured_peaks": {k: round(v, 1) for k, v in mp.items()},
-        "kernels": kernels[:10],
+        "kernels": kernels if a.all_kernels else kernels[:10],
         "graph_build_ms": round(graph_ms, 3), "basis_ms": round(basis_ms, 3), "wall_ms_per_step": round(wall_ms / a.steps, 4),
     }
     if not a.no_cpu_baseline:

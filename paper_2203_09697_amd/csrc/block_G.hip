@@ -462,6 +462,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
     e = gp_epilogue(); e.out = sc.dz;
     GP_TRY(gp_gemm_nt(ctx, d_ac, w->W_up_ac, E, O, H, e));                          // dz (opposite-edge path)
   } else if (hs) {
+    gp_prof_scope prof(ctx, "ew_dsilu2_half", 0.0, 12.0 * (double)EH);   // fp32 gradient + 4 bf16 arrays
     dsilu2_half_kernel<<<(unsigned)((EH / 4 + 256) / 256), 256, 0, ctx->stream>>>(
         grad_m_out, INV_SQRT2, (const __bf16*)s.z_up, (const __bf16*)s.z_skip, (__bf16*)d_up, (__bf16*)d_skip, EH);
     GP_LAUNCH_CHECK(ctx, "dsilu2_half_kernel");
@@ -532,6 +533,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   float* dz_ba = d_up;   // d_up is no longer needed on this stream
   GP_TRY(aux.before_write(d_up));
   if (hs) {
+    gp_prof_scope prof(ctx, "ew_gate_bwd_half", 0.0, 10.0 * (double)EH);   // 5 bf16 arrays
     gate_bwd_half_kernel<<<(unsigned)((EH / 4 + 256) / 256), 256, 0, ctx->stream>>>(
         (const __bf16*)dxg, (const __bf16*)s.z_ba, (const __bf16*)s.gate, (__bf16*)dz_ba, (__bf16*)dgate, EH);
     GP_LAUNCH_CHECK(ctx, "gate_bwd_half_kernel");

@@ -2,12 +2,14 @@
 // reductions and elementwise kernels the edge MLPs need (EdgeUpdate of paper Sec. 2.1 / 3.3).
 //
 // Tiling: a 256-thread workgroup (4 wavefronts of 64) owns a BM x BN tile of C; the K loop
-// advances BK = 16 at a time through LDS tiles As[k][m], Bs[k][n] (k-major, so the 32 lanes that
+// advances BK = 32 at a time through LDS tiles As[k][m], Bs[k][n] (k-major, so the 32 lanes that
 // feed one MFMA operand read consecutive LDS words).  Each wavefront owns
 // (BM/WAVES_M) x (BN/WAVES_N) of the tile as 32x32 MFMA blocks.  The next K-slab is fetched
-// into registers while the current one is multiplied and written to LDS between two barriers
-// (BK = 32 with two LDS buffers and one barrier per slab can be compiled in; it measured
-// slower because it halves the number of resident workgroups).
+// into registers while the current one is multiplied and written to LDS between two barriers.
+// With 32 k per slab a row of a k-contiguous operand contributes a whole 128-byte line to each
+// load instruction, which the memory pipeline delivers faster than two half lines (BK = 16
+// measured 5 % slower; two LDS buffers with one barrier per slab can be compiled in and measured
+// slower still, because they halve the number of resident workgroups).
 #include <stdarg.h>
 
 #include <type_traits>
@@ -17,7 +19,7 @@
 namespace {
 
 #ifndef GP_GEMM_BK
-#define GP_GEMM_BK 16
+#define GP_GEMM_BK 32
 #endif
 #ifndef GP_GEMM_NBUF
 #define GP_GEMM_NBUF 1
@@ -314,6 +316,7 @@ int launch_reduce(gp_ctx* ctx, const float* part, int splits, int64_t n, float* 
   const int blocks1 = (int)((n + per_block - 1) / per_block);
   const int blocks2 = (int)((n2 + RED_COLS - 1) / RED_COLS);
   const int vec = (n % 4 == 0) && (((uintptr_t)part | (uintptr_t)out) & 15) == 0;
+  gp_prof_scope prof(ctx, "reduce_parts", 0.0, 4.0 * ((double)(splits + 1) * n + (double)(splits2 + 1) * n2));
   reduce_parts_kernel<<<blocks1 + blocks2, RED_COLS * RED_LANES, 0, ctx->stream>>>(part, splits, n, vec, out, blocks1,
                                                                                   part2, splits2, n2, out2);
   GP_LAUNCH_CHECK(ctx, "reduce_parts_kernel");
@@ -545,8 +548,11 @@ int gp_colsum(gp_ctx* ctx, const float* X, int64_t rows, int N, float* out, floa
   colsum_plan(rows, &blocks, &per);
   size_t need = (size_t)blocks * N * sizeof(float);
   if (!part || part_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "colsum: scratch %zu < %zu", part_bytes, need);
-  colsum_part_kernel<<<blocks, 256, 0, ctx->stream>>>(X, rows, N, per, part);
-  GP_LAUNCH_CHECK(ctx, "colsum_part_kernel");
+  {
+    gp_prof_scope prof(ctx, "colsum_part", 0.0, 4.0 * (double)rows * N);
+    colsum_part_kernel<<<blocks, 256, 0, ctx->stream>>>(X, rows, N, per, part);
+    GP_LAUNCH_CHECK(ctx, "colsum_part_kernel");
+  }
   return gp_reduce_parts(ctx, part, blocks, N, out);
 }
 
@@ -557,6 +563,7 @@ int gp_reduce_parts(gp_ctx* ctx, const float* part, int splits, int64_t n, float
 
 int gp_ew_dsilu_mul(gp_ctx* ctx, const float* g, const float* z, float* out, int64_t n) {
   if (n == 0) return GP_OK;
+  gp_prof_scope prof(ctx, "ew_dsilu_mul", 0.0, 12.0 * (double)n);
   ew_dsilu_mul_kernel<<<nblk(n), 256, 0, ctx->stream>>>(g, z, out, n);
   GP_LAUNCH_CHECK(ctx, "ew_dsilu_mul_kernel");
   return GP_OK;
@@ -564,6 +571,7 @@ int gp_ew_dsilu_mul(gp_ctx* ctx, const float* g, const float* z, float* out, int
 
 int gp_ew_gate_bwd(gp_ctx* ctx, const float* dxg, const float* z, const float* gate, float* dz, float* dgate, int64_t n) {
   if (n == 0) return GP_OK;
+  gp_prof_scope prof(ctx, "ew_gate_bwd", 0.0, 20.0 * (double)n);
   ew_gate_bwd_kernel<<<nblk(n), 256, 0, ctx->stream>>>(dxg, z, gate, dz, dgate, n);
   GP_LAUNCH_CHECK(ctx, "ew_gate_bwd_kernel");
   return GP_OK;
@@ -571,6 +579,7 @@ int gp_ew_gate_bwd(gp_ctx* ctx, const float* dxg, const float* z, const float* g
 
 int gp_ew_add3(gp_ctx* ctx, const float* a, const float* b, const float* c, float* out, int64_t n) {
   if (n == 0) return GP_OK;
+  gp_prof_scope prof(ctx, "ew_add3", 0.0, (c ? 16.0 : 12.0) * (double)n);
   ew_add3_kernel<<<nblk(n), 256, 0, ctx->stream>>>(a, b, c, out, n);
   GP_LAUNCH_CHECK(ctx, "ew_add3_kernel");
   return GP_OK;

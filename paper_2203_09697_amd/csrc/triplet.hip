@@ -664,6 +664,7 @@ int gp_permute3(gp_ctx* ctx, const float* src, int n0, int n1, int n2, int p0, i
 int gp_ew_dsilu2(gp_ctx* ctx, const float* g, float s, const float* z1, const float* z2, float* d1, float* d2,
                  int64_t n) {
   if (n == 0) return GP_OK;
+  gp_prof_scope prof(ctx, "ew_dsilu2", 0.0, 20.0 * (double)n);
   ew_dsilu2_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(g, s, z1, z2, d1, d2, n);
   GP_LAUNCH_CHECK(ctx, "ew_dsilu2_kernel");
   return GP_OK;
