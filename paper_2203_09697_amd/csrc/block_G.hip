@@ -66,7 +66,7 @@ struct scratch_G {
   float* eh5;                // symmetric blocks only: a fifth [E, H] buffer
   // bf16 storage only: weight matrices rounded to bf16 once per call, so that both operands of the large
   // GEMMs are copied to LDS without conversion
-  __bf16 *W_ba_h, *W_skip_h, *W_down_h, *W_up_h, *W_bil_h, *WbilP_h;
+  __bf16 *W_ba_h, *W_skip_h, *W_down_h, *W_up_h, *W_bil_h, *WbilP_h, *W_up_ac_h;
 };
 
 size_t part_bytes_G(const gp_dims* d, int64_t E) {
@@ -113,6 +113,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, int64_t T, scratch_
   s->W_up_h = c.take<__bf16>(hs ? O * H : 0);
   s->W_bil_h = c.take<__bf16>(hs ? C * F * O : 0);
   s->WbilP_h = c.take<__bf16>(hs ? C * O * F : 0);
+  s->W_up_ac_h = c.take<__bf16>(hs && d->symmetric ? O * H : 0);
   return c.off;
 }
 
@@ -144,31 +145,76 @@ gp_graph mirrored(const gp_graph* g) {
   return m;
 }
 
+typedef __bf16 h4 __attribute__((ext_vector_type(4)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+// four consecutive elements of an fp32 or bf16 array (index a multiple of 4, base 16- / 8-byte aligned)
+__device__ __forceinline__ f4 load4(const float* p, int64_t i) { return *reinterpret_cast<const f4*>(p + i); }
+__device__ __forceinline__ f4 load4(const __bf16* p, int64_t i) {
+  const h4 h = *reinterpret_cast<const h4*>(p + i);
+  return f4{(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
+}
+__device__ __forceinline__ void store4(float* p, int64_t i, f4 v) { *reinterpret_cast<f4*>(p + i) = v; }
+__device__ __forceinline__ void store4(__bf16* p, int64_t i, f4 v) {
+  *reinterpret_cast<h4*>(p + i) = h4{(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+}
+
 // Symmetric message passing, forward: t[e,:] = sqrt(2) t[e,:] + u_ac[id_swap[e],:] (second term 0 without an
-// opposite edge); the up-projection GEMM then stores (act(.) + t) / 2.
-__global__ void sym_mix_kernel(float* __restrict__ t, const float* __restrict__ u_ac, const int32_t* __restrict__ id_swap,
+// opposite edge); the up-projection GEMM then stores (act(.) + t) / 2.  ST: storage type of t and u_ac.
+template <class ST>
+__global__ void sym_mix_kernel(ST* __restrict__ t, const ST* __restrict__ u_ac, const int32_t* __restrict__ id_swap,
                                int64_t E, int H) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= E * H) return;
   const int sw = id_swap[i / H];
-  t[i] = 1.41421356237309504880f * t[i] + (sw >= 0 ? u_ac[(int64_t)sw * H + (i % H)] : 0.f);
+  t[i] = (ST)(1.41421356237309504880f * (float)t[i] + (sw >= 0 ? (float)u_ac[(int64_t)sw * H + (i % H)] : 0.f));
 }
 // backward: d_up = g/2 silu'(z_up), d_skip = g/sqrt(2) silu'(z_skip), d_ac[e] = g[id_swap[e]]/2 silu'(z_ac[e]) (0 if none)
-__global__ void sym_bwd_kernel(const float* __restrict__ g, const float* __restrict__ z_up, const float* __restrict__ z_skip,
-                               const float* __restrict__ z_ac, const int32_t* __restrict__ id_swap, int64_t E, int H,
-                               float* __restrict__ d_up, float* __restrict__ d_skip, float* __restrict__ d_ac) {
+template <class ST>
+__global__ void sym_bwd_kernel(const float* __restrict__ g, const ST* __restrict__ z_up, const ST* __restrict__ z_skip,
+                               const ST* __restrict__ z_ac, const int32_t* __restrict__ id_swap, int64_t E, int H,
+                               ST* __restrict__ d_up, ST* __restrict__ d_skip, ST* __restrict__ d_ac) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= E * H) return;
   const float gv = g[i];
-  d_up[i] = 0.5f * gv * dsilu_f(z_up[i]);
-  d_skip[i] = 0.70710678118654752440f * gv * dsilu_f(z_skip[i]);
+  d_up[i] = (ST)(0.5f * gv * dsilu_f((float)z_up[i]));
+  d_skip[i] = (ST)(0.70710678118654752440f * gv * dsilu_f((float)z_skip[i]));
   const int sw = id_swap[i / H];
-  d_ac[i] = sw >= 0 ? 0.5f * g[(int64_t)sw * H + (i % H)] * dsilu_f(z_ac[i]) : 0.f;
+  d_ac[i] = (ST)(sw >= 0 ? 0.5f * g[(int64_t)sw * H + (i % H)] * dsilu_f((float)z_ac[i]) : 0.f);
+}
+// the same two steps on 4 consecutive features per thread (H % 4 == 0)
+template <class ST>
+__global__ void sym_mix4_kernel(ST* __restrict__ t, const ST* __restrict__ u_ac, const int32_t* __restrict__ id_swap,
+                                int64_t E, int H) {
+  const int64_t i = 4 * ((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
+  if (i >= E * H) return;
+  const int sw = id_swap[i / H];
+  f4 v = 1.41421356237309504880f * load4(t, i);
+  if (sw >= 0) v += load4(u_ac, (int64_t)sw * H + (i % H));
+  store4(t, i, v);
+}
+template <class ST>
+__global__ void sym_bwd4_kernel(const float* __restrict__ g, const ST* __restrict__ z_up, const ST* __restrict__ z_skip,
+                                const ST* __restrict__ z_ac, const int32_t* __restrict__ id_swap, int64_t E, int H,
+                                ST* __restrict__ d_up, ST* __restrict__ d_skip, ST* __restrict__ d_ac) {
+  const int64_t i = 4 * ((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
+  if (i >= E * H) return;
+  const f4 gv = load4(g, i), zu = load4(z_up, i), zs = load4(z_skip, i), za = load4(z_ac, i);
+  const int sw = id_swap[i / H];
+  f4 gs = {0.f, 0.f, 0.f, 0.f};
+  if (sw >= 0) gs = load4(g, (int64_t)sw * H + (i % H));
+  f4 du, ds, da;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    du[c] = 0.5f * gv[c] * dsilu_f(zu[c]);
+    ds[c] = 0.70710678118654752440f * gv[c] * dsilu_f(zs[c]);
+    da[c] = 0.5f * gs[c] * dsilu_f(za[c]);
+  }
+  store4(d_up, i, du);
+  store4(d_skip, i, ds);
+  store4(d_ac, i, da);
 }
 
 // ---- bf16 storage of the [E, emb] intermediates (bf16 blocks): elementwise kernels, 4 elements per thread
-typedef __bf16 h4 __attribute__((ext_vector_type(4)));
-typedef float f4 __attribute__((ext_vector_type(4)));
 
 // d1 = g s silu'(z1), d2 = g s silu'(z2);  g fp32, everything else bf16
 __global__ void dsilu2_half_kernel(const float* __restrict__ g, float s, const __bf16* __restrict__ z1,
@@ -256,7 +302,7 @@ __global__ void to_half_kernel(const float* __restrict__ in, __bf16* __restrict_
 // allow 16-byte rows of bf16.  They are consumed by bf16-operand GEMMs (which would round them
 // anyway) or by elementwise activation derivatives.  The buffers keep their fp32 sizes.
 bool half_storage(const gp_dims* d) {
-  return d->dtype == GP_BF16_F32ACC && !d->symmetric && d->emb % 8 == 0 && (d->emb_cbf * d->emb_bil) % 8 == 0;
+  return d->dtype == GP_BF16_F32ACC && d->emb % 8 == 0 && (d->emb_cbf * d->emb_bil) % 8 == 0;
 }
 
 // dst[q] (+)= src[perm[q]]
@@ -404,11 +450,18 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     // t = sqrt(2) t_skip + act(z W_up_ac)[id_swap]
     GP_REQUIRE(ctx, graph->id_swap, "gp_block_forward_G: graph->id_swap is needed by a symmetric block");
     float* u_ac = sc.eh[1];
-    e = gp_epilogue(); e.save_pre = s.z_ac; e.act = 1; e.out = u_ac;
+    e = gp_epilogue(); e.save_pre = s.z_ac; e.act = 1; e.out = u_ac; e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_OUT) : 0u;
     GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up_ac, E, H, O, e));
-    sym_mix_kernel<<<(unsigned)(((int64_t)E * H + 255) / 256), 256, 0, ctx->stream>>>(t_skip, u_ac, graph->id_swap, E, H);
-    GP_LAUNCH_CHECK(ctx, "sym_mix_kernel");
+    {
+      gp_prof_scope prof(ctx, "ew_sym_mix", 0.0, (hs ? 6.0 : 12.0) * (double)E * H);
+      const unsigned blocks = (unsigned)(((int64_t)E * H + 255) / 256), blocks4 = (unsigned)(((int64_t)E * H / 4 + 255) / 256);
+      if (hs) sym_mix4_kernel<__bf16><<<blocks4, 256, 0, ctx->stream>>>((__bf16*)t_skip, (const __bf16*)u_ac, graph->id_swap, E, H);
+      else if (H % 4 == 0) sym_mix4_kernel<float><<<blocks4, 256, 0, ctx->stream>>>(t_skip, u_ac, graph->id_swap, E, H);
+      else sym_mix_kernel<float><<<blocks, 256, 0, ctx->stream>>>(t_skip, u_ac, graph->id_swap, E, H);
+      GP_LAUNCH_CHECK(ctx, "sym_mix_kernel");
+    }
     e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = 0.5f; e.out = m_out;
+    e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST) : 0u;
     GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
     return GP_OK;
   }
@@ -455,12 +508,31 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   if (dims->symmetric) {
     GP_REQUIRE(ctx, graph->id_swap, "gp_block_backward_G: graph->id_swap is needed by a symmetric block");
     float* d_ac = sc.eh5;
-    sym_bwd_kernel<<<(unsigned)((EH + 255) / 256), 256, 0, ctx->stream>>>(grad_m_out, s.z_up, s.z_skip, s.z_ac, graph->id_swap,
-                                                                          E, H, d_up, d_skip, d_ac);
-    GP_LAUNCH_CHECK(ctx, "sym_bwd_kernel");
-    GP_TRY(gp_gemm_tn(ctx, s.z, d_ac, E, O, H, gw->W_up_ac, nullptr, sc.part, sc.part_bytes));
+    {
+      gp_prof_scope prof(ctx, "ew_sym_bwd", 0.0, (hs ? 20.0 : 32.0) * (double)EH);
+      const unsigned blocks = (unsigned)((EH + 255) / 256), blocks4 = (unsigned)((EH / 4 + 255) / 256);
+      const bool vec4 = H % 4 == 0 && ((uintptr_t)grad_m_out & 15) == 0;   // the library's own buffers are 256-byte aligned
+      if (hs && !vec4)
+        sym_bwd_kernel<__bf16><<<blocks, 256, 0, ctx->stream>>>(grad_m_out, (const __bf16*)s.z_up, (const __bf16*)s.z_skip,
+                                                               (const __bf16*)s.z_ac, graph->id_swap, E, H, (__bf16*)d_up,
+                                                               (__bf16*)d_skip, (__bf16*)d_ac);
+      else if (hs)
+        sym_bwd4_kernel<__bf16><<<blocks4, 256, 0, ctx->stream>>>(grad_m_out, (const __bf16*)s.z_up, (const __bf16*)s.z_skip,
+                                                                 (const __bf16*)s.z_ac, graph->id_swap, E, H, (__bf16*)d_up,
+                                                                 (__bf16*)d_skip, (__bf16*)d_ac);
+      else if (vec4)
+        sym_bwd4_kernel<float><<<blocks4, 256, 0, ctx->stream>>>(grad_m_out, s.z_up, s.z_skip, s.z_ac, graph->id_swap, E, H, d_up,
+                                                                d_skip, d_ac);
+      else
+        sym_bwd_kernel<float><<<blocks, 256, 0, ctx->stream>>>(grad_m_out, s.z_up, s.z_skip, s.z_ac, graph->id_swap, E, H, d_up,
+                                                              d_skip, d_ac);
+      GP_LAUNCH_CHECK(ctx, "sym_bwd_kernel");
+    }
+    GP_TRY(gp_gemm_tn(ctx, s.z, d_ac, E, O, H, gw->W_up_ac, nullptr, sc.part, sc.part_bytes, 0, hs));
     e = gp_epilogue(); e.out = sc.dz;
-    GP_TRY(gp_gemm_nt(ctx, d_ac, w->W_up_ac, E, O, H, e));                          // dz (opposite-edge path)
+    const float* W_up_ac = weight_operand(ctx, wh, w->W_up_ac, sc.W_up_ac_h, (int64_t)O * H, &rc);
+    GP_TRY(rc);
+    GP_TRY(gp_gemm_nt(ctx, d_ac, W_up_ac, E, O, H, e, hs, wh));                     // dz (opposite-edge path)
   } else if (hs) {
     gp_prof_scope prof(ctx, "ew_dsilu2_half", 0.0, 12.0 * (double)EH);   // fp32 gradient + 4 bf16 arrays
     dsilu2_half_kernel<<<(unsigned)((EH / 4 + 256) / 256), 256, 0, ctx->stream>>>(
