@@ -586,11 +586,13 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(rc);
   GP_TRY(gp_gemm_nn(ctx, sc.Gm, WbilP, E, F, C * O, e, hs, wh));                    // dz_dn
   GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));                   // [f, (c,o)]
-  e = gp_epilogue(); e.out = sc.V;
+  // V is read by the two per-edge kernels below only: bf16 storage halves its traffic
+  const bool vh = hs && (O == 32 || O == 64 || O == 128);
+  e = gp_epilogue(); e.out = sc.V; e.bf16 = vh ? EPI_BF_OUT : 0u;
   GP_TRY(gp_gemm_nn(ctx, s.x, sc.WbilV, E, C * O, F, e));                           // V[e', (c,o)]
-  GP_TRY(gp_tripG_edge_dRad(ctx, sc.V, sc.Hd, E, S, C, O, sc.dRad));                // dRad[e', (l,c)]
+  GP_TRY(gp_tripG_edge_dRad(ctx, sc.V, sc.Hd, E, S, C, O, sc.dRad, vh));            // dRad[e', (l,c)]
   if (grad_cos_kj && graph->n_triplets > 0) {
-    GP_TRY(gp_tripG_edge_U(ctx, s.Radt, sc.V, E, S, C, O, sc.U));
+    GP_TRY(gp_tripG_edge_U(ctx, s.Radt, sc.V, E, S, C, O, sc.U, vh));
     if (bwd_mfma)
       GP_TRY(gp_tripG_grad_cos_mfma(ctx, graph, basis->cos_alpha_kj, sc.U, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj));
     else

@@ -44,14 +44,15 @@ size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E, int64_t T);
 int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout,
                     int out_half = 0);
 // dRad[e, l*C + c] = sum_o V[e, c*O + o] * H[e, l, o]
-int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad);
+// v_half: V addresses bf16 elements
+int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad, int v_half = 0);
 // dst[a,b,c] = src element whose index along source dimension p0 is a, along p1 is b, along p2 is c
 // (src has dimensions n0 x n1 x n2; dst has n[p0] x n[p1] x n[p2]); for small weight tensors
 int gp_permute3(gp_ctx* ctx, const float* src, int n0, int n1, int n2, int p0, int p1, int p2, float* dst);
 // d1 = g * s * silu'(z1), d2 = g * s * silu'(z2)
 int gp_ew_dsilu2(gp_ctx* ctx, const float* g, float s, const float* z1, const float* z2, float* d1, float* d2, int64_t n);
 // U[e, l, o] = sum_c Radt[(l*C+c)*E + e] * V[e, c*O + o]
-int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, int S, int C, int O, float* U);
+int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, int S, int C, int O, float* U, int v_half = 0);
 // grad_cos_kj[q] (+)= sum_l Y_l0'(cos_alpha_kj[q]) sum_o dz[ji(q), o] U[kj(q), l, o]   (kj-major order)
 int gp_tripG_grad_cos(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* U, const float* dz,
                       int O, int S, int accumulate, float* grad_cos_kj);

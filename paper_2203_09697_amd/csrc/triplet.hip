@@ -562,9 +562,23 @@ edge_G_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64
   extern __shared__ float dyn_s[];   // rad_s[(l*C + c) * 64 + edge]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int64_t e0 = (int64_t)blockIdx.x * EG_EDGES;
-  for (int i = threadIdx.x; i < S * C * EG_EDGES; i += WPB * WAVE) {
-    const int64_t e = e0 + (i & (EG_EDGES - 1));
-    dyn_s[i] = e < E ? Radt[(int64_t)(i / EG_EDGES) * E + e] : 0.f;
+  {
+    // all loads of a thread before the first LDS write: a rolled loop would expose one memory round trip per pass
+    constexpr int PASSES = ST * 16 * EG_EDGES / (WPB * WAVE);   // emb_cbf <= 16
+    float r[PASSES];
+    const int n = S * C * EG_EDGES;
+#pragma unroll
+    for (int k = 0; k < PASSES; ++k) {
+      const int i = threadIdx.x + k * WPB * WAVE;
+      const int ic = i < n ? i : n - 1;
+      const int64_t e = e0 + (ic & (EG_EDGES - 1));
+      r[k] = Radt[(int64_t)(ic / EG_EDGES) * E + (e < E ? e : E - 1)];
+    }
+#pragma unroll
+    for (int k = 0; k < PASSES; ++k) {
+      const int i = threadIdx.x + k * WPB * WAVE;
+      if (i < n) dyn_s[i] = e0 + (i & (EG_EDGES - 1)) < E ? r[k] : 0.f;
+    }
   }
   __syncthreads();
   for (int el = w; el < EG_EDGES && e0 + el < E; el += WPB) {
@@ -606,6 +620,62 @@ edge_dRad_kernel(const float* __restrict__ V, const float* __restrict__ H, int64
   }
 }
 
+// dRad[e, l, c] = sum_o V[e, c, o] H[e, l, o] without LDS, for C <= 16 and O = 4 OQ: lane = (c, quarter q of the o
+// range).  A lane loads its OQ values of V[c, :] (the wavefront reads the edge's C x O block contiguously) and the
+// same OQ columns of the S rows of H (16 lanes share each address), all requested before the first use; the four
+// partial sums of a c are combined by two lane exchanges.  VT: storage type of V.
+template <int OQ, class VT>
+__global__ void __launch_bounds__(WPB* WAVE)
+edge_dRad_q_kernel(const VT* __restrict__ V, const float* __restrict__ H, int64_t E, int S, int C, float* __restrict__ dRad) {
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t e = (int64_t)blockIdx.x * WPB + w;
+  if (e >= E) return;
+  constexpr int O = 4 * OQ;
+  const int c = lane >> 2, q = lane & 3;
+  const VT* vp = V + (e * C + (c < C ? c : C - 1)) * O + q * OQ;
+  float v[OQ];
+  if (sizeof(VT) == 2) {
+    typedef __bf16 h8 __attribute__((ext_vector_type(8)));
+#pragma unroll
+    for (int i = 0; i < OQ; i += 8) {
+      const h8 t = *reinterpret_cast<const h8*>(vp + i);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[i + k] = (float)t[k];
+    }
+  } else {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int i = 0; i < OQ; i += 4) {
+      const f4 t = *reinterpret_cast<const f4*>(reinterpret_cast<const float*>(vp) + i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[i + k] = t[k];
+    }
+  }
+  float part[ST];
+#pragma unroll
+  for (int l = 0; l < ST; ++l) {
+    part[l] = 0.f;
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const float* hp = H + (e * S + (l < S ? l : S - 1)) * O + q * OQ;
+#pragma unroll
+    for (int i = 0; i < OQ; i += 4) {
+      const f4 t = *reinterpret_cast<const f4*>(hp + i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) part[l] += v[i + k] * t[k];
+    }
+  }
+#pragma unroll
+  for (int l = 0; l < ST; ++l) {
+    part[l] += __shfl_xor(part[l], 1);
+    part[l] += __shfl_xor(part[l], 2);
+  }
+  if (q == 0 && c < C) {
+#pragma unroll
+    for (int l = 0; l < ST; ++l)
+      if (l < S) dRad[e * S * C + l * C + c] = part[l];
+  }
+}
+
 __global__ void permute3_kernel(const float* __restrict__ src, int n0, int n1, int n2, int p0, int p1, int p2,
                                 float* __restrict__ dst) {
   const int n[3] = {n0, n1, n2};
@@ -633,7 +703,7 @@ __global__ void ew_dsilu2_kernel(const float* __restrict__ g, float s, const flo
 
 int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout, int out_half) {
   if (E == 0) return GP_OK;
-  GP_REQUIRE(ctx, Radt && H && Gout && S >= 1 && S <= ST && C >= 1 && O >= 1, "edge_G: bad arguments");
+  GP_REQUIRE(ctx, Radt && H && Gout && S >= 1 && S <= ST && C >= 1 && C <= 16 && O >= 1, "edge_G: bad arguments");
   gp_prof_scope prof(ctx, "tripG_edge_G", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
   edge_G_kernel<<<(unsigned)((E + EG_EDGES - 1) / EG_EDGES), WPB * WAVE, (size_t)S * C * EG_EDGES * sizeof(float), ctx->stream>>>(
       Radt, H, E, S, C, O, out_half, Gout);
@@ -641,12 +711,30 @@ int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, i
   return GP_OK;
 }
 
-int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad) {
+int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad, int v_half) {
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, V && H && dRad && S >= 1 && S <= ST && C >= 1 && O >= 1, "edge_dRad: bad arguments");
+  gp_prof_scope prof(ctx, "tripG_edge_dRad", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O) + (v_half ? 2.0 : 4.0) * E * C * O);
+  // 16-byte loads need 16-byte aligned rows: true for the widths below when the bases are (fp32 V and H: O % 4,
+  // bf16 V: O % 8)
+  const bool aligned = (((uintptr_t)V | (uintptr_t)H) & 15) == 0;
+  if (C <= 16 && aligned && (O == 32 || O == 64 || O == 128)) {
+    const __bf16* Vh = reinterpret_cast<const __bf16*>(V);
+#define GP_DRAD(OQ)                                                                                           \
+  do {                                                                                                        \
+    if (v_half) edge_dRad_q_kernel<OQ, __bf16><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(Vh, H, E, S, C, dRad); \
+    else edge_dRad_q_kernel<OQ, float><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(V, H, E, S, C, dRad);    \
+  } while (0)
+    if (O == 32) GP_DRAD(8);
+    else if (O == 64) GP_DRAD(16);
+    else GP_DRAD(32);
+#undef GP_DRAD
+    GP_LAUNCH_CHECK(ctx, "edge_dRad_q_kernel");
+    return GP_OK;
+  }
+  if (v_half) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "edge_dRad: bf16 V needs emb_cbf <= 16 and a width of 32, 64 or 128");
   const size_t lds = (size_t)WPB * (C + S) * (O + 1) * sizeof(float);
   if (lds > 64 * 1024) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "edge_dRad: (emb_cbf+num_spherical)*emb_bil too large");
-  gp_prof_scope prof(ctx, "tripG_edge_dRad", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
   edge_dRad_kernel<<<seg_blocks(E), WPB * WAVE, lds, ctx->stream>>>(V, H, E, S, C, O, dRad);
   GP_LAUNCH_CHECK(ctx, "edge_dRad_kernel");
   return GP_OK;

@@ -39,29 +39,55 @@ __device__ __forceinline__ void dy_l0(float c, int S, float* dY) {
 // wavefront per edge, lanes over o.
 constexpr int EU_EDGES = 64;
 
+constexpr int EU_CMAX = 16;   // largest emb_cbf
+
+// The slice of the transposed radial table for 64 consecutive edges, [(l*C + c) * 64 + edge], into LDS.  All loads
+// of a thread are issued before the first LDS write (a rolled loop would expose one memory round trip per pass).
+__device__ __forceinline__ void stage_radial_slice(const float* __restrict__ Radt, int64_t E, int64_t e0, int rows, float* rad_s) {
+  constexpr int PASSES = ST * EU_CMAX * EU_EDGES / (WPB * 64);
+  float r[PASSES];
+  const int n = rows * EU_EDGES;
+#pragma unroll
+  for (int k = 0; k < PASSES; ++k) {
+    const int i = threadIdx.x + k * WPB * 64;
+    const int ic = i < n ? i : n - 1;
+    const int64_t e = e0 + (ic & (EU_EDGES - 1));
+    r[k] = Radt[(int64_t)(ic / EU_EDGES) * E + (e < E ? e : E - 1)];
+  }
+#pragma unroll
+  for (int k = 0; k < PASSES; ++k) {
+    const int i = threadIdx.x + k * WPB * 64;
+    if (i < n) rad_s[i] = e0 + (i & (EU_EDGES - 1)) < E ? r[k] : 0.f;
+  }
+}
+
+// VT: storage type of V (fp32, or bf16 as written by the epilogue of the GEMM that produces it)
+template <class VT>
 __global__ void __launch_bounds__(WPB* 64)
-edge_U_kernel(const float* __restrict__ Radt, const float* __restrict__ V, int64_t E, int S, int C, int O,
+edge_U_kernel(const float* __restrict__ Radt, const VT* __restrict__ V, int64_t E, int S, int C, int O,
               float* __restrict__ U) {
   extern __shared__ float rad_s[];   // [(l*C + c) * 64 + edge]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int64_t e0 = (int64_t)blockIdx.x * EU_EDGES;
-  for (int i = threadIdx.x; i < S * C * EU_EDGES; i += WPB * 64) {
-    const int64_t e = e0 + (i & (EU_EDGES - 1));
-    rad_s[i] = e < E ? Radt[(int64_t)(i / EU_EDGES) * E + e] : 0.f;
-  }
+  stage_radial_slice(Radt, E, e0, S * C, rad_s);
   __syncthreads();
   for (int el = w; el < EU_EDGES && e0 + el < E; el += WPB) {
     const int64_t e = e0 + el;
     for (int o = lane; o < O; o += 64) {
+      // all C values of the column first (clamped index: no branch around a load), so that their latencies overlap
+      float v[EU_CMAX];
+#pragma unroll
+      for (int c = 0; c < EU_CMAX; ++c) v[c] = (float)V[(e * C + (c < C ? c : C - 1)) * O + o];
       float acc[ST];
 #pragma unroll
       for (int l = 0; l < ST; ++l) acc[l] = 0.f;
-      for (int c = 0; c < C; ++c) {
-        const float v = V[(e * C + c) * O + o];
 #pragma unroll
-        for (int l = 0; l < ST; ++l)
-          if (l < S) acc[l] += rad_s[(l * C + c) * EU_EDGES + el] * v;
-      }
+      for (int c = 0; c < EU_CMAX; ++c)
+        if (c < C) {
+#pragma unroll
+          for (int l = 0; l < ST; ++l)
+            if (l < S) acc[l] += rad_s[(l * C + c) * EU_EDGES + el] * v[c];
+        }
 #pragma unroll
       for (int l = 0; l < ST; ++l)
         if (l < S) U[(e * S + l) * O + o] = acc[l];
@@ -126,12 +152,14 @@ trip_dcos_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__
 
 }  // namespace
 
-int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, int S, int C, int O, float* U) {
+int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, int S, int C, int O, float* U, int v_half) {
   if (E == 0) return GP_OK;
-  GP_REQUIRE(ctx, Radt && V && U && S >= 1 && S <= ST && C >= 1 && O >= 1, "edge_U: bad arguments");
-  gp_prof_scope prof(ctx, "tripG_edge_U", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
-  edge_U_kernel<<<(unsigned)((E + EU_EDGES - 1) / EU_EDGES), WPB * 64, (size_t)S * C * EU_EDGES * sizeof(float), ctx->stream>>>(
-      Radt, V, E, S, C, O, U);
+  GP_REQUIRE(ctx, Radt && V && U && S >= 1 && S <= ST && C >= 1 && C <= EU_CMAX && O >= 1, "edge_U: bad arguments");
+  gp_prof_scope prof(ctx, "tripG_edge_U", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O) + (v_half ? 2.0 : 4.0) * E * C * O);
+  const unsigned blocks = (unsigned)((E + EU_EDGES - 1) / EU_EDGES);
+  const size_t lds = (size_t)S * C * EU_EDGES * sizeof(float);
+  if (v_half) edge_U_kernel<__bf16><<<blocks, WPB * 64, lds, ctx->stream>>>(Radt, reinterpret_cast<const __bf16*>(V), E, S, C, O, U);
+  else edge_U_kernel<float><<<blocks, WPB * 64, lds, ctx->stream>>>(Radt, V, E, S, C, O, U);
   GP_LAUNCH_CHECK(ctx, "edge_U_kernel");
   return GP_OK;
 }
