@@ -439,14 +439,15 @@ struct tn_plan_t {
   int64_t per;
 };
 
-// Split the reduction so that about two workgroups per CU exist, each reducing >= 512 rows.
+// Split the reduction so that about three workgroups per CU exist (what the register file holds), each
+// reducing >= 256 rows.
 tn_plan_t tn_plan(int64_t rows, int M, int N) {
   tn_plan_t p;
   p.tiles_m = (M + TILE_BM - 1) / TILE_BM;
   p.tiles_n = (N + tile_bn(N) - 1) / tile_bn(N);
   const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-  int64_t s = (512 + tiles - 1) / tiles;
-  const int64_t max_s = (rows + 511) / 512;
+  int64_t s = (768 + tiles - 1) / tiles;
+  const int64_t max_s = (rows + 255) / 256;
   if (s > max_s) s = max_s;
   if (s < 1) s = 1;
   int64_t per = (rows + s - 1) / s;
