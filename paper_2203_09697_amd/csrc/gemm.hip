@@ -127,7 +127,7 @@ struct loader_xcontig {
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE, bool VEC>
 __global__ void __launch_bounds__(THREADS)
 gemm_f32_kernel(const gemm_args g) {
-  static_assert(WAVES_M * WAVES_N == 4 || BM == 64, "four wavefronts per workgroup");
+  static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MB = WM / 32, NB = WN / 32;
   using loadA = typename std::conditional<MODE != MODE_TN, loader_kcontig<BM, VEC>, loader_xcontig<BM, VEC>>::type;
@@ -244,9 +244,6 @@ gemm_f32_kernel(const gemm_args g) {
             for (int c = 0; c < 4; ++c)
               if (col + c < g.N) dst[c] = v4[c];
         } else {
-#ifdef GP_GEMM_DEBUG_NOSTORE
-          if (v4[0] != 123.456f) continue;
-#endif
           if (g.vecC) epilogue_store4(g.epi, row, col, g.N, v4);
           else
             for (int c = 0; c < 4; ++c)
@@ -397,10 +394,7 @@ int launch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
 
 // tile shape by output width
 inline int tile_bn(int N) { return N > 64 ? 128 : N > 32 ? 64 : 32; }
-#ifndef GP_GEMM_BM
-#define GP_GEMM_BM 128
-#endif
-constexpr int TILE_BM = GP_GEMM_BM;
+constexpr int TILE_BM = 128;
 
 template <int MODE>
 int dispatch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
@@ -409,16 +403,15 @@ int dispatch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
   if (ctx->gemm_bf16 && !(MODE == MODE_TN && g.colsum_part)) return gp_gemm_bf16_launch(ctx, MODE, &g, splits);
   if (g.a_bf16 || g.b_bf16 || g.epi.bf16)
     return gp_fail(ctx, GP_BAD_ARG, "gemm: bf16 storage is only handled by the bf16-operand kernels");
-#if GP_GEMM_BM == 64
-  if (g.N > 64) return launch_gemm<TILE_BM, 128, 1, 4, MODE>(ctx, g, splits);
-  if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
-  return launch_gemm<128, 32, 4, 1, MODE>(ctx, g, splits);
-#endif
-#ifdef GP_GEMM_DEBUG_BN64
-  if (MODE != MODE_TN && g.N > 64) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
-#endif
-  if (g.N > 64) return launch_gemm<TILE_BM, 128, 2, 2, MODE>(ctx, g, splits);
-  if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
+  if (MODE == MODE_TN) {   // tile widths the split plan (tn_plan / tile_bn) was made for
+    if (g.N > 64) return launch_gemm<TILE_BM, 128, 2, 2, MODE>(ctx, g, splits);
+    if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
+    return launch_gemm<TILE_BM, 32, 4, 1, MODE>(ctx, g, splits);
+  }
+  // Row-panel GEMMs: narrower tiles than the MFMA rate alone would ask for.  The layers here have K <= a few
+  // hundred, so a workgroup is mostly prologue (first loads) and epilogue; more, smaller workgroups per CU let
+  // those phases of one workgroup overlap the main loop of another (measured at E = 43 372 and 300 000).
+  if (g.N > 64) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
   return launch_gemm<TILE_BM, 32, 4, 1, MODE>(ctx, g, splits);
 }
 
