@@ -854,6 +854,8 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
       g.lda % 8 == 0 && g.ldb % 8 == 0)
     return launch_dl<256, 256, 2, 4, 64, 2>(ctx, g);
   // the reduction over rows (TN) keeps the 128-row tiles its split plan was made for
+  // short contractions are all prologue and epilogue: smaller tiles, more workgroups per CU to overlap them
+  if (MODE != MODE_TN && g.K <= 128 && g.N > 64) GP_BF16_LAUNCH(128, 128, 2, 2);
   if (MODE != MODE_TN && g.M >= 8192 && g.N > 64) GP_BF16_LAUNCH(256, 128, 2, 2);
   if (g.N > 64) GP_BF16_LAUNCH(128, 128, 2, 2);
   if (g.N > 32) GP_BF16_LAUNCH(128, 64, 2, 2);
