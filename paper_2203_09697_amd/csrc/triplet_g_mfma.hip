@@ -98,7 +98,7 @@ __device__ __forceinline__ int64_t y_offset(int seg, int e) {   // in bf16 eleme
 }
 
 template <int SM>   // loops over l run to SM >= num_spherical (rows above num_spherical are zero)
-__global__ void __launch_bounds__(YT)
+__global__ void __launch_bounds__(YT, 3)   // three workgroups per CU: 168 registers (a few spilled) beat two at 192
 tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_ji,
                const int32_t* __restrict__ idx_kj, const float* __restrict__ cos_alpha,
