@@ -314,11 +314,14 @@ __global__ void permute_add_kernel(const float* __restrict__ src, const int32_t*
   dst[q] = accumulate ? dst[q] + v : v;
 }
 
-// the dense per-centre-atom form pays once an edge has about a hundred triplets
-bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
+// The dense per-centre-atom form pays once an edge has enough triplets: measured at 42 triplets per edge
+// (configuration 3) the forward pair of kernels wins (0.40 vs 0.52 ms) and the backward kernels lose (0.28 vs
+// 0.15 ms); at 333 (configuration 4) both win by far.
+constexpr double MFMA_FWD_DENSITY = 32.0, MFMA_BWD_DENSITY = 96.0;
+bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g, double min_density) {
   if (d->dtype != GP_BF16_F32ACC || ctx->trip_mfma == 0 || d->radial_at_target) return false;
   if (ctx->trip_mfma == 1) return true;
-  return g->n_edges > 0 && (double)g->n_triplets >= 96.0 * (double)g->n_edges;
+  return g->n_edges > 0 && (double)g->n_triplets >= min_density * (double)g->n_edges;
 }
 
 // The accumulator A[E, C, F] is stored as bf16 when the matrix-core kernel writes it and bf16 storage is on: its
@@ -348,7 +351,7 @@ const float* weight_operand(gp_ctx* ctx, bool half, const float* W, __bf16* W_h,
 }
 
 bool a_half(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
-  return half_storage(d) && (d->emb_cbf * d->int_emb) % 8 == 0 && want_trip_mfma(ctx, d, g) &&
+  return half_storage(d) && (d->emb_cbf * d->int_emb) % 8 == 0 && want_trip_mfma(ctx, d, g, MFMA_FWD_DENSITY) &&
          gp_tripG_mfma_usable(g, d->int_emb, d->num_spherical, d->emb_cbf);
 }
 
@@ -435,7 +438,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     const gp_graph gm = mirrored(graph);
     GP_TRY(gp_tripD_backward(ctx, &gm, basis->cos_alpha, nullptr, nullptr, nullptr, s.x, nullptr, F, S, 1, s.B1, nullptr));
     GP_TRY(gp_tripG_edge_G(ctx, s.Radt, s.B1, E, S, C, F, s.A));
-  } else if (want_trip_mfma(ctx, dims, graph) && gp_tripG_mfma_usable(graph, F, S, C))
+  } else if (want_trip_mfma(ctx, dims, graph, MFMA_FWD_DENSITY) && gp_tripG_mfma_usable(graph, F, S, C))
     GP_TRY(gp_tripG_forward_mfma(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes, ah));
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
@@ -573,7 +576,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
     }
   } else {
   // one pass over the triplets (kj-major): H[e', l, o]
-  const bool bwd_mfma = want_trip_mfma(ctx, dims, graph) && gp_tripG_mfma_bwd_usable(graph, O, S);
+  const bool bwd_mfma = want_trip_mfma(ctx, dims, graph, MFMA_BWD_DENSITY) && gp_tripG_mfma_bwd_usable(graph, O, S);
   if (bwd_mfma)
     GP_TRY(gp_tripG_backward_H_mfma(ctx, graph, basis->cos_alpha_kj, sc.dz, O, S, sc.Hd));
   else
