@@ -201,7 +201,10 @@ int gp_block_forward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, 
   e = gp_epilogue(); e.save_pre = s.z_dn; e.act = 1; e.out = s.x_kj;
   GP_TRY(gp_gemm_nn(ctx, s.xg, w->W_down, E, F, H, e));
   GP_TRY(gp_tripD_project_radial(ctx, basis->rad, w->W_sbf1, E, S, R, B, s.Q));
-  GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a, s.Bacc));
+  if (ctx->trip_mfma != 0 && gp_tripD_mfma_usable(graph, F, S, B))
+    GP_TRY(gp_tripD_forward_mfma(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a, s.Bacc));
+  else
+    GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a, s.Bacc));
   e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = x_ji; e.out = s.h0;
   GP_TRY(gp_gemm_nn(ctx, s.a, w->W_up, E, H, F, e));
 

@@ -18,6 +18,11 @@ int gp_tripD_forward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, con
 // From grad_a[E,F]:
 //   grad_x[e',f] = sum_{t: kj(t)=e'} grad_a[ji(t),f] s_t[f], multiplied by silu'(z[e',f]) if z != NULL
 //   grad_Q[e',l,b] = sum_{t: kj(t)=e'} Y_l(t) sum_f W2[b,f] grad_a[ji(t),f] x[e',f]
+// The same result on the fp32 matrix cores, grouped by centre atom (needs the centre-atom lists of gp_graph,
+// basis_emb 8, int_emb 32..128 in steps of 32, and the atom with the most in-edges to fit LDS).
+bool gp_tripD_mfma_usable(const gp_graph* g, int F, int S, int B);
+int gp_tripD_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Qt,
+                          const float* W2, int F, int S, int B, float* a, float* Bacc);
 int gp_tripD_backward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* x, const float* Q,
                       const float* W2, const float* grad_a, const float* z, int F, int S, int B,
                       float* grad_x, float* grad_Q);

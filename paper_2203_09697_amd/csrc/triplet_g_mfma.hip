@@ -59,12 +59,12 @@ __device__ __forceinline__ void wave_lds_sync() {
 // each XCD a contiguous range of them keeps every XCD equally busy (with part = id % 8 the XCDs that get the
 // high part numbers, which most atoms do not have, would idle) and runs the parts of one atom, which read the
 // same in-edge rows, side by side on one L2.
-__device__ __forceinline__ void atom_and_part(int& j, int& part) {
+__device__ __forceinline__ void atom_and_part(int parts, int& j, int& part) {
   const int n = (int)gridDim.x, q = n >> 3, r = n & 7;
   const int x = (int)blockIdx.x & 7, i = (int)blockIdx.x >> 3;
   const int w = x * q + (x < r ? x : r) + i;
-  j = w / PARTS;
-  part = w % PARTS;
+  j = w / parts;
+  part = w % parts;
 }
 
 // The share of one workgroup: centre atom j, its in-edge rows r0 .. r0+d-1
@@ -75,9 +75,9 @@ struct part_t {
 
 // false (for every thread of the workgroup alike) if this workgroup has nothing to do
 __device__ __forceinline__ bool centre_part(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
-                                            int kp_cap, part_t& P) {
+                                            int kp_cap, int parts, part_t& P) {
   int j, part;
-  atom_and_part(j, part);
+  atom_and_part(parts, j, part);
   P.r0 = row_ptr[j];
   P.d = row_ptr[j + 1] - P.r0;
   P.Kp = (P.d + 15) & ~15;
@@ -85,7 +85,7 @@ __device__ __forceinline__ bool centre_part(const int32_t* __restrict__ row_ptr,
   const int dout = out_ptr[j + 1] - P.o0;
   if (dout <= 0 || P.Kp > kp_cap) return false;
   int nparts = (dout + EPP - 1) / EPP;
-  nparts = nparts < PARTS ? nparts : PARTS;
+  nparts = nparts < parts ? nparts : parts;
   if (part >= nparts) return false;
   const int len = (((dout + nparts - 1) / nparts) + 3) & ~3;
   P.eb = part * len;
@@ -102,9 +102,9 @@ __global__ void __launch_bounds__(YT, 3)   // three workgroups per CU: 168 regis
 tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_ji,
                const int32_t* __restrict__ idx_kj, const float* __restrict__ cos_alpha,
-               const float* __restrict__ Radt, int64_t E, int S, int C, int kp_cap, __bf16* __restrict__ Yb) {
+               const float* __restrict__ Radt, int64_t E, int S, int C, int kp_cap, int parts, __bf16* __restrict__ Yb) {
   part_t P;
-  if (!centre_part(row_ptr, out_ptr, kp_cap, P)) return;
+  if (!centre_part(row_ptr, out_ptr, kp_cap, parts, P)) return;
   __shared__ int s_e[64], s_seg[64], s_cnt[64], s_gap[64];
   const int n_pg = P.Kp / 8;
   const int cp = threadIdx.x & 7;
@@ -208,15 +208,144 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
   }
 }
 
+// ---- variant D (Hadamard form, fp32): Bacc[e, b, f] = sum_{t in seg(e)} p_t[b] x[kj(t), f],
+// p_t[b] = sum_l Y_l0(cos alpha_t) Q[kj(t), l, b], and a[e, f] = sum_b W2[b, f] Bacc[e, b, f].
+// The same regrouping by centre atom j: rows (out-edge e, b), contraction over the in-edge rows p of j, columns f,
+// on the fp32 matrix cores (v_mfma_f32_32x32x2_f32: lane l feeds row / column l % 32 at k = l / 32).  X_j and the
+// atom's slice of Q (pre-multiplied by the normalisation of Y_l0 and the leading coefficient of P_l) are staged
+// in LDS once; the left operand p_t[b] is evaluated in registers from the cosine, one value per lane and MFMA,
+// so nothing of size T is stored.  A wavefront owns 4 out-edges (32 rows) by all F columns.
+constexpr int DB = 8;            // basis_emb of the kernel
+constexpr int LDQ = 64 + 8;      // floats per in-edge row of the staged Q: [l][b], padded so that the two k halves of a
+                                 // wavefront read disjoint banks
+
+template <int NT>   // F = 32 NT
+__global__ void __launch_bounds__(256)
+tripD_mfma_fwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
+                      const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_ji,
+                      const int32_t* __restrict__ idx_kj, const float* __restrict__ cos_alpha,
+                      const float* __restrict__ x, const float* __restrict__ Qt, const float* __restrict__ W2, int64_t E,
+                      int S, int kp_cap, int parts, float* __restrict__ a_out, float* __restrict__ Bacc) {
+  constexpr int F = 32 * NT, LDX = F + 32;   // row stride of the staged X: the two k halves read disjoint banks
+  part_t P;
+  if (!centre_part(row_ptr, out_ptr, kp_cap, parts, P)) return;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  float* X_s = reinterpret_cast<float*>(smem_raw);   // [Kp][LDX]
+  float* Q_s = X_s + (size_t)P.Kp * LDX;             // [Kp][LDQ]
+  __shared__ int s_e[64], s_seg[64], s_cnt[64], s_gap[64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < P.Kp * (F / 4); i += 256) {
+    const int p = i / (F / 4), f4 = (i % (F / 4)) * 4;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (p < P.d) v = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + p) * F + f4);
+    *reinterpret_cast<f32x4*>(&X_s[p * LDX + f4]) = v;
+  }
+  for (int i = threadIdx.x; i < P.Kp * 64; i += 256) {
+    const int p = i % P.Kp, lb = i / P.Kp;          // consecutive threads: consecutive rows of one (l, b) line of Qt
+    const int l = lb / DB;
+    float v = 0.f;
+    if (p < P.d && l < S) v = Y_NORM_M[l] * LEG_LEAD[l] * Qt[(int64_t)lb * E + P.r0 + p];
+    Q_s[p * LDQ + lb] = v;
+  }
+  const int kh = lane >> 5, l32 = lane & 31;
+  const int e_loc = l32 >> 3, b = l32 & 7;
+  for (int c0 = P.eb; c0 < P.ee; c0 += 64) {
+    __syncthreads();
+    if (threadIdx.x < 64 && c0 + (int)threadIdx.x < P.ee) {
+      const int e = out_list[P.o0 + c0 + threadIdx.x];
+      const int seg = seg_ptr_ji[e], cnt = seg_ptr_ji[e + 1] - seg;
+      // the segment lists rows r0, r0+1, ... with (at most) the row coming from atom i left out: first slot
+      // whose row is not r0 + slot
+      int lo = 0, hi = cnt;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (idx_kj[seg + mid] == P.r0 + mid) lo = mid + 1;
+        else hi = mid;
+      }
+      s_e[threadIdx.x] = e;
+      s_seg[threadIdx.x] = seg;
+      s_cnt[threadIdx.x] = cnt;
+      s_gap[threadIdx.x] = lo;
+    }
+    __syncthreads();
+    const int n = P.ee - c0 < 64 ? P.ee - c0 : 64;
+    for (int g0 = 4 * wave; g0 < n; g0 += 16) {
+      const int ei = g0 + e_loc;
+      const bool e_ok = ei < n;
+      const int eic = e_ok ? ei : n - 1;
+      const int seg = s_seg[eic], cnt = s_cnt[eic], gap = s_gap[eic];
+      f32x16 acc[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+      for (int kp0 = 0; kp0 < P.Kp / 2; kp0 += 4) {
+        float cs[4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {        // the four cosines first, so that their latencies overlap
+          const int p = 2 * (kp0 + u) + kh;
+          const int slot = p - (p > gap ? 1 : 0);
+          ok[u] = e_ok && p < P.d && p != gap && slot < cnt;
+          cs[u] = cos_alpha[ok[u] ? seg + slot : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int p = 2 * (kp0 + u) + kh;   // < Kp: Kp is a multiple of 16
+          const float* q = Q_s + p * LDQ + b;
+          // monic Legendre polynomials pi_{l+1} = x pi_l - l^2/(4 l^2 - 1) pi_{l-1}; the staged Q carries the rest
+          const float cv = cs[u];
+          float p0 = 1.f, p1 = cv;
+          float av = q[0];
+#pragma unroll
+          for (int l = 1; l < ST; ++l) {
+            av += p1 * q[l * DB];
+            const float p2 = cv * p1 - ((float)(l * l) / (float)(4 * l * l - 1)) * p0;
+            p0 = p1;
+            p1 = p2;
+          }
+          av = ok[u] ? av : 0.f;
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, X_s[p * LDX + t * 32 + l32], acc[t], 0, 0, 0);
+        }
+      }
+      // accumulator register v of lane (kh, l32): row 8 (v / 4) + 4 kh + v % 4 = (edge v / 4 of the group, b = 4 kh + v % 4),
+      // column l32 of the block
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const int f = t * 32 + l32;
+        float w2[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w2[i] = W2[(4 * kh + i) * F + f];
+#pragma unroll
+        for (int eg = 0; eg < 4; ++eg) {
+          const bool ok_e = g0 + eg < n;
+          const int64_t e = s_e[ok_e ? g0 + eg : n - 1];
+          float sum = 0.f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float v = acc[t][4 * eg + i];
+            sum += w2[i] * v;
+            if (ok_e) Bacc[(e * DB + 4 * kh + i) * F + f] = v;
+          }
+          sum += __shfl_xor(sum, 32);
+          if (ok_e && kh == 0) a_out[e * F + f] = sum;
+        }
+      }
+    }
+  }
+}
+
 template <int CB>   // F = 32 CB
 __global__ void __launch_bounds__(MT)
 tripG_mfma_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                   const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_ji,
-                  const float* __restrict__ x, const __bf16* __restrict__ Yb, int C, int kp_cap, int out_half,
+                  const float* __restrict__ x, const __bf16* __restrict__ Yb, int C, int kp_cap, int parts, int out_half,
                   float* __restrict__ A) {
   constexpr int F = 32 * CB;
   part_t P;
-  if (!centre_part(row_ptr, out_ptr, kp_cap, P)) return;
+  if (!centre_part(row_ptr, out_ptr, kp_cap, parts, P)) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   __bf16* XT = reinterpret_cast<__bf16*>(smem_raw);   // XT[f][p], row stride LDP
   // LDP/8 is odd, so the 16-byte reads of 8 lanes with consecutive f fall into 8 different bank groups
@@ -352,9 +481,9 @@ struct rows_t {
 constexpr int GPW = 8;   // row groups per workgroup aimed at (two per wavefront)
 
 __device__ __forceinline__ bool centre_rows(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
-                                            rows_t& P) {
+                                            int parts, rows_t& P) {
   int j, part;
-  atom_and_part(j, part);
+  atom_and_part(parts, j, part);
   P.r0 = row_ptr[j];
   P.d = row_ptr[j + 1] - P.r0;
   P.o0 = out_ptr[j];
@@ -362,7 +491,7 @@ __device__ __forceinline__ bool centre_rows(const int32_t* __restrict__ row_ptr,
   if (P.d <= 0) return false;
   const int groups = (P.d + 7) / 8;
   int nparts = (groups + GPW - 1) / GPW;
-  nparts = nparts < PARTS ? nparts : PARTS;
+  nparts = nparts < parts ? nparts : parts;
   if (part >= nparts) return false;
   const int len = (groups + nparts - 1) / nparts;
   P.gb = part * len;
@@ -391,10 +520,10 @@ __global__ void __launch_bounds__(256)
 tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                     const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_kj,
                     const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ cos_kj,
-                    const float* __restrict__ dz, int S, int kn_cap, float* __restrict__ H) {
+                    const float* __restrict__ dz, int S, int kn_cap, int parts, float* __restrict__ H) {
   constexpr int O = 32 * CB;
   rows_t P;
-  if (!centre_rows(row_ptr, out_ptr, P)) return;
+  if (!centre_rows(row_ptr, out_ptr, parts, P)) return;
   const int Kn = (P.dout + 15) & ~15;
   if (Kn > kn_cap) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -516,11 +645,11 @@ __global__ void __launch_bounds__(256)
 tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                        const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_kj,
                        const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ cos_kj,
-                       const float* __restrict__ U, const float* __restrict__ dz, int S, int kn_cap, int accumulate,
+                       const float* __restrict__ U, const float* __restrict__ dz, int S, int kn_cap, int parts, int accumulate,
                        float* __restrict__ grad_cos_kj) {
   constexpr int O = 16 * KS, LDO = O + 8;
   rows_t P;
-  if (!centre_rows(row_ptr, out_ptr, P)) return;
+  if (!centre_rows(row_ptr, out_ptr, parts, P)) return;
   const int Kn = (P.dout + 31) & ~31;
   if (Kn > kn_cap || P.dout == 0) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -646,6 +775,11 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
 }
 
 int kp_of(const gp_graph* g) { return (g->max_in_degree + 15) & ~15; }
+// Workgroups per centre atom: as many as the atom with the most out-edges (forward kernels: EPP edges each) or
+// in-edges (backward kernels: GPW groups of 8 rows each) needs, at most PARTS.  Launching PARTS everywhere
+// would leave most workgroups without work, and starting a workgroup is not free (1280 atoms x 8: 0.2 ms).
+int parts_out(const gp_graph* g) { const int n = (g->max_out_degree + EPP - 1) / EPP; return n < 1 ? 1 : n > PARTS ? PARTS : n; }
+int parts_in(const gp_graph* g) { const int n = (g->max_in_degree + 8 * GPW - 1) / (8 * GPW); return n < 1 ? 1 : n > PARTS ? PARTS : n; }
 int kn_of(const gp_graph* g) { return (g->max_out_degree + 31) & ~31; }
 // dz of the out-edges (bf16, transposed)
 size_t lds_H(int O, int kn) { return (size_t)(kn + 8) * O * sizeof(__bf16); }
@@ -662,6 +796,38 @@ bool gp_tripG_mfma_usable(const gp_graph* g, int F, int S, int C) {
   return (size_t)F * (kp_of(g) + 8) * sizeof(__bf16) <= LDS_MAX;
 }
 
+bool gp_tripD_mfma_usable(const gp_graph* g, int F, int S, int B) {
+  if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_in_degree <= 0) return false;
+  if (g->n_triplets <= 0) return false;   // the kernel reads cos_alpha[0] for absent triplets
+  if (g->n_atoms > INT32_MAX / PARTS) return false;
+  if (B != DB || F % 32 != 0 || F < 32 || F > 128 || S < 1 || S > ST) return false;
+  return (size_t)kp_of(g) * (F + 32 + LDQ) * sizeof(float) <= 64 * 1024;
+}
+
+int gp_tripD_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Qt,
+                          const float* W2, int F, int S, int B, float* a, float* Bacc) {
+  const int64_t E = g->n_edges, T = g->n_triplets;
+  if (E == 0) return GP_OK;
+  GP_REQUIRE(ctx, gp_tripD_mfma_usable(g, F, S, B), "triplet D (matrix-core form): graph lists or widths not supported");
+  GP_REQUIRE(ctx, g->seg_ptr_ji && g->idx_kj && cos_alpha && x && Qt && W2 && a && Bacc, "triplet D forward: NULL pointer");
+  const int kp_cap = kp_of(g), parts = parts_out(g);
+  const unsigned grid = (unsigned)(g->n_atoms * parts);
+  const size_t lds = (size_t)kp_cap * (F + 32 + LDQ) * sizeof(float);
+  const double Td = (double)T, Ed = (double)E;
+  gp_prof_scope prof(ctx, "tripD_mfma_fwd", Td * 2.0 * (S * B + B * F) + Ed * 2.0 * B * F,
+                     Td * 8.0 + Ed * 4.0 * (F + S * B + B * F + F) + Ed * 4.0);
+#define GP_D_FWD(NT)                                                                                              \
+  tripD_mfma_fwd_kernel<NT><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, \
+                                                             g->idx_kj, cos_alpha, x, Qt, W2, E, S, kp_cap, parts, a, Bacc)
+  if (F == 32) GP_D_FWD(1);
+  else if (F == 64) GP_D_FWD(2);
+  else if (F == 96) GP_D_FWD(3);
+  else GP_D_FWD(4);
+#undef GP_D_FWD
+  GP_LAUNCH_CHECK(ctx, "tripD_mfma_fwd_kernel");
+  return GP_OK;
+}
+
 int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
                           int F, int S, int C, float* A, void* ybuf, size_t ybytes, int out_half) {
   const int64_t E = g->n_edges, T = g->n_triplets;
@@ -669,8 +835,8 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
   GP_REQUIRE(ctx, gp_tripG_mfma_usable(g, F, S, C), "triplet G (matrix-core form): graph lists or widths not supported");
   GP_REQUIRE(ctx, g->seg_ptr_ji && (T == 0 || (g->idx_kj && cos_alpha)) && x && Radt && A && ybuf, "triplet G forward: NULL pointer");
   if (ybytes < gp_tripG_mfma_scratch(E, T)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "triplet G forward: y buffer too small");
-  const int kp_cap = kp_of(g);
-  const unsigned grid = (unsigned)(g->n_atoms * PARTS);
+  const int kp_cap = kp_of(g), parts = parts_out(g);
+  const unsigned grid = (unsigned)(g->n_atoms * parts);
   const double Td = (double)T, Ed = (double)E;
   __bf16* Yb = static_cast<__bf16*>(ybuf);
   {
@@ -678,10 +844,10 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
     const int yt = kp_cap >= YT ? YT : (kp_cap + 63) & ~63;
     if (S <= 7)
       tripG_y_kernel<7><<<grid, yt, 0, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj,
-                                                       cos_alpha, Radt, E, S, C, kp_cap, Yb);
+                                                       cos_alpha, Radt, E, S, C, kp_cap, parts, Yb);
     else
       tripG_y_kernel<8><<<grid, yt, 0, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj,
-                                                       cos_alpha, Radt, E, S, C, kp_cap, Yb);
+                                                       cos_alpha, Radt, E, S, C, kp_cap, parts, Yb);
     GP_LAUNCH_CHECK(ctx, "tripG_y_kernel");
   }
   {
@@ -698,7 +864,7 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
       lds_set = lds;                                                                                              \
     }                                                                                                             \
     tripG_mfma_kernel<CB><<<grid, mt, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, x,  \
-                                                          Yb, C, kp_cap, out_half, A);                            \
+                                                          Yb, C, kp_cap, parts, out_half, A);                     \
   } while (0)
     switch (F / 32) {
       case 1: GP_TRIPG_LAUNCH(1); break;
@@ -726,8 +892,8 @@ int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_al
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, gp_tripG_mfma_bwd_usable(g, O, S), "triplet G backward (matrix-core form): graph lists or widths not supported");
   GP_REQUIRE(ctx, dz && H && (T == 0 || cos_alpha_kj), "triplet G backward: NULL pointer");
-  const int kn_cap = kn_of(g);
-  const unsigned grid = (unsigned)(g->n_atoms * PARTS);
+  const int kn_cap = kn_of(g), parts = parts_in(g);
+  const unsigned grid = (unsigned)(g->n_atoms * parts);
   const size_t lds = lds_H(O, kn_cap);
   gp_prof_scope prof(ctx, "tripG_mfma_H", (double)T * 2.0 * 8 * O, (double)T * 4.0 + 4.0 * E * (O + (double)S * O));
 #define GP_TRIPG_LAUNCH(CB)                                                                                          \
@@ -739,7 +905,7 @@ int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_al
       lds_set = lds;                                                                                                 \
     }                                                                                                                \
     tripG_mfma_H_kernel<CB><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj,     \
-                                                             g->idx_ji_kj, cos_alpha_kj, dz, S, kn_cap, H);          \
+                                                             g->idx_ji_kj, cos_alpha_kj, dz, S, kn_cap, parts, H);   \
   } while (0)
   switch (O / 32) {
     case 1: GP_TRIPG_LAUNCH(1); break;
@@ -758,8 +924,8 @@ int gp_tripG_grad_cos_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
   if (E == 0 || T == 0) return GP_OK;
   GP_REQUIRE(ctx, gp_tripG_mfma_bwd_usable(g, O, S), "grad_cos (matrix-core form): graph lists or widths not supported");
   GP_REQUIRE(ctx, cos_alpha_kj && U && dz && grad_cos_kj, "grad_cos: NULL pointer");
-  const int kn_cap = kn_of(g);
-  const unsigned grid = (unsigned)(g->n_atoms * PARTS);
+  const int kn_cap = kn_of(g), parts = parts_in(g);
+  const unsigned grid = (unsigned)(g->n_atoms * parts);
   const size_t lds = (size_t)kn_cap * (O + 8) * sizeof(__bf16);
   gp_prof_scope prof(ctx, "tripG_mfma_dcos", (double)T * 2.0 * 8 * O, (double)T * 12.0 + 4.0 * E * (O + (double)S * O));
 #define GP_TRIPG_LAUNCH(KS)                                                                                          \
@@ -771,7 +937,7 @@ int gp_tripG_grad_cos_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
       lds_set = lds;                                                                                                 \
     }                                                                                                                \
     tripG_mfma_dcos_kernel<KS><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj,  \
-                                                                g->idx_ji_kj, cos_alpha_kj, U, dz, S, kn_cap,        \
+                                                                g->idx_ji_kj, cos_alpha_kj, U, dz, S, kn_cap, parts, \
                                                                 accumulate, grad_cos_kj);                            \
   } while (0)
   switch (O / 32) {
