@@ -79,6 +79,16 @@ size_t part_bytes_D(const gp_dims* d, int64_t E) {
   return m;
 }
 
+// The matrix-core backward kernel also yields the gradient of W_sbf2, so the forward pass need not keep Bacc
+// (E x basis_emb x int_emb floats).  Forward and backward must take the same decision: it depends only on the
+// context's switch, the widths and the graph.
+bool bwd_mfma_D(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
+  if (ctx->trip_mfma == 0) return false;
+  const int F = d->int_emb, S = d->num_spherical, B = d->basis_emb;
+  return gp_tripD_mfma_usable(g, F, S, B) && gp_tripD_mfma_bwd_usable(g, F, S, B) &&
+         gp_tripD_mfma_bwd_scratch(g, F) <= part_bytes_D(d, g->n_edges);
+}
+
 size_t carve_scratch_D(void* p, const gp_dims* d, int64_t E, scratch_D* s) {
   gp_carver c(p);
   const size_t H = d->emb, F = d->int_emb, B = d->basis_emb, S = d->num_spherical, R = d->num_radial;
@@ -202,7 +212,8 @@ int gp_block_forward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, 
   GP_TRY(gp_gemm_nn(ctx, s.xg, w->W_down, E, F, H, e));
   GP_TRY(gp_tripD_project_radial(ctx, basis->rad, w->W_sbf1, E, S, R, B, s.Q));
   if (ctx->trip_mfma != 0 && gp_tripD_mfma_usable(graph, F, S, B))
-    GP_TRY(gp_tripD_forward_mfma(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a, s.Bacc));
+    GP_TRY(gp_tripD_forward_mfma(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a,
+                                 bwd_mfma_D(ctx, dims, graph) ? nullptr : s.Bacc));
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a, s.Bacc));
   e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = x_ji; e.out = s.h0;
@@ -307,10 +318,15 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
     GP_TRY(gp_gemm_nt(ctx, dzcur, w->W_up, E, F, H, e));                                     // da
   }
   // triplet interaction
-  GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, s.x_kj, s.Q, w->W_sbf2, sc.dF1, s.z_dn, F, S, B,
-                           sc.dF2, sc.dQ));                                                   // dz_dn, dQ
-  GP_TRY(gp_tripD_weight_grads(ctx, sc.dF1, s.Bacc, basis->rad, sc.dQ, E, F, S, R, B, gw->W_sbf2, gw->W_sbf1,
-                               sc.part, sc.part_bytes));
+  const bool bwd_mfma = bwd_mfma_D(ctx, dims, graph);
+  if (bwd_mfma)
+    GP_TRY(gp_tripD_backward_mfma(ctx, graph, basis->cos_alpha_kj, s.x_kj, s.Q, w->W_sbf2, sc.dF1, s.z_dn, F, S, B,
+                                  sc.dF2, sc.dQ, gw->W_sbf2, sc.part, sc.part_bytes));        // dz_dn, dQ, dW_sbf2
+  else
+    GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, s.x_kj, s.Q, w->W_sbf2, sc.dF1, s.z_dn, F, S, B,
+                             sc.dF2, sc.dQ));                                                 // dz_dn, dQ
+  GP_TRY(gp_tripD_weight_grads(ctx, sc.dF1, bwd_mfma ? nullptr : s.Bacc, basis->rad, sc.dQ, E, F, S, R, B, gw->W_sbf2,
+                               gw->W_sbf1, sc.part, sc.part_bytes));
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dF2, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes); },
                     {sc.dF2}));
   {

@@ -26,6 +26,13 @@ int gp_tripD_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
 int gp_tripD_backward(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* x, const float* Q,
                       const float* W2, const float* grad_a, const float* z, int F, int S, int B,
                       float* grad_x, float* grad_Q);
+// Backward on the fp32 matrix cores, per centre atom: grad_x, grad_Q as gp_tripD_backward, and grad_W2 from the
+// same pass (no Bacc needed).  part: gp_tripD_mfma_bwd_scratch bytes.
+bool gp_tripD_mfma_bwd_usable(const gp_graph* g, int F, int S, int B);
+size_t gp_tripD_mfma_bwd_scratch(const gp_graph* g, int F);
+int gp_tripD_backward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* x, const float* Qt,
+                           const float* W2, const float* grad_a, const float* z, int F, int S, int B, float* grad_x,
+                           float* grad_Q, float* grad_W2, float* part, size_t part_bytes);
 
 // grad_W2[b,f] = sum_e grad_a[e,f] Bacc[e,b,f];  grad_W1[l*R+n,b] = sum_e rad[e,l*R+n] grad_Q[e,l*B+b]
 size_t gp_tripD_wgrad_scratch(int64_t E, int F, int S, int R, int B);

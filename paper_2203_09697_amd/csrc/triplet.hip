@@ -485,9 +485,11 @@ int gp_tripD_weight_grads(gp_ctx* ctx, const float* grad_a, const float* Bacc, c
     GP_HIP(ctx, hipMemsetAsync(grad_W1, 0, sizeof(float) * S * R * B, ctx->stream));
     return GP_OK;
   }
-  w2grad_part_kernel<<<blocks, 256, 0, ctx->stream>>>(grad_a, Bacc, E, F, B, per, part);
-  GP_LAUNCH_CHECK(ctx, "w2grad_part_kernel");
-  GP_TRY(gp_reduce_parts(ctx, part, blocks, (int64_t)B * F, grad_W2));
+  if (Bacc) {   // NULL: grad_W2 comes from the matrix-core backward kernel
+    w2grad_part_kernel<<<blocks, 256, 0, ctx->stream>>>(grad_a, Bacc, E, F, B, per, part);
+    GP_LAUNCH_CHECK(ctx, "w2grad_part_kernel");
+    GP_TRY(gp_reduce_parts(ctx, part, blocks, (int64_t)B * F, grad_W2));
+  }
   w1grad_part_kernel<<<blocks, 256, 0, ctx->stream>>>(rad, grad_Q, E, S, R, B, per, part);
   GP_LAUNCH_CHECK(ctx, "w1grad_part_kernel");
   GP_TRY(gp_reduce_parts(ctx, part, blocks, (int64_t)S * R * B, grad_W1));

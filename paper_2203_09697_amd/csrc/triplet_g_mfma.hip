@@ -23,6 +23,7 @@
 // Operands are rounded to bf16, sums are fp32.  Needs the centre-atom lists of gp_graph.
 #include <stdarg.h>
 
+#include "gemm.h"
 #include "triplet.h"
 
 namespace {
@@ -327,7 +328,7 @@ tripD_mfma_fwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
           for (int i = 0; i < 4; ++i) {
             const float v = acc[t][4 * eg + i];
             sum += w2[i] * v;
-            if (ok_e) Bacc[(e * DB + 4 * kh + i) * F + f] = v;
+            if (ok_e && Bacc) Bacc[(e * DB + 4 * kh + i) * F + f] = v;
           }
           sum += __shfl_xor(sum, 32);
           if (ok_e && kh == 0) a_out[e * F + f] = sum;
@@ -637,6 +638,230 @@ tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restri
   }
 }
 
+// Backward of the Hadamard form (variant D) for one centre atom on the fp32 matrix cores.
+//   H[e', l, f]   = sum_n Y_l0(cos alpha_(e', n)) ga[out(n), f]          MFMA rows (4 in-edge rows) x (l = 0..7),
+//                                                                        contraction over the out-edge positions n
+//   D[e', b, f]   = sum_l Q[e', l, b] H[e', l, f]
+//   gx[e', f]     = SiLU'(z[e', f]) sum_b W2[b, f] D[e', b, f]
+//   gQ[e', l, b]  = sum_f W2[b, f] x[e', f] H[e', l, f]
+//   gW2[b, f]     = sum_e' x[e', f] D[e', b, f]                          (one partial sum per workgroup)
+// which is the chain rule of a[e, f] = sum_t x[kj(t), f] sum_b W2[b, f] sum_l Y_l0(cos alpha_t) Q[kj(t), l, b] regrouped
+// by the source edge e' = kj(t).  ga of the out-edges is staged in LDS once per workgroup; Y_l0 is evaluated in
+// registers (a lane keeps one l); nothing of size T or E x B x F is read or written.
+template <int NT>   // F = 32 NT
+__global__ void __launch_bounds__(256, 2)   // three workgroups per CU would spill
+tripD_mfma_bwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
+                      const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_kj,
+                      const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ cos_kj,
+                      const float* __restrict__ x, const float* __restrict__ Qt, const float* __restrict__ W2,
+                      const float* __restrict__ ga, const float* __restrict__ z, int64_t E, int S, int kn_cap,
+                      int parts, float* __restrict__ gx, float* __restrict__ gQ, float* __restrict__ w2part) {
+  constexpr int F = 32 * NT, LDZ = F + 32;   // the two k halves of a wavefront read disjoint banks
+  constexpr int LDU = F + 4;
+  float* wp = w2part + (int64_t)blockIdx.x * DB * F;
+  rows_t P;
+  const bool work = centre_rows(row_ptr, out_ptr, parts, P);
+  const int Kn = work ? (P.dout + 15) & ~15 : 0;
+  if (!work || Kn > kn_cap) {
+    for (int i = threadIdx.x; i < DB * F; i += 256) wp[i] = 0.f;
+    return;
+  }
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  float* Q_w = reinterpret_cast<float*>(smem_raw);   // per wavefront: [4 rows][LDQ], element (l, b) at l * 8 + b
+  float* U_w = Q_w + 4 * 4 * LDQ;                    // per wavefront: x H of one row, [8 l][LDU]
+  float* Z_s = U_w + 4 * 8 * LDU;                    // [Kn][LDZ]; reused for the weight-gradient partial sums
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int32_t* outs = out_list + P.o0;
+  for (int i = threadIdx.x; i < Kn * (F / 4); i += 256) {
+    const int n = i / (F / 4), f4 = (i % (F / 4)) * 4;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (n < P.dout) v = *reinterpret_cast<const f32x4*>(ga + (int64_t)outs[n] * F + f4);
+    *reinterpret_cast<f32x4*>(&Z_s[n * LDZ + f4]) = v;
+  }
+  __syncthreads();
+
+  const int kh = lane >> 5, l32 = lane & 31;
+  const int l = l32 & 7;
+  float q[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) q[i] = l < S ? Y_NORM_M[l] * LEG_Q[l][i] : 0.f;
+  const bool odd = l & 1;
+  float w2[DB][NT], dw2[DB][NT];
+#pragma unroll
+  for (int b = 0; b < DB; ++b)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      w2[b][t] = W2[b * F + t * 32 + l32];
+      dw2[b][t] = 0.f;
+    }
+  float* Qw = Q_w + wave * 4 * LDQ;
+  float* Uw = U_w + wave * 8 * LDU;
+  float w2s[4 * NT];   // W2[b = lane / 8][slice lane % 8 of the columns]
+#pragma unroll
+  for (int k = 0; k < 4 * NT; ++k) w2s[k] = W2[(lane >> 3) * F + (lane & 7) * (4 * NT) + k];
+  const int nb = Kn / 16;   // batches of 8 k-steps (16 out-edge positions)
+
+  // a wavefront takes 4 in-edge rows (32 MFMA rows) at a time
+  for (int sg = 2 * P.gb + wave; sg < 2 * P.ge && sg * 4 < P.d; sg += 4) {
+    const int pa = sg * 4 + (l32 >> 3);
+    const bool pv = pa < P.d;
+    const rowinfo_t ri = row_info(seg_ptr_kj, idx_ji_kj, outs, P.r0 + (pv ? pa : P.d - 1));
+    // Q of the 4 rows: lane (row lane % 4, b = (lane / 4) % 8, l half lane / 32) fetches 4 values of l; they go to LDS
+    // after the main loop
+    float qv[4];
+    {
+      const int p = sg * 4 + (lane & 3), b = (lane >> 2) & 7;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int lq = 4 * kh + i;
+        qv[i] = (p < P.d && lq < S) ? Qt[(int64_t)(lq * DB + b) * E + P.r0 + p] : 0.f;
+      }
+    }
+    // x and z of the 4 rows, for the epilogue
+    float xv[4][NT], zv[4][NT];
+#pragma unroll
+    for (int eg = 0; eg < 4; ++eg) {
+      const int p = sg * 4 + eg;
+      const int64_t e = P.r0 + (p < P.d ? p : P.d - 1);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        xv[eg][t] = p < P.d ? x[e * F + t * 32 + l32] : 0.f;
+        zv[eg][t] = z ? z[e * F + t * 32 + l32] : 0.f;
+      }
+    }
+    f32x16 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+    // cosines of batch bt (2 marks "no triplet"), fetched one batch ahead
+    auto load_c = [&](int bt, float (&c)[8]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int n = bt * 16 + 2 * u + kh;
+        const int slot = n - (n > ri.gap ? 1 : 0);
+        const bool valid = bt < nb && pv && n != ri.gap && slot < ri.cnt;
+        const float cv = cos_kj[valid ? ri.seg + slot : 0];   // unconditional load, index 0 when unused
+        c[u] = valid ? cv : 2.f;
+      }
+    };
+    float cn[8];
+    load_c(0, cn);
+    for (int bt = 0; bt < nb; ++bt) {
+      float cc[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) cc[u] = cn[u];
+      load_c(bt + 1, cn);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool valid = cc[u] <= 1.5f;
+        const float cv = valid ? cc[u] : 0.f;
+        const float t2 = cv * cv;
+        const float yv = (odd ? cv : 1.f) * (q[0] + t2 * (q[1] + t2 * (q[2] + t2 * q[3])));
+        const float y = valid ? yv : 0.f;
+        const float* zr = Z_s + (bt * 16 + 2 * u + kh) * LDZ + l32;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(y, zr[t * 32], acc[t], 0, 0, 0);
+      }
+    }
+
+    wave_lds_sync();   // the previous pass's reads of Qw are done
+    {
+      const int pr = lane & 3, b = (lane >> 2) & 7;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Qw[pr * LDQ + (4 * kh + i) * DB + b] = qv[i];
+    }
+    wave_lds_sync();
+
+    // accumulator register v of lane (kh, l32): row 8 (v/4) + 4 kh + v%4 = (in-edge row v/4 of the pass, l = 4 kh + v%4),
+    // column l32 of the block
+#pragma unroll
+    for (int eg = 0; eg < 4; ++eg) {
+      const int p = sg * 4 + eg;
+      const bool ok = p < P.d;
+      const int64_t e = P.r0 + (ok ? p : P.d - 1);
+      float D[DB][NT];
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) D[b][t] = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float* qr = Qw + eg * LDQ + (4 * kh + i) * DB;
+        const f32x4 qa = *reinterpret_cast<const f32x4*>(qr), qb = *reinterpret_cast<const f32x4*>(qr + 4);
+        const float qq[DB] = {qa[0], qa[1], qa[2], qa[3], qb[0], qb[1], qb[2], qb[3]};
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const float h = acc[t][4 * eg + i];
+          Uw[(4 * kh + i) * LDU + t * 32 + l32] = xv[eg][t] * h;
+#pragma unroll
+          for (int b = 0; b < DB; ++b) D[b][t] += qq[b] * h;
+        }
+      }
+      float dxp[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        float sum = 0.f;
+#pragma unroll
+        for (int b = 0; b < DB; ++b) {
+          sum += w2[b][t] * D[b][t];
+          dw2[b][t] += xv[eg][t] * D[b][t];
+        }
+        dxp[t] = sum + __shfl_xor(sum, 32);
+      }
+      if (ok && kh == 0) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) gx[e * F + t * 32 + l32] = z ? dxp[t] * dsilu_f(zv[eg][t]) : dxp[t];
+      }
+      // gQ[l, b] = sum_f W2[b, f] U[l, f]: lane (b = lane / 8, slice fs = lane % 8 of the columns) forms its part of all
+      // 8 sums, then the 8 lanes of a b exchange them, halving the number of values each time; lane fs ends with l = fs
+      wave_lds_sync();
+      float gq[8];
+#pragma unroll
+      for (int lq = 0; lq < 8; ++lq) {
+        const float* ur = Uw + lq * LDU + (lane & 7) * (4 * NT);
+        float sum = 0.f;
+#pragma unroll
+        for (int k4 = 0; k4 < NT; ++k4) {
+          const f32x4 uv = *reinterpret_cast<const f32x4*>(ur + 4 * k4);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) sum += w2s[4 * k4 + c] * uv[c];
+        }
+        gq[lq] = sum;
+      }
+#pragma unroll
+      for (int m = 4, half = 4; m >= 1; m >>= 1, half >>= 1) {
+        const bool up = (lane & m) != 0;
+#pragma unroll
+        for (int i = 0; i < half; ++i) {
+          const float send = up ? gq[i] : gq[i + half];
+          const float keep = up ? gq[i + half] : gq[i];
+          gq[i] = keep + __shfl_xor(send, m);
+        }
+      }
+      if (ok && (lane & 7) < S) gQ[(e * S + (lane & 7)) * DB + (lane >> 3)] = gq[0];
+      wave_lds_sync();   // Uw is rewritten for the next row
+      __builtin_amdgcn_sched_barrier(0);   // keep the four rows' epilogues apart: interleaved they need twice the registers
+    }
+  }
+
+  // weight-gradient partial sum of the workgroup: 8 slots (wavefront, k half), summed in a fixed order
+  __syncthreads();
+  float* red = Z_s;
+#pragma unroll
+  for (int b = 0; b < DB; ++b)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) red[((wave * 2 + kh) * DB + b) * F + t * 32 + l32] = dw2[b][t];
+  __syncthreads();
+  for (int i = threadIdx.x; i < DB * F; i += 256) {
+    float sum = red[i];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) sum += red[k * DB * F + i];
+    wp[i] = sum;
+  }
+}
+
 // grad_cos_kj[slot of (e', e)] (+)= sum_l Y_l0'(cos) W[(e', l), e],  W = U_j . dz_out^T  (rows (in-edge row, l),
 // columns out-edge positions n, contraction over o).  U rows go straight from memory to A fragments,
 // dz of the out-edges is staged in LDS (bf16); the derivative weights are applied to the accumulators.
@@ -809,13 +1034,13 @@ int gp_tripD_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
   const int64_t E = g->n_edges, T = g->n_triplets;
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, gp_tripD_mfma_usable(g, F, S, B), "triplet D (matrix-core form): graph lists or widths not supported");
-  GP_REQUIRE(ctx, g->seg_ptr_ji && g->idx_kj && cos_alpha && x && Qt && W2 && a && Bacc, "triplet D forward: NULL pointer");
+  GP_REQUIRE(ctx, g->seg_ptr_ji && g->idx_kj && cos_alpha && x && Qt && W2 && a, "triplet D forward: NULL pointer");
   const int kp_cap = kp_of(g), parts = parts_out(g);
   const unsigned grid = (unsigned)(g->n_atoms * parts);
   const size_t lds = (size_t)kp_cap * (F + 32 + LDQ) * sizeof(float);
   const double Td = (double)T, Ed = (double)E;
   gp_prof_scope prof(ctx, "tripD_mfma_fwd", Td * 2.0 * (S * B + B * F) + Ed * 2.0 * B * F,
-                     Td * 8.0 + Ed * 4.0 * (F + S * B + B * F + F) + Ed * 4.0);
+                     Td * 8.0 + Ed * 4.0 * (F + S * B + (Bacc ? B * F : 0) + F) + Ed * 4.0);
 #define GP_D_FWD(NT)                                                                                              \
   tripD_mfma_fwd_kernel<NT><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, \
                                                              g->idx_kj, cos_alpha, x, Qt, W2, E, S, kp_cap, parts, a, Bacc)
@@ -876,6 +1101,56 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
     GP_LAUNCH_CHECK(ctx, "tripG_mfma_kernel");
   }
   return GP_OK;
+}
+
+namespace {
+size_t lds_D_bwd(int F, int kn) {
+  const size_t zs = (size_t)kn * (F + 32), red = (size_t)8 * DB * F;
+  return (4 * 4 * LDQ + 4 * 8 * (F + 4) + (zs > red ? zs : red)) * sizeof(float);
+}
+}  // namespace
+
+bool gp_tripD_mfma_bwd_usable(const gp_graph* g, int F, int S, int B) {
+  if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_out_degree <= 0) return false;
+  if (g->n_triplets <= 0) return false;   // the kernel reads cos_alpha_kj[0] for absent triplets
+  if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS) return false;
+  if (B != DB || F % 32 != 0 || F < 32 || F > 128 || S < 1 || S > ST) return false;
+  const int kn = (g->max_out_degree + 15) & ~15;
+  return lds_D_bwd(F, kn) <= 64 * 1024;
+}
+
+size_t gp_tripD_mfma_bwd_scratch(const gp_graph* g, int F) {
+  return gp_align((size_t)g->n_atoms * parts_in(g) * DB * F * sizeof(float));
+}
+
+int gp_tripD_backward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* x, const float* Qt,
+                           const float* W2, const float* grad_a, const float* z, int F, int S, int B, float* grad_x,
+                           float* grad_Q, float* grad_W2, float* part, size_t part_bytes) {
+  const int64_t E = g->n_edges, T = g->n_triplets;
+  if (E == 0) return GP_OK;
+  GP_REQUIRE(ctx, gp_tripD_mfma_bwd_usable(g, F, S, B), "triplet D backward (matrix-core form): graph lists or widths not supported");
+  GP_REQUIRE(ctx, cos_alpha_kj && x && Qt && W2 && grad_a && grad_x && grad_Q && grad_W2, "triplet D backward: NULL pointer");
+  if (!part || part_bytes < gp_tripD_mfma_bwd_scratch(g, F))
+    return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "triplet D backward: scratch too small");
+  const int kn_cap = (g->max_out_degree + 15) & ~15, parts = parts_in(g);
+  const unsigned grid = (unsigned)(g->n_atoms * parts);
+  const size_t lds = lds_D_bwd(F, kn_cap);
+  const double Td = (double)T, Ed = (double)E;
+  {
+    gp_prof_scope prof(ctx, "tripD_mfma_bwd", Td * 2.0 * 8 * F + Ed * 2.0 * (3.0 * 8 * DB * F + 2.0 * DB * F),
+                       Td * 4.0 + Ed * 4.0 * (4.0 * F + 2.0 * S * DB));
+#define GP_D_BWD(NT)                                                                                                 \
+  tripD_mfma_bwd_kernel<NT><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj,    \
+                                                             g->idx_ji_kj, cos_alpha_kj, x, Qt, W2, grad_a, z, E, S, \
+                                                             kn_cap, parts, grad_x, grad_Q, part)
+    if (F == 32) GP_D_BWD(1);
+    else if (F == 64) GP_D_BWD(2);
+    else if (F == 96) GP_D_BWD(3);
+    else GP_D_BWD(4);
+#undef GP_D_BWD
+    GP_LAUNCH_CHECK(ctx, "tripD_mfma_bwd_kernel");
+  }
+  return gp_reduce_parts(ctx, part, (int)grid, (int64_t)DB * F, grad_W2);
 }
 
 bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S) {

@@ -151,11 +151,29 @@ def test_block_D_cfg1_two_blocks_zero_bias(lib, ctx):
     _block_parity(lib, ctx, synth.get_workload("cfg1"), 2, n_blocks=2, bias_scale=0.0)
 
 
-def test_block_D_cfg2_shape_two_graphs(lib, ctx):
+@pytest.fixture
+def triplet_form(lib, ctx, request):
+    # 0: per-edge vector kernels, -1: the library's choice (matrix-core kernels where the widths allow)
+    lib.gp_set_triplet_mfma(ctx, request.param)
+    yield request.param
+    lib.gp_set_triplet_mfma(ctx, -1)
+
+
+@pytest.mark.parametrize("triplet_form", [-1, 0], indirect=True)
+def test_block_D_cfg2_shape_two_graphs(lib, ctx, triplet_form):
     # configuration-2 layer widths and neighbour cap on 2 of its 16 structures (oracle in seconds)
     w = synth.get_workload("cfg2")
     pos_gptr = synth.slab_adsorbate_positions(2, 4, 4, 4, 16, seed=5)
     _block_parity(lib, ctx, w, 5, n_blocks=2, pos_gptr=pos_gptr)
+
+
+@pytest.mark.parametrize("int_emb,num_spherical", [(32, 7), (96, 8), (128, 3), (64, 1)])
+def test_block_D_matrix_core_widths(lib, ctx, int_emb, num_spherical):
+    # every column-block count of the per-centre-atom fp32 matrix-core kernels (basis_emb 8), with fewer and with
+    # all 8 spherical orders, on one capped structure
+    w = synth.get_workload("cfg2", emb=64, int_emb=int_emb, num_spherical=num_spherical, n_res_before=1, n_res_after=1)
+    pos_gptr = synth.slab_adsorbate_positions(1, 4, 4, 4, 16, seed=9)
+    _block_parity(lib, ctx, w, 6, n_blocks=1, pos_gptr=pos_gptr)
 
 
 def test_block_D_odd_widths(lib, ctx):
