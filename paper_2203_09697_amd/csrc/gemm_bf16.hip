@@ -350,6 +350,36 @@ __device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[
                                               int wm0, int wn0, int split) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kh = lane >> 5, l32 = lane & 31;
+  if constexpr (MODE != MODE_TN && NB % 2 == 0) {
+    // Two blocks side by side (32 rows x 64 columns): 16 lanes cover 64 consecutive columns of a row, so a store
+    // instruction writes whole 128-byte lines of a bf16 matrix (two per row of an fp32 one) instead of halves.
+    float* stage = smem + wave * (32 * EPI_LD2);
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; j += 2) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD2 + jj * 32 + l32] = acc[i][j + jj][v];
+        wave_lds_sync();
+#pragma unroll 1
+        for (int it = 0; it < 8; ++it) {
+          const int r = it * 4 + (lane >> 4), c4 = (lane & 15) * 4;
+          const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[r * EPI_LD2 + c4]);
+          const int64_t row = m0 + wm0 + i * 32 + r;
+          const int col = n0 + wn0 + j * 32 + c4;
+          if (row >= g.M || col >= g.N) continue;
+          if (g.vecC) epilogue_store4(g.epi, row, col, g.N, v4);
+          else
+            for (int c = 0; c < 4; ++c)
+              if (col + c < g.N) epilogue_store(g.epi, row, col + c, g.N, v4[c]);
+        }
+        wave_lds_sync();
+      }
+    return;
+  }
   float* stage = smem + wave * (32 * EPI_LD);
 #pragma unroll
   for (int i = 0; i < MB; ++i)
@@ -619,7 +649,7 @@ int launch_hh(gp_ctx* ctx, gemm_args& g, int splits) {
   gp_prof_scope prof(ctx, name, 2.0 * mnk,
                      2.0 * (double)g.M * g.K + 2.0 * (double)g.K * g.N + 4.0 * (double)g.M * g.N * (MODE == MODE_TN ? splits : 1));
   constexpr size_t lds_main = sizeof(__bf16) * 2 * (size_t)(BM + BN) * LDK;
-  constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD;
+  constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD2;
   constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
   static_assert(lds <= 64 * 1024, "two slabs fit the default dynamic LDS limit");
   gemm_hh_kernel<BM, BN, WMS, WNS, MODE><<<grid, THREADS, lds, ctx->stream>>>(g);
@@ -784,7 +814,7 @@ int launch_dl(gp_ctx* ctx, gemm_args& g) {
   gp_prof_scope prof(ctx, name, 2.0 * mnk, 2.0 * (double)g.M * g.K + 2.0 * (double)g.K * g.N + 4.0 * (double)g.M * g.N);
   constexpr int NW = WMS * WNS;
   constexpr size_t lds_main = (size_t)STAGES * (BM + BN) * BK * 2;
-  constexpr size_t lds_epi = sizeof(float) * NW * 32 * EPI_LD;
+  constexpr size_t lds_epi = sizeof(float) * NW * 32 * EPI_LD2;
   constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
   static_assert((NW == 8 ? 1 : 2) * lds <= 160 * 1024, "fits the compute unit's LDS");
   static bool raised = false;
@@ -814,7 +844,7 @@ int launch_v(gp_ctx* ctx, gemm_args& g, int splits) {
                      (ABF ? 2.0 : 4.0) * (double)g.M * g.K + (BBF ? 2.0 : 4.0) * (double)g.K * g.N +
                          4.0 * (double)g.M * g.N * (MODE == MODE_TN ? splits : 1));
   constexpr size_t lds_main = sizeof(__bf16) * (size_t)(BM + BN) * LDK;
-  constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD;
+  constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD2;
   constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
   static_assert(lds <= 64 * 1024, "tile fits the default dynamic LDS limit");
   gemm_bf16_kernel<BM, BN, WMS, WNS, MODE, VEC, ABF, BBF><<<grid, THREADS, lds, ctx->stream>>>(g);

@@ -10,6 +10,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int THREADS = 256;
 constexpr int EPI_LD = 36;             // row stride of a wavefront's 32x32 staging block (floats)
+constexpr int EPI_LD2 = 68;            // ... of a 32x64 staging block (two blocks side by side)
 enum { MODE_NN = 0, MODE_NT = 1, MODE_TN = 2 };
 
 struct gemm_args {
