@@ -98,6 +98,19 @@ __device__ __forceinline__ int64_t y_offset(int seg, int e) {   // in bf16 eleme
   return ((int64_t)seg + 16 * (int64_t)e) * CP;
 }
 
+// coefficient of x^k in the Legendre polynomial P_l, l <= 7
+__host__ __device__ constexpr float leg_mono(int l, int k) {
+  constexpr float T[8][8] = {{1.f},
+                             {0.f, 1.f},
+                             {-0.5f, 0.f, 1.5f},
+                             {0.f, -1.5f, 0.f, 2.5f},
+                             {0.375f, 0.f, -3.75f, 0.f, 4.375f},
+                             {0.f, 1.875f, 0.f, -8.75f, 0.f, 7.875f},
+                             {-0.3125f, 0.f, 6.5625f, 0.f, -19.6875f, 0.f, 14.4375f},
+                             {0.f, -2.1875f, 0.f, 19.6875f, 0.f, -43.3125f, 0.f, 26.8125f}};
+  return T[l][k];
+}
+
 template <int SM>   // loops over l run to SM >= num_spherical (rows above num_spherical are zero)
 __global__ void __launch_bounds__(YT, 3)   // three workgroups per CU: 168 registers (a few spilled) beat two at 192
 tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
@@ -127,11 +140,29 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
         for (int pi = 0; pi < 8; ++pi) {
           const int p = 8 * pg + pi, c = cp + 8 * cc;
           const bool ok = active && l < S && c < C && p < P.d;
-          // pre-multiplied by the normalisation of Y_l0 and the leading coefficient of P_l (see below)
+          // pre-multiplied by the normalisation of Y_l0
           // unconditional load from a clamped (valid) address: no branch around it
           const float rv = Radt[(int64_t)((l < S ? l : S - 1) * C + (c < C ? c : C - 1)) * E + P.r0 + (p < P.d ? p : P.d - 1)];
-          rad[l][cc][pi] = ok ? Y_NORM_M[l] * LEG_LEAD[l] * rv : 0.f;
+          rad[l][cc][pi] = rv * (ok ? Y_NORM_M[l] : 0.f);   // the product uses rv on every path: the load cannot sink under a branch
         }
+    // From the Legendre expansion sum_l rad[l] P_l(x) to powers of x, once per position and c: the polynomial is then
+    // evaluated per triplet by Horner's rule, SM - 1 multiply-adds instead of a recurrence plus SM of them.  (The
+    // result is rounded to bf16; the cancellation in the power basis costs a few units of fp32 rounding.)
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+      for (int pi = 0; pi < 8; ++pi) {
+        float m[SM];
+#pragma unroll
+        for (int k = 0; k < SM; ++k) {
+          float sum = 0.f;
+#pragma unroll
+          for (int l = k; l < SM; l += 2) sum += leg_mono(l, k) * rad[l][cc][pi];
+          m[k] = sum;
+        }
+#pragma unroll
+        for (int k = 0; k < SM; ++k) rad[k][cc][pi] = m[k];
+      }
     for (int c0 = P.eb; c0 < P.ee; c0 += 64) {
       __syncthreads();
       if (threadIdx.x < 64 && c0 + (int)threadIdx.x < P.ee) {
@@ -153,8 +184,15 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
       __syncthreads();
       const int n = P.ee - c0 < 64 ? P.ee - c0 : 64;
       if (!active) continue;
-      // cosines of the 8 positions for edge ei of the chunk (0 and an unset mask bit where there is no triplet)
-      auto load_cos = [&](int ei, float (&cs)[8], unsigned& vmask) {
+      // Cosines of the 8 positions for edge ei of the chunk (0 and an unset mask bit where there is no triplet).  The 8
+      // threads of a position group need the same 8 cosines: thread cp fetches those of the group's edge number
+      // k0 + cp, and the group hands them round with lane exchanges while it works through 8 edges.  Loads and
+      // stores complete through one counter on this target, so a wait for loads also waits for every store issued
+      // before: one wait per 8 edges instead of one per edge.
+      if (e_off >= n) continue;
+      const int n_mine = (n - e_off + e_step - 1) / e_step;   // edges e_off, e_off + e_step, ... < n
+      auto load_cos = [&](int k, float (&cs)[8], unsigned& vmask) __attribute__((always_inline)) {
+        const int ei = e_off + (k < n_mine ? k : n_mine - 1) * e_step;   // clamped: loads stay unconditional
         const int seg = s_seg[ei], cnt = s_cnt[ei], gap = s_gap[ei];
         vmask = 0;
 #pragma unroll
@@ -162,47 +200,48 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
           const int p = 8 * pg + pi;
           const int q = p - (p > gap ? 1 : 0);
           const bool valid = p != gap && q < cnt;
-          cs[pi] = valid ? cos_alpha[seg + q] : 0.f;
+          cs[pi] = cos_alpha[valid ? seg + q : 0];   // index 0 exists: the kernel is not launched for T = 0
           vmask |= (valid ? 1u : 0u) << pi;
         }
       };
-      if (e_off >= n) continue;
       float cs_next[8];
       unsigned vm_next;
-      load_cos(e_off, cs_next, vm_next);
-      for (int ei = e_off; ei < n; ei += e_step) {
-        float cs[8];
-        const unsigned vm = vm_next;
+      load_cos(cp, cs_next, vm_next);
+      for (int k0 = 0; k0 < n_mine; k0 += 8) {
+        float cs_mine[8];
+        const unsigned vm_mine = vm_next;
 #pragma unroll
-        for (int pi = 0; pi < 8; ++pi) cs[pi] = cs_next[pi];
-        if (ei + e_step < n) load_cos(ei + e_step, cs_next, vm_next);   // in flight during the arithmetic below
-        float y[2][8];
+        for (int pi = 0; pi < 8; ++pi) cs_mine[pi] = cs_next[pi];
+        if (k0 + 8 < n_mine) load_cos(k0 + 8 + cp, cs_next, vm_next);   // in flight during the 8 edges below
+        const int jn = n_mine - k0 < 8 ? n_mine - k0 : 8;
+#pragma unroll 1
+        for (int jj = 0; jj < jn; ++jj) {
+          const int src = (int)(threadIdx.x & 63 & ~7) | jj;
+          const unsigned vm = (unsigned)__shfl((int)vm_mine, src);
+          const int ei = e_off + (k0 + jj) * e_step;
+          float y[2][8];
 #pragma unroll
-        for (int pi = 0; pi < 8; ++pi) {
-          // monic Legendre polynomials: pi_0 = 1, pi_1 = x, pi_{l+1} = x pi_l - l^2/(4 l^2 - 1) pi_{l-1};
-          // P_l = LEG_LEAD[l] pi_l.  Starting from pi_0 = 0 where there is no triplet zeroes the sums.
-          const float v = ((vm >> pi) & 1u) ? 1.f : 0.f;
-          float p0 = v, p1 = v * cs[pi];
-          float a0 = p0 * rad[0][0][pi], a1 = p0 * rad[0][1][pi];
+          for (int pi = 0; pi < 8; ++pi) {
+            const bool valid = (vm >> pi) & 1u;
+            const float x = __shfl(cs_mine[pi], src);
+            float a0 = rad[SM - 1][0][pi], a1 = rad[SM - 1][1][pi];
 #pragma unroll
-          for (int l = 1; l < SM; ++l) {
-            a0 += p1 * rad[l][0][pi];
-            a1 += p1 * rad[l][1][pi];
-            const float p2 = cs[pi] * p1 - ((float)(l * l) / (float)(4 * l * l - 1)) * p0;
-            p0 = p1;
-            p1 = p2;
+            for (int k = SM - 2; k >= 0; --k) {
+              a0 = a0 * x + rad[k][0][pi];
+              a1 = a1 * x + rad[k][1][pi];
+            }
+            y[0][pi] = valid ? a0 : 0.f;   // no triplet: zero row of the operand
+            y[1][pi] = valid ? a1 : 0.f;
           }
-          y[0][pi] = a0;
-          y[1][pi] = a1;
-        }
-        // c = cp and cp + 8: the 8 threads of a position group write 128 contiguous bytes per store
-        __bf16* dst = Yb + y_offset(s_seg[ei], s_e[ei]) + (int64_t)pg * (CP * 8) + cp * 8;
+          // c = cp and cp + 8: the 8 threads of a position group write 128 contiguous bytes per store
+          __bf16* dst = Yb + y_offset(s_seg[ei], s_e[ei]) + (int64_t)pg * (CP * 8) + cp * 8;
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-          bf16x8 v;
+          for (int cc = 0; cc < 2; ++cc) {
+            bf16x8 v;
 #pragma unroll
-          for (int pi = 0; pi < 8; ++pi) v[pi] = (__bf16)y[cc][pi];
-          *reinterpret_cast<bf16x8*>(dst + 64 * cc) = v;
+            for (int pi = 0; pi < 8; ++pi) v[pi] = (__bf16)y[cc][pi];
+            *reinterpret_cast<bf16x8*>(dst + 64 * cc) = v;
+          }
         }
       }
     }
