@@ -211,7 +211,7 @@ def main():
     kernels = []
     for name, d in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
         per_launch_ms = d["ms"] / d["launches"]
-        if name.startswith("gemm_f32"):
+        if name.startswith(("gemm_f32", "tripD_mfma")):
             ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_f32"], "mfma"
         elif name.startswith(("gemm_bf16", "tripG_mfma")):
             ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_bf16"], "mfma"
