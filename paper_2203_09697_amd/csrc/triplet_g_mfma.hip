@@ -539,6 +539,32 @@ __device__ __forceinline__ bool centre_rows(const int32_t* __restrict__ row_ptr,
   return P.gb < P.ge;
 }
 
+// Segment start, length and gap of every in-edge row of the workgroup's share, found once by the first threads
+// (one binary search each, all under way together and while the other threads stage their operand) instead of once
+// per row group by every lane.  rt holds 3 * cap ints, cap >= the rows of the share (share_rows on the host); the
+// caller synchronises before reading it.
+__host__ __device__ constexpr size_t row_tab_bytes(int cap) { return ((size_t)3 * cap * sizeof(int) + 15) & ~(size_t)15; }
+__device__ __forceinline__ void fill_row_table(const int32_t* __restrict__ seg_ptr_kj, const int32_t* __restrict__ idx_ji_kj,
+                                               const int32_t* __restrict__ outs, const rows_t& P, int* rt, int cap) {
+  const int row0 = P.gb * 8;
+  const int nrows = (P.ge * 8 < P.d ? P.ge * 8 : P.d) - row0;
+  for (int r = threadIdx.x; r < nrows; r += blockDim.x) {
+    const rowinfo_t ri = row_info(seg_ptr_kj, idx_ji_kj, outs, P.r0 + row0 + r);
+    rt[r] = ri.seg;
+    rt[cap + r] = ri.cnt;
+    rt[2 * cap + r] = ri.gap;
+  }
+}
+// row p of the atom (p >= P.gb * 8; rows past the end of the list give the last row's entry, which the callers mask)
+__device__ __forceinline__ rowinfo_t table_row(const int* rt, int cap, const rows_t& P, int p) {
+  const int r = (p < P.d ? p : P.d - 1) - P.gb * 8;
+  rowinfo_t ri;
+  ri.seg = rt[r];
+  ri.cnt = rt[cap + r];
+  ri.gap = rt[2 * cap + r];
+  return ri;
+}
+
 // Y_l0(x) = x^(l%2) (q0 + q1 x^2 + q2 x^4 + q3 x^6): Legendre polynomials in even/odd form,
 // normalised by sqrt((2l+1)/(4 pi))
 __device__ __constant__ float LEG_Q[ST][4] = {
@@ -560,17 +586,19 @@ __global__ void __launch_bounds__(256)
 tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                     const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_kj,
                     const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ cos_kj,
-                    const float* __restrict__ dz, int S, int kn_cap, int parts, float* __restrict__ H) {
+                    const float* __restrict__ dz, int S, int kn_cap, int parts, int rows_cap, float* __restrict__ H) {
   constexpr int O = 32 * CB;
   rows_t P;
   if (!centre_rows(row_ptr, out_ptr, parts, P)) return;
   const int Kn = (P.dout + 15) & ~15;
   if (Kn > kn_cap) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  __bf16* ZT = reinterpret_cast<__bf16*>(smem_raw);   // ZT[o][n], row stride LDN
+  int* row_tab = reinterpret_cast<int*>(smem_raw);
+  __bf16* ZT = reinterpret_cast<__bf16*>(smem_raw + row_tab_bytes(rows_cap));   // ZT[o][n], row stride LDN
   const int LDN = Kn + 8;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int32_t* outs = out_list + P.o0;
+  fill_row_table(seg_ptr_kj, idx_ji_kj, outs, P, row_tab, rows_cap);
 
   const int tiles_n = Kn / 16;
   for (int t = wave; t < tiles_n * CB; t += 4) {
@@ -604,7 +632,7 @@ tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restri
     for (int rb = 0; rb < 2; ++rb) {
       const int p = grp * 8 + rb * 4 + (l32 >> 3);
       pv[rb] = p < P.d;
-      ri[rb] = row_info(seg_ptr_kj, idx_ji_kj, outs, P.r0 + (pv[rb] ? p : P.d - 1));
+      ri[rb] = table_row(row_tab, rows_cap, P, p);
     }
     f32x16 acc[2][CB];
 #pragma unroll
@@ -694,7 +722,7 @@ tripD_mfma_bwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
                       const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ cos_kj,
                       const float* __restrict__ x, const float* __restrict__ Qt, const float* __restrict__ W2,
                       const float* __restrict__ ga, const float* __restrict__ z, int64_t E, int S, int kn_cap,
-                      int parts, float* __restrict__ gx, float* __restrict__ gQ, float* __restrict__ w2part) {
+                      int parts, int rows_cap, float* __restrict__ gx, float* __restrict__ gQ, float* __restrict__ w2part) {
   constexpr int F = 32 * NT, LDZ = F + 32;   // the two k halves of a wavefront read disjoint banks
   constexpr int LDU = F + 4;
   float* wp = w2part + (int64_t)blockIdx.x * DB * F;
@@ -706,11 +734,13 @@ tripD_mfma_bwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
     return;
   }
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  float* Q_w = reinterpret_cast<float*>(smem_raw);   // per wavefront: [4 rows][LDQ], element (l, b) at l * 8 + b
+  int* row_tab = reinterpret_cast<int*>(smem_raw);
+  float* Q_w = reinterpret_cast<float*>(smem_raw + row_tab_bytes(rows_cap));   // per wavefront: [4 rows][LDQ], element (l, b) at l * 8 + b
   float* U_w = Q_w + 4 * 4 * LDQ;                    // per wavefront: x H of one row, [8 l][LDU]
   float* Z_s = U_w + 4 * 8 * LDU;                    // [Kn][LDZ]; reused for the weight-gradient partial sums
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int32_t* outs = out_list + P.o0;
+  fill_row_table(seg_ptr_kj, idx_ji_kj, outs, P, row_tab, rows_cap);
   for (int i = threadIdx.x; i < Kn * (F / 4); i += 256) {
     const int n = i / (F / 4), f4 = (i % (F / 4)) * 4;
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
@@ -744,7 +774,7 @@ tripD_mfma_bwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
   for (int sg = 2 * P.gb + wave; sg < 2 * P.ge && sg * 4 < P.d; sg += 4) {
     const int pa = sg * 4 + (l32 >> 3);
     const bool pv = pa < P.d;
-    const rowinfo_t ri = row_info(seg_ptr_kj, idx_ji_kj, outs, P.r0 + (pv ? pa : P.d - 1));
+    const rowinfo_t ri = table_row(row_tab, rows_cap, P, pa);
     // Q of the 4 rows: lane (row lane % 4, b = (lane / 4) % 8, l half lane / 32) fetches 4 values of l; they go to LDS
     // after the main loop
     float qv[4];
@@ -909,7 +939,7 @@ __global__ void __launch_bounds__(256)
 tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                        const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_kj,
                        const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ cos_kj,
-                       const float* __restrict__ U, const float* __restrict__ dz, int S, int kn_cap, int parts, int accumulate,
+                       const float* __restrict__ U, const float* __restrict__ dz, int S, int kn_cap, int parts, int rows_cap, int accumulate,
                        float* __restrict__ grad_cos_kj) {
   constexpr int O = 16 * KS, LDO = O + 8;
   rows_t P;
@@ -917,9 +947,11 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
   const int Kn = (P.dout + 31) & ~31;
   if (Kn > kn_cap || P.dout == 0) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  __bf16* ZB = reinterpret_cast<__bf16*>(smem_raw);   // ZB[n][o], row stride LDO
+  int* row_tab = reinterpret_cast<int*>(smem_raw);
+  __bf16* ZB = reinterpret_cast<__bf16*>(smem_raw + row_tab_bytes(rows_cap));   // ZB[n][o], row stride LDO
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int32_t* outs = out_list + P.o0;
+  fill_row_table(seg_ptr_kj, idx_ji_kj, outs, P, row_tab, rows_cap);
 
   for (int it = threadIdx.x; it < Kn * (O / 8); it += 256) {
     const int n = it / (O / 8), oc = (it % (O / 8)) * 8;
@@ -948,7 +980,7 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
       const int p = grp * 8 + rb * 4 + (l32 >> 3);
       const bool ok = p < P.d && l < S;
       const int e = P.r0 + (p < P.d ? p : P.d - 1);
-      mine[rb] = row_info(seg_ptr_kj, idx_ji_kj, outs, e);
+      mine[rb] = table_row(row_tab, rows_cap, P, p);
       const float* src = U + ((int64_t)e * S + (l < S ? l : 0)) * O + kh * 8;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -1043,6 +1075,13 @@ int kp_of(const gp_graph* g) { return (g->max_in_degree + 15) & ~15; }
 // in-edges (backward kernels: GPW groups of 8 rows each) needs, at most PARTS.  Launching PARTS everywhere
 // would leave most workgroups without work, and starting a workgroup is not free (1280 atoms x 8: 0.2 ms).
 int parts_out(const gp_graph* g) { const int n = (g->max_out_degree + EPP - 1) / EPP; return n < 1 ? 1 : n > PARTS ? PARTS : n; }
+// most in-edge rows in one workgroup's share (centre_rows): the groups of the largest atom over its parts
+int share_rows(const gp_graph* g) {
+  const int groups = (g->max_in_degree + 7) / 8;
+  int nparts = (groups + GPW - 1) / GPW;
+  nparts = nparts < 1 ? 1 : nparts > PARTS ? PARTS : nparts;
+  return 8 * ((groups + nparts - 1) / nparts);
+}
 int parts_in(const gp_graph* g) { const int n = (g->max_in_degree + 8 * GPW - 1) / (8 * GPW); return n < 1 ? 1 : n > PARTS ? PARTS : n; }
 int kn_of(const gp_graph* g) { return (g->max_out_degree + 31) & ~31; }
 // dz of the out-edges (bf16, transposed)
@@ -1155,7 +1194,7 @@ bool gp_tripD_mfma_bwd_usable(const gp_graph* g, int F, int S, int B) {
   if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS) return false;
   if (B != DB || F % 32 != 0 || F < 32 || F > 128 || S < 1 || S > ST) return false;
   const int kn = (g->max_out_degree + 15) & ~15;
-  return lds_D_bwd(F, kn) <= 64 * 1024;
+  return lds_D_bwd(F, kn) + row_tab_bytes(share_rows(g)) <= 64 * 1024;
 }
 
 size_t gp_tripD_mfma_bwd_scratch(const gp_graph* g, int F) {
@@ -1171,9 +1210,9 @@ int gp_tripD_backward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
   GP_REQUIRE(ctx, cos_alpha_kj && x && Qt && W2 && grad_a && grad_x && grad_Q && grad_W2, "triplet D backward: NULL pointer");
   if (!part || part_bytes < gp_tripD_mfma_bwd_scratch(g, F))
     return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "triplet D backward: scratch too small");
-  const int kn_cap = (g->max_out_degree + 15) & ~15, parts = parts_in(g);
+  const int kn_cap = (g->max_out_degree + 15) & ~15, parts = parts_in(g), rows_cap = share_rows(g);
   const unsigned grid = (unsigned)(g->n_atoms * parts);
-  const size_t lds = lds_D_bwd(F, kn_cap);
+  const size_t lds = lds_D_bwd(F, kn_cap) + row_tab_bytes(rows_cap);
   const double Td = (double)T, Ed = (double)E;
   {
     gp_prof_scope prof(ctx, "tripD_mfma_bwd", Td * 2.0 * 8 * F + Ed * 2.0 * (3.0 * 8 * DB * F + 2.0 * DB * F),
@@ -1181,7 +1220,7 @@ int gp_tripD_backward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
 #define GP_D_BWD(NT)                                                                                                 \
   tripD_mfma_bwd_kernel<NT><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj,    \
                                                              g->idx_ji_kj, cos_alpha_kj, x, Qt, W2, grad_a, z, E, S, \
-                                                             kn_cap, parts, grad_x, grad_Q, part)
+                                                             kn_cap, parts, rows_cap, grad_x, grad_Q, part)
     if (F == 32) GP_D_BWD(1);
     else if (F == 64) GP_D_BWD(2);
     else if (F == 96) GP_D_BWD(3);
@@ -1197,7 +1236,8 @@ bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S) {
   if (g->n_triplets <= 0) return false;   // the kernels read cos_alpha_kj[0] for absent triplets
   if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS) return false;
   if (O % 32 != 0 || O < 32 || O > 128 || S < 1 || S > ST) return false;
-  return lds_H(O, kn_of(g)) <= LDS_MAX && (size_t)kn_of(g) * (O + 8) * sizeof(__bf16) <= LDS_MAX;
+  const size_t tab = row_tab_bytes(share_rows(g));   // the kernels' row table
+  return lds_H(O, kn_of(g)) + tab <= LDS_MAX && (size_t)kn_of(g) * (O + 8) * sizeof(__bf16) + tab <= LDS_MAX;
 }
 
 int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S,
@@ -1208,7 +1248,8 @@ int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_al
   GP_REQUIRE(ctx, dz && H && (T == 0 || cos_alpha_kj), "triplet G backward: NULL pointer");
   const int kn_cap = kn_of(g), parts = parts_in(g);
   const unsigned grid = (unsigned)(g->n_atoms * parts);
-  const size_t lds = lds_H(O, kn_cap);
+  const int rows_cap = share_rows(g);
+  const size_t lds = lds_H(O, kn_cap) + row_tab_bytes(rows_cap);
   gp_prof_scope prof(ctx, "tripG_mfma_H", (double)T * 2.0 * 8 * O, (double)T * 4.0 + 4.0 * E * (O + (double)S * O));
 #define GP_TRIPG_LAUNCH(CB)                                                                                          \
   do {                                                                                                               \
@@ -1219,7 +1260,8 @@ int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_al
       lds_set = lds;                                                                                                 \
     }                                                                                                                \
     tripG_mfma_H_kernel<CB><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj,     \
-                                                             g->idx_ji_kj, cos_alpha_kj, dz, S, kn_cap, parts, H);   \
+                                                             g->idx_ji_kj, cos_alpha_kj, dz, S, kn_cap, parts,       \
+                                                             rows_cap, H);                                           \
   } while (0)
   switch (O / 32) {
     case 1: GP_TRIPG_LAUNCH(1); break;
@@ -1240,7 +1282,8 @@ int gp_tripG_grad_cos_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
   GP_REQUIRE(ctx, cos_alpha_kj && U && dz && grad_cos_kj, "grad_cos: NULL pointer");
   const int kn_cap = kn_of(g), parts = parts_in(g);
   const unsigned grid = (unsigned)(g->n_atoms * parts);
-  const size_t lds = (size_t)kn_cap * (O + 8) * sizeof(__bf16);
+  const int rows_cap = share_rows(g);
+  const size_t lds = (size_t)kn_cap * (O + 8) * sizeof(__bf16) + row_tab_bytes(rows_cap);
   gp_prof_scope prof(ctx, "tripG_mfma_dcos", (double)T * 2.0 * 8 * O, (double)T * 12.0 + 4.0 * E * (O + (double)S * O));
 #define GP_TRIPG_LAUNCH(KS)                                                                                          \
   do {                                                                                                               \
@@ -1252,7 +1295,7 @@ int gp_tripG_grad_cos_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
     }                                                                                                                \
     tripG_mfma_dcos_kernel<KS><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj,  \
                                                                 g->idx_ji_kj, cos_alpha_kj, U, dz, S, kn_cap, parts, \
-                                                                accumulate, grad_cos_kj);                            \
+                                                                rows_cap, accumulate, grad_cos_kj);                            \
   } while (0)
   switch (O / 32) {
     case 1: GP_TRIPG_LAUNCH(2); break;
