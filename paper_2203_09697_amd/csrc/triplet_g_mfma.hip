@@ -971,6 +971,19 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
 
   const int kh = lane >> 5, l32 = lane & 31;
   const int l = l32 & 7;
+  // Y_l0'(x) for this lane's four l = 4 kh + i as polynomials in x^2 (times x for even l): from
+  // P_l = x^(l%2) sum_i q_i x^(2i), P_l' = sum_i (2i + l%2) q_i x^(2i + l%2 - 1)
+  float dq[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int lq = 4 * kh + i;
+    const float nrm = lq < S ? Y_NORM_M[lq] : 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (i & 1) dq[i][c] = nrm * (float)(2 * c + 1) * LEG_Q[lq][c];
+      else dq[i][c] = c < 3 ? nrm * (float)(2 * c + 2) * LEG_Q[lq][c + 1] : 0.f;
+    }
+  }
   for (int grp = P.gb + wave; grp < P.ge; grp += 4) {
     // A fragments: row (in-edge row l32/8 of the block, l), 8 consecutive o per k-step
     bf16x8 a[2][KS];
@@ -1046,22 +1059,12 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
         for (int pl = 0; pl < 4; ++pl) {
           const int slot = n - (n > rgap[rb][pl] ? 1 : 0);
           const bool valid = n != rgap[rb][pl] && slot < rcnt[rb][pl];
-          const float x = xs[rb][pl];
-          // dY[l] = sqrt((2l+1)/(4 pi)) P_l'(x), P'_{l+1} = P'_{l-1} + (2l+1) P_l; this lane needs l = 4 kh .. 4 kh + 3
-          float Pl[ST], dP[ST];
-          Pl[0] = 1.f; dP[0] = 0.f;
-          Pl[1] = x;   dP[1] = 1.f;
-#pragma unroll
-          for (int k = 1; k < ST - 1; ++k) {
-            Pl[k + 1] = ((float)(2 * k + 1) * x * Pl[k] - (float)k * Pl[k - 1]) * (1.0f / (float)(k + 1));
-            dP[k + 1] = dP[k - 1] + (float)(2 * k + 1) * Pl[k];
-          }
+          const float x = xs[rb][pl], t2 = x * x;
           float part = 0.f;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float lo = (i < S) ? Y_NORM_M[i] * dP[i] : 0.f;
-            const float hi = (4 + i < S) ? Y_NORM_M[4 + i] * dP[4 + i] : 0.f;
-            part += acc[rb][4 * pl + i] * (kh ? hi : lo);
+            const float w = dq[i][0] + t2 * (dq[i][1] + t2 * (dq[i][2] + t2 * dq[i][3]));
+            part += acc[rb][4 * pl + i] * ((i & 1) ? w : x * w);   // l = 4 kh + i even: odd derivative
           }
           const float total = part + __shfl_xor(part, 32, 64);
           if (valid && kh == (pl >> 1)) grad_cos_kj[rseg[rb][pl] + slot] = old[rb][pl] + total;
