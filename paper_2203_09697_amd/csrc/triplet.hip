@@ -122,7 +122,9 @@ tripD_fwd_kernel(const int32_t* __restrict__ seg, const int32_t* __restrict__ id
 #pragma unroll
         for (int i = 0; i < FPL; ++i) {
           const int f = fl + i * WAVE;
-          xv[u][i] = (f < F && id < n) ? x[kj * F + f] : 0.f;
+          // clamped column and a 0/1 factor instead of a select around the load: a load that is only needed on one
+          // side of a branch gets moved there and waited for on its own
+          xv[u][i] = x[kj * F + (f < F ? f : 0)] * ((f < F && id < n) ? 1.f : 0.f);
         }
       }
 #pragma unroll
@@ -200,7 +202,7 @@ tripD_bwd_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__
 #pragma unroll
         for (int i = 0; i < FPL; ++i) {
           const int f = fl + i * WAVE;
-          gv[u][i] = (f < F && id < n) ? ga[ji * F + f] : 0.f;
+          gv[u][i] = ga[ji * F + (f < F ? f : 0)] * ((f < F && id < n) ? 1.f : 0.f);   // as in the forward kernel
         }
       }
 #pragma unroll
@@ -556,7 +558,8 @@ namespace {
 
 // A workgroup takes 64 consecutive edges: their slice of the transposed radial table is 256
 // contiguous bytes per (l, c), staged in LDS once; then one wavefront per edge, lanes over o.
-constexpr int EG_EDGES = 64;
+constexpr int EG_EDGES = 32;   // edges per workgroup (14 KB of LDS: 8 wavefronts per SIMD fit); 64 measured 1 % slower
+constexpr int EG_UNR = 2;      // edges of a wavefront in flight together; 4 measured slower (registers)
 
 __global__ void __launch_bounds__(WPB* WAVE)
 edge_G_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64_t E, int S, int C, int O,
@@ -583,19 +586,31 @@ edge_G_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64
     }
   }
   __syncthreads();
-  for (int el = w; el < EG_EDGES && e0 + el < E; el += WPB) {
-    const int64_t e = e0 + el;
+  // EG_UNR edges of a wavefront at a time: their H rows are requested together, so the memory round trip (and the
+  // wait for the previous stores, which complete through the same counter) is paid once per EG_UNR edges
+  for (int el0 = w; el0 < EG_EDGES && e0 + el0 < E; el0 += EG_UNR * WPB) {
     for (int o = lane; o < O; o += WAVE) {
-      float h[ST];
+      float h[EG_UNR][ST];
 #pragma unroll
-      for (int l = 0; l < ST; ++l) h[l] = (l < S) ? H[(e * S + l) * O + o] : 0.f;
-      for (int c = 0; c < C; ++c) {
-        float s = 0.f;
+      for (int u = 0; u < EG_UNR; ++u) {
+        const int el = el0 + u * WPB;
+        const int64_t e = (el < EG_EDGES && e0 + el < E) ? e0 + el : e0 + el0;   // a valid row either way
 #pragma unroll
-        for (int l = 0; l < ST; ++l)
-          if (l < S) s += dyn_s[(l * C + c) * EG_EDGES + el] * h[l];
-        if (out_half) reinterpret_cast<__bf16*>(Gout)[(e * C + c) * O + o] = (__bf16)s;
-        else Gout[(e * C + c) * O + o] = s;
+        for (int l = 0; l < ST; ++l) h[u][l] = H[(e * S + (l < S ? l : S - 1)) * O + o];
+      }
+#pragma unroll
+      for (int u = 0; u < EG_UNR; ++u) {
+        const int el = el0 + u * WPB;
+        if (el >= EG_EDGES || e0 + el >= E) break;
+        const int64_t e = e0 + el;
+        for (int c = 0; c < C; ++c) {
+          float s = 0.f;
+#pragma unroll
+          for (int l = 0; l < ST; ++l)
+            if (l < S) s += dyn_s[(l * C + c) * EG_EDGES + el] * h[u][l];
+          if (out_half) reinterpret_cast<__bf16*>(Gout)[(e * C + c) * O + o] = (__bf16)s;
+          else Gout[(e * C + c) * O + o] = s;
+        }
       }
     }
   }
@@ -626,14 +641,14 @@ edge_dRad_kernel(const float* __restrict__ V, const float* __restrict__ H, int64
 // range).  A lane loads its OQ values of V[c, :] (the wavefront reads the edge's C x O block contiguously) and the
 // same OQ columns of the S rows of H (16 lanes share each address), all requested before the first use; the four
 // partial sums of a c are combined by two lane exchanges.  VT: storage type of V.
+constexpr int DQ_EPW = 1;   // edges per wavefront (4 measured 2 % slower: starting the wavefronts is not the limit)
 template <int OQ, class VT>
 __global__ void __launch_bounds__(WPB* WAVE)
 edge_dRad_q_kernel(const VT* __restrict__ V, const float* __restrict__ H, int64_t E, int S, int C, float* __restrict__ dRad) {
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int64_t e = (int64_t)blockIdx.x * WPB + w;
-  if (e >= E) return;
   constexpr int O = 4 * OQ;
   const int c = lane >> 2, q = lane & 3;
+  for (int64_t e = ((int64_t)blockIdx.x * WPB + w) * DQ_EPW, e_end = e + DQ_EPW < E ? e + DQ_EPW : E; e < e_end; ++e) {
   const VT* vp = V + (e * C + (c < C ? c : C - 1)) * O + q * OQ;
   float v[OQ];
   if (sizeof(VT) == 2) {
@@ -675,6 +690,7 @@ edge_dRad_q_kernel(const VT* __restrict__ V, const float* __restrict__ H, int64_
 #pragma unroll
     for (int l = 0; l < ST; ++l)
       if (l < S) dRad[e * S * C + l * C + c] = part[l];
+  }
   }
 }
 
@@ -722,10 +738,11 @@ int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, i
   const bool aligned = (((uintptr_t)V | (uintptr_t)H) & 15) == 0;
   if (C <= 16 && aligned && (O == 32 || O == 64 || O == 128)) {
     const __bf16* Vh = reinterpret_cast<const __bf16*>(V);
+    const unsigned dq_blocks = (unsigned)((E + WPB * DQ_EPW - 1) / (WPB * DQ_EPW));
 #define GP_DRAD(OQ)                                                                                           \
   do {                                                                                                        \
-    if (v_half) edge_dRad_q_kernel<OQ, __bf16><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(Vh, H, E, S, C, dRad); \
-    else edge_dRad_q_kernel<OQ, float><<<seg_blocks(E), WPB * WAVE, 0, ctx->stream>>>(V, H, E, S, C, dRad);    \
+    if (v_half) edge_dRad_q_kernel<OQ, __bf16><<<dq_blocks, WPB * WAVE, 0, ctx->stream>>>(Vh, H, E, S, C, dRad); \
+    else edge_dRad_q_kernel<OQ, float><<<dq_blocks, WPB * WAVE, 0, ctx->stream>>>(V, H, E, S, C, dRad);    \
   } while (0)
     if (O == 32) GP_DRAD(8);
     else if (O == 64) GP_DRAD(16);

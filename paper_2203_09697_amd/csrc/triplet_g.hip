@@ -37,11 +37,12 @@ __device__ __forceinline__ void dy_l0(float c, int S, float* dY) {
 // U[e, l, o] = sum_c Radt[(l*C+c)*E + e] * V[e, c*O + o].  A workgroup takes 64 consecutive edges and
 // stages their slice of the transposed radial table in LDS (256 contiguous bytes per (l, c)); then one
 // wavefront per edge, lanes over o.
-constexpr int EU_EDGES = 64;
+constexpr int EU_EDGES = 32;   // edges per workgroup (14 KB of LDS; 64: 4 % slower)
+constexpr int EU_UNR = 1;      // edges of a wavefront in flight together (2: 40 % slower, the 32 bf16 values in flight cost registers)
 
 constexpr int EU_CMAX = 16;   // largest emb_cbf
 
-// The slice of the transposed radial table for 64 consecutive edges, [(l*C + c) * 64 + edge], into LDS.  All loads
+// The slice of the transposed radial table for EU_EDGES consecutive edges, [(l*C + c) * EU_EDGES + edge], into LDS.  All loads
 // of a thread are issued before the first LDS write (a rolled loop would expose one memory round trip per pass).
 __device__ __forceinline__ void stage_radial_slice(const float* __restrict__ Radt, int64_t E, int64_t e0, int rows, float* rad_s) {
   constexpr int PASSES = ST * EU_CMAX * EU_EDGES / (WPB * 64);
@@ -66,31 +67,43 @@ template <class VT>
 __global__ void __launch_bounds__(WPB* 64)
 edge_U_kernel(const float* __restrict__ Radt, const VT* __restrict__ V, int64_t E, int S, int C, int O,
               float* __restrict__ U) {
-  extern __shared__ float rad_s[];   // [(l*C + c) * 64 + edge]
+  extern __shared__ float rad_s[];   // [(l*C + c) * EU_EDGES + edge]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int64_t e0 = (int64_t)blockIdx.x * EU_EDGES;
   stage_radial_slice(Radt, E, e0, S * C, rad_s);
   __syncthreads();
-  for (int el = w; el < EU_EDGES && e0 + el < E; el += WPB) {
-    const int64_t e = e0 + el;
+  // EU_UNR edges of a wavefront at a time, all their loads first (clamped indices: no branch around a load): the
+  // memory round trip, and the wait for the previous stores that comes with it, is paid once per EU_UNR edges
+  for (int el0 = w; el0 < EU_EDGES && e0 + el0 < E; el0 += EU_UNR * WPB) {
     for (int o = lane; o < O; o += 64) {
-      // all C values of the column first (clamped index: no branch around a load), so that their latencies overlap
-      float v[EU_CMAX];
+      VT v[EU_UNR][EU_CMAX];
 #pragma unroll
-      for (int c = 0; c < EU_CMAX; ++c) v[c] = (float)V[(e * C + (c < C ? c : C - 1)) * O + o];
-      float acc[ST];
+      for (int u = 0; u < EU_UNR; ++u) {
+        const int el = el0 + u * WPB;
+        const int64_t e = (el < EU_EDGES && e0 + el < E) ? e0 + el : e0 + el0;
 #pragma unroll
-      for (int l = 0; l < ST; ++l) acc[l] = 0.f;
+        for (int c = 0; c < EU_CMAX; ++c) v[u][c] = V[(e * C + (c < C ? c : C - 1)) * O + o];
+      }
 #pragma unroll
-      for (int c = 0; c < EU_CMAX; ++c)
-        if (c < C) {
+      for (int u = 0; u < EU_UNR; ++u) {
+        const int el = el0 + u * WPB;
+        if (el >= EU_EDGES || e0 + el >= E) break;
+        const int64_t e = e0 + el;
+        float acc[ST];
 #pragma unroll
-          for (int l = 0; l < ST; ++l)
-            if (l < S) acc[l] += rad_s[(l * C + c) * EU_EDGES + el] * v[c];
-        }
+        for (int l = 0; l < ST; ++l) acc[l] = 0.f;
 #pragma unroll
-      for (int l = 0; l < ST; ++l)
-        if (l < S) U[(e * S + l) * O + o] = acc[l];
+        for (int c = 0; c < EU_CMAX; ++c)
+          if (c < C) {
+            const float vc = (float)v[u][c];
+#pragma unroll
+            for (int l = 0; l < ST; ++l)
+              if (l < S) acc[l] += rad_s[(l * C + c) * EU_EDGES + el] * vc;
+          }
+#pragma unroll
+        for (int l = 0; l < ST; ++l)
+          if (l < S) U[(e * S + l) * O + o] = acc[l];
+      }
     }
   }
 }
@@ -113,7 +126,7 @@ trip_dcos_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__
 #pragma unroll
     for (int i = 0; i < FPL; ++i) {
       const int o = lane + i * 64;
-      Ur[l][i] = (l < S && o < O) ? U[(e * S + l) * O + o] : 0.f;
+      Ur[l][i] = U[(e * S + (l < S ? l : S - 1)) * O + (o < O ? o : 0)] * ((l < S && o < O) ? 1.f : 0.f);   // unconditional load
     }
   const int q0 = seg_kj[e], q1 = seg_kj[e + 1];
   for (int base = q0; base < q1; base += 64) {

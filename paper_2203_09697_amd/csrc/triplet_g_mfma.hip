@@ -274,10 +274,11 @@ tripD_mfma_fwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
   float* Q_s = X_s + (size_t)P.Kp * LDX;             // [Kp][LDQ]
   __shared__ int s_e[64], s_seg[64], s_cnt[64], s_gap[64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll 4
   for (int i = threadIdx.x; i < P.Kp * (F / 4); i += 256) {
     const int p = i / (F / 4), f4 = (i % (F / 4)) * 4;
-    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    if (p < P.d) v = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + p) * F + f4);
+    // clamped row times a 0/1 factor: the load stays outside any branch, and four of them are under way together
+    const f32x4 v = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + (p < P.d ? p : 0)) * F + f4) * (p < P.d ? 1.f : 0.f);
     *reinterpret_cast<f32x4*>(&X_s[p * LDX + f4]) = v;
   }
   for (int i = threadIdx.x; i < P.Kp * 64; i += 256) {
@@ -395,12 +396,15 @@ tripG_mfma_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
   // stage X_j: a wavefront takes a tile of 16 positions x 32 features; a lane converts two rows of
   // 4 features and writes 4 packed position pairs
   const int tiles_p = P.Kp / 16;
+  // loads from clamped rows times a 0/1 factor (a select around a load would move the load under a branch and have
+  // it waited for alone); unrolled so that the loads of several tiles are under way together
+#pragma unroll 4
   for (int t = wave; t < tiles_p * CB; t += (int)(blockDim.x >> 6)) {
     const int pp = (t % tiles_p) * 8 + (lane & 7), fq = (t / tiles_p) * 8 + (lane >> 3);
     const int p0 = 2 * pp;
-    f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
-    if (p0 < P.d) v0 = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + p0) * F + 4 * fq);
-    if (p0 + 1 < P.d) v1 = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + p0 + 1) * F + 4 * fq);
+    const bool ok0 = p0 < P.d, ok1 = p0 + 1 < P.d;
+    const f32x4 v0 = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + (ok0 ? p0 : 0)) * F + 4 * fq) * (ok0 ? 1.f : 0.f);
+    const f32x4 v1 = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + (ok1 ? p0 + 1 : 0)) * F + 4 * fq) * (ok1 ? 1.f : 0.f);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       bf16x2 pr;
@@ -601,12 +605,14 @@ tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restri
   fill_row_table(seg_ptr_kj, idx_ji_kj, outs, P, row_tab, rows_cap);
 
   const int tiles_n = Kn / 16;
+#pragma unroll 4
   for (int t = wave; t < tiles_n * CB; t += 4) {
     const int np = (t % tiles_n) * 8 + (lane & 7), oq = (t / tiles_n) * 8 + (lane >> 3);
     const int n0 = 2 * np;
-    f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
-    if (n0 < P.dout) v0 = *reinterpret_cast<const f32x4*>(dz + (int64_t)outs[n0] * O + 4 * oq);
-    if (n0 + 1 < P.dout) v1 = *reinterpret_cast<const f32x4*>(dz + (int64_t)outs[n0 + 1] * O + 4 * oq);
+    // the loop runs only if the atom has out-edges; loads from clamped positions times a 0/1 factor, see above
+    const bool ok0 = n0 < P.dout, ok1 = n0 + 1 < P.dout;
+    const f32x4 v0 = *reinterpret_cast<const f32x4*>(dz + (int64_t)outs[ok0 ? n0 : 0] * O + 4 * oq) * (ok0 ? 1.f : 0.f);
+    const f32x4 v1 = *reinterpret_cast<const f32x4*>(dz + (int64_t)outs[ok1 ? n0 + 1 : 0] * O + 4 * oq) * (ok1 ? 1.f : 0.f);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       bf16x2 pr;
@@ -741,10 +747,11 @@ tripD_mfma_bwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int32_t* outs = out_list + P.o0;
   fill_row_table(seg_ptr_kj, idx_ji_kj, outs, P, row_tab, rows_cap);
-  for (int i = threadIdx.x; i < Kn * (F / 4); i += 256) {
+#pragma unroll 4
+  for (int i = threadIdx.x; i < Kn * (F / 4); i += 256) {   // Kn > 0 only if the atom has out-edges
     const int n = i / (F / 4), f4 = (i % (F / 4)) * 4;
-    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    if (n < P.dout) v = *reinterpret_cast<const f32x4*>(ga + (int64_t)outs[n] * F + f4);
+    const bool ok = n < P.dout;
+    const f32x4 v = *reinterpret_cast<const f32x4*>(ga + (int64_t)outs[ok ? n : 0] * F + f4) * (ok ? 1.f : 0.f);
     *reinterpret_cast<f32x4*>(&Z_s[n * LDZ + f4]) = v;
   }
   __syncthreads();
@@ -783,7 +790,7 @@ tripD_mfma_bwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int lq = 4 * kh + i;
-        qv[i] = (p < P.d && lq < S) ? Qt[(int64_t)(lq * DB + b) * E + P.r0 + p] : 0.f;
+        qv[i] = Qt[(int64_t)((lq < S ? lq : S - 1) * DB + b) * E + P.r0 + (p < P.d ? p : P.d - 1)] * ((p < P.d && lq < S) ? 1.f : 0.f);
       }
     }
     // x and z of the 4 rows, for the epilogue
@@ -794,7 +801,7 @@ tripD_mfma_bwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
       const int64_t e = P.r0 + (p < P.d ? p : P.d - 1);
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        xv[eg][t] = p < P.d ? x[e * F + t * 32 + l32] : 0.f;
+        xv[eg][t] = x[e * F + t * 32 + l32] * (p < P.d ? 1.f : 0.f);   // e is clamped to a valid row
         zv[eg][t] = z ? z[e * F + t * 32 + l32] : 0.f;
       }
     }
@@ -953,18 +960,16 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
   const int32_t* outs = out_list + P.o0;
   fill_row_table(seg_ptr_kj, idx_ji_kj, outs, P, row_tab, rows_cap);
 
-  for (int it = threadIdx.x; it < Kn * (O / 8); it += 256) {
+#pragma unroll 4
+  for (int it = threadIdx.x; it < Kn * (O / 8); it += 256) {   // P.dout > 0 here
     const int n = it / (O / 8), oc = (it % (O / 8)) * 8;
+    const bool ok = n < P.dout;
+    const float* src = dz + (int64_t)outs[ok ? n : 0] * O + oc;   // clamped position times a 0/1 factor
+    const f32x4 v0 = *reinterpret_cast<const f32x4*>(src) * (ok ? 1.f : 0.f);
+    const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 4) * (ok ? 1.f : 0.f);
     bf16x8 v;
-    if (n < P.dout) {
-      const float* src = dz + (int64_t)outs[n] * O + oc;
-      const f32x4 v0 = *reinterpret_cast<const f32x4*>(src), v1 = *reinterpret_cast<const f32x4*>(src + 4);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) v[i] = (__bf16)v0[i], v[4 + i] = (__bf16)v1[i];
-    } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = (__bf16)0.f;
-    }
+    for (int i = 0; i < 4; ++i) v[i] = (__bf16)v0[i], v[4 + i] = (__bf16)v1[i];
     *reinterpret_cast<bf16x8*>(&ZB[n * LDO + oc]) = v;
   }
   __syncthreads();
