@@ -647,6 +647,7 @@ __global__ void __launch_bounds__(WPB* WAVE)
 edge_dRad_q_kernel(const VT* __restrict__ V, const float* __restrict__ H, int64_t E, int S, int C, float* __restrict__ dRad) {
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   constexpr int O = 4 * OQ;
+  __shared__ __attribute__((aligned(16))) float H_s[WPB][ST * O];
   const int c = lane >> 2, q = lane & 3;
   for (int64_t e = ((int64_t)blockIdx.x * WPB + w) * DQ_EPW, e_end = e + DQ_EPW < E ? e + DQ_EPW : E; e < e_end; ++e) {
   const VT* vp = V + (e * C + (c < C ? c : C - 1)) * O + q * OQ;
@@ -668,12 +669,25 @@ edge_dRad_q_kernel(const VT* __restrict__ V, const float* __restrict__ H, int64_
       for (int k = 0; k < 4; ++k) v[i + k] = t[k];
     }
   }
+  // the S x O block of H goes through the wavefront's LDS slice: fetched once (S O / 4 sixteen-byte loads spread over
+  // the lanes) instead of by each of the 16 lanes that share a quarter, which kept the address path busy 16 times over
+  {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const float* hp = H + e * S * O;
+#pragma unroll
+    for (int k = 0; k < (ST * O / 4 + WAVE - 1) / WAVE; ++k) {
+      const int idx = lane + k * WAVE;
+      const f4 t = *reinterpret_cast<const f4*>(hp + 4 * (idx < S * O / 4 ? idx : 0));
+      if (idx < S * O / 4) *reinterpret_cast<f4*>(&H_s[w][4 * idx]) = t;
+    }
+  }
+  wave_lds_sync();
   float part[ST];
 #pragma unroll
   for (int l = 0; l < ST; ++l) {
     part[l] = 0.f;
     typedef float f4 __attribute__((ext_vector_type(4)));
-    const float* hp = H + (e * S + (l < S ? l : S - 1)) * O + q * OQ;
+    const float* hp = &H_s[w][(l < S ? l : S - 1) * O + q * OQ];
 #pragma unroll
     for (int i = 0; i < OQ; i += 4) {
       const f4 t = *reinterpret_cast<const f4*>(hp + i);
@@ -681,6 +695,7 @@ edge_dRad_q_kernel(const VT* __restrict__ V, const float* __restrict__ H, int64_
       for (int k = 0; k < 4; ++k) part[l] += v[i + k] * t[k];
     }
   }
+  wave_lds_sync();   // the slice is rewritten for the next edge
 #pragma unroll
   for (int l = 0; l < ST; ++l) {
     part[l] += __shfl_xor(part[l], 1);
