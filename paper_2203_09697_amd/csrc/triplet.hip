@@ -122,9 +122,8 @@ tripD_fwd_kernel(const int32_t* __restrict__ seg, const int32_t* __restrict__ id
 #pragma unroll
         for (int i = 0; i < FPL; ++i) {
           const int f = fl + i * WAVE;
-          // clamped column and a 0/1 factor instead of a select around the load: a load that is only needed on one
-          // side of a branch gets moved there and waited for on its own
-          xv[u][i] = x[kj * F + (f < F ? f : 0)] * ((f < F && id < n) ? 1.f : 0.f);
+          // (the unconditional form of the backward kernel measured 20 % slower here, with up to 16 accumulator rows)
+          xv[u][i] = (f < F && id < n) ? x[kj * F + f] : 0.f;
         }
       }
 #pragma unroll
@@ -202,7 +201,9 @@ tripD_bwd_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__
 #pragma unroll
         for (int i = 0; i < FPL; ++i) {
           const int f = fl + i * WAVE;
-          gv[u][i] = ga[ji * F + (f < F ? f : 0)] * ((f < F && id < n) ? 1.f : 0.f);   // as in the forward kernel
+          // clamped column and a 0/1 factor instead of a select around the load: a load that is only needed on one
+          // side of a branch gets moved there and waited for on its own
+          gv[u][i] = ga[ji * F + (f < F ? f : 0)] * ((f < F && id < n) ? 1.f : 0.f);
         }
       }
 #pragma unroll
