@@ -63,6 +63,8 @@ struct scratch_G {
   void* ybuf;        // per-triplet y in bf16 for the matrix-core triplet kernels (bf16 blocks only)
   size_t ybytes;
   float *dA, *dB1, *gc_ji;   // radial factor at the target edge only: [E,C,F], [E,S,F], [T]
+  int32_t* iota;             // ... and bf16: 0, 1, ..., E-1 (the in-edges of an atom as a list, for the mirrored views)
+  float* Radt_out;           // ... and the radial table with its columns in out-list order [S*C, E]
   float* eh5;                // symmetric blocks only: a fifth [E, H] buffer
   // bf16 storage only: weight matrices rounded to bf16 once per call, so that both operands of the large
   // GEMMs are copied to LDS without conversion
@@ -105,6 +107,8 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, int64_t T, scratch_
   s->dA = c.take<float>(rt ? E * C * F : 0);
   s->dB1 = c.take<float>(rt ? E * S * F : 0);
   s->gc_ji = c.take<float>(rt ? (size_t)T : 0);
+  s->iota = c.take<int32_t>(rt && d->dtype == GP_BF16_F32ACC ? E : 0);
+  s->Radt_out = c.take<float>(rt && d->dtype == GP_BF16_F32ACC ? S * C * E : 0);
   s->eh5 = c.take<float>(d->symmetric ? E * H : 0);
   const bool hs = half_storage(d);
   s->W_ba_h = c.take<__bf16>(hs ? H * H : 0);
@@ -143,6 +147,31 @@ gp_graph mirrored(const gp_graph* g) {
   m.n_atoms = 0;   // the lists by centre atom do not describe the mirrored views
   m.row_ptr = m.out_ptr = m.out_list = nullptr;
   return m;
+}
+
+// The lists by centre atom for the mirrored views: the rows of an atom (the edges whose features are gathered) are
+// its out-edges, in out_list order, and the edges it accumulates into are its in-edges, which have consecutive ids
+// (iota = 0, 1, ... serves as their list).  The matrix-core kernels take the row list as a separate argument.
+gp_graph mirrored_lists(const gp_graph* g, const int32_t* iota) {
+  gp_graph m = mirrored(g);
+  m.n_atoms = g->n_atoms;
+  m.row_ptr = g->out_ptr;
+  m.out_ptr = g->row_ptr;
+  m.out_list = iota;
+  m.max_in_degree = g->max_out_degree;
+  m.max_out_degree = g->max_in_degree;
+  return m;
+}
+
+// dst[r, q] = src[r, list[q]] for the rows r = blockIdx.y of an [rows, n] matrix
+__global__ void gather_cols_kernel(const float* __restrict__ src, const int32_t* __restrict__ list, int64_t n, float* __restrict__ dst) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q < n) dst[(int64_t)blockIdx.y * n + q] = src[(int64_t)blockIdx.y * n + list[q]];
+}
+
+__global__ void iota_kernel(int32_t* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (int32_t)i;
 }
 
 typedef __bf16 h4 __attribute__((ext_vector_type(4)));
@@ -324,6 +353,14 @@ bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g, doub
   return g->n_edges > 0 && (double)g->n_triplets >= min_density * (double)g->n_edges;
 }
 
+// The same choice for blocks with the radial factor at the target edge, whose triplet sums run on the mirrored views
+bool want_rt_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g, double min_density) {
+  if (d->dtype != GP_BF16_F32ACC || ctx->trip_mfma == 0 || !d->radial_at_target) return false;
+  if (!g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0) return false;
+  if (ctx->trip_mfma == 1) return true;
+  return g->n_edges > 0 && (double)g->n_triplets >= min_density * (double)g->n_edges;
+}
+
 // The accumulator A[E, C, F] is stored as bf16 when the matrix-core kernel writes it and bf16 storage is on: its
 // only readers are two bf16-operand GEMMs.  Forward and backward must agree, so the triplet mode of the
 // context must not change between the two calls of a step.
@@ -436,7 +473,13 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     // A_e = Rad_e^T B1_e,  B1[e,l,f] = sum_{t in seg(e)} Y_l(t) x[kj(t),f]: the radial factor has left the sum
     GP_REQUIRE(ctx, graph->seg_ptr_kj && (graph->n_triplets == 0 || graph->idx_ji_kj), "gp_block_forward_G: kj-major view missing");
     const gp_graph gm = mirrored(graph);
-    GP_TRY(gp_tripD_backward(ctx, &gm, basis->cos_alpha, nullptr, nullptr, nullptr, s.x, nullptr, F, S, 1, s.B1, nullptr));
+    const gp_graph gml = mirrored_lists(graph, sc.iota);
+    if (want_rt_mfma(ctx, dims, graph, MFMA_BWD_DENSITY) && gp_tripG_mfma_H_usable(&gml, F, S)) {
+      iota_kernel<<<(unsigned)((E + 255) / 256), 256, 0, ctx->stream>>>(sc.iota, E);
+      GP_LAUNCH_CHECK(ctx, "iota_kernel");
+      GP_TRY(gp_tripG_backward_H_mfma(ctx, &gml, basis->cos_alpha, s.x, F, S, s.B1, graph->out_list));
+    } else
+      GP_TRY(gp_tripD_backward(ctx, &gm, basis->cos_alpha, nullptr, nullptr, nullptr, s.x, nullptr, F, S, 1, s.B1, nullptr));
     GP_TRY(gp_tripG_edge_G(ctx, s.Radt, s.B1, E, S, C, F, s.A));
   } else if (want_trip_mfma(ctx, dims, graph, MFMA_FWD_DENSITY) && gp_tripG_mfma_usable(graph, F, S, C))
     GP_TRY(gp_tripG_forward_mfma(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes, ah));
@@ -558,7 +601,17 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
     // mirror image of the source-edge form: G[e',c,o] = sum_{t: kj(t)=e'} y'_t[c] dz[ji(t),o] with
     // y'_t[c] = sum_l Y_l(t) Rad[ji(t),l,c] is the forward kernel on the mirrored views
     const gp_graph gm = mirrored(graph);
-    GP_TRY(gp_tripD_forward(ctx, &gm, basis->cos_alpha_kj, sc.dz, s.Radt, nullptr, O, S, C, nullptr, sc.Gm));
+    const gp_graph gml = mirrored_lists(graph, sc.iota);
+    if (want_rt_mfma(ctx, dims, graph, MFMA_FWD_DENSITY) && gp_tripG_mfma_usable(&gml, O, S, C)) {
+      iota_kernel<<<(unsigned)((E + 255) / 256), 256, 0, ctx->stream>>>(sc.iota, E);
+      GP_LAUNCH_CHECK(ctx, "iota_kernel");
+      // the radial table in out-list order, so that the threads of the y kernel read neighbouring columns
+      gather_cols_kernel<<<dim3((unsigned)((E + 255) / 256), (unsigned)(S * C)), 256, 0, ctx->stream>>>(s.Radt, graph->out_list, E, sc.Radt_out);
+      GP_LAUNCH_CHECK(ctx, "gather_cols_kernel");
+      GP_TRY(gp_tripG_forward_mfma(ctx, &gml, basis->cos_alpha_kj, sc.dz, sc.Radt_out, O, S, C, sc.Gm, sc.ybuf, sc.ybytes, 0,
+                                   graph->out_list, 1));
+    } else
+      GP_TRY(gp_tripD_forward(ctx, &gm, basis->cos_alpha_kj, sc.dz, s.Radt, nullptr, O, S, C, nullptr, sc.Gm));
     GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                 // [(c,o), f]
     e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
     GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e));                       // dz_dn

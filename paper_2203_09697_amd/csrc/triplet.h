@@ -74,11 +74,16 @@ int gp_tripG_grad_cos(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj,
 bool gp_tripG_mfma_usable(const gp_graph* g, int F, int S, int C);
 size_t gp_tripG_mfma_scratch(int64_t E, int64_t T);
 int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
-                          int F, int S, int C, float* A, void* ybuf, size_t ybytes, int out_half = 0);   // out_half: A is bf16
+                          int F, int S, int C, float* A, void* ybuf, size_t ybytes, int out_half = 0,   // out_half: A is bf16
+                          const int32_t* row_list = nullptr, int rad_by_pos = 0);
+// rad_by_pos: Radt's columns are in row_list order already (gathered by the caller)
+// row_list: edge ids of the atoms' rows where these are not consecutive (the mirrored views of a block with the
+// radial factor at the target edge: g->row_ptr then indexes row_list, and g->out_list holds consecutive ids)
 // Matrix-core forms of H[e',l,o] and of grad_cos (kj-major), same conditions on the graph; O a multiple of 32 up to 128
 bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S);
+bool gp_tripG_mfma_H_usable(const gp_graph* g, int O, int S);   // the H kernel alone (less LDS than grad_cos)
 int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S,
-                             float* H);
+                             float* H, const int32_t* row_list = nullptr);
 int gp_tripG_grad_cos_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* U, const float* dz,
                            int O, int S, int accumulate, float* grad_cos_kj);
 // 16-byte vectorised streaming kernels (triplet_stream.hip); return 1 if they handled the call

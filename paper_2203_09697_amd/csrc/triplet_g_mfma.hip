@@ -68,6 +68,10 @@ __device__ __forceinline__ void atom_and_part(int parts, int& j, int& part) {
   part = w % parts;
 }
 
+// Edge id of row position pos: the rows of an atom are consecutive edge ids (edges are sorted by target atom) unless
+// a list is given (the mirrored use: rows are the atom's out-edges, listed in out_list order).
+__device__ __forceinline__ int row_edge(const int32_t* __restrict__ row_list, int pos) { return row_list ? row_list[pos] : pos; }
+
 // The share of one workgroup: centre atom j, its in-edge rows r0 .. r0+d-1
 // (Kp = d rounded up to 16) and the slice [eb, ee) of its out-edge list.
 struct part_t {
@@ -116,7 +120,8 @@ __global__ void __launch_bounds__(YT, 3)   // three workgroups per CU: 168 regis
 tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_ji,
                const int32_t* __restrict__ idx_kj, const float* __restrict__ cos_alpha,
-               const float* __restrict__ Radt, int64_t E, int S, int C, int kp_cap, int parts, __bf16* __restrict__ Yb) {
+               const float* __restrict__ Radt, int64_t E, int S, int C, int kp_cap, int parts,
+               const int32_t* __restrict__ row_list, int rad_by_pos, __bf16* __restrict__ Yb) {
   part_t P;
   if (!centre_part(row_ptr, out_ptr, kp_cap, parts, P)) return;
   __shared__ int s_e[64], s_seg[64], s_cnt[64], s_gap[64];
@@ -131,6 +136,12 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
     const int e_off = left >= n_slots ? 0 : slot / left;
     const int pg = pg0 + (left >= n_slots ? slot : slot % left);
     const bool active = e_off < e_step;
+    int row_e[8];   // edge ids of the thread's 8 positions (clamped to the atom's last row)
+#pragma unroll
+    for (int pi = 0; pi < 8; ++pi) {
+      const int pos = P.r0 + (8 * pg + pi < P.d ? 8 * pg + pi : P.d - 1);
+      row_e[pi] = rad_by_pos ? pos : row_edge(row_list, pos);   // rad_by_pos: the radial table was gathered into list order
+    }
     float rad[SM][2][8];
 #pragma unroll
     for (int l = 0; l < SM; ++l)
@@ -142,7 +153,7 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
           const bool ok = active && l < S && c < C && p < P.d;
           // pre-multiplied by the normalisation of Y_l0
           // unconditional load from a clamped (valid) address: no branch around it
-          const float rv = Radt[(int64_t)((l < S ? l : S - 1) * C + (c < C ? c : C - 1)) * E + P.r0 + (p < P.d ? p : P.d - 1)];
+          const float rv = Radt[(int64_t)((l < S ? l : S - 1) * C + (c < C ? c : C - 1)) * E + row_e[pi]];
           rad[l][cc][pi] = rv * (ok ? Y_NORM_M[l] : 0.f);   // the product uses rv on every path: the load cannot sink under a branch
         }
     // From the Legendre expansion sum_l rad[l] P_l(x) to powers of x, once per position and c: the polynomial is then
@@ -173,7 +184,7 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
         int lo = 0, hi = cnt;
         while (lo < hi) {
           const int mid = (lo + hi) >> 1;
-          if (idx_kj[seg + mid] == P.r0 + mid) lo = mid + 1;
+          if (idx_kj[seg + mid] == row_edge(row_list, P.r0 + mid)) lo = mid + 1;
           else hi = mid;
         }
         s_e[threadIdx.x] = e;
@@ -383,7 +394,7 @@ __global__ void __launch_bounds__(MT)
 tripG_mfma_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                   const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_ji,
                   const float* __restrict__ x, const __bf16* __restrict__ Yb, int C, int kp_cap, int parts, int out_half,
-                  float* __restrict__ A) {
+                  const int32_t* __restrict__ row_list, float* __restrict__ A) {
   constexpr int F = 32 * CB;
   part_t P;
   if (!centre_part(row_ptr, out_ptr, kp_cap, parts, P)) return;
@@ -403,8 +414,8 @@ tripG_mfma_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
     const int pp = (t % tiles_p) * 8 + (lane & 7), fq = (t / tiles_p) * 8 + (lane >> 3);
     const int p0 = 2 * pp;
     const bool ok0 = p0 < P.d, ok1 = p0 + 1 < P.d;
-    const f32x4 v0 = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + (ok0 ? p0 : 0)) * F + 4 * fq) * (ok0 ? 1.f : 0.f);
-    const f32x4 v1 = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + (ok1 ? p0 + 1 : 0)) * F + 4 * fq) * (ok1 ? 1.f : 0.f);
+    const f32x4 v0 = *reinterpret_cast<const f32x4*>(x + (int64_t)row_edge(row_list, P.r0 + (ok0 ? p0 : 0)) * F + 4 * fq) * (ok0 ? 1.f : 0.f);
+    const f32x4 v1 = *reinterpret_cast<const f32x4*>(x + (int64_t)row_edge(row_list, P.r0 + (ok1 ? p0 + 1 : 0)) * F + 4 * fq) * (ok1 ? 1.f : 0.f);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       bf16x2 pr;
@@ -549,11 +560,12 @@ __device__ __forceinline__ bool centre_rows(const int32_t* __restrict__ row_ptr,
 // caller synchronises before reading it.
 __host__ __device__ constexpr size_t row_tab_bytes(int cap) { return ((size_t)3 * cap * sizeof(int) + 15) & ~(size_t)15; }
 __device__ __forceinline__ void fill_row_table(const int32_t* __restrict__ seg_ptr_kj, const int32_t* __restrict__ idx_ji_kj,
-                                               const int32_t* __restrict__ outs, const rows_t& P, int* rt, int cap) {
+                                               const int32_t* __restrict__ outs, const rows_t& P, int* rt, int cap,
+                                               const int32_t* __restrict__ row_list = nullptr) {
   const int row0 = P.gb * 8;
   const int nrows = (P.ge * 8 < P.d ? P.ge * 8 : P.d) - row0;
-  for (int r = threadIdx.x; r < nrows; r += blockDim.x) {
-    const rowinfo_t ri = row_info(seg_ptr_kj, idx_ji_kj, outs, P.r0 + row0 + r);
+  for (int r = threadIdx.x; r < nrows && r < cap; r += blockDim.x) {   // cap >= nrows by construction of the launch
+    const rowinfo_t ri = row_info(seg_ptr_kj, idx_ji_kj, outs, row_edge(row_list, P.r0 + row0 + r));
     rt[r] = ri.seg;
     rt[cap + r] = ri.cnt;
     rt[2 * cap + r] = ri.gap;
@@ -590,7 +602,8 @@ __global__ void __launch_bounds__(256)
 tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                     const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_ptr_kj,
                     const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ cos_kj,
-                    const float* __restrict__ dz, int S, int kn_cap, int parts, int rows_cap, float* __restrict__ H) {
+                    const float* __restrict__ dz, int S, int kn_cap, int parts, int rows_cap,
+                    const int32_t* __restrict__ row_list, float* __restrict__ H) {
   constexpr int O = 32 * CB;
   rows_t P;
   if (!centre_rows(row_ptr, out_ptr, parts, P)) return;
@@ -602,7 +615,7 @@ tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restri
   const int LDN = Kn + 8;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int32_t* outs = out_list + P.o0;
-  fill_row_table(seg_ptr_kj, idx_ji_kj, outs, P, row_tab, rows_cap);
+  fill_row_table(seg_ptr_kj, idx_ji_kj, outs, P, row_tab, rows_cap, row_list);
 
   const int tiles_n = Kn / 16;
 #pragma unroll 4
@@ -704,7 +717,7 @@ tripG_mfma_H_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restri
       for (int v = 0; v < 16; ++v) {
         const int p = grp * 8 + rb * 4 + (v >> 2), lo = 4 * kh + (v & 3);
         if (p >= P.d || lo >= S) continue;
-        float* dst = H + ((int64_t)(P.r0 + p) * S + lo) * O + l32;
+        float* dst = H + ((int64_t)row_edge(row_list, P.r0 + p) * S + lo) * O + l32;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) dst[cb * 32] = acc[rb][cb][v];
       }
@@ -1083,12 +1096,14 @@ int kp_of(const gp_graph* g) { return (g->max_in_degree + 15) & ~15; }
 // in-edges (backward kernels: GPW groups of 8 rows each) needs, at most PARTS.  Launching PARTS everywhere
 // would leave most workgroups without work, and starting a workgroup is not free (1280 atoms x 8: 0.2 ms).
 int parts_out(const gp_graph* g) { const int n = (g->max_out_degree + EPP - 1) / EPP; return n < 1 ? 1 : n > PARTS ? PARTS : n; }
-// most in-edge rows in one workgroup's share (centre_rows): the groups of the largest atom over its parts
+int parts_in(const gp_graph* g);
+// Most in-edge rows in one workgroup's share (centre_rows).  An atom with up to GPW groups is one share; a larger one
+// is cut into shares of at most GPW groups unless the number of parts is capped, and then the largest atom has the
+// largest share.  (Not simply the largest atom's share: with 9 groups in 2 parts it has 40 rows, an atom of 7 groups 56.)
 int share_rows(const gp_graph* g) {
-  const int groups = (g->max_in_degree + 7) / 8;
-  int nparts = (groups + GPW - 1) / GPW;
-  nparts = nparts < 1 ? 1 : nparts > PARTS ? PARTS : nparts;
-  return 8 * ((groups + nparts - 1) / nparts);
+  const int groups = (g->max_in_degree + 7) / 8, parts = parts_in(g);
+  const int whole = groups < GPW ? groups : GPW, cut = (groups + parts - 1) / parts;
+  return 8 * (whole > cut ? whole : cut);
 }
 int parts_in(const gp_graph* g) { const int n = (g->max_in_degree + 8 * GPW - 1) / (8 * GPW); return n < 1 ? 1 : n > PARTS ? PARTS : n; }
 int kn_of(const gp_graph* g) { return (g->max_out_degree + 31) & ~31; }
@@ -1140,7 +1155,8 @@ int gp_tripD_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
 }
 
 int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
-                          int F, int S, int C, float* A, void* ybuf, size_t ybytes, int out_half) {
+                          int F, int S, int C, float* A, void* ybuf, size_t ybytes, int out_half, const int32_t* row_list,
+                          int rad_by_pos) {
   const int64_t E = g->n_edges, T = g->n_triplets;
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, gp_tripG_mfma_usable(g, F, S, C), "triplet G (matrix-core form): graph lists or widths not supported");
@@ -1155,10 +1171,10 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
     const int yt = kp_cap >= YT ? YT : (kp_cap + 63) & ~63;
     if (S <= 7)
       tripG_y_kernel<7><<<grid, yt, 0, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj,
-                                                       cos_alpha, Radt, E, S, C, kp_cap, parts, Yb);
+                                                       cos_alpha, Radt, E, S, C, kp_cap, parts, row_list, rad_by_pos, Yb);
     else
       tripG_y_kernel<8><<<grid, yt, 0, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj,
-                                                       cos_alpha, Radt, E, S, C, kp_cap, parts, Yb);
+                                                       cos_alpha, Radt, E, S, C, kp_cap, parts, row_list, rad_by_pos, Yb);
     GP_LAUNCH_CHECK(ctx, "tripG_y_kernel");
   }
   {
@@ -1175,7 +1191,7 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
       lds_set = lds;                                                                                              \
     }                                                                                                             \
     tripG_mfma_kernel<CB><<<grid, mt, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, x,  \
-                                                          Yb, C, kp_cap, parts, out_half, A);                     \
+                                                          Yb, C, kp_cap, parts, out_half, row_list, A);           \
   } while (0)
     switch (F / 32) {
       case 1: GP_TRIPG_LAUNCH(1); break;
@@ -1248,11 +1264,19 @@ bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S) {
   return lds_H(O, kn_of(g)) + tab <= LDS_MAX && (size_t)kn_of(g) * (O + 8) * sizeof(__bf16) + tab <= LDS_MAX;
 }
 
+bool gp_tripG_mfma_H_usable(const gp_graph* g, int O, int S) {
+  if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_out_degree <= 0) return false;
+  if (g->n_triplets <= 0) return false;
+  if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS) return false;
+  if (O % 32 != 0 || O < 32 || O > 128 || S < 1 || S > ST) return false;
+  return lds_H(O, kn_of(g)) + row_tab_bytes(share_rows(g)) <= LDS_MAX;
+}
+
 int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S,
-                             float* H) {
+                             float* H, const int32_t* row_list) {
   const int64_t E = g->n_edges, T = g->n_triplets;
   if (E == 0) return GP_OK;
-  GP_REQUIRE(ctx, gp_tripG_mfma_bwd_usable(g, O, S), "triplet G backward (matrix-core form): graph lists or widths not supported");
+  GP_REQUIRE(ctx, gp_tripG_mfma_H_usable(g, O, S), "triplet G backward (matrix-core form): graph lists or widths not supported");
   GP_REQUIRE(ctx, dz && H && (T == 0 || cos_alpha_kj), "triplet G backward: NULL pointer");
   const int kn_cap = kn_of(g), parts = parts_in(g);
   const unsigned grid = (unsigned)(g->n_atoms * parts);
@@ -1269,7 +1293,7 @@ int gp_tripG_backward_H_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_al
     }                                                                                                                \
     tripG_mfma_H_kernel<CB><<<grid, 256, lds, ctx->stream>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj,     \
                                                              g->idx_ji_kj, cos_alpha_kj, dz, S, kn_cap, parts,       \
-                                                             rows_cap, H);                                           \
+                                                             rows_cap, row_list, H);                                 \
   } while (0)
   switch (O / 32) {
     case 1: GP_TRIPG_LAUNCH(1); break;

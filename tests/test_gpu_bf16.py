@@ -77,3 +77,11 @@ def test_block_G_bf16_narrow_cbf_eight_spherical(lib, ctx, trip_mode):
     w = replace(synth.get_workload("cfg3", emb=64, int_emb=32, emb_rbf=8, emb_cbf=5, emb_bil=16, num_radial=16,
                                    num_spherical=8), max_neighbors=12)
     _parity(lib, ctx, w, 3, 1, synth.slab_adsorbate_positions(2, 4, 4, 3, 10, seed=5), tol=2e-2)
+
+
+def test_block_G_bf16_dense_box_unequal_shares(lib, ctx, trip_mode):
+    # 90 atoms, cutoff 7: in-degrees from about 30 to 90, so the largest atom's rows are cut into two shares of the
+    # backward matrix-core kernels while atoms of 57..64 rows stay whole (the larger share)
+    from dataclasses import replace
+    w = replace(synth.get_workload("cfg3", emb=64, emb_rbf=8, cutoff=7.0), max_neighbors=0)
+    _parity(lib, ctx, w, 5, 1, synth.box_positions(90, 0.08, 0.9, seed=6), tol=2e-2)

@@ -78,10 +78,26 @@ def test_block_G_radial_at_target_cfg3_shape(lib, ctx):
     _parity(lib, ctx, w, 1, 1, synth.slab_adsorbate_positions(1, 8, 5, 4, 40, seed=2))
 
 
-def test_block_G_radial_at_target_cfg4_widths_bf16(lib, ctx):
+@pytest.fixture
+def trip_mode(lib, ctx, request):
+    # 0: per-edge vector triplet kernels, 1: matrix-core kernels whenever usable (here: on the mirrored views)
+    lib.gp_set_triplet_mfma(ctx, request.param)
+    yield request.param
+    lib.gp_set_triplet_mfma(ctx, -1)
+
+
+@pytest.mark.parametrize("trip_mode", [0, 1], indirect=True)
+def test_block_G_radial_at_target_cfg4_widths_bf16(lib, ctx, trip_mode):
     w = synth.get_workload("cfg4", cutoff=6.0, radial_at_target=True)
     assert w.dims.dtype == "bf16"
     _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3), tol=2e-2)
+
+
+@pytest.mark.parametrize("trip_mode", [0, 1], indirect=True)
+def test_block_G_radial_at_target_bf16_capped_two_structures(lib, ctx, trip_mode):
+    # neighbour cap (in- and out-edge lists of an atom differ) and two structures, configuration-3 widths
+    w = synth.get_workload("cfg3", radial_at_target=True)
+    _parity(lib, ctx, w, 3, 1, synth.slab_adsorbate_positions(2, 4, 4, 4, 16, seed=4), tol=2e-2)
 
 
 # ---- symmetric message passing (the two messages on a bond are coupled) ----
@@ -109,6 +125,7 @@ def test_block_G_symmetric_cfg3_shape_capped(lib, ctx):
     _parity(lib, ctx, w, 1, 1, synth.slab_adsorbate_positions(1, 8, 5, 4, 40, seed=2))
 
 
-def test_block_G_symmetric_and_radial_at_target_bf16(lib, ctx):
+@pytest.mark.parametrize("trip_mode", [0, 1], indirect=True)
+def test_block_G_symmetric_and_radial_at_target_bf16(lib, ctx, trip_mode):
     w = synth.get_workload("cfg4", cutoff=6.0, symmetric=True, radial_at_target=True)
     _parity(lib, ctx, w, 2, 1, synth.box_positions(60, 0.08, 0.9, seed=3), tol=2e-2)
