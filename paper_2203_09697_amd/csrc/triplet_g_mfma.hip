@@ -46,8 +46,6 @@ __device__ __constant__ float Y_NORM_M[ST] = {
     0.28209479177387814f, 0.4886025119029199f, 0.6307831305050401f, 0.7463526651802308f,
     0.8462843753216345f, 0.9356025796273888f, 1.0171072362820548f, 1.0925484305920792f};  // sqrt((2l+1)/(4 pi))
 
-// leading coefficient of the Legendre polynomial P_l: (2l)! / (2^l (l!)^2)
-__device__ __constant__ float LEG_LEAD[ST] = {1.f, 1.f, 1.5f, 2.5f, 4.375f, 7.875f, 14.4375f, 26.8125f};
 
 // wavefront-local ordering of LDS traffic (no other wavefront touches the slice concerned)
 __device__ __forceinline__ void wave_lds_sync() {
@@ -71,6 +69,21 @@ __device__ __forceinline__ void atom_and_part(int parts, int& j, int& part) {
 // Edge id of row position pos: the rows of an atom are consecutive edge ids (edges are sorted by target atom) unless
 // a list is given (the mirrored use: rows are the atom's out-edges, listed in out_list order).
 __device__ __forceinline__ int row_edge(const int32_t* __restrict__ row_list, int pos) { return row_list ? row_list[pos] : pos; }
+
+// First slot of a segment whose entry differs from the expected one, given that entries match up to some slot and
+// differ from it on (the segment is the expected list with at most one element left out); cnt if none differs.
+// (An 8-way search with its 8 probes loaded together, 3 memory round trips instead of 9 for 512 slots, measured
+// slower than this binary search: 0.117 vs 0.106 ms for the variant-D forward kernel at configuration 2.)
+template <class Expected>
+__device__ __forceinline__ int first_mismatch(const int32_t* __restrict__ seg_list, int cnt, Expected expected) {
+  int lo = 0, hi = cnt;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (seg_list[mid] == expected(mid)) lo = mid + 1;
+    else hi = mid;
+  }
+  return lo;
+}
 
 // The share of one workgroup: centre atom j, its in-edge rows r0 .. r0+d-1
 // (Kp = d rounded up to 16) and the slice [eb, ee) of its out-edge list.
@@ -181,12 +194,8 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
         const int seg = seg_ptr_ji[e], cnt = seg_ptr_ji[e + 1] - seg;
         // the segment lists rows r0, r0+1, ... with (at most) the row coming from atom i left
         // out: first slot whose row is not r0 + slot
-        int lo = 0, hi = cnt;
-        while (lo < hi) {
-          const int mid = (lo + hi) >> 1;
-          if (idx_kj[seg + mid] == row_edge(row_list, P.r0 + mid)) lo = mid + 1;
-          else hi = mid;
-        }
+        const int r0 = P.r0;
+        const int lo = first_mismatch(idx_kj + seg, cnt, [=](int slot) { return row_edge(row_list, r0 + slot); });
         s_e[threadIdx.x] = e;
         s_seg[threadIdx.x] = seg;
         s_cnt[threadIdx.x] = cnt;
@@ -267,8 +276,7 @@ tripG_y_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
 // in LDS once; the left operand p_t[b] is evaluated in registers from the cosine, one value per lane and MFMA,
 // so nothing of size T is stored.  A wavefront owns 4 out-edges (32 rows) by all F columns.
 constexpr int DB = 8;            // basis_emb of the kernel
-constexpr int LDQ = 64 + 8;      // floats per in-edge row of the staged Q: [l][b], padded so that the two k halves of a
-                                 // wavefront read disjoint banks
+constexpr int LDQ = 64;          // floats per in-edge row of the staged Q: [l][b] (unpadded, like X)
 
 template <int NT>   // F = 32 NT
 __global__ void __launch_bounds__(256)
@@ -277,7 +285,8 @@ tripD_mfma_fwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
                       const int32_t* __restrict__ idx_kj, const float* __restrict__ cos_alpha,
                       const float* __restrict__ x, const float* __restrict__ Qt, const float* __restrict__ W2, int64_t E,
                       int S, int kp_cap, int parts, float* __restrict__ a_out, float* __restrict__ Bacc) {
-  constexpr int F = 32 * NT, LDX = F + 32;   // row stride of the staged X: the two k halves read disjoint banks
+  constexpr int F = 32 * NT, LDX = F;   // row stride of the staged X (padding against the 2-way bank conflict of the
+                                        // two k halves measured 8 % slower: it costs a workgroup per CU)
   part_t P;
   if (!centre_part(row_ptr, out_ptr, kp_cap, parts, P)) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -292,12 +301,23 @@ tripD_mfma_fwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
     const f32x4 v = *reinterpret_cast<const f32x4*>(x + (int64_t)(P.r0 + (p < P.d ? p : 0)) * F + f4) * (p < P.d ? 1.f : 0.f);
     *reinterpret_cast<f32x4*>(&X_s[p * LDX + f4]) = v;
   }
-  for (int i = threadIdx.x; i < P.Kp * 64; i += 256) {
-    const int p = i % P.Kp, lb = i / P.Kp;          // consecutive threads: consecutive rows of one (l, b) line of Qt
-    const int l = lb / DB;
-    float v = 0.f;
-    if (p < P.d && l < S) v = Y_NORM_M[l] * LEG_LEAD[l] * Qt[(int64_t)lb * E + P.r0 + p];
-    Q_s[p * LDQ + lb] = v;
+  // Q of the atom's rows, converted from the Legendre expansion sum_l Y_l0(x) Q[l, b] to powers of x (coefficient k of
+  // column b at k * 8 + b), so that the left operand is one Horner evaluation per triplet and b.  A thread takes
+  // (row p, column b): its 8 loads (clamped addresses, a 0 factor outside the table) are under way together.
+#pragma unroll 2
+  for (int i = threadIdx.x; i < P.Kp * DB; i += 256) {
+    const int p = i % P.Kp, b = i / P.Kp;           // consecutive threads: consecutive rows of one (l, b) line of Qt
+    float ql[ST];
+#pragma unroll
+    for (int l = 0; l < ST; ++l)
+      ql[l] = Qt[(int64_t)((l < S ? l : 0) * DB + b) * E + P.r0 + (p < P.d ? p : 0)] * ((p < P.d && l < S) ? Y_NORM_M[l] : 0.f);
+#pragma unroll
+    for (int k = 0; k < ST; ++k) {
+      float sum = 0.f;
+#pragma unroll
+      for (int l = k; l < ST; l += 2) sum += leg_mono(l, k) * ql[l];
+      Q_s[p * LDQ + k * DB + b] = sum;
+    }
   }
   const int kh = lane >> 5, l32 = lane & 31;
   const int e_loc = l32 >> 3, b = l32 & 7;
@@ -308,12 +328,8 @@ tripD_mfma_fwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
       const int seg = seg_ptr_ji[e], cnt = seg_ptr_ji[e + 1] - seg;
       // the segment lists rows r0, r0+1, ... with (at most) the row coming from atom i left out: first slot
       // whose row is not r0 + slot
-      int lo = 0, hi = cnt;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (idx_kj[seg + mid] == P.r0 + mid) lo = mid + 1;
-        else hi = mid;
-      }
+      const int r0 = P.r0;
+      const int lo = first_mismatch(idx_kj + seg, cnt, [=](int slot) { return r0 + slot; });
       s_e[threadIdx.x] = e;
       s_seg[threadIdx.x] = seg;
       s_cnt[threadIdx.x] = cnt;
@@ -331,32 +347,34 @@ tripD_mfma_fwd_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __rest
       for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-      for (int kp0 = 0; kp0 < P.Kp / 2; kp0 += 4) {
-        float cs[4];
-        bool ok[4];
+      // cosines of 8 k-steps at a time (2 marks "no triplet"), fetched one batch ahead of their use
+      auto load_c = [&](int kp0, float (&c)[8]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {        // the four cosines first, so that their latencies overlap
+        for (int u = 0; u < 8; ++u) {
           const int p = 2 * (kp0 + u) + kh;
           const int slot = p - (p > gap ? 1 : 0);
-          ok[u] = e_ok && p < P.d && p != gap && slot < cnt;
-          cs[u] = cos_alpha[ok[u] ? seg + slot : 0];
+          const bool ok = e_ok && kp0 < P.Kp / 2 && p < P.d && p != gap && slot < cnt;
+          const float cv = cos_alpha[ok ? seg + slot : 0];   // unconditional load, index 0 when unused
+          c[u] = ok ? cv : 2.f;
         }
+      };
+      float cn[8];
+      load_c(0, cn);
+      for (int kp0 = 0; kp0 < P.Kp / 2; kp0 += 8) {   // Kp is a multiple of 16
+        float cs[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int p = 2 * (kp0 + u) + kh;   // < Kp: Kp is a multiple of 16
+        for (int u = 0; u < 8; ++u) cs[u] = cn[u];
+        load_c(kp0 + 8, cn);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int p = 2 * (kp0 + u) + kh;
           const float* q = Q_s + p * LDQ + b;
-          // monic Legendre polynomials pi_{l+1} = x pi_l - l^2/(4 l^2 - 1) pi_{l-1}; the staged Q carries the rest
-          const float cv = cs[u];
-          float p0 = 1.f, p1 = cv;
-          float av = q[0];
+          const bool ok = cs[u] <= 1.5f;
+          const float cv = ok ? cs[u] : 0.f;
+          float av = q[(ST - 1) * DB];
 #pragma unroll
-          for (int l = 1; l < ST; ++l) {
-            av += p1 * q[l * DB];
-            const float p2 = cv * p1 - ((float)(l * l) / (float)(4 * l * l - 1)) * p0;
-            p0 = p1;
-            p1 = p2;
-          }
-          av = ok[u] ? av : 0.f;
+          for (int k = ST - 2; k >= 0; --k) av = av * cv + q[k * DB];
+          av = ok ? av : 0.f;
 #pragma unroll
           for (int t = 0; t < NT; ++t)
             acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, X_s[p * LDX + t * 32 + l32], acc[t], 0, 0, 0);
@@ -519,13 +537,8 @@ __device__ __forceinline__ rowinfo_t row_info(const int32_t* __restrict__ seg_pt
   rowinfo_t r;
   r.seg = seg_ptr_kj[e];
   r.cnt = seg_ptr_kj[e + 1] - r.seg;
-  int lo = 0, hi = r.cnt;   // first slot whose target edge is not the out-edge at the same position
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (idx_ji_kj[r.seg + mid] == outs[mid]) lo = mid + 1;
-    else hi = mid;
-  }
-  r.gap = lo;
+  // first slot whose target edge is not the out-edge at the same position
+  r.gap = first_mismatch(idx_ji_kj + r.seg, r.cnt, [=](int slot) { return outs[slot]; });
   return r;
 }
 
@@ -1127,7 +1140,7 @@ bool gp_tripD_mfma_usable(const gp_graph* g, int F, int S, int B) {
   if (g->n_triplets <= 0) return false;   // the kernel reads cos_alpha[0] for absent triplets
   if (g->n_atoms > INT32_MAX / PARTS) return false;
   if (B != DB || F % 32 != 0 || F < 32 || F > 128 || S < 1 || S > ST) return false;
-  return (size_t)kp_of(g) * (F + 32 + LDQ) * sizeof(float) <= 64 * 1024;
+  return (size_t)kp_of(g) * (F + LDQ) * sizeof(float) <= 64 * 1024;
 }
 
 int gp_tripD_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Qt,
@@ -1138,7 +1151,7 @@ int gp_tripD_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
   GP_REQUIRE(ctx, g->seg_ptr_ji && g->idx_kj && cos_alpha && x && Qt && W2 && a, "triplet D forward: NULL pointer");
   const int kp_cap = kp_of(g), parts = parts_out(g);
   const unsigned grid = (unsigned)(g->n_atoms * parts);
-  const size_t lds = (size_t)kp_cap * (F + 32 + LDQ) * sizeof(float);
+  const size_t lds = (size_t)kp_cap * (F + LDQ) * sizeof(float);
   const double Td = (double)T, Ed = (double)E;
   gp_prof_scope prof(ctx, "tripD_mfma_fwd", Td * 2.0 * (S * B + B * F) + Ed * 2.0 * B * F,
                      Td * 8.0 + Ed * 4.0 * (F + S * B + (Bacc ? B * F : 0) + F) + Ed * 4.0);
