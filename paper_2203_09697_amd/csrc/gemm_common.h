@@ -31,7 +31,9 @@ struct gemm_args {
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ f32x4 ld4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
-__device__ __forceinline__ void st4(float* p, f32x4 v) { *reinterpret_cast<f32x4*>(p) = v; }
+// Epilogue outputs are streamed: [E, N] matrices far larger than the caches, read next by another kernel.  Non-temporal
+// stores measured 1-3 % faster on the store-bound layers and nowhere slower.
+__device__ __forceinline__ void st4(float* p, f32x4 v) { __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p)); }
 
 // element o of a matrix stored as fp32 or (bf) bf16
 __device__ __forceinline__ float ldx(const float* p, int64_t o, unsigned bf) {
@@ -58,7 +60,7 @@ __device__ __forceinline__ void stx4(float* p, int64_t o, unsigned bf, f32x4 v) 
   bf16x4 h;
 #pragma unroll
   for (int c = 0; c < 4; ++c) h[c] = (__bf16)v[c];
-  *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p) + o) = h;
+  __builtin_nontemporal_store(h, reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p) + o));
 }
 
 __device__ __forceinline__ void epilogue_store(const gp_epilogue& e, int64_t row, int col, int n, float v) {
