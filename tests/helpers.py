@@ -34,7 +34,7 @@ def oracle_basis_D(pos, g, dims):
     rad = obasis.sbf_radial(d, dims.cutoff, dims.num_spherical, dims.num_radial, dims.envelope_p)
     Y = obasis.y_l0(ca, dims.num_spherical)
     kj = torch.as_tensor(g["idx_kj"], dtype=torch.long)
-    sbf = (rad[kj] * Y[:, :, None]).reshape(len(kj), -1)
+    sbf = (rad[kj] * Y[:, :, None]).reshape(len(kj), rad.shape[1] * rad.shape[2])   # explicit width: also for 0 triplets
     return dict(d=d, unit=unit, cos_alpha=ca, rbf=rbf, rad=rad.reshape(rad.shape[0], -1), sbf=sbf)
 
 
@@ -45,6 +45,7 @@ def oracle_stack_D(g, ob, dims, W_list, m, gup):
     out = oblock.stack_D(mt, ob["rbf"], ob["sbf"], g["idx_kj"], g["idx_ji"], Wt, dims.n_res_before, dims.n_res_after)
     leaves = [mt] + [W[k] for W in Wt for k in W]
     grads = oblock.loss_and_grads(out, torch.tensor(gup, dtype=F64), leaves)
+    grads = [torch.zeros_like(l) if gr is None else gr for gr, l in zip(grads, leaves)]   # a leaf the output does not depend on
     gm = grads[0].numpy()
     gW, i = [], 1
     for W in Wt:
@@ -70,6 +71,7 @@ def oracle_stack_G(g, ob, dims, W_list, m, gup, want_grad_rbf=False):
     out = oblock.stack_G(mt, rbf, ob["Y"], g["idx_kj"], g["idx_ji"], Wt, getattr(dims, "radial_at_target", False), id_swap)
     leaves = [mt, rbf] + [W[k] for W in Wt for k in W]
     grads = oblock.loss_and_grads(out, torch.tensor(gup, dtype=F64), leaves)
+    grads = [torch.zeros_like(l) if gr is None else gr for gr, l in zip(grads, leaves)]   # a leaf the output does not depend on
     gm, grbf = grads[0].numpy(), grads[1].numpy()
     gW, i = [], 2
     for W in Wt:
