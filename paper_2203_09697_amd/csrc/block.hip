@@ -199,9 +199,14 @@ int gp_block_forward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, 
   const int H = dims->emb, F = dims->int_emb, B = dims->basis_emb, S = dims->num_spherical, R = dims->num_radial;
   float* x_ji = sc.buf[0];
 
+  // The projected radial table is needed only by the triplet kernel and the projection of the target-edge message only by
+  // the epilogue of the up-projection: both run on the side stream next to the chain that leads to the triplet sum (one
+  // GEMM of this size leaves part of the chip idle).
+  gp_aux aux(ctx);
+  GP_TRY(aux.on_aux([&] { return gp_tripD_project_radial(ctx, basis->rad, w->W_sbf1, E, S, R, B, s.Q); }, {s.Q}));
   gp_epilogue e;
   e.bias = w->b_ji; e.save_pre = s.z_ji; e.act = 1; e.out = x_ji;
-  GP_TRY(gp_gemm_nn(ctx, m_in, w->W_ji, E, H, H, e));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_nn(ctx, m_in, w->W_ji, E, H, H, e); }, {}));
   e = gp_epilogue(); e.out = s.Wrbf;
   GP_TRY(gp_gemm_nn(ctx, w->W_rbf1, w->W_rbf2, R, H, B, e));
   e = gp_epilogue(); e.out = s.gate;
@@ -210,12 +215,13 @@ int gp_block_forward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, 
   GP_TRY(gp_gemm_nn(ctx, m_in, w->W_kj, E, H, H, e));
   e = gp_epilogue(); e.save_pre = s.z_dn; e.act = 1; e.out = s.x_kj;
   GP_TRY(gp_gemm_nn(ctx, s.xg, w->W_down, E, F, H, e));
-  GP_TRY(gp_tripD_project_radial(ctx, basis->rad, w->W_sbf1, E, S, R, B, s.Q));
+  GP_TRY(aux.before_write(s.Q));   // the projected radial table, written on the side stream
   if (ctx->trip_mfma != 0 && gp_tripD_mfma_usable(graph, F, S, B))
     GP_TRY(gp_tripD_forward_mfma(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a,
                                  bwd_mfma_D(ctx, dims, graph) ? nullptr : s.Bacc));
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a, s.Bacc));
+  GP_TRY(aux.join());
   e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = x_ji; e.out = s.h0;
   GP_TRY(gp_gemm_nn(ctx, s.a, w->W_up, E, H, F, e));
 
