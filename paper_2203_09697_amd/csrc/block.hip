@@ -317,8 +317,22 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
     dzcur = dznext;
   }
   // h0 = x_ji + act(a W_up);  dh = dh0, dzcur = dz_up
+  // The branch through x_ji = act(m W_ji + b_ji) needs dh0 only: all of it (dz_ji, both gradients) runs on the side
+  // stream next to the chain through the triplet sum, whose kernels leave much of the chip idle; its input gradient
+  // is added by the epilogue of the last GEMM below.
+  float* const dz_kj = dzcur;   // free again once the two GEMMs that read dz_up are done
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.a, dzcur, E, F, H, gw->W_up, nullptr, sc.part_aux, sc.part_bytes); },
                     {dzcur}));
+  float* const dz_ji = other_dz();   // last read by side-stream work issued earlier, and written there: no wait needed
+  float* const dm_ji = next_buf();
+  GP_TRY(aux.on_aux(
+      [&] {
+        GP_TRY(gp_ew_dsilu_mul(ctx, dh, s.z_ji, dz_ji, EH));
+        GP_TRY(gp_gemm_tn(ctx, m_in, dz_ji, E, H, H, gw->W_ji, gw->b_ji, sc.part_aux, sc.part_bytes));
+        gp_epilogue e; e.out = dm_ji;
+        return gp_gemm_nt(ctx, dz_ji, w->W_ji, E, H, H, e);
+      },
+      {dz_ji, dm_ji}));
   {
     gp_epilogue e; e.out = sc.dF1;
     GP_TRY(gp_gemm_nt(ctx, dzcur, w->W_up, E, F, H, e));                                     // da
@@ -331,8 +345,13 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
   else
     GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, s.x_kj, s.Q, w->W_sbf2, sc.dF1, s.z_dn, F, S, B,
                              sc.dF2, sc.dQ));                                                 // dz_dn, dQ
-  GP_TRY(gp_tripD_weight_grads(ctx, sc.dF1, bwd_mfma ? nullptr : s.Bacc, basis->rad, sc.dQ, E, F, S, R, B, gw->W_sbf2,
-                               gw->W_sbf1, sc.part, sc.part_bytes));
+  // weight gradients that nothing below waits for: side stream (its own split-K buffer; its kernels run in order)
+  GP_TRY(aux.on_aux(
+      [&] {
+        return gp_tripD_weight_grads(ctx, sc.dF1, bwd_mfma ? nullptr : s.Bacc, basis->rad, sc.dQ, E, F, S, R, B, gw->W_sbf2,
+                                     gw->W_sbf1, sc.part_aux, sc.part_bytes);
+      },
+      {}));
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dF2, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes); },
                     {sc.dF2}));
   {
@@ -340,25 +359,19 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
     gp_epilogue e; e.out = T2;
     GP_TRY(gp_gemm_nt(ctx, sc.dF2, w->W_down, E, H, F, e));                                  // dxg
   }
-  GP_TRY(aux.before_write(T3));
-  GP_TRY(gp_ew_gate_bwd(ctx, T2, s.z_kj, s.gate, T3, dgate, EH));                            // dz_kj, dgate
+  GP_TRY(aux.before_write(dz_kj));
+  GP_TRY(gp_ew_gate_bwd(ctx, T2, s.z_kj, s.gate, dz_kj, dgate, EH));                         // dz_kj, dgate
   GP_TRY(gp_gemm_tn(ctx, basis->rbf, dgate, E, R, H, sc.dWrbf, nullptr, sc.part, sc.part_bytes));
   {
     gp_epilogue e; e.out = gw->W_rbf1;
     GP_TRY(gp_gemm_nt(ctx, sc.dWrbf, w->W_rbf2, R, B, H, e));
   }
   GP_TRY(gp_gemm_tn(ctx, w->W_rbf1, sc.dWrbf, R, B, H, gw->W_rbf2, nullptr, sc.part, sc.part_bytes));
-  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, T3, E, H, H, gw->W_kj, gw->b_kj, sc.part_aux, sc.part_bytes); }, {T3}));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, dz_kj, E, H, H, gw->W_kj, gw->b_kj, sc.part_aux, sc.part_bytes); }, {dz_kj}));
   {
-    gp_epilogue e; e.add_post = keep; e.out = grad_m_in;
-    GP_TRY(gp_gemm_nt(ctx, T3, w->W_kj, E, H, H, e));                                        // dm = skip + kj path
-  }
-  GP_TRY(aux.before_write(T1));
-  GP_TRY(gp_ew_dsilu_mul(ctx, dh, s.z_ji, T1, EH));                                          // dz_ji
-  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_in, T1, E, H, H, gw->W_ji, gw->b_ji, sc.part_aux, sc.part_bytes); }, {T1}));
-  {
-    gp_epilogue e; e.add_post = grad_m_in; e.out = grad_m_in;
-    GP_TRY(gp_gemm_nt(ctx, T1, w->W_ji, E, H, H, e));                                        // dm += ji path
+    GP_TRY(aux.before_write(dm_ji));   // the side stream's input gradient of the ji path
+    gp_epilogue e; e.add_pre = dm_ji; e.add_post = keep; e.out = grad_m_in;
+    GP_TRY(gp_gemm_nt(ctx, dz_kj, w->W_kj, E, H, H, e));                                     // dm = kj path + ji path + skip
   }
   return aux.join();
 }
