@@ -198,3 +198,34 @@ def test_block_D_deterministic(lib, ctx):
     g2, gw2 = st.backward(H.to_dev(gup, torch.float32))
     assert torch.equal(o1, o2) and torch.equal(g1, g2)
     assert all(torch.equal(gw1[k], gw2[0][k]) for k in gw1)
+
+
+def test_block_D_two_streams_match_one_stream(lib, ctx):
+    # With the side stream on, graphs of 2048 edges or more run the layers after the triplet sum as two row halves on
+    # two streams and parts of the backward pass beside the main chain; the forward is the same arithmetic per row,
+    # so it must agree bit for bit with the single-stream run, and the gradients (one sum taken in another order) closely.
+    from paper_2203_09697_amd.stack import StackD
+    w = synth.get_workload("cfg2")
+    pos, ref, e, t = _case(lib, ctx, w, 5, synth.slab_adsorbate_positions(2, 4, 4, 4, 16, seed=5))
+    E = len(ref["src"])
+    assert E >= 2048
+    W = [lib.weights_to_device(synth.weights_D(w.dims, seed=31 + b, bias_scale=0.1)) for b in range(2)]
+    m, gup = synth.edge_embeddings(E, w.dims.emb, seed=8)
+    gb = lib.gp_basis_forward(ctx, w.dims, e, t)
+    res = []
+    try:
+        for on in (True, False):
+            lib.gp_set_side_stream(ctx, on)
+            st = StackD(ctx, w.dims, W, t, gb)
+            out = st.forward(H.to_dev(m, torch.float32)).clone()
+            gm, gw = st.backward(H.to_dev(gup, torch.float32))
+            torch.cuda.synchronize()
+            res.append((out, gm.clone(), [{k: v.clone() for k, v in g.items()} for g in gw]))
+    finally:
+        lib.gp_set_side_stream(ctx, True)
+    (o2, g2, w2), (o1, g1, w1) = res
+    assert torch.equal(o2, o1)
+    assert H.rel_l2(g2.cpu().numpy(), g1.cpu().numpy()) < 1e-6
+    for b in range(2):
+        for k in w1[b]:
+            assert H.rel_l2(w2[b][k].cpu().numpy(), w1[b][k].cpu().numpy()) < 1e-6, (b, k)
