@@ -46,8 +46,11 @@ void gp_destroy(gp_ctx* ctx);
 const char* gp_last_error(const gp_ctx* ctx);
 const char* gp_version(void);
 
-/* The backward passes issue their weight-gradient GEMMs on a second, library-owned stream next to
- * the input-gradient chain and join it before returning (callers see single-stream semantics).
+/* The block calls issue work that their main chain does not wait for at once on a second, library-owned
+ * stream and join it before returning, so callers see single-stream semantics: the weight-gradient GEMMs of
+ * the backward passes next to the input-gradient chain; in the variant-D block also the branch through the
+ * target-edge projection and, from 2048 edges on, one half of the rows of the layers after the triplet sum
+ * (the same arithmetic per row: the forward result does not depend on the setting).
  * gp_set_side_stream(ctx, 0) keeps everything on the context's stream, e.g. to time kernels one
  * at a time; the environment variable GP_NO_AUX_STREAM=1 has the same effect at gp_create. */
 int gp_set_side_stream(gp_ctx* ctx, int on);
