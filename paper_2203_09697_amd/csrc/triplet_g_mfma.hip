@@ -546,7 +546,7 @@ __device__ __forceinline__ rowinfo_t row_info(const int32_t* __restrict__ seg_pt
 struct rows_t {
   int r0, d, o0, dout, gb, ge;
 };
-constexpr int GPW = 8;   // row groups per workgroup aimed at (two per wavefront)
+constexpr int GPW = 8;   // row groups per workgroup aimed at (two per wavefront; 4: variant-D backward kernel 0.130 -> 0.155 ms)
 
 __device__ __forceinline__ bool centre_rows(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                                             int parts, rows_t& P) {
@@ -1105,10 +1105,13 @@ tripG_mfma_dcos_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __res
 }
 
 int kp_of(const gp_graph* g) { return (g->max_in_degree + 15) & ~15; }
-// Workgroups per centre atom: as many as the atom with the most out-edges (forward kernels: EPP edges each) or
+// Workgroups per centre atom: as many as the atom with the most out-edges (forward kernels: PART_EDGES edges each) or
 // in-edges (backward kernels: GPW groups of 8 rows each) needs, at most PARTS.  Launching PARTS everywhere
 // would leave most workgroups without work, and starting a workgroup is not free (1280 atoms x 8: 0.2 ms).
-int parts_out(const gp_graph* g) { const int n = (g->max_out_degree + EPP - 1) / EPP; return n < 1 ? 1 : n > PARTS ? PARTS : n; }
+// (Shares of 32 rather than 64 out-edges: variant-D forward kernel 0.106 -> 0.080 ms at configuration 2, y kernel and
+// contraction 0.094 + 0.114 -> 0.076 + 0.083 ms at configuration 3; 16: the same.  Configuration 4 has 8 parts either way.)
+constexpr int PART_EDGES = 32;
+int parts_out(const gp_graph* g) { const int n = (g->max_out_degree + PART_EDGES - 1) / PART_EDGES; return n < 1 ? 1 : n > PARTS ? PARTS : n; }
 int parts_in(const gp_graph* g);
 // Most in-edge rows in one workgroup's share (centre_rows).  An atom with up to GPW groups is one share; a larger one
 // is cut into shares of at most GPW groups unless the number of parts is capped, and then the largest atom has the
