@@ -36,6 +36,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int ST = 8;        // max num_spherical
 constexpr int CP = 16;       // rows per edge in an MFMA tile = max emb_cbf
 constexpr int PARTS = 8;     // at most this many workgroups share one centre atom
+#ifndef GP_PARTS_IN
+#define GP_PARTS_IN 12
+#endif
+constexpr int PARTS_IN = GP_PARTS_IN;   // ... for the backward kernels, whose shares are in-edge rows (configuration 4: H kernel 1.19 ms
+                                        // with 8, 1.04 with 12 or 16; the forward kernels get 1 % slower above 8)
 constexpr int EPP = 64;      // target edges per workgroup
 constexpr int YT = 256;      // most threads of the y kernel (one per position of the longest row, rounded to 64)
 constexpr int MT = 512;      // most threads of the contraction kernel
@@ -1121,7 +1126,7 @@ int share_rows(const gp_graph* g) {
   const int whole = groups < GPW ? groups : GPW, cut = (groups + parts - 1) / parts;
   return 8 * (whole > cut ? whole : cut);
 }
-int parts_in(const gp_graph* g) { const int n = (g->max_in_degree + 8 * GPW - 1) / (8 * GPW); return n < 1 ? 1 : n > PARTS ? PARTS : n; }
+int parts_in(const gp_graph* g) { const int n = (g->max_in_degree + 8 * GPW - 1) / (8 * GPW); return n < 1 ? 1 : n > PARTS_IN ? PARTS_IN : n; }
 int kn_of(const gp_graph* g) { return (g->max_out_degree + 31) & ~31; }
 // dz of the out-edges (bf16, transposed)
 size_t lds_H(int O, int kn) { return (size_t)(kn + 8) * O * sizeof(__bf16); }
@@ -1133,7 +1138,7 @@ size_t gp_tripG_mfma_scratch(int64_t E, int64_t T) { return gp_align((size_t)(T 
 bool gp_tripG_mfma_usable(const gp_graph* g, int F, int S, int C) {
   if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_in_degree <= 0) return false;
   if (g->n_triplets <= 0) return false;   // the kernels read cos_alpha[0] for absent triplets
-  if (g->n_atoms > INT32_MAX / PARTS) return false;
+  if (g->n_atoms > INT32_MAX / PARTS_IN) return false;
   if (F % 32 != 0 || F < 32 || F > 128 || C < 1 || C > CP || S < 1 || S > ST) return false;
   return (size_t)F * (kp_of(g) + 8) * sizeof(__bf16) <= LDS_MAX;
 }
@@ -1141,7 +1146,7 @@ bool gp_tripG_mfma_usable(const gp_graph* g, int F, int S, int C) {
 bool gp_tripD_mfma_usable(const gp_graph* g, int F, int S, int B) {
   if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_in_degree <= 0) return false;
   if (g->n_triplets <= 0) return false;   // the kernel reads cos_alpha[0] for absent triplets
-  if (g->n_atoms > INT32_MAX / PARTS) return false;
+  if (g->n_atoms > INT32_MAX / PARTS_IN) return false;
   if (B != DB || F % 32 != 0 || F < 32 || F > 128 || S < 1 || S > ST) return false;
   return (size_t)kp_of(g) * (F + LDQ) * sizeof(float) <= 64 * 1024;
 }
@@ -1231,7 +1236,7 @@ size_t lds_D_bwd(int F, int kn) {
 bool gp_tripD_mfma_bwd_usable(const gp_graph* g, int F, int S, int B) {
   if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_out_degree <= 0) return false;
   if (g->n_triplets <= 0) return false;   // the kernel reads cos_alpha_kj[0] for absent triplets
-  if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS) return false;
+  if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS_IN) return false;
   if (B != DB || F % 32 != 0 || F < 32 || F > 128 || S < 1 || S > ST) return false;
   const int kn = (g->max_out_degree + 15) & ~15;
   return lds_D_bwd(F, kn) + row_tab_bytes(share_rows(g)) <= 64 * 1024;
@@ -1274,7 +1279,7 @@ int gp_tripD_backward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
 bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S) {
   if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_out_degree <= 0) return false;
   if (g->n_triplets <= 0) return false;   // the kernels read cos_alpha_kj[0] for absent triplets
-  if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS) return false;
+  if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS_IN) return false;
   if (O % 32 != 0 || O < 32 || O > 128 || S < 1 || S > ST) return false;
   const size_t tab = row_tab_bytes(share_rows(g));   // the kernels' row table
   return lds_H(O, kn_of(g)) + tab <= LDS_MAX && (size_t)kn_of(g) * (O + 8) * sizeof(__bf16) + tab <= LDS_MAX;
@@ -1283,7 +1288,7 @@ bool gp_tripG_mfma_bwd_usable(const gp_graph* g, int O, int S) {
 bool gp_tripG_mfma_H_usable(const gp_graph* g, int O, int S) {
   if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->max_out_degree <= 0) return false;
   if (g->n_triplets <= 0) return false;
-  if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS) return false;
+  if (!g->seg_ptr_kj || !g->idx_ji_kj || g->n_atoms > INT32_MAX / PARTS_IN) return false;
   if (O % 32 != 0 || O < 32 || O > 128 || S < 1 || S > ST) return false;
   return lds_H(O, kn_of(g)) + row_tab_bytes(share_rows(g)) <= LDS_MAX;
 }
