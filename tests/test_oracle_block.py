@@ -80,7 +80,7 @@ def test_gradients_match_central_differences(variant):
     for name, g in zip(names, grads):
         t = leaves[name]
         flat = t.detach().view(-1)
-        for idx in rng.choice(flat.numel(), size=min(6, flat.numel()), replace=False):
+        for idx in rng.choice(flat.numel(), size=min(64, flat.numel()), replace=False):
             old = float(flat[idx])
             with torch.no_grad():
                 flat[idx] = old + h; lp = float(loss())
@@ -287,8 +287,7 @@ def test_forces_are_negative_energy_gradient(variant):
     pos = s["pos"].astype(np.float64)
     h = 1e-4
     rng = np.random.default_rng(0)
-    for _ in range(8):
-        a, c = rng.integers(len(pos)), rng.integers(3)
+    for a, c in [(a, c) for a in range(len(pos)) for c in range(3)]:      # every coordinate
         pp, pm = pos.copy(), pos.copy()
         pp[a, c] += h; pm[a, c] -= h
         with torch.no_grad():
@@ -371,7 +370,7 @@ def test_radial_at_target_factorises_and_differentiates():
     L = (block.block_G(s["m"], gq, Y, s["idx_kj"], s["idx_ji"], W, radial_at_target=True) * s["gup"]).sum()
     (grad,) = torch.autograd.grad(L, gq)
     rng = np.random.default_rng(2)
-    for idx in rng.choice(g.numel(), size=8, replace=False):
+    for idx in rng.choice(g.numel(), size=64, replace=False):
         h = 1e-6
         def at(delta):
             y = g.clone().reshape(-1)
@@ -437,7 +436,7 @@ def test_symmetric_block_matches_explicit_loops_and_gradients():
     mq, wq = s["m"].clone().requires_grad_(True), W["W_up_ac"].clone().requires_grad_(True)
     gm, gw = torch.autograd.grad(loss(mq, wq), [mq, wq])
     for name, x0, gr in (("m", s["m"], gm), ("W_up_ac", W["W_up_ac"], gw)):
-        for idx in rng.choice(x0.numel(), size=6, replace=False):
+        for idx in rng.choice(x0.numel(), size=min(64, x0.numel()), replace=False):
             h = 1e-6
             def at(delta):
                 yv = x0.clone().reshape(-1)
