@@ -17,6 +17,23 @@ def rel_l2(got, ref):
     return float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got))
 
 
+def row_err(got, ref):
+    """Largest per-row relative L2 error: max_r |got_r - ref_r| / max(|ref_r|, rms row norm of ref).
+    A whole-tensor norm hides a few corrupted rows among 1e5 good ones; this does not.  Rows whose own norm is
+    below the tensor's rms row norm are measured against that rms (their own norm may be arbitrarily small)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    got = got.reshape(got.shape[0], -1) if got.ndim > 1 else got.reshape(-1, 1)
+    ref = ref.reshape(got.shape)
+    if ref.size == 0:
+        return 0.0
+    rn = np.sqrt((ref * ref).sum(axis=1))
+    floor = np.sqrt((rn * rn).mean())
+    if floor == 0:
+        return float(np.sqrt(((got - ref) ** 2).sum(axis=1)).max())
+    return float((np.sqrt(((got - ref) ** 2).sum(axis=1)) / np.maximum(rn, floor)).max())
+
+
 def t64(w):
     return {k: torch.tensor(np.asarray(v), dtype=F64) for k, v in w.items()}
 
@@ -62,14 +79,17 @@ def oracle_basis_G(pos, g, dims):
     return dict(d=d, unit=unit, cos_alpha=ca, rbf=rbf, Y=Y)
 
 
-def oracle_stack_G(g, ob, dims, W_list, m, gup, want_grad_rbf=False):
-    """Forward + gradients of L = sum(out * gup) w.r.t. m, every weight and (optionally) the radial basis."""
+def oracle_stack_G(g, ob, dims, W_list, m, gup, want_grad_rbf=False, want_grad_cos=False):
+    """Forward + gradients of L = sum(out * gup) w.r.t. m, every weight and the radial basis; with want_grad_cos
+    also w.r.t. cos(alpha) of every triplet, returned in kj-major order (sorted by (idx_kj, idx_ji))."""
     Wt = [{k: v.clone().requires_grad_(True) for k, v in t64(W).items()} for W in W_list]
     mt = torch.tensor(m, dtype=F64, requires_grad=True)
     rbf = ob["rbf"].detach().clone().requires_grad_(True)
     id_swap = ograph.reverse_edges(g["src"], g["dst"]) if getattr(dims, "symmetric", False) else None
-    out = oblock.stack_G(mt, rbf, ob["Y"], g["idx_kj"], g["idx_ji"], Wt, getattr(dims, "radial_at_target", False), id_swap)
-    leaves = [mt, rbf] + [W[k] for W in Wt for k in W]
+    cos = ob["cos_alpha"].detach().clone().requires_grad_(True)
+    Y = obasis.y_l0(cos, dims.num_spherical) if want_grad_cos else ob["Y"]
+    out = oblock.stack_G(mt, rbf, Y, g["idx_kj"], g["idx_ji"], Wt, getattr(dims, "radial_at_target", False), id_swap)
+    leaves = [mt, rbf] + [W[k] for W in Wt for k in W] + ([cos] if want_grad_cos else [])
     grads = oblock.loss_and_grads(out, torch.tensor(gup, dtype=F64), leaves)
     grads = [torch.zeros_like(l) if gr is None else gr for gr, l in zip(grads, leaves)]   # a leaf the output does not depend on
     gm, grbf = grads[0].numpy(), grads[1].numpy()
@@ -77,6 +97,9 @@ def oracle_stack_G(g, ob, dims, W_list, m, gup, want_grad_rbf=False):
     for W in Wt:
         gW.append({k: grads[i + j].numpy() for j, k in enumerate(W)})
         i += len(W)
+    if want_grad_cos:
+        order = np.lexsort((np.asarray(g["idx_ji"]), np.asarray(g["idx_kj"])))
+        return out.detach().numpy(), gm, gW, grbf, grads[-1].numpy()[order]
     return out.detach().numpy(), gm, gW, grbf
 
 

@@ -109,3 +109,61 @@ def test_forces_symmetric(lib, ctx):
     pos, E_gpu, f_gpu, E_ref, f_ref, e = _force_case(lib, ctx, w, synth.cube_positions(30, 6.0, 0.9, seed=3), 6, 2, 7)
     assert abs(E_gpu.sum() - E_ref) <= 1e-4 * max(1.0, abs(E_ref))
     assert H.rel_l2(f_gpu, f_ref) <= 1e-4, H.rel_l2(f_gpu, f_ref)
+
+
+# ---- graphs whose atoms need several shares of the per-centre-atom kernels -------------------------
+def _dense_box():
+    # 90 atoms, cutoff 7: in-degrees from about 30 to 90; the backward matrix-core kernels cut the rows of an atom
+    # into shares of 64, the forward ones its out-edges into shares of 32, so most atoms span 2-3 shares
+    from dataclasses import replace
+    return replace(synth.get_workload("cfg3", emb=64, emb_rbf=8, cutoff=7.0), max_neighbors=0), synth.box_positions(90, 0.08, 0.9, seed=6)
+
+
+@pytest.mark.parametrize("mode", [1, 0], ids=["matrix-core triplets", "vector triplets"])
+def test_forces_dense_box_bf16_several_shares(lib, ctx, mode):
+    w, pos_gptr = _dense_box()
+    lib.gp_set_triplet_mfma(ctx, mode)
+    try:
+        pos, E_gpu, f_gpu, E_ref, f_ref, e = _force_case(lib, ctx, w, pos_gptr, 8, 2, 32)
+    finally:
+        lib.gp_set_triplet_mfma(ctx, -1)
+    deg = np.diff(e["row_ptr"].cpu().numpy())
+    assert deg.max() > 64 and deg.min() < 64
+    assert abs(E_gpu.sum() - E_ref) <= 2e-2 * max(1.0, abs(E_ref))
+    assert H.rel_l2(f_gpu, f_ref) <= 2e-2, H.rel_l2(f_gpu, f_ref)
+    assert H.row_err(f_gpu, f_ref) <= 4 * 2e-2, H.row_err(f_gpu, f_ref)
+
+
+def test_forces_dense_box_fp32(lib, ctx):
+    from dataclasses import replace
+    w, pos_gptr = _dense_box()
+    w = replace(w, dims=replace(w.dims, dtype="f32"))
+    pos, E_gpu, f_gpu, E_ref, f_ref, e = _force_case(lib, ctx, w, pos_gptr, 8, 2, 32)
+    assert abs(E_gpu.sum() - E_ref) <= 1e-4 * max(1.0, abs(E_ref))
+    assert H.rel_l2(f_gpu, f_ref) <= 1e-4, H.rel_l2(f_gpu, f_ref)
+    assert H.row_err(f_gpu, f_ref) <= 4e-4, H.row_err(f_gpu, f_ref)
+
+
+@pytest.mark.timeout(900)
+def test_forces_cfg5_model_on_a_box_the_oracle_can_follow(lib, ctx):
+    """The whole force-training model of configuration 5 (3 bilinear blocks at its widths, bf16 GEMM operands, energy
+    head of width 256, forces) on a box of the same density and cutoff that is small enough for the full oracle
+    (which keeps every triplet's outer product for its reverse pass, 16 KB per triplet and block): 80 atoms,
+    in-degrees up to 79, so two or three shares per atom in every per-centre-atom kernel.  The matrix-core triplet
+    kernels are forced on, as the library picks them at full size (this box has 78 triplets per edge, below the
+    96 from which it would choose them by itself)."""
+    w = synth.get_workload("cfg5")
+    pos_gptr = synth.box_positions(80, 0.08, 0.9, seed=2)
+    lib.gp_set_triplet_mfma(ctx, 1)
+    try:
+        pos, E_gpu, f_gpu, E_ref, f_ref, e = _force_case(lib, ctx, w, pos_gptr, 0, w.n_blocks, w.head_hidden)
+    finally:
+        lib.gp_set_triplet_mfma(ctx, -1)
+    deg = np.diff(e["row_ptr"].cpu().numpy())
+    assert deg.max() > 64
+    err = np.abs(f_gpu - f_ref).max()
+    print("cfg5 model, 80-atom box: E=%d  max|f|=%.4e  max-abs force error=%.3e  rel-L2=%.2e" % (
+        len(e["src"]), np.abs(f_ref).max(), err, H.rel_l2(f_gpu, f_ref)))
+    assert abs(E_gpu.sum() - E_ref) <= 2e-2 * max(1.0, abs(E_ref))
+    assert H.rel_l2(f_gpu, f_ref) <= 2e-2, H.rel_l2(f_gpu, f_ref)
+    assert err <= 4 * 2e-2 * np.abs(f_ref).max()
