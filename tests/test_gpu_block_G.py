@@ -12,6 +12,8 @@ from tests import helpers as H
 pytestmark = pytest.mark.gpu
 TOL = 1e-4
 ROW_FACTOR = 4.0     # a row may deviate this much more than the whole tensor (single rows do not average rounding noise)
+ELEM_FACTOR = 16.0   # the same for tensors whose rows are single numbers (one value per triplet): nothing averages there, and
+                     # an element's rounding error scales with the size of ITS terms, whose distribution has a long tail
 
 
 @pytest.fixture(scope="module")
@@ -54,7 +56,7 @@ def _parity(lib, ctx, workload, seed, n_blocks, pos_gptr, tol=TOL):
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, bad
     # per-row bound: no row (edge, triplet, weight row) may be off by more than ROW_FACTOR times the tensor bound
-    bad = {k: v for k, v in rows.items() if not v <= ROW_FACTOR * tol}
+    bad = {k: v for k, v in rows.items() if not v <= (ELEM_FACTOR if pairs[k][1].ndim == 1 else ROW_FACTOR) * tol}
     assert not bad, ("per-row", bad)
     return errs
 
