@@ -21,12 +21,13 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_f32": (157.3, "TFLOP/s"), "mfma_bf16": (2
 ALU_KERNELS = ("tripD_fwd", "tripD_bwd", "tripG_fwd", "trip_bwd_H", "tripG_grad_cos", "tripG_edge")
 
 
-def measured_traffic(workload):
+def measured_traffic(workload, modified):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if any
-    (profiles/block_<variant>_<workload>_hbm_traffic.md; counters cannot be read from inside the run)."""
+    (profiles/block_<variant>_<workload>_hbm_traffic.md; counters cannot be read from inside the run).
+    Nothing for a run whose flags change the workload: the summaries cover the plain workloads only."""
     path = os.path.join(ROOT, "profiles", "block_%s_%s_hbm_traffic.md" % (workload.dims.variant, workload.name))
     out = {}
-    if os.path.exists(path):
+    if os.path.exists(path) and not modified:
         for line in open(path):
             cells = [c.strip() for c in line.strip().strip("|").split("|")]
             if len(cells) == 5 and cells[1].isdigit():
@@ -43,7 +44,9 @@ def sample_system(workload, seed):
         args[0] = max(1, args[0] // 2) if workload.dims.variant == "D" else 1
         return synth.slab_adsorbate_positions(*args, seed=seed), "%d of %d structures" % (args[0], workload.system_args[0])
     if workload.system == "box":
-        args[0] = 120
+        # the oracle keeps 16 KB per triplet and block for its reverse pass: 100 atoms (about 1e6 triplets) for one
+        # block, 80 atoms for the three blocks of the force workload
+        args[0] = 80 if workload.head_hidden else 100
         return synth.box_positions(*args, seed=seed), "%d-atom box at the same density and cutoff (workload: %d atoms)" % (
             args[0], workload.system_args[0])
     return synth.make_positions(workload, seed), "whole workload"
@@ -75,16 +78,48 @@ def cpu_baseline(workload, seed):
         Wh = H.t64(synth.weights_head(dims.emb, workload.head_hidden, seed=99))
         m64 = torch.tensor(m, dtype=torch.float64)
         run = lambda: oenergy.forces(oenergy.energy_G, pos, g["src"], g["dst"], g["idx_kj"], g["idx_ji"], m64, W_list, Wh, dims)
-    reps, dt = 0, 0.0
+    reps, dt, last = 0, 0.0, None
     while reps < 1 or (dt < 10.0 and reps < 8):      # about 10-30 s of CPU work in total
         t0 = time.perf_counter()
-        run()
+        last = run()
         dt += time.perf_counter() - t0
         reps += 1
-    return {"value": T * workload.n_blocks * reps / dt, "unit": "triplets/s", "cores": torch.get_num_threads(),
-            "kind": "oracle",
-            "sample": "%s (%d edges, %d triplets), %d blocks fwd+bwd in fp64, %d passes, %.1f s"
-                      % (what, E, T, workload.n_blocks, reps, dt)}
+    res = {"value": T * workload.n_blocks * reps / dt, "unit": "triplets/s", "cores": torch.get_num_threads(),
+           "kind": "oracle",
+           "sample": "%s (%d edges, %d triplets), %d blocks fwd+bwd in fp64, %d passes, %.1f s"
+                     % (what, E, T, workload.n_blocks, reps, dt)}
+    extra = None
+    if workload.head_hidden:
+        # force workload: the oracle's forces on the sample are also the reference for the library's forces there
+        extra = force_check(workload, seed, pos, gptr, m, last, what)
+    return res, extra
+
+
+def force_check(workload, seed, pos, gptr, m, oracle_result, what):
+    """The library's energy and forces for the sample structure the oracle has just been timed on (same model:
+    blocks, widths, head, bf16 GEMM operands, matrix-core triplet kernels as at full size) against the oracle's."""
+    import numpy as np
+    import torch
+
+    import paper_2203_09697_amd as gp
+    import synth
+    from paper_2203_09697_amd.binding_e import ForceModelG
+    dims = workload.dims
+    _e_ref, f_ref = oracle_result
+    ctx = gp.Context(0)
+    gp.gp_set_triplet_mfma(ctx, 1)
+    dptr = torch.as_tensor(gptr).to("cuda:0")
+    e, t = gp.build_graph(ctx, torch.as_tensor(pos).to("cuda:0"), dptr, dims.cutoff, workload.max_neighbors)
+    basis = gp.gp_basis_forward(ctx, dims, e, t)
+    W_list = [gp.weights_to_device(synth.weights_G(dims, seed=100 + b)) for b in range(workload.n_blocks)]
+    Wh = gp.weights_to_device(synth.weights_head(dims.emb, workload.head_hidden, seed=99))
+    model = ForceModelG(ctx, dims, W_list, Wh, workload.head_hidden, e, t, basis, dptr)
+    en, f = model.energy_and_forces(torch.as_tensor(m).to("cuda:0"))
+    torch.cuda.synchronize()
+    f = f.cpu().numpy().astype(np.float64)
+    return {"sample": what, "n_edges": e["n_edges"], "n_triplets": t["n_triplets"],
+            "force_max_abs_error": float(np.abs(f - f_ref).max()), "force_max_abs": float(np.abs(f_ref).max()),
+            "force_rel_l2": float(np.linalg.norm(f - f_ref) / np.linalg.norm(f_ref))}
 
 
 def main():
@@ -92,7 +127,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--workload", default="cfg4",
+                    help="cfg4 (default): the largest single-GPU configuration, 1000 atoms, 3e5 edges, 1e8 triplets, the "
+                         "paper's large-model widths; cfg1..cfg3 are the smaller parity cases, cfg5 the force-training step")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-kernels", action="store_true", help="list every kernel of the step, not only the ten longest")
@@ -230,12 +267,34 @@ def main():
                                                   "mfma_f32" if k["bound"] == "mfma" else None)
         k["frac_of_measured"] = round(k["achieved"] / measured[key], 4) if key else None
     top = kernels[0]
-    traffic = measured_traffic(w)
+    traffic = measured_traffic(w, bool(opts) or a.output_blocks)
     for k in kernels:
         k["traffic"] = traffic.get(k["kernel"])
     roofline = {"kernel": top["kernel"], "bound": top["bound"], "achieved": top["achieved"], "peak": top["peak"],
                 "unit": top["unit"], "frac": top["frac"], "frac_of_measured": top["frac_of_measured"], "avg_ms": top["avg_ms"],
                 "traffic": top["traffic"]}
+
+    # second roofline entry: the TripletUpdate + TripletAggr kernels of the forward pass taken together (they move the
+    # per-triplet data), as effective HBM rate = algorithmic bytes / their time.  Algorithmic bytes of the bilinear form
+    # with the accumulator materialised: 12 B per triplet (cos alpha and the two edge indices), the accumulator A as
+    # stored, the gathered rows x once and the radial table once; of the Hadamard form with the basis projection fused:
+    # 8 B per triplet (cos alpha, source-edge index), x and the radial table once, the aggregate once.
+    trip_names = ("tripG_y", "tripG_mfma_fwd", "tripG_fused_fwd", "tripG_fwd", "tripD_mfma_fwd", "tripD_fwd")
+    tk = [k for k in kernels if k["kernel"] in trip_names]
+    roofline_triplet = None
+    if tk:
+        F, S = dims.int_emb, dims.num_spherical
+        if dims.variant == "G":
+            a_bytes = 2.0 if any(k["kernel"] in ("tripG_mfma_fwd", "tripG_fused_fwd") for k in tk) else 4.0
+            alg = 12.0 * T + E * (4.0 * F + a_bytes * dims.emb_cbf * F + 4.0 * S * dims.emb_cbf)
+        else:
+            alg = 8.0 * T + E * (4.0 * F + 4.0 * F + 4.0 * S * dims.basis_emb)
+        per_block_ms = sum(k["ms_per_step"] for k in tk) / w.n_blocks
+        tr = [k["traffic"] for k in tk]
+        roofline_triplet = {"kernels": [k["kernel"] for k in tk], "bound": "hbm", "achieved": round(alg / (per_block_ms * 1e-3) / 1e9, 1),
+                            "peak": PEAK["hbm"][0], "unit": "GB/s", "frac": round(alg / (per_block_ms * 1e-3) / 1e9 / PEAK["hbm"][0], 4),
+                            "algorithmic_bytes": alg, "ms_per_block": round(per_block_ms, 4),
+                            "traffic": sum(tr) if all(x is not None for x in tr) else None}
 
     out = {
         "metric": "triplets/sec (interaction block fwd+bwd), 1 MI355X", "value": value, "unit": "triplets/s",
@@ -249,12 +308,15 @@ def main():
                                                         (", symmetric messages" if a.symmetric else "")),
                    "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed},
         "roofline": roofline,
+        "roofline_triplet": roofline_triplet,
         "measured_peaks": {k: round(v, 1) for k, v in mp.items()},
         "kernels": kernels if a.all_kernels else kernels[:10],
         "graph_build_ms": round(graph_ms, 3), "basis_ms": round(basis_ms, 3), "wall_ms_per_step": round(wall_ms / a.steps, 4),
     }
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, a.seed)
+        out["cpu_baseline"], fc = cpu_baseline(w, a.seed)
+        if fc is not None:
+            out["force_check"] = fc
     print(json.dumps(out))
 
 
