@@ -376,6 +376,17 @@ int gp_edges_by_source_workspace(int64_t n_atoms, int64_t n_edges, size_t* bytes
 int gp_edges_by_source(gp_ctx* ctx, const int32_t* src, int64_t n_atoms, int64_t n_edges,
                        void* ws, size_t ws_bytes, int32_t* out_ptr, int32_t* out_list);
 
+/* The same lists for callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the counters and the unsorted list live in a
+ * static device array inside the library (about 8.5 MiB per GPU, held until the process ends), so the call takes
+ * only inputs and outputs, allocates nothing and records no memset node (it clears its counters with a kernel).
+ * Limits: n_atoms <= 65536 and n_edges <= 2097152, beyond which it returns GP_UNSUPPORTED_DIMS; results are
+ * identical to gp_edges_by_source.  All calls on one GPU share that array: calls that overlap on one GPU (different
+ * streams or contexts) race and must be serialised by the caller.  GP_HIP_ERROR if the array's address could not
+ * be obtained on the context's device. */
+int gp_edges_by_source_static(gp_ctx* ctx, const int32_t* src, int64_t n_atoms, int64_t n_edges,
+                              int32_t* out_ptr, int32_t* out_list);
+
 /* forces[N,3] = -dL/dx given dL/dg (grad_rbf[E,R], Gaussian radial basis of variant G) and
  * dL/dcos(alpha) (grad_cos_kj[T], kj-major), with the graph held fixed:
  *   d d_e/dx_dst = u_e, d d_e/dx_src = -u_e;  cos(alpha_t) = -u_ji . u_kj, u_e = (x_dst-x_src)/d_e.

@@ -7,7 +7,7 @@ import torch
 __all__ = [
     "GpError", "load", "library_path", "Context", "Dims", "Graph", "Basis",
     "gp_version", "gp_profile_enable", "gp_profile_reset", "gp_profile_collect", "gp_set_side_stream", "gp_set_triplet_mfma",
-    "gp_measure_peaks", "gp_edges_by_source", "gp_reverse_edges", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
+    "gp_measure_peaks", "gp_edges_by_source", "gp_edges_by_source_static", "gp_reverse_edges", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
     "gp_block_forward_D", "gp_block_backward_D", "gp_triplet_aggregate_fwd",
     "gp_triplet_aggregate_bwd", "gp_linear_forward", "build_graph", "weights_to_device",
     "EXPORTED_SYMBOLS", "D_WEIGHT_ORDER",
@@ -30,7 +30,7 @@ EXPORTED_SYMBOLS = [
     "gp_block_forward_G", "gp_block_backward_G",
     "gp_energy_workspace", "gp_energy_forward", "gp_energy_backward",
     "gp_output_workspace", "gp_output_forward", "gp_output_backward",
-    "gp_edges_by_source_workspace", "gp_edges_by_source", "gp_forces_workspace", "gp_forces_from_basis_grad",
+    "gp_edges_by_source_workspace", "gp_edges_by_source", "gp_edges_by_source_static", "gp_forces_workspace", "gp_forces_from_basis_grad",
     "gp_triplet_aggregate_fwd", "gp_triplet_aggregate_bwd", "gp_linear_forward", "gp_linear_forward_bf16",
 ]
 
@@ -313,6 +313,13 @@ def gp_edges_by_source(ctx, edges):
     out_list = torch.empty(E, dtype=torch.int32, device=ctx.device)
     ctx.check(lib.gp_edges_by_source(ctx._h, _ptr(edges["src"]), C.c_int64(N), C.c_int64(E), _ptr(ws),
                                      C.c_size_t(ws.numel()), _ptr(out_ptr), _ptr(out_list)))
+    return out_ptr, out_list
+
+
+def gp_edges_by_source_static(ctx, src, n_atoms, out_ptr, out_list):
+    """The allocation-free variant: inputs and outputs only (all given by the caller), scratch inside the library."""
+    ctx.check(load().gp_edges_by_source_static(ctx._h, _ptr(src), C.c_int64(n_atoms), C.c_int64(src.shape[0]),
+                                               _ptr(out_ptr), _ptr(out_list)))
     return out_ptr, out_list
 
 

@@ -6,6 +6,8 @@
 
 #include "common.h"
 
+int gp_static_scratch_init(int device);   // energy.hip: address of the allocation-free entry point's scratch array
+
 extern "C" {
 
 const char* gp_version(void) { return "gpgnn 0.1 (gfx950)"; }
@@ -22,6 +24,9 @@ int gp_create(gp_ctx** out, int device_id, void* hip_stream) {
   // side stream at the default priority; without it everything simply runs on the main stream
   if (hipSetDevice(device_id) != hipSuccess || hipStreamCreateWithFlags(&c->aux_stream, hipStreamNonBlocking) != hipSuccess)
     c->aux_stream = nullptr;
+  // per-device address of the static scratch (the device is current here); a failure is reported by the entry point
+  // that needs it, not here
+  (void)gp_static_scratch_init(device_id);
   const char* no_aux = getenv("GP_NO_AUX_STREAM");
   c->use_aux = !(no_aux && no_aux[0] == '1');
   const char* tm = getenv("GP_TRIPLET_MFMA");

@@ -11,9 +11,33 @@
 #include "gemm.h"
 #include "triplet.h"
 
+#include <mutex>
+
 namespace {
 
 constexpr int WPB = 4;
+
+// ------------------------------------------------------------------ scratch of the allocation-free entry point
+// gp_edges_by_source_static keeps its counters and its unsorted list in this file-scope device array instead of a
+// caller's workspace.  Every GPU the library runs on holds its own copy for the life of the process.  In host code
+// the array's name is only a handle for hipGetSymbolAddress: the device address is looked up once per device
+// (gp_static_scratch_init, called by gp_create with that device current) and only that address is ever handed to
+// kernels.
+constexpr int64_t STATIC_MAX_ATOMS = 65536;
+constexpr int64_t STATIC_MAX_EDGES = 2097152;
+constexpr size_t STATIC_CNT_BYTES = sizeof(int32_t) * STATIC_MAX_ATOMS;            // a multiple of 256
+constexpr size_t STATIC_BYTES = 2 * STATIC_CNT_BYTES + sizeof(int32_t) * STATIC_MAX_EDGES;
+static __device__ __align__(256) unsigned char scratch[STATIC_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[MAX_DEVICES] = {nullptr};
+hipError_t g_static_err[MAX_DEVICES] = {hipSuccess};
+
+__global__ void fill_zero_kernel(int32_t* __restrict__ p, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
 
 // ------------------------------------------------------------------ out-edge lists (by source)
 __global__ void hist_kernel(const int32_t* __restrict__ key, int64_t n, int32_t* __restrict__ cnt) {
@@ -251,7 +275,59 @@ size_t carve_forces(void* p, int64_t E, int64_t T, forces_ws* w) {
 
 }  // namespace
 
+// Looks up this device's address of the static scratch array (once per device; the device must be current).
+int gp_static_scratch_init(int device) {
+  if (device < 0 || device >= MAX_DEVICES) return GP_BAD_ARG;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (g_static_ptr[device]) return GP_OK;
+  void* ptr = nullptr;
+  hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+  g_static_err[device] = e;
+  if (e != hipSuccess || !ptr) return GP_HIP_ERROR;
+  g_static_ptr[device] = ptr;
+  return GP_OK;
+}
+
 extern "C" {
+
+int gp_edges_by_source_static(gp_ctx* ctx, const int32_t* src, int64_t n_atoms, int64_t n_edges,
+                              int32_t* out_ptr, int32_t* out_list) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_REQUIRE(ctx, n_atoms >= 0 && n_edges >= 0 && out_ptr, "gp_edges_by_source_static: bad arguments");
+  if (n_atoms > STATIC_MAX_ATOMS || n_edges > STATIC_MAX_EDGES)
+    return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "gp_edges_by_source_static: %lld atoms / %lld edges exceed the static scratch "
+                   "(at most %lld atoms, %lld edges); use gp_edges_by_source with a workspace", (long long)n_atoms,
+                   (long long)n_edges, (long long)STATIC_MAX_ATOMS, (long long)STATIC_MAX_EDGES);
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  void* base = nullptr;
+  hipError_t init_err = hipSuccess;
+  if (ctx->device < MAX_DEVICES) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    base = g_static_ptr[ctx->device];
+    init_err = g_static_err[ctx->device];
+  }
+  if (!base)
+    return gp_fail(ctx, GP_HIP_ERROR, "gp_edges_by_source_static: no address for the static scratch on device %d (%s)",
+                   ctx->device, hipGetErrorString(init_err));
+  hipStream_t st = ctx->stream;
+  if (n_atoms == 0 || n_edges == 0) {
+    fill_zero_kernel<<<nblk(n_atoms + 1), 256, 0, st>>>(out_ptr, n_atoms + 1);
+    GP_LAUNCH_CHECK(ctx, "fill_zero_kernel");
+    return GP_OK;
+  }
+  GP_REQUIRE(ctx, src && out_list, "gp_edges_by_source_static: NULL pointer");
+  // the two counter arrays are adjacent: one fill clears both; the array keeps the previous call's contents
+  int32_t* cnt = (int32_t*)base;
+  int32_t* cursor = (int32_t*)((char*)base + STATIC_CNT_BYTES);
+  int32_t* tmp = (int32_t*)((char*)base + 2 * STATIC_CNT_BYTES);
+  fill_zero_kernel<<<nblk(2 * STATIC_MAX_ATOMS), 256, 0, st>>>(cnt, 2 * STATIC_MAX_ATOMS);
+  hist_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, cnt);
+  scan_small_kernel<<<1, 1024, 0, st>>>(cnt, n_atoms, out_ptr);
+  scatter_by_key_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, out_ptr, cursor, tmp);
+  sort_lists_kernel<<<wblk(n_atoms), 256, 0, st>>>(out_ptr, tmp, n_atoms, out_list);
+  GP_LAUNCH_CHECK(ctx, "edges_by_source kernels");
+  return GP_OK;
+}
 
 int gp_edges_by_source_workspace(int64_t n_atoms, int64_t n_edges, size_t* bytes) {
   if (!bytes || n_atoms < 0 || n_edges < 0) return GP_BAD_ARG;
