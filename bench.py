@@ -279,7 +279,7 @@ def main():
     # with the accumulator materialised: 12 B per triplet (cos alpha and the two edge indices), the accumulator A as
     # stored, the gathered rows x once and the radial table once; of the Hadamard form with the basis projection fused:
     # 8 B per triplet (cos alpha, source-edge index), x and the radial table once, the aggregate once.
-    trip_names = ("tripG_y", "tripG_mfma_fwd", "tripG_fused_fwd", "tripG_fwd", "tripD_mfma_fwd", "tripD_fwd")
+    trip_names = ("tripG_y", "tripG_mfma_fwd", "tripG_pack", "tripG_fused_fwd", "tripG_fwd", "tripD_mfma_fwd", "tripD_fwd")
     tk = [k for k in kernels if k["kernel"] in trip_names]
     roofline_triplet = None
     if tk:

@@ -59,7 +59,9 @@ int gp_set_side_stream(gp_ctx* ctx, int on);
  * carries its lists by centre atom they can run as dense products per centre atom on the matrix
  * cores.  mode 1: whenever the widths allow; 0: never (one wavefront per edge on the vector
  * units); -1 (default): only for graphs with at least 96 triplets per edge on average, where the
- * dense form pays.  GP_TRIPLET_MFMA=0/1 in the environment sets the mode at gp_create. */
+ * dense form pays; 2: as 1, but the forward sum in its two-kernel form (a kernel writes the per-triplet
+ * basis projection y in bf16, a second one contracts it) instead of the one-pass kernel that evaluates y in
+ * registers (kept for comparison).  GP_TRIPLET_MFMA=0/1/2 in the environment sets the mode at gp_create. */
 int gp_set_triplet_mfma(gp_ctx* ctx, int mode);
 
 /* Measurement aid (not a step of the method): while enabled, every kernel launch the library
@@ -257,8 +259,10 @@ typedef struct {
   float *res_after[GP_MAX_RES][4];
 } gp_weights_D;
 
-/* Bytes of the activation buffer kept from forward to backward, and of scratch space. */
-int gp_block_workspace(const gp_dims* dims, int64_t n_edges, int64_t n_triplets,
+/* Bytes of the activation buffer kept from forward to backward, and of scratch space.  n_atoms: gp_graph.n_atoms
+ * of the graph the block will run on (0 if it carries no lists by centre atom); a scratch buffer sized with 0 is
+ * accepted for any graph, the one-pass matrix-core triplet kernel of the bilinear block then stays unused. */
+int gp_block_workspace(const gp_dims* dims, int64_t n_atoms, int64_t n_edges, int64_t n_triplets,
                        size_t* saved_bytes /*host*/, size_t* scratch_bytes /*host*/);
 
 /* m_out[E,emb] = Block(m_in[E,emb]).  `saved` is written for the backward pass. */

@@ -352,11 +352,11 @@ def gp_basis_forward(ctx, dims, edges, trip, want_sbf=False):
 
 
 # ------------------------------------------------------------------ block
-def gp_block_workspace(dims, n_edges, n_triplets):
+def gp_block_workspace(dims, n_edges, n_triplets, n_atoms=0):
     lib = load()
     d = Dims(dims)
     a, b = C.c_size_t(), C.c_size_t()
-    rc = lib.gp_block_workspace(C.byref(d), C.c_int64(n_edges), C.c_int64(n_triplets), C.byref(a), C.byref(b))
+    rc = lib.gp_block_workspace(C.byref(d), C.c_int64(n_atoms), C.c_int64(n_edges), C.c_int64(n_triplets), C.byref(a), C.byref(b))
     if rc != 0:
         raise GpError(rc, "gp_block_workspace")
     return a.value, b.value

@@ -50,7 +50,7 @@ class StackG:
         self.w = weights_list
         self.n_blocks = len(weights_list)
         E, T = trip["n_edges"], trip["n_triplets"]
-        saved_b, scratch_b = B.gp_block_workspace(dims, E, T)
+        saved_b, scratch_b = B.gp_block_workspace(dims, E, T, trip.get("n_atoms", 0) if trip.get("out_list") is not None else 0)
         dev = ctx.device
         self.saved = [torch.empty(max(saved_b, 8), dtype=torch.uint8, device=dev) for _ in range(self.n_blocks)]
         self.scratch = torch.empty(max(scratch_b, 8), dtype=torch.uint8, device=dev)

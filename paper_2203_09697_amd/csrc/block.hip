@@ -161,9 +161,9 @@ int res_backward(gp_ctx* ctx, gp_aux& aux, const float* hin, float* const* w, fl
 
 extern "C" {
 
-int gp_block_workspace(const gp_dims* dims, int64_t n_edges, int64_t n_triplets, size_t* saved_bytes,
+int gp_block_workspace(const gp_dims* dims, int64_t n_atoms, int64_t n_edges, int64_t n_triplets, size_t* saved_bytes,
                        size_t* scratch_bytes) {
-  if (!dims || !saved_bytes || !scratch_bytes || n_edges < 0 || n_triplets < 0) return GP_BAD_ARG;
+  if (!dims || !saved_bytes || !scratch_bytes || n_atoms < 0 || n_edges < 0 || n_triplets < 0) return GP_BAD_ARG;
   if (dims->variant == GP_VARIANT_D) {
     saved_D s;
     scratch_D sc;
@@ -173,7 +173,7 @@ int gp_block_workspace(const gp_dims* dims, int64_t n_edges, int64_t n_triplets,
   }
   if (dims->variant == GP_VARIANT_G) {
     *saved_bytes = gp_block_G_saved_bytes(dims, n_edges);
-    *scratch_bytes = gp_block_G_scratch_bytes(dims, n_edges, n_triplets);
+    *scratch_bytes = gp_block_G_scratch_bytes(dims, n_atoms, n_edges, n_triplets);
     return GP_OK;
   }
   return GP_UNSUPPORTED_DIMS;

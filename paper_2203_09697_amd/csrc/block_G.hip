@@ -83,7 +83,7 @@ size_t part_bytes_G(const gp_dims* d, int64_t E) {
   return m;
 }
 
-size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, int64_t T, scratch_G* s) {
+size_t carve_scratch_G(void* p, const gp_dims* d, int64_t N, int64_t E, int64_t T, scratch_G* s) {
   gp_carver c(p);
   const size_t H = d->emb, F = d->int_emb, C = d->emb_cbf, O = d->emb_bil, S = d->num_spherical, R = d->num_radial;
   for (int i = 0; i < 4; ++i) s->eh[i] = c.take<float>(E * H);
@@ -101,7 +101,9 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t E, int64_t T, scratch_
   s->part_bytes = part_bytes_G(d, E);
   s->part = (float*)c.take<char>(s->part_bytes);
   s->part_aux = (float*)c.take<char>(s->part_bytes);
-  s->ybytes = d->dtype == GP_BF16_F32ACC ? gp_tripG_mfma_scratch(E, T) : 0;
+  // scratch of the matrix-core triplet kernels: the per-triplet y buffer of the two-kernel form, or the per-atom
+  // operand tables of the fused form (N > 0: the graph carries its lists by centre atom)
+  s->ybytes = d->dtype == GP_BF16_F32ACC ? std::max(gp_tripG_mfma_scratch(E, T), N > 0 ? gp_tripG_fused_scratch(N, E, d->int_emb) : (size_t)0) : 0;
   s->ybuf = c.take<char>(s->ybytes);
   const bool rt = d->radial_at_target != 0;
   s->dA = c.take<float>(rt ? E * C * F : 0);
@@ -349,7 +351,7 @@ __global__ void permute_add_kernel(const float* __restrict__ src, const int32_t*
 constexpr double MFMA_FWD_DENSITY = 32.0, MFMA_BWD_DENSITY = 96.0;
 bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g, double min_density) {
   if (d->dtype != GP_BF16_F32ACC || ctx->trip_mfma == 0 || d->radial_at_target) return false;
-  if (ctx->trip_mfma == 1) return true;
+  if (ctx->trip_mfma >= 1) return true;
   return g->n_edges > 0 && (double)g->n_triplets >= min_density * (double)g->n_edges;
 }
 
@@ -357,7 +359,7 @@ bool want_trip_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g, doub
 bool want_rt_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g, double min_density) {
   if (d->dtype != GP_BF16_F32ACC || ctx->trip_mfma == 0 || !d->radial_at_target) return false;
   if (!g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0) return false;
-  if (ctx->trip_mfma == 1) return true;
+  if (ctx->trip_mfma >= 1) return true;
   return g->n_edges > 0 && (double)g->n_triplets >= min_density * (double)g->n_edges;
 }
 
@@ -406,9 +408,9 @@ size_t gp_block_G_saved_bytes(const gp_dims* d, int64_t E) {
   saved_G s;
   return carve_saved_G(nullptr, d, E, &s);
 }
-size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E, int64_t T) {
+size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t N, int64_t E, int64_t T) {
   scratch_G s;
-  return carve_scratch_G(nullptr, d, E, T, &s);
+  return carve_scratch_G(nullptr, d, N, E, T, &s);
 }
 
 extern "C" {
@@ -428,7 +430,11 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   saved_G s;
   scratch_G sc;
   if (saved_bytes < carve_saved_G(saved, dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: saved buffer too small");
-  if (scratch_bytes < carve_scratch_G(scratch, dims, E, graph->n_triplets, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: scratch too small");
+  // a scratch buffer sized without the centre-atom lists (n_atoms = 0 in the query) is accepted: the fused triplet
+  // kernel, whose tables depend on the number of atoms, is then not used
+  if (scratch_bytes < carve_scratch_G(scratch, dims, graph->n_atoms, E, graph->n_triplets, &sc) &&
+      scratch_bytes < carve_scratch_G(scratch, dims, 0, E, graph->n_triplets, &sc))
+    return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: scratch too small");
   GP_HIP(ctx, hipSetDevice(ctx->device));
   gp_bf16_scope gemm_dtype(ctx, dims->dtype == GP_BF16_F32ACC);
   const int H = dims->emb, F = dims->int_emb, C = dims->emb_cbf, O = dims->emb_bil, S = dims->num_spherical,
@@ -481,8 +487,14 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     } else
       GP_TRY(gp_tripD_backward(ctx, &gm, basis->cos_alpha, nullptr, nullptr, nullptr, s.x, nullptr, F, S, 1, s.B1, nullptr));
     GP_TRY(gp_tripG_edge_G(ctx, s.Radt, s.B1, E, S, C, F, s.A));
-  } else if (want_trip_mfma(ctx, dims, graph, MFMA_FWD_DENSITY) && gp_tripG_mfma_usable(graph, F, S, C))
-    GP_TRY(gp_tripG_forward_mfma(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes, ah));
+  } else if (want_trip_mfma(ctx, dims, graph, MFMA_FWD_DENSITY) && gp_tripG_mfma_usable(graph, F, S, C)) {
+    // one pass with y evaluated in registers where the widths allow and the scratch holds its tables; the two-kernel
+    // form with the per-triplet y buffer otherwise, or when asked for (mode 2)
+    if (ctx->trip_mfma != 2 && gp_tripG_fused_usable(graph, F, S, C) && sc.ybytes >= gp_tripG_fused_scratch(graph->n_atoms, E, F))
+      GP_TRY(gp_tripG_forward_fused(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes, ah));
+    else
+      GP_TRY(gp_tripG_forward_mfma(ctx, graph, basis->cos_alpha, s.x, s.Radt, F, S, C, s.A, sc.ybuf, sc.ybytes, ah));
+  }
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
   e = gp_epilogue(); e.out = s.z;
@@ -533,7 +545,9 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   saved_G s;
   scratch_G sc;
   if (saved_bytes < carve_saved_G(const_cast<void*>(saved), dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: saved buffer too small");
-  if (scratch_bytes < carve_scratch_G(scratch, dims, E, graph->n_triplets, &sc)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: scratch too small");
+  if (scratch_bytes < carve_scratch_G(scratch, dims, graph->n_atoms, E, graph->n_triplets, &sc) &&
+      scratch_bytes < carve_scratch_G(scratch, dims, 0, E, graph->n_triplets, &sc))
+    return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: scratch too small");
   GP_HIP(ctx, hipSetDevice(ctx->device));
   gp_bf16_scope gemm_dtype(ctx, dims->dtype == GP_BF16_F32ACC);
   const int H = dims->emb, F = dims->int_emb, C = dims->emb_cbf, O = dims->emb_bil, S = dims->num_spherical,

@@ -25,7 +25,8 @@ struct gp_ctx {
   bool gemm_bf16 = false;   // set by a block call whose dims ask for bf16 GEMM operands
   hipStream_t aux_stream = nullptr;   // side stream for weight-gradient GEMMs (see aux_stream.h)
   bool use_aux = true;
-  int trip_mfma = -1;       // matrix-core triplet kernels of the bilinear block: -1 by graph density, 0 never, 1 whenever usable
+  int trip_mfma = -1;       // matrix-core triplet kernels of the bilinear block: -1 by graph density, 0 never, 1 whenever usable,
+                            // 2 as 1 but the forward pass in its two-kernel form (per-triplet y buffer) instead of the fused one
   std::vector<hipEvent_t> aux_event_pool;
   std::vector<gp_prof_entry> prof;
   std::vector<hipEvent_t> event_pool;

@@ -42,7 +42,7 @@ int gp_tripD_weight_grads(gp_ctx* ctx, const float* grad_a, const float* Bacc, c
 
 // workspace sizes of the variant-G block (block_G.hip)
 size_t gp_block_G_saved_bytes(const gp_dims* d, int64_t E);
-size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t E, int64_t T);
+size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t N, int64_t E, int64_t T);   // N: atoms of the graph's centre-atom lists, or 0
 
 // ---- variant G (bilinear interaction, Sec. 3.4) ---------------------------------------------
 // The forward accumulator A[e,c,f] = sum_t y_t[c] x[kj(t),f], y_t[c] = sum_l Y_l(t) Rad[kj(t),l,c],
@@ -76,6 +76,13 @@ size_t gp_tripG_mfma_scratch(int64_t E, int64_t T);
 int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
                           int F, int S, int C, float* A, void* ybuf, size_t ybytes, int out_half = 0,   // out_half: A is bf16
                           const int32_t* row_list = nullptr, int rad_by_pos = 0);
+// The same accumulator in one pass, without the per-triplet y buffer (triplet_g_fused.hip): y is evaluated in
+// registers inside the contraction kernel from a per-row coefficient table that a pre-pass lays out per centre
+// atom.  F = 32, 64 or 128; rows must be consecutive edge ids (no row_list).  ws: gp_tripG_fused_scratch bytes.
+bool gp_tripG_fused_usable(const gp_graph* g, int F, int S, int C);
+size_t gp_tripG_fused_scratch(int64_t N, int64_t E, int F);
+int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
+                           int F, int S, int C, float* A, void* ws, size_t ws_bytes, int out_half);
 // rad_by_pos: Radt's columns are in row_list order already (gathered by the caller)
 // row_list: edge ids of the atoms' rows where these are not consecutive (the mirrored views of a block with the
 // radial factor at the target edge: g->row_ptr then indexes row_list, and g->out_list holds consecutive ids)

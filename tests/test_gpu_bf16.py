@@ -44,10 +44,11 @@ def test_linear_forward_bf16(lib, ctx, rows, k, n, act):
     assert H.rel_l2(out, refr) < 2e-5
 
 
-@pytest.fixture(params=[1, 0], ids=["matrix-core triplets", "vector triplets"])
+@pytest.fixture(params=[1, 2, 0], ids=["matrix-core triplets", "matrix-core triplets, two-kernel forward", "vector triplets"])
 def trip_mode(request, lib, ctx):
-    """Both forms of the triplet sums of the bf16 block: per centre atom on the matrix cores (forced
-    on: these graphs are below the density at which the library picks it by itself) and per edge."""
+    """All forms of the triplet sums of the bf16 block: per centre atom on the matrix cores (forced on: these graphs
+    are below the density at which the library picks it by itself), with the forward sum in one pass (y evaluated
+    in registers) or as two kernels (per-triplet y buffer), and per edge on the vector units."""
     lib.gp_set_triplet_mfma(ctx, request.param)
     yield request.param
     lib.gp_set_triplet_mfma(ctx, -1)
