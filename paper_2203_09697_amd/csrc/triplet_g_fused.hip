@@ -28,21 +28,30 @@ namespace {
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
-constexpr int GE = 32;          // out-edges per work item
-constexpr int SLAB = 64;        // in-edge rows per slab
+constexpr int GE = 16;          // out-edges per work item (4 wavefronts x 4 edges)
+constexpr int SLAB = 32;        // in-edge rows per slab (one step of the matrix-core contraction)
+constexpr int ROWPAD = 64;      // every atom's rows are padded to a multiple of this in the packed tables
 constexpr int PADJ = 72;        // padded row space per atom: base_j = roundup8(row_ptr[j]) + PADJ j leaves room for
-                                // rounding every atom's rows up to a whole slab (d + 63) on an 8-aligned base (+ 7)
+                                // rounding every atom's rows up to a multiple of 64 (d + 63) on an 8-aligned base (+ 7)
 constexpr int COEF_ROW = 128;   // floats per padded row of the coefficient table: [half][c 16][4]
-constexpr int FT = 512;         // threads of the main kernel
+constexpr int FT = 256;         // threads of the main kernel
 
 __host__ __device__ inline int64_t padded_base(int r0, int64_t j) { return (((int64_t)r0 + 7) & ~(int64_t)7) + PADJ * j; }
-inline int64_t padded_rows(int64_t E, int64_t N) { return ((E + 7) & ~(int64_t)7) + PADJ * N + SLAB; }
+inline int64_t padded_rows(int64_t E, int64_t N) { return ((E + 7) & ~(int64_t)7) + PADJ * N + ROWPAD; }
 
-__device__ __forceinline__ int swz(int f) { return f ^ ((f >> 3) & 7); }   // 16-byte slot of feature f inside a p-block
+// Row r of a 16-row tile t of the matrix-core product stands for feature NT * rowperm(r) + t.  With rowperm the
+// transposition of r = 4 g + i to 4 i + g, the 4 accumulator registers i of lane (g, c) hold, over the NT tiles,
+// features NT (4 i + g) .. + NT - 1: for every i the lanes g = 0..3 of a column c together own 4 NT consecutive
+// features, so a store instruction writes whole 64-byte runs (NT = 8, bf16).  In LDS a slab's X^T is ordered
+// [p-block][t][r], so the 16 lanes of a fragment read 256 consecutive bytes.
+__device__ __forceinline__ int rowperm(int r) { return ((r & 3) << 2) | (r >> 2); }
 
-// grp_ptr[j] = number of work items of the atoms before j; grp_atom[w] = atom of work item w.  One workgroup.
+// Work items (atom, group of GE out-edges), numbered atom-major: item[w] = {first padded row of the atom, its number
+// of in-edge rows, out-list position of the group's first edge, edges in the group}; n_items[0] = their number.
+// One workgroup (a scan over the atoms).
 __global__ void __launch_bounds__(1024)
-fused_groups_kernel(const int32_t* __restrict__ out_ptr, int n_atoms, int32_t* __restrict__ grp_ptr, int32_t* __restrict__ grp_atom) {
+fused_items_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, int n_atoms,
+                   int32_t* __restrict__ n_items, int32_t* __restrict__ item) {
   __shared__ int32_t wave_tot[16];
   __shared__ int32_t carry;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -50,7 +59,8 @@ fused_groups_kernel(const int32_t* __restrict__ out_ptr, int n_atoms, int32_t* _
   __syncthreads();
   for (int base = 0; base < n_atoms; base += 1024) {
     const int j = base + tid;
-    const int v = j < n_atoms ? (out_ptr[j + 1] - out_ptr[j] + GE - 1) / GE : 0;
+    const int o0 = j < n_atoms ? out_ptr[j] : 0, dout = j < n_atoms ? out_ptr[j + 1] - o0 : 0;
+    const int v = (dout + GE - 1) / GE;
     int incl = v;
     for (int o = 1; o < 64; o <<= 1) {
       const int u = __shfl_up(incl, o, 64);
@@ -61,41 +71,54 @@ fused_groups_kernel(const int32_t* __restrict__ out_ptr, int n_atoms, int32_t* _
     int before = carry;
     for (int k = 0; k < w; ++k) before += wave_tot[k];
     if (j < n_atoms) {
-      grp_ptr[j] = before + incl - v;
-      for (int k = 0; k < v; ++k) grp_atom[before + incl - v + k] = j;
+      const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
+      const int first = before + incl - v;
+      for (int k = 0; k < v; ++k) {
+        int32_t* it = item + 4 * (int64_t)(first + k);
+        it[0] = (int32_t)padded_base(r0, j);
+        it[1] = d;
+        it[2] = o0 + GE * k;
+        it[3] = dout - GE * k < GE ? dout - GE * k : GE;
+      }
     }
     __syncthreads();
     if (tid == 1023) carry = before + incl;
     __syncthreads();
   }
-  if (tid == 0) grp_ptr[n_atoms] = carry;
+  if (tid == 0) n_items[0] = carry;
 }
 
 // Pre-pass, one workgroup per (atom j, 64 of its padded rows): X^T in bf16 as [p-block of 8 rows][f][8], the
 // coefficients of the powers of cos alpha as [row][half][c][4] (rows past the atom's last one and columns past C are
-// zero, so padded rows contribute nothing), and, from the workgroups of the first 64 rows, the position `gap` of the
-// row each out-edge's segment leaves out (its length if none).
+// zero, so padded rows contribute nothing), and, from the workgroups of the first 64 rows, for every out-edge of the
+// atom (at its out-list position) {edge id, start of its segment, position of the row the segment leaves out
+// (the number of rows if none)}.
 template <int SM>
 __global__ void __launch_bounds__(256)
 fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
                   const int32_t* __restrict__ seg_ptr_ji, const int32_t* __restrict__ idx_kj, const float* __restrict__ x,
                   const float* __restrict__ Radt, int64_t E, int S, int C, int F, __bf16* __restrict__ xb,
-                  float* __restrict__ coef, int32_t* __restrict__ gap) {
+                  float* __restrict__ coef, int32_t* __restrict__ edge_info) {
   const int j = blockIdx.x;
   const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
-  const int p0 = SLAB * (int)blockIdx.y;
+  const int p0 = ROWPAD * (int)blockIdx.y;
   if (blockIdx.y == 0) {
     const int o0 = out_ptr[j], dout = out_ptr[j + 1] - o0;
     for (int t = threadIdx.x; t < dout; t += 256) {
       const int e = out_list[o0 + t];
       const int seg = seg_ptr_ji[e], cnt = seg_ptr_ji[e + 1] - seg;
-      gap[e] = first_mismatch(idx_kj + seg, cnt, [=](int slot) { return r0 + slot; });
+      const int gap = first_mismatch(idx_kj + seg, cnt, [=](int slot) { return r0 + slot; });
+      int32_t* dst = edge_info + 4 * (int64_t)(o0 + t);
+      dst[0] = e;
+      dst[1] = seg;
+      dst[2] = gap;                   // = cnt = the number of rows when no row is left out
+      dst[3] = cnt;
     }
   }
-  if (p0 >= ((d + SLAB - 1) & ~(SLAB - 1))) return;
+  if (p0 >= ((d + ROWPAD - 1) & ~(ROWPAD - 1))) return;
   const int64_t base = padded_base(r0, j) + p0;
   // X^T: item (p-block pb, feature f); consecutive threads take consecutive f of the same rows
-  for (int it = threadIdx.x; it < (SLAB / 8) * F; it += 256) {
+  for (int it = threadIdx.x; it < (ROWPAD / 8) * F; it += 256) {
     const int pb = it / F, f = it % F;
     bf16x8 v;
 #pragma unroll
@@ -107,8 +130,8 @@ fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
     *reinterpret_cast<bf16x8*>(xb + ((base / 8 + pb) * F + f) * 8) = v;
   }
   // coefficients: item (row p, column c); consecutive threads take consecutive rows of one (l, c) line of Radt
-  for (int it = threadIdx.x; it < SLAB * CP; it += 256) {
-    const int pl = it % SLAB, c = it / SLAB, p = p0 + pl;
+  for (int it = threadIdx.x; it < ROWPAD * CP; it += 256) {
+    const int pl = it % ROWPAD, c = it / ROWPAD, p = p0 + pl;
     const bool ok = p < d && c < C;
     float rl[SM];
 #pragma unroll
@@ -128,173 +151,178 @@ fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
   }
 }
 
-__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); }   // vmcnt(0) only
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits [3:0] and [15:14], expcnt [6:4] = 7 and lgkmcnt [11:8] = 15: no wait)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_vm0() { wait_vmcnt<0>(); }
+constexpr int STAGES = 3;       // LDS ring: the loads of two slabs are under way while a third is worked on
 
+// Two workgroups of 4 wavefronts share a compute unit (the registers allow 8 wavefronts): they work on different
+// items and drift apart, so one's staging, stores and prologue run beside the other's arithmetic.
 template <int NT, int SM>   // F = 16 NT (NT = 2, 4, 8); SM = number of polynomial coefficients kept (>= num_spherical)
-__global__ void __launch_bounds__(FT, 1)
-tripG_fused_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
-                   const int32_t* __restrict__ seg_ptr_ji, const float* __restrict__ cos_alpha, const __bf16* __restrict__ xb,
-                   const float* __restrict__ coef, const int32_t* __restrict__ gap_of, const int32_t* __restrict__ grp_ptr,
-                   const int32_t* __restrict__ grp_atom, int n_atoms, int C, int out_half, float* __restrict__ A) {
+__global__ void __launch_bounds__(FT, 2)
+tripG_fused_kernel(const float* __restrict__ cos_alpha, int64_t T, const __bf16* __restrict__ xb, const float* __restrict__ coef,
+                   const int32_t* __restrict__ edge_info, const int32_t* __restrict__ n_items, const int32_t* __restrict__ item,
+                   int C, int out_half, float* __restrict__ A) {
   constexpr int F = 16 * NT;
   constexpr int XT_B = SLAB / 8 * F * 16, CF_B = SLAB * COEF_ROW * 4, CS_B = GE * SLAB * 4, BUF_B = XT_B + CF_B + CS_B;
-  constexpr int XT_LOADS = XT_B / 1024, CF_LOADS = CF_B / 1024;
+  constexpr int XT_LOADS = XT_B / 1024, CF_LOADS = CF_B / 1024, CS_LOADS = CS_B / 256;
+  static_assert(CF_LOADS % 4 == 0 && CS_LOADS % 4 == 0, "the loads of a slab are dealt evenly to the 4 wavefronts");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_e[GE], s_seg[GE], s_gap[GE];
 
-  // work item: (atom, group of GE out-edges), numbered atom-major; each XCD takes a contiguous range
-  const int total = grp_ptr[n_atoms];
+  // work items are numbered atom-major; each XCD (workgroup ids are dealt round-robin to the 8 XCDs) takes a contiguous
+  // range of them, so the groups of one atom, which stage the same rows, run side by side on one L2
+  const int total = n_items[0];
   const int q8 = total >> 3, r8 = total & 7, xcd = (int)blockIdx.x & 7, ith = (int)blockIdx.x >> 3;
   if (ith >= q8 + (xcd < r8 ? 1 : 0)) return;
   const int w = xcd * q8 + (xcd < r8 ? xcd : r8) + ith;
-  const int j = grp_atom[w];
-  const int part = w - grp_ptr[j];
-  const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
-  const int o0 = out_ptr[j] + GE * part;
-  const int n_e = out_ptr[j + 1] - o0 < GE ? out_ptr[j + 1] - o0 : GE;
-  const int64_t base = padded_base(r0, j);
+  const int4 it = *reinterpret_cast<const int4*>(item + 4 * (int64_t)w);
+  const int64_t base = it.x;
+  const int d = it.y, o0 = it.z, n_e = it.w;
   const int n_slab = (d + SLAB - 1) / SLAB;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kq = lane >> 4, c = lane & 15;
 
-  auto stage_async = [&](int slab, int buf) __attribute__((always_inline)) {
+  // per-lane parts of the source offsets (the same for every slab and load); the rest is uniform
+  // X^T: a load covers 4 consecutive (p-block, tile) pairs, 16 rows each: pair 4 ld + lane / 16
+  const int xt_lane = ((kq / NT) * F + NT * rowperm(c) + kq % NT) * 8;   // bf16 elements
+  const int cf_lane = (lane >> 4) * COEF_ROW + (lane & 15) * 4;          // floats: row lane/16 of the load's 4 rows, column lane%16
+  auto stage_tables = [&](int slab, int buf) __attribute__((always_inline)) {
     unsigned char* dst = smem + buf * BUF_B;
     const int64_t row0 = base + (int64_t)SLAB * slab;
 #pragma unroll
-    for (int L = 0; L < (XT_LOADS + 7) / 8; ++L) {
-      const int ld = wv + 8 * L;   // uniform
-      if (ld < XT_LOADS) {
-        const int piece = ld * 64 + lane, pb = piece / F, f = swz(piece % F);
-        const __bf16* src = xb + ((row0 / 8 + pb) * F + f) * 8;
-        __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(dst + ld * 1024), 16, 0, 0);
-      }
+    for (int L = 0; L < (XT_LOADS + 3) / 4; ++L) {
+      // uniform; a wavefront without a load of its own repeats the last one, so that every wavefront issues the same
+      // number of loads per slab and can wait for "all but the newest slab's"
+      const int ld = wv + 4 * L < XT_LOADS ? wv + 4 * L : XT_LOADS - 1;
+      const __bf16* src = xb + ((row0 / 8 + (4 * ld) / NT) * F + (4 * ld) % NT) * 8 + xt_lane;
+      __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(dst + ld * 1024), 16, 0, 0);
     }
 #pragma unroll
-    for (int L = 0; L < CF_LOADS / 8; ++L) {
-      const int ld = wv + 8 * L;
-      const int piece = ld * 64 + lane, h = piece >> 10, p = (piece & 1023) >> 4, cc = piece & 15;
-      const float* src = coef + (row0 + p) * COEF_ROW + h * 64 + cc * 4;
+    for (int L = 0; L < CF_LOADS / 4; ++L) {
+      const int ld = wv + 4 * L;   // pieces 64 ld ..: half ld / 8, rows 4 (ld % 8) .. + 3, columns 0..15
+      const float* src = coef + (row0 + 4 * (ld & 7)) * COEF_ROW + (ld >> 3) * 64 + cf_lane;
       __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(dst + XT_B + ld * 1024), 16, 0, 0);
     }
   };
-  // cosines of the group's edges for one slab: thread (edge tid / 16, rows 4 (tid % 16) .. + 3); the row the segment
-  // leaves out is marked 2, rows past the atom's last one give 0 (their coefficients are zero)
-  const int c_el = tid >> 4, c_p = 4 * (tid & 15);
-  auto load_cos = [&](int slab, float (&v)[4]) __attribute__((always_inline)) {
-    const int seg = s_seg[c_el], gap = s_gap[c_el];
+
+  constexpr int PW = (XT_LOADS + 3) / 4 + CF_LOADS / 4 + CS_LOADS / 4;   // loads per wavefront and slab
+  if (n_slab > 0) stage_tables(0, 0);
+  if (tid < GE) {
+    const int4 ei = *reinterpret_cast<const int4*>(edge_info + 4 * (int64_t)(o0 + (tid < n_e ? tid : 0)));
+    s_e[tid] = tid < n_e ? ei.x : -1;
+    s_seg[tid] = ei.y;
+    s_gap[tid] = tid < n_e ? ei.z : -1;
+  }
+  __syncthreads();
+  // Cosines: 4-byte global->LDS loads, a wavefront's load covers 2 edges x 32 rows.  Row P of the atom is slot P, or
+  // P - 1 behind the row the segment leaves out, of the edge's segment; the left-out row itself and rows past the
+  // atom's last one fetch some valid cosine that is never used (the former is zeroed below, the latter have zero
+  // coefficients).
+  int cs_seg[CS_LOADS / 4], cs_gap[CS_LOADS / 4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int P = SLAB * slab + c_p + i;
-      const bool ok = P < d && P != gap && c_el < n_e;
-      const float cv = cos_alpha[ok ? seg + P - (P > gap ? 1 : 0) : 0];   // index 0 exists: not launched for T = 0
-      v[i] = ok ? cv : (P == gap ? 2.f : 0.f);
+  for (int L = 0; L < CS_LOADS / 4; ++L) {
+    const int el = 2 * (wv + 4 * L) + (lane >> 5);
+    cs_seg[L] = s_seg[el];
+    cs_gap[L] = s_gap[el];
+  }
+  auto stage_cos = [&](int slab, int buf) __attribute__((always_inline)) {
+    unsigned char* dst = smem + buf * BUF_B + XT_B + CF_B;
+#pragma unroll
+    for (int L = 0; L < CS_LOADS / 4; ++L) {
+      const int ld = wv + 4 * L;
+      const int P = SLAB * slab + (lane & 31);
+      int64_t idx = (int64_t)cs_seg[L] + P - (P > cs_gap[L] ? 1 : 0);
+      idx = idx < 0 ? 0 : (idx < T ? idx : T - 1);   // edges past the group's last one, the end of the array
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(cos_alpha + idx), (lds_void_ptr)(dst + ld * 256), 4, 0, 0);
     }
   };
-  auto write_cos = [&](int buf, const float (&v)[4]) __attribute__((always_inline)) {
-    *reinterpret_cast<f32x4*>(smem + buf * BUF_B + XT_B + CF_B + (c_el * SLAB + c_p) * 4) = f32x4{v[0], v[1], v[2], v[3]};
-  };
-
-  if (n_slab > 0) stage_async(0, 0);
-  if (tid < GE) {
-    const bool ok = tid < n_e;
-    const int e = out_list[o0 + (ok ? tid : 0)];
-    s_e[tid] = ok ? e : -1;
-    s_seg[tid] = seg_ptr_ji[e];
-    s_gap[tid] = ok ? gap_of[e] : -1;
+  if (n_slab > 0) stage_cos(0, 0);
+  if (n_slab > 1) {
+    stage_tables(1, 1);
+    stage_cos(1, 1);
   }
-  __syncthreads();
-  float cosr[4];
-  if (n_slab > 0) {
-    load_cos(0, cosr);
-    wait_vm0();
-    write_cos(0, cosr);
-  }
-  __syncthreads();
 
   f32x4 acc[4][NT];
 #pragma unroll
   for (int e4 = 0; e4 < 4; ++e4)
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[e4][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
   int gap4[4];
 #pragma unroll
   for (int e4 = 0; e4 < 4; ++e4) gap4[e4] = __builtin_amdgcn_readfirstlane(s_gap[4 * wv + e4]);
+  if (n_slab > 1) wait_vmcnt<PW>();   // slab 0 has landed (this wavefront's part; the barrier covers the others')
+  else wait_vm0();
+  __syncthreads();
 
+  int b = 0;   // ring of STAGES buffers: slab s in buffer s % STAGES, slabs s + 1 and s + 2 on their way
   for (int s = 0; s < n_slab; ++s) {
-    const int b = s & 1;
-    const bool more = s + 1 < n_slab;
+    const int b2 = b >= 1 ? b - 1 : STAGES - 1;   // (s + 2) % STAGES
+    const bool more = s + 2 < n_slab;
     if (more) {
-      stage_async(s + 1, b ^ 1);
-      load_cos(s + 1, cosr);
+      stage_tables(s + 2, b2);
+      stage_cos(s + 2, b2);
     }
     const unsigned char* buf = smem + b * BUF_B;
     const float* coefS = reinterpret_cast<const float*>(buf + XT_B);
     const float* cosS = reinterpret_cast<const float*>(buf + XT_B + CF_B);
+    const int P0 = SLAB * s;
+    float cf[8][8];
 #pragma unroll
-    for (int ks = 0; ks < SLAB / 32; ++ks) {
-      const int P0 = SLAB * s + 32 * ks;
-      if (P0 < d) {
-        float cf[8][8];
+    for (int i = 0; i < 8; ++i) {
+      const int p = 8 * kq + i;
+      const f32x4 lo = *reinterpret_cast<const f32x4*>(coefS + (p * 16 + c) * 4);
+      const f32x4 hi = *reinterpret_cast<const f32x4*>(coefS + SLAB * 64 + (p * 16 + c) * 4);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int p = 32 * ks + 8 * kq + i;
-          const f32x4 lo = *reinterpret_cast<const f32x4*>(coefS + (p * 16 + c) * 4);
-          const f32x4 hi = *reinterpret_cast<const f32x4*>(coefS + 4096 + (p * 16 + c) * 4);
+      for (int k = 0; k < 4; ++k) cf[i][k] = lo[k], cf[i][4 + k] = hi[k];
+    }
+    bf16x8 yb[4];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) cf[i][k] = lo[k], cf[i][4 + k] = hi[k];
-        }
-        bf16x8 yb[4];
+    for (int e4 = 0; e4 < 4; ++e4) {
+      const float* cp = cosS + (4 * wv + e4) * SLAB + 8 * kq;
+      const f32x4 c0 = *reinterpret_cast<const f32x4*>(cp), c1 = *reinterpret_cast<const f32x4*>(cp + 4);
+      const float xv[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+      float y[8];
 #pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const float* cp = cosS + (4 * wv + e4) * SLAB + 32 * ks + 8 * kq;
-          const f32x4 c0 = *reinterpret_cast<const f32x4*>(cp), c1 = *reinterpret_cast<const f32x4*>(cp + 4);
-          float xv[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
-          const bool masked = gap4[e4] >= P0 && gap4[e4] < P0 + 32;   // uniform: this step holds the row the segment leaves out
-          if (masked) {
+      for (int i = 0; i < 8; ++i) {
+        float v = cf[i][SM - 1];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              const bool ok = xv[i] <= 1.5f;
-              const float xx = ok ? xv[i] : 0.f;
-              float y = cf[i][SM - 1];
-#pragma unroll
-              for (int k = SM - 2; k >= 0; --k) y = y * xx + cf[i][k];
-              yb[e4][i] = (__bf16)(ok ? y : 0.f);
-            }
-          } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              float y = cf[i][SM - 1];
-#pragma unroll
-              for (int k = SM - 2; k >= 0; --k) y = y * xv[i] + cf[i][k];
-              yb[e4][i] = (__bf16)y;
-            }
-          }
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const bf16x8 xa = *reinterpret_cast<const bf16x8*>(buf + (((4 * ks + kq) * F + swz(NT * c + t)) << 4));
-#pragma unroll
-          for (int e4 = 0; e4 < 4; ++e4)
-            acc[e4][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, yb[e4], acc[e4][t], 0, 0, 0);
-        }
+        for (int k = SM - 2; k >= 0; --k) v = v * xv[i] + cf[i][k];
+        y[i] = v;
       }
+      if (gap4[e4] >= P0 && gap4[e4] < P0 + SLAB) {   // uniform: this slab holds the row the segment leaves out (k = i)
+        const int gl = gap4[e4] - P0 - 8 * kq;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = gl == i ? 0.f : y[i];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) yb[e4][i] = (__bf16)y[i];
     }
-    if (more) {
-      wait_vm0();
-      write_cos(b ^ 1, cosr);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const bf16x8 xa = *reinterpret_cast<const bf16x8*>(buf + ((kq * F + t * 16 + c) << 4));
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4)
+        acc[e4][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, yb[e4], acc[e4][t], 0, 0, 0);
     }
+    if (more) wait_vmcnt<PW>();   // slab s + 1 has landed, slab s + 2 may still be under way
+    else wait_vm0();
     __syncthreads();
+    b = b == STAGES - 1 ? 0 : b + 1;
   }
 
-  // accumulator register i of tile t in lane (g = kq, c): feature NT (4 g + i) + t, i.e. 4 NT consecutive features
+  // accumulator register i of tile t in lane (g = kq, c): feature NT (4 i + g) + t
 #pragma unroll
   for (int e4 = 0; e4 < 4; ++e4) {
     const int el = 4 * wv + e4;
     if (el >= n_e || c >= C) continue;
-    const int64_t at = ((int64_t)s_e[el] * C + c) * F + 4 * NT * kq;
+    const int64_t at = ((int64_t)s_e[el] * C + c) * F + NT * kq;
     if (out_half) {
       __bf16* dst = reinterpret_cast<__bf16*>(A) + at;
 #pragma unroll
@@ -303,14 +331,14 @@ tripG_fused_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restric
           bf16x8 v;
 #pragma unroll
           for (int t = 0; t < 8; ++t) v[t] = (__bf16)acc[e4][t][i];
-          *reinterpret_cast<bf16x8*>(dst + 8 * i) = v;
+          *reinterpret_cast<bf16x8*>(dst + 32 * i) = v;
         } else {
 #pragma unroll
           for (int t = 0; t < NT; t += 2) {
             bf16x2 v;
             v[0] = (__bf16)acc[e4][t][i];
             v[1] = (__bf16)acc[e4][t + 1][i];
-            *reinterpret_cast<bf16x2*>(dst + NT * i + t) = v;
+            *reinterpret_cast<bf16x2*>(dst + 4 * NT * i + t) = v;
           }
         }
       }
@@ -321,7 +349,7 @@ tripG_fused_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restric
 #pragma unroll
         for (int t = 0; t < NT; t += 2) {
           typedef float f32x2 __attribute__((ext_vector_type(2)));
-          *reinterpret_cast<f32x2*>(dst + NT * i + t) = f32x2{acc[e4][t][i], acc[e4][t + 1][i]};
+          *reinterpret_cast<f32x2*>(dst + 4 * NT * i + t) = f32x2{acc[e4][t][i], acc[e4][t + 1][i]};
         }
     }
   }
@@ -330,16 +358,16 @@ tripG_fused_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restric
 struct fused_ws {
   __bf16* xb;
   float* coef;
-  int32_t *gap, *grp_ptr, *grp_atom;
+  int32_t *edge_info, *n_items, *item;
 };
 size_t carve_fused(void* p, int64_t N, int64_t E, int F, fused_ws* w) {
   gp_carver c(p);
   const int64_t rows = padded_rows(E, N);
   w->xb = c.take<__bf16>((size_t)rows * F);
   w->coef = c.take<float>((size_t)rows * COEF_ROW);
-  w->gap = c.take<int32_t>((size_t)E);
-  w->grp_ptr = c.take<int32_t>((size_t)N + 1);
-  w->grp_atom = c.take<int32_t>((size_t)(E / GE + N + 1));
+  w->edge_info = c.take<int32_t>(4 * (size_t)E);
+  w->n_items = c.take<int32_t>(4);
+  w->item = c.take<int32_t>(4 * (size_t)(E / GE + N + 1));
   return c.off;
 }
 
@@ -352,7 +380,7 @@ size_t gp_tripG_fused_scratch(int64_t N, int64_t E, int F) {
 
 bool gp_tripG_fused_usable(const gp_graph* g, int F, int S, int C) {
   if (!g || !g->row_ptr || !g->out_ptr || !g->out_list || g->n_atoms <= 0 || g->n_triplets <= 0) return false;
-  if (g->n_atoms > INT32_MAX / 64 || g->n_edges / GE + g->n_atoms > INT32_MAX / 2) return false;
+  if (g->n_edges + (int64_t)PADJ * g->n_atoms + ROWPAD + 8 > INT32_MAX || g->n_edges / GE + g->n_atoms > INT32_MAX / 8) return false;
   if (g->max_in_degree <= 0 || g->max_out_degree <= 0) return false;
   return (F == 32 || F == 64 || F == 128) && C >= 1 && C <= CP && S >= 1 && S <= ST;
 }
@@ -369,14 +397,14 @@ int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
   const double Td = (double)T, Ed = (double)E;
   {
     gp_prof_scope prof(ctx, "tripG_pack", Ed * 2.0 * S * 8 * CP, Ed * (4.0 * F + 4.0 * S * C + 2.0 * F + 4.0 * COEF_ROW + 8.0));
-    fused_groups_kernel<<<1, 1024, 0, st>>>(g->out_ptr, (int)N, w.grp_ptr, w.grp_atom);
-    const dim3 grid((unsigned)N, (unsigned)((g->max_in_degree + SLAB - 1) / SLAB));
+    fused_items_kernel<<<1, 1024, 0, st>>>(g->row_ptr, g->out_ptr, (int)N, w.n_items, w.item);
+    const dim3 grid((unsigned)N, (unsigned)((g->max_in_degree + ROWPAD - 1) / ROWPAD));
     if (S <= 7)
       fused_pack_kernel<7><<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj, x, Radt, E, S, C, F,
-                                                 w.xb, w.coef, w.gap);
+                                                 w.xb, w.coef, w.edge_info);
     else
       fused_pack_kernel<8><<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj, x, Radt, E, S, C, F,
-                                                 w.xb, w.coef, w.gap);
+                                                 w.xb, w.coef, w.edge_info);
     GP_LAUNCH_CHECK(ctx, "fused_pack_kernel");
   }
   {
@@ -384,15 +412,16 @@ int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
     const unsigned grid = (unsigned)(E / GE + N);   // an upper bound of the number of work items; the rest exit at once
 #define GP_FUSED_LAUNCH(NT, SM)                                                                                          \
   do {                                                                                                                   \
-    constexpr size_t lds = 2 * ((size_t)SLAB / 8 * 16 * NT * 16 + (size_t)SLAB * COEF_ROW * 4 + (size_t)GE * SLAB * 4);  \
+    constexpr size_t lds = STAGES * ((size_t)SLAB / 8 * 16 * NT * 16 + (size_t)SLAB * COEF_ROW * 4 + (size_t)GE * SLAB * 4); \
+    static_assert(2 * (lds + 256) <= 160 * 1024, "two workgroups per compute unit");                                     \
     static bool raised = false;                                                                                          \
-    if (!raised) {                                                                                                       \
+    if (!raised && lds > 64 * 1024) {                                                                                    \
       GP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&tripG_fused_kernel<NT, SM>),                        \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                            \
       raised = true;                                                                                                     \
     }                                                                                                                    \
-    tripG_fused_kernel<NT, SM><<<grid, FT, lds, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, cos_alpha,     \
-                                                      w.xb, w.coef, w.gap, w.grp_ptr, w.grp_atom, (int)N, C, out_half, A); \
+    tripG_fused_kernel<NT, SM><<<grid, FT, lds, st>>>(cos_alpha, T, w.xb, w.coef, w.edge_info, w.n_items, w.item, C,     \
+                                                      out_half, A);                                                      \
   } while (0)
     if (S <= 7) {
       if (F == 128) GP_FUSED_LAUNCH(8, 7);
