@@ -129,14 +129,24 @@ fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
     }
     *reinterpret_cast<bf16x8*>(xb + ((base / 8 + pb) * F + f) * 8) = v;
   }
-  // coefficients: item (row p, column c); consecutive threads take consecutive rows of one (l, c) line of Radt
+  // coefficients.  Radt is read with consecutive threads on consecutive rows of one (l, c) line and parked in LDS;
+  // the table is then written with consecutive threads on consecutive c of one row, i.e. in whole 256-byte runs
+  // (written straight from the first order, every 16-byte store went to a line of its own: 0.24 -> 0.1 ms at 3e5 edges).
+  __shared__ float s_r[SM * CP * (ROWPAD + 1)];
   for (int it = threadIdx.x; it < ROWPAD * CP; it += 256) {
     const int pl = it % ROWPAD, c = it / ROWPAD, p = p0 + pl;
     const bool ok = p < d && c < C;
-    float rl[SM];
 #pragma unroll
     for (int l = 0; l < SM; ++l)
-      rl[l] = Radt[(int64_t)((l < S ? l : 0) * C + (c < C ? c : 0)) * E + r0 + (p < d ? p : 0)] * ((ok && l < S) ? Y_NORM_M[l] : 0.f);
+      s_r[(l * CP + c) * (ROWPAD + 1) + pl] =
+          Radt[(int64_t)((l < S ? l : 0) * C + (c < C ? c : 0)) * E + r0 + (p < d ? p : 0)] * ((ok && l < S) ? Y_NORM_M[l] : 0.f);
+  }
+  __syncthreads();
+  for (int it = threadIdx.x; it < ROWPAD * CP; it += 256) {
+    const int c = it % CP, pl = it / CP;
+    float rl[SM];
+#pragma unroll
+    for (int l = 0; l < SM; ++l) rl[l] = s_r[(l * CP + c) * (ROWPAD + 1) + pl];
     float m[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
