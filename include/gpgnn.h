@@ -64,6 +64,12 @@ int gp_set_side_stream(gp_ctx* ctx, int on);
  * registers (kept for comparison).  GP_TRIPLET_MFMA=0/1/2 in the environment sets the mode at gp_create. */
 int gp_set_triplet_mfma(gp_ctx* ctx, int mode);
 
+/* Errors that only a kernel can detect are deferred: a block call given gp_graph.max_in_degree / max_out_degree
+ * below the true maxima skips the atoms above them (it never reads out of bounds) and leaves a mark that makes
+ * the NEXT block call on the context, or this call, return GP_BAD_ARG with a message.  gp_deferred_status
+ * synchronises the context's stream first, so it also reports what the calls still in flight find. */
+int gp_deferred_status(gp_ctx* ctx);
+
 /* Measurement aid (not a step of the method): while enabled, every kernel launch the library
  * issues on this context is bracketed by two HIP events on the context's stream.
  * gp_profile_get(i) synchronises on launch i and returns its kernel name (static string),
@@ -199,9 +205,19 @@ typedef struct {
 
 /* ------------------------------------------------------------------------------------------
  * Basis functions (Sec. 3.3 names a radial basis of the edge length and a spherical basis of
- * (d_kj, alpha_(kj,ji)); formulas are the standard ones, see the oracle's header).
- *   rbf[E, R]        D: u(d/c) sqrt(2/c) sin(n pi d/c)/d ;  G: u(d/c) exp(-((d/c-mu_n)/Delta)^2/2)
- *   rad[E, S*R]      D only (else NULL): u(d/c) N_ln j_l(z_ln d/c), flat index l*R + (n-1)
+ * (d_kj, alpha_(kj,ji)); the paper prints no formulas, these are the ones this library computes).
+ * With c = cutoff, x = d/c, p = envelope_p, R = num_radial, S = num_spherical:
+ *   envelope   u(x) = 1 - (p+1)(p+2)/2 x^p + p(p+2) x^(p+1) - p(p+1)/2 x^(p+2)   (u(1) = u'(1) = u''(1) = 0)
+ *   Bessel radial basis (variant D)    rbf_n(d) = u(x) sqrt(2/c) sin(n pi x) / d,          n = 1..R
+ *   Gaussian radial basis (variant G)  rbf_n(d) = u(x) exp(-((x - mu_n)/Delta)^2 / 2),     mu_n = n/(R-1), Delta = 1/(R-1), n = 0..R-1
+ *   spherical basis (variant D)        sbf_ln(d, alpha) = u(x) N_ln j_l(z_ln x) Y_l0(alpha), l = 0..S-1, n = 1..R,
+ *       j_l the spherical Bessel function of the first kind, z_ln its n-th positive zero,
+ *       N_ln = sqrt(2 / (c^3 j_(l+1)(z_ln)^2)), Y_l0(alpha) = sqrt((2l+1)/(4 pi)) P_l(cos alpha), P_l the Legendre
+ *       polynomial; evaluated in fp64 and rounded once
+ *   angular part (variant G)           Y_l0(alpha), l = 0..S-1
+ * Arrays:
+ *   rbf[E, R]        the radial basis of the variant selected by dims
+ *   rad[E, S*R]      D only (else NULL): the radial part u(x) N_ln j_l(z_ln x) of sbf, flat index l*R + (n-1)
  *   cos_alpha[T]     cos of the angle at j between bonds j-i and j-k = -unit[ji].unit[kj]
  *   cos_alpha_kj[T]  the same values in kj-major order (needs perm_kj; may be NULL with it)
  *   sbf[T, S*R]      optional materialised spherical basis rad[idx_kj[t]] * Y_l0(cos_alpha[t])
@@ -227,7 +243,8 @@ typedef struct {
    * gp_edges_fill / gp_triplets_fill produce: edges sorted by target atom, and idx_kj of the
    * segment of edge j->i equal to the in-edge rows of j in ascending order with at most the
    * row coming from atom i left out.  max_in_degree / max_out_degree must not be below the true
-   * maxima (atoms above them are skipped). */
+   * maxima: atoms above them are skipped (no access leaves its array) and the block call that notices leaves
+   * a deferred GP_BAD_ARG, see gp_deferred_status. */
   int64_t n_atoms;
   int32_t max_in_degree;       /* max over atoms of row_ptr[j+1] - row_ptr[j] */
   int32_t max_out_degree;      /* max over atoms of out_ptr[j+1] - out_ptr[j] */

@@ -6,6 +6,30 @@
 
 #include "common.h"
 
+namespace {
+__global__ void degree_check_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, int64_t n,
+                                    int max_in, int max_out, int* __restrict__ flag) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  if (row_ptr[j + 1] - row_ptr[j] > max_in || out_ptr[j + 1] - out_ptr[j] > max_out) *flag = 1;
+}
+}  // namespace
+
+int gp_check_degrees(gp_ctx* ctx, const gp_graph* g) {
+  if (!ctx->dflag_dev || !g || g->n_atoms <= 0 || !g->row_ptr || !g->out_ptr) return GP_OK;
+  degree_check_kernel<<<(unsigned)((g->n_atoms + 255) / 256), 256, 0, ctx->stream>>>(g->row_ptr, g->out_ptr, g->n_atoms,
+                                                                                   g->max_in_degree, g->max_out_degree, ctx->dflag_dev);
+  GP_LAUNCH_CHECK(ctx, "degree_check_kernel");
+  return GP_OK;
+}
+
+int gp_take_deferred(gp_ctx* ctx, const char* who) {
+  if (!ctx->dflag || !*(volatile int*)ctx->dflag) return GP_OK;
+  *(volatile int*)ctx->dflag = 0;
+  return gp_fail(ctx, GP_BAD_ARG, "%s: an earlier block call on this context was given gp_graph.max_in_degree / max_out_degree "
+                 "below the true maxima; the atoms above them were skipped and that call's results are incomplete", who);
+}
+
 int gp_static_scratch_init(int device);   // energy.hip: address of the allocation-free entry point's scratch array
 
 extern "C" {
@@ -27,6 +51,13 @@ int gp_create(gp_ctx** out, int device_id, void* hip_stream) {
   // per-device address of the static scratch (the device is current here); a failure is reported by the entry point
   // that needs it, not here
   (void)gp_static_scratch_init(device_id);
+  // one pinned, device-visible word for errors that only a kernel can detect
+  if (hipHostMalloc((void**)&c->dflag, sizeof(int), hipHostMallocMapped) == hipSuccess) {
+    *c->dflag = 0;
+    if (hipHostGetDevicePointer((void**)&c->dflag_dev, c->dflag, 0) != hipSuccess) c->dflag_dev = nullptr;
+  } else {
+    c->dflag = nullptr;
+  }
   const char* no_aux = getenv("GP_NO_AUX_STREAM");
   c->use_aux = !(no_aux && no_aux[0] == '1');
   const char* tm = getenv("GP_TRIPLET_MFMA");
@@ -44,6 +75,7 @@ void gp_destroy(gp_ctx* ctx) {
   for (auto e : ctx->event_pool) (void)hipEventDestroy(e);
   for (auto e : ctx->aux_event_pool) (void)hipEventDestroy(e);
   if (ctx->aux_stream) (void)hipStreamDestroy(ctx->aux_stream);
+  if (ctx->dflag) (void)hipHostFree(ctx->dflag);
   delete ctx;
 }
 
@@ -91,6 +123,13 @@ int gp_profile_get(gp_ctx* ctx, int64_t i, const char** name, float* ms, double*
   *flops = p.flops;
   *bytes = p.bytes;
   return GP_OK;
+}
+
+int gp_deferred_status(gp_ctx* ctx) {
+  if (!ctx) return GP_BAD_ARG;
+  GP_HIP(ctx, hipSetDevice(ctx->device));
+  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return gp_take_deferred(ctx, "gp_deferred_status");
 }
 
 const char* gp_last_error(const gp_ctx* ctx) { return ctx ? ctx->err : "null context"; }

@@ -8,7 +8,8 @@
 //   * before the main stream overwrites a buffer the side stream may still be reading,
 //     before_write(buffer) makes it wait for that reader;
 //   * join() makes the main stream wait for all side work; it is called before the entry point
-//     returns, so callers see ordinary single-stream semantics.
+//     returns (the destructor does the same on an early error return), so callers see ordinary
+//     single-stream semantics.
 #pragma once
 #include <initializer_list>
 
@@ -25,6 +26,9 @@ struct gp_aux {
 
   explicit gp_aux(gp_ctx* ctx) : c(ctx), main_s(ctx->stream), aux_s(ctx->use_aux ? ctx->aux_stream : nullptr) {}
   ~gp_aux() {
+    // an entry point that returns early (an error between on_aux and join) still leaves the main stream ordered
+    // behind the side work it started
+    if (last) (void)hipStreamWaitEvent(main_s, last, 0);
     for (hipEvent_t e : used) c->aux_event_pool.push_back(e);
   }
   bool active() const { return aux_s != nullptr; }

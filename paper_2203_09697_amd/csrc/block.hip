@@ -191,6 +191,7 @@ int gp_block_forward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, 
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, m_in && m_out && saved && scratch, "gp_block_forward_D: NULL pointer");
   GP_REQUIRE(ctx, basis->rbf && basis->rad && (graph->n_triplets == 0 || basis->cos_alpha), "gp_block_forward_D: basis arrays missing");
+  GP_TRY(gp_take_deferred(ctx, "gp_block_forward_D"));
   saved_D s;
   scratch_D sc;
   if (saved_bytes < carve_saved_D(saved, dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_D: saved buffer too small");
@@ -231,9 +232,12 @@ int gp_block_forward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, 
   GP_TRY(aux.on_aux([&] { return ji_rows(0, E); }, {}));
   GP_TRY(kj_rows(0, E));
   GP_TRY(aux.before_write(s.Q));   // the projected radial table, written on the side stream
-  if (ctx->trip_mfma != 0 && gp_tripD_mfma_usable(graph, F, S, B))
-    GP_TRY(gp_tripD_forward_mfma(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a,
-                                 bwd_mfma_D(ctx, dims, graph) ? nullptr : s.Bacc));
+  const bool fwd_mfma = ctx->trip_mfma != 0 && gp_tripD_mfma_usable(graph, F, S, B);
+  const bool keep_Bacc = !(fwd_mfma && bwd_mfma_D(ctx, dims, graph));
+  ctx->fwd_flags[saved] = keep_Bacc ? 1u : 0u;   // the backward call must agree on whether Bacc was written
+  if (fwd_mfma || bwd_mfma_D(ctx, dims, graph)) GP_TRY(gp_check_degrees(ctx, graph));
+  if (fwd_mfma)
+    GP_TRY(gp_tripD_forward_mfma(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a, keep_Bacc ? s.Bacc : nullptr));
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x_kj, s.Q, w->W_sbf2, F, S, B, s.a, s.Bacc));
   GP_TRY(aux.join());
@@ -367,6 +371,13 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
   }
   // triplet interaction
   const bool bwd_mfma = bwd_mfma_D(ctx, dims, graph);
+  {
+    // the matrix-core backward kernel does without Bacc; the per-edge one needs what the forward call stored
+    const auto it = ctx->fwd_flags.find(saved);
+    if (!bwd_mfma && it != ctx->fwd_flags.end() && it->second == 0u)
+      return gp_fail(ctx, GP_BAD_ARG, "gp_block_backward_D: the forward call of this `saved` buffer ran with the matrix-core triplet "
+                     "kernels and kept no accumulator; gp_set_triplet_mfma must not change between forward and backward");
+  }
   if (bwd_mfma)
     GP_TRY(gp_tripD_backward_mfma(ctx, graph, basis->cos_alpha_kj, s.x_kj, s.Q, w->W_sbf2, sc.dF1, s.z_dn, F, S, B,
                                   sc.dF2, sc.dQ, gw->W_sbf2, sc.part, sc.part_bytes));        // dz_dn, dQ, dW_sbf2

@@ -427,6 +427,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, m_in && m_out && saved && scratch, "gp_block_forward_G: NULL pointer");
   GP_REQUIRE(ctx, basis->rbf && (graph->n_triplets == 0 || basis->cos_alpha), "gp_block_forward_G: basis arrays missing");
+  GP_TRY(gp_take_deferred(ctx, "gp_block_forward_G"));
   saved_G s;
   scratch_G sc;
   if (saved_bytes < carve_saved_G(saved, dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_forward_G: saved buffer too small");
@@ -446,6 +447,8 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   GP_TRY(gp_gemm_nn(ctx, w->W_rbfS, w->W_rbfB, R, H, RB, e));                       // W_rbf = W_rbfS W_rbfB
   const bool hs = half_storage(dims);   // gate, z_ba, xg, z_skip, t_skip, z_up live in HBM as bf16
   const bool ah = a_half(ctx, dims, graph);
+  ctx->fwd_flags[saved] = ah ? 1u : 0u;   // element type of the accumulator A: the backward call must read it the same way
+  if (dims->dtype == GP_BF16_F32ACC && ctx->trip_mfma != 0) GP_TRY(gp_check_degrees(ctx, graph));
   e = gp_epilogue(); e.out = s.gate; e.bf16 = hs ? EPI_BF_OUT : 0u;
   GP_TRY(gp_gemm_nn(ctx, g, s.Wrbf, E, H, R, e));                                   // gate
   const float* m_op = m_in;   // the input messages as a GEMM operand
@@ -542,6 +545,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_REQUIRE(ctx, E > 0 && graph->n_triplets >= 0, "gp_block_backward_G: empty edge list");
   GP_REQUIRE(ctx, m_in && grad_m_out && grad_m_in && saved && scratch, "gp_block_backward_G: NULL pointer");
   GP_REQUIRE(ctx, basis->rbf && (graph->n_triplets == 0 || basis->cos_alpha_kj), "gp_block_backward_G: basis arrays missing");
+  GP_TRY(gp_take_deferred(ctx, "gp_block_backward_G"));
   saved_G s;
   scratch_G sc;
   if (saved_bytes < carve_saved_G(const_cast<void*>(saved), dims, E, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_block_backward_G: saved buffer too small");
@@ -610,6 +614,12 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   e = gp_epilogue(); e.out = grad_m_in;
   GP_TRY(gp_gemm_nt(ctx, d_skip, W_skip, E, H, H, e, hs, wh));                      // dm (skip path)
   const bool ah = a_half(ctx, dims, graph);
+  {
+    const auto it = ctx->fwd_flags.find(saved);
+    if (it != ctx->fwd_flags.end() && (it->second != 0u) != ah)
+      return gp_fail(ctx, GP_BAD_ARG, "gp_block_backward_G: the forward call of this `saved` buffer stored the triplet accumulator as %s; "
+                     "gp_set_triplet_mfma must not change between forward and backward", it->second ? "bf16" : "fp32");
+  }
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.A, sc.dz, E, C * F, O, gw->W_bil, nullptr, sc.part_aux, sc.part_bytes, ah, 0); }, {}));
   if (dims->radial_at_target) {
     // mirror image of the source-edge form: G[e',c,o] = sum_{t: kj(t)=e'} y'_t[c] dz[ji(t),o] with

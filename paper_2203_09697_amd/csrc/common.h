@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/gpgnn.h"
@@ -30,7 +31,21 @@ struct gp_ctx {
   std::vector<hipEvent_t> aux_event_pool;
   std::vector<gp_prof_entry> prof;
   std::vector<hipEvent_t> event_pool;
+  // Storage decisions of a block's forward call that its backward call must repeat (which buffers were written and
+  // in which element type), keyed by the `saved` buffer: the backward call compares instead of trusting the
+  // context's settings to be unchanged.
+  std::unordered_map<const void*, uint32_t> fwd_flags;
+  // Deferred errors of kernels (one int in pinned host memory that the device writes): set when a graph's
+  // max_in_degree / max_out_degree turn out to be below the true maxima; reported by the next block call or
+  // gp_deferred_status.
+  int* dflag = nullptr;       // host address
+  int* dflag_dev = nullptr;   // the same word as the device sees it
 };
+
+// Launches the check of gp_graph.max_in_degree / max_out_degree against the lists (sets the deferred-error word).
+int gp_check_degrees(gp_ctx* ctx, const gp_graph* g);
+// GP_BAD_ARG (and a message) if an earlier call on this context left a deferred error; clears it.
+int gp_take_deferred(gp_ctx* ctx, const char* who);
 
 // Brackets the launches issued during its lifetime with two HIP events on the context's
 // stream when profiling is on; otherwise does nothing.
