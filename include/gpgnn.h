@@ -423,7 +423,7 @@ int gp_forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* 
 /* ------------------------------------------------------------------------------------------
  * The core TripletUpdate + TripletAggr kernels on their own (Sec. 3.3: Hadamard product of the
  * gathered message with the projected basis, summed over k into edge j->i).
- *   Streaming form: s[T,F] is a materialised per-triplet basis projection (ji-major),
+ *   Streaming form (GP_TRIPLET_STREAM): s[T,F] is a materialised per-triplet basis projection (ji-major),
  *     a[e,f] = sum_{t in seg_ji(e)} x[idx_kj[t], f] * s[t, f].
  *   Backward: grad_x[e',f] = sum_{t: kj(t)=e'} grad_a[ji(t),f] * s[t,f]   (kj-major walk)
  *             grad_s[t,f]  = grad_a[ji(t),f] * x[kj(t),f].
@@ -433,6 +433,47 @@ int gp_triplet_aggregate_fwd(gp_ctx* ctx, const gp_graph* graph, int32_t width,
 int gp_triplet_aggregate_bwd(gp_ctx* ctx, const gp_graph* graph, const int32_t* perm_kj,
                              int32_t width, const float* x, const float* s, const float* grad_a,
                              float* grad_x, float* grad_s);
+
+/* The same two steps in the forms the interaction blocks run, which never materialise a per-triplet tensor: the
+ * basis projection of a triplet is recomputed from cos_alpha (4 bytes per triplet) and a per-edge table.
+ *   form GP_TRIPLET_PER_EDGE   one wavefront per target edge (forward) or source edge (backward), fp32 vector units
+ *   form GP_TRIPLET_PER_ATOM   the sums regrouped by centre atom j (all out-edges of j sum over the same in-edge rows)
+ *                              into dense products on the matrix cores; needs the lists by centre atom of gp_graph
+ *   form GP_TRIPLET_PER_ATOM_TWO_KERNELS   bilinear forward only: the earlier two-kernel form with a per-triplet
+ *                              buffer of the projection in bf16 (kept for comparison)
+ * Tables are stored transposed, one line per (l, b): Qt[(l*basis_emb + b)*E + e], Radt[(l*emb_cbf + c)*E + e].
+ * Y_l0 are the spherical harmonics of the basis comment above.  ws: gp_triplet_workspace(graph, width) bytes
+ * (may be NULL for the per-edge forms).  Errors: GP_BAD_ARG, GP_UNSUPPORTED_DIMS (widths a form does not
+ * implement, stated in the message), GP_BUFFER_TOO_SMALL.
+ *
+ * Hadamard form (Sec. 3.3), fp32:  p_t[b] = sum_l Y_l0(cos alpha_t) Q[kj(t), l, b];  s_t[f] = sum_b p_t[b] W_sbf2[b, f]
+ *   forward   a[e, f] = sum_{t in seg_ji(e)} x[kj(t), f] s_t[f];   Bacc[e, b, f] = sum_t p_t[b] x[kj(t), f]
+ *             (Bacc may be NULL in the per-atom form, which needs basis_emb = 8 and width 32, 64, 96 or 128)
+ *   backward  grad_x[e', f] = sum_{t: kj(t)=e'} grad_a[ji(t), f] s_t[f]
+ *             grad_Q[e', l, b] (stored [E, S, basis_emb]) = sum_{t: kj(t)=e'} Y_l0(t) sum_f W_sbf2[b, f] grad_a[ji(t), f] x[e', f]
+ *             grad_W_sbf2[b, f] = sum_e grad_a[e, f] Bacc[e, b, f]    (per-atom form only; NULL in the per-edge form)
+ * Bilinear form (Sec. 3.4):  y_t[c] = sum_l Y_l0(cos alpha_t) Rad[kj(t), l, c]
+ *   forward   A[e, c, f] = sum_{t in seg_ji(e)} y_t[c] x[kj(t), f]   (fp32 result; the per-atom forms round x and y to
+ *             bf16 on their way into the matrix cores and need emb_cbf <= 16, width 32, 64 or 128)
+ *   backward  H[e', l, o] = sum_{t: kj(t)=e'} Y_l0(cos alpha_t) dz[ji(t), o]   (dz[E, width]: gradient of the block's
+ *             bilinear result; everything else of the block's backward pass follows from H per edge)
+ *             grad_cos_kj[q] (+)= sum_l Y_l0'(cos alpha_q) sum_o dz[ji(q), o] U[kj(q), l, o]   (U[E, S, width]; kj-major) */
+enum { GP_TRIPLET_STREAM = 0, GP_TRIPLET_PER_EDGE = 1, GP_TRIPLET_PER_ATOM = 2, GP_TRIPLET_PER_ATOM_TWO_KERNELS = 3 };
+int gp_triplet_workspace(const gp_graph* graph, int32_t width, size_t* bytes /*host*/);
+int gp_triplet_hadamard_fwd(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t basis_emb,
+                            int32_t width, const float* cos_alpha, const float* x, const float* Qt, const float* W_sbf2,
+                            float* a, float* Bacc);
+int gp_triplet_hadamard_bwd(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t basis_emb,
+                            int32_t width, const float* cos_alpha_kj, const float* x, const float* Qt, const float* W_sbf2,
+                            const float* grad_a, float* grad_x, float* grad_Q, float* grad_W_sbf2, void* ws, size_t ws_bytes);
+int gp_triplet_bilinear_fwd(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t emb_cbf,
+                            int32_t width, const float* cos_alpha, const float* x, const float* Radt, float* A,
+                            void* ws, size_t ws_bytes);
+int gp_triplet_bilinear_bwd_H(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t width,
+                              const float* cos_alpha_kj, const float* dz, float* H);
+int gp_triplet_bilinear_grad_cos(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t width,
+                                 const float* cos_alpha_kj, const float* U, const float* dz, int32_t accumulate,
+                                 float* grad_cos_kj);
 
 /* Dense layer on its own: out = act(x @ W + b), fp32 MFMA.  act: 0 none, 1 SiLU.
  * x[rows,k], W[k,n], b[n] or NULL, out[rows,n]. */

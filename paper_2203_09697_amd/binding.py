@@ -10,6 +10,9 @@ __all__ = [
     "gp_measure_peaks", "gp_edges_by_source", "gp_edges_by_source_static", "gp_reverse_edges", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
     "gp_block_forward_D", "gp_block_backward_D", "gp_triplet_aggregate_fwd",
     "gp_triplet_aggregate_bwd", "gp_linear_forward", "build_graph", "weights_to_device",
+    "TRIPLET_STREAM", "TRIPLET_PER_EDGE", "TRIPLET_PER_ATOM", "TRIPLET_PER_ATOM_TWO_KERNELS", "gp_triplet_workspace",
+    "gp_triplet_hadamard_fwd", "gp_triplet_hadamard_bwd", "gp_triplet_bilinear_fwd", "gp_triplet_bilinear_bwd_H",
+    "gp_triplet_bilinear_grad_cos",
     "EXPORTED_SYMBOLS", "D_WEIGHT_ORDER",
 ]
 
@@ -32,6 +35,8 @@ EXPORTED_SYMBOLS = [
     "gp_output_workspace", "gp_output_forward", "gp_output_backward",
     "gp_edges_by_source_workspace", "gp_edges_by_source", "gp_edges_by_source_static", "gp_forces_workspace", "gp_forces_from_basis_grad",
     "gp_triplet_aggregate_fwd", "gp_triplet_aggregate_bwd", "gp_linear_forward", "gp_linear_forward_bf16",
+    "gp_triplet_workspace", "gp_triplet_hadamard_fwd", "gp_triplet_hadamard_bwd", "gp_triplet_bilinear_fwd",
+    "gp_triplet_bilinear_bwd_H", "gp_triplet_bilinear_grad_cos",
 ]
 
 
@@ -402,6 +407,72 @@ def gp_triplet_aggregate_bwd(ctx, trip, x, s, grad_a):
     ctx.check(lib.gp_triplet_aggregate_bwd(ctx._h, C.byref(g), _ptr(trip["perm_kj"]), C.c_int32(x.shape[1]), _ptr(x),
                                            _ptr(s), _ptr(grad_a), _ptr(gx), _ptr(gs)))
     return gx, gs
+
+
+TRIPLET_STREAM, TRIPLET_PER_EDGE, TRIPLET_PER_ATOM, TRIPLET_PER_ATOM_TWO_KERNELS = 0, 1, 2, 3
+
+
+def gp_triplet_workspace(ctx, trip, width):
+    """Scratch tensor for the per-centre-atom forms of the stand-alone triplet kernels."""
+    g = Graph(trip)
+    nb = C.c_size_t()
+    rc = load().gp_triplet_workspace(C.byref(g), C.c_int32(width), C.byref(nb))
+    if rc != 0:
+        raise GpError(rc, "gp_triplet_workspace")
+    return torch.empty(max(nb.value, 8), dtype=torch.uint8, device=ctx.device)
+
+
+def gp_triplet_hadamard_fwd(ctx, trip, form, S, cos_alpha, x, Qt, W2, want_Bacc=True):
+    """a [E,F], Bacc [E,B,F] (or None).  Qt [S*B, E], W2 [B, F]."""
+    g = Graph(trip)
+    B_, F = W2.shape
+    a = torch.empty_like(x)
+    Bacc = torch.empty((x.shape[0], B_, F), dtype=torch.float32, device=ctx.device) if want_Bacc else None
+    ctx.check(load().gp_triplet_hadamard_fwd(ctx._h, C.byref(g), C.c_int32(form), C.c_int32(S), C.c_int32(B_), C.c_int32(F),
+                                             _ptr(cos_alpha), _ptr(x), _ptr(Qt), _ptr(W2), _ptr(a), _ptr(Bacc)))
+    return a, Bacc
+
+
+def gp_triplet_hadamard_bwd(ctx, trip, form, S, cos_alpha_kj, x, Qt, W2, grad_a, ws=None):
+    """grad_x [E,F], grad_Q [E,S,B], grad_W2 [B,F] (per-atom form only, else None)."""
+    g = Graph(trip)
+    B_, F = W2.shape
+    gx = torch.empty_like(x)
+    gQ = torch.empty((x.shape[0], S, B_), dtype=torch.float32, device=ctx.device)
+    gW2 = torch.empty_like(W2) if form == TRIPLET_PER_ATOM else None
+    ctx.check(load().gp_triplet_hadamard_bwd(ctx._h, C.byref(g), C.c_int32(form), C.c_int32(S), C.c_int32(B_), C.c_int32(F),
+                                             _ptr(cos_alpha_kj), _ptr(x), _ptr(Qt), _ptr(W2), _ptr(grad_a), _ptr(gx), _ptr(gQ),
+                                             _ptr(gW2), _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0)))
+    return gx, gQ, gW2
+
+
+def gp_triplet_bilinear_fwd(ctx, trip, form, S, Cc, cos_alpha, x, Radt, ws=None):
+    """A [E, C, F] fp32.  Radt [S*C, E]."""
+    g = Graph(trip)
+    A = torch.empty((x.shape[0], Cc, x.shape[1]), dtype=torch.float32, device=ctx.device)
+    ctx.check(load().gp_triplet_bilinear_fwd(ctx._h, C.byref(g), C.c_int32(form), C.c_int32(S), C.c_int32(Cc), C.c_int32(x.shape[1]),
+                                             _ptr(cos_alpha), _ptr(x), _ptr(Radt), _ptr(A), _ptr(ws),
+                                             C.c_size_t(ws.numel() if ws is not None else 0)))
+    return A
+
+
+def gp_triplet_bilinear_bwd_H(ctx, trip, form, S, cos_alpha_kj, dz):
+    """H [E, S, O]."""
+    g = Graph(trip)
+    H = torch.empty((dz.shape[0], S, dz.shape[1]), dtype=torch.float32, device=ctx.device)
+    ctx.check(load().gp_triplet_bilinear_bwd_H(ctx._h, C.byref(g), C.c_int32(form), C.c_int32(S), C.c_int32(dz.shape[1]),
+                                               _ptr(cos_alpha_kj), _ptr(dz), _ptr(H)))
+    return H
+
+
+def gp_triplet_bilinear_grad_cos(ctx, trip, form, S, cos_alpha_kj, U, dz, grad_cos_kj=None):
+    """grad_cos_kj [T] (kj-major); added to the given tensor, else a new one is written."""
+    g = Graph(trip)
+    acc = grad_cos_kj is not None
+    out = grad_cos_kj if acc else torch.empty(trip["n_triplets"], dtype=torch.float32, device=ctx.device)
+    ctx.check(load().gp_triplet_bilinear_grad_cos(ctx._h, C.byref(g), C.c_int32(form), C.c_int32(S), C.c_int32(dz.shape[1]),
+                                                  _ptr(cos_alpha_kj), _ptr(U), _ptr(dz), C.c_int32(1 if acc else 0), _ptr(out)))
+    return out
 
 
 def gp_linear_forward(ctx, x, W, b=None, act=0, bf16=False):
