@@ -1,4 +1,5 @@
-"""The five benchmark workloads as plain data (shapes and generator parameters only)."""
+"""The five benchmark workloads, and one at the widest widths the paper trains, as plain data (shapes and generator
+parameters only)."""
 from dataclasses import dataclass, field, replace
 from typing import Tuple
 
@@ -70,6 +71,12 @@ CONFIGS = {
                        emb_cbf=16, emb_bil=64, num_radial=128, num_spherical=7, cutoff=12.0),
         system="box", system_args=(1000, 0.08, 0.9), max_neighbors=0, n_blocks=3,
         head_hidden=256),
+    # DimeNet++-XL widths (Sec. 4.1: hidden 2048, triplet width 256; the paper's 4 blocks) on the config-2 structures
+    "xl": Workload(
+        name="xl",
+        dims=BlockDims(variant="D", dtype="f32", emb=2048, int_emb=256, basis_emb=8,
+                       num_radial=6, num_spherical=7, cutoff=6.0),
+        system="slab", system_args=(16, 4, 4, 4, 16), max_neighbors=50, n_blocks=4),
 }
 
 

@@ -176,6 +176,16 @@ def test_block_D_matrix_core_widths(lib, ctx, int_emb, num_spherical):
     _block_parity(lib, ctx, w, 6, n_blocks=1, pos_gptr=pos_gptr)
 
 
+@pytest.mark.timeout(600)
+def test_block_D_xl_widths_small_structure(lib, ctx):
+    # the widest DimeNet++ the paper trains (Sec. 4.1: hidden width 2048, triplet width 256) on a structure small
+    # enough for the oracle; int_emb 256 is beyond the matrix-core triplet kernels (128) and runs the per-edge form
+    w = synth.get_workload("xl")
+    assert w.dims.emb == 2048 and w.dims.int_emb == 256
+    pos_gptr = synth.slab_adsorbate_positions(1, 3, 3, 3, 6, seed=11)
+    _block_parity(lib, ctx, w, 8, n_blocks=1, pos_gptr=pos_gptr)
+
+
 def test_block_D_odd_widths(lib, ctx):
     # widths that are not multiples of the tile sizes or of 4: exercises every ragged path
     w = synth.get_workload("cfg1", emb=36, int_emb=20, basis_emb=3, num_radial=5, num_spherical=4,
