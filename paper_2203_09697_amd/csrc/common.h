@@ -141,6 +141,25 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// Orders the distinct values tmp[0..n) ascending into out[0..n) by rank counting, one workgroup per list: the list is
+// parked in LDS (lists longer than SORT_LDS values are read from memory instead), every thread counts, for its
+// elements, the smaller ones.  All threads of the workgroup must call it.
+constexpr int SORT_LDS = 2048;
+__device__ __forceinline__ void sort_list_block(const int32_t* __restrict__ tmp, int n, int32_t* __restrict__ out, int32_t* lds) {
+  const bool staged = n <= SORT_LDS;
+  if (staged) {
+    for (int r = threadIdx.x; r < n; r += blockDim.x) lds[r] = tmp[r];
+    __syncthreads();
+  }
+  const int32_t* list = staged ? lds : tmp;
+  for (int r = threadIdx.x; r < n; r += blockDim.x) {
+    const int v = list[r];
+    int rank = 0;
+    for (int q = 0; q < n; ++q) rank += list[q] < v ? 1 : 0;
+    out[rank] = v;
+  }
+}
+
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 // d/dz [ z * sigmoid(z) ]
 __device__ __forceinline__ float dsilu_f(float z) {

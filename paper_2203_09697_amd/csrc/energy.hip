@@ -75,18 +75,13 @@ __global__ void scatter_by_key_kernel(const int32_t* __restrict__ key, int64_t n
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) tmp[ptr[key[i]] + atomicAdd(&cursor[key[i]], 1)] = (int32_t)i;
 }
-// order each list ascending by counting (lists are short); one wavefront per atom
+// order each list ascending by counting; one workgroup per atom
 __global__ void __launch_bounds__(256)
 sort_lists_kernel(const int32_t* __restrict__ ptr, const int32_t* __restrict__ tmp, int64_t n_atoms, int32_t* __restrict__ out) {
-  const int64_t j = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
-  if (j >= n_atoms) return;
+  __shared__ int32_t lds[SORT_LDS];
+  const int64_t j = blockIdx.x;
   const int b = ptr[j], n = ptr[j + 1] - b;
-  for (int r = threadIdx.x & 63; r < n; r += 64) {
-    const int v = tmp[b + r];
-    int rank = 0;
-    for (int q = 0; q < n; ++q) rank += tmp[b + q] < v ? 1 : 0;
-    out[b + rank] = v;
-  }
+  sort_list_block(tmp + b, n, out + b, lds);
 }
 
 // ------------------------------------------------------------------ energy head
@@ -324,7 +319,7 @@ int gp_edges_by_source_static(gp_ctx* ctx, const int32_t* src, int64_t n_atoms, 
   hist_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, cnt);
   scan_small_kernel<<<1, 1024, 0, st>>>(cnt, n_atoms, out_ptr);
   scatter_by_key_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, out_ptr, cursor, tmp);
-  sort_lists_kernel<<<wblk(n_atoms), 256, 0, st>>>(out_ptr, tmp, n_atoms, out_list);
+  sort_lists_kernel<<<(unsigned)n_atoms, 256, 0, st>>>(out_ptr, tmp, n_atoms, out_list);
   GP_LAUNCH_CHECK(ctx, "edges_by_source kernels");
   return GP_OK;
 }
@@ -359,7 +354,7 @@ int gp_edges_by_source(gp_ctx* ctx, const int32_t* src, int64_t n_atoms, int64_t
   hist_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, cnt);
   scan_small_kernel<<<1, 1024, 0, st>>>(cnt, n_atoms, out_ptr);
   scatter_by_key_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, out_ptr, cursor, tmp);
-  sort_lists_kernel<<<wblk(n_atoms), 256, 0, st>>>(out_ptr, tmp, n_atoms, out_list);
+  sort_lists_kernel<<<(unsigned)n_atoms, 256, 0, st>>>(out_ptr, tmp, n_atoms, out_list);
   GP_LAUNCH_CHECK(ctx, "edges_by_source kernels");
   return GP_OK;
 }
