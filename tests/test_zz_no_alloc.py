@@ -19,13 +19,14 @@ def _both(lib, ctx, pos, gptr, cutoff, cap):
     want_ptr, want_list = lib.gp_edges_by_source(ctx, e)                 # workspace variant
     out_ptr = torch.full((N + 1,), -7, dtype=torch.int32, device="cuda:0")
     out_list = torch.full((E,), -7, dtype=torch.int32, device="cuda:0")
-    before = torch.cuda.memory_allocated()
+    # torch's count of allocation requests (it only grows; tensors of earlier tests may be freed at any time)
+    before = torch.cuda.memory_stats().get("allocation.all.allocated", 0)
     raw = lib.load()
     rc = raw.gp_edges_by_source_static(ctx._h, C.c_void_p(e["src"].data_ptr()), C.c_int64(N), C.c_int64(E),
                                        C.c_void_p(out_ptr.data_ptr()), C.c_void_p(out_list.data_ptr()))
     assert rc == 0, raw.gp_last_error(ctx._h)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == before
     assert torch.equal(out_ptr, want_ptr) and torch.equal(out_list, want_list)
     # and against the definition: edge ids grouped by source atom, ascending within a group
     src = e["src"].cpu().numpy()
