@@ -486,6 +486,34 @@ int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, i
   return dispatch_gemm<MODE_NT>(ctx, g, 1);
 }
 
+// whether gp_gemm_nt2 can run as one launch (the conditions of the global->LDS bf16 kernel)
+bool gp_gemm_nt2_fused(const gp_ctx* ctx, const float* A, const float* Bt, const float* A2, const float* B2t, int64_t M, int N,
+                       int K, int a_bf16, int b_bf16) {
+  return ctx->gemm_bf16 && a_bf16 && b_bf16 && M >= 8192 && N > 128 && K % 64 == 0 && K >= 128 && aligned16(A) && aligned16(Bt) &&
+         aligned16(A2) && aligned16(B2t);
+}
+
+int gp_gemm_nt2(gp_ctx* ctx, const float* A, const float* Bt, const float* A2, const float* B2t, int64_t M, int N, int K,
+                float* out, int a_bf16, int b_bf16) {
+  GP_REQUIRE(ctx, A && Bt && A2 && B2t && out && M >= 0 && N > 0 && K > 0, "gemm_nt2: bad arguments");
+  if (M == 0) return GP_OK;
+  gp_epilogue e;
+  e.out = out;
+  if (!gp_gemm_nt2_fused(ctx, A, Bt, A2, B2t, M, N, K, a_bf16, b_bf16)) {
+    GP_TRY(gp_gemm_nt(ctx, A, Bt, M, N, K, e, a_bf16, b_bf16));
+    e.add_post = out;
+    return gp_gemm_nt(ctx, A2, B2t, M, N, K, e, a_bf16, b_bf16);
+  }
+  gemm_args g{};
+  g.A = A; g.B = Bt; g.A2 = A2; g.B2 = B2t; g.M = M; g.N = N; g.K = 2 * K; g.lda = K; g.ldb = K;
+  g.a_bf16 = a_bf16;
+  g.b_bf16 = b_bf16;
+  g.vecA = g.vecB = 1;
+  g.epi = e;
+  g.vecC = epi_vec_ok(e, N);
+  return dispatch_gemm<MODE_NT>(ctx, g, 1);
+}
+
 size_t gp_gemm_tn_scratch(int64_t rows, int M, int N) {
   tn_plan_t p = tn_plan(rows, M, N);
   return gp_align((size_t)p.splits * M * N * sizeof(float)) + gp_align((size_t)p.splits * p.tiles_m * N * sizeof(float));

@@ -732,12 +732,21 @@ gemm_dl_kernel(const gemm_args g) {
     }
   }
   const int n_slabs = g.K / BK;
+  // a second operand pair continues the contraction: its slabs follow the first pair's, at the same offsets from
+  // its own base addresses
+  const int n1 = g.A2 ? n_slabs / 2 : n_slabs;
+  const int64_t dA = g.A2 ? reinterpret_cast<const char*>(g.A2) - reinterpret_cast<const char*>(g.A) : 0;
+  const int64_t dB = g.A2 ? reinterpret_cast<const char*>(g.B2) - reinterpret_cast<const char*>(g.B) : 0;
   auto issue = [&](int slab, int stage) __attribute__((always_inline)) {
-    const int64_t kb = (int64_t)(slab < n_slabs ? slab : n_slabs - 1) * ROWB;   // past the end: re-read the last slab
+    const int sl = slab < n_slabs ? slab : n_slabs - 1;   // past the end: re-read the last slab
+    const bool second = sl >= n1;
+    const int64_t kb = (int64_t)(second ? sl - n1 : sl) * ROWB;
     char* dst = lds + stage * STAGE_B + wave * PER * 1024;
 #pragma unroll
-    for (int i = 0; i < PER; ++i)
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(src[i] + kb), (lds_void_ptr)(dst + i * 1024), 16, 0, 0);
+    for (int i = 0; i < PER; ++i) {
+      const int64_t d2 = second ? (wave * PER + i < A_LOADS ? dA : dB) : 0;   // uniform
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(src[i] + kb + d2), (lds_void_ptr)(dst + i * 1024), 16, 0, 0);
+    }
   };
 
   f32x16 acc[MB][NB];
@@ -881,8 +890,9 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
   } while (0)
   // tall activations times a wide weight matrix, both bf16 and k-contiguous: global->LDS loads, 256x256 tiles
   if (MODE == MODE_NT && g.a_bf16 && g.b_bf16 && g.M >= 8192 && g.N > 128 && g.K % 64 == 0 && g.K >= 128 &&
-      g.lda % 8 == 0 && g.ldb % 8 == 0)
+      g.lda % 8 == 0 && g.ldb % 8 == 0 && (!g.A2 || g.K % 128 == 0))
     return launch_dl<256, 256, 2, 4, 64, 2>(ctx, g);
+  if (g.A2) return gp_fail(ctx, GP_BAD_ARG, "gemm: a second operand pair is only taken by the global->LDS kernel");
   // the reduction over rows (TN) keeps the 128-row tiles its split plan was made for
   // short contractions are all prologue and epilogue: smaller tiles, more workgroups per CU to overlap them
   if (MODE != MODE_TN && g.K <= 128 && g.N > 64) GP_BF16_LAUNCH(128, 128, 2, 2);

@@ -25,6 +25,10 @@ struct gemm_args {
   int64_t k_per_split;     // TN only
   float* part;             // TN only: [splits, M, N]
   float* colsum_part;      // TN only, optional: [splits * tiles_m, N] partial column sums of B
+  // NT only, optional second operand pair: C = A B^T + A2 B2^T, each contraction K / 2 long (same leading dimensions);
+  // taken by the global->LDS kernel, which walks the second pair's slabs after the first's
+  const float* A2 = nullptr;
+  const float* B2 = nullptr;
   gp_epilogue epi;
 };
 
