@@ -470,7 +470,7 @@ int gp_triplet_bilinear_fwd(gp_ctx* ctx, const gp_graph* graph, int32_t form, in
                             int32_t width, const float* cos_alpha, const float* x, const float* Radt, float* A,
                             void* ws, size_t ws_bytes);
 int gp_triplet_bilinear_bwd_H(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t width,
-                              const float* cos_alpha_kj, const float* dz, float* H);
+                              const float* cos_alpha_kj, const float* dz, float* H, void* ws, size_t ws_bytes);
 int gp_triplet_bilinear_grad_cos(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t width,
                                  const float* cos_alpha_kj, const float* U, const float* dz, int32_t accumulate,
                                  float* grad_cos_kj);

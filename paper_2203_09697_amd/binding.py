@@ -456,12 +456,13 @@ def gp_triplet_bilinear_fwd(ctx, trip, form, S, Cc, cos_alpha, x, Radt, ws=None)
     return A
 
 
-def gp_triplet_bilinear_bwd_H(ctx, trip, form, S, cos_alpha_kj, dz):
+def gp_triplet_bilinear_bwd_H(ctx, trip, form, S, cos_alpha_kj, dz, ws=None):
     """H [E, S, O]."""
     g = Graph(trip)
     H = torch.empty((dz.shape[0], S, dz.shape[1]), dtype=torch.float32, device=ctx.device)
     ctx.check(load().gp_triplet_bilinear_bwd_H(ctx._h, C.byref(g), C.c_int32(form), C.c_int32(S), C.c_int32(dz.shape[1]),
-                                               _ptr(cos_alpha_kj), _ptr(dz), _ptr(H)))
+                                               _ptr(cos_alpha_kj), _ptr(dz), _ptr(H), _ptr(ws),
+                                               C.c_size_t(ws.numel() if ws is not None else 0)))
     return H
 
 

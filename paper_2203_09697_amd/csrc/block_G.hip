@@ -103,7 +103,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t N, int64_t E, int64_t 
   s->part_aux = (float*)c.take<char>(s->part_bytes);
   // scratch of the matrix-core triplet kernels: the per-triplet y buffer of the two-kernel form, or the per-atom
   // operand tables of the fused form (N > 0: the graph carries its lists by centre atom)
-  s->ybytes = d->dtype == GP_BF16_F32ACC ? std::max(gp_tripG_mfma_scratch(E, T), N > 0 ? gp_tripG_fused_scratch(N, E, d->int_emb) : (size_t)0) : 0;
+  s->ybytes = d->dtype == GP_BF16_F32ACC ? std::max(gp_tripG_mfma_scratch(E, T), N > 0 ? std::max(gp_tripG_fused_scratch(N, E, d->int_emb), gp_tripG_H_fused_scratch(N, E, d->emb_bil)) : (size_t)0) : 0;
   s->ybuf = c.take<char>(s->ybytes);
   const bool rt = d->radial_at_target != 0;
   s->dA = c.take<float>(rt ? E * C * F : 0);
@@ -660,7 +660,10 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   } else {
   // one pass over the triplets (kj-major): H[e', l, o]
   const bool bwd_mfma = want_trip_mfma(ctx, dims, graph, MFMA_BWD_DENSITY) && gp_tripG_mfma_bwd_usable(graph, O, S);
-  if (bwd_mfma)
+  if (bwd_mfma && ctx->trip_mfma != 2 && gp_tripG_H_fused_usable(graph, O, S) &&
+      sc.ybytes >= gp_tripG_H_fused_scratch(graph->n_atoms, E, O))
+    GP_TRY(gp_tripG_backward_H_fused(ctx, graph, basis->cos_alpha_kj, sc.dz, O, S, sc.Hd, sc.ybuf, sc.ybytes));
+  else if (bwd_mfma)
     GP_TRY(gp_tripG_backward_H_mfma(ctx, graph, basis->cos_alpha_kj, sc.dz, O, S, sc.Hd));
   else
     GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, nullptr, nullptr, nullptr, sc.dz, nullptr, O, S, 1,

@@ -108,4 +108,31 @@ __host__ __device__ constexpr float leg_mono(int l, int k) {
                              {0.f, -2.1875f, 0.f, 19.6875f, 0.f, -43.3125f, 0.f, 26.8125f}};
   return T[l][k];
 }
+// ---- shared by the one-pass kernels that stage per-atom operand tables through an LDS ring (triplet_g_fused*.hip)
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+
+constexpr int ROWPAD = 64;      // every atom's rows are padded to a multiple of this in the packed tables
+constexpr int PADJ = 72;        // padded row space per atom: base_j = roundup8(row_ptr[j]) + PADJ j leaves room for
+                                // rounding every atom's rows up to a multiple of 64 (d + 63) on an 8-aligned base (+ 7)
+__host__ __device__ inline int64_t padded_base(int r0, int64_t j) { return (((int64_t)r0 + 7) & ~(int64_t)7) + PADJ * j; }
+inline int64_t padded_rows(int64_t E, int64_t N) { return ((E + 7) & ~(int64_t)7) + PADJ * N + ROWPAD; }
+
+// Row r of a 16-row tile t of the matrix-core product stands for feature NT * rowperm(r) + t.  With rowperm the
+// transposition of r = 4 g + i to 4 i + g, the 4 accumulator registers i of lane (g, c) hold, over the NT tiles,
+// features NT (4 i + g) .. + NT - 1: for every i the lanes g = 0..3 of a column c together own 4 NT consecutive
+// features, so a store instruction writes whole 64-byte runs (NT = 8, bf16).  In LDS a slab's X^T is ordered
+// [p-block][t][r], so the 16 lanes of a fragment read 256 consecutive bytes.
+__device__ __forceinline__ int rowperm(int r) { return ((r & 3) << 2) | (r >> 2); }
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits [3:0] and [15:14], expcnt [6:4] = 7 and lgkmcnt [11:8] = 15: no wait)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_vm0() { wait_vmcnt<0>(); }
+constexpr int STAGES = 3;       // LDS ring: the loads of two slabs are under way while a third is worked on
+
+
 }  // namespace

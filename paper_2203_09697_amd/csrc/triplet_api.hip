@@ -20,6 +20,7 @@ int gp_triplet_workspace(const gp_graph* graph, int32_t width, size_t* bytes) {
   size_t b = gp_tripG_mfma_scratch(graph->n_edges, graph->n_triplets);
   if (graph->n_atoms > 0) {
     b = std::max(b, gp_tripG_fused_scratch(graph->n_atoms, graph->n_edges, width));
+    b = std::max(b, gp_tripG_H_fused_scratch(graph->n_atoms, graph->n_edges, width));
     b = std::max(b, gp_tripD_mfma_bwd_scratch(graph, width));
   }
   *bytes = b;
@@ -98,7 +99,7 @@ int gp_triplet_bilinear_fwd(gp_ctx* ctx, const gp_graph* graph, int32_t form, in
 }
 
 int gp_triplet_bilinear_bwd_H(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t width,
-                              const float* cos_alpha_kj, const float* dz, float* H) {
+                              const float* cos_alpha_kj, const float* dz, float* H, void* ws, size_t ws_bytes) {
   if (!ctx) return GP_BAD_ARG;
   GP_REQUIRE(ctx, graph && dz && H, "gp_triplet_bilinear_bwd_H: NULL pointer");
   GP_HIP(ctx, hipSetDevice(ctx->device));
@@ -111,6 +112,11 @@ int gp_triplet_bilinear_bwd_H(gp_ctx* ctx, const gp_graph* graph, int32_t form, 
                      "the kj-major view and at least one triplet (got %d)", width);
     GP_TRY(gp_take_deferred(ctx, "gp_triplet_bilinear_bwd_H"));
     GP_TRY(gp_check_degrees(ctx, graph));
+    // the one-pass kernel where its widths allow and a workspace is given, else the kernel that keeps all of an atom's
+    // out-edges in LDS
+    if (ws && gp_tripG_H_fused_usable(graph, width, num_spherical) &&
+        ws_bytes >= gp_tripG_H_fused_scratch(graph->n_atoms, graph->n_edges, width))
+      return gp_tripG_backward_H_fused(ctx, graph, cos_alpha_kj, dz, width, num_spherical, H, ws, ws_bytes);
     return gp_tripG_backward_H_mfma(ctx, graph, cos_alpha_kj, dz, width, num_spherical, H);
   }
   return gp_fail(ctx, GP_BAD_ARG, "gp_triplet_bilinear_bwd_H: unknown form %d", form);

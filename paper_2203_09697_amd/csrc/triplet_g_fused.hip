@@ -25,26 +25,10 @@
 
 namespace {
 
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef const __attribute__((address_space(1))) void* global_void_ptr;
-
 constexpr int GE = 16;          // out-edges per work item (4 wavefronts x 4 edges)
 constexpr int SLAB = 32;        // in-edge rows per slab (one step of the matrix-core contraction)
-constexpr int ROWPAD = 64;      // every atom's rows are padded to a multiple of this in the packed tables
-constexpr int PADJ = 72;        // padded row space per atom: base_j = roundup8(row_ptr[j]) + PADJ j leaves room for
-                                // rounding every atom's rows up to a multiple of 64 (d + 63) on an 8-aligned base (+ 7)
 constexpr int COEF_ROW = 128;   // floats per padded row of the coefficient table: [half][c 16][4]
 constexpr int FT = 256;         // threads of the main kernel
-
-__host__ __device__ inline int64_t padded_base(int r0, int64_t j) { return (((int64_t)r0 + 7) & ~(int64_t)7) + PADJ * j; }
-inline int64_t padded_rows(int64_t E, int64_t N) { return ((E + 7) & ~(int64_t)7) + PADJ * N + ROWPAD; }
-
-// Row r of a 16-row tile t of the matrix-core product stands for feature NT * rowperm(r) + t.  With rowperm the
-// transposition of r = 4 g + i to 4 i + g, the 4 accumulator registers i of lane (g, c) hold, over the NT tiles,
-// features NT (4 i + g) .. + NT - 1: for every i the lanes g = 0..3 of a column c together own 4 NT consecutive
-// features, so a store instruction writes whole 64-byte runs (NT = 8, bf16).  In LDS a slab's X^T is ordered
-// [p-block][t][r], so the 16 lanes of a fragment read 256 consecutive bytes.
-__device__ __forceinline__ int rowperm(int r) { return ((r & 3) << 2) | (r >> 2); }
 
 // Work items (atom, group of GE out-edges), numbered atom-major: item[w] = {first padded row of the atom, its number
 // of in-edge rows, out-list position of the group's first edge, edges in the group}; n_items[0] = their number.
@@ -160,15 +144,6 @@ fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
     *reinterpret_cast<f32x4*>(dst + 64) = f32x4{m[4], m[5], m[6], m[7]};
   }
 }
-
-// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits [3:0] and [15:14], expcnt [6:4] = 7 and lgkmcnt [11:8] = 15: no wait)
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-__device__ __forceinline__ void wait_vm0() { wait_vmcnt<0>(); }
-constexpr int STAGES = 3;       // LDS ring: the loads of two slabs are under way while a third is worked on
 
 // Two workgroups of 4 wavefronts share a compute unit (the registers allow 8 wavefronts): they work on different
 // items and drift apart, so one's staging, stores and prologue run beside the other's arithmetic.

@@ -92,9 +92,10 @@ def test_bilinear_forward_forms(lib, ctx, graph, form, F, C, S, tol):
     _check({"A": (A.reshape(E * C, F), A_ref.reshape(E * C, F))}, tol)
 
 
-@pytest.mark.parametrize("form,O,tol", [(1, 64, 1e-4), (2, 64, 2e-2), (1, 24, 1e-4), (2, 128, 2e-2)],
-                         ids=["per-edge", "per-atom", "per-edge odd", "per-atom 128"])
-def test_bilinear_backward_H_and_grad_cos(lib, ctx, graph, form, O, tol):
+@pytest.mark.parametrize("form,O,tol,with_ws", [(1, 64, 1e-4, False), (2, 64, 2e-2, True), (2, 64, 2e-2, False), (1, 24, 1e-4, False),
+                                                 (2, 128, 2e-2, True), (2, 32, 2e-2, True)],
+                         ids=["per-edge", "per-atom", "per-atom whole atom in LDS", "per-edge odd", "per-atom 128", "per-atom 32"])
+def test_bilinear_backward_H_and_grad_cos(lib, ctx, graph, form, O, tol, with_ws):
     ref, t, order = graph["ref"], graph["t"], graph["order"]
     E, T, S = len(ref["src"]), len(ref["idx_kj"]), 7
     rng = np.random.default_rng(O + form)
@@ -111,7 +112,8 @@ def test_bilinear_backward_H_and_grad_cos(lib, ctx, graph, form, O, tol):
     L = (Y * torch.einsum("to,tlo->tl", dzt[ji], Ut[kj])).sum()
     (gc_ref,) = torch.autograd.grad(L, cos)
     dzd = H.to_dev(dz, torch.float32)
-    Hg = lib.gp_triplet_bilinear_bwd_H(ctx, t, form, S, graph["cos_kj_d"], dzd)
+    ws = lib.gp_triplet_workspace(ctx, t, O) if with_ws else None   # with it the per-atom form is the one-pass kernel
+    Hg = lib.gp_triplet_bilinear_bwd_H(ctx, t, form, S, graph["cos_kj_d"], dzd, ws)
     gc = lib.gp_triplet_bilinear_grad_cos(ctx, t, form, S, graph["cos_kj_d"], H.to_dev(U, torch.float32), dzd)
     gc2 = lib.gp_triplet_bilinear_grad_cos(ctx, t, form, S, graph["cos_kj_d"], H.to_dev(U, torch.float32), dzd, grad_cos_kj=gc.clone())
     torch.cuda.synchronize()
