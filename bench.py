@@ -140,6 +140,10 @@ def main():
     ap.add_argument("--output-blocks", action="store_true",
                     help="variant-D workloads: add an output block (out_emb 256, 3 layers) after every interaction "
                          "block and differentiate the summed energies instead of a random upstream gradient")
+    ap.add_argument("--trip-mode", type=int, default=-1, choices=[-1, 0, 1, 2],
+                    help="variant-G triplet kernels: -1 the library's own choice, 0 per-edge vector kernels, 1 matrix-core "
+                         "kernels per centre atom, 2 the two-kernel forward and whole-atom backward forms")
+    ap.add_argument("--no-side-stream", action="store_true", help="weight-gradient GEMMs on the launch stream")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run one 256 MiB device copy first (known traffic, to scale rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -162,6 +166,10 @@ def main():
         sys.exit("bench.py: --radial-at-target / --symmetric apply to the variant-G workloads (cfg3, cfg4, cfg5)")
     pos, gptr = synth.make_positions(w, a.seed)
     ctx = gp.Context(0)
+    if a.trip_mode >= 0:
+        gp.gp_set_triplet_mfma(ctx, a.trip_mode)
+    if a.no_side_stream:
+        gp.gp_set_side_stream(ctx, False)
     dpos = torch.as_tensor(pos).to("cuda:0")
     dptr = torch.as_tensor(gptr).to("cuda:0")
 
@@ -267,7 +275,7 @@ def main():
                                                   "mfma_f32" if k["bound"] == "mfma" else None)
         k["frac_of_measured"] = round(k["achieved"] / measured[key], 4) if key else None
     top = kernels[0]
-    traffic = measured_traffic(w, bool(opts) or a.output_blocks)
+    traffic = measured_traffic(w, bool(opts) or a.output_blocks or a.trip_mode >= 0 or a.no_side_stream)
     for k in kernels:
         k["traffic"] = traffic.get(k["kernel"])
     roofline = {"kernel": top["kernel"], "bound": top["bound"], "achieved": top["achieved"], "peak": top["peak"],

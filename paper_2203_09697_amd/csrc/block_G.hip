@@ -103,7 +103,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t N, int64_t E, int64_t 
   s->part_aux = (float*)c.take<char>(s->part_bytes);
   // scratch of the matrix-core triplet kernels: the per-triplet y buffer of the two-kernel form, or the per-atom
   // operand tables of the fused form (N > 0: the graph carries its lists by centre atom)
-  s->ybytes = d->dtype == GP_BF16_F32ACC ? std::max(gp_tripG_mfma_scratch(E, T), N > 0 ? std::max(gp_tripG_fused_scratch(N, E, d->int_emb), gp_tripG_H_fused_scratch(N, E, d->emb_bil)) : (size_t)0) : 0;
+  s->ybytes = d->dtype == GP_BF16_F32ACC ? std::max(gp_tripG_mfma_scratch(E, T), N > 0 ? std::max(gp_tripG_fused_scratch(N, E, std::max(d->int_emb, d->emb_bil)), gp_tripG_H_fused_scratch(N, E, std::max(d->int_emb, d->emb_bil))) : (size_t)0) : 0;
   s->ybuf = c.take<char>(s->ybytes);
   const bool rt = d->radial_at_target != 0;
   s->dA = c.take<float>(rt ? E * C * F : 0);
@@ -486,7 +486,10 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     if (want_rt_mfma(ctx, dims, graph, MFMA_BWD_DENSITY) && gp_tripG_mfma_H_usable(&gml, F, S)) {
       iota_kernel<<<(unsigned)((E + 255) / 256), 256, 0, ctx->stream>>>(sc.iota, E);
       GP_LAUNCH_CHECK(ctx, "iota_kernel");
-      GP_TRY(gp_tripG_backward_H_mfma(ctx, &gml, basis->cos_alpha, s.x, F, S, s.B1, graph->out_list));
+      if (ctx->trip_mfma != 2 && gp_tripG_H_fused_usable(&gml, F, S) && sc.ybytes >= gp_tripG_H_fused_scratch(graph->n_atoms, E, F))
+        GP_TRY(gp_tripG_backward_H_fused(ctx, &gml, basis->cos_alpha, s.x, F, S, s.B1, sc.ybuf, sc.ybytes, graph->out_list));
+      else
+        GP_TRY(gp_tripG_backward_H_mfma(ctx, &gml, basis->cos_alpha, s.x, F, S, s.B1, graph->out_list));
     } else
       GP_TRY(gp_tripD_backward(ctx, &gm, basis->cos_alpha, nullptr, nullptr, nullptr, s.x, nullptr, F, S, 1, s.B1, nullptr));
     GP_TRY(gp_tripG_edge_G(ctx, s.Radt, s.B1, E, S, C, F, s.A));
@@ -638,8 +641,12 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
       // the radial table in out-list order, so that the threads of the y kernel read neighbouring columns
       gather_cols_kernel<<<dim3((unsigned)((E + 255) / 256), (unsigned)(S * C)), 256, 0, ctx->stream>>>(s.Radt, graph->out_list, E, sc.Radt_out);
       GP_LAUNCH_CHECK(ctx, "gather_cols_kernel");
-      GP_TRY(gp_tripG_forward_mfma(ctx, &gml, basis->cos_alpha_kj, sc.dz, sc.Radt_out, O, S, C, sc.Gm, sc.ybuf, sc.ybytes, 0,
-                                   graph->out_list, 1));
+      if (ctx->trip_mfma != 2 && gp_tripG_fused_usable(&gml, O, S, C) && sc.ybytes >= gp_tripG_fused_scratch(graph->n_atoms, E, O))
+        GP_TRY(gp_tripG_forward_fused(ctx, &gml, basis->cos_alpha_kj, sc.dz, sc.Radt_out, O, S, C, sc.Gm, sc.ybuf, sc.ybytes, 0,
+                                      graph->out_list));
+      else
+        GP_TRY(gp_tripG_forward_mfma(ctx, &gml, basis->cos_alpha_kj, sc.dz, sc.Radt_out, O, S, C, sc.Gm, sc.ybuf, sc.ybytes, 0,
+                                     graph->out_list, 1));
     } else
       GP_TRY(gp_tripD_forward(ctx, &gm, basis->cos_alpha_kj, sc.dz, s.Radt, nullptr, O, S, C, nullptr, sc.Gm));
     GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                 // [(c,o), f]

@@ -78,16 +78,18 @@ int gp_tripG_forward_mfma(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha
                           const int32_t* row_list = nullptr, int rad_by_pos = 0);
 // The same accumulator in one pass, without the per-triplet y buffer (triplet_g_fused.hip): y is evaluated in
 // registers inside the contraction kernel from a per-row coefficient table that a pre-pass lays out per centre
-// atom.  F = 32, 64 or 128; rows must be consecutive edge ids (no row_list).  ws: gp_tripG_fused_scratch bytes.
+// atom.  F = 32, 64 or 128.  ws: gp_tripG_fused_scratch bytes.  With a row_list (see below) the columns of Radt must
+// already be in row_list order.
 bool gp_tripG_fused_usable(const gp_graph* g, int F, int S, int C);
 size_t gp_tripG_fused_scratch(int64_t N, int64_t E, int F);
 int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
-                           int F, int S, int C, float* A, void* ws, size_t ws_bytes, int out_half);
-// H[e',l,o] in the same one-pass style (triplet_g_fused_bwd.hip): O = 32, 64 or 128, rows consecutive edge ids.
+                           int F, int S, int C, float* A, void* ws, size_t ws_bytes, int out_half,
+                           const int32_t* row_list = nullptr);
+// H[e',l,o] in the same one-pass style (triplet_g_fused_bwd.hip): O = 32, 64 or 128.
 bool gp_tripG_H_fused_usable(const gp_graph* g, int O, int S);
 size_t gp_tripG_H_fused_scratch(int64_t N, int64_t E, int O);
 int gp_tripG_backward_H_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S, float* H,
-                              void* ws, size_t ws_bytes);
+                              void* ws, size_t ws_bytes, const int32_t* row_list = nullptr);
 // rad_by_pos: Radt's columns are in row_list order already (gathered by the caller)
 // row_list: edge ids of the atoms' rows where these are not consecutive (the mirrored views of a block with the
 // radial factor at the target edge: g->row_ptr then indexes row_list, and g->out_list holds consecutive ids)

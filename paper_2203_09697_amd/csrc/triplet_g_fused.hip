@@ -81,8 +81,8 @@ template <int SM>
 __global__ void __launch_bounds__(256)
 fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
                   const int32_t* __restrict__ seg_ptr_ji, const int32_t* __restrict__ idx_kj, const float* __restrict__ x,
-                  const float* __restrict__ Radt, int64_t E, int S, int C, int F, __bf16* __restrict__ xb,
-                  float* __restrict__ coef, int32_t* __restrict__ edge_info) {
+                  const float* __restrict__ Radt, int64_t E, int S, int C, int F, const int32_t* __restrict__ rows,
+                  __bf16* __restrict__ xb, float* __restrict__ coef, int32_t* __restrict__ edge_info) {
   const int j = blockIdx.x;
   const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
   const int p0 = ROWPAD * (int)blockIdx.y;
@@ -91,7 +91,7 @@ fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
     for (int t = threadIdx.x; t < dout; t += 256) {
       const int e = out_list[o0 + t];
       const int seg = seg_ptr_ji[e], cnt = seg_ptr_ji[e + 1] - seg;
-      const int gap = first_mismatch(idx_kj + seg, cnt, [=](int slot) { return r0 + slot; });
+      const int gap = first_mismatch(idx_kj + seg, cnt, [=](int slot) { return rows ? rows[r0 + slot] : r0 + slot; });
       int32_t* dst = edge_info + 4 * (int64_t)(o0 + t);
       dst[0] = e;
       dst[1] = seg;
@@ -108,7 +108,8 @@ fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int p = p0 + 8 * pb + i;
-      const float xv = x[(int64_t)(r0 + (p < d ? p : 0)) * F + f];   // clamped row, zeroed below: the load stays unconditional
+      const int q = r0 + (p < d ? p : 0);                            // clamped row, zeroed below: the load stays unconditional
+      const float xv = x[(int64_t)(rows ? rows[q] : q) * F + f];
       v[i] = (__bf16)(p < d ? xv : 0.f);
     }
     *reinterpret_cast<bf16x8*>(xb + ((base / 8 + pb) * F + f) * 8) = v;
@@ -371,7 +372,7 @@ bool gp_tripG_fused_usable(const gp_graph* g, int F, int S, int C) {
 }
 
 int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha, const float* x, const float* Radt,
-                           int F, int S, int C, float* A, void* ws, size_t ws_bytes, int out_half) {
+                           int F, int S, int C, float* A, void* ws, size_t ws_bytes, int out_half, const int32_t* rows_list) {
   const int64_t E = g->n_edges, T = g->n_triplets, N = g->n_atoms;
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, gp_tripG_fused_usable(g, F, S, C), "triplet G (fused matrix-core form): graph lists or widths not supported");
@@ -386,10 +387,10 @@ int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
     const dim3 grid((unsigned)N, (unsigned)((g->max_in_degree + ROWPAD - 1) / ROWPAD));
     if (S <= 7)
       fused_pack_kernel<7><<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj, x, Radt, E, S, C, F,
-                                                 w.xb, w.coef, w.edge_info);
+                                                 rows_list, w.xb, w.coef, w.edge_info);
     else
       fused_pack_kernel<8><<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj, x, Radt, E, S, C, F,
-                                                 w.xb, w.coef, w.edge_info);
+                                                 rows_list, w.xb, w.coef, w.edge_info);
     GP_LAUNCH_CHECK(ctx, "fused_pack_kernel");
   }
   {

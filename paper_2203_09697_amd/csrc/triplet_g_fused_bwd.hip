@@ -82,7 +82,7 @@ fusedH_items_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restri
 __global__ void __launch_bounds__(256)
 fusedH_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
                    const int32_t* __restrict__ seg_ptr_kj, const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ dz,
-                   int O, __bf16* __restrict__ dzb, int32_t* __restrict__ row_info) {
+                   int O, const int32_t* __restrict__ rows, __bf16* __restrict__ dzb, int32_t* __restrict__ row_info) {
   const int j = blockIdx.x;
   const int ob = out_ptr[j], dout = out_ptr[j + 1] - ob;
   const int n0 = ROWPAD * (int)blockIdx.y;
@@ -90,7 +90,8 @@ fusedH_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restric
   if (blockIdx.y == 0) {
     const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
     for (int p = threadIdx.x; p < d; p += 256) {
-      const int seg = seg_ptr_kj[r0 + p], cnt = seg_ptr_kj[r0 + p + 1] - seg;
+      const int e = rows ? rows[r0 + p] : r0 + p;
+      const int seg = seg_ptr_kj[e], cnt = seg_ptr_kj[e + 1] - seg;
       row_info[2 * (int64_t)(r0 + p)] = seg;
       row_info[2 * (int64_t)(r0 + p) + 1] = first_mismatch(idx_ji_kj + seg, cnt, [=](int slot) { return outs[slot]; });
     }
@@ -115,7 +116,8 @@ template <int NT>   // O = 16 NT (NT = 2, 4, 8)
 // loop waits for every load in flight
 __global__ void __launch_bounds__(256, NT == 8 ? 2 : 3)
 tripG_H_fused_kernel(const float* __restrict__ cos_kj, int64_t T, const __bf16* __restrict__ dzb, const int32_t* __restrict__ row_info,
-                     const int32_t* __restrict__ n_items, const int32_t* __restrict__ item, int S, float* __restrict__ H) {
+                     const int32_t* __restrict__ n_items, const int32_t* __restrict__ item, int S,
+                     const int32_t* __restrict__ rows, float* __restrict__ H) {
   constexpr int O = 16 * NT;
   constexpr int Z_B = HSLAB / 8 * O * 16;            // dz^T of a slab: 4 position blocks x O x 8 bf16
   constexpr int CS_B = HR * HSLAB * 4;               // cosines of the group's rows for a slab
@@ -236,7 +238,8 @@ tripG_H_fused_kernel(const float* __restrict__ cos_kj, int64_t T, const __bf16* 
     for (int rt = 0; rt < HRT; ++rt) {
       const int pl = 8 * wv + 2 * rt + p2;
       if (pl >= n_rows) continue;
-      float* dst = H + ((int64_t)(e0 + pl) * S + l) * O + NT * kq;
+      const int e_out = rows ? rows[e0 + pl] : e0 + pl;
+      float* dst = H + ((int64_t)e_out * S + l) * O + NT * kq;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if constexpr (NT == 4 || NT == 8) {
@@ -280,7 +283,7 @@ bool gp_tripG_H_fused_usable(const gp_graph* g, int O, int S) {
 }
 
 int gp_tripG_backward_H_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S, float* H,
-                              void* ws, size_t ws_bytes) {
+                              void* ws, size_t ws_bytes, const int32_t* row_list) {
   const int64_t E = g->n_edges, T = g->n_triplets, N = g->n_atoms;
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, gp_tripG_H_fused_usable(g, O, S), "triplet G backward (one-pass matrix-core form): graph lists or widths not supported");
@@ -292,13 +295,13 @@ int gp_tripG_backward_H_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_a
     gp_prof_scope prof(ctx, "tripG_H_pack", 0.0, (double)E * (4.0 * O + 2.0 * O + 16.0));
     fusedH_items_kernel<<<1, 1024, 0, st>>>(g->row_ptr, g->out_ptr, (int)N, w.n_items, w.item);
     const dim3 grid((unsigned)N, (unsigned)((g->max_out_degree + ROWPAD - 1) / ROWPAD));
-    fusedH_pack_kernel<<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj, g->idx_ji_kj, dz, O, w.dzb, w.row_info);
+    fusedH_pack_kernel<<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj, g->idx_ji_kj, dz, O, row_list, w.dzb, w.row_info);
     GP_LAUNCH_CHECK(ctx, "fusedH_pack_kernel");
   }
   gp_prof_scope prof(ctx, "tripG_H_fused", (double)T * 2.0 * 8 * O, (double)T * 4.0 + (double)E * (2.0 * O + 4.0 * S * O));
   const unsigned grid = (unsigned)(E / HR + N);   // an upper bound of the number of work items; the rest exit at once
 #define GP_H_LAUNCH(NT) \
-  tripG_H_fused_kernel<NT><<<grid, 256, STAGES * (HSLAB / 8 * 16 * NT * 16 + HR * HSLAB * 4), st>>>(cos_alpha_kj, T, w.dzb, w.row_info, w.n_items, w.item, S, H)
+  tripG_H_fused_kernel<NT><<<grid, 256, STAGES * (HSLAB / 8 * 16 * NT * 16 + HR * HSLAB * 4), st>>>(cos_alpha_kj, T, w.dzb, w.row_info, w.n_items, w.item, S, row_list, H)
   if (O == 128) GP_H_LAUNCH(8);
   else if (O == 64) GP_H_LAUNCH(4);
   else GP_H_LAUNCH(2);
