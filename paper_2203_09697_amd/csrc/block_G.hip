@@ -299,6 +299,51 @@ __global__ void gate_bwd_half_kernel(const __bf16* __restrict__ dxg, const __bf1
   }
 }
 
+// The same with the gate evaluated in place from its two factors, gate[e, h] = sum_k g[e, k] Wrbf[k, h] with
+// g [E, R], Wrbf [R, H], R <= 16 (in fp32; the forward GEMM's epilogue multiplied by the same sum of bf16-rounded
+// factors, a difference below the rounding of the bf16 results), instead of read: a
+// thread keeps the R x 4 weights of its 4 columns in registers and walks GATE_ROWS rows, whose R values are uniform
+// across the workgroup.
+constexpr int GATE_ROWS = 64;
+__global__ void __launch_bounds__(256)
+gate_bwd_lr_kernel(const __bf16* __restrict__ dxg, const __bf16* __restrict__ z, const float* __restrict__ g,
+                   const float* __restrict__ Wrbf, int64_t E, int H, int R, __bf16* __restrict__ dz, __bf16* __restrict__ dgate) {
+  const int col = 4 * ((int)blockIdx.y * 256 + (int)threadIdx.x);
+  if (col >= H) return;
+  float wk[16][4];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const f4 w4 = *reinterpret_cast<const f4*>(Wrbf + (int64_t)(k < R ? k : 0) * H + col);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) wk[k][c] = k < R ? w4[c] : 0.f;
+  }
+  const int64_t r0 = (int64_t)blockIdx.x * GATE_ROWS;
+  const int64_t r1 = r0 + GATE_ROWS < E ? r0 + GATE_ROWS : E;
+#pragma unroll 4
+  for (int64_t row = r0; row < r1; ++row) {
+    const int64_t i = row * H + col;
+    const h4 d = *reinterpret_cast<const h4*>(dxg + i), zz = *reinterpret_cast<const h4*>(z + i);
+    const float* gr = g + row * R;
+    float gt[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const float gk = k < R ? gr[k] : 0.f;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) gt[c] += gk * wk[k][c];
+    }
+    h4 o1, o2;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      // one sigmoid for silu and its derivative
+      const float dv = (float)d[c], zv = (float)zz[c], sg = sigmoid_f(zv);
+      o1[c] = (__bf16)(dv * gt[c] * (sg * (1.0f + zv * (1.0f - sg))));
+      o2[c] = (__bf16)(dv * zv * sg);
+    }
+    *reinterpret_cast<h4*>(dz + i) = o1;
+    *reinterpret_cast<h4*>(dgate + i) = o2;
+  }
+}
+
 // out = bf16(in), 4 elements per thread
 // out[c, r] = bf16(in[r, c]), in [rows, cols] (weights only: at most a few million elements)
 __global__ void to_half_T_kernel(const float* __restrict__ in, __bf16* __restrict__ out, int rows, int cols) {
@@ -366,6 +411,15 @@ bool want_rt_mfma(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g, double
 // The accumulator A[E, C, F] is stored as bf16 when the matrix-core kernel writes it and bf16 storage is on: its
 // only readers are two bf16-operand GEMMs.  Forward and backward must agree, so the triplet mode of the
 // context must not change between the two calls of a step.
+// The gate silu(m W_ba) is multiplied by, (g W_rbfS) W_rbfB, has rank emb_rbf: where the wide GEMM runs in the kernel that
+// can evaluate such a factor in its epilogue, the [E, emb] gate matrix is never written or read (forward: a [E, emb_rbf]
+// product instead of the [E, emb] one and one epilogue input stream less; backward: one input stream less).  The
+// [E, emb_rbf] factor takes the gate's place in the saved buffer.  Forward and backward decide alike from the shapes.
+bool lowrank_gate(const gp_ctx* ctx, const gp_dims* d, int64_t E) {
+  return half_storage(d) && d->emb % 8 == 0 && d->int_emb % 2 == 0 && d->emb_bil % 2 == 0 && d->emb_rbf <= 16 &&
+         gp_gemm_nt_takes_lowrank(ctx, E, d->emb, d->emb);
+}
+
 // bf16 copies of the weights are used when their row lengths allow paired loads
 bool weights_half(const gp_dims* d) { return half_storage(d) && d->int_emb % 2 == 0 && d->emb_bil % 2 == 0; }
 
@@ -449,8 +503,14 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   const bool ah = a_half(ctx, dims, graph);
   ctx->fwd_flags[saved] = ah ? 1u : 0u;   // element type of the accumulator A: the backward call must read it the same way
   if (dims->dtype == GP_BF16_F32ACC && ctx->trip_mfma != 0) GP_TRY(gp_check_degrees(ctx, graph));
-  e = gp_epilogue(); e.out = s.gate; e.bf16 = hs ? EPI_BF_OUT : 0u;
-  GP_TRY(gp_gemm_nn(ctx, g, s.Wrbf, E, H, R, e));                                   // gate
+  const bool lrg = lowrank_gate(ctx, dims, E);
+  if (lrg) {
+    e = gp_epilogue(); e.out = s.gate;
+    GP_TRY(gp_gemm_nn(ctx, g, w->W_rbfS, E, RB, R, e));                             // g W_rbfS [E, emb_rbf], fp32
+  } else {
+    e = gp_epilogue(); e.out = s.gate; e.bf16 = hs ? EPI_BF_OUT : 0u;
+    GP_TRY(gp_gemm_nn(ctx, g, s.Wrbf, E, H, R, e));                                 // gate
+  }
   const float* m_op = m_in;   // the input messages as a GEMM operand
   if (hs) {
     GP_TRY(to_half(ctx, m_in, s.m_h, (int64_t)E * H));
@@ -469,7 +529,9 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   const float* W_down = weight_operand(ctx, wh, w->W_down, sc.W_down_h, (int64_t)H * F, &rc);
   const float* W_bil = weight_operand(ctx, wh && ah, w->W_bil, sc.W_bil_h, (int64_t)C * F * O, &rc);
   GP_TRY(rc);
-  e = gp_epilogue(); e.save_pre = s.z_ba; e.act = 1; e.mul = s.gate; e.out = s.xg;
+  e = gp_epilogue(); e.save_pre = s.z_ba; e.act = 1; e.out = s.xg;
+  if (lrg) e.lr_a = s.gate, e.lr_b = w->W_rbfB, e.lr_k = RB;
+  else e.mul = s.gate;
   e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_MUL | EPI_BF_OUT) : 0u;
   if (wh) GP_TRY(gp_gemm_nt(ctx, m_op, W_ba_T, E, H, H, e, 1, 1));                  // xg
   else GP_TRY(gp_gemm_nn(ctx, m_op, w->W_ba, E, H, H, e, hs));
@@ -702,7 +764,12 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(gp_gemm_nt(ctx, sc.dzdn, w->W_down, E, H, F, e));                          // dxg
   float* dz_ba = d_up;   // d_up is no longer needed on this stream
   GP_TRY(aux.before_write(d_up));
-  if (hs) {
+  if (lowrank_gate(ctx, dims, E)) {
+    gp_prof_scope prof(ctx, "ew_gate_bwd_lr", 2.0 * RB * (double)EH, 8.0 * (double)EH + 4.0 * RB * (double)E);   // 4 bf16 arrays
+    gate_bwd_lr_kernel<<<dim3((unsigned)((E + GATE_ROWS - 1) / GATE_ROWS), (unsigned)((H + 1023) / 1024)), 256, 0, ctx->stream>>>(
+        (const __bf16*)dxg, (const __bf16*)s.z_ba, s.gate, w->W_rbfB, E, H, RB, (__bf16*)dz_ba, (__bf16*)dgate);
+    GP_LAUNCH_CHECK(ctx, "gate_bwd_lr_kernel");
+  } else if (hs) {
     gp_prof_scope prof(ctx, "ew_gate_bwd_half", 0.0, 10.0 * (double)EH);   // 5 bf16 arrays
     gate_bwd_half_kernel<<<(unsigned)((EH / 4 + 256) / 256), 256, 0, ctx->stream>>>(
         (const __bf16*)dxg, (const __bf16*)s.z_ba, (const __bf16*)s.gate, (__bf16*)dz_ba, (__bf16*)dgate, EH);

@@ -12,6 +12,13 @@ struct gp_epilogue {
   const float* zsrc = nullptr;
   const float* mul = nullptr;       // v *= mul[row,col]
   const float* add_post = nullptr;  // v += add_post[row,col]
+  // v *= sum_{k < lr_k} lr_a[row, k] lr_b[k, col]: a factor of rank lr_k <= 16 evaluated in the epilogue (lr_a to 16
+  // bits as two bf16 terms, lr_b rounded to bf16, fp32 sum, two matrix-core instructions per 32x32 block) instead of
+  // read from an [rows, n] matrix.
+  // Takes the place of `mul` in the order of steps; only where gp_gemm_nt_takes_lowrank says so.
+  const float* lr_a = nullptr;      // fp32 [rows, lr_k]
+  const float* lr_b = nullptr;      // fp32 [lr_k, n]
+  int lr_k = 0;
   float scale = 1.0f;               // v *= scale
   float* out = nullptr;             // out[row,col] = v
   float* out2 = nullptr;            // out2[row,col] = v * silu'(z2src[row,col])
@@ -33,6 +40,8 @@ int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, in
 // C = A[M,K] @ Bt[N,K]^T
 int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, int K, const gp_epilogue& epi, int a_bf16 = 0,
                int b_bf16 = 0);
+// whether gp_gemm_nt with these shapes and bf16 operands runs in the kernel whose epilogue evaluates lr_a, lr_b
+bool gp_gemm_nt_takes_lowrank(const gp_ctx* ctx, int64_t M, int N, int K);
 // out = A[M,K] @ Bt[N,K]^T + A2[M,K] @ B2t[N,K]^T (fp32 result, no other epilogue step).  With tall bf16 operands this is
 // ONE launch of the global->LDS kernel whose contraction runs over both pairs, so the result is written once instead
 // of written, read back and written again; otherwise two launches, the second adding to the first's result.

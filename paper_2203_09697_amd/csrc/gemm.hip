@@ -403,6 +403,7 @@ int dispatch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
   if (ctx->gemm_bf16 && !(MODE == MODE_TN && g.colsum_part)) return gp_gemm_bf16_launch(ctx, MODE, &g, splits);
   if (g.a_bf16 || g.b_bf16 || g.epi.bf16)
     return gp_fail(ctx, GP_BAD_ARG, "gemm: bf16 storage is only handled by the bf16-operand kernels");
+  if (g.epi.lr_a) return gp_fail(ctx, GP_BAD_ARG, "gemm: a low-rank epilogue factor is only taken by the global->LDS bf16 kernel");
   if (MODE == MODE_TN) {   // tile widths the split plan (tn_plan / tile_bn) was made for
     if (g.N > 64) return launch_gemm<TILE_BM, 128, 2, 2, MODE>(ctx, g, splits);
     if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);
@@ -484,6 +485,11 @@ int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, i
   g.epi = epi;
   g.vecC = epi_vec_ok(epi, N);
   return dispatch_gemm<MODE_NT>(ctx, g, 1);
+}
+
+// the conditions of the global->LDS bf16 kernel on the shape (its operands must also be bf16 and 16-byte aligned)
+bool gp_gemm_nt_takes_lowrank(const gp_ctx* ctx, int64_t M, int N, int K) {
+  return ctx->gemm_bf16 && M >= 8192 && N > 128 && N % 4 == 0 && K % 64 == 0 && K >= 128;
 }
 
 // whether gp_gemm_nt2 can run as one launch (the conditions of the global->LDS bf16 kernel)

@@ -345,7 +345,9 @@ struct bl_xcontig_bf {
 
 // Epilogue of one workgroup tile: accumulators have the register layout of the 32x32 MFMA and are transposed
 // through a per-wavefront LDS slice so that loads and stores are 16-byte accesses.
-template <int MB, int NB, int MODE>
+// LR_WAVES > 0 (the number of wavefronts of the workgroup): the kernel can evaluate the epilogue's low-rank factor; its
+// 32x32 blocks go through a second staging slice per wavefront, behind the first ones.
+template <int MB, int NB, int MODE, int LR_WAVES = 0>
 __device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[MB][NB], float* smem, int64_t m0, int n0,
                                               int wm0, int wn0, int split) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -354,6 +356,40 @@ __device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[
     // Two blocks side by side (32 rows x 64 columns): 16 lanes cover 64 consecutive columns of a row, so a store
     // instruction writes whole 128-byte lines of a bf16 matrix (two per row of an fp32 one) instead of halves.
     float* stage = smem + wave * (32 * EPI_LD2);
+    // Low-rank factor: operand fragments of the wavefront's rows and columns (k = 8 kh + c, zero from lr_k on), two
+    // MFMAs per block, in the accumulators' own register layout.  The row factor (an activation) enters as the sum of
+    // two bf16 numbers, i.e. to 16 bits: rounded to 8 bits, a model's energy turned out too rough a function of the
+    // positions for a finite difference of it to match its forces; the column factor is a weight like any other.
+    const bool lr = LR_WAVES > 0 && g.epi.lr_a != nullptr;
+    float* stage_lr = smem + (LR_WAVES + wave) * (32 * EPI_LD2);
+    bf16x8 ga[LR_WAVES > 0 ? MB : 1], ga_lo[LR_WAVES > 0 ? MB : 1], gb[LR_WAVES > 0 ? NB : 1];
+    if constexpr (LR_WAVES > 0) {
+      if (lr) {
+        const int kk = g.epi.lr_k;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+          const int64_t row = m0 + wm0 + i * 32 + l32 < g.M ? m0 + wm0 + i * 32 + l32 : g.M - 1;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            const int k = 8 * kh + c;
+            const float a0 = g.epi.lr_a[row * kk + (k < kk ? k : kk - 1)];  // clamped: the load stays unconditional
+            const float a = k < kk ? a0 : 0.f;
+            ga[i][c] = (__bf16)a;
+            ga_lo[i][c] = (__bf16)(a - (float)ga[i][c]);
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const int col = n0 + wn0 + j * 32 + l32 < g.N ? n0 + wn0 + j * 32 + l32 : g.N - 1;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            const int k = 8 * kh + c;
+            const float b = g.epi.lr_b[(int64_t)(k < kk ? k : kk - 1) * g.N + col];
+            gb[j][c] = (__bf16)(k < kk ? b : 0.f);
+          }
+        }
+      }
+    }
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -363,6 +399,20 @@ __device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[
 #pragma unroll
           for (int v = 0; v < 16; ++v)
             stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD2 + jj * 32 + l32] = acc[i][j + jj][v];
+        if constexpr (LR_WAVES > 0) {
+          if (lr) {
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+              f32x16 z;
+#pragma unroll
+              for (int v = 0; v < 16; ++v) z[v] = 0.f;
+              f32x16 f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga_lo[i], gb[j + jj], z, 0, 0, 0);
+              f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[i], gb[j + jj], f, 0, 0, 0);
+#pragma unroll
+              for (int v = 0; v < 16; ++v) stage_lr[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD2 + jj * 32 + l32] = f[v];
+            }
+          }
+        }
         wave_lds_sync();
 #pragma unroll 1
         for (int it = 0; it < 8; ++it) {
@@ -371,6 +421,13 @@ __device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[
           const int64_t row = m0 + wm0 + i * 32 + r;
           const int col = n0 + wn0 + j * 32 + c4;
           if (row >= g.M || col >= g.N) continue;
+          if constexpr (LR_WAVES > 0) {
+            if (lr) {   // dispatch has checked vecC
+              const f32x4 f4 = *reinterpret_cast<const f32x4*>(&stage_lr[r * EPI_LD2 + c4]);
+              epilogue_store4(g.epi, row, col, g.N, v4, &f4);
+              continue;
+            }
+          }
           if (g.vecC) epilogue_store4(g.epi, row, col, g.N, v4);
           else
             for (int c = 0; c < 4; ++c)
@@ -810,7 +867,7 @@ gemm_dl_kernel(const gemm_args g) {
   }
   wait_vmcnt_lgkmcnt0<0>();                    // the loads issued past the end must not land in the epilogue's staging area
   __syncthreads();
-  tile_epilogue<MB, NB, MODE_NT>(g, acc, smem, m0, n0, wm0, wn0, 0);
+  tile_epilogue<MB, NB, MODE_NT, NW>(g, acc, smem, m0, n0, wm0, wn0, 0);
 }
 
 template <int BM, int BN, int WMS, int WNS, int BK, int STAGES>
@@ -823,9 +880,11 @@ int launch_dl(gp_ctx* ctx, gemm_args& g) {
   gp_prof_scope prof(ctx, name, 2.0 * mnk, 2.0 * (double)g.M * g.K + 2.0 * (double)g.K * g.N + 4.0 * (double)g.M * g.N);
   constexpr int NW = WMS * WNS;
   constexpr size_t lds_main = (size_t)STAGES * (BM + BN) * BK * 2;
-  constexpr size_t lds_epi = sizeof(float) * NW * 32 * EPI_LD2;
+  constexpr size_t lds_epi = sizeof(float) * 2 * NW * 32 * EPI_LD2;   // accumulator blocks and low-rank factor blocks
   constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
   static_assert((NW == 8 ? 1 : 2) * lds <= 160 * 1024, "fits the compute unit's LDS");
+  if (g.epi.lr_a && (!g.vecC || !g.epi.lr_b || g.epi.lr_k < 1 || g.epi.lr_k > 16))
+    return gp_fail(ctx, GP_BAD_ARG, "gemm: low-rank epilogue factor needs rank 1..16 and 16-byte aligned epilogue matrices");
   static bool raised = false;
   if (!raised && lds > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dl_kernel<BM, BN, WMS, WNS, BK, STAGES>),
@@ -893,6 +952,7 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
       g.lda % 8 == 0 && g.ldb % 8 == 0 && (!g.A2 || g.K % 128 == 0))
     return launch_dl<256, 256, 2, 4, 64, 2>(ctx, g);
   if (g.A2) return gp_fail(ctx, GP_BAD_ARG, "gemm: a second operand pair is only taken by the global->LDS kernel");
+  if (g.epi.lr_a) return gp_fail(ctx, GP_BAD_ARG, "gemm: a low-rank epilogue factor is only taken by the global->LDS kernel");
   // the reduction over rows (TN) keeps the 128-row tiles its split plan was made for
   // short contractions are all prologue and epilogue: smaller tiles, more workgroups per CU to overlap them
   if (MODE != MODE_TN && g.K <= 128 && g.N > 64) GP_BF16_LAUNCH(128, 128, 2, 2);

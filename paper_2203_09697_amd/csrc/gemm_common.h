@@ -83,7 +83,8 @@ __device__ __forceinline__ void epilogue_store(const gp_epilogue& e, int64_t row
 }
 
 // Same steps on 4 consecutive columns (col % 4 == 0, all pointers 16-byte aligned, n % 4 == 0).
-__device__ __forceinline__ void epilogue_store4(const gp_epilogue& e, int64_t row, int col, int n, f32x4 v) {
+// mulv: the low-rank factor's four values, where the kernel evaluates one
+__device__ __forceinline__ void epilogue_store4(const gp_epilogue& e, int64_t row, int col, int n, f32x4 v, const f32x4* mulv = nullptr) {
   const int64_t o = row * n + col;
   const unsigned b = e.bf16;
   if (e.bias) v += ld4(e.bias + col);
@@ -98,6 +99,7 @@ __device__ __forceinline__ void epilogue_store4(const gp_epilogue& e, int64_t ro
     for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
   }
   if (e.mul) v *= ldx4(e.mul, o, b & EPI_BF_MUL);
+  if (mulv) v *= *mulv;
   if (e.add_post) v += ldx4(e.add_post, o, b & EPI_BF_ADD_POST);
   v *= e.scale;
   if (e.out) stx4(e.out, o, b & EPI_BF_OUT, v);
