@@ -858,11 +858,30 @@ gemm_dl_kernel(const gemm_args g) {
     }
     wait_vmcnt_lgkmcnt0<(STAGES - 2) * PER>();
     __syncthreads();
-    issue(t + STAGES, st);
     read_frags(st1, 0);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_group(KS - 1);
-    __builtin_amdgcn_sched_barrier(0);
+    {
+      // The refill of the stage just freed goes out one load behind each MFMA of the slab's last group: issued in a
+      // block right after the barrier, the loads held every wavefront's first MFMA back by their own issue time.
+      const int slab = t + STAGES;
+      const int sl = slab < n_slabs ? slab : n_slabs - 1;   // past the end: re-read the last slab
+      const bool second = sl >= n1;
+      const int64_t kb = (int64_t)(second ? sl - n1 : sl) * ROWB;
+      char* dst = lds + st * STAGE_B + wave * PER * 1024;
+      static_assert(PER <= MB * NB, "one load per MFMA of a group");
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KS - 1) & 1][i], fb[(KS - 1) & 1][j], acc[i][j], 0, 0, 0);
+          const int q = i * NB + j;
+          if (q < PER) {
+            const int64_t d2 = second ? (wave * PER + q < A_LOADS ? dA : dB) : 0;   // uniform
+            __builtin_amdgcn_global_load_lds((global_void_ptr)(src[q] + kb + d2), (lds_void_ptr)(dst + q * 1024), 16, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+    }
     st = st1;
   }
   wait_vmcnt_lgkmcnt0<0>();                    // the loads issued past the end must not land in the epilogue's staging area
