@@ -473,7 +473,7 @@ int gp_triplet_bilinear_bwd_H(gp_ctx* ctx, const gp_graph* graph, int32_t form, 
                               const float* cos_alpha_kj, const float* dz, float* H, void* ws, size_t ws_bytes);
 int gp_triplet_bilinear_grad_cos(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t width,
                                  const float* cos_alpha_kj, const float* U, const float* dz, int32_t accumulate,
-                                 float* grad_cos_kj);
+                                 float* grad_cos_kj, void* ws, size_t ws_bytes);
 
 /* Dense layer on its own: out = act(x @ W + b), fp32 MFMA.  act: 0 none, 1 SiLU.
  * x[rows,k], W[k,n], b[n] or NULL, out[rows,n]. */

@@ -466,13 +466,14 @@ def gp_triplet_bilinear_bwd_H(ctx, trip, form, S, cos_alpha_kj, dz, ws=None):
     return H
 
 
-def gp_triplet_bilinear_grad_cos(ctx, trip, form, S, cos_alpha_kj, U, dz, grad_cos_kj=None):
+def gp_triplet_bilinear_grad_cos(ctx, trip, form, S, cos_alpha_kj, U, dz, grad_cos_kj=None, ws=None):
     """grad_cos_kj [T] (kj-major); added to the given tensor, else a new one is written."""
     g = Graph(trip)
     acc = grad_cos_kj is not None
     out = grad_cos_kj if acc else torch.empty(trip["n_triplets"], dtype=torch.float32, device=ctx.device)
     ctx.check(load().gp_triplet_bilinear_grad_cos(ctx._h, C.byref(g), C.c_int32(form), C.c_int32(S), C.c_int32(dz.shape[1]),
-                                                  _ptr(cos_alpha_kj), _ptr(U), _ptr(dz), C.c_int32(1 if acc else 0), _ptr(out)))
+                                                  _ptr(cos_alpha_kj), _ptr(U), _ptr(dz), C.c_int32(1 if acc else 0), _ptr(out),
+                                                  _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0)))
     return out
 
 

@@ -93,7 +93,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t N, int64_t E, int64_t 
   s->V = c.take<float>(E * C * O);
   s->dRad = c.take<float>(E * S * C);
   s->dzdn = c.take<float>(E * F);
-  s->U = c.take<float>(E * S * O);
+  s->U = c.take<float>(E * std::max<size_t>(S, 4) * O);   // fp32 [E, S, O], or bf16 [E, 8, O] for the one-pass grad-cos kernel
   s->WbilP = c.take<float>(C * O * F);
   s->WbilV = c.take<float>(F * C * O);
   s->dWrbf = c.take<float>(R * H);
@@ -103,7 +103,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t N, int64_t E, int64_t 
   s->part_aux = (float*)c.take<char>(s->part_bytes);
   // scratch of the matrix-core triplet kernels: the per-triplet y buffer of the two-kernel form, or the per-atom
   // operand tables of the fused form (N > 0: the graph carries its lists by centre atom)
-  s->ybytes = d->dtype == GP_BF16_F32ACC ? std::max(gp_tripG_mfma_scratch(E, T), N > 0 ? std::max(gp_tripG_fused_scratch(N, E, std::max(d->int_emb, d->emb_bil)), gp_tripG_H_fused_scratch(N, E, std::max(d->int_emb, d->emb_bil))) : (size_t)0) : 0;
+  s->ybytes = d->dtype == GP_BF16_F32ACC ? std::max(gp_tripG_mfma_scratch(E, T), N > 0 ? std::max({gp_tripG_fused_scratch(N, E, std::max(d->int_emb, d->emb_bil)), gp_tripG_H_fused_scratch(N, E, std::max(d->int_emb, d->emb_bil)), gp_tripG_dcos_fused_scratch(N, E, d->emb_bil, 0)}) : (size_t)0) : 0;
   s->ybuf = c.take<char>(s->ybytes);
   const bool rt = d->radial_at_target != 0;
   s->dA = c.take<float>(rt ? E * C * F : 0);
@@ -750,8 +750,13 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(gp_gemm_nn(ctx, s.x, sc.WbilV, E, C * O, F, e));                           // V[e', (c,o)]
   GP_TRY(gp_tripG_edge_dRad(ctx, sc.V, sc.Hd, E, S, C, O, sc.dRad, vh));            // dRad[e', (l,c)]
   if (grad_cos_kj && graph->n_triplets > 0) {
-    GP_TRY(gp_tripG_edge_U(ctx, s.Radt, sc.V, E, S, C, O, sc.U, vh));
-    if (bwd_mfma)
+    const bool dcos_fused = bwd_mfma && ctx->trip_mfma != 2 && gp_tripG_H_fused_usable(graph, O, S) &&
+                            sc.ybytes >= gp_tripG_dcos_fused_scratch(graph->n_atoms, E, O, 0);
+    GP_TRY(gp_tripG_edge_U(ctx, s.Radt, sc.V, E, S, C, O, sc.U, vh, dcos_fused));
+    if (dcos_fused)
+      GP_TRY(gp_tripG_grad_cos_fused(ctx, graph, basis->cos_alpha_kj, sc.U, 1, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj,
+                                     sc.ybuf, sc.ybytes));
+    else if (bwd_mfma)
       GP_TRY(gp_tripG_grad_cos_mfma(ctx, graph, basis->cos_alpha_kj, sc.U, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj));
     else
       GP_TRY(gp_tripG_grad_cos(ctx, graph, basis->cos_alpha_kj, sc.U, sc.dz, O, S, accumulate_basis_grads, grad_cos_kj));

@@ -64,7 +64,9 @@ int gp_permute3(gp_ctx* ctx, const float* src, int n0, int n1, int n2, int p0, i
 // d1 = g * s * silu'(z1), d2 = g * s * silu'(z2)
 int gp_ew_dsilu2(gp_ctx* ctx, const float* g, float s, const float* z1, const float* z2, float* d1, float* d2, int64_t n);
 // U[e, l, o] = sum_c Radt[(l*C+c)*E + e] * V[e, c*O + o]
-int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, int S, int C, int O, float* U, int v_half = 0);
+// out16: U is written as bf16 [E][8][O] (rows l >= S zero) instead of fp32 [E][S][O]
+int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, int S, int C, int O, float* U, int v_half = 0,
+                    int out16 = 0);
 // grad_cos_kj[q] (+)= sum_l Y_l0'(cos_alpha_kj[q]) sum_o dz[ji(q), o] U[kj(q), l, o]   (kj-major order)
 int gp_tripG_grad_cos(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* U, const float* dz,
                       int O, int S, int accumulate, float* grad_cos_kj);
@@ -90,6 +92,11 @@ bool gp_tripG_H_fused_usable(const gp_graph* g, int O, int S);
 size_t gp_tripG_H_fused_scratch(int64_t N, int64_t E, int O);
 int gp_tripG_backward_H_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S, float* H,
                               void* ws, size_t ws_bytes, const int32_t* row_list = nullptr);
+// grad_cos_kj in the same per-(atom, 32 rows) decomposition, wavefronts working alone without LDS.  U: bf16 [E][8][O]
+// (u_is_bf16_padded, as gp_tripG_edge_U writes it with out16) or fp32 [E][S][O] (converted into the workspace first).
+size_t gp_tripG_dcos_fused_scratch(int64_t N, int64_t E, int O, int with_u16);
+int gp_tripG_grad_cos_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const void* U, int u_is_bf16_padded,
+                            const float* dz, int O, int S, int accumulate, float* grad_cos_kj, void* ws, size_t ws_bytes);
 // rad_by_pos: Radt's columns are in row_list order already (gathered by the caller)
 // row_list: edge ids of the atoms' rows where these are not consecutive (the mirrored views of a block with the
 // radial factor at the target edge: g->row_ptr then indexes row_list, and g->out_list holds consecutive ids)

@@ -22,6 +22,7 @@ int gp_triplet_workspace(const gp_graph* graph, int32_t width, size_t* bytes) {
     b = std::max(b, gp_tripG_fused_scratch(graph->n_atoms, graph->n_edges, width));
     b = std::max(b, gp_tripG_H_fused_scratch(graph->n_atoms, graph->n_edges, width));
     b = std::max(b, gp_tripD_mfma_bwd_scratch(graph, width));
+    b = std::max(b, gp_tripG_dcos_fused_scratch(graph->n_atoms, graph->n_edges, width, 1));
   }
   *bytes = b;
   return GP_OK;
@@ -124,7 +125,7 @@ int gp_triplet_bilinear_bwd_H(gp_ctx* ctx, const gp_graph* graph, int32_t form, 
 
 int gp_triplet_bilinear_grad_cos(gp_ctx* ctx, const gp_graph* graph, int32_t form, int32_t num_spherical, int32_t width,
                                  const float* cos_alpha_kj, const float* U, const float* dz, int32_t accumulate,
-                                 float* grad_cos_kj) {
+                                 float* grad_cos_kj, void* ws, size_t ws_bytes) {
   if (!ctx) return GP_BAD_ARG;
   GP_REQUIRE(ctx, graph && U && dz && (graph->n_triplets == 0 || (cos_alpha_kj && grad_cos_kj)), "gp_triplet_bilinear_grad_cos: NULL pointer");
   GP_HIP(ctx, hipSetDevice(ctx->device));
@@ -137,6 +138,11 @@ int gp_triplet_bilinear_grad_cos(gp_ctx* ctx, const gp_graph* graph, int32_t for
                      "32, the kj-major view and at least one triplet (got %d)", width);
     GP_TRY(gp_take_deferred(ctx, "gp_triplet_bilinear_grad_cos"));
     GP_TRY(gp_check_degrees(ctx, graph));
+    // the one-pass kernel where its widths allow and a workspace is given, else the kernel that keeps all of an atom's
+    // out-edges in LDS
+    if (ws && gp_tripG_H_fused_usable(graph, width, num_spherical) &&
+        ws_bytes >= gp_tripG_dcos_fused_scratch(graph->n_atoms, graph->n_edges, width, 1))
+      return gp_tripG_grad_cos_fused(ctx, graph, cos_alpha_kj, U, 0, dz, width, num_spherical, accumulate, grad_cos_kj, ws, ws_bytes);
     return gp_tripG_grad_cos_mfma(ctx, graph, cos_alpha_kj, U, dz, width, num_spherical, accumulate, grad_cos_kj);
   }
   return gp_fail(ctx, GP_BAD_ARG, "gp_triplet_bilinear_grad_cos: unknown form %d", form);

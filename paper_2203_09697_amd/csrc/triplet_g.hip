@@ -63,7 +63,8 @@ __device__ __forceinline__ void stage_radial_slice(const float* __restrict__ Rad
 }
 
 // VT: storage type of V (fp32, or bf16 as written by the epilogue of the GEMM that produces it)
-template <class VT>
+// OUT16: U is written as bf16 [E][8][O] (rows l >= S zero), the operand layout of the one-pass grad-cos kernel
+template <class VT, bool OUT16>
 __global__ void __launch_bounds__(WPB* 64)
 edge_U_kernel(const float* __restrict__ Radt, const VT* __restrict__ V, int64_t E, int S, int C, int O,
               float* __restrict__ U) {
@@ -100,9 +101,16 @@ edge_U_kernel(const float* __restrict__ Radt, const VT* __restrict__ V, int64_t 
             for (int l = 0; l < ST; ++l)
               if (l < S) acc[l] += rad_s[(l * C + c) * EU_EDGES + el] * vc;
           }
+        if constexpr (OUT16) {
+          static_assert(ST == 8, "eight rows per edge");
+          __bf16* U16 = reinterpret_cast<__bf16*>(U);
 #pragma unroll
-        for (int l = 0; l < ST; ++l)
-          if (l < S) U[(e * S + l) * O + o] = acc[l];
+          for (int l = 0; l < ST; ++l) U16[(e * 8 + l) * O + o] = (__bf16)acc[l];
+        } else {
+#pragma unroll
+          for (int l = 0; l < ST; ++l)
+            if (l < S) U[(e * S + l) * O + o] = acc[l];
+        }
       }
     }
   }
@@ -165,14 +173,17 @@ trip_dcos_kernel(const int32_t* __restrict__ seg_kj, const int32_t* __restrict__
 
 }  // namespace
 
-int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, int S, int C, int O, float* U, int v_half) {
+int gp_tripG_edge_U(gp_ctx* ctx, const float* Radt, const float* V, int64_t E, int S, int C, int O, float* U, int v_half, int out16) {
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, Radt && V && U && S >= 1 && S <= ST && C >= 1 && C <= EU_CMAX && O >= 1, "edge_U: bad arguments");
   gp_prof_scope prof(ctx, "tripG_edge_U", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O) + (v_half ? 2.0 : 4.0) * E * C * O);
   const unsigned blocks = (unsigned)((E + EU_EDGES - 1) / EU_EDGES);
   const size_t lds = (size_t)S * C * EU_EDGES * sizeof(float);
-  if (v_half) edge_U_kernel<__bf16><<<blocks, WPB * 64, lds, ctx->stream>>>(Radt, reinterpret_cast<const __bf16*>(V), E, S, C, O, U);
-  else edge_U_kernel<float><<<blocks, WPB * 64, lds, ctx->stream>>>(Radt, V, E, S, C, O, U);
+  if (out16) {
+    if (v_half) edge_U_kernel<__bf16, true><<<blocks, WPB * 64, lds, ctx->stream>>>(Radt, reinterpret_cast<const __bf16*>(V), E, S, C, O, U);
+    else edge_U_kernel<float, true><<<blocks, WPB * 64, lds, ctx->stream>>>(Radt, V, E, S, C, O, U);
+  } else if (v_half) edge_U_kernel<__bf16, false><<<blocks, WPB * 64, lds, ctx->stream>>>(Radt, reinterpret_cast<const __bf16*>(V), E, S, C, O, U);
+  else edge_U_kernel<float, false><<<blocks, WPB * 64, lds, ctx->stream>>>(Radt, V, E, S, C, O, U);
   GP_LAUNCH_CHECK(ctx, "edge_U_kernel");
   return GP_OK;
 }

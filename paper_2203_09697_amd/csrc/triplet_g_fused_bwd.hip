@@ -255,6 +255,184 @@ tripG_H_fused_kernel(const float* __restrict__ cos_kj, int64_t T, const __bf16* 
   }
 }
 
+// ---- grad cos alpha in the same per-(atom, 32 rows) decomposition:
+//
+//   grad_cos[t = (e', e)] (+)= sum_l Y_l0'(cos alpha_t) W[(e', l), n(e)],   W = U_j dz_out^T  (contraction over o)
+//
+// Every wavefront works alone on 8 in-edge rows of the item (two 32x32x16 products of (4 rows x 8 l) by 32 out-list
+// positions per step); nothing is staged in LDS: the operand fragments of its rows (U, bf16, [edge][8][O]) stay in
+// registers for the whole item, those of the out-edges come per step from a bf16 copy of dz in out-list order (rows
+// of one atom: read by all wavefronts that work on it, hence from the caches), the cosines and the values to add to
+// are read, and the results written, in runs of 32 consecutive triplets.  No LDS and about 130 registers let a dozen
+// wavefronts per compute unit hide the latency of those loads; the kernel that keeps an atom's out-edges in LDS runs
+// four.
+__global__ void __launch_bounds__(256)
+dcos_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
+                 const int32_t* __restrict__ seg_ptr_kj, const int32_t* __restrict__ idx_ji_kj, const float* __restrict__ dz,
+                 int O, __bf16* __restrict__ dzr, int32_t* __restrict__ row_info) {
+  const int j = blockIdx.x;
+  const int ob = out_ptr[j], dout = out_ptr[j + 1] - ob;
+  const int n0 = ROWPAD * (int)blockIdx.y;
+  const int32_t* outs = out_list + ob;
+  if (blockIdx.y == 0) {
+    const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
+    for (int p = threadIdx.x; p < d; p += 256) {
+      const int seg = seg_ptr_kj[r0 + p], cnt = seg_ptr_kj[r0 + p + 1] - seg;
+      row_info[2 * (int64_t)(r0 + p)] = seg;
+      row_info[2 * (int64_t)(r0 + p) + 1] = first_mismatch(idx_ji_kj + seg, cnt, [=](int slot) { return outs[slot]; });
+    }
+  }
+  if (n0 >= ((dout + ROWPAD - 1) & ~(ROWPAD - 1))) return;
+  const int64_t base = padded_base(ob, j) + n0;
+  const int ch = O / 8;
+  for (int it = threadIdx.x; it < ROWPAD * ch; it += 256) {
+    const int n = n0 + it / ch, oc = (it % ch) * 8;
+    const bool ok = n < dout;
+    const float* src = dz + (int64_t)outs[ok ? n : 0] * O + oc;   // clamped position times a 0/1 factor: unconditional loads
+    const f32x4 v0 = *reinterpret_cast<const f32x4*>(src) * (ok ? 1.f : 0.f);
+    const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 4) * (ok ? 1.f : 0.f);
+    bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = (__bf16)v0[i], v[4 + i] = (__bf16)v1[i];
+    *reinterpret_cast<bf16x8*>(dzr + (base + it / ch) * O + oc) = v;
+  }
+}
+
+// U[e, l, o] fp32 ([E, S, O]) -> bf16 [E][8][O], rows l >= S zero
+__global__ void u16_kernel(const float* __restrict__ U, int64_t E, int S, int O, __bf16* __restrict__ U16) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (e, l, o / 4)
+  const int q = O / 4;
+  if (i >= E * 8 * q) return;
+  const int64_t e = i / (8 * q);
+  const int l = (int)(i / q) & 7, o = (int)(i % q) * 4;
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  bf16x4 v = {(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+  if (l < S) {
+    const f32x4 u = *reinterpret_cast<const f32x4*>(U + (e * S + l) * O + o);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] = (__bf16)u[c];
+  }
+  *reinterpret_cast<bf16x4*>(U16 + (e * 8 + l) * O + o) = v;
+}
+
+template <int KS>   // O = 16 KS (KS = 2, 4, 8)
+__global__ void __launch_bounds__(256, KS == 8 ? 2 : 3)
+tripG_dcos_fused_kernel(const float* __restrict__ cos_kj, int64_t T, const __bf16* __restrict__ U16, const __bf16* __restrict__ dzr,
+                        const int32_t* __restrict__ row_info, const int32_t* __restrict__ n_items, const int32_t* __restrict__ item,
+                        int S, int accumulate, float* __restrict__ grad_cos_kj) {
+  constexpr int O = 16 * KS;
+  const int total = n_items[0];
+  const int q8 = total >> 3, r8 = total & 7, xcd = (int)blockIdx.x & 7, ith = (int)blockIdx.x >> 3;
+  if (ith >= q8 + (xcd < r8 ? 1 : 0)) return;
+  const int w = xcd * q8 + (xcd < r8 ? xcd : r8) + ith;
+  const int4 it = *reinterpret_cast<const int4*>(item + 4 * (int64_t)w);
+  const int64_t base = it.x;
+  const int dout = it.y, e0 = it.z, n_rows = it.w;
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (8 * wv >= n_rows) return;          // wavefronts are independent: no barrier below
+  const int kh = lane >> 5, l32 = lane & 31;
+
+  // operand fragments of the wavefront's rows: MFMA row l32 = (row pl = l32 / 8 of the fragment, l = l32 % 8)
+  bf16x8 a[2][KS];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    const int p = 8 * wv + 4 * rt + (l32 >> 3);
+    const __bf16* src = U16 + ((int64_t)(e0 + (p < n_rows ? p : n_rows - 1)) * 8 + (l32 & 7)) * O + 8 * kh;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) a[rt][ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+  }
+  // segment start and left-out position of the 8 rows (uniform: scalar registers); rows past the group's end repeat
+  // its last row and are never stored
+  int seg[8], gap[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int p = 8 * wv + r;
+    const int64_t e = e0 + (p < n_rows ? p : n_rows - 1);
+    seg[r] = row_info[2 * e];
+    gap[r] = p < n_rows ? row_info[2 * e + 1] : -1 - dout;   // a row past the end: no position is valid (see `valid`)
+  }
+  // Y_l0'(x) for this lane's four l = 4 kh + i as polynomials in x^2 (times x for even l): from
+  // P_l = x^(l%2) sum_c q_c x^(2c), P_l' = sum_c (2c + l%2) q_c x^(2c + l%2 - 1)
+  float dq[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int lq = 4 * kh + i;
+    const float nrm = lq < S ? Y_NORM_M[lq] : 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (i & 1) dq[i][c] = nrm * (float)(2 * c + 1) * LEG_EO[lq][c];
+      else dq[i][c] = c < 3 ? nrm * (float)(2 * c + 2) * LEG_EO[lq][c + 1] : 0.f;
+    }
+  }
+
+  const int n_slab = (dout + 31) >> 5;
+  // position n of the out-list is slot n, or n - 1 behind the left-out position, of row r's segment
+  auto fetch = [&](int nb, bf16x8 (&b)[KS], float (&xs)[8], float (&old)[8]) __attribute__((always_inline)) {
+    const int n = nb * 32 + l32;
+    const __bf16* src = dzr + (base + n) * O + 8 * kh;   // rows up to the next multiple of 64 exist and are zero
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) b[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const bool valid = n < dout && n != gap[r] && gap[r] >= 0;
+      const int64_t at = valid ? (int64_t)seg[r] + n - (n > gap[r] ? 1 : 0) : 0;   // unconditional loads, index 0 when unused
+      xs[r] = cos_kj[at];
+      old[r] = accumulate ? grad_cos_kj[at] : 0.f;
+    }
+  };
+  bf16x8 b_n[KS];
+  float xs_n[8], old_n[8];
+  fetch(0, b_n, xs_n, old_n);
+  for (int nb = 0; nb < n_slab; ++nb) {
+    bf16x8 b[KS];
+    float xs[8], old[8];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) b[ks] = b_n[ks];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) xs[r] = xs_n[r], old[r] = old_n[r];
+    if (nb + 1 < n_slab) fetch(nb + 1, b_n, xs_n, old_n);
+    const int n = nb * 32 + l32;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      f32x16 acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks], b[ks], acc, 0, 0, 0);
+      // accumulator register 4 pl + i of lane (kh, n): row pl of the fragment, l = 4 kh + i
+#pragma unroll
+      for (int pl = 0; pl < 4; ++pl) {
+        const int r = 4 * rt + pl;
+        const float x = xs[r], t2 = x * x;
+        float part = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float wgt = dq[i][0] + t2 * (dq[i][1] + t2 * (dq[i][2] + t2 * dq[i][3]));
+          part += acc[4 * pl + i] * ((i & 1) ? wgt : x * wgt);   // l even: odd derivative
+        }
+        const float tot = part + __shfl_xor(part, 32, 64);
+        const bool valid = n < dout && n != gap[r] && gap[r] >= 0;
+        if (valid && kh == (pl >> 1)) grad_cos_kj[(int64_t)seg[r] + n - (n > gap[r] ? 1 : 0)] = old[r] + tot;
+      }
+    }
+  }
+}
+
+struct dcos_ws {
+  __bf16 *dzr, *u16;
+  int32_t *row_info, *n_items, *item;
+};
+size_t carve_dcos(void* p, int64_t N, int64_t E, int O, bool with_u16, dcos_ws* w) {
+  gp_carver c(p);
+  w->dzr = c.take<__bf16>((size_t)padded_rows(E, N) * O);
+  w->u16 = c.take<__bf16>(with_u16 ? (size_t)E * 8 * O : 0);
+  w->row_info = c.take<int32_t>(2 * (size_t)E);
+  w->n_items = c.take<int32_t>(4);
+  w->item = c.take<int32_t>(4 * (size_t)(E / HR + N + 1));
+  return c.off;
+}
+
 struct fusedH_ws {
   __bf16* dzb;
   int32_t *row_info, *n_items, *item;
@@ -307,5 +485,42 @@ int gp_tripG_backward_H_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_a
   else GP_H_LAUNCH(2);
 #undef GP_H_LAUNCH
   GP_LAUNCH_CHECK(ctx, "tripG_H_fused_kernel");
+  return GP_OK;
+}
+
+size_t gp_tripG_dcos_fused_scratch(int64_t N, int64_t E, int O, int with_u16) {
+  dcos_ws w;
+  return carve_dcos(nullptr, N, E, O, with_u16 != 0, &w);
+}
+
+int gp_tripG_grad_cos_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const void* U, int u_is_bf16_padded,
+                            const float* dz, int O, int S, int accumulate, float* grad_cos_kj, void* ws, size_t ws_bytes) {
+  const int64_t E = g->n_edges, T = g->n_triplets, N = g->n_atoms;
+  if (E == 0 || T == 0) return GP_OK;
+  GP_REQUIRE(ctx, gp_tripG_H_fused_usable(g, O, S), "grad_cos (one-pass matrix-core form): graph lists or widths not supported");
+  GP_REQUIRE(ctx, cos_alpha_kj && U && dz && grad_cos_kj && ws, "grad_cos: NULL pointer");
+  dcos_ws w;
+  if (ws_bytes < carve_dcos(ws, N, E, O, !u_is_bf16_padded, &w)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "grad_cos: workspace too small");
+  hipStream_t st = ctx->stream;
+  const __bf16* U16 = reinterpret_cast<const __bf16*>(U);
+  {
+    gp_prof_scope prof(ctx, "tripG_dcos_pack", 0.0, (double)E * (4.0 * O + 2.0 * O + 16.0));
+    if (!u_is_bf16_padded) {
+      const int64_t n = E * 8 * (O / 4);
+      u16_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(reinterpret_cast<const float*>(U), E, S, O, w.u16);
+      GP_LAUNCH_CHECK(ctx, "u16_kernel");
+      U16 = w.u16;
+    }
+    fusedH_items_kernel<<<1, 1024, 0, st>>>(g->row_ptr, g->out_ptr, (int)N, w.n_items, w.item);
+    const dim3 grid((unsigned)N, (unsigned)((g->max_out_degree + ROWPAD - 1) / ROWPAD));
+    dcos_pack_kernel<<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_kj, g->idx_ji_kj, dz, O, w.dzr, w.row_info);
+    GP_LAUNCH_CHECK(ctx, "dcos_pack_kernel");
+  }
+  gp_prof_scope prof(ctx, "tripG_dcos_fused", (double)T * 2.0 * 8 * O, (double)T * (accumulate ? 12.0 : 8.0) + (double)E * (2.0 * O + 16.0 * O));
+  const unsigned grid = (unsigned)(E / HR + N);   // an upper bound of the number of work items; the rest exit at once
+  if (O == 128) tripG_dcos_fused_kernel<8><<<grid, 256, 0, st>>>(cos_alpha_kj, T, U16, w.dzr, w.row_info, w.n_items, w.item, S, accumulate, grad_cos_kj);
+  else if (O == 64) tripG_dcos_fused_kernel<4><<<grid, 256, 0, st>>>(cos_alpha_kj, T, U16, w.dzr, w.row_info, w.n_items, w.item, S, accumulate, grad_cos_kj);
+  else tripG_dcos_fused_kernel<2><<<grid, 256, 0, st>>>(cos_alpha_kj, T, U16, w.dzr, w.row_info, w.n_items, w.item, S, accumulate, grad_cos_kj);
+  GP_LAUNCH_CHECK(ctx, "tripG_dcos_fused_kernel");
   return GP_OK;
 }

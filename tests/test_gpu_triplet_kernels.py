@@ -114,8 +114,9 @@ def test_bilinear_backward_H_and_grad_cos(lib, ctx, graph, form, O, tol, with_ws
     dzd = H.to_dev(dz, torch.float32)
     ws = lib.gp_triplet_workspace(ctx, t, O) if with_ws else None   # with it the per-atom form is the one-pass kernel
     Hg = lib.gp_triplet_bilinear_bwd_H(ctx, t, form, S, graph["cos_kj_d"], dzd, ws)
-    gc = lib.gp_triplet_bilinear_grad_cos(ctx, t, form, S, graph["cos_kj_d"], H.to_dev(U, torch.float32), dzd)
-    gc2 = lib.gp_triplet_bilinear_grad_cos(ctx, t, form, S, graph["cos_kj_d"], H.to_dev(U, torch.float32), dzd, grad_cos_kj=gc.clone())
+    gc = lib.gp_triplet_bilinear_grad_cos(ctx, t, form, S, graph["cos_kj_d"], H.to_dev(U, torch.float32), dzd, ws=ws)
+    gc2 = lib.gp_triplet_bilinear_grad_cos(ctx, t, form, S, graph["cos_kj_d"], H.to_dev(U, torch.float32), dzd, grad_cos_kj=gc.clone(),
+                                           ws=ws)
     torch.cuda.synchronize()
     lib.gp_deferred_status(ctx)
     _check({"H": (Hg.reshape(E * S, O), H_ref.reshape(E * S, O)), "grad_cos_kj": (gc, gc_ref.numpy()[order]),
