@@ -522,7 +522,9 @@ int gp_gemm_nt2(gp_ctx* ctx, const float* A, const float* Bt, const float* A2, c
 
 size_t gp_gemm_tn_scratch(int64_t rows, int M, int N) {
   tn_plan_t p = tn_plan(rows, M, N);
-  return gp_align((size_t)p.splits * M * N * sizeof(float)) + gp_align((size_t)p.splits * p.tiles_m * N * sizeof(float));
+  const size_t a = gp_align((size_t)p.splits * M * N * sizeof(float)) + gp_align((size_t)p.splits * p.tiles_m * N * sizeof(float));
+  const size_t b = gp_align((size_t)gp_gemm_bf16_tn_dl_splits(rows, M, N) * M * N * sizeof(float));   // the bf16 kernel with its own plan
+  return a > b ? a : b;
 }
 
 int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M, int N, float* out,
@@ -548,6 +550,13 @@ int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M,
   g.k_per_split = p.per;
   g.part = part;
   g.vecC = (N % 4 == 0) && aligned16(part) && ((size_t)M * N % 4 == 0);
+  if (ctx->gemm_bf16 && !colsum_out) {
+    const int s_dl = gp_gemm_bf16_tn_dl_splits(rows, M, N);
+    if (s_dl > 0 && gp_gemm_bf16_tn_dl_ok(&g)) {
+      GP_TRY(gp_gemm_bf16_tn_dl(ctx, &g, s_dl));
+      return launch_reduce(ctx, part, s_dl, (int64_t)M * N, out, nullptr, 0, 0, nullptr);
+    }
+  }
   float* cpart = (float*)((char*)part + gp_align((size_t)p.splits * M * N * sizeof(float)));
   g.colsum_part = colsum_out ? cpart : nullptr;
   GP_TRY(dispatch_gemm<MODE_TN>(ctx, g, p.splits));

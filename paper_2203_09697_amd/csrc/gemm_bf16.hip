@@ -916,6 +916,207 @@ int launch_dl(gp_ctx* ctx, gemm_args& g) {
   return GP_OK;
 }
 
+// ---- C = A^T B with both operands stored as bf16, [rows, M] and [rows, N], the contraction running over the rows (the
+// weight gradients of the wide layers: rows = edges).  Both operands have the contraction index as their slow one, so
+// a global->LDS load brings whole 512-byte row pieces [k][x] and the MFMA operand fragments (8 consecutive k for one
+// x per lane) are read with the LDS transpose loads of this target: within 16 lanes, lane i of ds_read_b64_tr_b16
+// receives element i % 4 of the 8 bytes addressed by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4 (checked on the
+// device).  With lane i addressing k-row i / 4, x-columns 4 (i % 4) .. + 3 of a 4 x 16 block, it receives 4 consecutive k
+// of column i.  No register staging, no repacking: the kernel that converts column pairs in registers spends as
+// many vector instructions on that as on the products.
+//
+// 256x256 tiles, 8 wavefronts of 128x64 as in gemm_dl_kernel; a slab is BK rows of both operands (BK KB), ring of
+// STAGES.  LDS: [k][32 chunks of 16 bytes], chunk c of row k at position c ^ 2 (k % 4): the four rows a transpose load
+// touches (32 bytes each) fall into four different quarters of the 128 bytes of banks.
+// Workgroup = (tile, split): the splits cut the rows into runs of whole slabs; partial sums go to part[split].
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
+
+template <int BK, int STAGES>
+__global__ void __launch_bounds__(512, 1)
+gemm_tn_dl_kernel(const gemm_args g, int slabs_per_split) {
+  constexpr int BM = 256, BN = 256, NW = 8, WAVES_N = 4, WM = 128, WN = 64, MB = 4, NB = 2;
+  constexpr int PART_B = BK * 512;                    // bytes of one operand's slab
+  constexpr int STAGE_B = 2 * PART_B;
+  constexpr int PER = STAGE_B / 1024 / NW;            // 16-byte loads per wavefront and slab (two rows each)
+  constexpr int KS = BK / 16;
+  static_assert(BK % 16 == 0 && PER >= 1 && PER <= MB * NB && PER * (STAGES - 1) < 64, "slab shape");
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  char* lds = reinterpret_cast<char*>(smem);
+
+  const int tiles_n = g.N / BN, tiles = (int)(g.M / BM) * tiles_n;
+  const int wg = xcd_remap(blockIdx.x, gridDim.x);    // the tiles of a split (same rows of both operands) share an XCD's L2
+  const int tile = wg % tiles, split = wg / tiles;
+  const int64_t m0 = (int64_t)(tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int64_t rows = g.K;
+  const int64_t k_begin = (int64_t)split * slabs_per_split * BK;
+  int64_t k_end = k_begin + (int64_t)slabs_per_split * BK;
+  if (k_end > rows) k_end = rows;
+  const int n_slabs = (int)((k_end - k_begin + BK - 1) / BK);   // >= 1: the host makes no empty split
+  const int rem = (int)(k_end - k_begin) - (n_slabs - 1) * BK;  // rows of the last slab
+
+  // this lane's source for each of the wavefront's loads (slab 0): wavefronts 0-3 bring A, 4-7 bring B
+  const bool is_a = wave < NW / 2;
+  const int64_t ld2 = (is_a ? g.lda : g.ldb) * 2;     // bytes per row
+  const char* src[PER];   // the lane's 16 bytes in slab 0
+  const char* lim[PER];   // the same columns in the matrix's last row: rows past it read that one (and are zeroed in LDS)
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    const int j = (wave & 3) * PER + q;               // pair of rows within the operand's slab
+    const int row = 2 * j + (lane >> 5), pos = lane & 31;
+    const int c = pos ^ (2 * (row & 3));
+    const char* col = is_a ? reinterpret_cast<const char*>(g.A) + (m0 + c * 8) * 2 : reinterpret_cast<const char*>(g.B) + ((int64_t)n0 + c * 8) * 2;
+    src[q] = col + (k_begin + row) * ld2;
+    lim[q] = col + (rows - 1) * ld2;
+  }
+  const int64_t slab_b = BK * ld2;
+  auto issue_one = [&](int slab, int stage, int q) __attribute__((always_inline)) {
+    const int sl = slab < n_slabs ? slab : n_slabs - 1;           // past the end: re-read the last slab
+    const char* p = src[q] + sl * slab_b;
+    p = p < lim[q] ? p : lim[q];
+    char* dst = lds + stage * STAGE_B + (is_a ? 0 : PART_B) + ((wave & 3) * PER + q) * 1024;
+    __builtin_amdgcn_global_load_lds((global_void_ptr)p, (lds_void_ptr)dst, 16, 0, 0);
+  };
+  // the last slab of the last split may be short: its missing rows are zeroed in LDS once it has landed
+  auto zero_tail = [&](int stage) __attribute__((always_inline)) {
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    for (int part = 0; part < 2; ++part) {
+      char* base = lds + stage * STAGE_B + part * PART_B + rem * 512;
+      for (int i = threadIdx.x; i < (BK - rem) * 32; i += 512) *reinterpret_cast<f32x4_t*>(base + i * 16) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+    __syncthreads();
+  };
+
+  f32x16 acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // transpose-load addresses: 16-lane block b = lane / 16 holds k-half kh = b / 2 and x-half b % 2 of a 32-wide MFMA
+  // block; its lane i addresses row 8 kh + 4 h + i / 4 (h = 0, 1: the two loads of a fragment), 8 bytes at x = 16 (b % 2) + 4 (i % 4)
+  const int b16 = lane >> 4, i16 = lane & 15;
+  const int kh = b16 >> 1;
+  const int krow = 8 * kh + (i16 >> 2);               // + 4 h + 16 ks
+  const int sw = 2 * (i16 >> 2);                      // 2 (row % 4): 4 h, 8 kh and 16 ks are multiples of 4
+  int a_off[MB], b_off[NB];                           // byte offset of the lane's 8 bytes within a row, swizzled
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+    const int c = (wm0 + 32 * i) / 8 + 2 * (b16 & 1) + ((i16 & 3) >> 1);
+    a_off[i] = ((c ^ sw) << 4) + ((i16 & 1) << 3);
+  }
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int c = (wn0 + 32 * j) / 8 + 2 * (b16 & 1) + ((i16 & 3) >> 1);
+    b_off[j] = PART_B + ((c ^ sw) << 4) + ((i16 & 1) << 3);
+  }
+  bf16x8 fa[2][MB], fb[2][NB];
+  auto read_frags = [&](int stage, int ks) __attribute__((always_inline)) {
+    const char* sb = lds + stage * STAGE_B + (16 * ks + krow) * 512;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(sb + a_off[i]));
+      const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(sb + 4 * 512 + a_off[i]));
+      typedef short v8s __attribute__((ext_vector_type(8)));
+      const v8s both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      fa[ks & 1][i] = __builtin_bit_cast(bf16x8, both);
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(sb + b_off[j]));
+      const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(sb + 4 * 512 + b_off[j]));
+      typedef short v8s __attribute__((ext_vector_type(8)));
+      const v8s both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      fb[ks & 1][j] = __builtin_bit_cast(bf16x8, both);
+    }
+  };
+  auto mfma_group = [&](int ks) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+  };
+
+#pragma unroll
+  for (int s = 0; s < STAGES; ++s)
+#pragma unroll
+    for (int q = 0; q < PER; ++q) issue_one(s, s, q);
+  wait_vmcnt_lgkmcnt0<(STAGES - 1) * PER>();   // slab 0 has landed (this wavefront's part)
+  __syncthreads();                             // ... and everybody else's
+  if (n_slabs == 1 && rem < BK) zero_tail(0);
+  read_frags(0, 0);
+  int st = 0;
+  for (int t = 0; t < n_slabs; ++t) {
+    const int st1 = st == STAGES - 1 ? 0 : st + 1;
+#pragma unroll
+    for (int ks = 0; ks + 1 < KS; ++ks) {
+      read_frags(st, ks + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(ks);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_vmcnt_lgkmcnt0<(STAGES - 2) * PER>();
+    __syncthreads();
+    if (t + 2 == n_slabs && rem < BK) zero_tail(st1);   // slab t + 1 is the short one (uniform)
+    read_frags(st1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    {
+      // the refill of the stage just freed, one load behind each MFMA of the slab's last group
+      int q = 0;
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KS - 1) & 1][i], fb[(KS - 1) & 1][j], acc[i][j], 0, 0, 0);
+          if (q < PER) issue_one(t + STAGES, st, q);
+          ++q;
+          __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    st = st1;
+  }
+  wait_vmcnt_lgkmcnt0<0>();                    // the loads issued past the end must not land in the epilogue's staging area
+  __syncthreads();
+  tile_epilogue<MB, NB, MODE_TN>(g, acc, smem, m0, n0, wm0, wn0, split);
+}
+
+// shapes the transposed global->LDS kernel takes: both operands bf16, widths multiples of 256, many rows
+bool tn_dl_shape(const gemm_args& g) {
+  return g.a_bf16 && g.b_bf16 && g.M % 256 == 0 && g.N % 256 == 0 && g.M <= 4096 && g.N <= 4096 && g.K >= 8192 && g.lda % 8 == 0 &&
+         g.ldb % 8 == 0 && (reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && g.vecC;
+}
+
+int launch_tn_dl(gp_ctx* ctx, gemm_args& g, int splits) {
+  constexpr int BK = 32, STAGES = 4;
+  const int tiles = (int)(g.M / 256) * (g.N / 256);
+  const int64_t slabs = ((int64_t)g.K + BK - 1) / BK;
+  const int per = (int)((slabs + splits - 1) / splits);
+  if ((int64_t)(splits - 1) * per >= slabs) return gp_fail(ctx, GP_BAD_ARG, "gemm_tn: empty split in the plan");
+  gp_prof_scope prof(ctx, "gemm_bf16_dl_tn_256x256", 2.0 * (double)g.M * g.N * g.K,
+                     2.0 * (double)g.K * (g.M + g.N) + 4.0 * (double)g.M * g.N * splits);
+  constexpr size_t lds_main = (size_t)STAGES * BK * 1024;
+  constexpr size_t lds_epi = sizeof(float) * 8 * 32 * EPI_LD;
+  constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+  static_assert(lds <= 160 * 1024, "fits the compute unit's LDS");
+  static bool raised = false;
+  if (!raised) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tn_dl_kernel<BK, STAGES>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+      return gp_fail(ctx, GP_HIP_ERROR, "gemm: cannot raise the dynamic LDS limit to %zu bytes", lds);
+    raised = true;
+  }
+  gemm_tn_dl_kernel<BK, STAGES><<<dim3((unsigned)(tiles * splits)), 512, lds, ctx->stream>>>(g, per);
+  GP_LAUNCH_CHECK(ctx, "gemm_tn_dl_kernel");
+  return GP_OK;
+}
+
 template <int BM, int BN, int WMS, int WNS, int MODE, bool VEC, bool ABF = false, bool BBF = false>
 int launch_v(gp_ctx* ctx, gemm_args& g, int splits) {
   const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
@@ -983,6 +1184,20 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
 }
 
 }  // namespace
+
+// The transposed global->LDS kernel: whether it takes the shape, how it splits the rows (about one workgroup per compute
+// unit: tiles x splits), and its launch.  gp_gemm_tn sizes its partial sums with the same plan.
+int gp_gemm_bf16_tn_dl_splits(int64_t rows, int M, int N) {
+  if (M % 256 || N % 256 || M > 4096 || N > 4096 || rows < 8192) return 0;
+  const int tiles = (M / 256) * (N / 256);
+  const int64_t slabs = (rows + 31) / 32;
+  int64_t s = tiles >= 256 ? 1 : 256 / tiles;
+  if (s > slabs) s = slabs;
+  const int64_t per = (slabs + s - 1) / s;
+  return (int)((slabs + per - 1) / per);
+}
+bool gp_gemm_bf16_tn_dl_ok(const void* args) { return tn_dl_shape(*static_cast<const gemm_args*>(args)); }
+int gp_gemm_bf16_tn_dl(gp_ctx* ctx, void* args, int splits) { return launch_tn_dl(ctx, *static_cast<gemm_args*>(args), splits); }
 
 // Called by gp_gemm_nn / gp_gemm_nt / gp_gemm_tn when the context asks for bf16 operands; `g` has
 // been filled exactly as for the fp32 kernels (same tile geometry, same split-K plan).
