@@ -926,7 +926,7 @@ int launch_dl(gp_ctx* ctx, gemm_args& g) {
 // many vector instructions on that as on the products.
 //
 // 256x256 tiles, 8 wavefronts of 128x64 as in gemm_dl_kernel; a slab is BK rows of both operands (BK KB), ring of
-// STAGES.  LDS: [k][32 chunks of 16 bytes], chunk c of row k at position c ^ 2 (k % 4): the four rows a transpose load
+// STAGES (64 rows, two stages).  LDS: [k][32 chunks of 16 bytes], chunk c of row k at position c ^ 2 (k % 4): the four rows a transpose load
 // touches (32 bytes each) fall into four different quarters of the 128 bytes of banks.
 // Workgroup = (tile, split): the splits cut the rows into runs of whole slabs; partial sums go to part[split].
 typedef short v4s __attribute__((ext_vector_type(4)));
@@ -1087,6 +1087,8 @@ gemm_tn_dl_kernel(const gemm_args g, int slabs_per_split) {
   tile_epilogue<MB, NB, MODE_TN>(g, acc, smem, m0, n0, wm0, wn0, split);
 }
 
+constexpr int TN_DL_BK = 64;   // rows per slab
+
 // shapes the transposed global->LDS kernel takes: both operands bf16, widths multiples of 256, many rows
 bool tn_dl_shape(const gemm_args& g) {
   return g.a_bf16 && g.b_bf16 && g.M % 256 == 0 && g.N % 256 == 0 && g.M <= 4096 && g.N <= 4096 && g.K >= 8192 && g.lda % 8 == 0 &&
@@ -1094,7 +1096,7 @@ bool tn_dl_shape(const gemm_args& g) {
 }
 
 int launch_tn_dl(gp_ctx* ctx, gemm_args& g, int splits) {
-  constexpr int BK = 32, STAGES = 4;
+  constexpr int BK = TN_DL_BK, STAGES = 2;   // 32-row slabs with a ring of 3, 4 or 5: 10 % slower (twice the barriers per MFMA)
   const int tiles = (int)(g.M / 256) * (g.N / 256);
   const int64_t slabs = ((int64_t)g.K + BK - 1) / BK;
   const int per = (int)((slabs + splits - 1) / splits);
@@ -1190,7 +1192,7 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
 int gp_gemm_bf16_tn_dl_splits(int64_t rows, int M, int N) {
   if (M % 256 || N % 256 || M > 4096 || N > 4096 || rows < 8192) return 0;
   const int tiles = (M / 256) * (N / 256);
-  const int64_t slabs = (rows + 31) / 32;
+  const int64_t slabs = (rows + TN_DL_BK - 1) / TN_DL_BK;
   int64_t s = tiles >= 256 ? 1 : 256 / tiles;
   if (s > slabs) s = slabs;
   const int64_t per = (slabs + s - 1) / s;
