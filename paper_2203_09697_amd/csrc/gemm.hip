@@ -468,6 +468,7 @@ int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, in
   g.vecB = b_bf16 ? (N % 2 == 0 && ((uintptr_t)B & 3) == 0) : (N % 4 == 0) && aligned16(B);
   g.epi = epi;
   g.vecC = epi_vec_ok(epi, N);
+  g.epi_kind = gp_epilogue_kind(g.epi, g.vecC);
   return dispatch_gemm<MODE_NN>(ctx, g, 1);
 }
 
@@ -484,6 +485,7 @@ int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, i
   g.vecB = (K % (b_bf16 ? 8 : 4) == 0) && aligned16(Bt);
   g.epi = epi;
   g.vecC = epi_vec_ok(epi, N);
+  g.epi_kind = gp_epilogue_kind(g.epi, g.vecC);
   return dispatch_gemm<MODE_NT>(ctx, g, 1);
 }
 
@@ -517,6 +519,7 @@ int gp_gemm_nt2(gp_ctx* ctx, const float* A, const float* Bt, const float* A2, c
   g.vecA = g.vecB = 1;
   g.epi = e;
   g.vecC = epi_vec_ok(e, N);
+  g.epi_kind = gp_epilogue_kind(g.epi, g.vecC);
   return dispatch_gemm<MODE_NT>(ctx, g, 1);
 }
 

@@ -347,73 +347,90 @@ struct bl_xcontig_bf {
 // through a per-wavefront LDS slice so that loads and stores are 16-byte accesses.
 // LR_WAVES > 0 (the number of wavefronts of the workgroup): the kernel can evaluate the epilogue's low-rank factor; its
 // 32x32 blocks go through a second staging slice per wavefront, behind the first ones.
-template <int MB, int NB, int MODE, int LR_WAVES = 0>
-__device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[MB][NB], float* smem, int64_t m0, int n0,
-                                              int wm0, int wn0, int split) {
+// The paired path for one combination of epilogue steps (KIND; EK_GENERIC tests the options per value).
+template <int MB, int NB, int LR_WAVES, int KIND>
+__device__ __forceinline__ void tile_epilogue_pairs(const gemm_args& g, f32x16 (&acc)[MB][NB], float* smem, int64_t m0, int n0,
+                                                    int wm0, int wn0) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kh = lane >> 5, l32 = lane & 31;
-  if constexpr (MODE != MODE_TN && NB % 2 == 0) {
-    // Two blocks side by side (32 rows x 64 columns): 16 lanes cover 64 consecutive columns of a row, so a store
-    // instruction writes whole 128-byte lines of a bf16 matrix (two per row of an fp32 one) instead of halves.
-    float* stage = smem + wave * (32 * EPI_LD2);
-    // Low-rank factor: operand fragments of the wavefront's rows and columns (k = 8 kh + c, zero from lr_k on), two
-    // MFMAs per block, in the accumulators' own register layout.  The row factor (an activation) enters as the sum of
-    // two bf16 numbers, i.e. to 16 bits: rounded to 8 bits, a model's energy turned out too rough a function of the
-    // positions for a finite difference of it to match its forces; the column factor is a weight like any other.
-    const bool lr = LR_WAVES > 0 && g.epi.lr_a != nullptr;
-    float* stage_lr = smem + (LR_WAVES + wave) * (32 * EPI_LD2);
-    bf16x8 ga[LR_WAVES > 0 ? MB : 1], ga_lo[LR_WAVES > 0 ? MB : 1], gb[LR_WAVES > 0 ? NB : 1];
-    if constexpr (LR_WAVES > 0) {
-      if (lr) {
-        const int kk = g.epi.lr_k;
+  // Two blocks side by side (32 rows x 64 columns): 16 lanes cover 64 consecutive columns of a row, so a store
+  // instruction writes whole 128-byte lines of a bf16 matrix (two per row of an fp32 one) instead of halves.
+  float* stage = smem + wave * (32 * EPI_LD2);
+  // Low-rank factor: operand fragments of the wavefront's rows and columns (k = 8 kh + c, zero from lr_k on), two
+  // MFMAs per block, in the accumulators' own register layout.  The row factor (an activation) enters as the sum of
+  // two bf16 numbers, i.e. to 16 bits: rounded to 8 bits, a model's energy turned out too rough a function of the
+  // positions for a finite difference of it to match its forces; the column factor is a weight like any other.
+  constexpr bool LR_POSSIBLE = LR_WAVES > 0 && (KIND == EK_GENERIC || KIND == EK_PRE_SILU_LR_BF16);
+  const bool lr = LR_POSSIBLE && g.epi.lr_a != nullptr;
+  float* stage_lr = smem + (LR_WAVES + wave) * (32 * EPI_LD2);
+  bf16x8 ga[LR_POSSIBLE ? MB : 1], ga_lo[LR_POSSIBLE ? MB : 1], gb[LR_POSSIBLE ? NB : 1];
+  if constexpr (LR_POSSIBLE) {
+    if (lr) {
+      const int kk = g.epi.lr_k;
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-          const int64_t row = m0 + wm0 + i * 32 + l32 < g.M ? m0 + wm0 + i * 32 + l32 : g.M - 1;
+      for (int i = 0; i < MB; ++i) {
+        const int64_t row = m0 + wm0 + i * 32 + l32 < g.M ? m0 + wm0 + i * 32 + l32 : g.M - 1;
 #pragma unroll
-          for (int c = 0; c < 8; ++c) {
-            const int k = 8 * kh + c;
-            const float a0 = g.epi.lr_a[row * kk + (k < kk ? k : kk - 1)];  // clamped: the load stays unconditional
-            const float a = k < kk ? a0 : 0.f;
-            ga[i][c] = (__bf16)a;
-            ga_lo[i][c] = (__bf16)(a - (float)ga[i][c]);
-          }
+        for (int c = 0; c < 8; ++c) {
+          const int k = 8 * kh + c;
+          const float a0 = g.epi.lr_a[row * kk + (k < kk ? k : kk - 1)];  // clamped: the load stays unconditional
+          const float a = k < kk ? a0 : 0.f;
+          ga[i][c] = (__bf16)a;
+          ga_lo[i][c] = (__bf16)(a - (float)ga[i][c]);
         }
+      }
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-          const int col = n0 + wn0 + j * 32 + l32 < g.N ? n0 + wn0 + j * 32 + l32 : g.N - 1;
+      for (int j = 0; j < NB; ++j) {
+        const int col = n0 + wn0 + j * 32 + l32 < g.N ? n0 + wn0 + j * 32 + l32 : g.N - 1;
 #pragma unroll
-          for (int c = 0; c < 8; ++c) {
-            const int k = 8 * kh + c;
-            const float b = g.epi.lr_b[(int64_t)(k < kk ? k : kk - 1) * g.N + col];
-            gb[j][c] = (__bf16)(k < kk ? b : 0.f);
-          }
+        for (int c = 0; c < 8; ++c) {
+          const int k = 8 * kh + c;
+          const float b = g.epi.lr_b[(int64_t)(k < kk ? k : kk - 1) * g.N + col];
+          gb[j][c] = (__bf16)(k < kk ? b : 0.f);
         }
       }
     }
+  }
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
+  for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int j = 0; j < NB; j += 2) {
+    for (int j = 0; j < NB; j += 2) {
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
+      for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-          for (int v = 0; v < 16; ++v)
-            stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD2 + jj * 32 + l32] = acc[i][j + jj][v];
-        if constexpr (LR_WAVES > 0) {
-          if (lr) {
+        for (int v = 0; v < 16; ++v)
+          stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD2 + jj * 32 + l32] = acc[i][j + jj][v];
+      if constexpr (LR_POSSIBLE) {
+        if (lr) {
 #pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-              f32x16 z;
+          for (int jj = 0; jj < 2; ++jj) {
+            f32x16 z;
 #pragma unroll
-              for (int v = 0; v < 16; ++v) z[v] = 0.f;
-              f32x16 f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga_lo[i], gb[j + jj], z, 0, 0, 0);
-              f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[i], gb[j + jj], f, 0, 0, 0);
+            for (int v = 0; v < 16; ++v) z[v] = 0.f;
+            f32x16 f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga_lo[i], gb[j + jj], z, 0, 0, 0);
+            f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[i], gb[j + jj], f, 0, 0, 0);
 #pragma unroll
-              for (int v = 0; v < 16; ++v) stage_lr[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD2 + jj * 32 + l32] = f[v];
-            }
+            for (int v = 0; v < 16; ++v) stage_lr[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD2 + jj * 32 + l32] = f[v];
           }
         }
-        wave_lds_sync();
+      }
+      wave_lds_sync();
+      // a block pair that lies inside the matrix takes the loop without bounds or option tests
+      const bool inside = m0 + wm0 + i * 32 + 32 <= g.M && n0 + wn0 + j * 32 + 64 <= g.N;
+      if (KIND != EK_GENERIC && inside) {
+        if constexpr (KIND != EK_GENERIC) {
+          const int c4 = (lane & 15) * 4;
+          const int64_t o0 = (m0 + wm0 + i * 32 + (lane >> 4)) * g.N + (n0 + wn0 + j * 32 + c4);
+#pragma unroll 4
+          for (int it = 0; it < 8; ++it) {
+            const int r = it * 4 + (lane >> 4);
+            const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[r * EPI_LD2 + c4]);
+            f32x4 f4 = {1.f, 1.f, 1.f, 1.f};
+            if constexpr (KIND == EK_PRE_SILU_LR_BF16) f4 = *reinterpret_cast<const f32x4*>(&stage_lr[r * EPI_LD2 + c4]);
+            epilogue_store4_kind<KIND>(g.epi, o0 + (int64_t)it * 4 * g.N, v4, f4);
+          }
+        }
+      } else {
 #pragma unroll 1
         for (int it = 0; it < 8; ++it) {
           const int r = it * 4 + (lane >> 4), c4 = (lane & 15) * 4;
@@ -421,7 +438,7 @@ __device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[
           const int64_t row = m0 + wm0 + i * 32 + r;
           const int col = n0 + wn0 + j * 32 + c4;
           if (row >= g.M || col >= g.N) continue;
-          if constexpr (LR_WAVES > 0) {
+          if constexpr (LR_POSSIBLE) {
             if (lr) {   // dispatch has checked vecC
               const f32x4 f4 = *reinterpret_cast<const f32x4*>(&stage_lr[r * EPI_LD2 + c4]);
               epilogue_store4(g.epi, row, col, g.N, v4, &f4);
@@ -433,8 +450,29 @@ __device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[
             for (int c = 0; c < 4; ++c)
               if (col + c < g.N) epilogue_store(g.epi, row, col + c, g.N, v4[c]);
         }
-        wave_lds_sync();
       }
+      wave_lds_sync();
+    }
+}
+
+template <int MB, int NB, int MODE, int LR_WAVES = 0>
+__device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[MB][NB], float* smem, int64_t m0, int n0,
+                                              int wm0, int wn0, int split) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kh = lane >> 5, l32 = lane & 31;
+  if constexpr (MODE != MODE_TN && NB % 2 == 0) {
+    switch (g.epi_kind) {   // uniform
+      case EK_OUT_F32: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_OUT_F32>(g, acc, smem, m0, n0, wm0, wn0); break;
+      case EK_OUT_BF16: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_OUT_BF16>(g, acc, smem, m0, n0, wm0, wn0); break;
+      case EK_PRE_SILU_BF16: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_PRE_SILU_BF16>(g, acc, smem, m0, n0, wm0, wn0); break;
+      case EK_PRE_SILU_LR_BF16:
+        if constexpr (LR_WAVES > 0) { tile_epilogue_pairs<MB, NB, LR_WAVES, EK_PRE_SILU_LR_BF16>(g, acc, smem, m0, n0, wm0, wn0); break; }
+        [[fallthrough]];
+      case EK_PRE_SILU_ADD_F32:
+        if (g.epi_kind == EK_PRE_SILU_ADD_F32) { tile_epilogue_pairs<MB, NB, LR_WAVES, EK_PRE_SILU_ADD_F32>(g, acc, smem, m0, n0, wm0, wn0); break; }
+        [[fallthrough]];
+      default: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_GENERIC>(g, acc, smem, m0, n0, wm0, wn0); break;
+    }
     return;
   }
   float* stage = smem + wave * (32 * EPI_LD);

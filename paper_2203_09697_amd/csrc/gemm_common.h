@@ -30,7 +30,32 @@ struct gemm_args {
   const float* A2 = nullptr;
   const float* B2 = nullptr;
   gp_epilogue epi;
+  int epi_kind = 0;        // EK_*: which fixed sequence of epilogue steps `epi` amounts to (set by gp_epilogue_kind on the host)
 };
+
+// The epilogue is a list of optional steps; tested inside the store loop, the options cost some forty branches per 4
+// values and made the epilogue as long as a third of a 1024-deep main loop.  The combinations the blocks use are
+// therefore recognised on the host and the tile epilogue switches ONCE per tile to a loop compiled for that combination;
+// anything else takes the general loop.
+enum {
+  EK_GENERIC = 0,
+  EK_OUT_F32,                 // out (fp32)
+  EK_OUT_BF16,                // out (bf16)
+  EK_PRE_SILU_BF16,           // save_pre (bf16), SiLU, out (bf16)
+  EK_PRE_SILU_LR_BF16,        // save_pre (bf16), SiLU, times the low-rank factor, out (bf16)
+  EK_PRE_SILU_ADD_F32,        // save_pre (bf16), SiLU, + add_post (bf16), times scale, out (fp32)
+};
+inline int gp_epilogue_kind(const gp_epilogue& e, int vecC) {
+  if (!vecC || e.bias || e.add_pre || e.out2 || e.act == 2 || e.mul || !e.out) return EK_GENERIC;
+  const unsigned b = e.bf16;
+  if (!e.save_pre && e.act == 0 && !e.lr_a && !e.add_post && e.scale == 1.0f)
+    return (b & EPI_BF_OUT) ? EK_OUT_BF16 : EK_OUT_F32;
+  if (e.save_pre && (b & EPI_BF_SAVE_PRE) && e.act == 1) {
+    if (!e.add_post && e.scale == 1.0f && (b & EPI_BF_OUT)) return e.lr_a ? EK_PRE_SILU_LR_BF16 : EK_PRE_SILU_BF16;
+    if (e.add_post && (b & EPI_BF_ADD_POST) && !e.lr_a && !(b & EPI_BF_OUT)) return EK_PRE_SILU_ADD_F32;
+  }
+  return EK_GENERIC;
+}
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
@@ -108,6 +133,31 @@ __device__ __forceinline__ void epilogue_store4(const gp_epilogue& e, int64_t ro
 #pragma unroll
     for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
     stx4(e.out2, o, b & EPI_BF_OUT2, v);
+  }
+}
+
+__device__ __forceinline__ void st4h(float* p, int64_t o, f32x4 v) {
+  bf16x4 h;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) h[c] = (__bf16)v[c];
+  __builtin_nontemporal_store(h, reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p) + o));
+}
+// The steps of one of the fixed combinations on 4 consecutive columns; no option is tested here.
+template <int KIND>
+__device__ __forceinline__ void epilogue_store4_kind(const gp_epilogue& e, int64_t o, f32x4 v, f32x4 lr) {
+  static_assert(KIND != EK_GENERIC, "the general loop calls epilogue_store4");
+  if constexpr (KIND == EK_OUT_F32) st4(e.out + o, v);
+  else if constexpr (KIND == EK_OUT_BF16) st4h(e.out, o, v);
+  else {
+    st4h(e.save_pre, o, v);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] = silu_f(v[c]);
+    if constexpr (KIND == EK_PRE_SILU_LR_BF16) v *= lr;
+    if constexpr (KIND == EK_PRE_SILU_ADD_F32) {
+      v += ldx4(e.add_post, o, 1u);
+      v *= e.scale;
+      st4(e.out + o, v);
+    } else st4h(e.out, o, v);
   }
 }
 
