@@ -223,35 +223,62 @@ gemm_f32_kernel(const gemm_args g) {
   // eight 128-byte row segments per instruction.
   __syncthreads();   // all wavefronts are done with the operand tiles; LDS is reused below
   float* stage = smem + wave * (32 * EPI_LD);
+  // one block: through the wavefront's LDS slice, then the epilogue steps; EMASK != 0: a loop compiled for exactly
+  // those steps for blocks inside the matrix, the general one (options tested per 4 values) otherwise
+  auto blocks = [&](auto emask) __attribute__((always_inline)) {
+    constexpr unsigned EMASK = decltype(emask)::value;
 #pragma unroll
-  for (int i = 0; i < MB; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
+      for (int j = 0; j < NB; ++j) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD + l32] = acc[i][j][v];
-      wave_lds_sync();
+        for (int v = 0; v < 16; ++v) stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD + l32] = acc[i][j][v];
+        wave_lds_sync();
+        const bool inside = m0 + wm0 + i * 32 + 32 <= g.M && n0 + wn0 + j * 32 + 32 <= g.N;
+        if (EMASK != 0 && MODE != MODE_TN && inside) {
+          if constexpr (EMASK != 0) {
+            const int c4 = (lane & 7) * 4, col = n0 + wn0 + j * 32 + c4;
+            const int64_t o0 = (m0 + wm0 + i * 32 + (lane >> 3)) * g.N + col;
 #pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        const int r = it * 8 + (lane >> 3), c4 = (lane & 7) * 4;
-        const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[r * EPI_LD + c4]);
-        const int64_t row = m0 + wm0 + i * 32 + r;
-        const int col = n0 + wn0 + j * 32 + c4;
-        if (row >= g.M || col >= g.N) continue;
-        if (MODE == MODE_TN) {
-          float* dst = g.part + ((int64_t)blockIdx.y * g.M + row) * g.N + col;
-          if (g.vecC) *reinterpret_cast<f32x4*>(dst) = v4;
-          else
-            for (int c = 0; c < 4; ++c)
-              if (col + c < g.N) dst[c] = v4[c];
+            for (int it = 0; it < 4; ++it) {
+              const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[(it * 8 + (lane >> 3)) * EPI_LD + c4]);
+              epilogue_store4_mask<EMASK>(g.epi, o0 + (int64_t)it * 8 * g.N, col, v4);
+            }
+          }
         } else {
-          if (g.vecC) epilogue_store4(g.epi, row, col, g.N, v4);
-          else
-            for (int c = 0; c < 4; ++c)
-              if (col + c < g.N) epilogue_store(g.epi, row, col + c, g.N, v4[c]);
+#pragma unroll 1
+          for (int it = 0; it < 4; ++it) {
+            const int r = it * 8 + (lane >> 3), c4 = (lane & 7) * 4;
+            const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[r * EPI_LD + c4]);
+            const int64_t row = m0 + wm0 + i * 32 + r;
+            const int col = n0 + wn0 + j * 32 + c4;
+            if (row >= g.M || col >= g.N) continue;
+            if (MODE == MODE_TN) {
+              float* dst = g.part + ((int64_t)blockIdx.y * g.M + row) * g.N + col;
+              if (g.vecC) *reinterpret_cast<f32x4*>(dst) = v4;
+              else
+                for (int c = 0; c < 4; ++c)
+                  if (col + c < g.N) dst[c] = v4[c];
+            } else {
+              if (g.vecC) epilogue_store4(g.epi, row, col, g.N, v4);
+              else
+                for (int c = 0; c < 4; ++c)
+                  if (col + c < g.N) epilogue_store(g.epi, row, col + c, g.N, v4[c]);
+            }
+          }
         }
+        wave_lds_sync();
       }
-      wave_lds_sync();
+  };
+  if constexpr (MODE == MODE_TN) blocks(std::integral_constant<unsigned, 0u>{});
+  else {
+    switch (g.epi_mask) {   // uniform
+#define GP_EM_CASE(M) case M: blocks(std::integral_constant<unsigned, M>{}); break;
+      GP_EM_LIST(GP_EM_CASE)
+#undef GP_EM_CASE
+      default: blocks(std::integral_constant<unsigned, 0u>{}); break;
     }
+  }
   if (MODE == MODE_TN && g.colsum_part && threadIdx.x < BN && n0 + (int)threadIdx.x < g.N)
     g.colsum_part[((int64_t)blockIdx.y * tiles_m + tile_m) * g.N + n0 + threadIdx.x] = colsum;
 }
@@ -469,6 +496,7 @@ int gp_gemm_nn(gp_ctx* ctx, const float* A, const float* B, int64_t M, int N, in
   g.epi = epi;
   g.vecC = epi_vec_ok(epi, N);
   g.epi_kind = gp_epilogue_kind(g.epi, g.vecC);
+  g.epi_mask = gp_epilogue_mask(g.epi, g.vecC);
   return dispatch_gemm<MODE_NN>(ctx, g, 1);
 }
 
@@ -486,6 +514,7 @@ int gp_gemm_nt(gp_ctx* ctx, const float* A, const float* Bt, int64_t M, int N, i
   g.epi = epi;
   g.vecC = epi_vec_ok(epi, N);
   g.epi_kind = gp_epilogue_kind(g.epi, g.vecC);
+  g.epi_mask = gp_epilogue_mask(g.epi, g.vecC);
   return dispatch_gemm<MODE_NT>(ctx, g, 1);
 }
 
@@ -520,6 +549,7 @@ int gp_gemm_nt2(gp_ctx* ctx, const float* A, const float* Bt, const float* A2, c
   g.epi = e;
   g.vecC = epi_vec_ok(e, N);
   g.epi_kind = gp_epilogue_kind(g.epi, g.vecC);
+  g.epi_mask = gp_epilogue_mask(g.epi, g.vecC);
   return dispatch_gemm<MODE_NT>(ctx, g, 1);
 }
 

@@ -31,7 +31,20 @@ struct gemm_args {
   const float* B2 = nullptr;
   gp_epilogue epi;
   int epi_kind = 0;        // EK_*: which fixed sequence of epilogue steps `epi` amounts to (set by gp_epilogue_kind on the host)
+  unsigned epi_mask = 0;   // EM_*: the steps present when every matrix is fp32 (0: take the general loop); fp32 kernels
 };
+
+// fp32 kernels: the steps present as a bit mask; the kernel switches once per tile over the masks listed in
+// GP_EM_LIST (those of the variant-D block) to a loop compiled for that mask
+enum : unsigned { EM_BIAS = 1, EM_ADD_PRE = 2, EM_SAVE_PRE = 4, EM_ACT1 = 8, EM_ACT2 = 16, EM_MUL = 32, EM_ADD_POST = 64, EM_SCALE = 128,
+                  EM_OUT = 256, EM_OUT2 = 512 };
+#define GP_EM_LIST(X) X(256) X(269) X(333) X(272) X(320) X(832) X(301) X(268) X(332) X(768) X(322)
+inline unsigned gp_epilogue_mask(const gp_epilogue& e, int vecC) {
+  if (!vecC || e.bf16 || e.lr_a) return 0;
+  return (e.bias ? EM_BIAS : 0u) | (e.add_pre ? EM_ADD_PRE : 0u) | (e.save_pre ? EM_SAVE_PRE : 0u) | (e.act == 1 ? EM_ACT1 : 0u) |
+         (e.act == 2 ? EM_ACT2 : 0u) | (e.mul ? EM_MUL : 0u) | (e.add_post ? EM_ADD_POST : 0u) | (e.scale != 1.0f ? EM_SCALE : 0u) |
+         (e.out ? EM_OUT : 0u) | (e.out2 ? EM_OUT2 : 0u);
+}
 
 // The epilogue is a list of optional steps; tested inside the store loop, the options cost some forty branches per 4
 // values and made the epilogue as long as a third of a 1024-deep main loop.  The combinations the blocks use are
@@ -158,6 +171,33 @@ __device__ __forceinline__ void epilogue_store4_kind(const gp_epilogue& e, int64
       v *= e.scale;
       st4(e.out + o, v);
     } else st4h(e.out, o, v);
+  }
+}
+
+// The steps named by the mask M on 4 consecutive columns of fp32 matrices, in the order of epilogue_store4; no option is tested.
+template <unsigned M>
+__device__ __forceinline__ void epilogue_store4_mask(const gp_epilogue& e, int64_t o, int col, f32x4 v) {
+  if constexpr ((M & EM_BIAS) != 0) v += ld4(e.bias + col);
+  if constexpr ((M & EM_ADD_PRE) != 0) v += ld4(e.add_pre + o);
+  if constexpr ((M & EM_SAVE_PRE) != 0) st4(e.save_pre + o, v);
+  if constexpr ((M & EM_ACT1) != 0) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] = silu_f(v[c]);
+  }
+  if constexpr ((M & EM_ACT2) != 0) {
+    const f32x4 z = ld4(e.zsrc + o);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
+  }
+  if constexpr ((M & EM_MUL) != 0) v *= ld4(e.mul + o);
+  if constexpr ((M & EM_ADD_POST) != 0) v += ld4(e.add_post + o);
+  if constexpr ((M & EM_SCALE) != 0) v *= e.scale;
+  if constexpr ((M & EM_OUT) != 0) st4(e.out + o, v);
+  if constexpr ((M & EM_OUT2) != 0) {
+    const f32x4 z = ld4(e.z2src + o);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
+    st4(e.out2 + o, v);
   }
 }
 
