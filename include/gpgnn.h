@@ -295,6 +295,16 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
                         const float* m_in, const void* saved, size_t saved_bytes,
                         const float* grad_m_out, float* grad_m_in, gp_weights_D* grad_w,
                         void* scratch, size_t scratch_bytes);
+/* The same, and the gradient with respect to the basis (forces of the energy-centric model, Sec. 3.2, 3.3):
+ * grad_rbf[E, num_radial] = dL/d(radial basis), grad_rad[E, num_spherical, num_radial] = dL/d(radial part of the
+ * spherical basis, basis->rad), grad_cos_kj[T] = dL/dcos(alpha) in kj-major order; any of them may be NULL.  With
+ * accumulate_basis_grads != 0 they are added to (several blocks share one basis), else overwritten. */
+int gp_block_backward_D_basis(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
+                              const gp_graph* graph, const gp_basis* basis,
+                              const float* m_in, const void* saved, size_t saved_bytes,
+                              const float* grad_m_out, float* grad_m_in, gp_weights_D* grad_w,
+                              float* grad_rbf, float* grad_rad, float* grad_cos_kj, int32_t accumulate_basis_grads,
+                              void* scratch, size_t scratch_bytes);
 
 /* ------------------------------------------------------------------------------------------
  * Interaction block, variant G (Sec. 3.4: a bilinear layer replaces the Hadamard product; the

@@ -8,7 +8,7 @@ __all__ = [
     "GpError", "load", "library_path", "Context", "Dims", "Graph", "Basis",
     "gp_version", "gp_deferred_status", "gp_profile_enable", "gp_profile_reset", "gp_profile_collect", "gp_set_side_stream", "gp_set_triplet_mfma",
     "gp_measure_peaks", "gp_edges_by_source", "gp_edges_by_source_static", "gp_reverse_edges", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
-    "gp_block_forward_D", "gp_block_backward_D", "gp_triplet_aggregate_fwd",
+    "gp_block_forward_D", "gp_block_backward_D", "gp_block_backward_D_basis", "gp_triplet_aggregate_fwd",
     "gp_triplet_aggregate_bwd", "gp_linear_forward", "build_graph", "weights_to_device",
     "TRIPLET_STREAM", "TRIPLET_PER_EDGE", "TRIPLET_PER_ATOM", "TRIPLET_PER_ATOM_TWO_KERNELS", "gp_triplet_workspace",
     "gp_triplet_hadamard_fwd", "gp_triplet_hadamard_bwd", "gp_triplet_bilinear_fwd", "gp_triplet_bilinear_bwd_H",
@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = [
     "gp_edges_workspace", "gp_edges_count", "gp_edges_fill", "gp_edges_count_pbc", "gp_edges_fill_pbc",
     "gp_triplets_count_pbc", "gp_triplets_fill_pbc",
     "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill", "gp_csr_max_degree", "gp_reverse_edges",
-    "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D",
+    "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D", "gp_block_backward_D_basis",
     "gp_block_forward_G", "gp_block_backward_G",
     "gp_energy_workspace", "gp_energy_forward", "gp_energy_backward",
     "gp_output_workspace", "gp_output_forward", "gp_output_backward",
@@ -387,6 +387,19 @@ def gp_block_backward_D(ctx, dims, w, trip, basis, m_in, saved, grad_m_out, grad
     ctx.check(lib.gp_block_backward_D(ctx._h, C.byref(d), C.byref(ws), C.byref(g), C.byref(b), _ptr(m_in), _ptr(saved),
                                       C.c_size_t(saved.numel()), _ptr(grad_m_out), _ptr(grad_m_in), C.byref(gws),
                                       _ptr(scratch), C.c_size_t(scratch.numel())))
+    return grad_m_in, grad_w
+
+
+def gp_block_backward_D_basis(ctx, dims, w, trip, basis, m_in, saved, grad_m_out, grad_m_in, grad_w, scratch,
+                              grad_rbf=None, grad_rad=None, grad_cos_kj=None, accumulate=False):
+    """gp_block_backward_D plus the gradients with respect to the basis (written into the given tensors)."""
+    lib = load()
+    d, g, b = Dims(dims), Graph(trip), Basis(basis)
+    ws, gws = _weights_D(dims, w), _weights_D(dims, grad_w)
+    ctx.check(lib.gp_block_backward_D_basis(ctx._h, C.byref(d), C.byref(ws), C.byref(g), C.byref(b), _ptr(m_in), _ptr(saved),
+                                            C.c_size_t(saved.numel()), _ptr(grad_m_out), _ptr(grad_m_in), C.byref(gws),
+                                            _ptr(grad_rbf), _ptr(grad_rad), _ptr(grad_cos_kj), C.c_int32(1 if accumulate else 0),
+                                            _ptr(scratch), C.c_size_t(scratch.numel())))
     return grad_m_in, grad_w
 
 

@@ -61,6 +61,7 @@ struct scratch_D {
   float* buf[7];     // [E,H] each
   float *dF1, *dF2;  // [E,F]
   float* dQ;         // [E,S*B]
+  float* P;          // [E,S,F]: per-edge factor of the gradient with respect to cos(alpha) (basis gradients only)
   float* dWrbf;      // [R,H]
   float* part;
   float* part_aux;   // split-K partials of the GEMMs issued on the side stream
@@ -96,6 +97,7 @@ size_t carve_scratch_D(void* p, const gp_dims* d, int64_t E, scratch_D* s) {
   s->dF1 = c.take<float>(E * F);
   s->dF2 = c.take<float>(E * F);
   s->dQ = c.take<float>(E * S * B);
+  s->P = c.take<float>(E * S * F);
   s->dWrbf = c.take<float>(R * H);
   s->part_bytes = part_bytes_D(d, E);
   s->part = (float*)c.take<char>(s->part_bytes);
@@ -274,10 +276,39 @@ int gp_block_forward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, 
   return rows_forward(0, E);
 }
 
-int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, const gp_graph* graph,
-                        const gp_basis* basis, const float* m_in, const void* saved, size_t saved_bytes,
-                        const float* grad_m_out, float* grad_m_in, gp_weights_D* gw, void* scratch,
-                        size_t scratch_bytes) {
+}  // extern "C"
+
+namespace {
+
+// P[e, l, f] = x[e, f] sum_b W_sbf2[b, f] Q[e, l, b]: with it, dL/dcos(alpha_t) = sum_l Y_l0'(cos alpha_t) sum_f
+// grad_a[ji(t), f] P[kj(t), l, f], the same contraction as the bilinear block's (U = P, dz = grad_a)
+__global__ void cos_factor_kernel(const float* __restrict__ x, const float* __restrict__ W2, const float* __restrict__ Qt, int64_t E,
+                                  int S, int B, int F, float* __restrict__ P) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (e, l, f)
+  if (i >= E * S * F) return;
+  const int f = (int)(i % F), l = (int)((i / F) % S);
+  const int64_t e = i / ((int64_t)F * S);
+  float s = 0.f;
+  for (int b = 0; b < B; ++b) s += W2[b * F + f] * Qt[(int64_t)(l * B + b) * E + e];
+  P[i] = x[e * F + f] * s;
+}
+
+// grad_rad[e, l, n] (+)= sum_b grad_Q[e, l, b] W_sbf1[(l, n), b]   (Q[e, l, b] = sum_n rad[e, l, n] W_sbf1[(l, n), b])
+__global__ void grad_rad_kernel(const float* __restrict__ gQ, const float* __restrict__ W1, int64_t E, int S, int R, int B,
+                                int accumulate, float* __restrict__ grad_rad) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (e, l, n)
+  if (i >= E * S * R) return;
+  const int n = (int)(i % R), l = (int)((i / R) % S);
+  const int64_t e = i / ((int64_t)R * S);
+  float s = 0.f;
+  for (int b = 0; b < B; ++b) s += gQ[(e * S + l) * B + b] * W1[(l * R + n) * B + b];
+  grad_rad[i] = accumulate ? grad_rad[i] + s : s;
+}
+
+int backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, const gp_graph* graph, const gp_basis* basis,
+               const float* m_in, const void* saved, size_t saved_bytes, const float* grad_m_out, float* grad_m_in,
+               gp_weights_D* gw, float* grad_rbf, float* grad_rad, float* grad_cos_kj, int accumulate_basis_grads,
+               void* scratch, size_t scratch_bytes) {
   if (!ctx) return GP_BAD_ARG;
   GP_TRY(check_dims_D(ctx, dims));
   GP_TRY(check_weights_D(ctx, dims, w, "weights"));
@@ -391,6 +422,19 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
                                      gw->W_sbf1, sc.part_aux, sc.part_bytes);
       },
       {}));
+  // gradients with respect to the basis (forces, Sec. 3.2): radial part of the spherical basis from grad_Q, cos(alpha)
+  // through the per-edge factor P and the kernel the bilinear block uses for the same contraction
+  if (grad_rad) {
+    const int64_t n = E * S * R;
+    grad_rad_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(sc.dQ, w->W_sbf1, E, S, R, B, accumulate_basis_grads, grad_rad);
+    GP_LAUNCH_CHECK(ctx, "grad_rad_kernel");
+  }
+  if (grad_cos_kj && graph->n_triplets > 0) {
+    const int64_t n = E * S * F;
+    cos_factor_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(s.x_kj, w->W_sbf2, s.Q, E, S, B, F, sc.P);
+    GP_LAUNCH_CHECK(ctx, "cos_factor_kernel");
+    GP_TRY(gp_tripG_grad_cos(ctx, graph, basis->cos_alpha_kj, sc.P, sc.dF1, F, S, accumulate_basis_grads, grad_cos_kj));
+  }
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dF2, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes); },
                     {sc.dF2}));
   {
@@ -401,6 +445,11 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
   GP_TRY(aux.before_write(dz_kj));
   GP_TRY(gp_ew_gate_bwd(ctx, T2, s.z_kj, s.gate, dz_kj, dgate, EH));                         // dz_kj, dgate
   GP_TRY(gp_gemm_tn(ctx, basis->rbf, dgate, E, R, H, sc.dWrbf, nullptr, sc.part, sc.part_bytes));
+  if (grad_rbf) {   // dL/drbf = dgate W_rbf^T
+    gp_epilogue e; e.out = grad_rbf;
+    if (accumulate_basis_grads) e.add_post = grad_rbf;
+    GP_TRY(gp_gemm_nt(ctx, dgate, s.Wrbf, E, R, H, e));
+  }
   {
     gp_epilogue e; e.out = gw->W_rbf1;
     GP_TRY(gp_gemm_nt(ctx, sc.dWrbf, w->W_rbf2, R, B, H, e));
@@ -413,6 +462,26 @@ int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w,
     GP_TRY(gp_gemm_nt(ctx, dz_kj, w->W_kj, E, H, H, e));                                     // dm = kj path + ji path + skip
   }
   return aux.join();
+}
+
+}  // namespace
+
+extern "C" {
+
+int gp_block_backward_D(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, const gp_graph* graph,
+                        const gp_basis* basis, const float* m_in, const void* saved, size_t saved_bytes,
+                        const float* grad_m_out, float* grad_m_in, gp_weights_D* gw, void* scratch,
+                        size_t scratch_bytes) {
+  return backward_D(ctx, dims, w, graph, basis, m_in, saved, saved_bytes, grad_m_out, grad_m_in, gw, nullptr, nullptr, nullptr, 0,
+                    scratch, scratch_bytes);
+}
+
+int gp_block_backward_D_basis(gp_ctx* ctx, const gp_dims* dims, const gp_weights_D* w, const gp_graph* graph,
+                              const gp_basis* basis, const float* m_in, const void* saved, size_t saved_bytes,
+                              const float* grad_m_out, float* grad_m_in, gp_weights_D* gw, float* grad_rbf, float* grad_rad,
+                              float* grad_cos_kj, int32_t accumulate_basis_grads, void* scratch, size_t scratch_bytes) {
+  return backward_D(ctx, dims, w, graph, basis, m_in, saved, saved_bytes, grad_m_out, grad_m_in, gw, grad_rbf, grad_rad,
+                    grad_cos_kj, accumulate_basis_grads, scratch, scratch_bytes);
 }
 
 }  // extern "C"

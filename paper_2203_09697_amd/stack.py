@@ -35,12 +35,20 @@ class StackD:
             cur = self.m[b]
         return cur
 
-    def backward(self, grad_out):
+    def backward(self, grad_out, basis_grads=None):
+        """basis_grads: dict with any of 'grad_rbf' [E, R], 'grad_rad' [E, S * R], 'grad_cos_kj' [T] (fp32 device
+        tensors): the blocks' gradients with respect to the basis are summed into them."""
         g = grad_out
         for b in reversed(range(self.n_blocks)):
             m_in = self.m_in if b == 0 else self.m[b - 1]
             out = self.g[b % 2]
-            B.gp_block_backward_D(self.ctx, self.dims, self.w[b], self.trip, self.basis, m_in, self.saved[b], g, out,
-                                  self.grad_w[b], self.scratch)
+            if basis_grads is None:
+                B.gp_block_backward_D(self.ctx, self.dims, self.w[b], self.trip, self.basis, m_in, self.saved[b], g, out,
+                                      self.grad_w[b], self.scratch)
+            else:
+                B.gp_block_backward_D_basis(self.ctx, self.dims, self.w[b], self.trip, self.basis, m_in, self.saved[b], g, out,
+                                            self.grad_w[b], self.scratch, basis_grads.get("grad_rbf"),
+                                            basis_grads.get("grad_rad"), basis_grads.get("grad_cos_kj"),
+                                            accumulate=b != self.n_blocks - 1)
             g = out
         return g, self.grad_w

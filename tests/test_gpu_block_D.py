@@ -176,6 +176,46 @@ def test_block_D_matrix_core_widths(lib, ctx, int_emb, num_spherical):
     _block_parity(lib, ctx, w, 6, n_blocks=1, pos_gptr=pos_gptr)
 
 
+@pytest.mark.parametrize("triplet_form", [-1, 0], indirect=True)
+def test_block_D_basis_gradients(lib, ctx, triplet_form):
+    """Gradients with respect to the radial basis, the radial part of the spherical basis and cos(alpha) of a two-block
+    stack (the second block overwrites, the first adds) against autograd of the oracle, in which the per-triplet
+    spherical basis is the product rad[kj] * Y_l0(cos alpha) of the two leaves."""
+    from oracle import basis as obasis
+    from paper_2203_09697_amd.stack import StackD
+    w = synth.get_workload("cfg2")
+    dims = w.dims
+    pos, ref, e, t = _case(lib, ctx, w, 5, synth.slab_adsorbate_positions(2, 4, 4, 4, 16, seed=5))
+    E, T = len(ref["src"]), len(ref["idx_kj"])
+    W_list = [synth.weights_D(dims, seed=200 + b, bias_scale=0.1) for b in range(2)]
+    m, gup = synth.edge_embeddings(E, dims.emb, seed=12)
+    ob = H.oracle_basis_D(pos, ref, dims)
+    rbf = ob["rbf"].detach().clone().requires_grad_(True)
+    rad = ob["rad"].detach().clone().requires_grad_(True)                 # [E, S * R]
+    ca = ob["cos_alpha"].detach().clone().requires_grad_(True)
+    kj = torch.as_tensor(ref["idx_kj"], dtype=torch.long)
+    S, R = dims.num_spherical, dims.num_radial
+    sbf = (rad.reshape(E, S, R)[kj] * obasis.y_l0(ca, S)[:, :, None]).reshape(T, S * R)
+    out = oblock.stack_D(torch.tensor(m, dtype=F64), rbf, sbf, ref["idx_kj"], ref["idx_ji"], [H.t64(W) for W in W_list],
+                         dims.n_res_before, dims.n_res_after)
+    g_rbf, g_rad, g_ca = torch.autograd.grad((out * torch.tensor(gup, dtype=F64)).sum(), [rbf, rad, ca])
+    gb = lib.gp_basis_forward(ctx, dims, e, t)
+    stack = StackD(ctx, dims, [lib.weights_to_device(W) for W in W_list], t, gb)
+    stack.forward(H.to_dev(m, torch.float32))
+    bg = {"grad_rbf": torch.full((E, R), 7.0, dtype=torch.float32, device="cuda:0"),      # must be overwritten
+          "grad_rad": torch.full((E, S * R), 7.0, dtype=torch.float32, device="cuda:0"),
+          "grad_cos_kj": torch.full((T,), 7.0, dtype=torch.float32, device="cuda:0")}
+    stack.backward(H.to_dev(gup, torch.float32), basis_grads=bg)
+    torch.cuda.synchronize()
+    order = t["perm_kj"].cpu().numpy()
+    errs = {"grad_rbf": H.rel_l2(bg["grad_rbf"].cpu().numpy(), g_rbf.numpy()),
+            "grad_rad": H.rel_l2(bg["grad_rad"].cpu().numpy(), g_rad.numpy()),
+            "grad_cos_kj": H.rel_l2(bg["grad_cos_kj"].cpu().numpy(), g_ca.numpy()[order])}
+    print(errs)
+    assert all(v <= TOL for v in errs.values()), errs
+    assert g_ca.abs().max() > 1e-8 and g_rad.abs().max() > 1e-8
+
+
 @pytest.mark.timeout(600)
 def test_block_D_xl_widths_small_structure(lib, ctx):
     # the widest DimeNet++ the paper trains (Sec. 4.1: hidden width 2048, triplet width 256) on a structure small
