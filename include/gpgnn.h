@@ -429,6 +429,14 @@ int gp_forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* 
                               const int32_t* out_ptr, const int32_t* out_list, int64_t n_atoms,
                               const float* dist, const float* unit, const float* grad_rbf,
                               const float* grad_cos_kj, float* forces, void* ws, size_t ws_bytes);
+/* The same for variant D (Sec. 3.2, 3.3: forces of the energy-centric Hadamard model): grad_rbf[E,R] is the gradient
+ * with respect to the Bessel radial basis, grad_rad[E,S,R] with respect to the radial part of the spherical basis
+ * (basis->rad), both as gp_block_backward_D_basis returns them; same workspace. */
+int gp_forces_from_basis_grad_D(gp_ctx* ctx, const gp_dims* dims, const gp_graph* graph,
+                                const int32_t* perm_kj, const int32_t* row_ptr,
+                                const int32_t* out_ptr, const int32_t* out_list, int64_t n_atoms,
+                                const float* dist, const float* unit, const float* grad_rbf, const float* grad_rad,
+                                const float* grad_cos_kj, float* forces, void* ws, size_t ws_bytes);
 
 /* ------------------------------------------------------------------------------------------
  * The core TripletUpdate + TripletAggr kernels on their own (Sec. 3.3: Hadamard product of the

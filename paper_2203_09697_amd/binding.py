@@ -33,7 +33,7 @@ EXPORTED_SYMBOLS = [
     "gp_block_forward_G", "gp_block_backward_G",
     "gp_energy_workspace", "gp_energy_forward", "gp_energy_backward",
     "gp_output_workspace", "gp_output_forward", "gp_output_backward",
-    "gp_edges_by_source_workspace", "gp_edges_by_source", "gp_edges_by_source_static", "gp_forces_workspace", "gp_forces_from_basis_grad",
+    "gp_edges_by_source_workspace", "gp_edges_by_source", "gp_edges_by_source_static", "gp_forces_workspace", "gp_forces_from_basis_grad", "gp_forces_from_basis_grad_D",
     "gp_triplet_aggregate_fwd", "gp_triplet_aggregate_bwd", "gp_linear_forward", "gp_linear_forward_bf16",
     "gp_triplet_workspace", "gp_triplet_hadamard_fwd", "gp_triplet_hadamard_bwd", "gp_triplet_bilinear_fwd",
     "gp_triplet_bilinear_bwd_H", "gp_triplet_bilinear_grad_cos",

@@ -7,7 +7,7 @@ from . import binding as B
 from .binding_g import StackG
 
 __all__ = ["gp_energy_workspace", "gp_energy_forward", "gp_energy_backward", "gp_edges_by_source",
-           "gp_forces_from_basis_grad", "ForceModelG"]
+           "gp_forces_from_basis_grad", "gp_forces_from_basis_grad_D", "ForceModelG", "ForceModelD"]
 
 
 class _WeightsHead(C.Structure):
@@ -56,6 +56,55 @@ def gp_forces_from_basis_grad(ctx, dims, edges, trip, out_ptr, out_list, grad_rb
         B._ptr(out_list), C.c_int64(edges["n_atoms"]), B._ptr(edges["dist"]), B._ptr(edges["unit"]), B._ptr(grad_rbf),
         B._ptr(grad_cos_kj), B._ptr(forces), B._ptr(ws), C.c_size_t(ws.numel())))
     return forces
+
+
+def gp_forces_from_basis_grad_D(ctx, dims, edges, trip, out_ptr, out_list, grad_rbf, grad_rad, grad_cos_kj, forces, ws):
+    d, g = B.Dims(dims), B.Graph(trip)
+    ctx.check(B.load().gp_forces_from_basis_grad_D(
+        ctx._h, C.byref(d), C.byref(g), B._ptr(trip["perm_kj"]), B._ptr(edges["row_ptr"]), B._ptr(out_ptr),
+        B._ptr(out_list), C.c_int64(edges["n_atoms"]), B._ptr(edges["dist"]), B._ptr(edges["unit"]), B._ptr(grad_rbf),
+        B._ptr(grad_rad), B._ptr(grad_cos_kj), B._ptr(forces), B._ptr(ws), C.c_size_t(ws.numel())))
+    return forces
+
+
+class ForceModelD:
+    """Variant-D block stack + energy head; energy_and_forces() runs forward, backward and the position-gradient
+    assembly.  Allocation and call sequencing only."""
+
+    def __init__(self, ctx, dims, weights_list, head_w, hidden, edges, trip, basis, graph_ptr):
+        from .stack import StackD
+        self.ctx, self.dims, self.edges, self.trip, self.basis = ctx, dims, edges, trip, basis
+        self.stack = StackD(ctx, dims, weights_list, trip, basis)
+        self.head_w, self.hidden, self.graph_ptr = head_w, hidden, graph_ptr
+        dev = ctx.device
+        N, E, T = edges["n_atoms"], edges["n_edges"], trip["n_triplets"]
+        sb, cb = gp_energy_workspace(dims.emb, hidden, N)
+        self.h_saved = torch.empty(max(sb, 8), dtype=torch.uint8, device=dev)
+        self.h_scratch = torch.empty(max(cb, 8), dtype=torch.uint8, device=dev)
+        self.energy = torch.empty(graph_ptr.shape[0] - 1, dtype=torch.float32, device=dev)
+        self.grad_m = torch.empty((E, dims.emb), dtype=torch.float32, device=dev)
+        self.basis_grads = {"grad_rbf": torch.empty((E, dims.num_radial), dtype=torch.float32, device=dev),
+                            "grad_rad": torch.empty((E, dims.num_spherical * dims.num_radial), dtype=torch.float32, device=dev),
+                            "grad_cos_kj": torch.empty(max(T, 1), dtype=torch.float32, device=dev)}
+        self.forces = torch.empty((N, 3), dtype=torch.float32, device=dev)
+        self.out_ptr, self.out_list = gp_edges_by_source(ctx, edges)
+        nb = C.c_size_t()
+        ctx.check(B.load().gp_forces_workspace(C.c_int64(E), C.c_int64(T), C.byref(nb)))
+        self.f_ws = torch.empty(max(nb.value, 8), dtype=torch.uint8, device=dev)
+        self.head_grad = {k: torch.empty_like(v) for k, v in head_w.items()}
+
+    def energy_and_forces(self, m0):
+        d = self.dims
+        m = self.stack.forward(m0)
+        gp_energy_forward(self.ctx, d.emb, self.hidden, self.head_w, m, self.edges["row_ptr"], self.graph_ptr, self.energy,
+                          self.h_saved)
+        gp_energy_backward(self.ctx, d.emb, self.hidden, self.head_w, self.edges["dst"], self.edges["n_atoms"],
+                           self.h_saved, self.grad_m, self.head_grad, self.h_scratch)
+        self.stack.backward(self.grad_m, basis_grads=self.basis_grads)
+        bg = self.basis_grads
+        gp_forces_from_basis_grad_D(self.ctx, d, self.edges, self.trip, self.out_ptr, self.out_list, bg["grad_rbf"],
+                                    bg["grad_rad"], bg["grad_cos_kj"], self.forces, self.f_ws)
+        return self.energy, self.forces
 
 
 class ForceModelG:

@@ -96,6 +96,41 @@ __global__ void basis_edge_D_kernel(const float* __restrict__ dist, int64_t n_ed
   }
 }
 
+// variant D, for forces: gd[e] = sum_n grad_rbf[e,n] d rbf_n / dd + sum_{l,n} grad_rad[e,l,n] d rad_ln / dd with
+//   rbf_n(d) = u(x) sqrt(2/c) sin(k x) / d,  k = (n+1) pi,  x = d / c
+//   rad_ln(d) = u(x) N_ln j_l(z_ln x),  j_l'(y) = j_{l-1}(y) - (l+1)/y j_l(y)  (j_0' = -j_1)
+// one thread per edge (a few dozen terms in fp64; not a hot kernel)
+__global__ void grad_dist_bessel_kernel(const float* __restrict__ dist, const float* __restrict__ grad_rbf,
+                                        const float* __restrict__ grad_rad, int64_t n_edges, int S, int R, int p, double cutoff,
+                                        bessel_table tab, float* __restrict__ gd) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_edges) return;
+  const double d = (double)dist[e], x = d / cutoff;
+  double xp1 = 1.0;                       // x^(p-1)
+  for (int k = 0; k < p - 1; ++k) xp1 *= x;
+  const double a = -0.5 * (p + 1) * (p + 2), b = (double)p * (p + 2), c = -0.5 * p * (p + 1);
+  const double u = 1.0 + xp1 * x * (a + x * (b + x * c));
+  const double du = xp1 * (p * a + x * ((p + 1) * b + x * (p + 2) * c)) / cutoff;   // du/dd
+  double s = 0.0;
+  if (grad_rbf) {
+    const double pre = sqrt(2.0 / cutoff);
+    for (int n = 0; n < R; ++n) {
+      const double k = (double)(n + 1) * M_PI, sn = sin(k * x), cs = cos(k * x);
+      s += (double)grad_rbf[e * R + n] * pre * (du * sn / d + u * (k / cutoff * cs / d - sn / (d * d)));
+    }
+  }
+  if (grad_rad) {
+    for (int l = 0; l < S; ++l)
+      for (int n = 0; n < R; ++n) {
+        const double z = tab.z[l * R + n], y = z * x;
+        const double jl = sph_bessel(l, y);
+        const double djl = l == 0 ? -sph_bessel(1, y) : sph_bessel(l - 1, y) - (double)(l + 1) / y * jl;
+        s += (double)grad_rad[e * S * R + l * R + n] * tab.norm[l * R + n] * (du * jl + u * z / cutoff * djl);
+      }
+  }
+  gd[e] = (float)s;
+}
+
 // variant G: g[E,R] Gaussian radial basis
 __global__ void basis_edge_G_kernel(const float* __restrict__ dist, int64_t n_edges, int R, int p,
                                     double cutoff, float* __restrict__ g) {
@@ -199,5 +234,20 @@ extern "C" int gp_basis_forward(gp_ctx* ctx, const gp_dims* dims, const float* d
   } else if (n_triplets > 0) {
     GP_REQUIRE(ctx, !cos_alpha_kj && !sbf, "gp_basis_forward: cos_alpha_kj/sbf need cos_alpha");
   }
+  return GP_OK;
+}
+
+// dL/dd per edge from the gradients with respect to the Bessel radial basis and the radial part of the spherical
+// basis (either may be NULL)
+int gp_grad_dist_bessel(gp_ctx* ctx, const gp_dims* dims, const float* dist, const float* grad_rbf, const float* grad_rad,
+                        int64_t n_edges, float* gd) {
+  if (n_edges == 0) return GP_OK;
+  const int S = dims->num_spherical, R = dims->num_radial;
+  GP_REQUIRE(ctx, S >= 1 && S <= MAX_S && R >= 1 && R <= MAX_R_BESSEL, "grad_dist_bessel: basis sizes out of range");
+  bessel_table tab;
+  make_bessel_table(S, R, (double)dims->cutoff, &tab);
+  grad_dist_bessel_kernel<<<(unsigned)((n_edges + 255) / 256), 256, 0, ctx->stream>>>(dist, grad_rbf, grad_rad, n_edges, S, R,
+                                                                                      dims->envelope_p, (double)dims->cutoff, tab, gd);
+  GP_LAUNCH_CHECK(ctx, "grad_dist_bessel_kernel");
   return GP_OK;
 }

@@ -44,6 +44,10 @@ struct gp_ctx {
 
 // Launches the check of gp_graph.max_in_degree / max_out_degree against the lists (sets the deferred-error word).
 int gp_check_degrees(gp_ctx* ctx, const gp_graph* g);
+// dL/dd per edge from the gradients with respect to the Bessel radial basis and the radial part of the spherical basis of
+// the Hadamard variant (basis.hip; either gradient may be NULL)
+int gp_grad_dist_bessel(gp_ctx* ctx, const gp_dims* dims, const float* dist, const float* grad_rbf, const float* grad_rad,
+                        int64_t n_edges, float* gd);
 // GP_BAD_ARG (and a message) if an earlier call on this context left a deferred error; clears it.
 int gp_take_deferred(gp_ctx* ctx, const char* who);
 

@@ -429,14 +429,19 @@ int gp_forces_workspace(int64_t n_edges, int64_t n_triplets, size_t* bytes) {
   return GP_OK;
 }
 
-int gp_forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* graph, const int32_t* perm_kj,
-                              const int32_t* row_ptr, const int32_t* out_ptr, const int32_t* out_list,
-                              int64_t n_atoms, const float* dist, const float* unit, const float* grad_rbf,
-                              const float* grad_cos_kj, float* forces, void* ws, size_t ws_bytes) {
+}  // extern "C"
+
+namespace {
+// variant G: grad_rad is NULL and the radial basis is the Gaussian one; variant D: Bessel radial basis and the radial
+// part of the spherical basis
+int forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* graph, const int32_t* perm_kj,
+                           const int32_t* row_ptr, const int32_t* out_ptr, const int32_t* out_list,
+                           int64_t n_atoms, const float* dist, const float* unit, const float* grad_rbf, const float* grad_rad,
+                           const float* grad_cos_kj, float* forces, void* ws, size_t ws_bytes) {
   if (!ctx) return GP_BAD_ARG;
   GP_REQUIRE(ctx, dims && graph, "gp_forces_from_basis_grad: dims/graph is NULL");
-  if (dims->variant != GP_VARIANT_G)
-    return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "gp_forces_from_basis_grad: only the Gaussian radial basis (variant G) is implemented");
+  const bool bessel = dims->variant == GP_VARIANT_D;
+  if (!bessel && dims->variant != GP_VARIANT_G) return gp_fail(ctx, GP_BAD_ARG, "gp_forces_from_basis_grad: unknown variant %d", dims->variant);
   const int64_t E = graph->n_edges, T = graph->n_triplets;
   GP_REQUIRE(ctx, n_atoms >= 0 && E >= 0 && T >= 0, "gp_forces_from_basis_grad: negative size");
   if (n_atoms == 0) return GP_OK;
@@ -448,13 +453,15 @@ int gp_forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* 
     GP_LAUNCH_CHECK(ctx, "fill_kernel");
     return GP_OK;
   }
-  GP_REQUIRE(ctx, out_list && dist && unit && grad_rbf && ws, "gp_forces_from_basis_grad: NULL pointer");
+  GP_REQUIRE(ctx, out_list && dist && unit && grad_rbf && ws && (!bessel || grad_rad), "gp_forces_from_basis_grad: NULL pointer");
   GP_REQUIRE(ctx, T == 0 || (grad_cos_kj && perm_kj && graph->idx_kj && graph->seg_ptr_ji && graph->idx_ji_kj && graph->seg_ptr_kj),
              "gp_forces_from_basis_grad: triplet arrays missing");
   forces_ws w;
   if (ws_bytes < carve_forces(ws, E, T, &w)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_forces_from_basis_grad: workspace too small");
-  grad_dist_gauss_kernel<<<wblk(E), 256, 0, st>>>(dist, grad_rbf, E, dims->num_radial, dims->envelope_p,
-                                                  (double)dims->cutoff, w.gd);
+  if (bessel) GP_TRY(gp_grad_dist_bessel(ctx, dims, dist, grad_rbf, grad_rad, E, w.gd));
+  else
+    grad_dist_gauss_kernel<<<wblk(E), 256, 0, st>>>(dist, grad_rbf, E, dims->num_radial, dims->envelope_p,
+                                                    (double)dims->cutoff, w.gd);
   if (T > 0) {
     unpermute_kernel<<<nblk(T), 256, 0, st>>>(grad_cos_kj, perm_kj, T, w.gc_ji);
     // cos = -unit[ji].unit[kj]: d/d unit[ji] = -unit[kj] (ji-major walk), d/d unit[kj] = -unit[ji] (kj-major walk)
@@ -467,6 +474,32 @@ int gp_forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* 
   atom_force_kernel<<<wblk(n_atoms), 256, 0, st>>>(w.dv, row_ptr, out_ptr, out_list, n_atoms, forces);
   GP_LAUNCH_CHECK(ctx, "force kernels");
   return GP_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int gp_forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* graph, const int32_t* perm_kj,
+                              const int32_t* row_ptr, const int32_t* out_ptr, const int32_t* out_list,
+                              int64_t n_atoms, const float* dist, const float* unit, const float* grad_rbf,
+                              const float* grad_cos_kj, float* forces, void* ws, size_t ws_bytes) {
+  if (!ctx) return GP_BAD_ARG;
+  if (dims && dims->variant != GP_VARIANT_G)
+    return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "gp_forces_from_basis_grad: the Gaussian radial basis (variant G); variant D has "
+                   "gp_forces_from_basis_grad_D");
+  return forces_from_basis_grad(ctx, dims, graph, perm_kj, row_ptr, out_ptr, out_list, n_atoms, dist, unit, grad_rbf, nullptr,
+                                grad_cos_kj, forces, ws, ws_bytes);
+}
+
+int gp_forces_from_basis_grad_D(gp_ctx* ctx, const gp_dims* dims, const gp_graph* graph, const int32_t* perm_kj,
+                                const int32_t* row_ptr, const int32_t* out_ptr, const int32_t* out_list,
+                                int64_t n_atoms, const float* dist, const float* unit, const float* grad_rbf,
+                                const float* grad_rad, const float* grad_cos_kj, float* forces, void* ws, size_t ws_bytes) {
+  if (!ctx) return GP_BAD_ARG;
+  if (dims && dims->variant != GP_VARIANT_D)
+    return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "gp_forces_from_basis_grad_D: the Bessel bases of variant D");
+  return forces_from_basis_grad(ctx, dims, graph, perm_kj, row_ptr, out_ptr, out_list, n_atoms, dist, unit, grad_rbf, grad_rad,
+                                grad_cos_kj, forces, ws, ws_bytes);
 }
 
 }  // extern "C"

@@ -167,3 +167,39 @@ def test_forces_cfg5_model_on_a_box_the_oracle_can_follow(lib, ctx):
     assert abs(E_gpu.sum() - E_ref) <= 2e-2 * max(1.0, abs(E_ref))
     assert H.rel_l2(f_gpu, f_ref) <= 2e-2, H.rel_l2(f_gpu, f_ref)
     assert err <= 4 * 2e-2 * np.abs(f_ref).max()
+
+
+@pytest.mark.parametrize("triplet_mode", [-1, 0], ids=["library's choice of triplet kernels", "per-edge triplet kernels"])
+def test_forces_variant_D(lib, ctx, triplet_mode):
+    """Forces of the Hadamard (DimeNet++-style, energy-centric) model, Sec. 3.2/3.3: two blocks + head on two capped
+    structures at configuration 2's widths, against automatic differentiation of the oracle's energy through the Bessel
+    radial basis, the spherical basis and cos(alpha)."""
+    from paper_2203_09697_amd.binding_e import ForceModelD
+    w = synth.get_workload("cfg2")
+    dims = w.dims
+    pos, gptr = synth.slab_adsorbate_positions(2, 3, 3, 3, 8, seed=21)
+    ref = H.oracle_graph(pos, gptr, dims.cutoff, w.max_neighbors)
+    e, t = lib.build_graph(ctx, H.to_dev(pos, torch.float32), H.to_dev(gptr, torch.int32), dims.cutoff, w.max_neighbors)
+    assert np.array_equal(t["idx_kj"].cpu().numpy(), ref["idx_kj"])
+    E, hidden = len(ref["src"]), 16
+    W_list = [synth.weights_D(dims, seed=400 + b, bias_scale=0.1) for b in range(2)]
+    Wh = synth.weights_head(dims.emb, hidden, seed=5, bias_scale=0.1)
+    m0, _ = synth.edge_embeddings(E, dims.emb, seed=9)
+    lib.gp_set_triplet_mfma(ctx, triplet_mode)
+    try:
+        gb = lib.gp_basis_forward(ctx, dims, e, t)
+        model = ForceModelD(ctx, dims, [lib.weights_to_device(W) for W in W_list], lib.weights_to_device(Wh), hidden, e, t, gb,
+                            H.to_dev(gptr, torch.int32))
+        energy, forces = model.energy_and_forces(H.to_dev(m0, torch.float32))
+        torch.cuda.synchronize()
+    finally:
+        lib.gp_set_triplet_mfma(ctx, -1)
+    E_ref, f_ref = oenergy.forces(oenergy.energy_D, pos, ref["src"], ref["dst"], ref["idx_kj"], ref["idx_ji"],
+                                  torch.tensor(m0, dtype=torch.float64), [H.t64(W) for W in W_list], H.t64(Wh), dims)
+    f_gpu = forces.cpu().numpy()
+    scale = np.abs(f_ref).max()
+    print("variant D forces: E=%d max|f|=%.4e max-abs error=%.3e rel-L2=%.2e" % (E, scale, np.abs(f_gpu - f_ref).max(), H.rel_l2(f_gpu, f_ref)))
+    assert abs(energy.cpu().numpy().sum() - E_ref) <= 1e-4 * max(1.0, abs(E_ref))
+    assert H.rel_l2(f_gpu, f_ref) <= 1e-4
+    assert np.abs(f_gpu - f_ref).max() <= 2e-4 * scale
+    assert np.abs(f_gpu.sum(axis=0)).max() <= 1e-4 * scale * np.sqrt(len(pos))
