@@ -135,3 +135,17 @@ int gp_deferred_status(gp_ctx* ctx) {
 const char* gp_last_error(const gp_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 
 }  // extern "C"
+
+namespace {
+__global__ void zero_words_kernel(uint32_t* __restrict__ p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+}  // namespace
+
+int gp_zero_async(hipStream_t st, void* p, size_t bytes) {
+  const size_t n = bytes / 4;
+  if (n == 0) return (int)hipSuccess;
+  zero_words_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(static_cast<uint32_t*>(p), n);
+  return (int)hipGetLastError();
+}

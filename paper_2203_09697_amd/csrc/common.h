@@ -44,6 +44,9 @@ struct gp_ctx {
 
 // Launches the check of gp_graph.max_in_degree / max_out_degree against the lists (sets the deferred-error word).
 int gp_check_degrees(gp_ctx* ctx, const gp_graph* g);
+// Clears `bytes` (a multiple of 4) of device memory with a kernel on `st`.  The library records no memset nodes: a caller
+// may capture its calls in a HIP graph, and memset nodes have given wrong results on replays on this target.
+int gp_zero_async(hipStream_t st, void* p, size_t bytes);
 // dL/dd per edge from the gradients with respect to the Bessel radial basis and the radial part of the spherical basis of
 // the Hadamard variant (basis.hip; either gradient may be NULL)
 int gp_grad_dist_bessel(gp_ctx* ctx, const gp_dims* dims, const float* dist, const float* grad_rbf, const float* grad_rad,

@@ -338,7 +338,7 @@ int gp_edges_by_source(gp_ctx* ctx, const int32_t* src, int64_t n_atoms, int64_t
   GP_HIP(ctx, hipSetDevice(ctx->device));
   hipStream_t st = ctx->stream;
   if (n_atoms == 0 || n_edges == 0) {
-    GP_HIP(ctx, hipMemsetAsync(out_ptr, 0, sizeof(int32_t) * (n_atoms + 1), st));
+    GP_HIP(ctx, (hipError_t)gp_zero_async(st, out_ptr, sizeof(int32_t) * (n_atoms + 1)));
     return GP_OK;
   }
   GP_REQUIRE(ctx, src && out_list && ws, "gp_edges_by_source: NULL pointer");
@@ -349,8 +349,8 @@ int gp_edges_by_source(gp_ctx* ctx, const int32_t* src, int64_t n_atoms, int64_t
   int32_t* cnt = c.take<int32_t>(n_atoms);
   int32_t* cursor = c.take<int32_t>(n_atoms);
   int32_t* tmp = c.take<int32_t>(n_edges);
-  GP_HIP(ctx, hipMemsetAsync(cnt, 0, sizeof(int32_t) * n_atoms, st));
-  GP_HIP(ctx, hipMemsetAsync(cursor, 0, sizeof(int32_t) * n_atoms, st));
+  GP_HIP(ctx, (hipError_t)gp_zero_async(st, cnt, sizeof(int32_t) * n_atoms));
+  GP_HIP(ctx, (hipError_t)gp_zero_async(st, cursor, sizeof(int32_t) * n_atoms));
   hist_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, cnt);
   scan_small_kernel<<<1, 1024, 0, st>>>(cnt, n_atoms, out_ptr);
   scatter_by_key_kernel<<<nblk(n_edges), 256, 0, st>>>(src, n_edges, out_ptr, cursor, tmp);
@@ -380,8 +380,11 @@ int gp_energy_forward(gp_ctx* ctx, int32_t emb, int32_t hidden, const gp_weights
   if (saved_bytes < carve_head_saved(saved, n_atoms, emb, hidden, &s)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_energy_forward: saved buffer too small");
   GP_HIP(ctx, hipSetDevice(ctx->device));
   hipStream_t st = ctx->stream;
-  atom_sum_kernel<<<wblk(n_atoms * ((emb + 63) / 64)), 256, 0, st>>>(m, row_ptr, n_atoms, emb, s.h);
-  GP_LAUNCH_CHECK(ctx, "atom_sum_kernel");
+  {
+    gp_prof_scope prof(ctx, "head_atom_sum", 0.0, 0.0);   // the number of edges is not known here: time only
+    atom_sum_kernel<<<wblk(n_atoms * ((emb + 63) / 64)), 256, 0, st>>>(m, row_ptr, n_atoms, emb, s.h);
+    GP_LAUNCH_CHECK(ctx, "atom_sum_kernel");
+  }
   gp_epilogue e;
   e.bias = w->b1; e.save_pre = s.z1; e.act = 1; e.out = s.a1;
   GP_TRY(gp_gemm_nn(ctx, s.h, w->W1, n_atoms, hidden, emb, e));
@@ -409,6 +412,7 @@ int gp_energy_backward(gp_ctx* ctx, int32_t emb, int32_t hidden, const gp_weight
   e.out = sc.dh;
   GP_TRY(gp_gemm_nt(ctx, sc.dz1, w->W1, n_atoms, emb, hidden, e));
   if (n_edges > 0) {
+    gp_prof_scope prof(ctx, "head_gather_rows", 0.0, 4.0 * (double)emb * ((double)n_edges + (double)n_atoms));
     gather_rows_kernel<<<nblk(n_edges * emb), 256, 0, st>>>(sc.dh, dst, n_edges, emb, grad_m);
     GP_LAUNCH_CHECK(ctx, "gather_rows_kernel");
   }
@@ -463,8 +467,12 @@ int forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* gra
     grad_dist_gauss_kernel<<<wblk(E), 256, 0, st>>>(dist, grad_rbf, E, dims->num_radial, dims->envelope_p,
                                                     (double)dims->cutoff, w.gd);
   if (T > 0) {
-    unpermute_kernel<<<nblk(T), 256, 0, st>>>(grad_cos_kj, perm_kj, T, w.gc_ji);
+    {
+      gp_prof_scope prof(ctx, "forces_reorder_cos", 0.0, 12.0 * (double)T);
+      unpermute_kernel<<<nblk(T), 256, 0, st>>>(grad_cos_kj, perm_kj, T, w.gc_ji);
+    }
     // cos = -unit[ji].unit[kj]: d/d unit[ji] = -unit[kj] (ji-major walk), d/d unit[kj] = -unit[ji] (kj-major walk)
+    gp_prof_scope prof(ctx, "forces_edge_sums", 12.0 * (double)T, 16.0 * (double)T);
     edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_ji, graph->idx_kj, w.gc_ji, unit, E, 0, w.gu);
     edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_kj, graph->idx_ji_kj, grad_cos_kj, unit, E, 1, w.gu);
   } else {

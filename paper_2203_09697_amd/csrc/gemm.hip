@@ -565,8 +565,8 @@ int gp_gemm_tn(gp_ctx* ctx, const float* A, const float* B, int64_t rows, int M,
   GP_REQUIRE(ctx, !colsum_out || !(a_bf16 || b_bf16), "gemm_tn: column sums need fp32 operands");
   GP_REQUIRE(ctx, A && B && out && rows >= 0 && M > 0 && N > 0, "gemm_tn: bad arguments");
   if (rows == 0) {
-    GP_HIP(ctx, hipMemsetAsync(out, 0, sizeof(float) * M * N, ctx->stream));
-    if (colsum_out) GP_HIP(ctx, hipMemsetAsync(colsum_out, 0, sizeof(float) * N, ctx->stream));
+    GP_HIP(ctx, (hipError_t)gp_zero_async(ctx->stream, out, sizeof(float) * M * N));
+    if (colsum_out) GP_HIP(ctx, (hipError_t)gp_zero_async(ctx->stream, colsum_out, sizeof(float) * N));
     return GP_OK;
   }
   if (rows > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "gemm_tn: too many rows");

@@ -632,7 +632,7 @@ int edges_fill_impl(gp_ctx* ctx, const char* who, const float* pos, const int32_
   if (n_atoms > INT32_MAX - 1 || n_edges > INT32_MAX) return gp_fail(ctx, GP_INT32_OVERFLOW, "%s: sizes exceed int32", who);
   GP_HIP(ctx, hipSetDevice(ctx->device));
   if (n_atoms == 0 || n_graphs == 0) {
-    GP_HIP(ctx, hipMemsetAsync(row_ptr, 0, sizeof(int32_t) * (n_atoms + 1), ctx->stream));
+    GP_HIP(ctx, (hipError_t)gp_zero_async(ctx->stream, row_ptr, sizeof(int32_t) * (n_atoms + 1)));
     return GP_OK;
   }
   GP_REQUIRE(ctx, pos && graph_ptr && ws, "%s: NULL pointer", who);
@@ -715,8 +715,8 @@ int triplets_count_impl(gp_ctx* ctx, const int32_t* src, const int32_t* dst, con
   if (ws_bytes < need) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "gp_triplets_count: workspace %zu < %zu", ws_bytes, need);
   GP_HIP(ctx, hipSetDevice(ctx->device));
   hipStream_t st = ctx->stream;
-  GP_HIP(ctx, hipMemsetAsync(w.out_deg, 0, sizeof(int32_t) * n_atoms, st));
-  GP_HIP(ctx, hipMemsetAsync(w.cursor, 0, sizeof(int32_t) * n_atoms, st));
+  GP_HIP(ctx, (hipError_t)gp_zero_async(st, w.out_deg, sizeof(int32_t) * n_atoms));
+  GP_HIP(ctx, (hipError_t)gp_zero_async(st, w.cursor, sizeof(int32_t) * n_atoms));
   triplet_count_kernel<<<blocks_for(n_edges, 256), 256, 0, st>>>(src, dst, offset, row_ptr, (int)n_edges, w.cnt, w.skip, w.out_deg);
   GP_LAUNCH_CHECK(ctx, "triplet_count_kernel");
   GP_TRY(scan_exclusive(ctx, w.cnt, w.seg_ji, n_edges, w.totals + 0, w.scan_tmp));
@@ -742,8 +742,8 @@ int triplets_fill_impl(gp_ctx* ctx, const int32_t* src, const int32_t* dst, cons
   GP_HIP(ctx, hipSetDevice(ctx->device));
   hipStream_t st = ctx->stream;
   if (n_edges == 0 || n_atoms == 0) {
-    GP_HIP(ctx, hipMemsetAsync(seg_ptr_ji, 0, sizeof(int32_t) * (n_edges + 1), st));
-    if (seg_ptr_kj) GP_HIP(ctx, hipMemsetAsync(seg_ptr_kj, 0, sizeof(int32_t) * (n_edges + 1), st));
+    GP_HIP(ctx, (hipError_t)gp_zero_async(st, seg_ptr_ji, sizeof(int32_t) * (n_edges + 1)));
+    if (seg_ptr_kj) GP_HIP(ctx, (hipError_t)gp_zero_async(st, seg_ptr_kj, sizeof(int32_t) * (n_edges + 1)));
     return GP_OK;
   }
   GP_REQUIRE(ctx, src && dst && row_ptr && ws, "gp_triplets_fill: NULL pointer");
@@ -758,7 +758,7 @@ int triplets_fill_impl(gp_ctx* ctx, const int32_t* src, const int32_t* dst, cons
   }
   if (!want_kj) return GP_OK;
   GP_TRY(scan_exclusive(ctx, w.out_deg, w.out_ptr, n_atoms, w.totals + 1, nullptr));
-  GP_HIP(ctx, hipMemsetAsync(w.cursor, 0, sizeof(int32_t) * n_atoms, st));
+  GP_HIP(ctx, (hipError_t)gp_zero_async(st, w.cursor, sizeof(int32_t) * n_atoms));
   out_scatter_kernel<<<blocks_for(n_edges, 256), 256, 0, st>>>(src, (int)n_edges, w.out_ptr, w.cursor, w.out_tmp);
   GP_LAUNCH_CHECK(ctx, "out_scatter_kernel");
   out_sort_kernel<<<(unsigned)n_atoms, 256, 0, st>>>(w.out_ptr, w.out_tmp, (int)n_atoms, w.out_list);

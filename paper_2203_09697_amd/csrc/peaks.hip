@@ -91,7 +91,7 @@ int gp_measure_peaks(gp_ctx* ctx, void* ws, size_t ws_bytes, double* copy_gbps, 
       return GP_HIP_ERROR;
     return GP_OK;
   };
-  if (hipMemsetAsync(ws, 0, half, st) != hipSuccess) rc = GP_HIP_ERROR;
+  if (gp_zero_async(st, ws, half) != (int)hipSuccess) rc = GP_HIP_ERROR;
   if (rc == GP_OK) rc = timed([&] { peak_copy_kernel<<<256 * 16, 256, 0, st>>>((const f32x4*)src, (f32x4*)dst, n16); });
   if (rc == GP_OK) *copy_gbps = 2.0 * (double)half * reps / (ms * 1e-3) / 1e9;
   const int blocks = 256 * 8;   // 8 workgroups of 4 wavefronts per CU

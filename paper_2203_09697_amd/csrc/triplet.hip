@@ -484,8 +484,8 @@ int gp_tripD_weight_grads(gp_ctx* ctx, const float* grad_a, const float* Bacc, c
   if (!part || part_bytes < gp_tripD_wgrad_scratch(E, F, S, R, B))
     return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "triplet D weight grads: scratch too small");
   if (E == 0) {
-    GP_HIP(ctx, hipMemsetAsync(grad_W2, 0, sizeof(float) * B * F, ctx->stream));
-    GP_HIP(ctx, hipMemsetAsync(grad_W1, 0, sizeof(float) * S * R * B, ctx->stream));
+    GP_HIP(ctx, (hipError_t)gp_zero_async(ctx->stream, grad_W2, sizeof(float) * B * F));
+    GP_HIP(ctx, (hipError_t)gp_zero_async(ctx->stream, grad_W1, sizeof(float) * S * R * B));
     return GP_OK;
   }
   if (Bacc) {   // NULL: grad_W2 comes from the matrix-core backward kernel
