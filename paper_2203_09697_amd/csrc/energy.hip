@@ -144,6 +144,17 @@ __global__ void gather_rows_kernel(const float* __restrict__ dh, const int32_t* 
   const int64_t e = i / H;
   gm[i] = dh[(int64_t)dst[e] * H + (i % H)];
 }
+// the same for H % 4 == 0: one wavefront per edge row, 16 bytes per lane and step (the source rows are few and stay cached;
+// the [E, H] result is a pure write stream)
+__global__ void __launch_bounds__(256)
+gather_rows4_kernel(const float* __restrict__ dh, const int32_t* __restrict__ dst, int64_t n_edges, int H, float* __restrict__ gm) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  const int64_t e = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+  if (e >= n_edges) return;
+  const f4* src = reinterpret_cast<const f4*>(dh + (int64_t)dst[e] * H);
+  f4* out = reinterpret_cast<f4*>(gm + e * H);
+  for (int i = threadIdx.x & 63; i < H / 4; i += 64) __builtin_nontemporal_store(src[i], out + i);
+}
 __global__ void fill_kernel(float* p, int64_t n, float v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -195,6 +206,58 @@ edge_unit_grad_kernel(const int32_t* __restrict__ seg, const int32_t* __restrict
     float* o = gu + 3 * e;
     if (accumulate) { o[0] += sx; o[1] += sy; o[2] += sz; }
     else { o[0] = sx; o[1] = sy; o[2] = sz; }
+  }
+}
+// The ji-major walk without reordering grad cos: for centre atom j the triplets (in-edge row p, out-list position n)
+// form a d_in x d_out matrix stored by rows (kj-major) with one position left out per row; the sum over the triplets of
+// out-edge e = out_list[n] is a column sum of it.  gap[e'] = the left-out position of row e' (the number of positions
+// if none), one binary search per in-edge.
+__global__ void __launch_bounds__(256)
+row_gap_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
+               const int32_t* __restrict__ seg_kj, const int32_t* __restrict__ idx_ji_kj, int32_t* __restrict__ gap) {
+  const int j = blockIdx.x;
+  const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
+  const int32_t* outs = out_list + out_ptr[j];
+  for (int p = threadIdx.x; p < d; p += 256) {
+    const int seg = seg_kj[r0 + p], cnt = seg_kj[r0 + p + 1] - seg;
+    int lo = 0, hi = cnt;   // first slot whose target edge is not the out-list entry of the same position
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (idx_ji_kj[seg + mid] == outs[mid]) lo = mid + 1;
+      else hi = mid;
+    }
+    gap[r0 + p] = lo;
+  }
+}
+// gu[e, :] = -sum_{rows p of j} gc_kj[(p, n)] unit[e'_p, :] for e = out_list[out_ptr[j] + n]; workgroup = (atom, 64 positions),
+// lanes over positions (consecutive triplets of a row), the four wavefronts over rows
+__global__ void __launch_bounds__(256)
+edge_unit_grad_cols_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
+                           const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_kj, const int32_t* __restrict__ gap,
+                           const float* __restrict__ gc_kj, int64_t T, const float* __restrict__ unit, float* __restrict__ gu) {
+  const int j = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int ob = out_ptr[j], dout = out_ptr[j + 1] - ob;
+  const int n = 64 * (int)blockIdx.y + lane;
+  if (64 * (int)blockIdx.y >= dout) return;
+  const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
+  float sx = 0.f, sy = 0.f, sz = 0.f;
+  for (int p = wv; p < d; p += 4) {
+    const int e1 = r0 + p, seg = seg_kj[e1], gp = gap[e1];
+    const bool valid = n < dout && n != gp;
+    int64_t at = valid ? seg + n - (n > gp ? 1 : 0) : seg;
+    at = at < T ? at : T - 1;                                       // a row without triplets at the very end
+    const float g = gc_kj[at] * (valid ? 1.f : 0.f);                // unconditional load
+    const float* u = unit + 3 * (int64_t)e1;
+    sx -= g * u[0]; sy -= g * u[1]; sz -= g * u[2];
+  }
+  __shared__ float red[3][3][64];
+  if (wv > 0) { red[wv - 1][0][lane] = sx; red[wv - 1][1][lane] = sy; red[wv - 1][2][lane] = sz; }
+  __syncthreads();
+  if (wv == 0 && n < dout) {
+#pragma unroll
+    for (int k = 0; k < 3; ++k) { sx += red[k][0][lane]; sy += red[k][1][lane]; sz += red[k][2][lane]; }
+    float* o = gu + 3 * (int64_t)out_list[ob + n];
+    o[0] = sx; o[1] = sy; o[2] = sz;
   }
 }
 // dv[e,:] = (gu - (gu.u) u) / d + gd * u   (gradient w.r.t. the edge vector x_dst - x_src)
@@ -258,11 +321,13 @@ size_t carve_head_scratch(void* p, int64_t N, int H, int K, head_scratch* s) {
 }
 struct forces_ws {
   float *gd, *gc_ji, *gu, *dv;
+  int32_t* gap;
 };
 size_t carve_forces(void* p, int64_t E, int64_t T, forces_ws* w) {
   gp_carver c(p);
   w->gd = c.take<float>(E);
   w->gc_ji = c.take<float>(T);
+  w->gap = c.take<int32_t>(E);
   w->gu = c.take<float>(3 * E);
   w->dv = c.take<float>(3 * E);
   return c.off;
@@ -413,7 +478,10 @@ int gp_energy_backward(gp_ctx* ctx, int32_t emb, int32_t hidden, const gp_weight
   GP_TRY(gp_gemm_nt(ctx, sc.dz1, w->W1, n_atoms, emb, hidden, e));
   if (n_edges > 0) {
     gp_prof_scope prof(ctx, "head_gather_rows", 0.0, 4.0 * (double)emb * ((double)n_edges + (double)n_atoms));
-    gather_rows_kernel<<<nblk(n_edges * emb), 256, 0, st>>>(sc.dh, dst, n_edges, emb, grad_m);
+    if (emb % 4 == 0 && (reinterpret_cast<uintptr_t>(grad_m) & 15) == 0 && (reinterpret_cast<uintptr_t>(sc.dh) & 15) == 0)
+      gather_rows4_kernel<<<wblk(n_edges), 256, 0, st>>>(sc.dh, dst, n_edges, emb, grad_m);
+    else
+      gather_rows_kernel<<<nblk(n_edges * emb), 256, 0, st>>>(sc.dh, dst, n_edges, emb, grad_m);
     GP_LAUNCH_CHECK(ctx, "gather_rows_kernel");
   }
   if (grad_w) {
@@ -467,13 +535,17 @@ int forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* gra
     grad_dist_gauss_kernel<<<wblk(E), 256, 0, st>>>(dist, grad_rbf, E, dims->num_radial, dims->envelope_p,
                                                     (double)dims->cutoff, w.gd);
   if (T > 0) {
-    {
-      gp_prof_scope prof(ctx, "forces_reorder_cos", 0.0, 12.0 * (double)T);
-      unpermute_kernel<<<nblk(T), 256, 0, st>>>(grad_cos_kj, perm_kj, T, w.gc_ji);
-    }
     // cos = -unit[ji].unit[kj]: d/d unit[ji] = -unit[kj] (ji-major walk), d/d unit[kj] = -unit[ji] (kj-major walk)
-    gp_prof_scope prof(ctx, "forces_edge_sums", 12.0 * (double)T, 16.0 * (double)T);
-    edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_ji, graph->idx_kj, w.gc_ji, unit, E, 0, w.gu);
+    gp_prof_scope prof(ctx, "forces_edge_sums", 12.0 * (double)T, 12.0 * (double)T);
+    if (graph->max_out_degree > 0) {
+      // the ji-major walk as column sums over the kj-major order: no reordered copy of grad cos
+      row_gap_kernel<<<(unsigned)n_atoms, 256, 0, st>>>(row_ptr, out_ptr, out_list, graph->seg_ptr_kj, graph->idx_ji_kj, w.gap);
+      edge_unit_grad_cols_kernel<<<dim3((unsigned)n_atoms, (unsigned)((graph->max_out_degree + 63) / 64)), 256, 0, st>>>(
+          row_ptr, out_ptr, out_list, graph->seg_ptr_kj, w.gap, grad_cos_kj, T, unit, w.gu);
+    } else {
+      unpermute_kernel<<<nblk(T), 256, 0, st>>>(grad_cos_kj, perm_kj, T, w.gc_ji);
+      edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_ji, graph->idx_kj, w.gc_ji, unit, E, 0, w.gu);
+    }
     edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_kj, graph->idx_ji_kj, grad_cos_kj, unit, E, 1, w.gu);
   } else {
     fill_kernel<<<nblk(3 * E), 256, 0, st>>>(w.gu, 3 * E, 0.f);
