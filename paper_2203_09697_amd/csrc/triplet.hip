@@ -617,6 +617,79 @@ edge_G_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64
   }
 }
 
+// The same product written as bf16 for O = 32, 64 or 128: the edge's S x O block of H (fp32, contiguous) goes once
+// through the wavefront's LDS slice, a lane owns (c, 8 consecutive o) pieces of the edge's C x O result (contiguous)
+// and writes each with one 16-byte store instead of C stores of 2 bytes per lane.
+template <int O>
+__global__ void __launch_bounds__(WPB* WAVE)
+edge_G16_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64_t E, int S, int C, __bf16* __restrict__ Gout) {
+  typedef __bf16 h8 __attribute__((ext_vector_type(8)));
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  constexpr int CH = O / 8;
+  constexpr int NV = (ST * O / 4 + WAVE - 1) / WAVE;   // 16-byte pieces of the H block per lane
+  extern __shared__ float dyn_s[];                     // rad_s[(l*C + c) * EG_EDGES + edge]
+  __shared__ __attribute__((aligned(16))) float H_s[WPB][2][ST * O];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int64_t e0 = (int64_t)blockIdx.x * EG_EDGES;
+  {
+    constexpr int PASSES = ST * 16 * EG_EDGES / (WPB * WAVE);
+    float r[PASSES];
+    const int n = S * C * EG_EDGES;
+#pragma unroll
+    for (int k = 0; k < PASSES; ++k) {
+      const int i = threadIdx.x + k * WPB * WAVE;
+      const int ic = i < n ? i : n - 1;
+      const int64_t e = e0 + (ic & (EG_EDGES - 1));
+      r[k] = Radt[(int64_t)(ic / EG_EDGES) * E + (e < E ? e : E - 1)];
+    }
+#pragma unroll
+    for (int k = 0; k < PASSES; ++k) {
+      const int i = threadIdx.x + k * WPB * WAVE;
+      if (i < n) dyn_s[i] = e0 + (i & (EG_EDGES - 1)) < E ? r[k] : 0.f;
+    }
+  }
+  __syncthreads();
+  const int n_piece = S * O / 4;
+  auto fetch = [&](int el, f4 (&v)[NV]) __attribute__((always_inline)) {
+    const int64_t e = e0 + el < E ? e0 + el : E - 1;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int i = lane + WAVE * k;
+      v[k] = *reinterpret_cast<const f4*>(H + e * S * O + 4 * (i < n_piece ? i : 0));
+    }
+  };
+  f4 vn[NV];
+  if (e0 + w < E) fetch(w, vn);
+  int buf = 0;
+  for (int el = w; el < EG_EDGES && e0 + el < E; el += WPB, buf ^= 1) {
+    float* hs = H_s[w][buf];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int i = lane + WAVE * k;
+      if (i < n_piece) *reinterpret_cast<f4*>(hs + 4 * i) = vn[k];
+    }
+    if (el + WPB < EG_EDGES && e0 + el + WPB < E) fetch(el + WPB, vn);
+    wave_lds_sync();
+    const int64_t e = e0 + el;
+    for (int item = lane; item < C * CH; item += WAVE) {
+      const int c = item / CH, oc = item % CH;
+      float acc[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+      for (int l = 0; l < S; ++l) {
+        const float r = dyn_s[(l * C + c) * EG_EDGES + el];
+        const f4 a = *reinterpret_cast<const f4*>(hs + l * O + 8 * oc), b = *reinterpret_cast<const f4*>(hs + l * O + 8 * oc + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] += r * a[i], acc[4 + i] += r * b[i];
+      }
+      h8 out;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) out[i] = (__bf16)acc[i];
+      *reinterpret_cast<h8*>(Gout + (e * C + c) * O + 8 * oc) = out;
+    }
+  }
+}
+
 __global__ void __launch_bounds__(WPB* WAVE)
 edge_dRad_kernel(const float* __restrict__ V, const float* __restrict__ H, int64_t E, int S, int C, int O,
                  float* __restrict__ dRad) {
@@ -739,8 +812,15 @@ int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, i
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, Radt && H && Gout && S >= 1 && S <= ST && C >= 1 && C <= 16 && O >= 1, "edge_G: bad arguments");
   gp_prof_scope prof(ctx, "tripG_edge_G", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
-  edge_G_kernel<<<(unsigned)((E + EG_EDGES - 1) / EG_EDGES), WPB * WAVE, (size_t)S * C * EG_EDGES * sizeof(float), ctx->stream>>>(
-      Radt, H, E, S, C, O, out_half, Gout);
+  const unsigned blocks = (unsigned)((E + EG_EDGES - 1) / EG_EDGES);
+  const size_t lds = (size_t)S * C * EG_EDGES * sizeof(float);
+  if (out_half && (O == 32 || O == 64 || O == 128) && ((reinterpret_cast<uintptr_t>(H) | reinterpret_cast<uintptr_t>(Gout)) & 15) == 0) {
+    __bf16* Gh = reinterpret_cast<__bf16*>(Gout);
+    if (O == 32) edge_G16_kernel<32><<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, H, E, S, C, Gh);
+    else if (O == 64) edge_G16_kernel<64><<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, H, E, S, C, Gh);
+    else edge_G16_kernel<128><<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, H, E, S, C, Gh);
+  } else
+    edge_G_kernel<<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, H, E, S, C, O, out_half, Gout);
   GP_LAUNCH_CHECK(ctx, "edge_G_kernel");
   return GP_OK;
 }
