@@ -140,9 +140,10 @@ def main():
     ap.add_argument("--output-blocks", action="store_true",
                     help="variant-D workloads: add an output block (out_emb 256, 3 layers) after every interaction "
                          "block and differentiate the summed energies instead of a random upstream gradient")
-    ap.add_argument("--trip-mode", type=int, default=-1, choices=[-1, 0, 1, 2],
+    ap.add_argument("--trip-mode", type=int, default=-1, choices=[-1, 0, 1, 2, 3],
                     help="variant-G triplet kernels: -1 the library's own choice, 0 per-edge vector kernels, 1 matrix-core "
-                         "kernels per centre atom, 2 the two-kernel forward and whole-atom backward forms")
+                         "kernels per centre atom, 2 the two-kernel forward and whole-atom backward forms, 3 the one-pass "
+                         "forward kernel with y evaluated on the vector units")
     ap.add_argument("--no-side-stream", action="store_true", help="weight-gradient GEMMs on the launch stream")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run one 256 MiB device copy first (known traffic, to scale rocprofv3 byte counters)")

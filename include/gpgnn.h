@@ -60,8 +60,10 @@ int gp_set_side_stream(gp_ctx* ctx, int on);
  * cores.  mode 1: whenever the widths allow; 0: never (one wavefront per edge on the vector
  * units); -1 (default): only for graphs with at least 96 triplets per edge on average, where the
  * dense form pays; 2: as 1, but the forward sum in its two-kernel form (a kernel writes the per-triplet
- * basis projection y in bf16, a second one contracts it) instead of the one-pass kernel that evaluates y in
- * registers (kept for comparison).  GP_TRIPLET_MFMA=0/1/2 in the environment sets the mode at gp_create. */
+ * basis projection y in bf16, a second one contracts it) instead of the one-pass kernel (kept for comparison);
+ * 3: as 1, but the one-pass forward kernel evaluates y on the vector units (Horner's rule per value) instead of
+ * forming it with a first matrix-core product (kept for comparison).  GP_TRIPLET_MFMA=0..3 in the environment
+ * sets the mode at gp_create. */
 int gp_set_triplet_mfma(gp_ctx* ctx, int mode);
 
 /* Errors that only a kernel can detect are deferred: a block call given gp_graph.max_in_degree / max_out_degree

@@ -61,7 +61,7 @@ int gp_create(gp_ctx** out, int device_id, void* hip_stream) {
   const char* no_aux = getenv("GP_NO_AUX_STREAM");
   c->use_aux = !(no_aux && no_aux[0] == '1');
   const char* tm = getenv("GP_TRIPLET_MFMA");
-  if (tm && tm[0] >= '0' && tm[0] <= '2') c->trip_mfma = tm[0] - '0';
+  if (tm && tm[0] >= '0' && tm[0] <= '3') c->trip_mfma = tm[0] - '0';
   *out = c;
   return GP_OK;
 }
@@ -86,7 +86,7 @@ int gp_set_side_stream(gp_ctx* ctx, int on) {
 }
 
 int gp_set_triplet_mfma(gp_ctx* ctx, int mode) {
-  if (!ctx || mode < -1 || mode > 2) return GP_BAD_ARG;
+  if (!ctx || mode < -1 || mode > 3) return GP_BAD_ARG;
   ctx->trip_mfma = mode;
   return GP_OK;
 }

@@ -77,7 +77,7 @@ fused_items_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restric
 // zero, so padded rows contribute nothing), and, from the workgroups of the first 64 rows, for every out-edge of the
 // atom (at its out-list position) {edge id, start of its segment, position of the row the segment leaves out
 // (the number of rows if none)}.
-template <int SM>
+template <int SM, bool RADB = false>
 __global__ void __launch_bounds__(256)
 fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
                   const int32_t* __restrict__ seg_ptr_ji, const int32_t* __restrict__ idx_kj, const float* __restrict__ x,
@@ -132,6 +132,14 @@ fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
     float rl[SM];
 #pragma unroll
     for (int l = 0; l < SM; ++l) rl[l] = s_r[(l * CP + c) * (ROWPAD + 1) + pl];
+    if constexpr (RADB) {
+      // the normalised radial values themselves, bf16 [row][c][8 l]: the kernel forms y with the matrix cores
+      bf16x8 v;
+#pragma unroll
+      for (int l = 0; l < 8; ++l) v[l] = (__bf16)(l < SM ? rl[l < SM ? l : 0] : 0.f);
+      *reinterpret_cast<bf16x8*>(reinterpret_cast<__bf16*>(coef) + ((base + pl) * CP + c) * 8) = v;
+      continue;
+    }
     float m[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
@@ -341,6 +349,206 @@ tripG_fused_kernel(const float* __restrict__ cos_alpha, int64_t T, const __bf16*
   }
 }
 
+// The same sum with y itself formed on the matrix cores.  For 4 rows p_q (q = 0..3) and the wavefront's 4 out-edges e',
+//
+//   y[p_q, e', c] = sum_l P_l(cos alpha(p_q, e')) R[p_q, l, c]        (R: normalised radial values, bf16)
+//
+// is one v_mfma_f32_16x16x32_bf16 with rows (q, e'), contraction index (q', l) and an operand that is zero unless q' = q:
+// lane (kq, r = (q, e')) supplies the 8 Legendre values of its pair when kq = q and zeros otherwise, lane (kq, c) of the
+// other operand the 8 radial values of row p_kq.  Taking p_q = 8 q + j in the j-th of 8 such products, lane (g, c) ends up
+// with y[8 g + j, e' = i, c] in result register i of product j: for every edge i exactly the 8 consecutive rows it must
+// supply to the second product D[f, c] += X^T[f, p] Y[p, c].  A quarter of the first product's arithmetic is used, but
+// the vector units, where the one-pass kernel above spends most of its time (7 multiply-adds per value y), are left with
+// the Legendre recurrence of the wavefront's 128 (row, edge) pairs per slab: two pairs per lane, handed to the lanes that
+// feed the products through a slice of LDS the wavefront owns (its LDS operations complete in order: no barrier).
+template <int NT>
+__global__ void __launch_bounds__(FT, 2)
+tripG_fusedM_kernel(const float* __restrict__ cos_alpha, int64_t T, const __bf16* __restrict__ xb, const __bf16* __restrict__ radb,
+                    const int32_t* __restrict__ edge_info, const int32_t* __restrict__ n_items, const int32_t* __restrict__ item,
+                    int C, int S, int out_half, float* __restrict__ A) {
+  constexpr int F = 16 * NT;
+  constexpr int XT_B = SLAB / 8 * F * 16, RB_B = SLAB * CP * 16, CS_B = GE * SLAB * 4, BUF_B = XT_B + RB_B + CS_B;
+  constexpr int XT_LOADS = XT_B / 1024, RB_LOADS = RB_B / 1024, CS_LOADS = CS_B / 256;
+  static_assert(RB_LOADS % 4 == 0 && CS_LOADS % 4 == 0 && CP == 16, "the loads of a slab are dealt evenly to the 4 wavefronts");
+  constexpr int PAIR_B = 4 * SLAB * 16;   // a wavefront's pairs of one slab, 8 bf16 each: [row % 8][row / 8][edge]
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int s_e[GE], s_seg[GE], s_gap[GE];
+  unsigned char* pairS = smem + STAGES * BUF_B;   // 4 slices of PAIR_B bytes, then PAIR_B bytes of zeros
+
+  const int total = n_items[0];
+  const int q8 = total >> 3, r8 = total & 7, xcd = (int)blockIdx.x & 7, ith = (int)blockIdx.x >> 3;
+  if (ith >= q8 + (xcd < r8 ? 1 : 0)) return;
+  const int w = xcd * q8 + (xcd < r8 ? xcd : r8) + ith;
+  const int4 it = *reinterpret_cast<const int4*>(item + 4 * (int64_t)w);
+  const int64_t base = it.x;
+  const int d = it.y, o0 = it.z, n_e = it.w;
+  const int n_slab = (d + SLAB - 1) / SLAB;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kq = lane >> 4, c = lane & 15;
+
+  const int xt_lane = ((kq / NT) * F + NT * rowperm(c) + kq % NT) * 8;   // bf16 elements (see the kernel above)
+  auto stage_tables = [&](int slab, int buf) __attribute__((always_inline)) {
+    unsigned char* dst = smem + buf * BUF_B;
+    const int64_t row0 = base + (int64_t)SLAB * slab;
+#pragma unroll
+    for (int L = 0; L < (XT_LOADS + 3) / 4; ++L) {
+      const int ld = wv + 4 * L < XT_LOADS ? wv + 4 * L : XT_LOADS - 1;
+      const __bf16* src = xb + ((row0 / 8 + (4 * ld) / NT) * F + (4 * ld) % NT) * 8 + xt_lane;
+      __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(dst + ld * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int L = 0; L < RB_LOADS / 4; ++L) {
+      const int ld = wv + 4 * L;   // rows 4 ld .. 4 ld + 3: 1 KB, contiguous in the table
+      const __bf16* src = radb + (row0 + 4 * ld) * (CP * 8) + lane * 8;
+      __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(dst + XT_B + ld * 1024), 16, 0, 0);
+    }
+  };
+  constexpr int PW = (XT_LOADS + 3) / 4 + RB_LOADS / 4 + CS_LOADS / 4;
+  if (n_slab > 0) stage_tables(0, 0);
+  reinterpret_cast<uint64_t*>(pairS + 4 * PAIR_B)[tid] = 0ull;
+  if (tid < GE) {
+    const int4 ei = *reinterpret_cast<const int4*>(edge_info + 4 * (int64_t)(o0 + (tid < n_e ? tid : 0)));
+    s_e[tid] = tid < n_e ? ei.x : -1;
+    s_seg[tid] = ei.y;
+    s_gap[tid] = tid < n_e ? ei.z : -1;
+  }
+  __syncthreads();
+  int cs_seg[CS_LOADS / 4], cs_gap[CS_LOADS / 4];
+#pragma unroll
+  for (int L = 0; L < CS_LOADS / 4; ++L) {
+    const int el = 2 * (wv + 4 * L) + (lane >> 5);
+    cs_seg[L] = s_seg[el];
+    cs_gap[L] = s_gap[el];
+  }
+  auto stage_cos = [&](int slab, int buf) __attribute__((always_inline)) {
+    unsigned char* dst = smem + buf * BUF_B + XT_B + RB_B;
+#pragma unroll
+    for (int L = 0; L < CS_LOADS / 4; ++L) {
+      const int ld = wv + 4 * L;
+      const int P = SLAB * slab + (lane & 31);
+      int64_t idx = (int64_t)cs_seg[L] + P - (P > cs_gap[L] ? 1 : 0);
+      idx = idx < 0 ? 0 : (idx < T ? idx : T - 1);
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(cos_alpha + idx), (lds_void_ptr)(dst + ld * 256), 4, 0, 0);
+    }
+  };
+  if (n_slab > 0) stage_cos(0, 0);
+  if (n_slab > 1) {
+    stage_tables(1, 1);
+    stage_cos(1, 1);
+  }
+
+  f32x4 acc[4][NT];
+#pragma unroll
+  for (int e4 = 0; e4 < 4; ++e4)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[e4][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // Legendre values: this lane evaluates the pairs (rows r_p and r_p + 4, edge e_p) and stores them at positions lane
+  // and lane + 64 of the slice ...
+  const int e_p = lane & 3, r_p = 8 * ((lane >> 2) & 3) + (lane >> 4);
+  const int my_gap = s_gap[4 * wv + e_p] - r_p;   // the left-out row relative to the lane's first row of slab 0
+  unsigned char* pair_wr = pairS + wv * PAIR_B + lane * 16;
+  // ... and feeds the first products as lane (kq, r = (q, e')): the pair (row 8 q + j, e') when q = kq, zeros otherwise
+  const unsigned char* pair_rd = (c >> 2) == kq ? pairS + wv * PAIR_B + (4 * kq + (c & 3)) * 16 : pairS + 4 * PAIR_B;
+  if (n_slab > 1) wait_vmcnt<PW>();
+  else wait_vm0();
+  __syncthreads();
+
+  int b = 0;
+  for (int s = 0; s < n_slab; ++s) {
+    const int b2 = b >= 1 ? b - 1 : STAGES - 1;
+    const bool more = s + 2 < n_slab;
+    if (more) {
+      stage_tables(s + 2, b2);
+      stage_cos(s + 2, b2);
+    }
+    const unsigned char* buf = smem + b * BUF_B;
+    const unsigned char* radS = buf + XT_B;
+    const float* cosS = reinterpret_cast<const float*>(buf + XT_B + RB_B);
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const float* cp = cosS + (4 * wv + e_p) * SLAB + r_p;
+    const f32x2 cx = {cp[0], cp[4]};
+    const int gl = my_gap - SLAB * s;   // 0 or 4 if the left-out row is this lane's first or second
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      // Legendre polynomials P_0..P_7 of the pair's cosine (the normalisation sits in the radial table)
+      const float x = cx[h];
+      float P[8];
+      P[0] = 1.f;
+      P[1] = x;
+#pragma unroll
+      for (int l = 1; l < 7; ++l) P[l + 1] = ((float)(2 * l + 1) / (float)(l + 1)) * x * P[l] - ((float)l / (float)(l + 1)) * P[l - 1];
+      union {
+        bf16x8 h8;
+        u32x4 w;
+      } pk;
+#pragma unroll
+      for (int l = 0; l < 8; ++l) pk.h8[l] = (__bf16)P[l];
+      if (gl == 4 * h) pk.w = u32x4{0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4*>(pair_wr + 1024 * h) = pk.w;
+    }
+    bf16x8 yb[4];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bf16x8 rb = *reinterpret_cast<const bf16x8*>(radS + (((8 * kq + j) * CP + c) << 4));
+      const bf16x8 pa = *reinterpret_cast<const bf16x8*>(pair_rd + 256 * j);
+      const f32x4 y = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, rb, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) yb[i][j] = (__bf16)y[i];
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const bf16x8 xa = *reinterpret_cast<const bf16x8*>(buf + ((kq * F + t * 16 + c) << 4));
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4)
+        acc[e4][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, yb[e4], acc[e4][t], 0, 0, 0);
+    }
+    if (more) wait_vmcnt<PW>();
+    else wait_vm0();
+    __syncthreads();
+    b = b == STAGES - 1 ? 0 : b + 1;
+  }
+
+  // accumulator register i of tile t in lane (g = kq, c): feature NT (4 i + g) + t
+#pragma unroll
+  for (int e4 = 0; e4 < 4; ++e4) {
+    const int el = 4 * wv + e4;
+    if (el >= n_e || c >= C) continue;
+    const int64_t at = ((int64_t)s_e[el] * C + c) * F + NT * kq;
+    if (out_half) {
+      __bf16* dst = reinterpret_cast<__bf16*>(A) + at;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (NT == 8) {
+          bf16x8 v;
+#pragma unroll
+          for (int t = 0; t < 8; ++t) v[t] = (__bf16)acc[e4][t][i];
+          *reinterpret_cast<bf16x8*>(dst + 32 * i) = v;
+        } else {
+#pragma unroll
+          for (int t = 0; t < NT; t += 2) {
+            bf16x2 v;
+            v[0] = (__bf16)acc[e4][t][i];
+            v[1] = (__bf16)acc[e4][t + 1][i];
+            *reinterpret_cast<bf16x2*>(dst + 4 * NT * i + t) = v;
+          }
+        }
+      }
+    } else {
+      float* dst = A + at;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int t = 0; t < NT; t += 2) {
+          typedef float f32x2 __attribute__((ext_vector_type(2)));
+          *reinterpret_cast<f32x2*>(dst + 4 * NT * i + t) = f32x2{acc[e4][t][i], acc[e4][t + 1][i]};
+        }
+    }
+  }
+}
+
 struct fused_ws {
   __bf16* xb;
   float* coef;
@@ -381,11 +589,15 @@ int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
   if (ws_bytes < carve_fused(ws, N, E, F, &w)) return gp_fail(ctx, GP_BUFFER_TOO_SMALL, "triplet G forward: workspace too small");
   hipStream_t st = ctx->stream;
   const double Td = (double)T, Ed = (double)E;
+  const bool y_mfma = ctx->trip_mfma != 3;   // mode 3: the earlier one-pass kernel that evaluates y on the vector units
   {
     gp_prof_scope prof(ctx, "tripG_pack", Ed * 2.0 * S * 8 * CP, Ed * (4.0 * F + 4.0 * S * C + 2.0 * F + 4.0 * COEF_ROW + 8.0));
     fused_items_kernel<<<1, 1024, 0, st>>>(g->row_ptr, g->out_ptr, (int)N, w.n_items, w.item);
     const dim3 grid((unsigned)N, (unsigned)((g->max_in_degree + ROWPAD - 1) / ROWPAD));
-    if (S <= 7)
+    if (y_mfma)
+      fused_pack_kernel<8, true><<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj, x, Radt, E, S, C,
+                                                       F, rows_list, w.xb, w.coef, w.edge_info);
+    else if (S <= 7)
       fused_pack_kernel<7><<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj, x, Radt, E, S, C, F,
                                                  rows_list, w.xb, w.coef, w.edge_info);
     else
@@ -396,6 +608,28 @@ int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
   {
     gp_prof_scope prof(ctx, "tripG_fused_fwd", Td * (2.0 * C * F + 2.0 * S * C), Td * 4.0 + Ed * ((out_half ? 2.0 : 4.0) * C * F + 2.0 * F + 4.0 * COEF_ROW));
     const unsigned grid = (unsigned)(E / GE + N);   // an upper bound of the number of work items; the rest exit at once
+#define GP_FUSEDM_LAUNCH(NT)                                                                                             \
+  do {                                                                                                                   \
+    constexpr size_t lds = STAGES * ((size_t)SLAB / 8 * 16 * NT * 16 + (size_t)SLAB * CP * 16 + (size_t)GE * SLAB * 4) +  \
+                           5 * (size_t)4 * SLAB * 16; /* + the wavefronts' Legendre pairs and the zeros */              \
+    static_assert(2 * (lds + 256) <= 160 * 1024, "two workgroups per compute unit");                                     \
+    static bool raised = false;                                                                                          \
+    if (!raised && lds > 64 * 1024) {                                                                                    \
+      GP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&tripG_fusedM_kernel<NT>),                           \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                            \
+      raised = true;                                                                                                     \
+    }                                                                                                                    \
+    tripG_fusedM_kernel<NT><<<grid, FT, lds, st>>>(cos_alpha, T, w.xb, reinterpret_cast<const __bf16*>(w.coef), w.edge_info,  \
+                                                   w.n_items, w.item, C, S, out_half, A);                                \
+  } while (0)
+    if (y_mfma) {
+      if (F == 128) GP_FUSEDM_LAUNCH(8);
+      else if (F == 64) GP_FUSEDM_LAUNCH(4);
+      else GP_FUSEDM_LAUNCH(2);
+      GP_LAUNCH_CHECK(ctx, "tripG_fusedM_kernel");
+      return GP_OK;
+    }
+#undef GP_FUSEDM_LAUNCH
 #define GP_FUSED_LAUNCH(NT, SM)                                                                                          \
   do {                                                                                                                   \
     constexpr size_t lds = STAGES * ((size_t)SLAB / 8 * 16 * NT * 16 + (size_t)SLAB * COEF_ROW * 4 + (size_t)GE * SLAB * 4); \

@@ -44,7 +44,8 @@ def test_linear_forward_bf16(lib, ctx, rows, k, n, act):
     assert H.rel_l2(out, refr) < 2e-5
 
 
-@pytest.fixture(params=[1, 2, 0], ids=["matrix-core triplets", "matrix-core triplets, two-kernel forward", "vector triplets"])
+@pytest.fixture(params=[1, 2, 3, 0], ids=["matrix-core triplets", "matrix-core triplets, two-kernel forward",
+                                          "matrix-core triplets, y on the vector units", "vector triplets"])
 def trip_mode(request, lib, ctx):
     """All forms of the triplet sums of the bf16 block: per centre atom on the matrix cores (forced on: these graphs
     are below the density at which the library picks it by itself), with the forward sum in one pass (y evaluated
