@@ -69,6 +69,7 @@ struct scratch_G {
   // bf16 storage only: weight matrices rounded to bf16 once per call, so that both operands of the large
   // GEMMs are copied to LDS without conversion
   __bf16 *W_ba_h, *W_skip_h, *W_down_h, *W_up_h, *W_bil_h, *WbilP_h, *W_up_ac_h;
+  __bf16* x_h;   // backward: the saved x rounded to bf16, an operand of the global->LDS GEMM kernel
 };
 
 size_t part_bytes_G(const gp_dims* d, int64_t E) {
@@ -120,6 +121,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t N, int64_t E, int64_t 
   s->W_bil_h = c.take<__bf16>(hs ? C * F * O : 0);
   s->WbilP_h = c.take<__bf16>(hs ? C * O * F : 0);
   s->W_up_ac_h = c.take<__bf16>(hs && d->symmetric ? O * H : 0);
+  s->x_h = c.take<__bf16>(hs ? E * F : 0);
   return c.off;
 }
 
@@ -420,6 +422,9 @@ bool lowrank_gate(const gp_ctx* ctx, const gp_dims* d, int64_t E) {
          gp_gemm_nt_takes_lowrank(ctx, E, d->emb, d->emb);
 }
 
+// z [E, emb_bil] is stored as bf16 where both of its GEMM operand roles allow 16-byte pieces
+bool z_half(const gp_dims* d) { return half_storage(d) && d->int_emb % 2 == 0 && d->emb_bil % 8 == 0 && d->emb % 8 == 0; }
+
 // bf16 copies of the weights are used when their row lengths allow paired loads
 bool weights_half(const gp_dims* d) { return half_storage(d) && d->int_emb % 2 == 0 && d->emb_bil % 2 == 0; }
 
@@ -565,7 +570,10 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   }
   else
     GP_TRY(gp_tripD_forward(ctx, graph, basis->cos_alpha, s.x, s.Radt, nullptr, F, S, C, nullptr, s.A));
-  e = gp_epilogue(); e.out = s.z;
+  // z is an operand of the up-projections and of their weight gradients only: stored as bf16, like every other operand
+  // of a bf16 block, it goes from memory to LDS without a conversion (z_half() says when)
+  const bool zh = z_half(dims);
+  e = gp_epilogue(); e.out = s.z; e.bf16 = zh ? EPI_BF_OUT : 0u;
   GP_TRY(gp_gemm_nn(ctx, s.A, W_bil, E, O, C * F, e, ah, wh && ah));                // z
   float* t_skip = sc.eh[0];
   e = gp_epilogue(); e.save_pre = s.z_skip; e.act = 1; e.out = t_skip; e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_OUT) : 0u;
@@ -577,7 +585,11 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     GP_REQUIRE(ctx, graph->id_swap, "gp_block_forward_G: graph->id_swap is needed by a symmetric block");
     float* u_ac = sc.eh[1];
     e = gp_epilogue(); e.save_pre = s.z_ac; e.act = 1; e.out = u_ac; e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_OUT) : 0u;
-    GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up_ac, E, H, O, e));
+    if (zh) {
+      GP_TRY(to_half_T(ctx, w->W_up_ac, sc.W_up_ac_h, O, H));                       // [H, O]
+      GP_TRY(gp_gemm_nt(ctx, s.z, reinterpret_cast<const float*>(sc.W_up_ac_h), E, H, O, e, 1, 1));
+    } else
+      GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up_ac, E, H, O, e));
     {
       gp_prof_scope prof(ctx, "ew_sym_mix", 0.0, (hs ? 6.0 : 12.0) * (double)E * H);
       const unsigned blocks = (unsigned)(((int64_t)E * H + 255) / 256), blocks4 = (unsigned)(((int64_t)E * H / 4 + 255) / 256);
@@ -588,12 +600,20 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     }
     e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = 0.5f; e.out = m_out;
     e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST) : 0u;
-    GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
+    if (zh) {
+      GP_TRY(to_half_T(ctx, w->W_up, sc.W_up_h, O, H));
+      GP_TRY(gp_gemm_nt(ctx, s.z, reinterpret_cast<const float*>(sc.W_up_h), E, H, O, e, 1, 1));
+    } else
+      GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
     return GP_OK;
   }
   e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = INV_SQRT2; e.out = m_out;
   e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST) : 0u;
-  GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
+  if (zh) {
+    GP_TRY(to_half_T(ctx, w->W_up, sc.W_up_h, O, H));                               // [H, O]: activations times a [N, K] weight
+    GP_TRY(gp_gemm_nt(ctx, s.z, reinterpret_cast<const float*>(sc.W_up_h), E, H, O, e, 1, 1));
+  } else
+    GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
   return GP_OK;
 }
 
@@ -657,7 +677,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
                                                               d_skip, d_ac);
       GP_LAUNCH_CHECK(ctx, "sym_bwd_kernel");
     }
-    GP_TRY(gp_gemm_tn(ctx, s.z, d_ac, E, O, H, gw->W_up_ac, nullptr, sc.part, sc.part_bytes, 0, hs));
+    GP_TRY(gp_gemm_tn(ctx, s.z, d_ac, E, O, H, gw->W_up_ac, nullptr, sc.part, sc.part_bytes, z_half(dims), hs));
     e = gp_epilogue(); e.out = sc.dz;
     const float* W_up_ac = weight_operand(ctx, wh, w->W_up_ac, sc.W_up_ac_h, (int64_t)O * H, &rc);
     GP_TRY(rc);
@@ -670,7 +690,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   } else {
     GP_TRY(gp_ew_dsilu2(ctx, grad_m_out, INV_SQRT2, s.z_up, s.z_skip, d_up, d_skip, EH));
   }
-  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.z, d_up, E, O, H, gw->W_up, nullptr, sc.part_aux, sc.part_bytes, 0, hs); }, {d_up}));
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.z, d_up, E, O, H, gw->W_up, nullptr, sc.part_aux, sc.part_bytes, z_half(dims), hs); }, {d_up}));
   e = gp_epilogue(); e.out = sc.dz;
   if (dims->symmetric) e.add_post = sc.dz;
   GP_TRY(gp_gemm_nt(ctx, d_up, W_up, E, O, H, e, hs, wh));                          // dz
@@ -739,15 +759,23 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
                              sc.Hd, nullptr));
   GP_TRY(gp_tripG_edge_G(ctx, s.Radt, sc.Hd, E, S, C, O, sc.Gm, hs));               // G[e', (c,o)] (bf16 with hs)
   GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                   // [(c,o), f]
-  e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
+  // dz_dn is an operand of two GEMMs only: bf16 with bf16 storage and weights
+  const bool dh = hs && wh && F % 8 == 0;
+  e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn; e.bf16 = dh ? EPI_BF_OUT : 0u;
   const float* WbilP = weight_operand(ctx, wh, sc.WbilP, sc.WbilP_h, (int64_t)C * O * F, &rc);
   GP_TRY(rc);
   GP_TRY(gp_gemm_nn(ctx, sc.Gm, WbilP, E, F, C * O, e, hs, wh));                    // dz_dn
-  GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));                   // [f, (c,o)]
   // V is read by the two per-edge kernels below only: bf16 storage halves its traffic
   const bool vh = hs && (O == 32 || O == 64 || O == 128);
   e = gp_epilogue(); e.out = sc.V; e.bf16 = vh ? EPI_BF_OUT : 0u;
-  GP_TRY(gp_gemm_nn(ctx, s.x, sc.WbilV, E, C * O, F, e));                           // V[e', (c,o)]
+  if (dh) {
+    // x times the [(c,o), f] copy of W_bil, both bf16 and k-contiguous: the form the global->LDS kernel takes
+    GP_TRY(to_half(ctx, s.x, sc.x_h, (int64_t)E * F));
+    GP_TRY(gp_gemm_nt(ctx, reinterpret_cast<const float*>(sc.x_h), WbilP, E, C * O, F, e, 1, 1));   // V[e', (c,o)]
+  } else {
+    GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));                 // [f, (c,o)]
+    GP_TRY(gp_gemm_nn(ctx, s.x, sc.WbilV, E, C * O, F, e));                         // V[e', (c,o)]
+  }
   GP_TRY(gp_tripG_edge_dRad(ctx, sc.V, sc.Hd, E, S, C, O, sc.dRad, vh));            // dRad[e', (l,c)]
   if (grad_cos_kj && graph->n_triplets > 0) {
     const bool dcos_fused = bwd_mfma && ctx->trip_mfma != 2 && gp_tripG_H_fused_usable(graph, O, S) &&
@@ -764,9 +792,15 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   }
   GP_TRY(gp_gemm_tn(ctx, g, sc.dRad, E, R, S * C, sc.dWcP, nullptr, sc.part, sc.part_bytes));   // [n, (l,c)]
   GP_TRY(gp_permute3(ctx, sc.dWcP, R, S, C, 1, 0, 2, gw->W_c));                     // -> [l, n, c]
-  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dzdn, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes, hs, 0); }, {}));
+  const bool dzdn_half = !dims->radial_at_target && hs && wh && F % 8 == 0;   // as written above
+  GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dzdn, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes, hs, dzdn_half); }, {}));
   e = gp_epilogue(); e.out = dxg; e.bf16 = hs ? EPI_BF_OUT : 0u;
-  GP_TRY(gp_gemm_nt(ctx, sc.dzdn, w->W_down, E, H, F, e));                          // dxg
+  if (dzdn_half) {
+    const float* W_down = weight_operand(ctx, true, w->W_down, sc.W_down_h, (int64_t)H * F, &rc);
+    GP_TRY(rc);
+    GP_TRY(gp_gemm_nt(ctx, sc.dzdn, W_down, E, H, F, e, 1, 1));                     // dxg
+  } else
+    GP_TRY(gp_gemm_nt(ctx, sc.dzdn, w->W_down, E, H, F, e));                        // dxg
   float* dz_ba = d_up;   // d_up is no longer needed on this stream
   GP_TRY(aux.before_write(d_up));
   if (lowrank_gate(ctx, dims, E)) {

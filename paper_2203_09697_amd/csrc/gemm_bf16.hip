@@ -391,6 +391,25 @@ __device__ __forceinline__ void tile_epilogue_pairs(const gemm_args& g, f32x16 (
       }
     }
   }
+  // The addend of a small tile that lies inside the matrix is fetched for all of the wavefront's blocks at once, before
+  // the first block is staged: fetched block by block in the loop below, each block waited for its own loads (a narrow
+  // contraction leaves nothing else to hide them behind).
+  constexpr bool PRELOAD = KIND == EK_PRE_SILU_ADD_F32 && MB * NB <= 4;
+  bf16x4 addp[PRELOAD ? MB : 1][PRELOAD ? NB / 2 : 1][PRELOAD ? 8 : 1];
+  bool preloaded = false;
+  if constexpr (PRELOAD) {
+    preloaded = m0 + wm0 + MB * 32 <= g.M && n0 + wn0 + NB * 32 <= g.N;
+    if (preloaded) {
+      const __bf16* ap = reinterpret_cast<const __bf16*>(g.epi.add_post) + (m0 + wm0 + (lane >> 4)) * g.N + (n0 + wn0 + (lane & 15) * 4);
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; j += 2)
+#pragma unroll
+          for (int it = 0; it < 8; ++it)
+            addp[i][j / 2][it] = *reinterpret_cast<const bf16x4*>(ap + (int64_t)(i * 32 + it * 4) * g.N + j * 32);
+    }
+  }
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -421,6 +440,17 @@ __device__ __forceinline__ void tile_epilogue_pairs(const gemm_args& g, f32x16 (
         if constexpr (KIND != EK_GENERIC) {
           const int c4 = (lane & 15) * 4;
           const int64_t o0 = (m0 + wm0 + i * 32 + (lane >> 4)) * g.N + (n0 + wn0 + j * 32 + c4);
+          if constexpr (PRELOAD) {
+            if (preloaded) {
+#pragma unroll
+              for (int it = 0; it < 8; ++it) {
+                const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[(it * 4 + (lane >> 4)) * EPI_LD2 + c4]);
+                epilogue_store4_kind<KIND>(g.epi, o0 + (int64_t)it * 4 * g.N, v4, f32x4{1.f, 1.f, 1.f, 1.f}, &addp[i][j / 2][it]);
+              }
+              wave_lds_sync();
+              continue;
+            }
+          }
 #pragma unroll 4
           for (int it = 0; it < 8; ++it) {
             const int r = it * 4 + (lane >> 4);

@@ -157,7 +157,8 @@ __device__ __forceinline__ void st4h(float* p, int64_t o, f32x4 v) {
 }
 // The steps of one of the fixed combinations on 4 consecutive columns; no option is tested here.
 template <int KIND>
-__device__ __forceinline__ void epilogue_store4_kind(const gp_epilogue& e, int64_t o, f32x4 v, f32x4 lr) {
+__device__ __forceinline__ void epilogue_store4_kind(const gp_epilogue& e, int64_t o, f32x4 v, f32x4 lr,
+                                                     const bf16x4* add_loaded = nullptr) {
   static_assert(KIND != EK_GENERIC, "the general loop calls epilogue_store4");
   if constexpr (KIND == EK_OUT_F32) st4(e.out + o, v);
   else if constexpr (KIND == EK_OUT_BF16) st4h(e.out, o, v);
@@ -167,7 +168,10 @@ __device__ __forceinline__ void epilogue_store4_kind(const gp_epilogue& e, int64
     for (int c = 0; c < 4; ++c) v[c] = silu_f(v[c]);
     if constexpr (KIND == EK_PRE_SILU_LR_BF16) v *= lr;
     if constexpr (KIND == EK_PRE_SILU_ADD_F32) {
-      v += ldx4(e.add_post, o, 1u);
+      if (add_loaded) {   // the caller has fetched the addend's 4 values already
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] += (float)(*add_loaded)[c];
+      } else v += ldx4(e.add_post, o, 1u);
       v *= e.scale;
       st4(e.out + o, v);
     } else st4h(e.out, o, v);
