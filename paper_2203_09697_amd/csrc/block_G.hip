@@ -69,6 +69,7 @@ struct scratch_G {
   // bf16 storage only: weight matrices rounded to bf16 once per call, so that both operands of the large
   // GEMMs are copied to LDS without conversion
   __bf16 *W_ba_h, *W_skip_h, *W_down_h, *W_up_h, *W_bil_h, *WbilP_h, *W_up_ac_h;
+  __bf16* WbilV_h;   // backward: the [f, (c,o)] copy of W_bil
   __bf16* x_h;   // backward: the saved x rounded to bf16, an operand of the global->LDS GEMM kernel
 };
 
@@ -121,6 +122,7 @@ size_t carve_scratch_G(void* p, const gp_dims* d, int64_t N, int64_t E, int64_t 
   s->W_bil_h = c.take<__bf16>(hs ? C * F * O : 0);
   s->WbilP_h = c.take<__bf16>(hs ? C * O * F : 0);
   s->W_up_ac_h = c.take<__bf16>(hs && d->symmetric ? O * H : 0);
+  s->WbilV_h = c.take<__bf16>(hs ? F * C * O : 0);
   s->x_h = c.take<__bf16>(hs ? E * F : 0);
   return c.off;
 }
@@ -531,8 +533,12 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   }
   const float* W_ba_T = reinterpret_cast<const float*>(sc.W_ba_h);
   const float* W_skip_T = reinterpret_cast<const float*>(sc.W_skip_h);
-  const float* W_down = weight_operand(ctx, wh, w->W_down, sc.W_down_h, (int64_t)H * F, &rc);
-  const float* W_bil = weight_operand(ctx, wh && ah, w->W_bil, sc.W_bil_h, (int64_t)C * F * O, &rc);
+  // the two weights that contract a wide row into a narrow one likewise, where the activations are bf16
+  const bool down_T = wh && hs && H % 8 == 0, bil_T = wh && ah;
+  if (down_T) GP_TRY(to_half_T(ctx, w->W_down, sc.W_down_h, H, F));                 // [F, H]
+  if (bil_T) GP_TRY(to_half_T(ctx, w->W_bil, sc.W_bil_h, C * F, O));                // [O, (c,f)]
+  const float* W_down = down_T ? reinterpret_cast<const float*>(sc.W_down_h) : weight_operand(ctx, wh, w->W_down, sc.W_down_h, (int64_t)H * F, &rc);
+  const float* W_bil = bil_T ? reinterpret_cast<const float*>(sc.W_bil_h) : w->W_bil;
   GP_TRY(rc);
   e = gp_epilogue(); e.save_pre = s.z_ba; e.act = 1; e.out = s.xg;
   if (lrg) e.lr_a = s.gate, e.lr_b = w->W_rbfB, e.lr_k = RB;
@@ -541,7 +547,8 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   if (wh) GP_TRY(gp_gemm_nt(ctx, m_op, W_ba_T, E, H, H, e, 1, 1));                  // xg
   else GP_TRY(gp_gemm_nn(ctx, m_op, w->W_ba, E, H, H, e, hs));
   e = gp_epilogue(); e.save_pre = s.z_dn; e.act = 1; e.out = s.x;
-  GP_TRY(gp_gemm_nn(ctx, s.xg, W_down, E, F, H, e, hs, wh));                        // x
+  if (down_T) GP_TRY(gp_gemm_nt(ctx, s.xg, W_down, E, F, H, e, 1, 1));              // x
+  else GP_TRY(gp_gemm_nn(ctx, s.xg, W_down, E, F, H, e, hs, wh));
   GP_TRY(gp_permute3(ctx, w->W_c, S, R, C, 0, 2, 1, s.WcT));                        // WcT[(l,c), n]
   e = gp_epilogue(); e.out = s.Radt;
   GP_TRY(gp_gemm_nt(ctx, s.WcT, g, S * C, (int)E, R, e));                           // Radt[(l,c), e]
@@ -574,7 +581,8 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   // of a bf16 block, it goes from memory to LDS without a conversion (z_half() says when)
   const bool zh = z_half(dims);
   e = gp_epilogue(); e.out = s.z; e.bf16 = zh ? EPI_BF_OUT : 0u;
-  GP_TRY(gp_gemm_nn(ctx, s.A, W_bil, E, O, C * F, e, ah, wh && ah));                // z
+  if (bil_T) GP_TRY(gp_gemm_nt(ctx, s.A, W_bil, E, O, C * F, e, 1, 1));             // z
+  else GP_TRY(gp_gemm_nn(ctx, s.A, W_bil, E, O, C * F, e, ah, 0));
   float* t_skip = sc.eh[0];
   e = gp_epilogue(); e.save_pre = s.z_skip; e.act = 1; e.out = t_skip; e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_OUT) : 0u;
   if (wh) GP_TRY(gp_gemm_nt(ctx, m_op, W_skip_T, E, H, H, e, 1, 1));
@@ -764,7 +772,12 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn; e.bf16 = dh ? EPI_BF_OUT : 0u;
   const float* WbilP = weight_operand(ctx, wh, sc.WbilP, sc.WbilP_h, (int64_t)C * O * F, &rc);
   GP_TRY(rc);
-  GP_TRY(gp_gemm_nn(ctx, sc.Gm, WbilP, E, F, C * O, e, hs, wh));                    // dz_dn
+  if (dh && (C * O) % 8 == 0) {
+    GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));                 // [f, (c,o)]
+    GP_TRY(to_half(ctx, sc.WbilV, sc.WbilV_h, (int64_t)F * C * O));
+    GP_TRY(gp_gemm_nt(ctx, sc.Gm, reinterpret_cast<const float*>(sc.WbilV_h), E, F, C * O, e, 1, 1));   // dz_dn
+  } else
+    GP_TRY(gp_gemm_nn(ctx, sc.Gm, WbilP, E, F, C * O, e, hs, wh));                  // dz_dn
   // V is read by the two per-edge kernels below only: bf16 storage halves its traffic
   const bool vh = hs && (O == 32 || O == 64 || O == 128);
   e = gp_epilogue(); e.out = sc.V; e.bf16 = vh ? EPI_BF_OUT : 0u;

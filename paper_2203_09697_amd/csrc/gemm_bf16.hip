@@ -936,16 +936,19 @@ gemm_dl_kernel(const gemm_args g) {
       const bool second = sl >= n1;
       const int64_t kb = (int64_t)(second ? sl - n1 : sl) * ROWB;
       char* dst = lds + st * STAGE_B + wave * PER * 1024;
-      static_assert(PER <= MB * NB, "one load per MFMA of a group");
+      constexpr int LPM = (PER + MB * NB - 1) / (MB * NB);   // loads behind each MFMA (1 for the 256x256 tile)
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KS - 1) & 1][i], fb[(KS - 1) & 1][j], acc[i][j], 0, 0, 0);
-          const int q = i * NB + j;
-          if (q < PER) {
-            const int64_t d2 = second ? (wave * PER + q < A_LOADS ? dA : dB) : 0;   // uniform
-            __builtin_amdgcn_global_load_lds((global_void_ptr)(src[q] + kb + d2), (lds_void_ptr)(dst + q * 1024), 16, 0, 0);
+#pragma unroll
+          for (int u = 0; u < LPM; ++u) {
+            const int q = (i * NB + j) * LPM + u;
+            if (q < PER) {
+              const int64_t d2 = second ? (wave * PER + q < A_LOADS ? dA : dB) : 0;   // uniform
+              __builtin_amdgcn_global_load_lds((global_void_ptr)(src[q] + kb + d2), (lds_void_ptr)(dst + q * 1024), 16, 0, 0);
+            }
           }
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -964,7 +967,8 @@ int launch_dl(gp_ctx* ctx, gemm_args& g) {
   static char name[48];
   if (!name[0]) snprintf(name, sizeof(name), "gemm_bf16_dl_nt_%dx%d", BM, BN);
   const double mnk = (double)g.M * g.N * g.K;
-  gp_prof_scope prof(ctx, name, 2.0 * mnk, 2.0 * (double)g.M * g.K + 2.0 * (double)g.K * g.N + 4.0 * (double)g.M * g.N);
+  gp_prof_scope prof(ctx, name, 2.0 * mnk,
+                     2.0 * (double)g.M * g.K + 2.0 * (double)g.K * g.N + ((g.epi.bf16 & EPI_BF_OUT) ? 2.0 : 4.0) * (double)g.M * g.N);
   constexpr int NW = WMS * WNS;
   constexpr size_t lds_main = (size_t)STAGES * (BM + BN) * BK * 2;
   constexpr size_t lds_epi = sizeof(float) * 2 * NW * 32 * EPI_LD2;   // accumulator blocks and low-rank factor blocks
@@ -1241,6 +1245,13 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
   if (MODE == MODE_NT && g.a_bf16 && g.b_bf16 && g.M >= 8192 && g.N > 128 && g.K % 64 == 0 && g.K >= 128 &&
       g.lda % 8 == 0 && g.ldb % 8 == 0 && (!g.A2 || g.K % 128 == 0))
     return launch_dl<256, 256, 2, 4, 64, 2>(ctx, g);
+  // ... times a narrow one (a long contraction into 33..128 columns): the same kernel streams the activations, which is all
+  // that bounds these products, through a deeper ring; 8 wavefronts of 64x64 or 32x64
+  if (MODE == MODE_NT && g.a_bf16 && g.b_bf16 && g.M >= 8192 && g.N > 32 && g.N <= 128 && g.K % 64 == 0 && g.K >= 256 &&
+      g.lda % 8 == 0 && g.ldb % 8 == 0 && !g.A2 && !g.epi.lr_a) {
+    if (g.N > 64) return launch_dl<256, 128, 4, 2, 64, 3>(ctx, g);
+    return launch_dl<256, 64, 8, 1, 64, 3>(ctx, g);
+  }
   if (g.A2) return gp_fail(ctx, GP_BAD_ARG, "gemm: a second operand pair is only taken by the global->LDS kernel");
   if (g.epi.lr_a) return gp_fail(ctx, GP_BAD_ARG, "gemm: a low-rank epilogue factor is only taken by the global->LDS kernel");
   // the reduction over rows (TN) keeps the 128-row tiles its split plan was made for
