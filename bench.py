@@ -144,6 +144,9 @@ def main():
                     help="variant-G triplet kernels: -1 the library's own choice, 0 per-edge vector kernels, 1 matrix-core "
                          "kernels per centre atom, 2 the two-kernel forward and whole-atom backward forms, 3 the one-pass "
                          "forward kernel with y evaluated on the vector units")
+    ap.add_argument("--f32-gemm", choices=["split", "native"], default="split",
+                    help="fp32 GEMMs: operands split into three bf16 planes on the bf16 matrix cores (the library's default), or "
+                         "the fp32-operand matrix-core instruction")
     ap.add_argument("--no-side-stream", action="store_true", help="weight-gradient GEMMs on the launch stream")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run one 256 MiB device copy first (known traffic, to scale rocprofv3 byte counters)")
@@ -171,6 +174,8 @@ def main():
         gp.gp_set_triplet_mfma(ctx, a.trip_mode)
     if a.no_side_stream:
         gp.gp_set_side_stream(ctx, False)
+    if a.f32_gemm == "native":
+        gp.gp_set_f32_gemm(ctx, False)
     dpos = torch.as_tensor(pos).to("cuda:0")
     dptr = torch.as_tensor(gptr).to("cuda:0")
 
@@ -276,7 +281,7 @@ def main():
                                                   "mfma_f32" if k["bound"] == "mfma" else None)
         k["frac_of_measured"] = round(k["achieved"] / measured[key], 4) if key else None
     top = kernels[0]
-    traffic = measured_traffic(w, bool(opts) or a.output_blocks or a.trip_mode >= 0 or a.no_side_stream)
+    traffic = measured_traffic(w, bool(opts) or a.output_blocks or a.trip_mode >= 0 or a.no_side_stream or a.f32_gemm != "split")
     for k in kernels:
         k["traffic"] = traffic.get(k["kernel"])
     roofline = {"kernel": top["kernel"], "bound": top["bound"], "achieved": top["achieved"], "peak": top["peak"],

@@ -66,6 +66,13 @@ int gp_set_side_stream(gp_ctx* ctx, int on);
  * sets the mode at gp_create. */
 int gp_set_triplet_mfma(gp_ctx* ctx, int mode);
 
+/* GEMMs with fp32 operands and results (the fp32 blocks, Sec. 3.3; the energy head).  split = 1 (default): on the bf16
+ * matrix cores, every operand element entering as three bf16 numbers whose sum is the fp32 value (24 significant
+ * bits) and six of the nine plane products accumulated in fp32, the dropped ones below 2^-24 of the product: results
+ * agree with fp32 arithmetic to its rounding error, at 2.7 times the fp32-operand matrix-core rate of this chip.
+ * split = 0: the fp32-operand matrix-core instruction.  GP_F32_GEMM=0/1 in the environment sets it at gp_create. */
+int gp_set_f32_gemm(gp_ctx* ctx, int split);
+
 /* Errors that only a kernel can detect are deferred: a block call given gp_graph.max_in_degree / max_out_degree
  * below the true maxima skips the atoms above them (it never reads out of bounds) and leaves a mark that makes
  * the NEXT block call on the context, or this call, return GP_BAD_ARG with a message.  gp_deferred_status

@@ -6,7 +6,7 @@ import torch
 
 __all__ = [
     "GpError", "load", "library_path", "Context", "Dims", "Graph", "Basis",
-    "gp_version", "gp_deferred_status", "gp_profile_enable", "gp_profile_reset", "gp_profile_collect", "gp_set_side_stream", "gp_set_triplet_mfma",
+    "gp_version", "gp_deferred_status", "gp_profile_enable", "gp_profile_reset", "gp_profile_collect", "gp_set_side_stream", "gp_set_triplet_mfma", "gp_set_f32_gemm",
     "gp_measure_peaks", "gp_edges_by_source", "gp_edges_by_source_static", "gp_reverse_edges", "gp_edges", "gp_triplets", "gp_basis_forward", "gp_block_workspace",
     "gp_block_forward_D", "gp_block_backward_D", "gp_block_backward_D_basis", "gp_triplet_aggregate_fwd",
     "gp_triplet_aggregate_bwd", "gp_linear_forward", "build_graph", "weights_to_device",
@@ -25,7 +25,7 @@ STATUS = {0: "GP_OK", -1: "GP_BAD_ARG", -2: "GP_BUFFER_TOO_SMALL", -3: "GP_INT32
 
 EXPORTED_SYMBOLS = [
     "gp_create", "gp_destroy", "gp_last_error", "gp_version",
-    "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get", "gp_set_side_stream", "gp_set_triplet_mfma", "gp_deferred_status", "gp_measure_peaks",
+    "gp_profile_enable", "gp_profile_reset", "gp_profile_count", "gp_profile_get", "gp_set_side_stream", "gp_set_triplet_mfma", "gp_set_f32_gemm", "gp_deferred_status", "gp_measure_peaks",
     "gp_edges_workspace", "gp_edges_count", "gp_edges_fill", "gp_edges_count_pbc", "gp_edges_fill_pbc",
     "gp_triplets_count_pbc", "gp_triplets_fill_pbc",
     "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill", "gp_csr_max_degree", "gp_reverse_edges",
@@ -200,6 +200,10 @@ def gp_measure_peaks(ctx, mib=512):
 
 def gp_set_triplet_mfma(ctx, mode):
     ctx.check(load().gp_set_triplet_mfma(ctx._h, C.c_int(mode)))
+
+
+def gp_set_f32_gemm(ctx, split):
+    ctx.check(load().gp_set_f32_gemm(ctx._h, C.c_int(1 if split else 0)))
 
 
 def gp_deferred_status(ctx):

@@ -62,6 +62,8 @@ int gp_create(gp_ctx** out, int device_id, void* hip_stream) {
   c->use_aux = !(no_aux && no_aux[0] == '1');
   const char* tm = getenv("GP_TRIPLET_MFMA");
   if (tm && tm[0] >= '0' && tm[0] <= '3') c->trip_mfma = tm[0] - '0';
+  const char* fg = getenv("GP_F32_GEMM");
+  if (fg && (fg[0] == '0' || fg[0] == '1')) c->f32_split = fg[0] == '1';
   *out = c;
   return GP_OK;
 }
@@ -88,6 +90,12 @@ int gp_set_side_stream(gp_ctx* ctx, int on) {
 int gp_set_triplet_mfma(gp_ctx* ctx, int mode) {
   if (!ctx || mode < -1 || mode > 3) return GP_BAD_ARG;
   ctx->trip_mfma = mode;
+  return GP_OK;
+}
+
+int gp_set_f32_gemm(gp_ctx* ctx, int split) {
+  if (!ctx || split < 0 || split > 1) return GP_BAD_ARG;
+  ctx->f32_split = split != 0;
   return GP_OK;
 }
 

@@ -24,6 +24,7 @@ struct gp_ctx {
   char err[512] = {0};
   bool prof_on = false;
   bool gemm_bf16 = false;   // set by a block call whose dims ask for bf16 GEMM operands
+  bool f32_split = true;    // fp32 GEMMs on the bf16 matrix cores with three bf16 planes per operand (false: fp32 MFMA)
   hipStream_t aux_stream = nullptr;   // side stream for weight-gradient GEMMs (see aux_stream.h)
   bool use_aux = true;
   int trip_mfma = -1;       // matrix-core triplet kernels of the bilinear block: -1 by graph density, 0 never, 1 whenever usable,

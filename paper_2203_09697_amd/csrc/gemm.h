@@ -63,6 +63,8 @@ int gp_ew_gate_bwd(gp_ctx* ctx, const float* dxg, const float* z, const float* g
 int gp_ew_add3(gp_ctx* ctx, const float* a, const float* b, const float* c, float* out, int64_t n);  // c may be NULL
 // bf16-operand kernels (gemm_bf16.hip); mode 0 NN, 1 NT, 2 TN; args is the fp32 path's argument block
 int gp_gemm_bf16_launch(gp_ctx* ctx, int mode, void* args, int splits);
+// fp32 operands and result on the bf16 matrix cores, each operand as three bf16 planes (gemm_bf16.hip)
+int gp_gemm_split_launch(gp_ctx* ctx, int mode, void* args, int splits);
 // A^T B with both operands bf16 through global->LDS loads and LDS transpose reads: number of splits of its plan (0: the
 // shape is not taken), whether the filled argument block qualifies, launch
 int gp_gemm_bf16_tn_dl_splits(int64_t rows, int M, int N);

@@ -54,6 +54,24 @@ __device__ __forceinline__ bf16x8 to_bf16x8_masked(const float* v, uint32_t bits
   return r;
 }
 
+// 8 fp32 values as PL bf16 planes, `plane` elements apart: plane 0 holds the values rounded to bf16, plane p what is left
+// after planes 0..p-1 rounded again.  Three planes carry 24 significant bits, i.e. the fp32 value itself.
+template <int PL>
+__device__ __forceinline__ void split_store8(__bf16* dst, int plane, const float* v) {
+  float r[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) r[c] = v[c];
+#pragma unroll
+  for (int p = 0; p < PL; ++p) {
+    const bf16x8 h = to_bf16x8(r);
+    *reinterpret_cast<bf16x8*>(dst + p * plane) = h;
+    if (p + 1 < PL) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) r[c] -= (float)h[c];
+    }
+  }
+}
+
 // Source rows = tile rows, contraction index contiguous; item = (row, group of 8 k).
 template <int X, bool VEC>
 struct bl_kcontig {
@@ -114,6 +132,19 @@ struct bl_kcontig {
       const int row = idx / K8, kq = (idx % K8) * 8;
       *reinterpret_cast<bf16x8*>(&S[row * LDK + kq]) =
           tail ? to_bf16x8_masked(r[it], (mask >> (8 * it)) & 0xFFu) : to_bf16x8(r[it]);
+    }
+  }
+  template <int PL>
+  __device__ __forceinline__ void store_planes(__bf16* __restrict__ S, int plane, bool tail) const {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      if (!ALL && idx >= ITEMS) continue;
+      const int row = idx / K8, kq = (idx % K8) * 8;
+      float v[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) v[c] = (!tail || ((mask >> (8 * it + c)) & 1u)) ? r[it][c] : 0.f;
+      split_store8<PL>(&S[row * LDK + kq], plane, v);
     }
   }
 };
@@ -204,6 +235,36 @@ struct bl_xcontig {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) col[kk] = r[it][kk][c];
         *reinterpret_cast<bf16x8*>(&S[(xq + c) * LDK + kq]) = tail ? to_bf16x8_masked(col, kmask[it]) : to_bf16x8(col);
+      }
+    }
+  }
+  template <int PL>
+  __device__ __forceinline__ void store_planes(__bf16* __restrict__ S, int plane, bool tail) const {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = threadIdx.x + it * THREADS;
+      if (!ALL && idx >= GROUPS) continue;
+      const int kq = (idx % K8) * 8, xq = (idx / K8) * 4;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        float col[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) col[kk] = (!tail || ((kmask[it] >> kk) & 1u)) ? r[it][kk][c] : 0.f;
+        split_store8<PL>(&S[(xq + c) * LDK + kq], plane, col);
+      }
+    }
+  }
+  // cs[it][c] += the sum over the 8 k rows this thread holds of column xq + c (the fetched slab)
+  __device__ __forceinline__ void add_colsum(float (&cs)[NV][4], bool tail) const {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      if (!ALL && (int)threadIdx.x + it * THREADS >= GROUPS) continue;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        float t = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) t += (!tail || ((kmask[it] >> kk) & 1u)) ? r[it][kk][c] : 0.f;
+        cs[it][c] += t;
       }
     }
   }
@@ -631,6 +692,146 @@ gemm_bf16_kernel(const gemm_args g) {
   }
 
   tile_epilogue<MB, NB, MODE>(g, acc, smem, m0, n0, wm0, wn0, blockIdx.y);
+}
+
+// fp32 operands, fp32 result, on the bf16 matrix cores: each operand element goes into LDS as three bf16 numbers whose
+// sum is the fp32 value (hi + mid + lo, 24 significant bits), and a k-step multiplies the six plane pairs whose
+// product is not below 2^-24 of the full one (hi.hi, hi.mid, mid.hi, hi.lo, mid.mid, lo.hi), smallest first, into the
+// fp32 accumulator: the error of a product is that of one fp32 rounding.  Six bf16 MFMAs (32 cycles each for 16 k)
+// replace eight fp32 ones (64 cycles each for 2 k): the fp32-operand MFMA rate of this chip is a sixteenth of the
+// bf16 one.  Same tiles, loaders and pipeline as gemm_bf16_kernel, the fp32 kernel's epilogue (all matrices fp32)
+// and, for A^T B, its column sums of B (the bias gradient), taken from the loader's registers in fp32.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE, bool VEC>
+__global__ void __launch_bounds__(THREADS, 2)
+gemm_split_kernel(const gemm_args g) {
+  static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+  constexpr int PL = 3;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int MB = WM / 32, NB = WN / 32;
+  using loadA = typename std::conditional<MODE != MODE_TN, bl_kcontig<BM, VEC>, bl_xcontig<BM, VEC>>::type;
+  using loadB = typename std::conditional<MODE == MODE_NT, bl_kcontig<BN, VEC>, bl_xcontig<BN, VEC>>::type;
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  constexpr int PA = BM * LDK, PB = BN * LDK;   // plane strides (bf16 elements)
+  __bf16* As = reinterpret_cast<__bf16*>(smem);
+  __bf16* Bs = As + PL * PA;
+
+  const int tiles_n = (g.N + BN - 1) / BN;
+  const int tiles_m = (int)((g.M + BM - 1) / BM);
+  const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  const int tile_m = tile / tiles_n;
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int n0 = (tile % tiles_n) * BN;
+
+  int64_t k_begin = 0, k_end = g.K;
+  if (MODE == MODE_TN) {
+    k_begin = (int64_t)blockIdx.y * g.k_per_split;
+    k_end = k_begin + g.k_per_split < (int64_t)g.K ? k_begin + g.k_per_split : (int64_t)g.K;
+  }
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int kh = lane >> 5, l32 = lane & 31;
+
+  f32x16 acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  constexpr int CSN = MODE == MODE_TN ? loadB::NV : 1;
+  float cs[CSN][4];
+#pragma unroll
+  for (int it = 0; it < CSN; ++it)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) cs[it][c] = 0.f;
+  const bool want_cs = MODE == MODE_TN && g.colsum_part != nullptr;
+
+  if (k_begin < k_end) {
+    loadA la;
+    loadB lb;
+    la.init(g.A, g.lda, m0, g.M);
+    lb.init(g.B, g.ldb, n0, g.N);
+    auto multiply = [&]() {
+#pragma unroll
+      for (int kk = 0; kk < BKH; kk += 16) {
+        bf16x8 a[PL][MB], b[PL][NB];
+#pragma unroll
+        for (int p = 0; p < PL; ++p) {
+#pragma unroll
+          for (int i = 0; i < MB; ++i) a[p][i] = *reinterpret_cast<const bf16x8*>(&As[p * PA + (wm0 + i * 32 + l32) * LDK + kk + kh * 8]);
+#pragma unroll
+          for (int j = 0; j < NB; ++j) b[p][j] = *reinterpret_cast<const bf16x8*>(&Bs[p * PB + (wn0 + j * 32 + l32) * LDK + kk + kh * 8]);
+        }
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int j = 0; j < NB; ++j) {
+            f32x16 c = acc[i][j];
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2][i], b[0][j], c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[2][j], c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[1][j], c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[0][j], c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[1][j], c, 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[0][j], c, 0, 0, 0);
+          }
+      }
+    };
+    // the slab held in the loaders' registers goes to LDS; its part of the column sums is taken on the way
+    auto store = [&](int64_t slab, bool tail) {
+      la.template store_planes<PL>(As, PA, tail);
+      lb.template store_planes<PL>(Bs, PB, tail);
+      if constexpr (MODE == MODE_TN) {
+        if (want_cs && (slab % tiles_m) == tile_m) lb.add_colsum(cs, tail);
+      }
+    };
+    const int64_t n_full = (k_end - k_begin) / BKH;
+    if (n_full > 0) {
+      la.fetch_full(k_begin);
+      lb.fetch_full(k_begin);
+      store(0, false);
+      __syncthreads();
+      for (int64_t s = 1; s < n_full; ++s) {
+        la.fetch_full(k_begin + s * BKH);
+        lb.fetch_full(k_begin + s * BKH);
+        multiply();
+        __syncthreads();
+        store(s, false);
+        __syncthreads();
+      }
+      multiply();
+      __syncthreads();
+    }
+    const int64_t k_tail = k_begin + n_full * BKH;
+    if (k_tail < k_end) {
+      la.fetch_tail(k_tail, k_end);
+      lb.fetch_tail(k_tail, k_end);
+      store(n_full, true);
+      __syncthreads();
+      multiply();
+      __syncthreads();
+    }
+  }
+
+  tile_epilogue_f32<MB, NB, MODE>(g, acc, smem, m0, n0, wm0, wn0, blockIdx.y);
+  if constexpr (MODE == MODE_TN) {
+    if (want_cs) {
+      // the 4 threads that share a group of 4 columns (one per 8-k group of the slab) are neighbouring lanes
+#pragma unroll
+      for (int it = 0; it < CSN; ++it) {
+        const int idx = threadIdx.x + it * THREADS;
+        const int xq = (idx / K8) * 4;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          float v = cs[it][c];
+          v += __shfl_xor(v, 1, 64);
+          v += __shfl_xor(v, 2, 64);
+          if ((threadIdx.x & 3) == 0 && (loadB::ALL || idx < loadB::GROUPS) && xq + c < BN && n0 + xq + c < g.N)
+            g.colsum_part[((int64_t)blockIdx.y * tiles_m + tile_m) * g.N + n0 + xq + c] = v;
+        }
+      }
+    }
+  }
 }
 
 // Both operands stored as bf16.  A slab is then only 6 sixteen-byte loads per thread, so NS slabs are kept in
@@ -1266,6 +1467,38 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
 
 }  // namespace
 
+template <int BM, int BN, int WMS, int WNS, int MODE>
+int launch_split(gp_ctx* ctx, gemm_args& g, int splits) {
+  const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  if (tiles > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
+  if (g.lda >= MAX_LD || g.ldb >= MAX_LD) return gp_fail(ctx, GP_BAD_ARG, "gemm (split fp32): leading dimension above %lld", (long long)MAX_LD);
+  dim3 grid((unsigned)tiles, (unsigned)splits, 1);
+  static char name[48];
+  if (!name[0]) snprintf(name, sizeof(name), "gemm_f32x3_%s_%dx%d", MODE == MODE_NN ? "nn" : MODE == MODE_NT ? "nt" : "tn", BM, BN);
+  const double mnk = (double)g.M * g.N * g.K;
+  gp_prof_scope prof(ctx, name, 2.0 * mnk,
+                     4.0 * ((double)g.M * g.K + (double)g.K * g.N + (double)g.M * g.N * (MODE == MODE_TN ? splits : 1)));
+  constexpr size_t lds_main = sizeof(__bf16) * 3 * (size_t)(BM + BN) * LDK;
+  constexpr size_t lds_epi = sizeof(float) * 4 * 32 * EPI_LD;
+  constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+  static_assert(lds <= 64 * 1024, "tile fits the default dynamic LDS limit");
+  if (g.vecA && g.vecB) gemm_split_kernel<BM, BN, WMS, WNS, MODE, true><<<grid, THREADS, lds, ctx->stream>>>(g);
+  else gemm_split_kernel<BM, BN, WMS, WNS, MODE, false><<<grid, THREADS, lds, ctx->stream>>>(g);
+  GP_LAUNCH_CHECK(ctx, "gemm_split_kernel");
+  return GP_OK;
+}
+
+template <int MODE>
+int dispatch_split(gp_ctx* ctx, gemm_args& g, int splits) {
+  if (MODE == MODE_TN) {   // tile widths the split plan of the reduction over rows was made for
+    if (g.N > 64) return launch_split<128, 128, 2, 2, MODE>(ctx, g, splits);
+    if (g.N > 32) return launch_split<128, 64, 2, 2, MODE>(ctx, g, splits);
+    return launch_split<128, 32, 4, 1, MODE>(ctx, g, splits);
+  }
+  if (g.N > 64) return launch_split<128, 64, 2, 2, MODE>(ctx, g, splits);
+  return launch_split<128, 32, 4, 1, MODE>(ctx, g, splits);
+}
+
 // The transposed global->LDS kernel: whether it takes the shape, how it splits the rows (about one workgroup per compute
 // unit: tiles x splits), and its launch.  gp_gemm_tn sizes its partial sums with the same plan.
 int gp_gemm_bf16_tn_dl_splits(int64_t rows, int M, int N) {
@@ -1289,3 +1522,10 @@ int gp_gemm_bf16_launch(gp_ctx* ctx, int mode, void* args, int splits) {
   return dispatch<MODE_TN>(ctx, g, splits);
 }
 
+// fp32 operands and result through three bf16 planes per operand (gemm_split_kernel); `g` filled as for the fp32 kernels
+int gp_gemm_split_launch(gp_ctx* ctx, int mode, void* args, int splits) {
+  gemm_args& g = *static_cast<gemm_args*>(args);
+  if (mode == MODE_NN) return dispatch_split<MODE_NN>(ctx, g, splits);
+  if (mode == MODE_NT) return dispatch_split<MODE_NT>(ctx, g, splits);
+  return dispatch_split<MODE_TN>(ctx, g, splits);
+}

@@ -212,6 +212,75 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Epilogue of one workgroup tile whose matrices are all fp32 (the fp32-result kernels).  The 32x32 MFMA block keeps, in
+// register v of lane l, row 8*(v/4) + 4*(l/32) + v%4 and column l%32.  Each wavefront transposes one block at a time
+// through its own LDS slice (32 x EPI_LD floats at smem + wave * 32 * EPI_LD; the caller has synchronised the workgroup)
+// so that a lane ends up with 4 consecutive columns: loads and stores become 16-byte accesses, eight 128-byte row
+// segments per instruction.  Blocks inside the matrix take a loop compiled for exactly the steps g.epi_mask names, the
+// others the general one (options tested per 4 values); MODE_TN writes the partial sums of split `split`.
+template <int MB, int NB, int MODE, unsigned EMASK>
+__device__ __forceinline__ void tile_epilogue_f32_blocks(const gemm_args& g, f32x16 (&acc)[MB][NB], float* smem, int64_t m0, int n0,
+                                                         int wm0, int wn0, int split) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kh = lane >> 5, l32 = lane & 31;
+  float* stage = smem + wave * (32 * EPI_LD);
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) stage[((v >> 2) * 8 + kh * 4 + (v & 3)) * EPI_LD + l32] = acc[i][j][v];
+      wave_lds_sync();
+      const bool inside = m0 + wm0 + i * 32 + 32 <= g.M && n0 + wn0 + j * 32 + 32 <= g.N;
+      if (EMASK != 0 && MODE != MODE_TN && inside) {
+        if constexpr (EMASK != 0) {
+          const int c4 = (lane & 7) * 4, col = n0 + wn0 + j * 32 + c4;
+          const int64_t o0 = (m0 + wm0 + i * 32 + (lane >> 3)) * g.N + col;
+#pragma unroll
+          for (int it = 0; it < 4; ++it) {
+            const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[(it * 8 + (lane >> 3)) * EPI_LD + c4]);
+            epilogue_store4_mask<EMASK>(g.epi, o0 + (int64_t)it * 8 * g.N, col, v4);
+          }
+        }
+      } else {
+#pragma unroll 1
+        for (int it = 0; it < 4; ++it) {
+          const int r = it * 8 + (lane >> 3), c4 = (lane & 7) * 4;
+          const f32x4 v4 = *reinterpret_cast<const f32x4*>(&stage[r * EPI_LD + c4]);
+          const int64_t row = m0 + wm0 + i * 32 + r;
+          const int col = n0 + wn0 + j * 32 + c4;
+          if (row >= g.M || col >= g.N) continue;
+          if (MODE == MODE_TN) {
+            float* dst = g.part + ((int64_t)split * g.M + row) * g.N + col;
+            if (g.vecC) *reinterpret_cast<f32x4*>(dst) = v4;
+            else
+              for (int c = 0; c < 4; ++c)
+                if (col + c < g.N) dst[c] = v4[c];
+          } else {
+            if (g.vecC) epilogue_store4(g.epi, row, col, g.N, v4);
+            else
+              for (int c = 0; c < 4; ++c)
+                if (col + c < g.N) epilogue_store(g.epi, row, col + c, g.N, v4[c]);
+          }
+        }
+      }
+      wave_lds_sync();
+    }
+}
+template <int MB, int NB, int MODE>
+__device__ __forceinline__ void tile_epilogue_f32(const gemm_args& g, f32x16 (&acc)[MB][NB], float* smem, int64_t m0, int n0,
+                                                  int wm0, int wn0, int split) {
+  if constexpr (MODE == MODE_TN) tile_epilogue_f32_blocks<MB, NB, MODE, 0u>(g, acc, smem, m0, n0, wm0, wn0, split);
+  else {
+    switch (g.epi_mask) {   // uniform
+#define GP_EM_CASE(M) case M: tile_epilogue_f32_blocks<MB, NB, MODE, M>(g, acc, smem, m0, n0, wm0, wn0, split); break;
+      GP_EM_LIST(GP_EM_CASE)
+#undef GP_EM_CASE
+      default: tile_epilogue_f32_blocks<MB, NB, MODE, 0u>(g, acc, smem, m0, n0, wm0, wn0, split); break;
+    }
+  }
+}
+
 // Workgroup ids are dealt round-robin to the 8 XCDs; renumber them so that each XCD works on
 // a contiguous range of tiles and neighbouring tiles (same A rows) share that XCD's L2.
 __device__ __forceinline__ int xcd_remap(int bid, int n) {

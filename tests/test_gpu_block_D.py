@@ -59,9 +59,16 @@ def test_basis_D_large_cutoff_small_arguments(lib, ctx):
         assert H.rel_l2(rad_g[:, col], rad_o[:, col]) < 1e-4, col
 
 
+@pytest.fixture(params=[1, 0], ids=["fp32 as three bf16 planes", "fp32 matrix-core instruction"])
+def f32_gemm(lib, ctx, request):
+    lib.gp_set_f32_gemm(ctx, request.param)
+    yield request.param
+    lib.gp_set_f32_gemm(ctx, 1)
+
+
 @pytest.mark.parametrize("rows,k,n,act", [(1, 4, 4, 0), (37, 32, 16, 1), (300, 6, 32, 0), (1000, 256, 256, 1),
                                             (513, 64, 256, 1), (2049, 256, 64, 0), (129, 42, 8, 0), (5, 7, 3, 1)])
-def test_linear_forward(lib, ctx, rows, k, n, act):
+def test_linear_forward(lib, ctx, rows, k, n, act, f32_gemm):
     rng = np.random.default_rng(rows + k)
     x = rng.standard_normal((rows, k)).astype(np.float32)
     W = synth.glorot(rng, (k, n))
@@ -71,6 +78,27 @@ def test_linear_forward(lib, ctx, rows, k, n, act):
     z = torch.tensor(x, dtype=F64) @ torch.tensor(W, dtype=F64) + torch.tensor(b, dtype=F64)
     ref = oblock.act(z) if act else z
     assert H.rel_l2(out.cpu().numpy(), ref.numpy()) < 1e-5
+
+
+def test_split_gemm_is_as_exact_as_fp32(lib, ctx):
+    # Operands with 24 significant bits and a wide range of magnitudes: the product through three bf16 planes per
+    # operand must sit as close to the fp64 product as the one the fp32-operand instruction gives (both accumulate
+    # in fp32), far below what a single bf16 plane would give (about 4e-3).
+    rng = np.random.default_rng(11)
+    rows, k, n = 4099, 1000, 264
+    x = (rng.standard_normal((rows, k)) * np.exp(rng.uniform(-6, 6, (rows, 1)))).astype(np.float32)
+    W = (rng.standard_normal((k, n)) * np.exp(rng.uniform(-3, 3, (1, n)))).astype(np.float32)
+    b = np.zeros(n, np.float32)
+    ref = (torch.tensor(x, dtype=F64) @ torch.tensor(W, dtype=F64)).numpy()
+    err = {}
+    for mode in (1, 0):
+        lib.gp_set_f32_gemm(ctx, mode)
+        out = lib.gp_linear_forward(ctx, H.to_dev(x, torch.float32), H.to_dev(W, torch.float32), H.to_dev(b, torch.float32), 0)
+        err[mode] = H.rel_l2(out.cpu().numpy(), ref)
+    lib.gp_set_f32_gemm(ctx, 1)
+    print("fp32 GEMM rel-L2 against fp64: three bf16 planes %.3e, fp32 instruction %.3e" % (err[1], err[0]))
+    assert err[0] < 1e-6 and err[1] < 1e-6
+    assert err[1] < 2.0 * err[0] + 1e-7
 
 
 @pytest.mark.parametrize("width", [3, 16, 32, 64, 128, 200])
@@ -157,6 +185,16 @@ def triplet_form(lib, ctx, request):
     lib.gp_set_triplet_mfma(ctx, request.param)
     yield request.param
     lib.gp_set_triplet_mfma(ctx, -1)
+
+
+def test_block_D_cfg2_shape_fp32_instruction(lib, ctx):
+    # the same block with its GEMMs on the fp32-operand matrix-core instruction (not the default)
+    lib.gp_set_f32_gemm(ctx, 0)
+    try:
+        w = synth.get_workload("cfg2")
+        _block_parity(lib, ctx, w, 5, n_blocks=2, pos_gptr=synth.slab_adsorbate_positions(2, 4, 4, 4, 16, seed=5))
+    finally:
+        lib.gp_set_f32_gemm(ctx, 1)
 
 
 @pytest.mark.parametrize("triplet_form", [-1, 0], indirect=True)
