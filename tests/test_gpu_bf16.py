@@ -87,3 +87,16 @@ def test_block_G_bf16_dense_box_unequal_shares(lib, ctx, trip_mode):
     from dataclasses import replace
     w = replace(synth.get_workload("cfg3", emb=64, emb_rbf=8, cutoff=7.0), max_neighbors=0)
     _parity(lib, ctx, w, 5, 1, synth.box_positions(90, 0.08, 0.9, seed=6), tol=2e-2)
+
+
+def test_block_G_bf16_tall_odd_widths(lib, ctx):
+    # More than 8192 edges, so that the layers run in the global->LDS GEMM kernels (their tall-matrix condition), at
+    # widths that leave partial tiles in every one of them: 96 and 40 output columns in the 128- and 64-wide tiles,
+    # contractions of 256, 640 and 1536, one 256-wide column tile for the gated layer with its low-rank factor.
+    from dataclasses import replace
+    w = replace(synth.get_workload("cfg3", emb=256, int_emb=96, emb_rbf=16, emb_cbf=16, emb_bil=40, num_radial=32,
+                                   num_spherical=7, cutoff=5.0), max_neighbors=0)
+    pos_gptr = synth.box_positions(330, 0.08, 0.9, seed=9)
+    ref = H.oracle_graph(pos_gptr[0], pos_gptr[1], w.dims.cutoff, 0)
+    assert len(ref["src"]) > 8192, len(ref["src"])
+    _parity(lib, ctx, w, 7, 1, pos_gptr, tol=2e-2)
