@@ -556,6 +556,8 @@ __device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[
       case EK_OUT_F32: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_OUT_F32>(g, acc, smem, m0, n0, wm0, wn0); break;
       case EK_OUT_BF16: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_OUT_BF16>(g, acc, smem, m0, n0, wm0, wn0); break;
       case EK_PRE_SILU_BF16: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_PRE_SILU_BF16>(g, acc, smem, m0, n0, wm0, wn0); break;
+      case EK_DSILU_BF16: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_DSILU_BF16>(g, acc, smem, m0, n0, wm0, wn0); break;
+      case EK_PRE_SILU_F32: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_PRE_SILU_F32>(g, acc, smem, m0, n0, wm0, wn0); break;
       case EK_PRE_SILU_LR_BF16:
         if constexpr (LR_WAVES > 0) { tile_epilogue_pairs<MB, NB, LR_WAVES, EK_PRE_SILU_LR_BF16>(g, acc, smem, m0, n0, wm0, wn0); break; }
         [[fallthrough]];
@@ -1010,7 +1012,9 @@ __device__ __forceinline__ void wait_vmcnt_lgkmcnt0() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | ((N >> 4) << 14));
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES>
+// REFILL = false: the contraction is at most STAGES slabs long, the prologue has requested all of it and the loop requests
+// nothing more (with refills, a 128-long contraction re-read its last slab twice: twice the load traffic).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, bool REFILL = true>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, WAVES_M * WAVES_N == 8 ? 1 : 2)
 gemm_dl_kernel(const gemm_args g) {
   constexpr int NW = WAVES_M * WAVES_N;
@@ -1125,7 +1129,8 @@ gemm_dl_kernel(const gemm_args g) {
       mfma_group(ks);
       __builtin_amdgcn_sched_barrier(0);
     }
-    wait_vmcnt_lgkmcnt0<(STAGES - 2) * PER>();
+    if (REFILL) wait_vmcnt_lgkmcnt0<(STAGES - 2) * PER>();
+    else wait_vmcnt_lgkmcnt0<0>();   // nothing is requested in the loop: every slab's loads were issued in the prologue
     __syncthreads();
     read_frags(st1, 0);
     __builtin_amdgcn_sched_barrier(0);
@@ -1146,7 +1151,7 @@ gemm_dl_kernel(const gemm_args g) {
 #pragma unroll
           for (int u = 0; u < LPM; ++u) {
             const int q = (i * NB + j) * LPM + u;
-            if (q < PER) {
+            if (REFILL && q < PER) {
               const int64_t d2 = second ? (wave * PER + q < A_LOADS ? dA : dB) : 0;   // uniform
               __builtin_amdgcn_global_load_lds((global_void_ptr)(src[q] + kb + d2), (lds_void_ptr)(dst + q * 1024), 16, 0, 0);
             }
@@ -1161,12 +1166,12 @@ gemm_dl_kernel(const gemm_args g) {
   tile_epilogue<MB, NB, MODE_NT, NW>(g, acc, smem, m0, n0, wm0, wn0, 0);
 }
 
-template <int BM, int BN, int WMS, int WNS, int BK, int STAGES>
+template <int BM, int BN, int WMS, int WNS, int BK, int STAGES, bool REFILL = true>
 int launch_dl(gp_ctx* ctx, gemm_args& g) {
   const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (tiles > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
   static char name[48];
-  if (!name[0]) snprintf(name, sizeof(name), "gemm_bf16_dl_nt_%dx%d", BM, BN);
+  if (!name[0]) snprintf(name, sizeof(name), "gemm_bf16_dl_nt_%dx%d%s", BM, BN, REFILL ? "" : "_shortk");
   const double mnk = (double)g.M * g.N * g.K;
   gp_prof_scope prof(ctx, name, 2.0 * mnk,
                      2.0 * (double)g.M * g.K + 2.0 * (double)g.K * g.N + ((g.epi.bf16 & EPI_BF_OUT) ? 2.0 : 4.0) * (double)g.M * g.N);
@@ -1179,12 +1184,13 @@ int launch_dl(gp_ctx* ctx, gemm_args& g) {
     return gp_fail(ctx, GP_BAD_ARG, "gemm: low-rank epilogue factor needs rank 1..16 and 16-byte aligned epilogue matrices");
   static bool raised = false;
   if (!raised && lds > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dl_kernel<BM, BN, WMS, WNS, BK, STAGES>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dl_kernel<BM, BN, WMS, WNS, BK, STAGES, REFILL>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return gp_fail(ctx, GP_HIP_ERROR, "gemm: cannot raise the dynamic LDS limit to %zu bytes", lds);
     raised = true;
   }
-  gemm_dl_kernel<BM, BN, WMS, WNS, BK, STAGES><<<dim3((unsigned)tiles), 64 * NW, lds, ctx->stream>>>(g);
+  if (!REFILL && g.K > BK * STAGES) return gp_fail(ctx, GP_BAD_ARG, "gemm: contraction longer than the ring of the no-refill kernel");
+  gemm_dl_kernel<BM, BN, WMS, WNS, BK, STAGES, REFILL><<<dim3((unsigned)tiles), 64 * NW, lds, ctx->stream>>>(g);
   GP_LAUNCH_CHECK(ctx, "gemm_dl_kernel");
   return GP_OK;
 }
@@ -1445,7 +1451,7 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
   // tall activations times a wide weight matrix, both bf16 and k-contiguous: global->LDS loads, 256x256 tiles
   if (MODE == MODE_NT && g.a_bf16 && g.b_bf16 && g.M >= 8192 && g.N > 128 && g.K % 64 == 0 && g.K >= 128 &&
       g.lda % 8 == 0 && g.ldb % 8 == 0 && (!g.A2 || g.K % 128 == 0))
-    return launch_dl<256, 256, 2, 4, 64, 2>(ctx, g);
+    return g.K <= 128 ? launch_dl<256, 256, 2, 4, 64, 2, false>(ctx, g) : launch_dl<256, 256, 2, 4, 64, 2>(ctx, g);
   // ... times a narrow one (a long contraction into 33..128 columns): the same kernel streams the activations, which is all
   // that bounds these products, through a deeper ring; 8 wavefronts of 64x64 or 32x64
   if (MODE == MODE_NT && g.a_bf16 && g.b_bf16 && g.M >= 8192 && g.N > 32 && g.N <= 128 && g.K % 64 == 0 && g.K >= 256 &&

@@ -57,12 +57,18 @@ enum {
   EK_PRE_SILU_BF16,           // save_pre (bf16), SiLU, out (bf16)
   EK_PRE_SILU_LR_BF16,        // save_pre (bf16), SiLU, times the low-rank factor, out (bf16)
   EK_PRE_SILU_ADD_F32,        // save_pre (bf16), SiLU, + add_post (bf16), times scale, out (fp32)
+  EK_DSILU_BF16,              // times SiLU'(zsrc) (fp32), out (bf16)
+  EK_PRE_SILU_F32,            // save_pre (fp32), SiLU, out (fp32)
 };
 inline int gp_epilogue_kind(const gp_epilogue& e, int vecC) {
-  if (!vecC || e.bias || e.add_pre || e.out2 || e.act == 2 || e.mul || !e.out) return EK_GENERIC;
+  if (!vecC || e.bias || e.add_pre || e.out2 || e.mul || !e.out) return EK_GENERIC;
   const unsigned b = e.bf16;
+  if (e.act == 2)
+    return (!e.save_pre && !e.lr_a && !e.add_post && e.scale == 1.0f && e.zsrc && !(b & EPI_BF_ZSRC) && (b & EPI_BF_OUT)) ? EK_DSILU_BF16
+                                                                                                                        : EK_GENERIC;
   if (!e.save_pre && e.act == 0 && !e.lr_a && !e.add_post && e.scale == 1.0f)
     return (b & EPI_BF_OUT) ? EK_OUT_BF16 : EK_OUT_F32;
+  if (e.save_pre && b == 0u && e.act == 1 && !e.add_post && !e.lr_a && e.scale == 1.0f) return EK_PRE_SILU_F32;
   if (e.save_pre && (b & EPI_BF_SAVE_PRE) && e.act == 1) {
     if (!e.add_post && e.scale == 1.0f && (b & EPI_BF_OUT)) return e.lr_a ? EK_PRE_SILU_LR_BF16 : EK_PRE_SILU_BF16;
     if (e.add_post && (b & EPI_BF_ADD_POST) && !e.lr_a && !(b & EPI_BF_OUT)) return EK_PRE_SILU_ADD_F32;
@@ -162,7 +168,17 @@ __device__ __forceinline__ void epilogue_store4_kind(const gp_epilogue& e, int64
   static_assert(KIND != EK_GENERIC, "the general loop calls epilogue_store4");
   if constexpr (KIND == EK_OUT_F32) st4(e.out + o, v);
   else if constexpr (KIND == EK_OUT_BF16) st4h(e.out, o, v);
-  else {
+  else if constexpr (KIND == EK_PRE_SILU_F32) {
+    st4(e.save_pre + o, v);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] = silu_f(v[c]);
+    st4(e.out + o, v);
+  } else if constexpr (KIND == EK_DSILU_BF16) {
+    const f32x4 z = ld4(e.zsrc + o);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] *= dsilu_f(z[c]);
+    st4h(e.out, o, v);
+  } else {
     st4h(e.save_pre, o, v);
 #pragma unroll
     for (int c = 0; c < 4; ++c) v[c] = silu_f(v[c]);
