@@ -16,8 +16,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# mfma_f32x3: fp32 GEMMs computed as six bf16 plane products per fp32 product (operands split into three bf16 planes):
+# the ceiling of their fp32-equivalent rate is a sixth of the bf16 matrix-core peak
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma_f32": (157.3, "TFLOP/s"), "mfma_bf16": (2500.0, "TFLOP/s"),
-        "alu_f32": (78.6, "TFLOP/s")}
+        "mfma_f32x3": (round(2500.0 / 6.0, 1), "TFLOP/s"), "alu_f32": (78.6, "TFLOP/s")}
 ALU_KERNELS = ("tripD_fwd", "tripD_bwd", "tripG_fwd", "trip_bwd_H", "tripG_grad_cos", "tripG_edge")
 
 
@@ -262,7 +264,9 @@ def main():
     kernels = []
     for name, d in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
         per_launch_ms = d["ms"] / d["launches"]
-        if name.startswith(("gemm_f32", "tripD_mfma")):
+        if name.startswith("gemm_f32x3"):
+            ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_f32x3"], "mfma"
+        elif name.startswith(("gemm_f32", "tripD_mfma")):
             ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_f32"], "mfma"
         elif name.startswith(("gemm_bf16", "tripG_mfma")):
             ach, (peak, unit), bound = d["flops"] / (d["ms"] * 1e-3) / 1e12, PEAK["mfma_bf16"], "mfma"
@@ -275,9 +279,11 @@ def main():
                         "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
     # the same fractions against rates measured on this GPU (copy kernel, register-resident MFMA chains)
     mp = gp.gp_measure_peaks(ctx)
-    measured = {"hbm": mp["copy_GBps"], "mfma_f32": mp["mfma_f32_TFLOPs"], "mfma_bf16": mp["mfma_bf16_TFLOPs"]}
+    measured = {"hbm": mp["copy_GBps"], "mfma_f32": mp["mfma_f32_TFLOPs"], "mfma_bf16": mp["mfma_bf16_TFLOPs"],
+                "mfma_f32x3": mp["mfma_bf16_TFLOPs"] / 6.0}
     for k in kernels:
         key = "hbm" if k["bound"] == "hbm" else ("mfma_bf16" if k["peak"] == PEAK["mfma_bf16"][0] else
+                                                  "mfma_f32x3" if k["peak"] == PEAK["mfma_f32x3"][0] else
                                                   "mfma_f32" if k["bound"] == "mfma" else None)
         k["frac_of_measured"] = round(k["achieved"] / measured[key], 4) if key else None
     top = kernels[0]
@@ -320,7 +326,9 @@ def main():
                                                         ", output block per interaction block" if a.output_blocks else
                                                         (", radial factor at the target edge" if a.radial_at_target else "") +
                                                         (", symmetric messages" if a.symmetric else "")),
-                   "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed},
+                   "cutoff": dims.cutoff, "max_neighbors": w.max_neighbors, "seed": a.seed,
+                   "f32_gemm": "three bf16 planes per operand, six products, fp32 accumulation (error as fp32)" if a.f32_gemm == "split"
+                               else "fp32-operand matrix-core instruction"},
         "roofline": roofline,
         "roofline_triplet": roofline_triplet,
         "measured_peaks": {k: round(v, 1) for k, v in mp.items()},

@@ -65,6 +65,7 @@ int gp_ew_add3(gp_ctx* ctx, const float* a, const float* b, const float* c, floa
 int gp_gemm_bf16_launch(gp_ctx* ctx, int mode, void* args, int splits);
 // fp32 operands and result on the bf16 matrix cores, each operand as three bf16 planes (gemm_bf16.hip)
 int gp_gemm_split_launch(gp_ctx* ctx, int mode, void* args, int splits);
+bool gp_gemm_split_tn_ok(int64_t M, int N, int vecA, int vecB);   // whether A^T B of this shape runs in that form
 // A^T B with both operands bf16 through global->LDS loads and LDS transpose reads: number of splits of its plan (0: the
 // shape is not taken), whether the filled argument block qualifies, launch
 int gp_gemm_bf16_tn_dl_splits(int64_t rows, int M, int N);

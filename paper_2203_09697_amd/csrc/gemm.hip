@@ -371,9 +371,8 @@ int dispatch_gemm(gp_ctx* ctx, gemm_args& g, int splits) {
   if (g.a_bf16 || g.b_bf16 || g.epi.bf16)
     return gp_fail(ctx, GP_BAD_ARG, "gemm: bf16 storage is only handled by the bf16-operand kernels");
   if (g.epi.lr_a) return gp_fail(ctx, GP_BAD_ARG, "gemm: a low-rank epilogue factor is only taken by the global->LDS bf16 kernel");
-  // the reduction over rows stays on the fp32-operand instruction: its loaders transpose in registers and its partial sums
-  // are traffic, not arithmetic (measured: 60 vs 65 us at 43 372 x 256 x 256, 2.30 vs 2.38 ms at 43 372 x 2048 x 2048)
-  if (ctx->f32_split && MODE != MODE_TN) return gp_gemm_split_launch(ctx, MODE, &g, splits);
+  // the reduction over rows in that form has one tile shape (128 x 128) and wants 16-byte aligned rows
+  if (ctx->f32_split && (MODE != MODE_TN || gp_gemm_split_tn_ok(g.M, g.N, g.vecA, g.vecB))) return gp_gemm_split_launch(ctx, MODE, &g, splits);
   if (MODE == MODE_TN) {   // tile widths the split plan (tn_plan / tile_bn) was made for
     if (g.N > 64) return launch_gemm<TILE_BM, 128, 2, 2, MODE>(ctx, g, splits);
     if (g.N > 32) return launch_gemm<TILE_BM, 64, 2, 2, MODE>(ctx, g, splits);

@@ -254,20 +254,6 @@ struct bl_xcontig {
       }
     }
   }
-  // cs[it][c] += the sum over the 8 k rows this thread holds of column xq + c (the fetched slab)
-  __device__ __forceinline__ void add_colsum(float (&cs)[NV][4], bool tail) const {
-#pragma unroll
-    for (int it = 0; it < NV; ++it) {
-      if (!ALL && (int)threadIdx.x + it * THREADS >= GROUPS) continue;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        float t = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) t += (!tail || ((kmask[it] >> kk) & 1u)) ? r[it][kk][c] : 0.f;
-        cs[it][c] += t;
-      }
-    }
-  }
 };
 
 // ---- operands already stored as bf16 (activations written by a producer's epilogue): no conversion,
@@ -701,16 +687,17 @@ gemm_bf16_kernel(const gemm_args g) {
 // product is not below 2^-24 of the full one (hi.hi, hi.mid, mid.hi, hi.lo, mid.mid, lo.hi), smallest first, into the
 // fp32 accumulator: the error of a product is that of one fp32 rounding.  Six bf16 MFMAs (32 cycles each for 16 k)
 // replace eight fp32 ones (64 cycles each for 2 k): the fp32-operand MFMA rate of this chip is a sixteenth of the
-// bf16 one.  Same tiles, loaders and pipeline as gemm_bf16_kernel, the fp32 kernel's epilogue (all matrices fp32)
-// and, for A^T B, its column sums of B (the bias gradient), taken from the loader's registers in fp32.
+// bf16 one.  Same tiles, loaders and pipeline as gemm_bf16_kernel, the fp32 kernel's epilogue (all matrices fp32).
+// A B and A B^T; A^T B has a kernel of its own (gemm_split_tn_kernel).
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE, bool VEC>
 __global__ void __launch_bounds__(THREADS, 2)
 gemm_split_kernel(const gemm_args g) {
   static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+  static_assert(MODE != MODE_TN, "the reduction over rows runs in gemm_split_tn_kernel");
   constexpr int PL = 3;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MB = WM / 32, NB = WN / 32;
-  using loadA = typename std::conditional<MODE != MODE_TN, bl_kcontig<BM, VEC>, bl_xcontig<BM, VEC>>::type;
+  using loadA = bl_kcontig<BM, VEC>;
   using loadB = typename std::conditional<MODE == MODE_NT, bl_kcontig<BN, VEC>, bl_xcontig<BN, VEC>>::type;
   extern __shared__ __attribute__((aligned(16))) float smem[];
   constexpr int PA = BM * LDK, PB = BN * LDK;   // plane strides (bf16 elements)
@@ -720,15 +707,9 @@ gemm_split_kernel(const gemm_args g) {
   const int tiles_n = (g.N + BN - 1) / BN;
   const int tiles_m = (int)((g.M + BM - 1) / BM);
   const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  const int tile_m = tile / tiles_n;
-  const int64_t m0 = (int64_t)tile_m * BM;
+  const int64_t m0 = (int64_t)(tile / tiles_n) * BM;
   const int n0 = (tile % tiles_n) * BN;
-
-  int64_t k_begin = 0, k_end = g.K;
-  if (MODE == MODE_TN) {
-    k_begin = (int64_t)blockIdx.y * g.k_per_split;
-    k_end = k_begin + g.k_per_split < (int64_t)g.K ? k_begin + g.k_per_split : (int64_t)g.K;
-  }
+  const int64_t k_begin = 0, k_end = g.K;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
@@ -741,13 +722,6 @@ gemm_split_kernel(const gemm_args g) {
     for (int j = 0; j < NB; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  constexpr int CSN = MODE == MODE_TN ? loadB::NV : 1;
-  float cs[CSN][4];
-#pragma unroll
-  for (int it = 0; it < CSN; ++it)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) cs[it][c] = 0.f;
-  const bool want_cs = MODE == MODE_TN && g.colsum_part != nullptr;
 
   if (k_begin < k_end) {
     loadA la;
@@ -779,13 +753,9 @@ gemm_split_kernel(const gemm_args g) {
           }
       }
     };
-    // the slab held in the loaders' registers goes to LDS; its part of the column sums is taken on the way
-    auto store = [&](int64_t slab, bool tail) {
+    auto store = [&](int64_t, bool tail) {   // the slab held in the loaders' registers goes to LDS
       la.template store_planes<PL>(As, PA, tail);
       lb.template store_planes<PL>(Bs, PB, tail);
-      if constexpr (MODE == MODE_TN) {
-        if (want_cs && (slab % tiles_m) == tile_m) lb.add_colsum(cs, tail);
-      }
     };
     const int64_t n_full = (k_end - k_begin) / BKH;
     if (n_full > 0) {
@@ -815,25 +785,7 @@ gemm_split_kernel(const gemm_args g) {
     }
   }
 
-  tile_epilogue_f32<MB, NB, MODE>(g, acc, smem, m0, n0, wm0, wn0, blockIdx.y);
-  if constexpr (MODE == MODE_TN) {
-    if (want_cs) {
-      // the 4 threads that share a group of 4 columns (one per 8-k group of the slab) are neighbouring lanes
-#pragma unroll
-      for (int it = 0; it < CSN; ++it) {
-        const int idx = threadIdx.x + it * THREADS;
-        const int xq = (idx / K8) * 4;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          float v = cs[it][c];
-          v += __shfl_xor(v, 1, 64);
-          v += __shfl_xor(v, 2, 64);
-          if ((threadIdx.x & 3) == 0 && (loadB::ALL || idx < loadB::GROUPS) && xq + c < BN && n0 + xq + c < g.N)
-            g.colsum_part[((int64_t)blockIdx.y * tiles_m + tile_m) * g.N + n0 + xq + c] = v;
-        }
-      }
-    }
-  }
+  tile_epilogue_f32<MB, NB, MODE>(g, acc, smem, m0, n0, wm0, wn0, 0);
 }
 
 // Both operands stored as bf16.  A slab is then only 6 sixteen-byte loads per thread, so NS slabs are kept in
@@ -1473,6 +1425,158 @@ int dispatch(gp_ctx* ctx, gemm_args& g, int splits) {
 
 }  // namespace
 
+// ---- C = A^T B with fp32 operands [rows, M], [rows, N] as three bf16 planes each (see gemm_split_kernel): the weight
+// gradients of the fp32 blocks.  The contraction index is the slow one of both operands, so a slab (32 rows x 128
+// columns per operand) is split where it is loaded, 4 consecutive columns per thread, and stored as it lies in memory,
+// [plane][k][x] in bf16; the MFMA operand fragments (8 consecutive k of one x per lane) come from the LDS transpose loads
+// as in gemm_tn_dl_kernel (chunk c of row k at c ^ 2 (k % 4)), so nothing is transposed in registers.  128x128 tiles, four
+// wavefronts of 64x64, grid (tiles, splits) and partial sums as the fp32 kernel's plan (tn_plan) lays them out; the
+// column sums of B (bias gradients) are taken from the loaded fp32 values.  Needs 16-byte aligned rows (the caller
+// falls back to the fp32-operand kernel otherwise).
+__global__ void __launch_bounds__(THREADS, 2)
+gemm_split_tn_kernel(const gemm_args g) {
+  constexpr int PL = 3, BM = 128, BN = 128, BK = 32, MB = 2, NB = 2;
+  constexpr int ROW_B = 256;                          // bytes of a slab row of one operand and plane (128 bf16)
+  constexpr int PLANE_B = BK * ROW_B, OPER_B = PL * PLANE_B;
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  char* lds = reinterpret_cast<char*>(smem);
+
+  const int tiles_n = (g.N + BN - 1) / BN;
+  const int tiles_m = (int)((g.M + BM - 1) / BM);
+  const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  const int tile_m = tile / tiles_n;
+  const int m0 = tile_m * BM, n0 = (tile % tiles_n) * BN;
+  const int64_t k_begin = (int64_t)blockIdx.y * g.k_per_split;
+  const int64_t k_end = k_begin + g.k_per_split < (int64_t)g.K ? k_begin + g.k_per_split : (int64_t)g.K;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+
+  // loader: thread t holds, per operand, the 4 columns 4 (t % 32) .. + 3 of the rows t / 32 + 8 i (i = 0..3) of the slab;
+  // columns past the matrix are read from its last 4 (their products are never stored)
+  const int lx = (threadIdx.x & 31) * 4, lr = threadIdx.x >> 5;
+  const int ax = m0 + lx + 4 <= (int)g.M ? m0 + lx : (int)g.M - 4;
+  const int bx = n0 + lx + 4 <= g.N ? n0 + lx : g.N - 4;
+  f32x4 ra[4], rb[4];
+  auto fetch = [&](int64_t k0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t k = k0 + lr + 8 * i;
+      const int64_t kc = k < k_end ? k : k_end - 1;   // rows past the end: a valid row, zeroed below
+      ra[i] = *reinterpret_cast<const f32x4*>(g.A + kc * g.lda + ax);
+      rb[i] = *reinterpret_cast<const f32x4*>(g.B + kc * g.ldb + bx);
+    }
+  };
+  f32x4 cs = {0.f, 0.f, 0.f, 0.f};                   // column sums of B over this thread's rows
+  const bool want_cs = g.colsum_part != nullptr;
+  auto split4 = [&](char* dst, f32x4 v) __attribute__((always_inline)) {
+#pragma unroll
+    for (int p = 0; p < PL; ++p) {
+      bf16x4 h;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) h[c] = (__bf16)v[c];
+      *reinterpret_cast<bf16x4*>(dst + p * PLANE_B) = h;
+      if (p + 1 < PL) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] -= (float)h[c];
+      }
+    }
+  };
+  auto store = [&](int64_t k0, int slab) __attribute__((always_inline)) {
+    const bool mine = want_cs && (slab % tiles_m) == tile_m;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = lr + 8 * i;
+      const float keep = k0 + row < k_end ? 1.f : 0.f;
+      const int off = row * ROW_B + ((((lx >> 3) ^ (2 * (row & 3)))) << 4) + ((lx & 4) << 1);
+      split4(lds + off, ra[i] * keep);
+      split4(lds + OPER_B + off, rb[i] * keep);
+      if (mine) cs += rb[i] * keep;
+    }
+  };
+
+  f32x16 acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // transpose-load addresses (see gemm_tn_dl_kernel): 16-lane block b holds k-half b / 2 and x-half b % 2 of a 32-wide block
+  const int b16 = lane >> 4, i16 = lane & 15;
+  const int krow = 8 * (b16 >> 1) + (i16 >> 2);       // + 4 h + 16 ks
+  const int sw = 2 * (i16 >> 2);
+  int a_off[MB], b_off[NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i) a_off[i] = ((((wm0 + 32 * i) / 8 + 2 * (b16 & 1) + ((i16 & 3) >> 1)) ^ sw) << 4) + ((i16 & 1) << 3);
+#pragma unroll
+  for (int j = 0; j < NB; ++j) b_off[j] = OPER_B + ((((wn0 + 32 * j) / 8 + 2 * (b16 & 1) + ((i16 & 3) >> 1)) ^ sw) << 4) + ((i16 & 1) << 3);
+  auto frag = [&](const char* p) __attribute__((always_inline)) {
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)p);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(p + 4 * ROW_B));
+    typedef short v8s __attribute__((ext_vector_type(8)));
+    const v8s both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, both);
+  };
+  auto multiply = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const char* sb = lds + (16 * ks + krow) * ROW_B;
+      bf16x8 a[PL][MB], b[PL][NB];
+#pragma unroll
+      for (int p = 0; p < PL; ++p) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) a[p][i] = frag(sb + p * PLANE_B + a_off[i]);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) b[p][j] = frag(sb + p * PLANE_B + b_off[j]);
+      }
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          f32x16 c = acc[i][j];
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2][i], b[0][j], c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[2][j], c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[1][j], c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[0][j], c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[1][j], c, 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[0][j], c, 0, 0, 0);
+        }
+    }
+  };
+
+  if (k_begin < k_end) {
+    const int n_slabs = (int)((k_end - k_begin + BK - 1) / BK);
+    fetch(k_begin);
+    store(k_begin, 0);
+    __syncthreads();
+    for (int s = 1; s < n_slabs; ++s) {
+      fetch(k_begin + (int64_t)s * BK);
+      multiply();
+      __syncthreads();
+      store(k_begin + (int64_t)s * BK, s);
+      __syncthreads();
+    }
+    multiply();
+  }
+  __syncthreads();   // all wavefronts are done with the operand planes; LDS is reused below
+  if (want_cs) {
+    // the 8 threads that share 4 columns (one per row group) sit in different wavefronts: through LDS, fixed order
+    float* red = smem;
+    *reinterpret_cast<f32x4*>(red + lr * BN + lx) = cs;
+    __syncthreads();
+    if (threadIdx.x < BN) {
+      float t = 0.f;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) t += red[r * BN + threadIdx.x];
+      // a thread whose columns were clamped into the matrix holds sums of other columns: only true columns are written
+      if (n0 + (int)threadIdx.x < g.N) g.colsum_part[((int64_t)blockIdx.y * tiles_m + tile_m) * g.N + n0 + threadIdx.x] = t;
+    }
+    __syncthreads();
+  }
+  tile_epilogue_f32<MB, NB, MODE_TN>(g, acc, smem, m0, n0, wm0, wn0, blockIdx.y);
+}
+
 template <int BM, int BN, int WMS, int WNS, int MODE>
 int launch_split(gp_ctx* ctx, gemm_args& g, int splits) {
   const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
@@ -1494,15 +1598,26 @@ int launch_split(gp_ctx* ctx, gemm_args& g, int splits) {
   return GP_OK;
 }
 
+int launch_split_tn(gp_ctx* ctx, gemm_args& g, int splits) {
+  const int64_t tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
+  if (tiles > INT32_MAX) return gp_fail(ctx, GP_BAD_ARG, "gemm: too many tiles");
+  if (!gp_gemm_split_tn_ok(g.M, g.N, g.vecA, g.vecB)) return gp_fail(ctx, GP_BAD_ARG, "gemm (split fp32, A^T B): shape or alignment not taken");
+  gp_prof_scope prof(ctx, "gemm_f32x3_tn_128x128", 2.0 * (double)g.M * g.N * g.K,
+                     4.0 * ((double)g.M * g.K + (double)g.K * g.N + (double)g.M * g.N * splits));
+  constexpr size_t lds = 2 * 3 * 32 * 256;   // both operands, three planes, 32 rows of 128 bf16 (above the epilogue's staging)
+  static_assert(lds >= sizeof(float) * 4 * 32 * EPI_LD && lds >= sizeof(float) * 8 * 128 && lds <= 64 * 1024, "LDS uses of the kernel");
+  gemm_split_tn_kernel<<<dim3((unsigned)tiles, (unsigned)splits, 1), THREADS, lds, ctx->stream>>>(g);
+  GP_LAUNCH_CHECK(ctx, "gemm_split_tn_kernel");
+  return GP_OK;
+}
+
 template <int MODE>
 int dispatch_split(gp_ctx* ctx, gemm_args& g, int splits) {
-  if (MODE == MODE_TN) {   // tile widths the split plan of the reduction over rows was made for
-    if (g.N > 64) return launch_split<128, 128, 2, 2, MODE>(ctx, g, splits);
-    if (g.N > 32) return launch_split<128, 64, 2, 2, MODE>(ctx, g, splits);
-    return launch_split<128, 32, 4, 1, MODE>(ctx, g, splits);
-  }
+  if constexpr (MODE == MODE_TN) return launch_split_tn(ctx, g, splits);
+  else {
   if (g.N > 64) return launch_split<128, 64, 2, 2, MODE>(ctx, g, splits);
   return launch_split<128, 32, 4, 1, MODE>(ctx, g, splits);
+  }
 }
 
 // The transposed global->LDS kernel: whether it takes the shape, how it splits the rows (about one workgroup per compute
@@ -1535,3 +1650,6 @@ int gp_gemm_split_launch(gp_ctx* ctx, int mode, void* args, int splits) {
   if (mode == MODE_NT) return dispatch_split<MODE_NT>(ctx, g, splits);
   return dispatch_split<MODE_TN>(ctx, g, splits);
 }
+
+// A^T B in the three-plane form: 128-wide tiles of its plan (N > 64), rows of both operands in 16-byte pieces
+bool gp_gemm_split_tn_ok(int64_t M, int N, int vecA, int vecB) { return N > 64 && M >= 4 && vecA && vecB; }

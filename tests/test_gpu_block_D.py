@@ -271,6 +271,15 @@ def test_block_D_odd_widths(lib, ctx):
     _block_parity(lib, ctx, w, 4, n_blocks=1)
 
 
+@pytest.mark.parametrize("f32_gemm", [1, 0], indirect=True, ids=["fp32 as three bf16 planes", "fp32 matrix-core instruction"])
+def test_block_D_partial_tiles(lib, ctx, f32_gemm):
+    # widths that are multiples of 4 (16-byte rows: the vector loaders and the three-plane weight-gradient kernel) but of
+    # no tile size: 200 and 72 columns in 128-, 64- and 32-wide tiles, contractions of 200, 72, 12 with a partial last slab
+    w = synth.get_workload("cfg1", emb=200, int_emb=72, basis_emb=8, num_radial=12, num_spherical=5,
+                           n_res_before=1, n_res_after=1)
+    _block_parity(lib, ctx, w, 6, n_blocks=1)
+
+
 def test_block_D_deterministic(lib, ctx):
     from paper_2203_09697_amd.stack import StackD
     w = synth.get_workload("cfg1")
