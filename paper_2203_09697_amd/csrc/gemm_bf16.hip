@@ -1615,6 +1615,8 @@ template <int MODE>
 int dispatch_split(gp_ctx* ctx, gemm_args& g, int splits) {
   if constexpr (MODE == MODE_TN) return launch_split_tn(ctx, g, splits);
   else {
+  // wide results with work for every compute unit several times over: twice the MFMAs per operand fragment read
+  if (g.N > 64 && ((g.M + 127) / 128) * ((g.N + 127) / 128) >= 2048) return launch_split<128, 128, 2, 2, MODE>(ctx, g, splits);
   if (g.N > 64) return launch_split<128, 64, 2, 2, MODE>(ctx, g, splits);
   return launch_split<128, 32, 4, 1, MODE>(ctx, g, splits);
   }

@@ -67,7 +67,8 @@ def f32_gemm(lib, ctx, request):
 
 
 @pytest.mark.parametrize("rows,k,n,act", [(1, 4, 4, 0), (37, 32, 16, 1), (300, 6, 32, 0), (1000, 256, 256, 1),
-                                            (513, 64, 256, 1), (2049, 256, 64, 0), (129, 42, 8, 0), (5, 7, 3, 1)])
+                                            (513, 64, 256, 1), (2049, 256, 64, 0), (129, 42, 8, 0), (5, 7, 3, 1),
+                                            (16400, 72, 2048, 1)])   # the last: enough tiles for the 128 x 128 form
 def test_linear_forward(lib, ctx, rows, k, n, act, f32_gemm):
     rng = np.random.default_rng(rows + k)
     x = rng.standard_normal((rows, k)).astype(np.float32)
