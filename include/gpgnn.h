@@ -349,6 +349,29 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
                         float* grad_rbf, float* grad_cos_kj, int32_t accumulate_basis_grads,
                         void* scratch, size_t scratch_bytes);
 
+/* The same two calls for a stack of bilinear blocks with bf16 GEMM operands (Sec. 3.4; Sec. 4.5 stacks several blocks).
+ * Such a block reads its input messages only as bf16 GEMM operands, so the block below can hand them over in that
+ * storage: with m_out_bf16 != 0, m_out receives [E, emb] bf16 values (the fp32 result rounded to nearest even, i.e.
+ * exactly what the next block would round it to) instead of fp32; with m_in_bf16 != 0, m_in is such a matrix and the
+ * rounding pass over it is skipped; the backward call of that block must be given the same m_in with the same flag.
+ * Likewise for the gradients in the backward pass: grad_m_in_bf16 != 0 stores grad_m_in as bf16, grad_m_out_bf16 != 0
+ * reads grad_m_out as bf16 (this rounds a gradient once more than the fp32 hand-over does; not available for
+ * symmetric blocks, whose opposite-edge gather reads fp32).  All flags 0: identical to the calls above.
+ * gp_block_G_stacks_bf16(dims) returns 1 when dims allow the flags (variant G, bf16 operands, emb a multiple of 8,
+ * even int_emb and emb_bil), else 0; a flag given for other dims fails with GP_BAD_ARG.  Everything else (pointers on the
+ * device, sizes, ownership, errors) as for gp_block_forward_G / gp_block_backward_G. */
+int gp_block_G_stacks_bf16(const gp_dims* dims);
+int gp_block_forward_G_stacked(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
+                               const gp_graph* graph, const gp_basis* basis,
+                               const void* m_in, int32_t m_in_bf16, void* m_out, int32_t m_out_bf16,
+                               void* saved, size_t saved_bytes, void* scratch, size_t scratch_bytes);
+int gp_block_backward_G_stacked(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
+                                const gp_graph* graph, const gp_basis* basis,
+                                const void* m_in, int32_t m_in_bf16, const void* saved, size_t saved_bytes,
+                                const void* grad_m_out, int32_t grad_m_out_bf16, void* grad_m_in, int32_t grad_m_in_bf16,
+                                gp_weights_G* grad_w, float* grad_rbf, float* grad_cos_kj,
+                                int32_t accumulate_basis_grads, void* scratch, size_t scratch_bytes);
+
 /* ------------------------------------------------------------------------------------------
  * Energy head (Sec. 3.3 output step: messages summed per target atom, then an MLP) and forces
  * (Sec. 3.2, energy-centric: f = -dE/dx by back-propagation).

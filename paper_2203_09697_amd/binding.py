@@ -30,7 +30,7 @@ EXPORTED_SYMBOLS = [
     "gp_triplets_count_pbc", "gp_triplets_fill_pbc",
     "gp_triplets_workspace", "gp_triplets_count", "gp_triplets_fill", "gp_csr_max_degree", "gp_reverse_edges",
     "gp_basis_forward", "gp_block_workspace", "gp_block_forward_D", "gp_block_backward_D", "gp_block_backward_D_basis",
-    "gp_block_forward_G", "gp_block_backward_G",
+    "gp_block_forward_G", "gp_block_backward_G", "gp_block_G_stacks_bf16", "gp_block_forward_G_stacked", "gp_block_backward_G_stacked",
     "gp_energy_workspace", "gp_energy_forward", "gp_energy_backward",
     "gp_output_workspace", "gp_output_forward", "gp_output_backward",
     "gp_edges_by_source_workspace", "gp_edges_by_source", "gp_edges_by_source_static", "gp_forces_workspace", "gp_forces_from_basis_grad", "gp_forces_from_basis_grad_D",

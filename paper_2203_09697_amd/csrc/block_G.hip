@@ -252,13 +252,14 @@ __global__ void sym_bwd4_kernel(const float* __restrict__ g, const ST* __restric
 // ---- bf16 storage of the [E, emb] intermediates (bf16 blocks): elementwise kernels, 4 elements per thread
 
 // d1 = g s silu'(z1), d2 = g s silu'(z2);  g fp32, everything else bf16
-__global__ void dsilu2_half_kernel(const float* __restrict__ g, float s, const __bf16* __restrict__ z1,
+template <class GT>   // GT: storage of g (float, or __bf16 when the block above handed its input gradient over as bf16)
+__global__ void dsilu2_half_kernel(const GT* __restrict__ g, float s, const __bf16* __restrict__ z1,
                                    const __bf16* __restrict__ z2, __bf16* __restrict__ d1, __bf16* __restrict__ d2,
                                    int64_t n) {
   const int64_t i = 4 * ((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
   if (i >= n) return;
   if (i + 3 < n) {
-    const f4 gv = *reinterpret_cast<const f4*>(g + i);
+    const f4 gv = load4(g, i);
     const h4 a = *reinterpret_cast<const h4*>(z1 + i), b = *reinterpret_cast<const h4*>(z2 + i);
     h4 o1, o2;
 #pragma unroll
@@ -270,8 +271,8 @@ __global__ void dsilu2_half_kernel(const float* __restrict__ g, float s, const _
     *reinterpret_cast<h4*>(d2 + i) = o2;
   } else {
     for (int64_t k = i; k < n; ++k) {
-      d1[k] = (__bf16)(g[k] * s * dsilu_f((float)z1[k]));
-      d2[k] = (__bf16)(g[k] * s * dsilu_f((float)z2[k]));
+      d1[k] = (__bf16)((float)g[k] * s * dsilu_f((float)z1[k]));
+      d2[k] = (__bf16)((float)g[k] * s * dsilu_f((float)z2[k]));
     }
   }
 }
@@ -474,11 +475,13 @@ size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t N, int64_t E, int64_t 
   return carve_scratch_G(nullptr, d, N, E, T, &s);
 }
 
-extern "C" {
+namespace {
 
-int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
-                       const gp_basis* basis, const float* m_in, float* m_out, void* saved, size_t saved_bytes,
-                       void* scratch, size_t scratch_bytes) {
+// m_in_h / m_out_h: the block input / output is a bf16 matrix (a stack of bf16 blocks hands its messages over in the
+// storage its GEMMs read them in; the values are those the fp32 hand-over would be rounded to)
+int forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
+              const gp_basis* basis, const float* m_in, int m_in_h, float* m_out, int m_out_h, void* saved, size_t saved_bytes,
+              void* scratch, size_t scratch_bytes) {
   if (!ctx) return GP_BAD_ARG;
   GP_TRY(check_dims_G(ctx, dims));
   GP_TRY(check_weights_G(ctx, dims, w, "weights"));
@@ -518,8 +521,11 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     e = gp_epilogue(); e.out = s.gate; e.bf16 = hs ? EPI_BF_OUT : 0u;
     GP_TRY(gp_gemm_nn(ctx, g, s.Wrbf, E, H, R, e));                                 // gate
   }
+  GP_REQUIRE(ctx, !(m_in_h || m_out_h) || (hs && weights_half(dims)), "gp_block_forward_G_stacked: bf16 messages need a block that stores bf16 (see gp_block_G_stacks_bf16)");
   const float* m_op = m_in;   // the input messages as a GEMM operand
-  if (hs) {
+  if (m_in_h) {
+    // already rounded; the backward call is handed the same matrix again
+  } else if (hs) {
     GP_TRY(to_half(ctx, m_in, s.m_h, (int64_t)E * H));
     m_op = reinterpret_cast<const float*>(s.m_h);
   }
@@ -607,7 +613,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
       GP_LAUNCH_CHECK(ctx, "sym_mix_kernel");
     }
     e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = 0.5f; e.out = m_out;
-    e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST) : 0u;
+    e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST | (m_out_h ? EPI_BF_OUT : 0u)) : 0u;
     if (zh) {
       GP_TRY(to_half_T(ctx, w->W_up, sc.W_up_h, O, H));
       GP_TRY(gp_gemm_nt(ctx, s.z, reinterpret_cast<const float*>(sc.W_up_h), E, H, O, e, 1, 1));
@@ -616,7 +622,7 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
     return GP_OK;
   }
   e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = INV_SQRT2; e.out = m_out;
-  e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST) : 0u;
+  e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST | (m_out_h ? EPI_BF_OUT : 0u)) : 0u;
   if (zh) {
     GP_TRY(to_half_T(ctx, w->W_up, sc.W_up_h, O, H));                               // [H, O]: activations times a [N, K] weight
     GP_TRY(gp_gemm_nt(ctx, s.z, reinterpret_cast<const float*>(sc.W_up_h), E, H, O, e, 1, 1));
@@ -625,10 +631,11 @@ int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, 
   return GP_OK;
 }
 
-int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
-                        const gp_basis* basis, const float* m_in, const void* saved, size_t saved_bytes,
-                        const float* grad_m_out, float* grad_m_in, gp_weights_G* gw, float* grad_rbf,
-                        float* grad_cos_kj, int32_t accumulate_basis_grads, void* scratch, size_t scratch_bytes) {
+// m_in_h as in forward_G; gmo_h / gmi_h: the gradient coming in / going out is a bf16 matrix
+int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
+               const gp_basis* basis, const float* m_in, int m_in_h, const void* saved, size_t saved_bytes,
+               const float* grad_m_out, int gmo_h, float* grad_m_in, int gmi_h, gp_weights_G* gw, float* grad_rbf,
+               float* grad_cos_kj, int32_t accumulate_basis_grads, void* scratch, size_t scratch_bytes) {
   if (!ctx) return GP_BAD_ARG;
   GP_TRY(check_dims_G(ctx, dims));
   GP_TRY(check_weights_G(ctx, dims, w, "weights"));
@@ -656,6 +663,8 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   gp_epilogue e;
 
   const bool wh = weights_half(dims);
+  GP_REQUIRE(ctx, !(m_in_h || gmo_h || gmi_h) || (hs && wh), "gp_block_backward_G_stacked: bf16 messages need a block that stores bf16 (see gp_block_G_stacks_bf16)");
+  GP_REQUIRE(ctx, !gmo_h || !dims->symmetric, "gp_block_backward_G_stacked: a symmetric block takes its incoming gradient as fp32");
   int rc = GP_OK;
   const float* W_up = weight_operand(ctx, wh, w->W_up, sc.W_up_h, (int64_t)O * H, &rc);
   const float* W_skip = weight_operand(ctx, wh, w->W_skip, sc.W_skip_h, (int64_t)H * H, &rc);
@@ -691,9 +700,13 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
     GP_TRY(rc);
     GP_TRY(gp_gemm_nt(ctx, d_ac, W_up_ac, E, O, H, e, hs, wh));                     // dz (opposite-edge path)
   } else if (hs) {
-    gp_prof_scope prof(ctx, "ew_dsilu2_half", 0.0, 12.0 * (double)EH);   // fp32 gradient + 4 bf16 arrays
-    dsilu2_half_kernel<<<(unsigned)((EH / 4 + 256) / 256), 256, 0, ctx->stream>>>(
-        grad_m_out, INV_SQRT2, (const __bf16*)s.z_up, (const __bf16*)s.z_skip, (__bf16*)d_up, (__bf16*)d_skip, EH);
+    gp_prof_scope prof(ctx, "ew_dsilu2_half", 0.0, (gmo_h ? 10.0 : 12.0) * (double)EH);   // the gradient + 4 bf16 arrays
+    if (gmo_h)
+      dsilu2_half_kernel<__bf16><<<(unsigned)((EH / 4 + 256) / 256), 256, 0, ctx->stream>>>(
+          reinterpret_cast<const __bf16*>(grad_m_out), INV_SQRT2, (const __bf16*)s.z_up, (const __bf16*)s.z_skip, (__bf16*)d_up, (__bf16*)d_skip, EH);
+    else
+      dsilu2_half_kernel<float><<<(unsigned)((EH / 4 + 256) / 256), 256, 0, ctx->stream>>>(
+          grad_m_out, INV_SQRT2, (const __bf16*)s.z_up, (const __bf16*)s.z_skip, (__bf16*)d_up, (__bf16*)d_skip, EH);
     GP_LAUNCH_CHECK(ctx, "dsilu2_half_kernel");
   } else {
     GP_TRY(gp_ew_dsilu2(ctx, grad_m_out, INV_SQRT2, s.z_up, s.z_skip, d_up, d_skip, EH));
@@ -702,7 +715,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   e = gp_epilogue(); e.out = sc.dz;
   if (dims->symmetric) e.add_post = sc.dz;
   GP_TRY(gp_gemm_nt(ctx, d_up, W_up, E, O, H, e, hs, wh));                          // dz
-  const float* m_op = hs ? reinterpret_cast<const float*>(s.m_h) : m_in;   // rounded copy written by the forward pass
+  const float* m_op = m_in_h ? m_in : hs ? reinterpret_cast<const float*>(s.m_h) : m_in;   // rounded copy written by the forward pass
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_op, d_skip, E, H, H, gw->W_skip, nullptr, sc.part_aux, sc.part_bytes, hs, hs); }, {}));
   // dm = d_skip W_skip^T + dz_ba W_ba^T.  With bf16 storage both products run as ONE GEMM at the end of the call (its
   // contraction walks both operand pairs), so dm is written once instead of written, read back and written again
@@ -835,7 +848,7 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
   GP_TRY(gp_gemm_tn(ctx, w->W_rbfS, sc.dWrbf, R, RB, H, gw->W_rbfB, nullptr, sc.part, sc.part_bytes));
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, m_op, dz_ba, E, H, H, gw->W_ba, nullptr, sc.part_aux, sc.part_bytes, hs, hs); }, {}));
   if (dm_fused) {
-    GP_TRY(gp_gemm_nt2(ctx, d_skip, W_skip, dz_ba, W_ba, E, H, H, grad_m_in, 1, 1));  // dm, both paths
+    GP_TRY(gp_gemm_nt2(ctx, d_skip, W_skip, dz_ba, W_ba, E, H, H, grad_m_in, 1, 1, gmi_h));  // dm, both paths
   } else {
     e = gp_epilogue(); e.add_post = grad_m_in; e.out = grad_m_in;
     GP_TRY(gp_gemm_nt(ctx, dz_ba, W_ba, E, H, H, e, hs, wh));                       // dm += ba path
@@ -849,6 +862,45 @@ int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w,
     GP_TRY(gp_gemm_nn(ctx, sc.dRad, s.WcT, E, R, S * C, e));
   }
   return aux.join();
+}
+
+}  // namespace
+
+extern "C" {
+
+int gp_block_forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
+                       const gp_basis* basis, const float* m_in, float* m_out, void* saved, size_t saved_bytes,
+                       void* scratch, size_t scratch_bytes) {
+  return forward_G(ctx, dims, w, graph, basis, m_in, 0, m_out, 0, saved, saved_bytes, scratch, scratch_bytes);
+}
+
+int gp_block_backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
+                        const gp_basis* basis, const float* m_in, const void* saved, size_t saved_bytes,
+                        const float* grad_m_out, float* grad_m_in, gp_weights_G* gw, float* grad_rbf,
+                        float* grad_cos_kj, int32_t accumulate_basis_grads, void* scratch, size_t scratch_bytes) {
+  return backward_G(ctx, dims, w, graph, basis, m_in, 0, saved, saved_bytes, grad_m_out, 0, grad_m_in, 0, gw, grad_rbf, grad_cos_kj,
+                    accumulate_basis_grads, scratch, scratch_bytes);
+}
+
+int gp_block_G_stacks_bf16(const gp_dims* dims) {
+  return dims && dims->variant == GP_VARIANT_G && half_storage(dims) && weights_half(dims) ? 1 : 0;
+}
+
+int gp_block_forward_G_stacked(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
+                               const gp_basis* basis, const void* m_in, int32_t m_in_bf16, void* m_out, int32_t m_out_bf16,
+                               void* saved, size_t saved_bytes, void* scratch, size_t scratch_bytes) {
+  return forward_G(ctx, dims, w, graph, basis, static_cast<const float*>(m_in), m_in_bf16 != 0, static_cast<float*>(m_out),
+                   m_out_bf16 != 0, saved, saved_bytes, scratch, scratch_bytes);
+}
+
+int gp_block_backward_G_stacked(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_graph* graph,
+                                const gp_basis* basis, const void* m_in, int32_t m_in_bf16, const void* saved, size_t saved_bytes,
+                                const void* grad_m_out, int32_t grad_m_out_bf16, void* grad_m_in, int32_t grad_m_in_bf16,
+                                gp_weights_G* gw, float* grad_rbf, float* grad_cos_kj, int32_t accumulate_basis_grads,
+                                void* scratch, size_t scratch_bytes) {
+  return backward_G(ctx, dims, w, graph, basis, static_cast<const float*>(m_in), m_in_bf16 != 0, saved, saved_bytes,
+                    static_cast<const float*>(grad_m_out), grad_m_out_bf16 != 0, static_cast<float*>(grad_m_in), grad_m_in_bf16 != 0,
+                    gw, grad_rbf, grad_cos_kj, accumulate_basis_grads, scratch, scratch_bytes);
 }
 
 }  // extern "C"

@@ -45,8 +45,9 @@ bool gp_gemm_nt_takes_lowrank(const gp_ctx* ctx, int64_t M, int N, int K);
 // out = A[M,K] @ Bt[N,K]^T + A2[M,K] @ B2t[N,K]^T (fp32 result, no other epilogue step).  With tall bf16 operands this is
 // ONE launch of the global->LDS kernel whose contraction runs over both pairs, so the result is written once instead
 // of written, read back and written again; otherwise two launches, the second adding to the first's result.
+// out_bf16: the result is stored as bf16 (bf16-operand kernels only).
 int gp_gemm_nt2(gp_ctx* ctx, const float* A, const float* Bt, const float* A2, const float* B2t, int64_t M, int N, int K,
-                float* out, int a_bf16 = 0, int b_bf16 = 0);
+                float* out, int a_bf16 = 0, int b_bf16 = 0, int out_bf16 = 0);
 // out[M,N] = A[rows,M]^T @ B[rows,N]; deterministic two-stage reduction through `part`.
 // If colsum_out != NULL it also receives colsum_out[n] = sum_r B[r,n] (the bias gradient).
 size_t gp_gemm_tn_scratch(int64_t rows, int M, int N);

@@ -476,14 +476,17 @@ bool gp_gemm_nt2_fused(const gp_ctx* ctx, const float* A, const float* Bt, const
 }
 
 int gp_gemm_nt2(gp_ctx* ctx, const float* A, const float* Bt, const float* A2, const float* B2t, int64_t M, int N, int K,
-                float* out, int a_bf16, int b_bf16) {
+                float* out, int a_bf16, int b_bf16, int out_bf16) {
   GP_REQUIRE(ctx, A && Bt && A2 && B2t && out && M >= 0 && N > 0 && K > 0, "gemm_nt2: bad arguments");
+  GP_REQUIRE(ctx, !out_bf16 || ctx->gemm_bf16, "gemm_nt2: a bf16 result needs the bf16-operand kernels");
   if (M == 0) return GP_OK;
   gp_epilogue e;
   e.out = out;
+  e.bf16 = out_bf16 ? EPI_BF_OUT : 0u;
   if (!gp_gemm_nt2_fused(ctx, A, Bt, A2, B2t, M, N, K, a_bf16, b_bf16)) {
     GP_TRY(gp_gemm_nt(ctx, A, Bt, M, N, K, e, a_bf16, b_bf16));
     e.add_post = out;
+    e.bf16 = out_bf16 ? (EPI_BF_OUT | EPI_BF_ADD_POST) : 0u;
     return gp_gemm_nt(ctx, A2, B2t, M, N, K, e, a_bf16, b_bf16);
   }
   gemm_args g{};

@@ -441,7 +441,7 @@ __device__ __forceinline__ void tile_epilogue_pairs(const gemm_args& g, f32x16 (
   // The addend of a small tile that lies inside the matrix is fetched for all of the wavefront's blocks at once, before
   // the first block is staged: fetched block by block in the loop below, each block waited for its own loads (a narrow
   // contraction leaves nothing else to hide them behind).
-  constexpr bool PRELOAD = KIND == EK_PRE_SILU_ADD_F32 && MB * NB <= 4;
+  constexpr bool PRELOAD = (KIND == EK_PRE_SILU_ADD_F32 || KIND == EK_PRE_SILU_ADD_BF16) && MB * NB <= 4;
   bf16x4 addp[PRELOAD ? MB : 1][PRELOAD ? NB / 2 : 1][PRELOAD ? 8 : 1];
   bool preloaded = false;
   if constexpr (PRELOAD) {
@@ -549,6 +549,9 @@ __device__ __forceinline__ void tile_epilogue(const gemm_args& g, f32x16 (&acc)[
         [[fallthrough]];
       case EK_PRE_SILU_ADD_F32:
         if (g.epi_kind == EK_PRE_SILU_ADD_F32) { tile_epilogue_pairs<MB, NB, LR_WAVES, EK_PRE_SILU_ADD_F32>(g, acc, smem, m0, n0, wm0, wn0); break; }
+        [[fallthrough]];
+      case EK_PRE_SILU_ADD_BF16:
+        if (g.epi_kind == EK_PRE_SILU_ADD_BF16) { tile_epilogue_pairs<MB, NB, LR_WAVES, EK_PRE_SILU_ADD_BF16>(g, acc, smem, m0, n0, wm0, wn0); break; }
         [[fallthrough]];
       default: tile_epilogue_pairs<MB, NB, LR_WAVES, EK_GENERIC>(g, acc, smem, m0, n0, wm0, wn0); break;
     }

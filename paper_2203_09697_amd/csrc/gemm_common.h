@@ -59,6 +59,7 @@ enum {
   EK_PRE_SILU_ADD_F32,        // save_pre (bf16), SiLU, + add_post (bf16), times scale, out (fp32)
   EK_DSILU_BF16,              // times SiLU'(zsrc) (fp32), out (bf16)
   EK_PRE_SILU_F32,            // save_pre (fp32), SiLU, out (fp32)
+  EK_PRE_SILU_ADD_BF16,       // save_pre (bf16), SiLU, + add_post (bf16), times scale, out (bf16)
 };
 inline int gp_epilogue_kind(const gp_epilogue& e, int vecC) {
   if (!vecC || e.bias || e.add_pre || e.out2 || e.mul || !e.out) return EK_GENERIC;
@@ -71,7 +72,7 @@ inline int gp_epilogue_kind(const gp_epilogue& e, int vecC) {
   if (e.save_pre && b == 0u && e.act == 1 && !e.add_post && !e.lr_a && e.scale == 1.0f) return EK_PRE_SILU_F32;
   if (e.save_pre && (b & EPI_BF_SAVE_PRE) && e.act == 1) {
     if (!e.add_post && e.scale == 1.0f && (b & EPI_BF_OUT)) return e.lr_a ? EK_PRE_SILU_LR_BF16 : EK_PRE_SILU_BF16;
-    if (e.add_post && (b & EPI_BF_ADD_POST) && !e.lr_a && !(b & EPI_BF_OUT)) return EK_PRE_SILU_ADD_F32;
+    if (e.add_post && (b & EPI_BF_ADD_POST) && !e.lr_a) return (b & EPI_BF_OUT) ? EK_PRE_SILU_ADD_BF16 : EK_PRE_SILU_ADD_F32;
   }
   return EK_GENERIC;
 }
@@ -183,13 +184,14 @@ __device__ __forceinline__ void epilogue_store4_kind(const gp_epilogue& e, int64
 #pragma unroll
     for (int c = 0; c < 4; ++c) v[c] = silu_f(v[c]);
     if constexpr (KIND == EK_PRE_SILU_LR_BF16) v *= lr;
-    if constexpr (KIND == EK_PRE_SILU_ADD_F32) {
+    if constexpr (KIND == EK_PRE_SILU_ADD_F32 || KIND == EK_PRE_SILU_ADD_BF16) {
       if (add_loaded) {   // the caller has fetched the addend's 4 values already
 #pragma unroll
         for (int c = 0; c < 4; ++c) v[c] += (float)(*add_loaded)[c];
       } else v += ldx4(e.add_post, o, 1u);
       v *= e.scale;
-      st4(e.out + o, v);
+      if constexpr (KIND == EK_PRE_SILU_ADD_BF16) st4h(e.out, o, v);
+      else st4(e.out + o, v);
     } else st4h(e.out, o, v);
   }
 }

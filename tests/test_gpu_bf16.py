@@ -100,3 +100,34 @@ def test_block_G_bf16_tall_odd_widths(lib, ctx):
     ref = H.oracle_graph(pos_gptr[0], pos_gptr[1], w.dims.cutoff, 0)
     assert len(ref["src"]) > 8192, len(ref["src"])
     _parity(lib, ctx, w, 7, 1, pos_gptr, tol=2e-2)
+
+
+def test_stack_G_bf16_handoff_between_blocks(lib, ctx):
+    # Three bf16 blocks with the messages (and gradients) handed from block to block as bf16 against the same stack with
+    # fp32 hand-over.  A block reads its input only as bf16 GEMM operands, so the forward result must be bit-identical;
+    # the gradients are rounded once more on their way down and may differ by bf16 rounding noise.
+    from paper_2203_09697_amd.binding_g import StackG, gp_block_G_stacks_bf16
+    w = synth.get_workload("cfg3", emb=64, emb_rbf=8)
+    dims = w.dims
+    assert gp_block_G_stacks_bf16(dims)
+    pos, gptr = synth.slab_adsorbate_positions(2, 4, 4, 3, 10, seed=4)
+    e, t = lib.build_graph(ctx, H.to_dev(pos, torch.float32), H.to_dev(gptr, torch.int32), dims.cutoff, w.max_neighbors)
+    gb = lib.gp_basis_forward(ctx, dims, e, t)
+    E = e["n_edges"]
+    W_list = [lib.weights_to_device(synth.weights_G(dims, seed=300 + b)) for b in range(3)]
+    m, gup = synth.edge_embeddings(E, dims.emb, seed=3)
+    res = {}
+    for handoff in (False, True):
+        stack = StackG(ctx, dims, W_list, t, gb, handoff_bf16=handoff)
+        assert stack.half_m == handoff and stack.half_g == handoff
+        out = stack.forward(H.to_dev(m, torch.float32)).clone()
+        grbf = torch.empty((E, dims.num_radial), dtype=torch.float32, device="cuda:0")
+        gm, gW = stack.backward(H.to_dev(gup, torch.float32), grad_rbf=grbf)
+        torch.cuda.synchronize()
+        res[handoff] = (out.cpu().numpy(), gm.clone().cpu().numpy(), grbf.cpu().numpy(),
+                        {k: v.clone().cpu().numpy() for k, v in gW[0].items()})
+    assert np.array_equal(res[False][0], res[True][0])
+    assert H.rel_l2(res[True][1], res[False][1]) < 1e-2
+    assert H.rel_l2(res[True][2], res[False][2]) < 1e-2
+    for k in res[False][3]:
+        assert H.rel_l2(res[True][3][k], res[False][3][k]) < 1e-2, k
