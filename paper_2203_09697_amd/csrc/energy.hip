@@ -231,24 +231,89 @@ row_gap_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ 
 }
 // gu[e, :] = -sum_{rows p of j} gc_kj[(p, n)] unit[e'_p, :] for e = out_list[out_ptr[j] + n]; workgroup = (atom, 64 positions),
 // lanes over positions (consecutive triplets of a row), the four wavefronts over rows
+// Sum over the wavefront, valid in lane 63 only, with data-parallel-primitive moves (no LDS crossbar): an inclusive scan
+// inside each row of 16 lanes (row_shr 1, 2, 4, 8; lanes without a source add 0), then lane 15 of rows 0 and 2 into rows 1
+// and 3 (row_bcast:15), then lane 31 into rows 2 and 3 (row_bcast:31).
+__device__ __forceinline__ float wave_sum_lane63(float v) {
+  auto add = [](float x, int moved) { return x + __builtin_bit_cast(float, moved); };
+  const auto bits = [](float x) { return __builtin_bit_cast(int, x); };
+  v = add(v, __builtin_amdgcn_update_dpp(0, bits(v), 0x111, 0xf, 0xf, false));
+  v = add(v, __builtin_amdgcn_update_dpp(0, bits(v), 0x112, 0xf, 0xf, false));
+  v = add(v, __builtin_amdgcn_update_dpp(0, bits(v), 0x114, 0xf, 0xf, false));
+  v = add(v, __builtin_amdgcn_update_dpp(0, bits(v), 0x118, 0xf, 0xf, false));
+  v = add(v, __builtin_amdgcn_update_dpp(0, bits(v), 0x142, 0xa, 0xf, false));
+  v = add(v, __builtin_amdgcn_update_dpp(0, bits(v), 0x143, 0xc, 0xf, false));
+  return v;
+}
+// ROWS: the same pass also takes the kj-major walk, whose sum over the triplets of in-edge e' is a ROW sum of the same
+// matrix: rpart[(e', chunk), :] = -sum over this workgroup's 64 positions of gc unit[out-edge]; the caller adds the chunks
+// of a row up (every (row, chunk) pair below gridDim.y is written, zeros past the atom's last chunk), so grad cos is read
+// once for both walks and the kj-major one needs no index per triplet.
+template <bool ROWS>
 __global__ void __launch_bounds__(256)
 edge_unit_grad_cols_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr,
                            const int32_t* __restrict__ out_list, const int32_t* __restrict__ seg_kj, const int32_t* __restrict__ gap,
-                           const float* __restrict__ gc_kj, int64_t T, const float* __restrict__ unit, float* __restrict__ gu) {
+                           const float* __restrict__ gc_kj, int64_t T, const float* __restrict__ unit, float* __restrict__ gu,
+                           float* __restrict__ rpart) {
   const int j = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int ob = out_ptr[j], dout = out_ptr[j + 1] - ob;
   const int n = 64 * (int)blockIdx.y + lane;
-  if (64 * (int)blockIdx.y >= dout) return;
   const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
+  if (64 * (int)blockIdx.y >= dout) {
+    if (ROWS)
+      for (int i = threadIdx.x; i < 3 * d; i += 256) rpart[((int64_t)(r0 + i / 3) * gridDim.y + blockIdx.y) * 3 + i % 3] = 0.f;
+    return;
+  }
+  float ox = 0.f, oy = 0.f, oz = 0.f;   // unit vector of this lane's out-edge
+  if (ROWS && n < dout) {
+    const float* u = unit + 3 * (int64_t)out_list[ob + n];
+    ox = u[0]; oy = u[1]; oz = u[2];
+  }
   float sx = 0.f, sy = 0.f, sz = 0.f;
-  for (int p = wv; p < d; p += 4) {
-    const int e1 = r0 + p, seg = seg_kj[e1], gp = gap[e1];
-    const bool valid = n < dout && n != gp;
-    int64_t at = valid ? seg + n - (n > gp ? 1 : 0) : seg;
-    at = at < T ? at : T - 1;                                       // a row without triplets at the very end
-    const float g = gc_kj[at] * (valid ? 1.f : 0.f);                // unconditional load
-    const float* u = unit + 3 * (int64_t)e1;
-    sx -= g * u[0]; sy -= g * u[1]; sz -= g * u[2];
+  // the rows' segment starts and left-out positions first, 1024 rows at a time: read in the loop they made every row a
+  // chain of two memory round trips (segment start, then the value), 75 rows per wavefront one after the other
+  constexpr int RCH = 1024;
+  __shared__ int32_t s_seg[RCH], s_gap[RCH];
+  for (int pb = 0; pb < d; pb += RCH) {
+    const int dn = d - pb < RCH ? d - pb : RCH;
+    __syncthreads();
+    for (int i = threadIdx.x; i < dn; i += 256) {
+      s_seg[i] = seg_kj[r0 + pb + i];
+      s_gap[i] = gap[r0 + pb + i];
+    }
+    __syncthreads();
+    // batches of 8 rows per wavefront: all loads of a batch first, its stores last (loads and stores complete through one
+    // counter: a store inside the loop would make the next row's load wait for it)
+    for (int p0 = wv; p0 < dn; p0 += 32) {
+      float g[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int p = p0 + 4 * q, pc = p < dn ? p : dn - 1;
+        const int seg = s_seg[pc], gp = s_gap[pc];
+        const bool valid = p < dn && n < dout && n != gp;
+        int64_t at = valid ? seg + n - (n > gp ? 1 : 0) : seg;
+        at = at < T ? at : T - 1;                                     // a row without triplets at the very end
+        g[q] = gc_kj[at] * (valid ? 1.f : 0.f);                       // unconditional load
+      }
+      float rx[8], ry[8], rz[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int p = p0 + 4 * q, pc = p < dn ? p : dn - 1;
+        const float* u = unit + 3 * (int64_t)(r0 + pb + pc);
+        sx -= g[q] * u[0]; sy -= g[q] * u[1]; sz -= g[q] * u[2];      // g = 0 for rows past the end
+        if (ROWS) { rx[q] = wave_sum_lane63(g[q] * ox); ry[q] = wave_sum_lane63(g[q] * oy); rz[q] = wave_sum_lane63(g[q] * oz); }
+      }
+      if (ROWS && lane == 63) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const int p = p0 + 4 * q;
+          if (p < dn) {
+            float* o = rpart + ((int64_t)(r0 + pb + p) * gridDim.y + blockIdx.y) * 3;
+            o[0] = -rx[q]; o[1] = -ry[q]; o[2] = -rz[q];
+          }
+        }
+      }
+    }
   }
   __shared__ float red[3][3][64];
   if (wv > 0) { red[wv - 1][0][lane] = sx; red[wv - 1][1][lane] = sy; red[wv - 1][2][lane] = sz; }
@@ -259,6 +324,15 @@ edge_unit_grad_cols_kernel(const int32_t* __restrict__ row_ptr, const int32_t* _
     float* o = gu + 3 * (int64_t)out_list[ob + n];
     o[0] = sx; o[1] = sy; o[2] = sz;
   }
+}
+// gu[e, :] += sum_c rpart[(e, c), :]
+__global__ void add_row_parts_kernel(const float* __restrict__ rpart, int nc, int64_t n3, float* __restrict__ gu) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (edge, component)
+  if (i >= n3) return;
+  const float* p = rpart + (i / 3) * nc * 3 + i % 3;
+  float t = 0.f;
+  for (int c = 0; c < nc; ++c) t += p[3 * c];
+  gu[i] += t;
 }
 // dv[e,:] = (gu - (gu.u) u) / d + gd * u   (gradient w.r.t. the edge vector x_dst - x_src)
 __global__ void edge_vec_grad_kernel(const float* __restrict__ gu, const float* __restrict__ gd,
@@ -537,16 +611,27 @@ int forces_from_basis_grad(gp_ctx* ctx, const gp_dims* dims, const gp_graph* gra
   if (T > 0) {
     // cos = -unit[ji].unit[kj]: d/d unit[ji] = -unit[kj] (ji-major walk), d/d unit[kj] = -unit[ji] (kj-major walk)
     gp_prof_scope prof(ctx, "forces_edge_sums", 12.0 * (double)T, 12.0 * (double)T);
-    if (graph->max_out_degree > 0) {
-      // the ji-major walk as column sums over the kj-major order: no reordered copy of grad cos
+    const int nc = (graph->max_out_degree + 63) / 64;
+    if (graph->max_out_degree > 0 && (int64_t)E * nc * 3 <= T) {
+      // both walks as sums over the per-atom (in-edge, out-position) matrix in kj-major order, grad cos read once: columns
+      // = the ji-major walk, rows = the kj-major one, per 64-position chunk; the chunks' row sums (E x nc x 3 floats)
+      // borrow the buffer of the reordered copy that this path does not make
       row_gap_kernel<<<(unsigned)n_atoms, 256, 0, st>>>(row_ptr, out_ptr, out_list, graph->seg_ptr_kj, graph->idx_ji_kj, w.gap);
-      edge_unit_grad_cols_kernel<<<dim3((unsigned)n_atoms, (unsigned)((graph->max_out_degree + 63) / 64)), 256, 0, st>>>(
-          row_ptr, out_ptr, out_list, graph->seg_ptr_kj, w.gap, grad_cos_kj, T, unit, w.gu);
+      edge_unit_grad_cols_kernel<true><<<dim3((unsigned)n_atoms, (unsigned)nc), 256, 0, st>>>(
+          row_ptr, out_ptr, out_list, graph->seg_ptr_kj, w.gap, grad_cos_kj, T, unit, w.gu, w.gc_ji);
+      add_row_parts_kernel<<<nblk(3 * E), 256, 0, st>>>(w.gc_ji, nc, 3 * E, w.gu);
     } else {
-      unpermute_kernel<<<nblk(T), 256, 0, st>>>(grad_cos_kj, perm_kj, T, w.gc_ji);
-      edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_ji, graph->idx_kj, w.gc_ji, unit, E, 0, w.gu);
+      if (graph->max_out_degree > 0) {
+        // the ji-major walk as column sums over the kj-major order: no reordered copy of grad cos
+        row_gap_kernel<<<(unsigned)n_atoms, 256, 0, st>>>(row_ptr, out_ptr, out_list, graph->seg_ptr_kj, graph->idx_ji_kj, w.gap);
+        edge_unit_grad_cols_kernel<false><<<dim3((unsigned)n_atoms, (unsigned)nc), 256, 0, st>>>(
+            row_ptr, out_ptr, out_list, graph->seg_ptr_kj, w.gap, grad_cos_kj, T, unit, w.gu, nullptr);
+      } else {
+        unpermute_kernel<<<nblk(T), 256, 0, st>>>(grad_cos_kj, perm_kj, T, w.gc_ji);
+        edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_ji, graph->idx_kj, w.gc_ji, unit, E, 0, w.gu);
+      }
+      edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_kj, graph->idx_ji_kj, grad_cos_kj, unit, E, 1, w.gu);
     }
-    edge_unit_grad_kernel<<<wblk(E), 256, 0, st>>>(graph->seg_ptr_kj, graph->idx_ji_kj, grad_cos_kj, unit, E, 1, w.gu);
   } else {
     fill_kernel<<<nblk(3 * E), 256, 0, st>>>(w.gu, 3 * E, 0.f);
   }
