@@ -72,36 +72,18 @@ fused_items_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restric
   if (tid == 0) n_items[0] = carry;
 }
 
-// Pre-pass, one workgroup per (atom j, 64 of its padded rows): X^T in bf16 as [p-block of 8 rows][f][8], the
-// coefficients of the powers of cos alpha as [row][half][c][4] (rows past the atom's last one and columns past C are
-// zero, so padded rows contribute nothing), and, from the workgroups of the first 64 rows, for every out-edge of the
-// atom (at its out-list position) {edge id, start of its segment, position of the row the segment leaves out
-// (the number of rows if none)}.
-template <int SM, bool RADB = false>
+// Pre-pass, one workgroup per (atom j, 64 of its padded rows), in two kernels.  First X^T in bf16 as [p-block of 8 rows][f][8]
+// (no LDS, so many workgroups per compute unit; inside the second kernel its stores held back the loads of the radial
+// part, which complete through the same counter).  Rows past the atom's last one are zero: padded rows contribute nothing.
 __global__ void __launch_bounds__(256)
-fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
-                  const int32_t* __restrict__ seg_ptr_ji, const int32_t* __restrict__ idx_kj, const float* __restrict__ x,
-                  const float* __restrict__ Radt, int64_t E, int S, int C, int F, const int32_t* __restrict__ rows,
-                  __bf16* __restrict__ xb, float* __restrict__ coef, int32_t* __restrict__ edge_info) {
+fused_pack_x_kernel(const int32_t* __restrict__ row_ptr, const float* __restrict__ x, int F, const int32_t* __restrict__ rows,
+                    __bf16* __restrict__ xb) {
   const int j = blockIdx.x;
   const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
   const int p0 = ROWPAD * (int)blockIdx.y;
-  if (blockIdx.y == 0) {
-    const int o0 = out_ptr[j], dout = out_ptr[j + 1] - o0;
-    for (int t = threadIdx.x; t < dout; t += 256) {
-      const int e = out_list[o0 + t];
-      const int seg = seg_ptr_ji[e], cnt = seg_ptr_ji[e + 1] - seg;
-      const int gap = first_mismatch(idx_kj + seg, cnt, [=](int slot) { return rows ? rows[r0 + slot] : r0 + slot; });
-      int32_t* dst = edge_info + 4 * (int64_t)(o0 + t);
-      dst[0] = e;
-      dst[1] = seg;
-      dst[2] = gap;                   // = cnt = the number of rows when no row is left out
-      dst[3] = cnt;
-    }
-  }
   if (p0 >= ((d + ROWPAD - 1) & ~(ROWPAD - 1))) return;
   const int64_t base = padded_base(r0, j) + p0;
-  // X^T: item (p-block pb, feature f); consecutive threads take consecutive f of the same rows
+  // item (p-block pb, feature f); consecutive threads take consecutive f of the same rows
   for (int it = threadIdx.x; it < (ROWPAD / 8) * F; it += 256) {
     const int pb = it / F, f = it % F;
     bf16x8 v;
@@ -114,6 +96,43 @@ fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict
     }
     *reinterpret_cast<bf16x8*>(xb + ((base / 8 + pb) * F + f) * 8) = v;
   }
+}
+
+// The out-edge table of the pre-pass, one thread per out-edge (grid: atoms x blocks of 256 out-edges): {edge id, start of its
+// segment, position of the row the segment leaves out (the number of rows if none), rows in the segment}; the search for
+// the left-out row is a chain of dependent loads, which the other two kernels no longer wait behind.
+__global__ void __launch_bounds__(256)
+fused_pack_info_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
+                       const int32_t* __restrict__ seg_ptr_ji, const int32_t* __restrict__ idx_kj, const int32_t* __restrict__ rows,
+                       int32_t* __restrict__ edge_info) {
+  const int j = blockIdx.x;
+  const int r0 = row_ptr[j];
+  const int o0 = out_ptr[j], dout = out_ptr[j + 1] - o0;
+  const int t = 256 * (int)blockIdx.y + threadIdx.x;
+  if (t >= dout) return;
+  const int e = out_list[o0 + t];
+  const int seg = seg_ptr_ji[e], cnt = seg_ptr_ji[e + 1] - seg;
+  const int gap = first_mismatch(idx_kj + seg, cnt, [=](int slot) { return rows ? rows[r0 + slot] : r0 + slot; });
+  int32_t* dst = edge_info + 4 * (int64_t)(o0 + t);
+  dst[0] = e;
+  dst[1] = seg;
+  dst[2] = gap;                   // = cnt = the number of rows when no row is left out
+  dst[3] = cnt;
+}
+
+// Third kernel, the first one's grid: the coefficients of the powers of cos alpha as [row][half][c][4] (rows past the atom's last one
+// and columns past C are zero), or with RADB the radial values themselves.
+template <int SM, bool RADB = false>
+__global__ void __launch_bounds__(256)
+fused_pack_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_list,
+                  const int32_t* __restrict__ seg_ptr_ji, const int32_t* __restrict__ idx_kj, const float* __restrict__ x,
+                  const float* __restrict__ Radt, int64_t E, int S, int C, int F, const int32_t* __restrict__ rows,
+                  __bf16* __restrict__ xb, float* __restrict__ coef, int32_t* __restrict__ edge_info) {
+  const int j = blockIdx.x;
+  const int r0 = row_ptr[j], d = row_ptr[j + 1] - r0;
+  const int p0 = ROWPAD * (int)blockIdx.y;
+  if (p0 >= ((d + ROWPAD - 1) & ~(ROWPAD - 1))) return;
+  const int64_t base = padded_base(r0, j) + p0;
   // coefficients.  Radt is read with consecutive threads on consecutive rows of one (l, c) line and parked in LDS;
   // the table is then written with consecutive threads on consecutive c of one row, i.e. in whole 256-byte runs
   // (written straight from the first order, every 16-byte store went to a line of its own: 0.24 -> 0.1 ms at 3e5 edges).
@@ -594,6 +613,9 @@ int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
     gp_prof_scope prof(ctx, "tripG_pack", Ed * 2.0 * S * 8 * CP, Ed * (4.0 * F + 4.0 * S * C + 2.0 * F + 4.0 * COEF_ROW + 8.0));
     fused_items_kernel<<<1, 1024, 0, st>>>(g->row_ptr, g->out_ptr, (int)N, w.n_items, w.item);
     const dim3 grid((unsigned)N, (unsigned)((g->max_in_degree + ROWPAD - 1) / ROWPAD));
+    fused_pack_x_kernel<<<grid, 256, 0, st>>>(g->row_ptr, x, F, rows_list, w.xb);
+    fused_pack_info_kernel<<<dim3((unsigned)N, (unsigned)((g->max_out_degree + 255) / 256)), 256, 0, st>>>(
+        g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj, rows_list, w.edge_info);
     if (y_mfma)
       fused_pack_kernel<8, true><<<grid, 256, 0, st>>>(g->row_ptr, g->out_ptr, g->out_list, g->seg_ptr_ji, g->idx_kj, x, Radt, E, S, C,
                                                        F, rows_list, w.xb, w.coef, w.edge_info);
