@@ -131,3 +131,16 @@ def test_stack_G_bf16_handoff_between_blocks(lib, ctx):
     assert H.rel_l2(res[True][2], res[False][2]) < 1e-2
     for k in res[False][3]:
         assert H.rel_l2(res[True][3][k], res[False][3][k]) < 1e-2, k
+
+
+def test_block_G_bf16_symmetric_two_blocks(lib, ctx):
+    # two symmetric bf16 blocks: the messages go from the first to the second as bf16, the gradient comes back as fp32
+    # (the opposite-edge gather of a symmetric block's backward pass reads fp32)
+    from paper_2203_09697_amd.binding_g import StackG
+    w = synth.get_workload("cfg3", emb=64, emb_rbf=8, symmetric=True)
+    pos_gptr = synth.slab_adsorbate_positions(2, 4, 4, 3, 10, seed=8)
+    _parity(lib, ctx, w, 9, 2, pos_gptr, tol=2e-2)
+    e, t = lib.build_graph(ctx, H.to_dev(pos_gptr[0], torch.float32), H.to_dev(pos_gptr[1], torch.int32), w.dims.cutoff, w.max_neighbors)
+    gb = lib.gp_basis_forward(ctx, w.dims, e, t)
+    stack = StackG(ctx, w.dims, [lib.weights_to_device(synth.weights_G(w.dims, seed=b)) for b in range(2)], t, gb)
+    assert stack.half_m and not stack.half_g
