@@ -456,8 +456,11 @@ const float* weight_operand(gp_ctx* ctx, bool half, const float* W, __bf16* W_h,
 }
 
 bool a_half(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
-  return half_storage(d) && (d->emb_cbf * d->int_emb) % 8 == 0 && want_trip_mfma(ctx, d, g, MFMA_FWD_DENSITY) &&
-         gp_tripG_mfma_usable(g, d->int_emb, d->num_spherical, d->emb_cbf);
+  if (!half_storage(d) || (d->emb_cbf * d->int_emb) % 8 != 0) return false;
+  // radial factor at the target edge: A (and its gradient) is written by a per-edge product, whose 16-byte bf16 stores and
+  // loads exist for these widths
+  if (d->radial_at_target) return d->emb_cbf <= 16 && (d->int_emb == 32 || d->int_emb == 64 || d->int_emb == 128);
+  return want_trip_mfma(ctx, d, g, MFMA_FWD_DENSITY) && gp_tripG_mfma_usable(g, d->int_emb, d->num_spherical, d->emb_cbf);
 }
 
 int check_weights_G(gp_ctx* ctx, const gp_dims* d, const gp_weights_G* w, const char* what) {
@@ -576,7 +579,7 @@ int forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_
         GP_TRY(gp_tripG_backward_H_mfma(ctx, &gml, basis->cos_alpha, s.x, F, S, s.B1, graph->out_list));
     } else
       GP_TRY(gp_tripD_backward(ctx, &gm, basis->cos_alpha, nullptr, nullptr, nullptr, s.x, nullptr, F, S, 1, s.B1, nullptr));
-    GP_TRY(gp_tripG_edge_G(ctx, s.Radt, s.B1, E, S, C, F, s.A));
+    GP_TRY(gp_tripG_edge_G(ctx, s.Radt, s.B1, E, S, C, F, s.A, ah));
   } else if (want_trip_mfma(ctx, dims, graph, MFMA_FWD_DENSITY) && gp_tripG_mfma_usable(graph, F, S, C)) {
     // one pass with y evaluated in registers where the widths allow and the scratch holds its tables; the two-kernel
     // form with the per-triplet y buffer otherwise, or when asked for (mode 2)
@@ -760,12 +763,12 @@ int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp
     e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
     GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e));                       // dz_dn
     GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 2, 0, 1, sc.WbilV));                 // [o, (c,f)]
-    e = gp_epilogue(); e.out = sc.dA;
+    e = gp_epilogue(); e.out = sc.dA; e.bf16 = ah ? EPI_BF_OUT : 0u;   // read by the per-edge products below only
     GP_TRY(gp_gemm_nn(ctx, sc.dz, sc.WbilV, E, C * F, O, e));                       // dA[e, (c,f)]
-    GP_TRY(gp_tripG_edge_dRad(ctx, sc.dA, s.B1, E, S, C, F, sc.dRad));              // dRad[e, (l,c)]
+    GP_TRY(gp_tripG_edge_dRad(ctx, sc.dA, s.B1, E, S, C, F, sc.dRad, ah));          // dRad[e, (l,c)]
     if (grad_cos_kj && graph->n_triplets > 0) {
       GP_REQUIRE(ctx, graph->perm_kj, "gp_block_backward_G: graph->perm_kj is needed for grad_cos_kj with radial_at_target");
-      GP_TRY(gp_tripG_edge_U(ctx, s.Radt, sc.dA, E, S, C, F, sc.dB1));              // dB1[e,l,f]
+      GP_TRY(gp_tripG_edge_U(ctx, s.Radt, sc.dA, E, S, C, F, sc.dB1, ah));          // dB1[e,l,f]
       GP_TRY(gp_tripG_grad_cos(ctx, &gm, basis->cos_alpha, sc.dB1, s.x, F, S, 0, sc.gc_ji));   // ji-major order
       permute_add_kernel<<<(unsigned)((graph->n_triplets + 255) / 256), 256, 0, ctx->stream>>>(
           sc.gc_ji, graph->perm_kj, graph->n_triplets, accumulate_basis_grads, grad_cos_kj);
