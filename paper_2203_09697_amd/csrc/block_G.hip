@@ -745,23 +745,32 @@ int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp
     // y'_t[c] = sum_l Y_l(t) Rad[ji(t),l,c] is the forward kernel on the mirrored views
     const gp_graph gm = mirrored(graph);
     const gp_graph gml = mirrored_lists(graph, sc.iota);
+    bool gh = false;
     if (want_rt_mfma(ctx, dims, graph, MFMA_FWD_DENSITY) && gp_tripG_mfma_usable(&gml, O, S, C)) {
       iota_kernel<<<(unsigned)((E + 255) / 256), 256, 0, ctx->stream>>>(sc.iota, E);
       GP_LAUNCH_CHECK(ctx, "iota_kernel");
       // the radial table in out-list order, so that the threads of the y kernel read neighbouring columns
       gather_cols_kernel<<<dim3((unsigned)((E + 255) / 256), (unsigned)(S * C)), 256, 0, ctx->stream>>>(s.Radt, graph->out_list, E, sc.Radt_out);
       GP_LAUNCH_CHECK(ctx, "gather_cols_kernel");
+      // G' is read by the next GEMM only: bf16 from the matrix-core kernels where that GEMM takes bf16 operands
+      gh = hs && wh && (C * O) % 8 == 0;
       if (ctx->trip_mfma != 2 && gp_tripG_fused_usable(&gml, O, S, C) && sc.ybytes >= gp_tripG_fused_scratch(graph->n_atoms, E, O))
-        GP_TRY(gp_tripG_forward_fused(ctx, &gml, basis->cos_alpha_kj, sc.dz, sc.Radt_out, O, S, C, sc.Gm, sc.ybuf, sc.ybytes, 0,
+        GP_TRY(gp_tripG_forward_fused(ctx, &gml, basis->cos_alpha_kj, sc.dz, sc.Radt_out, O, S, C, sc.Gm, sc.ybuf, sc.ybytes, gh,
                                       graph->out_list));
       else
-        GP_TRY(gp_tripG_forward_mfma(ctx, &gml, basis->cos_alpha_kj, sc.dz, sc.Radt_out, O, S, C, sc.Gm, sc.ybuf, sc.ybytes, 0,
+        GP_TRY(gp_tripG_forward_mfma(ctx, &gml, basis->cos_alpha_kj, sc.dz, sc.Radt_out, O, S, C, sc.Gm, sc.ybuf, sc.ybytes, gh,
                                      graph->out_list, 1));
     } else
       GP_TRY(gp_tripD_forward(ctx, &gm, basis->cos_alpha_kj, sc.dz, s.Radt, nullptr, O, S, C, nullptr, sc.Gm));
-    GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                 // [(c,o), f]
     e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
-    GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e));                       // dz_dn
+    if (gh) {
+      GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));               // [f, (c,o)]; the buffer is rewritten below
+      GP_TRY(to_half(ctx, sc.WbilV, sc.WbilV_h, (int64_t)F * C * O));
+      GP_TRY(gp_gemm_nt(ctx, sc.Gm, reinterpret_cast<const float*>(sc.WbilV_h), E, F, C * O, e, 1, 1));   // dz_dn
+    } else {
+      GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));               // [(c,o), f]
+      GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e));                     // dz_dn
+    }
     GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 2, 0, 1, sc.WbilV));                 // [o, (c,f)]
     e = gp_epilogue(); e.out = sc.dA; e.bf16 = ah ? EPI_BF_OUT : 0u;   // read by the per-edge products below only
     GP_TRY(gp_gemm_nn(ctx, sc.dz, sc.WbilV, E, C * F, O, e));                       // dA[e, (c,f)]
