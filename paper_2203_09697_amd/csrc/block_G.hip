@@ -786,15 +786,19 @@ int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp
   } else {
   // one pass over the triplets (kj-major): H[e', l, o]
   const bool bwd_mfma = want_trip_mfma(ctx, dims, graph, MFMA_BWD_DENSITY) && gp_tripG_mfma_bwd_usable(graph, O, S);
+  // H is read by the two per-edge products only: bf16 from the one-pass kernel where they take it so
+  bool hh = false;
   if (bwd_mfma && ctx->trip_mfma != 2 && gp_tripG_H_fused_usable(graph, O, S) &&
-      sc.ybytes >= gp_tripG_H_fused_scratch(graph->n_atoms, E, O))
-    GP_TRY(gp_tripG_backward_H_fused(ctx, graph, basis->cos_alpha_kj, sc.dz, O, S, sc.Hd, sc.ybuf, sc.ybytes));
+      sc.ybytes >= gp_tripG_H_fused_scratch(graph->n_atoms, E, O)) {
+    hh = hs && gp_tripG_edge_takes_half_H(C, O);
+    GP_TRY(gp_tripG_backward_H_fused(ctx, graph, basis->cos_alpha_kj, sc.dz, O, S, sc.Hd, sc.ybuf, sc.ybytes, nullptr, hh));
+  }
   else if (bwd_mfma)
     GP_TRY(gp_tripG_backward_H_mfma(ctx, graph, basis->cos_alpha_kj, sc.dz, O, S, sc.Hd));
   else
     GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, nullptr, nullptr, nullptr, sc.dz, nullptr, O, S, 1,
                              sc.Hd, nullptr));
-  GP_TRY(gp_tripG_edge_G(ctx, s.Radt, sc.Hd, E, S, C, O, sc.Gm, hs));               // G[e', (c,o)] (bf16 with hs)
+  GP_TRY(gp_tripG_edge_G(ctx, s.Radt, sc.Hd, E, S, C, O, sc.Gm, hs, hh));           // G[e', (c,o)] (bf16 with hs)
   GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                   // [(c,o), f]
   // dz_dn is an operand of two GEMMs only: bf16 with bf16 storage and weights
   const bool dh = hs && wh && F % 8 == 0;
@@ -818,7 +822,7 @@ int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp
     GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));                 // [f, (c,o)]
     GP_TRY(gp_gemm_nn(ctx, s.x, sc.WbilV, E, C * O, F, e));                         // V[e', (c,o)]
   }
-  GP_TRY(gp_tripG_edge_dRad(ctx, sc.V, sc.Hd, E, S, C, O, sc.dRad, vh));            // dRad[e', (l,c)]
+  GP_TRY(gp_tripG_edge_dRad(ctx, sc.V, sc.Hd, E, S, C, O, sc.dRad, vh, hh));        // dRad[e', (l,c)]
   if (grad_cos_kj && graph->n_triplets > 0) {
     const bool dcos_fused = bwd_mfma && ctx->trip_mfma != 2 && gp_tripG_H_fused_usable(graph, O, S) &&
                             sc.ybytes >= gp_tripG_dcos_fused_scratch(graph->n_atoms, E, O, 0);

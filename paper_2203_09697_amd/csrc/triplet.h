@@ -52,12 +52,15 @@ size_t gp_block_G_scratch_bytes(const gp_dims* d, int64_t N, int64_t E, int64_t 
 // source edge follows from H by the two small per-edge products below.
 
 // Gout[e, c*O + o] = sum_l Radt[(l*C+c)*E + e] * H[e, l, o]
-// (out_half: Gout addresses bf16 elements)
+// (out_half: Gout addresses bf16 elements; h_half: so does H, taken only together with out_half at widths 32, 64, 128)
 int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout,
-                    int out_half = 0);
+                    int out_half = 0, int h_half = 0);
+// whether the two per-edge products read a bf16 H at these widths (16-byte aligned H, V, G)
+bool gp_tripG_edge_takes_half_H(int C, int O);
 // dRad[e, l*C + c] = sum_o V[e, c*O + o] * H[e, l, o]
-// v_half: V addresses bf16 elements
-int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad, int v_half = 0);
+// v_half: V addresses bf16 elements; h_half: so does H (emb_cbf <= 16 and widths 32, 64, 128 only)
+int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad, int v_half = 0,
+                       int h_half = 0);
 // dst[a,b,c] = src element whose index along source dimension p0 is a, along p1 is b, along p2 is c
 // (src has dimensions n0 x n1 x n2; dst has n[p0] x n[p1] x n[p2]); for small weight tensors
 int gp_permute3(gp_ctx* ctx, const float* src, int n0, int n1, int n2, int p0, int p1, int p2, float* dst);
@@ -91,7 +94,7 @@ int gp_tripG_forward_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alph
 bool gp_tripG_H_fused_usable(const gp_graph* g, int O, int S);
 size_t gp_tripG_H_fused_scratch(int64_t N, int64_t E, int O);
 int gp_tripG_backward_H_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S, float* H,
-                              void* ws, size_t ws_bytes, const int32_t* row_list = nullptr);
+                              void* ws, size_t ws_bytes, const int32_t* row_list = nullptr, int out_half = 0);   // out_half: H is bf16
 // grad_cos_kj in the same per-(atom, 32 rows) decomposition, wavefronts working alone without LDS.  U: bf16 [E][8][O]
 // (u_is_bf16_padded, as gp_tripG_edge_U writes it with out16) or fp32 [E][S][O] (converted into the workspace first).
 size_t gp_tripG_dcos_fused_scratch(int64_t N, int64_t E, int O, int with_u16);

@@ -620,13 +620,14 @@ edge_G_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64
 // The same product written as bf16 for O = 32, 64 or 128: the edge's S x O block of H (fp32, contiguous) goes once
 // through the wavefront's LDS slice, a lane owns (c, 8 consecutive o) pieces of the edge's C x O result (contiguous)
 // and writes each with one 16-byte store instead of C stores of 2 bytes per lane.
-template <int O>
+template <int O, class HT>   // HT: storage of H (float or __bf16)
 __global__ void __launch_bounds__(WPB* WAVE)
-edge_G16_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int64_t E, int S, int C, __bf16* __restrict__ Gout) {
+edge_G16_kernel(const float* __restrict__ Radt, const HT* __restrict__ H, int64_t E, int S, int C, __bf16* __restrict__ Gout) {
   typedef __bf16 h8 __attribute__((ext_vector_type(8)));
   typedef float f4 __attribute__((ext_vector_type(4)));
   constexpr int CH = O / 8;
-  constexpr int NV = (ST * O / 4 + WAVE - 1) / WAVE;   // 16-byte pieces of the H block per lane
+  constexpr int PE = 16 / (int)sizeof(HT);             // elements per 16-byte piece
+  constexpr int NV = (ST * O / PE + WAVE - 1) / WAVE;  // 16-byte pieces of the H block per lane
   extern __shared__ float dyn_s[];                     // rad_s[(l*C + c) * EG_EDGES + edge]
   __shared__ __attribute__((aligned(16))) float H_s[WPB][2][ST * O];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -649,13 +650,13 @@ edge_G16_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int
     }
   }
   __syncthreads();
-  const int n_piece = S * O / 4;
+  const int n_piece = S * O / PE;
   auto fetch = [&](int el, f4 (&v)[NV]) __attribute__((always_inline)) {
     const int64_t e = e0 + el < E ? e0 + el : E - 1;
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
       const int i = lane + WAVE * k;
-      v[k] = *reinterpret_cast<const f4*>(H + e * S * O + 4 * (i < n_piece ? i : 0));
+      v[k] = *reinterpret_cast<const f4*>(H + e * S * O + PE * (i < n_piece ? i : 0));
     }
   };
   f4 vn[NV];
@@ -666,7 +667,14 @@ edge_G16_kernel(const float* __restrict__ Radt, const float* __restrict__ H, int
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
       const int i = lane + WAVE * k;
-      if (i < n_piece) *reinterpret_cast<f4*>(hs + 4 * i) = vn[k];
+      if (i < n_piece) {
+        if constexpr (sizeof(HT) == 4) *reinterpret_cast<f4*>(hs + 4 * i) = vn[k];
+        else {   // 8 bf16 values: widened on their way into the slice
+          const h8 h = __builtin_bit_cast(h8, vn[k]);
+          *reinterpret_cast<f4*>(hs + 8 * i) = f4{(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
+          *reinterpret_cast<f4*>(hs + 8 * i + 4) = f4{(float)h[4], (float)h[5], (float)h[6], (float)h[7]};
+        }
+      }
     }
     if (el + WPB < EG_EDGES && e0 + el + WPB < E) fetch(el + WPB, vn);
     wave_lds_sync();
@@ -716,9 +724,9 @@ edge_dRad_kernel(const float* __restrict__ V, const float* __restrict__ H, int64
 // same OQ columns of the S rows of H (16 lanes share each address), all requested before the first use; the four
 // partial sums of a c are combined by two lane exchanges.  VT: storage type of V.
 constexpr int DQ_EPW = 1;   // edges per wavefront (4 measured 2 % slower: starting the wavefronts is not the limit)
-template <int OQ, class VT>
+template <int OQ, class VT, class HT>   // storage of V and of H (float or __bf16)
 __global__ void __launch_bounds__(WPB* WAVE)
-edge_dRad_q_kernel(const VT* __restrict__ V, const float* __restrict__ H, int64_t E, int S, int C, float* __restrict__ dRad) {
+edge_dRad_q_kernel(const VT* __restrict__ V, const HT* __restrict__ H, int64_t E, int S, int C, float* __restrict__ dRad) {
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   constexpr int O = 4 * OQ;
   __shared__ __attribute__((aligned(16))) float H_s[WPB][ST * O];
@@ -747,12 +755,21 @@ edge_dRad_q_kernel(const VT* __restrict__ V, const float* __restrict__ H, int64_
   // the lanes) instead of by each of the 16 lanes that share a quarter, which kept the address path busy 16 times over
   {
     typedef float f4 __attribute__((ext_vector_type(4)));
-    const float* hp = H + e * S * O;
+    constexpr int PE = 16 / (int)sizeof(HT);   // elements per 16-byte piece
+    const HT* hp = H + e * S * O;
 #pragma unroll
-    for (int k = 0; k < (ST * O / 4 + WAVE - 1) / WAVE; ++k) {
+    for (int k = 0; k < (ST * O / PE + WAVE - 1) / WAVE; ++k) {
       const int idx = lane + k * WAVE;
-      const f4 t = *reinterpret_cast<const f4*>(hp + 4 * (idx < S * O / 4 ? idx : 0));
-      if (idx < S * O / 4) *reinterpret_cast<f4*>(&H_s[w][4 * idx]) = t;
+      const f4 t = *reinterpret_cast<const f4*>(hp + PE * (idx < S * O / PE ? idx : 0));
+      if (idx < S * O / PE) {
+        if constexpr (sizeof(HT) == 4) *reinterpret_cast<f4*>(&H_s[w][4 * idx]) = t;
+        else {
+          typedef __bf16 h8 __attribute__((ext_vector_type(8)));
+          const h8 h = __builtin_bit_cast(h8, t);
+          *reinterpret_cast<f4*>(&H_s[w][8 * idx]) = f4{(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
+          *reinterpret_cast<f4*>(&H_s[w][8 * idx + 4]) = f4{(float)h[4], (float)h[5], (float)h[6], (float)h[7]};
+        }
+      }
     }
   }
   wave_lds_sync();
@@ -808,37 +825,55 @@ __global__ void ew_dsilu2_kernel(const float* __restrict__ g, float s, const flo
 
 }  // namespace
 
-int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout, int out_half) {
+bool gp_tripG_edge_takes_half_H(int C, int O) { return C >= 1 && C <= 16 && (O == 32 || O == 64 || O == 128); }
+
+int gp_tripG_edge_G(gp_ctx* ctx, const float* Radt, const float* H, int64_t E, int S, int C, int O, float* Gout, int out_half,
+                    int h_half) {
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, Radt && H && Gout && S >= 1 && S <= ST && C >= 1 && C <= 16 && O >= 1, "edge_G: bad arguments");
-  gp_prof_scope prof(ctx, "tripG_edge_G", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O + C * O));
+  gp_prof_scope prof(ctx, "tripG_edge_G", 2.0 * E * S * C * O,
+                     4.0 * E * S * C + (h_half ? 2.0 : 4.0) * E * S * O + (out_half ? 2.0 : 4.0) * E * C * O);
   const unsigned blocks = (unsigned)((E + EG_EDGES - 1) / EG_EDGES);
   const size_t lds = (size_t)S * C * EG_EDGES * sizeof(float);
   if (out_half && (O == 32 || O == 64 || O == 128) && ((reinterpret_cast<uintptr_t>(H) | reinterpret_cast<uintptr_t>(Gout)) & 15) == 0) {
     __bf16* Gh = reinterpret_cast<__bf16*>(Gout);
-    if (O == 32) edge_G16_kernel<32><<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, H, E, S, C, Gh);
-    else if (O == 64) edge_G16_kernel<64><<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, H, E, S, C, Gh);
-    else edge_G16_kernel<128><<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, H, E, S, C, Gh);
-  } else
+    const __bf16* Hh = reinterpret_cast<const __bf16*>(H);
+#define GP_EG16(OW)                                                                                          \
+  do {                                                                                                       \
+    if (h_half) edge_G16_kernel<OW, __bf16><<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, Hh, E, S, C, Gh); \
+    else edge_G16_kernel<OW, float><<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, H, E, S, C, Gh);         \
+  } while (0)
+    if (O == 32) GP_EG16(32);
+    else if (O == 64) GP_EG16(64);
+    else GP_EG16(128);
+#undef GP_EG16
+  } else {
+    if (h_half) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "edge_G: a bf16 H needs a bf16 result, a width of 32, 64 or 128 and 16-byte aligned arrays");
     edge_G_kernel<<<blocks, WPB * WAVE, lds, ctx->stream>>>(Radt, H, E, S, C, O, out_half, Gout);
+  }
   GP_LAUNCH_CHECK(ctx, "edge_G_kernel");
   return GP_OK;
 }
 
-int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad, int v_half) {
+int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, int S, int C, int O, float* dRad, int v_half,
+                       int h_half) {
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, V && H && dRad && S >= 1 && S <= ST && C >= 1 && O >= 1, "edge_dRad: bad arguments");
-  gp_prof_scope prof(ctx, "tripG_edge_dRad", 2.0 * E * S * C * O, 4.0 * E * (S * C + S * O) + (v_half ? 2.0 : 4.0) * E * C * O);
+  gp_prof_scope prof(ctx, "tripG_edge_dRad", 2.0 * E * S * C * O,
+                     4.0 * E * S * C + (h_half ? 2.0 : 4.0) * E * S * O + (v_half ? 2.0 : 4.0) * E * C * O);
   // 16-byte loads need 16-byte aligned rows: true for the widths below when the bases are (fp32 V and H: O % 4,
   // bf16 V: O % 8)
   const bool aligned = (((uintptr_t)V | (uintptr_t)H) & 15) == 0;
   if (C <= 16 && aligned && (O == 32 || O == 64 || O == 128)) {
     const __bf16* Vh = reinterpret_cast<const __bf16*>(V);
+    const __bf16* Hh = reinterpret_cast<const __bf16*>(H);
     const unsigned dq_blocks = (unsigned)((E + WPB * DQ_EPW - 1) / (WPB * DQ_EPW));
 #define GP_DRAD(OQ)                                                                                           \
   do {                                                                                                        \
-    if (v_half) edge_dRad_q_kernel<OQ, __bf16><<<dq_blocks, WPB * WAVE, 0, ctx->stream>>>(Vh, H, E, S, C, dRad); \
-    else edge_dRad_q_kernel<OQ, float><<<dq_blocks, WPB * WAVE, 0, ctx->stream>>>(V, H, E, S, C, dRad);    \
+    if (v_half && h_half) edge_dRad_q_kernel<OQ, __bf16, __bf16><<<dq_blocks, WPB * WAVE, 0, ctx->stream>>>(Vh, Hh, E, S, C, dRad); \
+    else if (v_half) edge_dRad_q_kernel<OQ, __bf16, float><<<dq_blocks, WPB * WAVE, 0, ctx->stream>>>(Vh, H, E, S, C, dRad); \
+    else if (h_half) edge_dRad_q_kernel<OQ, float, __bf16><<<dq_blocks, WPB * WAVE, 0, ctx->stream>>>(V, Hh, E, S, C, dRad); \
+    else edge_dRad_q_kernel<OQ, float, float><<<dq_blocks, WPB * WAVE, 0, ctx->stream>>>(V, H, E, S, C, dRad);    \
   } while (0)
     if (O == 32) GP_DRAD(8);
     else if (O == 64) GP_DRAD(16);
@@ -847,7 +882,7 @@ int gp_tripG_edge_dRad(gp_ctx* ctx, const float* V, const float* H, int64_t E, i
     GP_LAUNCH_CHECK(ctx, "edge_dRad_q_kernel");
     return GP_OK;
   }
-  if (v_half) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "edge_dRad: bf16 V needs emb_cbf <= 16 and a width of 32, 64 or 128");
+  if (v_half || h_half) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "edge_dRad: bf16 V or H needs emb_cbf <= 16 and a width of 32, 64 or 128");
   const size_t lds = (size_t)WPB * (C + S) * (O + 1) * sizeof(float);
   if (lds > 64 * 1024) return gp_fail(ctx, GP_UNSUPPORTED_DIMS, "edge_dRad: (emb_cbf+num_spherical)*emb_bil too large");
   edge_dRad_kernel<<<seg_blocks(E), WPB * WAVE, lds, ctx->stream>>>(V, H, E, S, C, O, dRad);

@@ -117,7 +117,7 @@ template <int NT>   // O = 16 NT (NT = 2, 4, 8)
 __global__ void __launch_bounds__(256, NT == 8 ? 2 : 3)
 tripG_H_fused_kernel(const float* __restrict__ cos_kj, int64_t T, const __bf16* __restrict__ dzb, const int32_t* __restrict__ row_info,
                      const int32_t* __restrict__ n_items, const int32_t* __restrict__ item, int S,
-                     const int32_t* __restrict__ rows, float* __restrict__ H) {
+                     const int32_t* __restrict__ rows, int out_half, float* __restrict__ H) {
   constexpr int O = 16 * NT;
   constexpr int Z_B = HSLAB / 8 * O * 16;            // dz^T of a slab: 4 position blocks x O x 8 bf16
   constexpr int CS_B = HR * HSLAB * 4;               // cosines of the group's rows for a slab
@@ -240,6 +240,20 @@ tripG_H_fused_kernel(const float* __restrict__ cos_kj, int64_t T, const __bf16* 
       if (pl >= n_rows) continue;
       const int e_out = rows ? rows[e0 + pl] : e0 + pl;
       float* dst = H + ((int64_t)e_out * S + l) * O + NT * kq;
+      if (out_half) {   // H as bf16 (its readers are the two per-edge products): the same elements, half the bytes
+        __bf16* dh = reinterpret_cast<__bf16*>(H) + ((int64_t)e_out * S + l) * O + NT * kq;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int t = 0; t < NT; t += 2) {
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            bf16x2 v;
+            v[0] = (__bf16)acc[rt][t][i];
+            v[1] = (__bf16)acc[rt][t + 1][i];
+            *reinterpret_cast<bf16x2*>(dh + 4 * NT * i + t) = v;
+          }
+        continue;
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if constexpr (NT == 4 || NT == 8) {
@@ -461,7 +475,7 @@ bool gp_tripG_H_fused_usable(const gp_graph* g, int O, int S) {
 }
 
 int gp_tripG_backward_H_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_alpha_kj, const float* dz, int O, int S, float* H,
-                              void* ws, size_t ws_bytes, const int32_t* row_list) {
+                              void* ws, size_t ws_bytes, const int32_t* row_list, int out_half) {
   const int64_t E = g->n_edges, T = g->n_triplets, N = g->n_atoms;
   if (E == 0) return GP_OK;
   GP_REQUIRE(ctx, gp_tripG_H_fused_usable(g, O, S), "triplet G backward (one-pass matrix-core form): graph lists or widths not supported");
@@ -479,7 +493,7 @@ int gp_tripG_backward_H_fused(gp_ctx* ctx, const gp_graph* g, const float* cos_a
   gp_prof_scope prof(ctx, "tripG_H_fused", (double)T * 2.0 * 8 * O, (double)T * 4.0 + (double)E * (2.0 * O + 4.0 * S * O));
   const unsigned grid = (unsigned)(E / HR + N);   // an upper bound of the number of work items; the rest exit at once
 #define GP_H_LAUNCH(NT) \
-  tripG_H_fused_kernel<NT><<<grid, 256, STAGES * (HSLAB / 8 * 16 * NT * 16 + HR * HSLAB * 4), st>>>(cos_alpha_kj, T, w.dzb, w.row_info, w.n_items, w.item, S, row_list, H)
+  tripG_H_fused_kernel<NT><<<grid, 256, STAGES * (HSLAB / 8 * 16 * NT * 16 + HR * HSLAB * 4), st>>>(cos_alpha_kj, T, w.dzb, w.row_info, w.n_items, w.item, S, row_list, out_half, H)
   if (O == 128) GP_H_LAUNCH(8);
   else if (O == 64) GP_H_LAUNCH(4);
   else GP_H_LAUNCH(2);
