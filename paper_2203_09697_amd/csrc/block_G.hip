@@ -354,21 +354,6 @@ gate_bwd_lr_kernel(const __bf16* __restrict__ dxg, const __bf16* __restrict__ z,
 }
 
 // out = bf16(in), 4 elements per thread
-// out[c, r] = bf16(in[r, c]), in [rows, cols] (weights only: at most a few million elements)
-__global__ void to_half_T_kernel(const float* __restrict__ in, __bf16* __restrict__ out, int rows, int cols) {
-  __shared__ float t[32][33];
-  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
-  for (int i = threadIdx.y; i < 32; i += 8) {
-    const int r = r0 + i, c = c0 + threadIdx.x;
-    t[i][threadIdx.x] = (r < rows && c < cols) ? in[(int64_t)r * cols + c] : 0.f;
-  }
-  __syncthreads();
-  for (int i = threadIdx.y; i < 32; i += 8) {
-    const int c = c0 + i, r = r0 + threadIdx.x;
-    if (c < cols && r < rows) out[(int64_t)c * rows + r] = (__bf16)t[threadIdx.x][i];
-  }
-}
-
 __global__ void to_half_kernel(const float* __restrict__ in, __bf16* __restrict__ out, int64_t n) {
   const int64_t i = 4 * ((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
   if (i >= n) return;
@@ -380,6 +365,48 @@ __global__ void to_half_kernel(const float* __restrict__ in, __bf16* __restrict_
     *reinterpret_cast<h4*>(out + i) = o;
   } else {
     for (int64_t k = i; k < n; ++k) out[k] = (__bf16)in[k];
+  }
+}
+
+// Several small fp32 -> bf16 conversions in one launch: blockIdx.y names the job, blockIdx.x one 32 x 32
+// tile of one of its `batch` consecutive [rows, cols] matrices.  A job writes each matrix transposed
+// (batches consecutive again), or as it stands with row stride dst_ld and batch stride dst_batch.
+struct half_job {
+  const float* src;
+  __bf16* dst;
+  int rows, cols, batch, transpose, dst_ld, dst_batch;
+};
+constexpr int HALF_JOBS_MAX = 8;
+struct half_jobs {
+  half_job j[HALF_JOBS_MAX];
+};
+__global__ void to_half_jobs_kernel(half_jobs jobs) {
+  __shared__ float t[32][33];
+  const half_job jb = jobs.j[blockIdx.y];
+  const int tc = (jb.cols + 31) / 32, tr = (jb.rows + 31) / 32;
+  int tile = blockIdx.x;
+  if (tile >= tc * tr * jb.batch) return;   // the whole workgroup
+  const int b = tile / (tc * tr);
+  tile %= tc * tr;
+  const int r0 = (tile / tc) * 32, c0 = (tile % tc) * 32;
+  const float* in = jb.src + (int64_t)b * jb.rows * jb.cols;
+  if (!jb.transpose) {
+    __bf16* out = jb.dst + (int64_t)b * jb.dst_batch;
+    for (int i = threadIdx.y; i < 32; i += 8) {
+      const int r = r0 + i, c = c0 + threadIdx.x;
+      if (r < jb.rows && c < jb.cols) out[(int64_t)r * jb.dst_ld + c] = (__bf16)in[(int64_t)r * jb.cols + c];
+    }
+    return;
+  }
+  __bf16* out = jb.dst + (int64_t)b * jb.rows * jb.cols;
+  for (int i = threadIdx.y; i < 32; i += 8) {
+    const int r = r0 + i, c = c0 + threadIdx.x;
+    t[i][threadIdx.x] = (r < jb.rows && c < jb.cols) ? in[(int64_t)r * jb.cols + c] : 0.f;
+  }
+  __syncthreads();
+  for (int i = threadIdx.y; i < 32; i += 8) {
+    const int c = c0 + i, r = r0 + threadIdx.x;
+    if (c < jb.cols && r < jb.rows) out[(int64_t)c * jb.rows + r] = (__bf16)t[threadIdx.x][i];
   }
 }
 
@@ -441,19 +468,36 @@ int to_half(gp_ctx* ctx, const float* in, __bf16* out, int64_t n) {
   GP_LAUNCH_CHECK(ctx, "to_half_kernel");
   return GP_OK;
 }
-int to_half_T(gp_ctx* ctx, const float* in, __bf16* out, int rows, int cols) {
-  gp_prof_scope prof(ctx, "to_half", 0.0, 6.0 * (double)rows * cols);
-  to_half_T_kernel<<<dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, ctx->stream>>>(in, out, rows, cols);
-  GP_LAUNCH_CHECK(ctx, "to_half_T_kernel");
-  return GP_OK;
-}
-// the weight as a GEMM operand: its bf16 copy (made here) or the fp32 original
-const float* weight_operand(gp_ctx* ctx, bool half, const float* W, __bf16* W_h, int64_t n, int* rc) {
-  if (!half) return W;
-  const int r = to_half(ctx, W, W_h, n);
-  if (r != GP_OK) *rc = r;
-  return reinterpret_cast<const float*>(W_h);
-}
+// the bf16 copies of a block's weights, gathered and made by one launch
+struct half_batch {
+  gp_ctx* ctx;
+  half_jobs jobs{};
+  int n = 0, tiles = 0;
+  double elems = 0.0;
+  explicit half_batch(gp_ctx* c) : ctx(c) {}
+  // dst = src (transpose == false) or its transpose, for each of `batch` consecutive [rows, cols] matrices;
+  // dst_ld / dst_batch (elements, plain copies only) default to the dense layout
+  const float* add(const float* src, __bf16* dst, int rows, int cols, bool transpose, int batch = 1, int dst_ld = 0,
+                   int dst_batch = 0) {
+    if (n < HALF_JOBS_MAX && rows > 0 && cols > 0 && batch > 0) {
+      jobs.j[n++] = half_job{src, dst, rows, cols, batch, transpose ? 1 : 0, dst_ld ? dst_ld : cols,
+                             dst_batch ? dst_batch : rows * cols};
+      const int t = ((rows + 31) / 32) * ((cols + 31) / 32) * batch;
+      tiles = t > tiles ? t : tiles;
+      elems += (double)rows * cols * batch;
+    } else if (rows > 0 && cols > 0 && batch > 0)
+      n = HALF_JOBS_MAX + 1;   // reported by run()
+    return reinterpret_cast<const float*>(dst);
+  }
+  int run() {
+    if (n == 0) return GP_OK;
+    GP_REQUIRE(ctx, n <= HALF_JOBS_MAX, "half_batch: more conversions than one launch takes");
+    gp_prof_scope prof(ctx, "to_half", 0.0, 6.0 * elems);
+    to_half_jobs_kernel<<<dim3((unsigned)tiles, (unsigned)n), dim3(32, 8), 0, ctx->stream>>>(jobs);
+    GP_LAUNCH_CHECK(ctx, "to_half_jobs_kernel");
+    return GP_OK;
+  }
+};
 
 bool a_half(const gp_ctx* ctx, const gp_dims* d, const gp_graph* g) {
   if (!half_storage(d) || (d->emb_cbf * d->int_emb) % 8 != 0) return false;
@@ -540,19 +584,23 @@ int forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_
   int rc = GP_OK;
   // the two H x H weights as transposed bf16 copies: activations times a [N, K] weight is the form the
   // global->LDS GEMM kernel takes
+  half_batch wcopy(ctx);   // one launch for all of them
   if (wh) {
-    GP_TRY(to_half_T(ctx, w->W_ba, sc.W_ba_h, H, H));
-    GP_TRY(to_half_T(ctx, w->W_skip, sc.W_skip_h, H, H));
+    wcopy.add(w->W_ba, sc.W_ba_h, H, H, true);
+    wcopy.add(w->W_skip, sc.W_skip_h, H, H, true);
   }
   const float* W_ba_T = reinterpret_cast<const float*>(sc.W_ba_h);
   const float* W_skip_T = reinterpret_cast<const float*>(sc.W_skip_h);
   // the two weights that contract a wide row into a narrow one likewise, where the activations are bf16
   const bool down_T = wh && hs && H % 8 == 0, bil_T = wh && ah;
-  if (down_T) GP_TRY(to_half_T(ctx, w->W_down, sc.W_down_h, H, F));                 // [F, H]
-  if (bil_T) GP_TRY(to_half_T(ctx, w->W_bil, sc.W_bil_h, C * F, O));                // [O, (c,f)]
-  const float* W_down = down_T ? reinterpret_cast<const float*>(sc.W_down_h) : weight_operand(ctx, wh, w->W_down, sc.W_down_h, (int64_t)H * F, &rc);
-  const float* W_bil = bil_T ? reinterpret_cast<const float*>(sc.W_bil_h) : w->W_bil;
-  GP_TRY(rc);
+  const float* W_down = wh ? wcopy.add(w->W_down, sc.W_down_h, H, F, down_T) : w->W_down;   // [F, H] with down_T
+  const float* W_bil = bil_T ? wcopy.add(w->W_bil, sc.W_bil_h, C * F, O, true) : w->W_bil;  // [O, (c,f)]
+  // and the up-projection(s) as [H, O] where z is bf16
+  if (z_half(dims)) {
+    wcopy.add(w->W_up, sc.W_up_h, O, H, true);
+    if (dims->symmetric) wcopy.add(w->W_up_ac, sc.W_up_ac_h, O, H, true);
+  }
+  GP_TRY(wcopy.run());
   e = gp_epilogue(); e.save_pre = s.z_ba; e.act = 1; e.out = s.xg;
   if (lrg) e.lr_a = s.gate, e.lr_b = w->W_rbfB, e.lr_k = RB;
   else e.mul = s.gate;
@@ -607,7 +655,6 @@ int forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_
     float* u_ac = sc.eh[1];
     e = gp_epilogue(); e.save_pre = s.z_ac; e.act = 1; e.out = u_ac; e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_OUT) : 0u;
     if (zh) {
-      GP_TRY(to_half_T(ctx, w->W_up_ac, sc.W_up_ac_h, O, H));                       // [H, O]
       GP_TRY(gp_gemm_nt(ctx, s.z, reinterpret_cast<const float*>(sc.W_up_ac_h), E, H, O, e, 1, 1));
     } else
       GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up_ac, E, H, O, e));
@@ -622,7 +669,6 @@ int forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_
     e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = 0.5f; e.out = m_out;
     e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST | (m_out_h ? EPI_BF_OUT : 0u)) : 0u;
     if (zh) {
-      GP_TRY(to_half_T(ctx, w->W_up, sc.W_up_h, O, H));
       GP_TRY(gp_gemm_nt(ctx, s.z, reinterpret_cast<const float*>(sc.W_up_h), E, H, O, e, 1, 1));
     } else
       GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
@@ -631,7 +677,6 @@ int forward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp_
   e = gp_epilogue(); e.save_pre = s.z_up; e.act = 1; e.add_post = t_skip; e.scale = INV_SQRT2; e.out = m_out;
   e.bf16 = hs ? (EPI_BF_SAVE_PRE | EPI_BF_ADD_POST | (m_out_h ? EPI_BF_OUT : 0u)) : 0u;
   if (zh) {
-    GP_TRY(to_half_T(ctx, w->W_up, sc.W_up_h, O, H));                               // [H, O]: activations times a [N, K] weight
     GP_TRY(gp_gemm_nt(ctx, s.z, reinterpret_cast<const float*>(sc.W_up_h), E, H, O, e, 1, 1));
   } else
     GP_TRY(gp_gemm_nn(ctx, s.z, w->W_up, E, H, O, e));
@@ -673,10 +718,26 @@ int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp
   GP_REQUIRE(ctx, !(m_in_h || gmo_h || gmi_h) || (hs && wh), "gp_block_backward_G_stacked: bf16 messages need a block that stores bf16 (see gp_block_G_stacks_bf16)");
   GP_REQUIRE(ctx, !gmo_h || !dims->symmetric, "gp_block_backward_G_stacked: a symmetric block takes its incoming gradient as fp32");
   int rc = GP_OK;
-  const float* W_up = weight_operand(ctx, wh, w->W_up, sc.W_up_h, (int64_t)O * H, &rc);
-  const float* W_skip = weight_operand(ctx, wh, w->W_skip, sc.W_skip_h, (int64_t)H * H, &rc);
-  const float* W_ba = weight_operand(ctx, wh, w->W_ba, sc.W_ba_h, (int64_t)H * H, &rc);
-  GP_TRY(rc);
+  // the bf16 copies of the weights this pass multiplies by, one launch
+  const bool dzdn_half = !dims->radial_at_target && hs && wh && F % 8 == 0;   // dz_dn stored as bf16 (below)
+  const float *W_up = w->W_up, *W_skip = w->W_skip, *W_ba = w->W_ba, *W_up_ac = w->W_up_ac, *W_down = w->W_down;
+  const float* WbilP = sc.WbilP;
+  if (wh) {
+    half_batch wcopy(ctx);
+    W_up = wcopy.add(w->W_up, sc.W_up_h, O, H, false);
+    W_skip = wcopy.add(w->W_skip, sc.W_skip_h, H, H, false);
+    W_ba = wcopy.add(w->W_ba, sc.W_ba_h, H, H, false);
+    if (dims->symmetric) W_up_ac = wcopy.add(w->W_up_ac, sc.W_up_ac_h, O, H, false);
+    if (dzdn_half) W_down = wcopy.add(w->W_down, sc.W_down_h, H, F, false);
+    // W_bil [c, f, o] as [(c,o), f]: C transposes
+    if (!dims->radial_at_target) {
+      WbilP = wcopy.add(w->W_bil, sc.WbilP_h, F, O, true, C);
+      // and as [f, (c,o)]: matrix c lands at column c O of rows C O long
+      if (dzdn_half && (C * O) % 8 == 0) wcopy.add(w->W_bil, sc.WbilV_h, F, O, false, C, C * O, O);
+    } else if ((C * O) % 8 == 0)
+      wcopy.add(w->W_bil, sc.WbilV_h, F, O, false, C, C * O, O);   // read where G' is bf16
+    GP_TRY(wcopy.run());
+  }
   gp_aux aux(ctx);   // the large weight-gradient GEMMs run on the side stream
   if (dims->symmetric) {
     GP_REQUIRE(ctx, graph->id_swap, "gp_block_backward_G: graph->id_swap is needed by a symmetric block");
@@ -703,8 +764,6 @@ int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp
     }
     GP_TRY(gp_gemm_tn(ctx, s.z, d_ac, E, O, H, gw->W_up_ac, nullptr, sc.part, sc.part_bytes, z_half(dims), hs));
     e = gp_epilogue(); e.out = sc.dz;
-    const float* W_up_ac = weight_operand(ctx, wh, w->W_up_ac, sc.W_up_ac_h, (int64_t)O * H, &rc);
-    GP_TRY(rc);
     GP_TRY(gp_gemm_nt(ctx, d_ac, W_up_ac, E, O, H, e, hs, wh));                     // dz (opposite-edge path)
   } else if (hs) {
     gp_prof_scope prof(ctx, "ew_dsilu2_half", 0.0, (gmo_h ? 10.0 : 12.0) * (double)EH);   // the gradient + 4 bf16 arrays
@@ -764,9 +823,7 @@ int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp
       GP_TRY(gp_tripD_forward(ctx, &gm, basis->cos_alpha_kj, sc.dz, s.Radt, nullptr, O, S, C, nullptr, sc.Gm));
     e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn;
     if (gh) {
-      GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));               // [f, (c,o)]; the buffer is rewritten below
-      GP_TRY(to_half(ctx, sc.WbilV, sc.WbilV_h, (int64_t)F * C * O));
-      GP_TRY(gp_gemm_nt(ctx, sc.Gm, reinterpret_cast<const float*>(sc.WbilV_h), E, F, C * O, e, 1, 1));   // dz_dn
+      GP_TRY(gp_gemm_nt(ctx, sc.Gm, reinterpret_cast<const float*>(sc.WbilV_h), E, F, C * O, e, 1, 1));   // dz_dn ([f, (c,o)] copy)
     } else {
       GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));               // [(c,o), f]
       GP_TRY(gp_gemm_nn(ctx, sc.Gm, sc.WbilP, E, F, C * O, e));                     // dz_dn
@@ -799,16 +856,12 @@ int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp
     GP_TRY(gp_tripD_backward(ctx, graph, basis->cos_alpha_kj, nullptr, nullptr, nullptr, sc.dz, nullptr, O, S, 1,
                              sc.Hd, nullptr));
   GP_TRY(gp_tripG_edge_G(ctx, s.Radt, sc.Hd, E, S, C, O, sc.Gm, hs, hh));           // G[e', (c,o)] (bf16 with hs)
-  GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));                   // [(c,o), f]
+  if (!wh) GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 0, 2, 1, sc.WbilP));          // [(c,o), f]; the bf16 copy was made above
   // dz_dn is an operand of two GEMMs only: bf16 with bf16 storage and weights
   const bool dh = hs && wh && F % 8 == 0;
   e = gp_epilogue(); e.act = 2; e.zsrc = s.z_dn; e.out = sc.dzdn; e.bf16 = dh ? EPI_BF_OUT : 0u;
-  const float* WbilP = weight_operand(ctx, wh, sc.WbilP, sc.WbilP_h, (int64_t)C * O * F, &rc);
-  GP_TRY(rc);
   if (dh && (C * O) % 8 == 0) {
-    GP_TRY(gp_permute3(ctx, w->W_bil, C, F, O, 1, 0, 2, sc.WbilV));                 // [f, (c,o)]
-    GP_TRY(to_half(ctx, sc.WbilV, sc.WbilV_h, (int64_t)F * C * O));
-    GP_TRY(gp_gemm_nt(ctx, sc.Gm, reinterpret_cast<const float*>(sc.WbilV_h), E, F, C * O, e, 1, 1));   // dz_dn
+    GP_TRY(gp_gemm_nt(ctx, sc.Gm, reinterpret_cast<const float*>(sc.WbilV_h), E, F, C * O, e, 1, 1));   // dz_dn ([f, (c,o)] copy)
   } else
     GP_TRY(gp_gemm_nn(ctx, sc.Gm, WbilP, E, F, C * O, e, hs, wh));                  // dz_dn
   // V is read by the two per-edge kernels below only: bf16 storage halves its traffic
@@ -838,12 +891,9 @@ int backward_G(gp_ctx* ctx, const gp_dims* dims, const gp_weights_G* w, const gp
   }
   GP_TRY(gp_gemm_tn(ctx, g, sc.dRad, E, R, S * C, sc.dWcP, nullptr, sc.part, sc.part_bytes));   // [n, (l,c)]
   GP_TRY(gp_permute3(ctx, sc.dWcP, R, S, C, 1, 0, 2, gw->W_c));                     // -> [l, n, c]
-  const bool dzdn_half = !dims->radial_at_target && hs && wh && F % 8 == 0;   // as written above
   GP_TRY(aux.on_aux([&] { return gp_gemm_tn(ctx, s.xg, sc.dzdn, E, H, F, gw->W_down, nullptr, sc.part_aux, sc.part_bytes, hs, dzdn_half); }, {}));
   e = gp_epilogue(); e.out = dxg; e.bf16 = hs ? EPI_BF_OUT : 0u;
   if (dzdn_half) {
-    const float* W_down = weight_operand(ctx, true, w->W_down, sc.W_down_h, (int64_t)H * F, &rc);
-    GP_TRY(rc);
     GP_TRY(gp_gemm_nt(ctx, sc.dzdn, W_down, E, H, F, e, 1, 1));                     // dxg
   } else
     GP_TRY(gp_gemm_nt(ctx, sc.dzdn, w->W_down, E, H, F, e));                        // dxg
